@@ -1,0 +1,244 @@
+"""CPU oracle for the tensor access trace of one training iteration.
+
+TEST INFRASTRUCTURE ONLY; shares no code with the HIP library.
+
+The paper's profiler (Section 3.1) marks every input and output tensor of a GPU
+operator active while the operator runs and records tensor sizes and kernel
+times.  In this build the operators are the library's own kernel launches, so
+the trace is a function of the model shape alone: this file writes that
+function out from the canonical kernel schedule (one record per launch, in
+launch order), independently of the library's launcher.
+
+A trace is
+  tensors: list of (bytes, kind, name); bytes = payload rounded up to 256
+  kernels: list of (op, operands, flops); operands = sorted list of
+           (tensor id, flags), flags bit0 = read, bit1 = written
+  tau:     modelled kernel times in ns (a deterministic stand-in for measured
+           times: max(flops/F, bytes/W) + c with integer constants)
+
+Tensor ids: persistent tensors first (parameter-list order; per parameter the
+compute weight, then the fp32 master copy when the precision is bf16, then the
+two AdamW moments), then the token and label buffers, then transient tensors
+in order of first write.
+
+Pins (tests/test_oracle_plan.py): kernel and tensor counts in closed form,
+persistent bytes = 12 or 14 bytes per parameter, every transient written before
+read, peak memory at the loss kernel in closed form.  The exact schedule is a
+reading of this build (the paper names no kernels): parity unpinned beyond
+those invariants.
+"""
+from __future__ import annotations
+
+from .model import param_specs
+
+# op codes (shared numbering is part of the written specification, not shared code)
+(EMBED_FWD, NORM_FWD, GEMM, ROPE_FWD, ATTN_FWD, GELU_FWD, SWIGLU_FWD, CE_FWD_BWD, LOSS_REDUCE,
+ GEMM_DX, GEMM_DW, BIAS_GRAD, GELU_BWD, SWIGLU_BWD, NORM_BWD, NORM_BWD_PARAMS, ATTN_BWD_PRE,
+ ATTN_BWD, ROPE_BWD, EMBED_BWD, POSEMB_BWD, ADAMW) = range(22)
+
+# tensor kinds
+K_WEIGHT, K_MASTER, K_M, K_V, K_INPUT, K_ACT, K_GRAD, K_PGRAD = range(8)
+
+READ, WRITE = 1, 2
+NORM_BWD_ROWS = 16          # rows of the token dimension handled by one norm-backward workgroup
+
+# modelled kernel time constants
+MODEL_FLOPS_PER_S = 1_250_000_000_000_000     # half of the dense bf16 MFMA peak
+MODEL_BYTES_PER_S = 4_000_000_000_000         # half of the HBM peak
+MODEL_LAUNCH_NS = 4_000
+
+
+def _r256(n):
+    return (n + 255) // 256 * 256
+
+
+def vocab_ld(V):
+    """Leading dimension of the logits matrix: vocabulary rounded up to 64 columns."""
+    return (V + 63) // 64 * 64
+
+
+class _Builder:
+    def __init__(self):
+        self.tensors, self.kernels, self.ids = [], [], {}
+
+    def tensor(self, name, nbytes, kind):
+        assert name not in self.ids, name
+        self.ids[name] = len(self.tensors)
+        self.tensors.append((_r256(nbytes), kind, name))
+        return self.ids[name]
+
+    def kernel(self, op, reads=(), writes=(), inouts=(), flops=0):
+        fl = {}
+        for n in reads:
+            fl[self.ids[n]] = fl.get(self.ids[n], 0) | READ
+        for n in writes:
+            fl[self.ids[n]] = fl.get(self.ids[n], 0) | WRITE
+        for n in inouts:
+            fl[self.ids[n]] = fl.get(self.ids[n], 0) | READ | WRITE
+        self.kernels.append((op, sorted(fl.items()), int(flops)))
+
+
+def build_trace(cfg):
+    a, L, d, H, f, V, T, B = (cfg[k] for k in ("arch", "L", "d", "H", "f", "V", "T", "B"))
+    gpt = a == "gpt"
+    bf16 = cfg["precision"] == "bf16"
+    e = 2 if bf16 else 4                 # element size of weights, activations, gradients
+    S = B * T
+    Vp = vocab_ld(V)
+    b = _Builder()
+    specs = param_specs(cfg)
+
+    # ---- persistent tensors
+    for name, shape, _ in specs:
+        n = 1
+        for s in shape:
+            n *= s
+        b.tensor(name, n * e, K_WEIGHT)
+        if bf16:
+            b.tensor(name + ".master", n * 4, K_MASTER)
+        b.tensor(name + ".m", n * 4, K_M)
+        b.tensor(name + ".v", n * 4, K_V)
+    b.tensor("tokens", S * 4, K_INPUT)
+    b.tensor("labels", S * 4, K_INPUT)
+
+    act = lambda name, n, es=e: b.tensor(name, n * es, K_ACT)
+    grd = lambda name, n, es=e: b.tensor(name, n * es, K_GRAD)
+    nb = (S + NORM_BWD_ROWS - 1) // NORM_BWD_ROWS
+    nstat = 2 if gpt else 1              # LayerNorm keeps mean and rstd, RMSNorm rstd
+    norm_p = (lambda p, k: [p + k + "_g", p + k + "_b"]) if gpt else (lambda p, k: [p + k + "_g"])
+    nk = "ln" if gpt else "rms"
+    attn_flops = 2 * B * H * T * T * (d // H)       # two T x T x dh products, causal half
+
+    # ---- forward
+    act("x0", S * d)
+    b.kernel(EMBED_FWD, reads=["tokens", "wte"] + (["wpe"] if gpt else []), writes=["x0"])
+    x = "x0"
+    for i in range(L):
+        p = f"l{i}."
+        act(p + "h1", S * d); act(p + "st1", S * nstat, 4)
+        b.kernel(NORM_FWD, reads=[x] + norm_p(p, nk + "1"), writes=[p + "h1", p + "st1"])
+        act(p + "qkv", S * 3 * d)
+        b.kernel(GEMM, reads=[p + "h1", p + "w_qkv"] + ([p + "b_qkv"] if gpt else []),
+                 writes=[p + "qkv"], flops=2 * S * 3 * d * d)
+        if not gpt:
+            b.kernel(ROPE_FWD, inouts=[p + "qkv"])
+        act(p + "ao", S * d); act(p + "lse", B * H * T, 4)
+        b.kernel(ATTN_FWD, reads=[p + "qkv"], writes=[p + "ao", p + "lse"], flops=attn_flops)
+        act(p + "xm", S * d)
+        b.kernel(GEMM, reads=[p + "ao", p + "w_o", x] + ([p + "b_o"] if gpt else []),
+                 writes=[p + "xm"], flops=2 * S * d * d)
+        act(p + "h2", S * d); act(p + "st2", S * nstat, 4)
+        b.kernel(NORM_FWD, reads=[p + "xm"] + norm_p(p, nk + "2"), writes=[p + "h2", p + "st2"])
+        if gpt:
+            act(p + "u", S * f)
+            b.kernel(GEMM, reads=[p + "h2", p + "w_fc1", p + "b_fc1"], writes=[p + "u"], flops=2 * S * f * d)
+            act(p + "act", S * f)
+            b.kernel(GELU_FWD, reads=[p + "u"], writes=[p + "act"])
+            w2, b2 = p + "w_fc2", [p + "b_fc2"]
+        else:
+            act(p + "u", S * 2 * f)
+            b.kernel(GEMM, reads=[p + "h2", p + "w_gu"], writes=[p + "u"], flops=2 * S * 2 * f * d)
+            act(p + "act", S * f)
+            b.kernel(SWIGLU_FWD, reads=[p + "u"], writes=[p + "act"])
+            w2, b2 = p + "w_down", []
+        act(p + "xo", S * d)
+        b.kernel(GEMM, reads=[p + "act", w2, p + "xm"] + b2, writes=[p + "xo"], flops=2 * S * d * f)
+        x = p + "xo"
+    fin = "lnf" if gpt else "rmsf"
+    fin_p = [fin + "_g"] + ([fin + "_b"] if gpt else [])
+    act("hf", S * d); act("stf", S * nstat, 4)
+    b.kernel(NORM_FWD, reads=[x] + fin_p, writes=["hf", "stf"])
+    act("logits", S * Vp)
+    b.kernel(GEMM, reads=["hf", "w_head"], writes=["logits"], flops=2 * S * V * d)
+    act("losses", S, 4)
+    b.kernel(CE_FWD_BWD, reads=["labels"], inouts=["logits"], writes=["losses"])
+    act("loss", 1, 4)
+    b.kernel(LOSS_REDUCE, reads=["losses"], writes=["loss"])
+
+    # ---- backward
+    def pgrad(name):
+        idx = b.ids[name]
+        return b.tensor("g." + name, b.tensors[idx][0] if not bf16 else b.tensors[idx][0], K_PGRAD)
+
+    def norm_bwd(dy, xin, st, pnames, dres, dx, part):
+        grd(dx, S * d); grd(part, nb * len(pnames) * d, 4)
+        b.kernel(NORM_BWD, reads=[dy, xin, st, pnames[0]] + ([dres] if dres else []), writes=[dx, part])
+        for n in pnames:
+            pgrad(n)
+        b.kernel(NORM_BWD_PARAMS, reads=[part], writes=["g." + n for n in pnames])
+
+    grd("dhf", S * d)
+    b.kernel(GEMM_DX, reads=["logits", "w_head"], writes=["dhf"], flops=2 * S * V * d)
+    pgrad("w_head")
+    b.kernel(GEMM_DW, reads=["logits", "hf"], writes=["g.w_head"], flops=2 * S * V * d)
+    norm_bwd("dhf", x, "stf", fin_p, None, "dxf", "partf")
+    dx = "dxf"
+    for i in reversed(range(L)):
+        p = f"l{i}."
+        xin = f"l{i - 1}.xo" if i > 0 else "x0"
+        w2 = p + ("w_fc2" if gpt else "w_down")
+        w1 = p + ("w_fc1" if gpt else "w_gu")
+        f1 = f if gpt else 2 * f
+        grd(p + "dact", S * f)
+        b.kernel(GEMM_DX, reads=[dx, w2], writes=[p + "dact"], flops=2 * S * d * f)
+        pgrad(w2)
+        b.kernel(GEMM_DW, reads=[dx, p + "act"], writes=["g." + w2], flops=2 * S * d * f)
+        if gpt:
+            pgrad(p + "b_fc2")
+            b.kernel(BIAS_GRAD, reads=[dx], writes=["g." + p + "b_fc2"])
+            b.kernel(GELU_BWD, reads=[p + "u"], inouts=[p + "dact"])
+            du = p + "dact"
+        else:
+            grd(p + "du", S * 2 * f)
+            b.kernel(SWIGLU_BWD, reads=[p + "dact", p + "u"], writes=[p + "du"])
+            du = p + "du"
+        grd(p + "dh2", S * d)
+        b.kernel(GEMM_DX, reads=[du, w1], writes=[p + "dh2"], flops=2 * S * f1 * d)
+        pgrad(w1)
+        b.kernel(GEMM_DW, reads=[du, p + "h2"], writes=["g." + w1], flops=2 * S * f1 * d)
+        if gpt:
+            pgrad(p + "b_fc1")
+            b.kernel(BIAS_GRAD, reads=[du], writes=["g." + p + "b_fc1"])
+        norm_bwd(p + "dh2", p + "xm", p + "st2", norm_p(p, nk + "2"), dx, p + "dxm", p + "part2")
+        grd(p + "dao", S * d)
+        b.kernel(GEMM_DX, reads=[p + "dxm", p + "w_o"], writes=[p + "dao"], flops=2 * S * d * d)
+        pgrad(p + "w_o")
+        b.kernel(GEMM_DW, reads=[p + "dxm", p + "ao"], writes=["g." + p + "w_o"], flops=2 * S * d * d)
+        if gpt:
+            pgrad(p + "b_o")
+            b.kernel(BIAS_GRAD, reads=[p + "dxm"], writes=["g." + p + "b_o"])
+        grd(p + "delta", B * H * T, 4)
+        b.kernel(ATTN_BWD_PRE, reads=[p + "dao", p + "ao"], writes=[p + "delta"])
+        grd(p + "dqkv", S * 3 * d)
+        b.kernel(ATTN_BWD, reads=[p + "dao", p + "qkv", p + "lse", p + "delta"], writes=[p + "dqkv"],
+                 flops=attn_flops * 5 // 2)
+        if not gpt:
+            b.kernel(ROPE_BWD, inouts=[p + "dqkv"])
+        grd(p + "dh1", S * d)
+        b.kernel(GEMM_DX, reads=[p + "dqkv", p + "w_qkv"], writes=[p + "dh1"], flops=2 * S * 3 * d * d)
+        pgrad(p + "w_qkv")
+        b.kernel(GEMM_DW, reads=[p + "dqkv", p + "h1"], writes=["g." + p + "w_qkv"], flops=2 * S * 3 * d * d)
+        if gpt:
+            pgrad(p + "b_qkv")
+            b.kernel(BIAS_GRAD, reads=[p + "dqkv"], writes=["g." + p + "b_qkv"])
+        norm_bwd(p + "dh1", xin, p + "st1", norm_p(p, nk + "1"), p + "dxm", p + "dx", p + "part1")
+        dx = p + "dx"
+    pgrad("wte")
+    b.kernel(EMBED_BWD, reads=[dx, "tokens"], writes=["g.wte"])
+    if gpt:
+        pgrad("wpe")
+        b.kernel(POSEMB_BWD, reads=[dx], writes=["g.wpe"])
+
+    # ---- optimizer: one launch per parameter tensor
+    for name, _, _ in specs:
+        state = [name] + ([name + ".master"] if bf16 else []) + [name + ".m", name + ".v"]
+        b.kernel(ADAMW, reads=["g." + name], inouts=state)
+
+    tau = []
+    for op, operands, flops in b.kernels:
+        nbytes = sum(b.tensors[t][0] for t, _ in operands)
+        tf = -(-flops * 10**9 // MODEL_FLOPS_PER_S)
+        tb = -(-nbytes * 10**9 // MODEL_BYTES_PER_S)
+        tau.append(max(tf, tb) + MODEL_LAUNCH_NS)
+    return dict(tensors=b.tensors, kernels=b.kernels, tau=tau, ids=b.ids,
+                n_persistent=b.ids["labels"] + 1)
