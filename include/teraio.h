@@ -1,0 +1,213 @@
+/*
+ * teraio.h -- C ABI of the MI355X-native lifetime-aware tensor offloading library.
+ *
+ * The calls follow the pipeline of the paper (arXiv 2506.06472, Section 3, system overview):
+ *   profile one iteration -> tensor access trace and kernel times   (Section 3.1, tracking tensors)
+ *   analyse lifetimes     -> inactive periods and memory demand M   (Section 3.1, analysing activity)
+ *   build a plan          -> offload / prefetch entries              (Section 3.2, Algorithm 1)
+ *   run training steps under the plan                               (Section 3.3, migration engine)
+ *
+ * Conventions
+ *   - every function returns 0 on success or a negative tio_status; out-parameters are written
+ *     only on success; tio_last_error() gives a thread-local message for the last failure.
+ *   - handles (tio_ctx, tio_trace, tio_lifetimes, tio_plan) are owned by the library and released
+ *     by their _free / _destroy call; pointers inside a *_view stay valid until then.
+ *   - "host" pointers are ordinary host memory borrowed for the duration of the call;
+ *     "device" pointers are GPU memory owned by the caller for the lifetime of the context.
+ *   - no exceptions cross this boundary; nothing here allocates GPU memory: the caller hands
+ *     over the arena (GPU) and the slow-tier pool (pinned host) when the context is created.
+ */
+#ifndef TERAIO_H
+#define TERAIO_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum tio_status {
+    TIO_OK = 0,
+    TIO_ERR_INVALID_ARG = -1,
+    TIO_ERR_OOM_HOST = -2,            /* slow-tier pool too small */
+    TIO_ERR_ACTIVE_SET_EXCEEDS_CAP = -3, /* one kernel's operands alone exceed the capacity */
+    TIO_ERR_PLAN_INVALID = -4,
+    TIO_ERR_PLAN_STALE = -5,          /* plan was built from a different trace */
+    TIO_ERR_HIP = -6,
+    TIO_ERR_ARENA_TOO_SMALL = -7,     /* address assignment does not fit the arena */
+    TIO_ERR_NO_GPU_CODE = -8
+} tio_status;
+
+enum { TIO_ARCH_GPT = 0, TIO_ARCH_LLAMA = 1 };
+enum { TIO_PREC_FP32 = 0, TIO_PREC_BF16 = 1 };
+enum { TIO_PROFILE_MEASURED = 0, TIO_PROFILE_MODELLED = 1 };
+enum { TIO_OFFLOAD = 0, TIO_PREFETCH = 1 };
+
+/* Model and optimizer shape.  GPT: LayerNorm, GELU (tanh form), biases, learned positions.
+ * Llama: RMSNorm, RoPE on adjacent pairs, SwiGLU, no biases.  The LM head is untied. */
+typedef struct tio_model_cfg {
+    int32_t arch, n_layers, d_model, n_heads, d_ff, vocab, seq_len, batch;
+    int32_t precision;               /* TIO_PREC_* : element type of weights, activations, gradients */
+    float lr, beta1, beta2, adam_eps, weight_decay, norm_eps, rope_theta;
+} tio_model_cfg;
+
+typedef struct tio_runtime_cfg {
+    void *arena;                     /* device, 256-byte aligned; every tensor lives here */
+    uint64_t arena_bytes;
+    void *host_pool;                 /* host, pinned; stands in for the paper's SSD tier */
+    uint64_t host_bytes;
+    void *compute_stream, *d2h_stream, *h2d_stream; /* hipStream_t, default priority; d2h may equal h2d */
+    uint64_t slow_tier_bw;           /* bytes/s per direction enforced on the copy streams; 0 = unthrottled */
+    int32_t poison_freed;            /* debug: fill released arena ranges with NaN patterns */
+    int32_t reserved;
+} tio_runtime_cfg;
+
+typedef struct tio_ctx tio_ctx;
+typedef struct tio_trace tio_trace;
+typedef struct tio_lifetimes tio_lifetimes;
+typedef struct tio_plan tio_plan;
+
+/* ---- flat read-only views for element-by-element comparison ------------------------------- */
+typedef struct tio_trace_view {
+    int32_t n_kernels, n_tensors, n_persistent, n_operands;
+    const int32_t *op;               /* [n_kernels] operator code */
+    const int32_t *operand_off;      /* [n_kernels+1] into the two arrays below */
+    const int32_t *operand_tensor;   /* sorted by tensor id within a kernel */
+    const int32_t *operand_flags;    /* bit0 read, bit1 written */
+    const int64_t *flops;            /* [n_kernels] */
+    const int64_t *tau_ns;           /* [n_kernels] kernel times used for planning */
+    const uint64_t *tensor_bytes;    /* [n_tensors] payload rounded up to 256 */
+    const int32_t *tensor_kind;      /* [n_tensors] 0 weight 1 master 2 m 3 v 4 input 5 activation 6 gradient 7 parameter gradient */
+} tio_trace_view;
+
+typedef struct tio_lifetimes_view {
+    int32_t n_kernels, n_periods;
+    const uint64_t *M;               /* [n_kernels] bytes live at each kernel (Algorithm 1, input M) */
+    const int32_t *tensor;           /* [n_periods] the set I: (t, s, start, end) */
+    const uint64_t *bytes;
+    const int32_t *start, *end;      /* bounding active kernels; end >= n_kernels wraps into the next iteration */
+} tio_lifetimes_view;
+
+typedef struct tio_plan_entry {
+    int32_t tensor, kind;            /* TIO_OFFLOAD / TIO_PREFETCH */
+    int32_t trigger, deadline;       /* unrolled kernel indices, see tio_build_plan */
+    int32_t urgent, pair;
+} tio_plan_entry;
+
+typedef struct tio_alloc {
+    int32_t tensor;
+    int32_t first_kernel, last_kernel; /* residency interval, unrolled (last may be >= n_kernels) */
+    uint64_t address;                /* byte offset in the arena */
+} tio_alloc;
+
+typedef struct tio_plan_view {
+    int32_t n_kernels, n_entries, n_greedy, n_forced, n_allocs, reserved;
+    const tio_plan_entry *entries;   /* issue order */
+    const uint64_t *Mp;              /* [n_kernels] planned residency M' */
+    const tio_alloc *allocs;
+    uint64_t cap_bytes;              /* capacity asked for */
+    uint64_t planning_cap_bytes;     /* capacity Algorithm 1 was run with (<= cap_bytes, lowered until the layout fits) */
+    uint64_t arena_bytes_needed;     /* highest address used + size */
+    uint64_t host_bytes_needed;
+    uint64_t bytes_per_direction;    /* sum of sizes of migrated periods */
+} tio_plan_view;
+
+typedef struct tio_plan_opts {
+    int32_t duplex;                  /* 1: offload and prefetch channels are independent (default); 0: one channel */
+    int32_t layout_retries;          /* how many times the planning capacity may be lowered (default 24) */
+    uint64_t min_bytes;              /* periods of smaller tensors are candidates of last resort only (default 0) */
+    uint64_t arena_bytes;            /* arena the layout must fit; 0 = cap_bytes */
+} tio_plan_opts;
+
+typedef struct tio_step_stats {
+    float loss;
+    int32_t step;
+    int64_t wall_ns;                 /* host clock, launch of the first kernel to completion of the last */
+    int64_t kernel_ns;               /* sum of kernel times (only when measured) */
+    uint64_t d2h_bytes, h2d_bytes;
+    int64_t d2h_busy_ns, h2d_busy_ns;/* copy-stream time incl. pacing (only when measured) */
+    int32_t n_kernels, n_migrations;
+} tio_step_stats;
+
+const char *tio_last_error(void);
+const char *tio_version(void);
+
+/* ---- model description (pure CPU) ---------------------------------------------------------- */
+/* Parameter list in parameter-list order (embeddings, layer 0..L-1, final norm, head). */
+int tio_param_count(const tio_model_cfg *cfg, int32_t *out_n);
+int tio_param_info(const tio_model_cfg *cfg, int32_t index, char *name_buf, size_t name_cap,
+                   int64_t *out_rows, int64_t *out_cols);
+
+/* ---- Section 3.1: trace and lifetimes (pure CPU unless measured) ------------------------------ */
+/* Structural trace of one iteration with modelled kernel times; needs no GPU. */
+int tio_trace_build(const tio_model_cfg *cfg, tio_trace **out);
+/* Trace from caller-supplied arrays (synthetic traces for planner tests). view is copied. */
+int tio_trace_import(const tio_trace_view *view, tio_trace **out);
+/* Replaces the kernel times (host array of n_kernels int64 ns). */
+int tio_trace_set_tau(tio_trace *trace, const int64_t *tau_ns, int32_t n);
+int tio_trace_export(const tio_trace *trace, tio_trace_view *out);
+void tio_trace_free(tio_trace *trace);
+
+/* Runs iterations of the real kernels (uncapped layout: the arena must hold the whole
+ * iteration), marks every operand of every launch active and times each launch with HIP events;
+ * tau = median of three iterations.  tokens/labels: host int32 [batch, seq_len].
+ * mode TIO_PROFILE_MODELLED skips the GPU and equals tio_trace_build. */
+int tio_profile_iteration(tio_ctx *ctx, const int32_t *tokens, const int32_t *labels, int mode,
+                          tio_trace **out);
+
+/* Inactive periods and memory demand per kernel. */
+int tio_analyze_lifetimes(const tio_trace *trace, tio_lifetimes **out);
+int tio_lifetimes_export(const tio_lifetimes *life, tio_lifetimes_view *out);
+void tio_lifetimes_free(tio_lifetimes *life);
+
+/* ---- Section 3.2: Algorithm 1 + urgent pass + address assignment (pure CPU) ------------------- */
+/* mem_cap_bytes: M_GPU.  slow_tier_bw: bytes/s of each migration channel (0 = unlimited).
+ * An entry is issued just before kernel (trigger mod N) is launched, once kernel trigger-1 has
+ * completed.  An offload must be complete before kernel `deadline` reuses the memory; a prefetch
+ * before kernel `deadline` (the tensor's next use) runs.  The tensor is counted out of GPU memory
+ * at kernels [offload.deadline, prefetch.trigger-1].  Returning 0 with forced (urgent) entries
+ * is not an error: the engine stalls kernels as the paper describes.  opts may be NULL. */
+int tio_build_plan(const tio_trace *trace, const tio_lifetimes *life, uint64_t mem_cap_bytes,
+                   uint64_t slow_tier_bw, const tio_plan_opts *opts, tio_plan **out);
+int tio_plan_export(const tio_plan *plan, tio_plan_view *out);
+/* Structural re-check of a plan against trace and lifetimes: residency of every operand,
+ * residency <= cap at every kernel, non-overlapping addresses. */
+int tio_plan_validate(const tio_trace *trace, const tio_lifetimes *life, const tio_plan *plan);
+void tio_plan_free(tio_plan *plan);
+
+/* ---- Section 3.3: runtime ---------------------------------------------------------------------- */
+int tio_ctx_create(const tio_model_cfg *cfg, const tio_runtime_cfg *rt, tio_ctx **out);
+int tio_ctx_destroy(tio_ctx *ctx);
+/* Loads parameter `index` from host fp32 values (rounded to the compute precision; fp32 master
+ * copy kept in bf16 mode); moments are zeroed and the step counter of the context is reset. */
+int tio_params_load(tio_ctx *ctx, int32_t index, const float *host_values, int64_t numel);
+/* which: 0 compute weight, 1 master copy (bf16 mode only), 2 first moment, 3 second moment;
+ * values are returned as fp32 wherever the tensor currently lives (GPU or slow tier). */
+int tio_params_read(tio_ctx *ctx, int32_t index, int32_t which, float *host_dst, int64_t numel);
+/* Gradient of parameter `index` as captured during the last step run with capture_grads != 0. */
+int tio_grads_read(tio_ctx *ctx, int32_t index, float *host_dst, int64_t numel);
+/* Bandwidth enforced on the copy streams from the next step on (0 = unthrottled). */
+int tio_set_slow_tier_bw(tio_ctx *ctx, uint64_t bytes_per_s);
+
+/* One training iteration: forward, backward, AdamW, with the plan's migrations on the copy
+ * streams.  plan == NULL runs the uncapped layout with no migration.  tokens/labels: host int32.
+ * Blocks until the compute stream has finished the iteration (copies may still be in flight). */
+int tio_train_step(tio_ctx *ctx, const int32_t *tokens, const int32_t *labels,
+                   const tio_plan *plan, int32_t capture_grads, tio_step_stats *out);
+
+/* ---- single operators on caller-provided device buffers (kernel parity tests, benchmarks) ---- */
+/* C[M,N] = A . B^T (+ bias[N]) (+ resid[M,N]); a_kmajor/b_kmajor: operand stored [K, rows]
+ * instead of [rows, K].  dtype TIO_PREC_*.  All leading dimensions in elements, multiples of 8. */
+int tio_op_gemm(void *stream, int32_t dtype, int32_t a_kmajor, int32_t b_kmajor,
+                int64_t M, int64_t N, int64_t K,
+                const void *A, int64_t lda, const void *B, int64_t ldb,
+                const void *bias, const void *resid, int64_t ldr, void *C, int64_t ldc);
+/* Timed repetitions of one operator on the given stream, HIP events around the launches;
+ * returns average ns per launch.  op codes as in the trace; dims as documented per operator. */
+int tio_op_bench(tio_ctx *ctx, int32_t kernel_index, int32_t reps, double *out_avg_ns);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TERAIO_H */

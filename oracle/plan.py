@@ -285,5 +285,5 @@ def build_plan(trace, life, cap, bw, duplex=True, min_bytes=0):
     for pair, (t, s, start, end, k_off, k_pre, u_off, u_pre) in enumerate(sel):
         entries.append((t, OFFLOAD, start + 1, k_off, u_off, pair))
         entries.append((t, PREFETCH, k_pre + 1, end, u_pre, pair))
-    entries.sort(key=lambda e: (e[2] % N, -e[4], e[1], e[0], e[5]))
+    entries.sort(key=lambda e: (e[2] % N, e[1], -e[4], e[0], e[5]))
     return dict(entries=entries, Mp=Mp, n_greedy=n_greedy, n_forced=len(sel) - n_greedy)

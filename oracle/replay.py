@@ -61,7 +61,7 @@ def check_plan(trace, life, plan, cap):
     if entries:
         assert moved >= max(life["M"]) - cap, "moved fewer bytes than peak - capacity"
     # sorted in issue order
-    key = lambda e: (e[2] % N, -e[4], e[1], e[0], e[5])
+    key = lambda e: (e[2] % N, e[1], -e[4], e[0], e[5])
     assert list(entries) == sorted(entries, key=key)
     return dict(bytes_per_direction=moved, pairs=len(win))
 

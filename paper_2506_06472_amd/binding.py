@@ -1,0 +1,245 @@
+"""ctypes binding of libteraio.so: argument marshalling only, same names as the C ABI.
+
+Every step of the method runs inside the library; nothing here computes.  The
+library must be present: loading fails loudly otherwise (there is no fallback).
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libteraio.so")
+
+ARCH = {"gpt": 0, "llama": 1}
+PREC = {"fp32": 0, "bf16": 1}
+PROFILE_MEASURED, PROFILE_MODELLED = 0, 1
+OFFLOAD, PREFETCH = 0, 1
+
+
+class TioError(RuntimeError):
+    def __init__(self, code, msg):
+        super().__init__(f"teraio error {code}: {msg}")
+        self.code = code
+
+
+class ModelCfg(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("arch", "n_layers", "d_model", "n_heads", "d_ff", "vocab", "seq_len",
+                                          "batch", "precision")] + \
+               [(n, C.c_float) for n in ("lr", "beta1", "beta2", "adam_eps", "weight_decay", "norm_eps", "rope_theta")]
+
+
+class RuntimeCfg(C.Structure):
+    _fields_ = [("arena", C.c_void_p), ("arena_bytes", C.c_uint64), ("host_pool", C.c_void_p),
+                ("host_bytes", C.c_uint64), ("compute_stream", C.c_void_p), ("d2h_stream", C.c_void_p),
+                ("h2d_stream", C.c_void_p), ("slow_tier_bw", C.c_uint64), ("poison_freed", C.c_int32),
+                ("reserved", C.c_int32)]
+
+
+class TraceView(C.Structure):
+    _fields_ = [("n_kernels", C.c_int32), ("n_tensors", C.c_int32), ("n_persistent", C.c_int32),
+                ("n_operands", C.c_int32),
+                ("op", C.POINTER(C.c_int32)), ("operand_off", C.POINTER(C.c_int32)),
+                ("operand_tensor", C.POINTER(C.c_int32)), ("operand_flags", C.POINTER(C.c_int32)),
+                ("flops", C.POINTER(C.c_int64)), ("tau_ns", C.POINTER(C.c_int64)),
+                ("tensor_bytes", C.POINTER(C.c_uint64)), ("tensor_kind", C.POINTER(C.c_int32))]
+
+
+class LifetimesView(C.Structure):
+    _fields_ = [("n_kernels", C.c_int32), ("n_periods", C.c_int32), ("M", C.POINTER(C.c_uint64)),
+                ("tensor", C.POINTER(C.c_int32)), ("bytes", C.POINTER(C.c_uint64)),
+                ("start", C.POINTER(C.c_int32)), ("end", C.POINTER(C.c_int32))]
+
+
+class PlanEntry(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("tensor", "kind", "trigger", "deadline", "urgent", "pair")]
+
+
+class Alloc(C.Structure):
+    _fields_ = [("tensor", C.c_int32), ("first_kernel", C.c_int32), ("last_kernel", C.c_int32),
+                ("address", C.c_uint64)]
+
+
+class PlanView(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("n_kernels", "n_entries", "n_greedy", "n_forced", "n_allocs", "reserved")] + \
+               [("entries", C.POINTER(PlanEntry)), ("Mp", C.POINTER(C.c_uint64)), ("allocs", C.POINTER(Alloc))] + \
+               [(n, C.c_uint64) for n in ("cap_bytes", "planning_cap_bytes", "arena_bytes_needed",
+                                          "host_bytes_needed", "bytes_per_direction")]
+
+
+class PlanOpts(C.Structure):
+    _fields_ = [("duplex", C.c_int32), ("layout_retries", C.c_int32), ("min_bytes", C.c_uint64),
+                ("arena_bytes", C.c_uint64)]
+
+
+class StepStats(C.Structure):
+    _fields_ = [("loss", C.c_float), ("step", C.c_int32), ("wall_ns", C.c_int64), ("kernel_ns", C.c_int64),
+                ("d2h_bytes", C.c_uint64), ("h2d_bytes", C.c_uint64), ("d2h_busy_ns", C.c_int64),
+                ("h2d_busy_ns", C.c_int64), ("n_kernels", C.c_int32), ("n_migrations", C.c_int32)]
+
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(f"{LIB_PATH} is missing: run `python -c 'import __graft_entry__ as g; g.build()'`")
+        _lib = C.CDLL(LIB_PATH)
+        _lib.tio_last_error.restype = C.c_char_p
+        _lib.tio_version.restype = C.c_char_p
+        for name in ("tio_trace_free", "tio_lifetimes_free", "tio_plan_free"):
+            getattr(_lib, name).restype = None
+            getattr(_lib, name).argtypes = [C.c_void_p]
+    return _lib
+
+
+def _check(rc):
+    if rc != 0:
+        raise TioError(rc, lib().tio_last_error().decode())
+
+
+def model_cfg(cfg: dict) -> ModelCfg:
+    return ModelCfg(ARCH[cfg["arch"]], cfg["L"], cfg["d"], cfg["H"], cfg["f"], cfg["V"], cfg["T"], cfg["B"],
+                    PREC[cfg["precision"]], cfg.get("lr", 1e-3), cfg.get("beta1", 0.9), cfg.get("beta2", 0.999),
+                    cfg.get("adam_eps", 1e-8), cfg.get("weight_decay", 0.01), cfg.get("eps", 1e-5),
+                    cfg.get("rope_theta", 10000.0))
+
+
+def _arr(ptr, n, dtype):
+    if n == 0:
+        return np.zeros(0, dtype=dtype)
+    return np.ctypeslib.as_array(ptr, shape=(n,)).astype(dtype, copy=True)
+
+
+# ------------------------------------------------------------------ model description
+def tio_param_list(cfg: dict):
+    """[(name, rows, cols)] in parameter-list order."""
+    mc = model_cfg(cfg)
+    n = C.c_int32()
+    _check(lib().tio_param_count(C.byref(mc), C.byref(n)))
+    out = []
+    buf = C.create_string_buffer(64)
+    for i in range(n.value):
+        r, c = C.c_int64(), C.c_int64()
+        _check(lib().tio_param_info(C.byref(mc), i, buf, 64, C.byref(r), C.byref(c)))
+        out.append((buf.value.decode(), r.value, c.value))
+    return out
+
+
+# ------------------------------------------------------------------ trace / lifetimes / plan handles
+class Trace:
+    def __init__(self, handle):
+        self.h = handle
+
+    def __del__(self):
+        if getattr(self, "h", None):
+            lib().tio_trace_free(self.h)
+            self.h = None
+
+    def export(self):
+        v = TraceView()
+        _check(lib().tio_trace_export(self.h, C.byref(v)))
+        return dict(n_kernels=v.n_kernels, n_tensors=v.n_tensors, n_persistent=v.n_persistent,
+                    op=_arr(v.op, v.n_kernels, np.int32), operand_off=_arr(v.operand_off, v.n_kernels + 1, np.int32),
+                    operand_tensor=_arr(v.operand_tensor, v.n_operands, np.int32),
+                    operand_flags=_arr(v.operand_flags, v.n_operands, np.int32),
+                    flops=_arr(v.flops, v.n_kernels, np.int64), tau=_arr(v.tau_ns, v.n_kernels, np.int64),
+                    tensor_bytes=_arr(v.tensor_bytes, v.n_tensors, np.uint64),
+                    tensor_kind=_arr(v.tensor_kind, v.n_tensors, np.int32))
+
+    def set_tau(self, tau):
+        t = np.ascontiguousarray(tau, dtype=np.int64)
+        _check(lib().tio_trace_set_tau(self.h, t.ctypes.data_as(C.POINTER(C.c_int64)), len(t)))
+
+
+def tio_trace_build(cfg: dict) -> Trace:
+    mc = model_cfg(cfg)
+    h = C.c_void_p()
+    _check(lib().tio_trace_build(C.byref(mc), C.byref(h)))
+    return Trace(h)
+
+
+def tio_trace_import(n_persistent, operand_lists, tensor_bytes, tau, tensor_kind=None, op=None) -> Trace:
+    """operand_lists: per kernel a sorted list of (tensor, flags)."""
+    nk, nt = len(operand_lists), len(tensor_bytes)
+    off = np.zeros(nk + 1, dtype=np.int32)
+    ten, fl = [], []
+    for k, ops in enumerate(operand_lists):
+        for t, f in ops:
+            ten.append(t)
+            fl.append(f)
+        off[k + 1] = len(ten)
+    ten = np.asarray(ten, dtype=np.int32)
+    fl = np.asarray(fl, dtype=np.int32)
+    tb = np.asarray(tensor_bytes, dtype=np.uint64)
+    ta = np.asarray(tau, dtype=np.int64)
+    kind = np.asarray(tensor_kind if tensor_kind is not None else [5] * nt, dtype=np.int32)
+    opc = np.asarray(op if op is not None else [0] * nk, dtype=np.int32)
+    fz = np.zeros(nk, dtype=np.int64)
+    p = lambda a, ty: a.ctypes.data_as(C.POINTER(ty))
+    v = TraceView(nk, nt, n_persistent, len(ten), p(opc, C.c_int32), p(off, C.c_int32), p(ten, C.c_int32),
+                  p(fl, C.c_int32), p(fz, C.c_int64), p(ta, C.c_int64), p(tb, C.c_uint64), p(kind, C.c_int32))
+    h = C.c_void_p()
+    _check(lib().tio_trace_import(C.byref(v), C.byref(h)))
+    return Trace(h)
+
+
+class Lifetimes:
+    def __init__(self, handle):
+        self.h = handle
+
+    def __del__(self):
+        if getattr(self, "h", None):
+            lib().tio_lifetimes_free(self.h)
+            self.h = None
+
+    def export(self):
+        v = LifetimesView()
+        _check(lib().tio_lifetimes_export(self.h, C.byref(v)))
+        n = v.n_periods
+        return dict(M=_arr(v.M, v.n_kernels, np.uint64), tensor=_arr(v.tensor, n, np.int32),
+                    bytes=_arr(v.bytes, n, np.uint64), start=_arr(v.start, n, np.int32), end=_arr(v.end, n, np.int32))
+
+
+def tio_analyze_lifetimes(trace: Trace) -> Lifetimes:
+    h = C.c_void_p()
+    _check(lib().tio_analyze_lifetimes(trace.h, C.byref(h)))
+    return Lifetimes(h)
+
+
+class Plan:
+    def __init__(self, handle):
+        self.h = handle
+
+    def __del__(self):
+        if getattr(self, "h", None):
+            lib().tio_plan_free(self.h)
+            self.h = None
+
+    def export(self):
+        v = PlanView()
+        _check(lib().tio_plan_export(self.h, C.byref(v)))
+        entries = [(e.tensor, e.kind, e.trigger, e.deadline, e.urgent, e.pair)
+                   for e in (v.entries[i] for i in range(v.n_entries))]
+        allocs = [(a.tensor, a.first_kernel, a.last_kernel, a.address) for a in (v.allocs[i] for i in range(v.n_allocs))]
+        return dict(entries=entries, Mp=[int(x) for x in _arr(v.Mp, v.n_kernels, np.uint64)], allocs=allocs,
+                    n_greedy=v.n_greedy, n_forced=v.n_forced, cap=v.cap_bytes, planning_cap=v.planning_cap_bytes,
+                    arena_needed=v.arena_bytes_needed, host_needed=v.host_bytes_needed,
+                    bytes_per_direction=v.bytes_per_direction)
+
+
+def tio_build_plan(trace: Trace, life: Lifetimes, mem_cap_bytes: int, slow_tier_bw: int, duplex=True,
+                   min_bytes=0, arena_bytes=0, layout_retries=24) -> Plan:
+    o = PlanOpts(1 if duplex else 0, layout_retries, min_bytes, arena_bytes)
+    h = C.c_void_p()
+    _check(lib().tio_build_plan(trace.h, life.h, C.c_uint64(mem_cap_bytes), C.c_uint64(slow_tier_bw), C.byref(o),
+                                C.byref(h)))
+    return Plan(h)
+
+
+def tio_plan_validate(trace: Trace, life: Lifetimes, plan: Plan):
+    _check(lib().tio_plan_validate(trace.h, life.h, plan.h))

@@ -1,0 +1,502 @@
+// Lifetime analysis (Section 3.1), Algorithm 1 with the urgent pass (Section 3.2) and the arena
+// address assignment.  Integer arithmetic only; every tie is broken deterministically.
+#include "analysis.h"
+
+#include <algorithm>
+#include <map>
+#include <numeric>
+#include <tuple>
+
+namespace tio {
+
+typedef unsigned __int128 u128;
+
+// ------------------------------------------------------------------------------------------------
+// trace
+// ------------------------------------------------------------------------------------------------
+static uint64_t mix(uint64_t h, uint64_t v) {
+    h ^= v + 0x9E3779B97F4A7C15ull + (h << 6) + (h >> 2);
+    return h * 0xBF58476D1CE4E5B9ull;
+}
+
+void Trace::rehash() {
+    uint64_t h = 0x1234567ull;
+    h = mix(h, (uint64_t)n_kernels); h = mix(h, (uint64_t)n_tensors); h = mix(h, (uint64_t)n_persistent);
+    for (auto v : op) h = mix(h, (uint64_t)v);
+    for (auto v : operand_off) h = mix(h, (uint64_t)v);
+    for (auto v : operand_tensor) h = mix(h, (uint64_t)v);
+    for (auto v : operand_flags) h = mix(h, (uint64_t)v);
+    for (auto v : tensor_bytes) h = mix(h, v);
+    structure_hash = h;
+}
+
+Trace trace_from_program(const Program &P) {
+    Trace t;
+    t.n_kernels = (int32_t)P.kernels.size();
+    t.n_tensors = (int32_t)P.tensors.size();
+    t.n_persistent = P.n_persistent;
+    t.operand_off.push_back(0);
+    for (const KernelRec &k : P.kernels) {
+        std::map<int32_t, int32_t> fl;            // sorted by tensor id, flags merged
+        for (int r = 0; r < kMaxRoles; ++r)
+            if (k.t[r] >= 0) fl[k.t[r]] |= k.fl[r];
+        for (auto &kv : fl) { t.operand_tensor.push_back(kv.first); t.operand_flags.push_back(kv.second); }
+        t.operand_off.push_back((int32_t)t.operand_tensor.size());
+        t.op.push_back(k.op);
+        t.flops.push_back(k.flops);
+    }
+    for (const TensorInfo &ti : P.tensors) { t.tensor_bytes.push_back(ti.bytes); t.tensor_kind.push_back(ti.kind); }
+    t.tau.assign(t.n_kernels, 0);
+    model_tau(t);
+    t.rehash();
+    return t;
+}
+
+void model_tau(Trace &t) {
+    // half of the dense bf16 MFMA peak, half of the HBM peak, a fixed launch cost
+    const u128 F = 1250000000000000ull, Wb = 4000000000000ull;
+    const int64_t launch = 4000;
+    for (int k = 0; k < t.n_kernels; ++k) {
+        u128 bytes = 0;
+        for (int i = t.operand_off[k]; i < t.operand_off[k + 1]; ++i) bytes += t.tensor_bytes[t.operand_tensor[i]];
+        u128 tf = ((u128)t.flops[k] * 1000000000ull + F - 1) / F;
+        u128 tb = (bytes * 1000000000ull + Wb - 1) / Wb;
+        t.tau[k] = (int64_t)std::max(tf, tb) + launch;
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// Section 3.1: active kernels -> inactive periods and memory demand
+// ------------------------------------------------------------------------------------------------
+Lifetimes analyze(const Trace &t) {
+    Lifetimes L;
+    const int N = t.n_kernels;
+    L.n_kernels = N;
+    L.structure_hash = t.structure_hash;
+    L.active.assign(t.n_tensors, {});
+    for (int k = 0; k < N; ++k)
+        for (int i = t.operand_off[k]; i < t.operand_off[k + 1]; ++i) L.active[t.operand_tensor[i]].push_back(k);
+    // difference array for the transient lifetimes
+    std::vector<int64_t> diff(N + 1, 0);
+    uint64_t always = 0;
+    for (int id = 0; id < t.n_tensors; ++id) {
+        const auto &a = L.active[id];
+        const uint64_t s = t.tensor_bytes[id];
+        const bool persistent = id < t.n_persistent;
+        if (persistent) always += s;
+        else if (!a.empty()) { diff[a.front()] += (int64_t)s; diff[a.back() + 1] -= (int64_t)s; }
+        if (a.empty() || t.tensor_kind[id] == KIND_INPUT) continue;   // host rewrites inputs every iteration
+        for (size_t i = 0; i + 1 < a.size(); ++i)
+            if (a[i + 1] - a[i] >= 2) L.periods.push_back({id, s, a[i], a[i + 1]});
+        if (persistent && a.front() + N - a.back() >= 2) L.periods.push_back({id, s, a.back(), a.front() + N});
+    }
+    L.M.assign(N, 0);
+    int64_t run = 0;
+    for (int k = 0; k < N; ++k) { run += diff[k]; L.M[k] = always + (uint64_t)run; }
+    for (const Period &p : L.periods) {
+        L.v_tensor.push_back(p.tensor); L.v_bytes.push_back(p.bytes);
+        L.v_start.push_back(p.start); L.v_end.push_back(p.end);
+    }
+    return L;
+}
+
+// ------------------------------------------------------------------------------------------------
+// I/O bandwidth usage state of one migration direction: busy intervals on the cyclic timeline
+// ------------------------------------------------------------------------------------------------
+namespace {
+
+struct Channel {
+    int64_t P;
+    std::vector<int64_t> b, e;       // sorted, disjoint, merged when touching; 0 <= b < e <= P
+
+    // smallest t >= lo with [t,t+dur) free and t+dur <= hi; -1 if none
+    int64_t earliest(int64_t lo, int64_t hi, int64_t dur) const {
+        if (hi - lo < dur) return -1;
+        int64_t t = lo;
+        for (int64_t j = lo / P; j <= (hi - 1) / P; ++j) {
+            const int64_t off = j * P;
+            size_t i = std::upper_bound(e.begin(), e.end(), lo - off) - e.begin();
+            for (; i < b.size() && b[i] + off < hi; ++i) {
+                if (t + dur <= b[i] + off) return t;
+                t = std::max(t, e[i] + off);
+                if (t + dur > hi) return -1;
+            }
+        }
+        return t + dur <= hi ? t : -1;
+    }
+    // largest t >= lo with [t,t+dur) free and t+dur <= hi; -1 if none
+    int64_t latest(int64_t lo, int64_t hi, int64_t dur) const {
+        if (hi - lo < dur) return -1;
+        int64_t t = hi - dur;
+        for (int64_t j = (hi - 1) / P; j >= lo / P; --j) {
+            const int64_t off = j * P;
+            int64_t i = (int64_t)(std::lower_bound(b.begin(), b.end(), hi - off) - b.begin()) - 1;
+            for (; i >= 0 && e[i] + off > lo; --i) {
+                if (e[i] + off <= t) return t;
+                t = std::min(t, b[i] + off - dur);
+                if (t < lo) return -1;
+            }
+        }
+        return t >= lo ? t : -1;
+    }
+    void put(int64_t x, int64_t y) {
+        size_t i = std::lower_bound(b.begin(), b.end(), x) - b.begin();
+        const bool left = i > 0 && e[i - 1] == x, right = i < b.size() && b[i] == y;
+        if (left && right) { e[i - 1] = e[i]; b.erase(b.begin() + i); e.erase(e.begin() + i); }
+        else if (left) e[i - 1] = y;
+        else if (right) b[i] = x;
+        else { b.insert(b.begin() + i, x); e.insert(e.begin() + i, y); }
+    }
+    void insert(int64_t t0, int64_t t1) {
+        if (t1 <= t0) return;
+        const int64_t a = t0 % P, z = a + (t1 - t0);
+        if (z <= P) put(a, z);
+        else { put(a, P); put(0, z - P); }
+    }
+};
+
+struct Cand { int32_t tensor; uint64_t bytes; int32_t start, end; bool alive; };
+
+// lexicographic "better" for the forced pass: furthest next use, larger tensor, earlier start, smaller id
+struct ForcedKey {
+    int64_t dist; uint64_t bytes; int32_t start, tensor;
+    bool better_than(const ForcedKey &o) const {
+        return std::make_tuple(dist, bytes, -start, -tensor) > std::make_tuple(o.dist, o.bytes, -o.start, -o.tensor);
+    }
+};
+
+}  // namespace
+
+void select_periods(const Trace &t, const Lifetimes &life, uint64_t cap, uint64_t bw, bool duplex,
+                    uint64_t min_bytes, Plan &out) {
+    const int N = t.n_kernels;
+    const std::vector<int64_t> &tau = t.tau;
+    std::vector<int64_t> T(2 * N + 1, 0);
+    for (int k = 0; k < 2 * N; ++k) T[k + 1] = T[k] + tau[k % N];
+    const int64_t Ttot = T[N];
+    std::vector<uint64_t> Mp = life.M;
+    std::vector<Cand> I, small;
+    for (const Period &p : life.periods)
+        (p.bytes >= min_bytes ? I : small).push_back({p.tensor, p.bytes, p.start, p.end, true});
+    Channel ch_off{Ttot, {}, {}}, ch_pre_own{Ttot, {}, {}};
+    Channel &ch_pre = duplex ? ch_pre_own : ch_off;
+    std::vector<Pair> sel;
+    auto dur = [&](uint64_t s) -> int64_t { return bw ? (int64_t)(((u128)s * 1000000000ull + bw - 1) / bw) : 0; };
+
+    // ---- Algorithm 1
+    std::vector<int64_t> over(2 * N + 1);
+    while (*std::max_element(Mp.begin(), Mp.end()) > cap) {
+        over[0] = 0;
+        for (int k = 0; k < 2 * N; ++k) over[k + 1] = over[k] + (Mp[k % N] > cap ? tau[k % N] : 0);
+        int best = -1;
+        int64_t best_score = 0, bg = 0, bto = 0, btp = 0, bd = 0;
+        int32_t bko = 0, bkp = 0;
+        for (int i = 0; i < (int)I.size(); ++i) {
+            const Cand &c = I[i];
+            if (!c.alive) continue;
+            const int64_t d = dur(c.bytes), lo = T[c.start + 1], hi = T[c.end];
+            const int64_t g = ch_off.earliest(lo, hi, d);
+            if (g < 0) continue;
+            const int64_t t_offloaded = g + d;
+            const int64_t t_prefetch = ch_pre.latest(lo, hi, d);
+            if (t_prefetch < 0 || !(t_offloaded < t_prefetch)) continue;
+            const int32_t k_off = (int32_t)(std::lower_bound(T.begin(), T.end(), t_offloaded) - T.begin());
+            const int32_t k_pre = (int32_t)(std::upper_bound(T.begin(), T.end(), t_prefetch) - T.begin()) - 2;
+            if (k_off > k_pre) continue;
+            const int64_t score = over[k_pre + 1] - over[k_off];     // B / s = sum of tau over the region C
+            if (score <= 0) continue;
+            bool take = best < 0;
+            if (!take) {
+                const Cand &o = I[best];
+                take = std::make_tuple(score, c.bytes, -c.start, -c.tensor, -c.end) >
+                       std::make_tuple(best_score, o.bytes, -o.start, -o.tensor, -o.end);
+            }
+            if (take) { best = i; best_score = score; bg = g; bto = t_offloaded; btp = t_prefetch; bd = d; bko = k_off; bkp = k_pre; }
+        }
+        if (best < 0) break;
+        Cand &c = I[best];
+        sel.push_back({c.tensor, c.bytes, c.start, c.end, bko, bkp, 0, 0});
+        for (int k = bko; k <= bkp; ++k) Mp[k % N] -= c.bytes;
+        ch_off.insert(bg, bto);
+        ch_pre.insert(btp, btp + bd);
+        c.alive = false;
+    }
+    out.n_greedy = (int32_t)sel.size();
+
+    // ---- urgent pass: at every kernel still above capacity evict the inactive tensor whose next use
+    //      is furthest away, either by widening an already selected window or by selecting a new period
+    auto frame = [&](int32_t start, int32_t end, int k) -> int32_t {
+        if (start < k && k < end) return k;
+        if (start < k + N && k + N < end) return k + N;
+        return -1;
+    };
+    for (int k = 0; k < N; ++k) {
+        while (Mp[k] > cap) {
+            int what = 0, ref = -1; int32_t bkk = 0;     // what: 1 selected pair, 2 period in I, 3 period in small
+            ForcedKey bk{};
+            auto consider = [&](int w, int r, int32_t kk, int32_t end, uint64_t bytes, int32_t start, int32_t tensor) {
+                ForcedKey key{(int64_t)end - kk, bytes, start, tensor};
+                if (!what || key.better_than(bk)) { what = w; ref = r; bkk = kk; bk = key; }
+            };
+            for (int pass = 0; pass < 2 && !what; ++pass) {
+                for (int i = 0; i < (int)sel.size(); ++i) {
+                    const Pair &p = sel[i];
+                    const int32_t kk = frame(p.start, p.end, k);
+                    if (kk < 0 || (p.k_off <= kk && kk <= p.k_pre)) continue;
+                    if (pass == 0 && min_bytes && p.bytes < min_bytes) continue;
+                    consider(1, i, kk, p.end, p.bytes, p.start, p.tensor);
+                }
+                std::vector<Cand> &pool = pass == 0 ? I : small;
+                for (int i = 0; i < (int)pool.size(); ++i) {
+                    const Cand &c = pool[i];
+                    if (!c.alive) continue;
+                    const int32_t kk = frame(c.start, c.end, k);
+                    if (kk < 0) continue;
+                    consider(pass == 0 ? 2 : 3, i, kk, c.end, c.bytes, c.start, c.tensor);
+                }
+            }
+            if (!what)
+                throw PlanError{TIO_ERR_ACTIVE_SET_EXCEEDS_CAP,
+                                "operands of kernel " + std::to_string(k) + " alone exceed the capacity"};
+            int idx = ref;
+            if (what != 1) {
+                Cand &c = (what == 2 ? I : small)[ref];
+                c.alive = false;
+                sel.push_back({c.tensor, c.bytes, c.start, c.end, bkk, bkk - 1, 1, 1});   // empty window, grown below
+                idx = (int)sel.size() - 1;
+            }
+            Pair &p = sel[idx];
+            if (bkk < p.k_off) {                       // pull the offload deadline forward
+                for (int j = bkk; j < p.k_off; ++j) Mp[j % N] -= p.bytes;
+                p.k_off = bkk; p.urgent_off = 1;
+            } else {                                   // push the prefetch back
+                int32_t last = bkk;
+                for (int j = bkk; j < p.end; ++j) if (Mp[j % N] > cap) last = j;
+                for (int j = p.k_pre + 1; j <= last; ++j) Mp[j % N] -= p.bytes;
+                p.k_pre = last; p.urgent_pre = 1;
+            }
+        }
+    }
+    out.n_forced = (int32_t)sel.size() - out.n_greedy;
+    out.n_kernels = N;
+    out.Mp = Mp;
+    out.pairs = sel;
+    out.entries.clear();
+    out.bytes_moved = 0;
+    for (int i = 0; i < (int)sel.size(); ++i) {
+        const Pair &p = sel[i];
+        out.entries.push_back({p.tensor, TIO_OFFLOAD, p.start + 1, p.k_off, p.urgent_off, i});
+        out.entries.push_back({p.tensor, TIO_PREFETCH, p.k_pre + 1, p.end, p.urgent_pre, i});
+        out.bytes_moved += p.bytes;
+    }
+    std::sort(out.entries.begin(), out.entries.end(), [N](const tio_plan_entry &a, const tio_plan_entry &b) {
+        // at one trigger point offloads are issued before prefetches (a prefetch may reuse the range an
+        // offload of the same point empties), urgent ones first within each direction
+        return std::make_tuple(a.trigger % N, a.kind, -a.urgent, a.tensor, a.pair) <
+               std::make_tuple(b.trigger % N, b.kind, -b.urgent, b.tensor, b.pair);
+    });
+}
+
+// ------------------------------------------------------------------------------------------------
+// address assignment
+// ------------------------------------------------------------------------------------------------
+static bool time_conflict(const Alloc &x, const Alloc &y, int N) {
+    if (x.whole_cycle || y.whole_cycle) return true;
+    auto ov = [](int a0, int a1, int b0, int b1) { return a0 <= b1 && b0 <= a1; };
+    return ov(x.first, x.last, y.first, y.last) || ov(x.first, x.last, y.first + N, y.last + N) ||
+           ov(x.first + N, x.last + N, y.first, y.last);
+}
+
+bool assign_addresses(const Trace &t, const Lifetimes &life, uint64_t arena_bytes, Plan &plan) {
+    const int N = t.n_kernels;
+    plan.allocs.clear();
+    plan.alloc_of.assign(t.n_tensors, {});
+    std::vector<std::vector<int>> pairs_of(t.n_tensors);
+    for (int i = 0; i < (int)plan.pairs.size(); ++i) pairs_of[plan.pairs[i].tensor].push_back(i);
+    for (int id = 0; id < t.n_tensors; ++id) {
+        const auto &a = life.active[id];
+        auto &ps = pairs_of[id];
+        std::sort(ps.begin(), ps.end(), [&](int x, int y) { return plan.pairs[x].start < plan.pairs[y].start; });
+        auto add = [&](int first, int last, int born, int ended, bool whole) {
+            Alloc al;
+            al.tensor = id; al.born_by_pair = born; al.ended_by_pair = ended; al.whole_cycle = whole;
+            if (first >= N) { first -= N; last -= N; }
+            al.first = first; al.last = last;
+            plan.allocs.push_back(al);
+            const int idx = (int)plan.allocs.size() - 1;
+            plan.alloc_of[id].push_back(idx);
+            if (born >= 0) plan.pairs[born].alloc_after = idx;
+            if (ended >= 0) plan.pairs[ended].alloc_before = idx;
+        };
+        if (id < t.n_persistent) {
+            if (ps.empty()) { add(0, N - 1, -1, -1, true); continue; }
+            for (size_t i = 0; i < ps.size(); ++i) {
+                const Pair &cur = plan.pairs[ps[i]];
+                const bool wrap = i + 1 == ps.size();
+                const Pair &nxt = plan.pairs[ps[wrap ? 0 : i + 1]];
+                add(cur.k_pre + 1, nxt.k_off - 1 + (wrap ? N : 0), ps[i], ps[wrap ? 0 : i + 1], false);
+            }
+        } else {
+            if (a.empty()) continue;
+            int cur = a.front(), born = -1;
+            for (int pi : ps) {
+                const Pair &p = plan.pairs[pi];
+                add(cur, p.k_off - 1, born, pi, false);
+                cur = p.k_pre + 1; born = pi;
+            }
+            add(cur, a.back(), born, -1, false);
+        }
+    }
+    // first fit, largest first
+    const int A = (int)plan.allocs.size();
+    std::vector<int> order(A);
+    std::iota(order.begin(), order.end(), 0);
+    std::sort(order.begin(), order.end(), [&](int x, int y) {
+        const Alloc &ax = plan.allocs[x], &ay = plan.allocs[y];
+        const uint64_t sx = t.tensor_bytes[ax.tensor], sy = t.tensor_bytes[ay.tensor];
+        return std::make_tuple(sy, ax.first, ax.tensor, ax.last) < std::make_tuple(sx, ay.first, ay.tensor, ay.last);
+    });
+    std::vector<int> placed;
+    std::vector<std::pair<uint64_t, uint64_t>> busy;
+    uint64_t top = 0;
+    for (int idx : order) {
+        Alloc &al = plan.allocs[idx];
+        const uint64_t s = t.tensor_bytes[al.tensor];
+        busy.clear();
+        for (int j : placed) {
+            const Alloc &o = plan.allocs[j];
+            if (time_conflict(al, o, N)) busy.push_back({o.address, o.address + t.tensor_bytes[o.tensor]});
+        }
+        std::sort(busy.begin(), busy.end());
+        uint64_t addr = 0;
+        for (auto &iv : busy) {
+            if (addr + s <= iv.first) break;
+            addr = std::max(addr, iv.second);
+        }
+        al.address = addr;
+        top = std::max(top, addr + s);
+        placed.push_back(idx);
+    }
+    plan.arena_needed = top;
+
+    // slow-tier slots: a home slot for every persistent tensor, one slot per migrated transient period
+    uint64_t h = 0;
+    plan.persistent_home.assign(t.n_persistent, 0);
+    for (int id = 0; id < t.n_persistent; ++id) { plan.persistent_home[id] = h; h += t.tensor_bytes[id]; }
+    for (Pair &p : plan.pairs) {
+        if (p.tensor < t.n_persistent) p.host_offset = plan.persistent_home[p.tensor];
+        else { p.host_offset = h; h += p.bytes; }
+    }
+    plan.host_needed = h;
+
+    // address reuse: the first writer of an allocation waits for the offload that emptied the range.
+    // Sweep two cycles of the issue order with a map "address range -> last occupant".
+    std::vector<std::vector<int>> born_at(N);       // allocations that start at kernel k, prefetches first
+    for (const tio_plan_entry &e : plan.entries)
+        if (e.kind == TIO_PREFETCH) born_at[e.trigger % N].push_back(plan.pairs[e.pair].alloc_after);
+    for (int i = 0; i < A; ++i) {
+        const Alloc &al = plan.allocs[i];
+        if (al.born_by_pair < 0 && !al.whole_cycle) born_at[al.first % N].push_back(i);
+    }
+    std::map<uint64_t, std::pair<uint64_t, int>> occ;   // start -> (end, alloc)
+    for (int cycle = 0; cycle < 2; ++cycle)
+        for (int k = 0; k < N; ++k)
+            for (int ai : born_at[k]) {
+                Alloc &al = plan.allocs[ai];
+                const uint64_t a0 = al.address, a1 = a0 + t.tensor_bytes[al.tensor];
+                if (cycle == 1) al.wait_pairs.clear();
+                auto it = occ.lower_bound(a0);
+                if (it != occ.begin()) { auto pv = std::prev(it); if (pv->second.first > a0) it = pv; }
+                std::vector<std::pair<uint64_t, std::pair<uint64_t, int>>> keep;
+                while (it != occ.end() && it->first < a1) {
+                    const uint64_t b0 = it->first, b1 = it->second.first;
+                    const int who = it->second.second;
+                    const int ep = plan.allocs[who].ended_by_pair;
+                    if (cycle == 1 && ep >= 0 && std::find(al.wait_pairs.begin(), al.wait_pairs.end(), ep) == al.wait_pairs.end())
+                        al.wait_pairs.push_back(ep);
+                    if (b0 < a0) keep.push_back({b0, {a0, who}});
+                    if (b1 > a1) keep.push_back({a1, {b1, who}});
+                    it = occ.erase(it);
+                }
+                for (auto &kv : keep) occ[kv.first] = kv.second;
+                occ[a0] = {a1, ai};
+            }
+
+    // executor tables
+    plan.entries_at.assign(N, {});
+    plan.kernel_wait_pre.assign(N, {});
+    plan.kernel_wait_off.assign(N, {});
+    plan.kernel_needs_event.assign(N, 0);
+    for (int i = 0; i < (int)plan.entries.size(); ++i) {
+        const tio_plan_entry &e = plan.entries[i];
+        plan.entries_at[e.trigger % N].push_back(i);
+        plan.kernel_needs_event[(e.trigger - 1 + N) % N] = 1;
+    }
+    for (int i = 0; i < (int)plan.pairs.size(); ++i) plan.kernel_wait_pre[plan.pairs[i].end % N].push_back(i);
+    for (int i = 0; i < A; ++i) {
+        const Alloc &al = plan.allocs[i];
+        if (al.born_by_pair < 0 && !al.whole_cycle)
+            for (int p : al.wait_pairs) plan.kernel_wait_off[al.first % N].push_back(p);
+    }
+    plan.v_allocs.clear();
+    for (const Alloc &al : plan.allocs) plan.v_allocs.push_back({al.tensor, al.first, al.last, al.address});
+    return top <= arena_bytes;
+}
+
+uint64_t address_at(const Plan &plan, int32_t tensor, int32_t k) {
+    const int N = plan.n_kernels;
+    for (int ai : plan.alloc_of[tensor]) {
+        const Alloc &al = plan.allocs[ai];
+        if (al.whole_cycle || (al.first <= k && k <= al.last) || (al.first <= k + N && k + N <= al.last)) return al.address;
+    }
+    return UINT64_MAX;
+}
+
+// ------------------------------------------------------------------------------------------------
+// plan = selection + layout, with the planning capacity lowered until the layout fits the arena
+// ------------------------------------------------------------------------------------------------
+Plan build_plan(const Trace &t, const Lifetimes &life, uint64_t cap, uint64_t bw, const tio_plan_opts &o) {
+    if (t.structure_hash != life.structure_hash) throw PlanError{TIO_ERR_PLAN_STALE, "lifetimes belong to another trace"};
+    const uint64_t peak = *std::max_element(life.M.begin(), life.M.end());
+    const uint64_t arena = o.arena_bytes ? o.arena_bytes : cap;
+    const int retries = o.layout_retries > 0 ? o.layout_retries : 24;
+    uint64_t pc = std::min(cap, peak);
+    const uint64_t step = std::max<uint64_t>(256, std::min(cap, peak) / 50);
+    for (int r = 0; r <= retries; ++r) {
+        Plan p;
+        p.cap = cap; p.planning_cap = pc; p.bw = bw; p.structure_hash = t.structure_hash;
+        select_periods(t, life, pc, bw, o.duplex != 0, o.min_bytes, p);
+        if (assign_addresses(t, life, arena, p)) return p;
+        if (pc <= step) break;
+        pc -= step;
+    }
+    throw PlanError{TIO_ERR_ARENA_TOO_SMALL, "no address assignment fits the arena"};
+}
+
+void validate_plan(const Trace &t, const Lifetimes &life, const Plan &plan) {
+    const int N = t.n_kernels;
+    if (plan.structure_hash != t.structure_hash || plan.n_kernels != N) throw PlanError{TIO_ERR_PLAN_STALE, "plan belongs to another trace"};
+    std::vector<uint64_t> M2 = life.M;
+    for (const Pair &p : plan.pairs) {
+        if (!(p.start < p.k_off && p.k_off <= p.k_pre + 1 && p.k_pre + 1 <= p.end))
+            throw PlanError{TIO_ERR_PLAN_INVALID, "window outside its inactive period"};
+        for (int k = p.k_off; k <= p.k_pre; ++k) M2[k % N] -= p.bytes;
+    }
+    for (int k = 0; k < N; ++k) {
+        if (M2[k] != plan.Mp[k]) throw PlanError{TIO_ERR_PLAN_INVALID, "memory estimate differs from a recount"};
+        if (M2[k] > plan.planning_cap) throw PlanError{TIO_ERR_PLAN_INVALID, "residency above capacity at kernel " + std::to_string(k)};
+        for (int i = t.operand_off[k]; i < t.operand_off[k + 1]; ++i)
+            if (address_at(plan, t.operand_tensor[i], k) == UINT64_MAX)
+                throw PlanError{TIO_ERR_PLAN_INVALID, "operand not resident at kernel " + std::to_string(k)};
+    }
+    const int A = (int)plan.allocs.size();
+    for (int i = 0; i < A; ++i)
+        for (int j = i + 1; j < A; ++j) {
+            const Alloc &x = plan.allocs[i], &y = plan.allocs[j];
+            const uint64_t x1 = x.address + t.tensor_bytes[x.tensor], y1 = y.address + t.tensor_bytes[y.tensor];
+            if (x.address < y1 && y.address < x1 && time_conflict(x, y, N))
+                throw PlanError{TIO_ERR_PLAN_INVALID, "two resident tensors overlap in the arena"};
+        }
+}
+
+}  // namespace tio

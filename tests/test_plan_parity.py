@@ -1,0 +1,155 @@
+"""Library (C ABI, pure-CPU half) against the oracle, bit for bit: trace, lifetimes, plan."""
+import numpy as np
+import pytest
+
+import paper_2506_06472_amd as tio
+from oracle import plan as op
+from oracle import replay as orp
+from oracle import trace as ot
+from synth import CONFIGS
+from planlib import load_golden, random_trace
+
+
+def lib_trace_from_oracle(tr):
+    return tio.tio_trace_import(tr["n_persistent"], [ops for _, ops, _ in tr["kernels"]],
+                                [t[0] for t in tr["tensors"]], tr["tau"], [t[1] for t in tr["tensors"]],
+                                [k[0] for k in tr["kernels"]])
+
+
+def assert_same_plan(tr, lt, ll, cap, bw, **kw):
+    """Library plan == oracle plan at the planning capacity the library settled on."""
+    try:
+        pl = tio.tio_build_plan(lt, ll, cap, bw, **kw).export()
+    except tio.TioError as e:
+        assert e.code == -3, e
+        with pytest.raises(ValueError):
+            op.build_plan(tr, op.analyze_lifetimes(tr), cap, bw, duplex=kw.get("duplex", True),
+                          min_bytes=kw.get("min_bytes", 0))
+        return None
+    life = op.analyze_lifetimes(tr)
+    ref = op.build_plan(tr, life, pl["planning_cap"], bw, duplex=kw.get("duplex", True), min_bytes=kw.get("min_bytes", 0))
+    assert pl["entries"] == ref["entries"]
+    assert pl["Mp"] == ref["Mp"]
+    assert (pl["n_greedy"], pl["n_forced"]) == (ref["n_greedy"], ref["n_forced"])
+    st = orp.check_plan(tr, life, ref, pl["planning_cap"])
+    assert st["bytes_per_direction"] == pl["bytes_per_direction"]
+    arena = kw.get("arena_bytes") or cap
+    assert pl["arena_needed"] <= arena
+    orp.check_layout(tr, life, ref, pl["allocs"], arena)
+    return pl
+
+
+@pytest.mark.parametrize("name", list(CONFIGS))
+def test_trace_and_lifetimes_bit_exact(name):
+    cfg = CONFIGS[name]
+    tr = ot.build_trace(cfg)
+    lt = tio.tio_trace_build(cfg)
+    v = lt.export()
+    assert (v["n_kernels"], v["n_tensors"], v["n_persistent"]) == (len(tr["kernels"]), len(tr["tensors"]), tr["n_persistent"])
+    assert v["op"].tolist() == [k[0] for k in tr["kernels"]]
+    assert v["flops"].tolist() == [k[2] for k in tr["kernels"]]
+    assert v["tau"].tolist() == tr["tau"]
+    assert v["tensor_bytes"].tolist() == [t[0] for t in tr["tensors"]]
+    assert v["tensor_kind"].tolist() == [t[1] for t in tr["tensors"]]
+    off = [0]
+    flat = []
+    for _, ops, _ in tr["kernels"]:
+        flat += ops
+        off.append(len(flat))
+    assert v["operand_off"].tolist() == off
+    assert v["operand_tensor"].tolist() == [t for t, _ in flat]
+    assert v["operand_flags"].tolist() == [f for _, f in flat]
+    life = op.analyze_lifetimes(tr)
+    lv = tio.tio_analyze_lifetimes(lt).export()
+    assert lv["M"].tolist() == life["M"]
+    got = sorted(zip(lv["tensor"].tolist(), lv["bytes"].tolist(), lv["start"].tolist(), lv["end"].tolist()))
+    assert got == sorted(life["periods"])
+    # parameter list
+    from oracle.model import param_specs
+    assert [(n, int(np.prod(s))) for n, s, _ in param_specs(cfg)] == [(n, r * c) for n, r, c in tio.tio_param_list(cfg)]
+
+
+@pytest.mark.parametrize("name", ["plan_example_a.txt", "plan_example_c.txt"])
+def test_golden_examples_through_the_c_abi(name):
+    tr, cap, bw, entries, Mp, _ = load_golden(name)
+    lt = lib_trace_from_oracle(tr)
+    ll = tio.tio_analyze_lifetimes(lt)
+    pl = tio.tio_build_plan(lt, ll, cap, bw, arena_bytes=1 << 20).export()
+    assert pl["planning_cap"] == cap and pl["entries"] == entries and pl["Mp"] == Mp
+
+
+def test_golden_infeasible_through_the_c_abi():
+    tr, cap, bw, *_ = load_golden("plan_example_b.txt")
+    lt = lib_trace_from_oracle(tr)
+    with pytest.raises(tio.TioError) as e:
+        tio.tio_build_plan(lt, tio.tio_analyze_lifetimes(lt), cap, bw)
+    assert e.value.code == -3
+
+
+@pytest.mark.parametrize("name,frac,bw,min_bytes", [
+    ("tiny_gpt_fp32", 0.5, 25 * 10**9, 0), ("tiny_gpt_fp32", 0.5, 10**8, 0), ("tiny_gpt_fp32", 0.3, 0, 0),
+    ("tiny_gpt_fp32", 0.7, 10**12, 65536), ("tiny_llama_fp32", 0.5, 25 * 10**9, 0),
+    ("tiny_llama_fp32", 0.4, 10**9, 32768), ("tiny_llama_fp32", 0.9, 10**10, 0)])
+def test_model_plans_bit_exact(name, frac, bw, min_bytes):
+    cfg = CONFIGS[name]
+    tr = ot.build_trace(cfg)
+    lt = tio.tio_trace_build(cfg)
+    ll = tio.tio_analyze_lifetimes(lt)
+    cap = int(max(op.analyze_lifetimes(tr)["M"]) * frac)
+    for duplex in (True, False):
+        pl = assert_same_plan(tr, lt, ll, cap, bw, min_bytes=min_bytes, duplex=duplex)
+        assert pl is not None
+        tio.tio_plan_validate(lt, ll, tio.tio_build_plan(lt, ll, cap, bw, min_bytes=min_bytes, duplex=duplex))
+
+
+def test_random_synthetic_traces_bit_exact():
+    rng = np.random.default_rng(9)
+    n = 0
+    for trial in range(80):
+        tr = random_trace(rng, N=int(rng.integers(5, 40)), n_pers=int(rng.integers(1, 6)),
+                          n_trans=int(rng.integers(3, 30)))
+        # the library rounds nothing itself, but addresses are 256-aligned: use 256-multiples
+        tr["tensors"] = [(s * 32, k, nme) for s, k, nme in tr["tensors"]]
+        lt = lib_trace_from_oracle(tr)
+        ll = tio.tio_analyze_lifetimes(lt)
+        life = op.analyze_lifetimes(tr)
+        cap = int(max(life["M"]) * rng.uniform(0.3, 1.0)) // 256 * 256
+        bw = int(10 ** rng.uniform(9, 12.5))
+        pl = assert_same_plan(tr, lt, ll, cap, bw, duplex=bool(trial % 2), arena_bytes=4 * max(life["M"]))
+        n += pl is not None
+    assert n > 30
+
+
+def test_uncapped_plan_is_empty_and_layout_valid():
+    cfg = CONFIGS["tiny_gpt_fp32"]
+    tr = ot.build_trace(cfg)
+    life = op.analyze_lifetimes(tr)
+    lt = tio.tio_trace_build(cfg)
+    ll = tio.tio_analyze_lifetimes(lt)
+    pl = tio.tio_build_plan(lt, ll, 2**62, 0).export()
+    assert pl["entries"] == [] and pl["Mp"] == life["M"]
+    assert max(life["M"]) <= pl["arena_needed"] <= int(1.3 * max(life["M"]))
+    orp.check_layout(tr, life, dict(entries=[]), pl["allocs"], pl["arena_needed"])
+
+
+def test_stale_and_invalid_arguments_are_reported():
+    lt = tio.tio_trace_build(CONFIGS["tiny_gpt_fp32"])
+    lt2 = tio.tio_trace_build(CONFIGS["tiny_llama_fp32"])
+    with pytest.raises(tio.TioError) as e:
+        tio.tio_build_plan(lt, tio.tio_analyze_lifetimes(lt2), 10**6, 10**9)
+    assert e.value.code == -5
+    with pytest.raises(tio.TioError):
+        tio.tio_trace_build(dict(CONFIGS["tiny_gpt_fp32"], d=130))
+    with pytest.raises(tio.TioError):
+        lt.set_tau([1, 2, 3])
+
+
+@pytest.mark.slow
+def test_gpt2_small_plan_bit_exact_at_full_size():
+    cfg = CONFIGS["gpt2_small_bf16"]
+    tr = ot.build_trace(cfg)
+    lt = tio.tio_trace_build(cfg)
+    ll = tio.tio_analyze_lifetimes(lt)
+    cap = int(max(op.analyze_lifetimes(tr)["M"]) * cfg["cap_frac"])
+    pl = assert_same_plan(tr, lt, ll, cap, 25 * 10**9, min_bytes=1 << 20)
+    assert pl["bytes_per_direction"] >= max(op.analyze_lifetimes(tr)["M"]) - cap
