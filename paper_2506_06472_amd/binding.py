@@ -88,6 +88,9 @@ def lib():
     if _lib is None:
         if not os.path.exists(LIB_PATH):
             raise ImportError(f"{LIB_PATH} is missing: run `python -c 'import __graft_entry__ as g; g.build()'`")
+        # torch owns the arena, the pinned pool and the streams: its HIP runtime must be the one in
+        # the process before the library (which needs libamdhip64 too) is mapped
+        import torch  # noqa: F401
         _lib = C.CDLL(LIB_PATH)
         _lib.tio_last_error.restype = C.c_char_p
         _lib.tio_version.restype = C.c_char_p
@@ -243,3 +246,97 @@ def tio_build_plan(trace: Trace, life: Lifetimes, mem_cap_bytes: int, slow_tier_
 
 def tio_plan_validate(trace: Trace, life: Lifetimes, plan: Plan):
     _check(lib().tio_plan_validate(trace.h, life.h, plan.h))
+
+
+# ------------------------------------------------------------------ runtime (needs a GPU)
+class Context:
+    """Owns the arena (GPU), the slow-tier pool (pinned host) and three streams via torch,
+    and a tio_ctx handle created on them."""
+
+    def __init__(self, cfg: dict, arena_bytes: int, host_bytes: int, slow_tier_bw: int = 0, single_copy_stream=False):
+        import torch
+        if not torch.cuda.is_available():
+            raise RuntimeError("a GPU is required for the runtime part of the library")
+        self.torch = torch
+        self.cfg = dict(cfg)
+        self.params = tio_param_list(cfg)
+        self.index = {n: i for i, (n, _, _) in enumerate(self.params)}
+        arena_bytes = (int(arena_bytes) + 4096 + 255) // 256 * 256     # the library keeps the last 4 KiB for itself
+        self.arena = torch.empty(arena_bytes, dtype=torch.uint8, device="cuda:0")
+        self.host = torch.empty(int(host_bytes), dtype=torch.uint8, pin_memory=True)
+        self.s_compute = torch.cuda.Stream(device="cuda:0")
+        self.s_d2h = torch.cuda.Stream(device="cuda:0")
+        self.s_h2d = self.s_d2h if single_copy_stream else torch.cuda.Stream(device="cuda:0")
+        rt = RuntimeCfg(self.arena.data_ptr(), arena_bytes, self.host.data_ptr(), int(host_bytes),
+                        self.s_compute.cuda_stream, self.s_d2h.cuda_stream, self.s_h2d.cuda_stream,
+                        int(slow_tier_bw), 0, 0)
+        mc = model_cfg(cfg)
+        self.h = C.c_void_p()
+        torch.cuda.synchronize()
+        _check(lib().tio_ctx_create(C.byref(mc), C.byref(rt), C.byref(self.h)))
+
+    def close(self):
+        if getattr(self, "h", None):
+            lib().tio_ctx_destroy(self.h)
+            self.h = None
+            self.arena = self.host = None
+
+    def __del__(self):
+        self.close()
+
+    def tio_params_load(self, params: dict):
+        for name, arr in params.items():
+            a = np.ascontiguousarray(arr, dtype=np.float32).reshape(-1)
+            _check(lib().tio_params_load(self.h, self.index[name], a.ctypes.data_as(C.POINTER(C.c_float)),
+                                         C.c_int64(a.size)))
+
+    def tio_params_read(self, name: str, which: int = 0):
+        _, r, c = self.params[self.index[name]]
+        out = np.empty(r * c, dtype=np.float32)
+        _check(lib().tio_params_read(self.h, self.index[name], which, out.ctypes.data_as(C.POINTER(C.c_float)),
+                                     C.c_int64(out.size)))
+        return out.reshape((r, c) if r > 1 else (c,))
+
+    def tio_grads_read(self, name: str):
+        _, r, c = self.params[self.index[name]]
+        out = np.empty(r * c, dtype=np.float32)
+        _check(lib().tio_grads_read(self.h, self.index[name], out.ctypes.data_as(C.POINTER(C.c_float)),
+                                    C.c_int64(out.size)))
+        return out.reshape((r, c) if r > 1 else (c,))
+
+    def tio_set_slow_tier_bw(self, bw: int):
+        _check(lib().tio_set_slow_tier_bw(self.h, C.c_uint64(int(bw))))
+
+    def tio_train_step(self, tokens, labels, plan: Plan | None = None, capture_grads=False):
+        t = np.ascontiguousarray(tokens, dtype=np.int32)
+        l = np.ascontiguousarray(labels, dtype=np.int32)
+        st = StepStats()
+        _check(lib().tio_train_step(self.h, t.ctypes.data_as(C.POINTER(C.c_int32)), l.ctypes.data_as(C.POINTER(C.c_int32)),
+                                    plan.h if plan is not None else None, 1 if capture_grads else 0, C.byref(st)))
+        return {f: getattr(st, f) for f, _ in StepStats._fields_}
+
+    def tio_profile_iteration(self, tokens, labels, mode=PROFILE_MEASURED) -> Trace:
+        t = np.ascontiguousarray(tokens, dtype=np.int32)
+        l = np.ascontiguousarray(labels, dtype=np.int32)
+        h = C.c_void_p()
+        _check(lib().tio_profile_iteration(self.h, t.ctypes.data_as(C.POINTER(C.c_int32)),
+                                           l.ctypes.data_as(C.POINTER(C.c_int32)), mode, C.byref(h)))
+        return Trace(h)
+
+    def tio_op_bench(self, kernel_index: int, reps: int = 10) -> float:
+        out = C.c_double()
+        _check(lib().tio_op_bench(self.h, kernel_index, reps, C.byref(out)))
+        return out.value
+
+
+def tio_ctx_create(cfg, arena_bytes, host_bytes, slow_tier_bw=0, single_copy_stream=False) -> Context:
+    return Context(cfg, arena_bytes, host_bytes, slow_tier_bw, single_copy_stream)
+
+
+def tio_op_gemm(stream_handle, dtype, a_kmajor, b_kmajor, M, N, K, A_ptr, lda, B_ptr, ldb, bias_ptr, resid_ptr, ldr,
+                C_ptr, ldc):
+    """Raw pointers (ints) of device buffers; see include/teraio.h."""
+    vp = lambda p: C.c_void_p(p) if p else None
+    _check(lib().tio_op_gemm(vp(stream_handle), PREC[dtype], int(a_kmajor), int(b_kmajor), C.c_int64(M), C.c_int64(N),
+                             C.c_int64(K), vp(A_ptr), C.c_int64(lda), vp(B_ptr), C.c_int64(ldb), vp(bias_ptr),
+                             vp(resid_ptr), C.c_int64(ldr), vp(C_ptr), C.c_int64(ldc)))

@@ -58,6 +58,7 @@ struct Plan {
     uint64_t cap = 0, planning_cap = 0, arena_needed = 0, host_needed = 0, bytes_moved = 0, bw = 0;
     int32_t n_greedy = 0, n_forced = 0;
     uint64_t structure_hash = 0;
+    uint64_t serial = 0;               // unique per built plan; the runtime uses it to notice a plan change
     std::vector<uint64_t> Mp;
     std::vector<Pair> pairs;                     // selection order (= pair id)
     std::vector<tio_plan_entry> entries;         // issue order

@@ -1,5 +1,6 @@
 // C ABI: handles, views and error reporting for the pure-CPU half (trace, lifetimes, plan).
 // The runtime entry points (context, training step) live in runtime.hip.
+#include <atomic>
 #include <cstring>
 #include <new>
 #include <stdexcept>
@@ -146,7 +147,10 @@ int tio_build_plan(const tio_trace *trace, const tio_lifetimes *life, uint64_t c
     TIO_GUARD_BEGIN
     tio_plan_opts o{1, 24, 0, 0};
     if (opts) o = *opts;
-    *out = new tio_plan{build_plan(trace->t, life->l, cap, bw, o)};
+    static std::atomic<uint64_t> serial{1};
+    tio_plan *h = new tio_plan{build_plan(trace->t, life->l, cap, bw, o)};
+    h->p.serial = serial.fetch_add(1);
+    *out = h;
     return TIO_OK;
     TIO_GUARD_END
 }

@@ -1,0 +1,599 @@
+// Memory-bound kernels of the training step: embedding, LayerNorm / RMSNorm, GELU, SwiGLU, RoPE,
+// fused softmax cross-entropy, bias gradient, AdamW, plus small utilities.  All are bound by HBM:
+// 16-byte coalesced accesses, fp32 arithmetic, wavefront (64-lane) reductions, fixed summation
+// orders (no floating-point atomics) so that results do not depend on timing or addresses.
+#include <stdexcept>
+
+#include "../../include/teraio.h"
+#include "device_common.h"
+#include "kernels.h"
+
+namespace tio {
+namespace k {
+
+namespace {
+
+constexpr int TPB = 256;
+inline unsigned blocks_for(int64_t n, int per) { return (unsigned)((n + per - 1) / per); }
+
+// ---------------------------------------------------------------- embedding
+template <typename T>
+__global__ void __launch_bounds__(TPB) embed_fwd_k(const int32_t *__restrict__ tok, const T *__restrict__ wte,
+                                                   const T *__restrict__ wpe, T *__restrict__ x, int64_t S,
+                                                   int64_t d, int64_t Tn) {
+    constexpr int V = Vec16<T>::N;
+    const int64_t cpr = d / V;
+    const int64_t idx = (int64_t)blockIdx.x * TPB + threadIdx.x;
+    if (idx >= S * cpr) return;
+    const int64_t row = idx / cpr, c = idx % cpr;
+    Vec16<T> a;
+    a.load(wte + (int64_t)tok[row] * d + c * V);
+    if (wpe) {
+        Vec16<T> p;
+        p.load(wpe + (row % Tn) * d + c * V);
+        float fa[V], fp[V];
+        a.get(fa); p.get(fp);
+#pragma unroll
+        for (int i = 0; i < V; ++i) fa[i] += fp[i];
+        a.set(fa);
+    }
+    a.store(x + row * d + c * V);
+}
+
+// One launch: workgroups [0,S) accumulate the rows of repeated tokens in position order (the
+// workgroup of the first occurrence does the work), workgroups [S,S+V) zero the rows of unused ids.
+template <typename T>
+__global__ void __launch_bounds__(TPB) embed_bwd_k(const T *__restrict__ dx, const int32_t *__restrict__ tok,
+                                                   T *__restrict__ dw, int64_t S, int64_t d, int64_t Vn) {
+    constexpr int V = Vec16<T>::N;
+    const int64_t cpr = d / V;
+    const int64_t blk = blockIdx.x;
+    if (blk >= S) {
+        const int32_t id = (int32_t)(blk - S);
+        int found = 0;
+        for (int64_t i = threadIdx.x; i < S; i += TPB) found |= (tok[i] == id);
+        if (__syncthreads_or(found)) return;
+        Vec16<T> z;
+        float f[V];
+#pragma unroll
+        for (int i = 0; i < V; ++i) f[i] = 0.f;
+        z.set(f);
+        for (int64_t c = threadIdx.x; c < cpr; c += TPB) z.store(dw + (int64_t)id * d + c * V);
+        return;
+    }
+    const int32_t id = tok[blk];
+    int earlier = 0;
+    for (int64_t i = threadIdx.x; i < blk; i += TPB) earlier |= (tok[i] == id);
+    if (__syncthreads_or(earlier)) return;
+    for (int64_t c = threadIdx.x; c < cpr; c += TPB) {
+        float acc[V];
+#pragma unroll
+        for (int i = 0; i < V; ++i) acc[i] = 0.f;
+        for (int64_t s = blk; s < S; ++s) {
+            if (tok[s] != id) continue;
+            Vec16<T> g;
+            g.load(dx + s * d + c * V);
+            float f[V];
+            g.get(f);
+#pragma unroll
+            for (int i = 0; i < V; ++i) acc[i] += f[i];
+        }
+        Vec16<T> o;
+        o.set(acc);
+        o.store(dw + (int64_t)id * d + c * V);
+    }
+}
+
+template <typename T>
+__global__ void __launch_bounds__(TPB) posemb_bwd_k(const T *__restrict__ dx, T *__restrict__ dw, int64_t B,
+                                                    int64_t Tn, int64_t d) {
+    constexpr int V = Vec16<T>::N;
+    const int64_t cpr = d / V;
+    const int64_t idx = (int64_t)blockIdx.x * TPB + threadIdx.x;
+    if (idx >= Tn * cpr) return;
+    const int64_t t = idx / cpr, c = idx % cpr;
+    float acc[V];
+#pragma unroll
+    for (int i = 0; i < V; ++i) acc[i] = 0.f;
+    for (int64_t b = 0; b < B; ++b) {
+        Vec16<T> g;
+        g.load(dx + (b * Tn + t) * d + c * V);
+        float f[V];
+        g.get(f);
+#pragma unroll
+        for (int i = 0; i < V; ++i) acc[i] += f[i];
+    }
+    Vec16<T> o;
+    o.set(acc);
+    o.store(dw + t * d + c * V);
+}
+
+// ---------------------------------------------------------------- norms
+// one wavefront per row; the row is re-read from cache for the second and third pass
+template <typename T, bool RMS>
+__global__ void __launch_bounds__(TPB) norm_fwd_k(const T *__restrict__ x, const T *__restrict__ g,
+                                                  const T *__restrict__ b, T *__restrict__ y,
+                                                  float *__restrict__ stats, int64_t S, int64_t d, float eps) {
+    constexpr int V = Vec16<T>::N;
+    const int lane = threadIdx.x & 63;
+    const int64_t row = (int64_t)blockIdx.x * (TPB / 64) + (threadIdx.x >> 6);
+    if (row >= S) return;
+    const int64_t cpr = d / V;
+    const T *xr = x + row * d;
+    float mean = 0.f;
+    if (!RMS) {
+        float s = 0.f;
+        for (int64_t c = lane; c < cpr; c += 64) {
+            Vec16<T> v; v.load(xr + c * V);
+            float f[V]; v.get(f);
+#pragma unroll
+            for (int i = 0; i < V; ++i) s += f[i];
+        }
+        mean = wave_sum(s) / (float)d;
+    }
+    float q = 0.f;
+    for (int64_t c = lane; c < cpr; c += 64) {
+        Vec16<T> v; v.load(xr + c * V);
+        float f[V]; v.get(f);
+#pragma unroll
+        for (int i = 0; i < V; ++i) { const float t = f[i] - mean; q += t * t; }
+    }
+    const float rstd = 1.0f / sqrtf(wave_sum(q) / (float)d + eps);
+    if (lane == 0) {
+        if (RMS) stats[row] = rstd;
+        else { stats[2 * row] = mean; stats[2 * row + 1] = rstd; }
+    }
+    for (int64_t c = lane; c < cpr; c += 64) {
+        Vec16<T> v, gv; v.load(xr + c * V); gv.load(g + c * V);
+        float f[V], gf[V], bf[V];
+        v.get(f); gv.get(gf);
+        if (!RMS) { Vec16<T> bv; bv.load(b + c * V); bv.get(bf); }
+#pragma unroll
+        for (int i = 0; i < V; ++i) {
+            const float xh = (f[i] - mean) * rstd;
+            f[i] = RMS ? xh * gf[i] : xh * gf[i] + bf[i];
+        }
+        Vec16<T> o; o.set(f); o.store(y + row * d + c * V);
+    }
+}
+
+// one workgroup per kNormBwdRows rows, rows in order; column sums for the gain / bias gradients are
+// kept in LDS, each column owned by one thread, and written out as one partial row per workgroup
+template <typename T, bool RMS>
+__global__ void __launch_bounds__(TPB) norm_bwd_k(const T *__restrict__ dy, const T *__restrict__ x,
+                                                  const float *__restrict__ stats, const T *__restrict__ g,
+                                                  const T *__restrict__ dres, T *__restrict__ dx,
+                                                  float *__restrict__ part, int64_t S, int64_t d, int rows_per_blk) {
+    constexpr int V = Vec16<T>::N;
+    constexpr int NP = RMS ? 1 : 2;
+    extern __shared__ float lds[];          // NP*d accumulators, then 16 floats for reductions
+    float *acc = lds;
+    float *red = lds + NP * d;
+    const int64_t cpr = d / V;
+    for (int64_t i = threadIdx.x; i < NP * d; i += TPB) acc[i] = 0.f;
+    const int64_t r0 = (int64_t)blockIdx.x * rows_per_blk;
+    const int64_t r1 = r0 + rows_per_blk < S ? r0 + rows_per_blk : S;
+    const int w = threadIdx.x >> 6, l = threadIdx.x & 63;
+    for (int64_t row = r0; row < r1; ++row) {
+        const float mean = RMS ? 0.f : stats[2 * row];
+        const float rstd = RMS ? stats[row] : stats[2 * row + 1];
+        float s1 = 0.f, s2 = 0.f;
+        for (int64_t c = threadIdx.x; c < cpr; c += TPB) {
+            Vec16<T> a, b, gv; a.load(dy + row * d + c * V); b.load(x + row * d + c * V); gv.load(g + c * V);
+            float fa[V], fb[V], fg[V]; a.get(fa); b.get(fb); gv.get(fg);
+#pragma unroll
+            for (int i = 0; i < V; ++i) {
+                const float xh = (fb[i] - mean) * rstd, dxh = fa[i] * fg[i];
+                s1 += dxh; s2 += dxh * xh;
+            }
+        }
+        s1 = wave_sum(s1); s2 = wave_sum(s2);
+        __syncthreads();
+        if (l == 0) { red[w] = s1; red[4 + w] = s2; }
+        __syncthreads();
+        s1 = (red[0] + red[1] + red[2] + red[3]) / (float)d;
+        s2 = (red[4] + red[5] + red[6] + red[7]) / (float)d;
+        if (RMS) s1 = 0.f;
+        for (int64_t c = threadIdx.x; c < cpr; c += TPB) {
+            Vec16<T> a, b, gv; a.load(dy + row * d + c * V); b.load(x + row * d + c * V); gv.load(g + c * V);
+            float fa[V], fb[V], fg[V], fr[V], out[V]; a.get(fa); b.get(fb); gv.get(fg);
+            if (dres) { Vec16<T> r; r.load(dres + row * d + c * V); r.get(fr); }
+#pragma unroll
+            for (int i = 0; i < V; ++i) {
+                const float xh = (fb[i] - mean) * rstd, dxh = fa[i] * fg[i];
+                out[i] = rstd * (dxh - s1 - xh * s2) + (dres ? fr[i] : 0.f);
+                acc[c * V + i] += fa[i] * xh;
+                if (!RMS) acc[d + c * V + i] += fa[i];
+            }
+            Vec16<T> o; o.set(out); o.store(dx + row * d + c * V);
+        }
+    }
+    __syncthreads();
+    float *p = part + (int64_t)blockIdx.x * NP * d;
+    for (int64_t i = threadIdx.x; i < NP * d; i += TPB) p[i] = acc[i];
+}
+
+template <typename T, bool RMS>
+__global__ void __launch_bounds__(TPB) norm_bwd_params_k(const float *__restrict__ part, T *__restrict__ dg,
+                                                         T *__restrict__ db, int64_t nb, int64_t d) {
+    constexpr int NP = RMS ? 1 : 2;
+    const int64_t col = (int64_t)blockIdx.x * TPB + threadIdx.x;
+    if (col >= d) return;
+    float sg = 0.f, sb = 0.f;
+    for (int64_t b = 0; b < nb; ++b) {
+        sg += part[b * NP * d + col];
+        if (!RMS) sb += part[b * NP * d + d + col];
+    }
+    dg[col] = from_f32<T>(sg);
+    if (!RMS) db[col] = from_f32<T>(sb);
+}
+
+// ---------------------------------------------------------------- activations
+__device__ __forceinline__ float gelu_f(float x) {
+    const float u = 0.7978845608028654f * (x + 0.044715f * x * x * x);
+    return 0.5f * x * (1.0f + tanhf(u));
+}
+__device__ __forceinline__ float gelu_grad_f(float x) {
+    const float u = 0.7978845608028654f * (x + 0.044715f * x * x * x);
+    const float t = tanhf(u);
+    return 0.5f * (1.0f + t) + 0.5f * x * (1.0f - t * t) * 0.7978845608028654f * (1.0f + 3.0f * 0.044715f * x * x);
+}
+
+template <typename T>
+__global__ void __launch_bounds__(TPB) gelu_fwd_k(const T *__restrict__ u, T *__restrict__ y, int64_t nvec) {
+    constexpr int V = Vec16<T>::N;
+    const int64_t i = (int64_t)blockIdx.x * TPB + threadIdx.x;
+    if (i >= nvec) return;
+    Vec16<T> a; a.load(u + i * V);
+    float f[V]; a.get(f);
+#pragma unroll
+    for (int j = 0; j < V; ++j) f[j] = gelu_f(f[j]);
+    a.set(f); a.store(y + i * V);
+}
+
+template <typename T>
+__global__ void __launch_bounds__(TPB) gelu_bwd_k(T *__restrict__ dact, const T *__restrict__ u, int64_t nvec) {
+    constexpr int V = Vec16<T>::N;
+    const int64_t i = (int64_t)blockIdx.x * TPB + threadIdx.x;
+    if (i >= nvec) return;
+    Vec16<T> a, b; a.load(dact + i * V); b.load(u + i * V);
+    float fa[V], fb[V]; a.get(fa); b.get(fb);
+#pragma unroll
+    for (int j = 0; j < V; ++j) fa[j] *= gelu_grad_f(fb[j]);
+    a.set(fa); a.store(dact + i * V);
+}
+
+template <typename T>
+__global__ void __launch_bounds__(TPB) swiglu_fwd_k(const T *__restrict__ gu, T *__restrict__ y, int64_t S, int64_t f) {
+    constexpr int V = Vec16<T>::N;
+    const int64_t cpr = f / V;
+    const int64_t idx = (int64_t)blockIdx.x * TPB + threadIdx.x;
+    if (idx >= S * cpr) return;
+    const int64_t row = idx / cpr, c = idx % cpr;
+    Vec16<T> a, b; a.load(gu + row * 2 * f + c * V); b.load(gu + row * 2 * f + f + c * V);
+    float fg[V], fu[V]; a.get(fg); b.get(fu);
+#pragma unroll
+    for (int j = 0; j < V; ++j) fg[j] = fg[j] / (1.0f + expf(-fg[j])) * fu[j];
+    a.set(fg); a.store(y + row * f + c * V);
+}
+
+template <typename T>
+__global__ void __launch_bounds__(TPB) swiglu_bwd_k(const T *__restrict__ dy, const T *__restrict__ gu,
+                                                    T *__restrict__ dgu, int64_t S, int64_t f) {
+    constexpr int V = Vec16<T>::N;
+    const int64_t cpr = f / V;
+    const int64_t idx = (int64_t)blockIdx.x * TPB + threadIdx.x;
+    if (idx >= S * cpr) return;
+    const int64_t row = idx / cpr, c = idx % cpr;
+    Vec16<T> a, b, e; a.load(gu + row * 2 * f + c * V); b.load(gu + row * 2 * f + f + c * V); e.load(dy + row * f + c * V);
+    float fg[V], fu[V], fd[V]; a.get(fg); b.get(fu); e.get(fd);
+#pragma unroll
+    for (int j = 0; j < V; ++j) {
+        const float s = 1.0f / (1.0f + expf(-fg[j]));
+        const float dg = fd[j] * fu[j] * (s + fg[j] * s * (1.0f - s));
+        fu[j] = fd[j] * fg[j] * s;
+        fg[j] = dg;
+    }
+    a.set(fg); a.store(dgu + row * 2 * f + c * V);
+    b.set(fu); b.store(dgu + row * 2 * f + f + c * V);
+}
+
+// rotation of adjacent pairs of q and k, in place; angle = pos * theta^(-2i/dh), in double
+template <typename T>
+__global__ void __launch_bounds__(TPB) rope_k(T *__restrict__ qkv, int64_t S, int64_t Tn, int64_t d, int64_t dh,
+                                              double log_theta, float sign) {
+    constexpr int V = Vec16<T>::N;
+    const int64_t cpr = 2 * d / V;                         // q and k columns only
+    const int64_t idx = (int64_t)blockIdx.x * TPB + threadIdx.x;
+    if (idx >= S * cpr) return;
+    const int64_t row = idx / cpr, c = idx % cpr;
+    const int64_t col = c * V;                             // column in [0, 2d)
+    T *p = qkv + row * 3 * d + col;
+    Vec16<T> a; a.load(p);
+    float f[V]; a.get(f);
+    const double pos = (double)(row % Tn);
+#pragma unroll
+    for (int j = 0; j < V; j += 2) {
+        const int64_t i = ((col + j) % dh) / 2;
+        const double ang = pos * exp(-2.0 * (double)i / (double)dh * log_theta);
+        double sn, cs;
+        sincos(ang, &sn, &cs);
+        const float cf = (float)cs, sf = sign * (float)sn;
+        const float x0 = f[j], x1 = f[j + 1];
+        f[j] = x0 * cf - x1 * sf;
+        f[j + 1] = x0 * sf + x1 * cf;
+    }
+    a.set(f); a.store(p);
+}
+
+// ---------------------------------------------------------------- cross entropy
+// one workgroup per row: online max / sum-of-exponentials, then dlogits written in place
+template <typename T>
+__global__ void __launch_bounds__(TPB) ce_k(T *__restrict__ logits, const int32_t *__restrict__ labels,
+                                            float *__restrict__ losses, int64_t S, int64_t Vn, int64_t ld) {
+    constexpr int V = Vec16<T>::N;
+    __shared__ float red[8];
+    const int64_t row = blockIdx.x;
+    T *xr = logits + row * ld;
+    const int64_t nchunk = ld / V;
+    float m = -INFINITY, s = 0.f;
+    for (int64_t c = threadIdx.x; c < nchunk; c += TPB) {
+        if (c * V >= Vn) break;
+        Vec16<T> a; a.load(xr + c * V);
+        float f[V]; a.get(f);
+#pragma unroll
+        for (int j = 0; j < V; ++j) {
+            if (c * V + j < Vn) {
+                const float x = f[j];
+                if (x > m) { s = s * expf(m - x) + 1.0f; m = x; }
+                else s += expf(x - m);
+            }
+        }
+    }
+    const float M = block_max<TPB / 64>(m, red);
+    const float tot = block_sum<TPB / 64>(m == -INFINITY ? 0.f : s * expf(m - M), red);
+    const float lse = M + logf(tot);
+    const int32_t lab = labels[row];
+    if (threadIdx.x == 0) losses[row] = lse - to_f32(xr[lab]);
+    __syncthreads();                                       // the label logit is read before it is overwritten
+    const float invS = 1.0f / (float)S;
+    for (int64_t c = threadIdx.x; c < nchunk; c += TPB) {
+        Vec16<T> a; a.load(xr + c * V);
+        float f[V]; a.get(f);
+#pragma unroll
+        for (int j = 0; j < V; ++j) {
+            const int64_t col = c * V + j;
+            f[j] = col < Vn ? (expf(f[j] - lse) - (col == lab ? 1.0f : 0.0f)) * invS : 0.0f;
+        }
+        a.set(f); a.store(xr + c * V);
+    }
+}
+
+__global__ void __launch_bounds__(TPB) loss_reduce_k(const float *__restrict__ losses, float *__restrict__ loss, int64_t S) {
+    __shared__ float red[8];
+    float s = 0.f;
+    for (int64_t i = threadIdx.x; i < S; i += TPB) s += losses[i];
+    const float t = block_sum<TPB / 64>(s, red);
+    if (threadIdx.x == 0) loss[0] = t / (float)S;
+}
+
+// ---------------------------------------------------------------- bias gradient: column sums
+// workgroup = 32 columns x 8 row groups; each thread adds its rows in order, groups are combined in order
+template <typename T>
+__global__ void __launch_bounds__(TPB) bias_grad_k(const T *__restrict__ dy, T *__restrict__ db, int64_t S,
+                                                   int64_t n, int64_t ld) {
+    __shared__ float red[8][33];
+    const int c = threadIdx.x & 31, rg = threadIdx.x >> 5;
+    const int64_t col = (int64_t)blockIdx.x * 32 + c;
+    float s = 0.f;
+    if (col < n)
+        for (int64_t r = rg; r < S; r += 8) s += to_f32(dy[r * ld + col]);
+    red[rg][c] = s;
+    __syncthreads();
+    if (rg == 0 && col < n) {
+        float t = 0.f;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) t += red[i][c];
+        db[col] = from_f32<T>(t);
+    }
+}
+
+// ---------------------------------------------------------------- AdamW
+// reads g, theta (fp32 master), m, v; writes theta, m, v and, in bf16 mode, the bf16 compute weight
+template <typename T>
+__global__ void __launch_bounds__(TPB) adamw_k(const T *__restrict__ g, T *__restrict__ w, float *__restrict__ master,
+                                               float *__restrict__ m, float *__restrict__ v, int64_t n, float lr,
+                                               float b1, float b2, float eps, float wd, float inv_bc1, float inv_bc2) {
+    const int64_t i0 = ((int64_t)blockIdx.x * TPB + threadIdx.x) * 4;
+    if (i0 >= n) return;
+    float *theta = master ? master : reinterpret_cast<float *>(w);
+    if (i0 + 4 <= n) {
+        float gg[4];
+        if (sizeof(T) == 4) {
+            const float4 t = *reinterpret_cast<const float4 *>(g + i0);
+            gg[0] = t.x; gg[1] = t.y; gg[2] = t.z; gg[3] = t.w;
+        } else {
+            const uint2 t = *reinterpret_cast<const uint2 *>(g + i0);
+            gg[0] = __uint_as_float(t.x << 16); gg[1] = __uint_as_float(t.x & 0xffff0000u);
+            gg[2] = __uint_as_float(t.y << 16); gg[3] = __uint_as_float(t.y & 0xffff0000u);
+        }
+        float4 th = *reinterpret_cast<float4 *>(theta + i0), mm = *reinterpret_cast<float4 *>(m + i0),
+               vv = *reinterpret_cast<float4 *>(v + i0);
+        float *pt = &th.x, *pm = &mm.x, *pv = &vv.x;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            pm[j] = b1 * pm[j] + (1.0f - b1) * gg[j];
+            pv[j] = b2 * pv[j] + (1.0f - b2) * gg[j] * gg[j];
+            pt[j] = pt[j] - lr * (pm[j] * inv_bc1 / (sqrtf(pv[j] * inv_bc2) + eps) + wd * pt[j]);
+        }
+        *reinterpret_cast<float4 *>(theta + i0) = th;
+        *reinterpret_cast<float4 *>(m + i0) = mm;
+        *reinterpret_cast<float4 *>(v + i0) = vv;
+        if (master) {
+            uint2 o;
+            o.x = f32_to_bf16_bits(pt[0]) | (f32_to_bf16_bits(pt[1]) << 16);
+            o.y = f32_to_bf16_bits(pt[2]) | (f32_to_bf16_bits(pt[3]) << 16);
+            *reinterpret_cast<uint2 *>(w + i0) = o;
+        }
+    } else {
+        for (int64_t i = i0; i < n; ++i) {
+            const float gi = to_f32(g[i]);
+            const float mi = b1 * m[i] + (1.0f - b1) * gi;
+            const float vi = b2 * v[i] + (1.0f - b2) * gi * gi;
+            const float ti = theta[i] - lr * (mi * inv_bc1 / (sqrtf(vi * inv_bc2) + eps) + wd * theta[i]);
+            m[i] = mi; v[i] = vi; theta[i] = ti;
+            if (master) w[i] = from_f32<T>(ti);
+        }
+    }
+}
+
+// ---------------------------------------------------------------- utilities
+__global__ void __launch_bounds__(TPB) fill_u32_k(uint32_t *p, uint32_t value, int64_t n) {
+    const int64_t i = (int64_t)blockIdx.x * TPB + threadIdx.x;
+    if (i < n) p[i] = value;
+}
+
+template <typename T>
+__global__ void __launch_bounds__(TPB) convert_k(const float *__restrict__ src, T *__restrict__ dst, int64_t n) {
+    const int64_t i = (int64_t)blockIdx.x * TPB + threadIdx.x;
+    if (i < n) dst[i] = from_f32<T>(src[i]);
+}
+
+__global__ void pace_begin_k(unsigned long long *slot) {
+    if (threadIdx.x == 0) *slot = wall_clock64();
+}
+// waits until `ticks` of the constant-rate clock have passed since the stamp; the tick count is
+// bounded by the host, so the loop always ends
+__global__ void pace_wait_k(const unsigned long long *slot, unsigned long long ticks) {
+    if (threadIdx.x != 0) return;
+    const unsigned long long t0 = *slot;
+    while (wall_clock64() - t0 < ticks) __builtin_amdgcn_s_sleep(32);
+}
+
+}  // namespace
+
+#define TIO_DISPATCH(dtype, ...)                                  \
+    do {                                                          \
+        if ((dtype) == TIO_PREC_BF16) { using T = bf16_t; __VA_ARGS__; } \
+        else { using T = float; __VA_ARGS__; }                    \
+    } while (0)
+
+void embed_fwd(hipStream_t s, int dtype, const int32_t *tok, const void *wte, const void *wpe, void *x, int64_t S,
+               int64_t d, int64_t Tn) {
+    TIO_DISPATCH(dtype, {
+        const int64_t n = S * (d / Vec16<T>::N);
+        embed_fwd_k<T><<<blocks_for(n, TPB), TPB, 0, s>>>(tok, (const T *)wte, (const T *)wpe, (T *)x, S, d, Tn);
+    });
+}
+
+void embed_bwd(hipStream_t s, int dtype, const void *dx, const int32_t *tok, void *dwte, int64_t S, int64_t d, int64_t V) {
+    TIO_DISPATCH(dtype, { embed_bwd_k<T><<<(unsigned)(S + V), TPB, 0, s>>>((const T *)dx, tok, (T *)dwte, S, d, V); });
+}
+
+void posemb_bwd(hipStream_t s, int dtype, const void *dx, void *dwpe, int64_t B, int64_t Tn, int64_t d) {
+    TIO_DISPATCH(dtype, {
+        const int64_t n = Tn * (d / Vec16<T>::N);
+        posemb_bwd_k<T><<<blocks_for(n, TPB), TPB, 0, s>>>((const T *)dx, (T *)dwpe, B, Tn, d);
+    });
+}
+
+void norm_fwd(hipStream_t s, int dtype, bool rms, const void *x, const void *g, const void *b, void *y, float *stats,
+              int64_t S, int64_t d, float eps) {
+    TIO_DISPATCH(dtype, {
+        const unsigned nb = blocks_for(S, TPB / 64);
+        if (rms) norm_fwd_k<T, true><<<nb, TPB, 0, s>>>((const T *)x, (const T *)g, nullptr, (T *)y, stats, S, d, eps);
+        else norm_fwd_k<T, false><<<nb, TPB, 0, s>>>((const T *)x, (const T *)g, (const T *)b, (T *)y, stats, S, d, eps);
+    });
+}
+
+void norm_bwd(hipStream_t s, int dtype, bool rms, const void *dy, const void *x, const float *stats, const void *g,
+              const void *dres, void *dx, float *part, int64_t S, int64_t d, int64_t nb) {
+    const int rows = (int)((S + nb - 1) / nb);
+    const size_t lds = ((rms ? 1 : 2) * d + 16) * sizeof(float);
+    TIO_DISPATCH(dtype, {
+        if (rms) norm_bwd_k<T, true><<<(unsigned)nb, TPB, lds, s>>>((const T *)dy, (const T *)x, stats, (const T *)g,
+                                                                    (const T *)dres, (T *)dx, part, S, d, rows);
+        else norm_bwd_k<T, false><<<(unsigned)nb, TPB, lds, s>>>((const T *)dy, (const T *)x, stats, (const T *)g,
+                                                                 (const T *)dres, (T *)dx, part, S, d, rows);
+    });
+}
+
+void norm_bwd_params(hipStream_t s, int dtype, bool rms, const float *part, void *dg, void *db, int64_t nb, int64_t d) {
+    TIO_DISPATCH(dtype, {
+        if (rms) norm_bwd_params_k<T, true><<<blocks_for(d, TPB), TPB, 0, s>>>(part, (T *)dg, nullptr, nb, d);
+        else norm_bwd_params_k<T, false><<<blocks_for(d, TPB), TPB, 0, s>>>(part, (T *)dg, (T *)db, nb, d);
+    });
+}
+
+void gelu_fwd(hipStream_t s, int dtype, const void *u, void *y, int64_t n) {
+    TIO_DISPATCH(dtype, {
+        const int64_t nv = n / Vec16<T>::N;
+        gelu_fwd_k<T><<<blocks_for(nv, TPB), TPB, 0, s>>>((const T *)u, (T *)y, nv);
+    });
+}
+
+void gelu_bwd(hipStream_t s, int dtype, void *dact, const void *u, int64_t n) {
+    TIO_DISPATCH(dtype, {
+        const int64_t nv = n / Vec16<T>::N;
+        gelu_bwd_k<T><<<blocks_for(nv, TPB), TPB, 0, s>>>((T *)dact, (const T *)u, nv);
+    });
+}
+
+void swiglu_fwd(hipStream_t s, int dtype, const void *gu, void *y, int64_t S, int64_t f) {
+    TIO_DISPATCH(dtype, {
+        const int64_t n = S * (f / Vec16<T>::N);
+        swiglu_fwd_k<T><<<blocks_for(n, TPB), TPB, 0, s>>>((const T *)gu, (T *)y, S, f);
+    });
+}
+
+void swiglu_bwd(hipStream_t s, int dtype, const void *dact, const void *gu, void *dgu, int64_t S, int64_t f) {
+    TIO_DISPATCH(dtype, {
+        const int64_t n = S * (f / Vec16<T>::N);
+        swiglu_bwd_k<T><<<blocks_for(n, TPB), TPB, 0, s>>>((const T *)dact, (const T *)gu, (T *)dgu, S, f);
+    });
+}
+
+void rope(hipStream_t s, int dtype, void *qkv, int64_t B, int64_t Tn, int64_t H, int64_t dh, float theta, bool inverse) {
+    const int64_t S = B * Tn, d = H * dh;
+    TIO_DISPATCH(dtype, {
+        const int64_t n = S * (2 * d / Vec16<T>::N);
+        rope_k<T><<<blocks_for(n, TPB), TPB, 0, s>>>((T *)qkv, S, Tn, d, dh, log((double)theta), inverse ? -1.0f : 1.0f);
+    });
+}
+
+void ce_fwd_bwd(hipStream_t s, int dtype, void *logits, const int32_t *labels, float *losses, int64_t S, int64_t V,
+                int64_t ld) {
+    TIO_DISPATCH(dtype, { ce_k<T><<<(unsigned)S, TPB, 0, s>>>((T *)logits, labels, losses, S, V, ld); });
+}
+
+void loss_reduce(hipStream_t s, const float *losses, float *loss, int64_t S) {
+    loss_reduce_k<<<1, TPB, 0, s>>>(losses, loss, S);
+}
+
+void bias_grad(hipStream_t s, int dtype, const void *dy, void *db, int64_t S, int64_t n, int64_t ld) {
+    TIO_DISPATCH(dtype, { bias_grad_k<T><<<blocks_for(n, 32), TPB, 0, s>>>((const T *)dy, (T *)db, S, n, ld); });
+}
+
+void adamw(hipStream_t s, int dtype, const void *g, void *w, float *master, float *m, float *v, int64_t n, float lr,
+           float beta1, float beta2, float eps, float wd, float bc1, float bc2) {
+    TIO_DISPATCH(dtype, {
+        adamw_k<T><<<blocks_for(n, TPB * 4), TPB, 0, s>>>((const T *)g, (T *)w, master, m, v, n, lr, beta1, beta2, eps, wd,
+                                                          1.0f / bc1, 1.0f / bc2);
+    });
+}
+
+void fill_u32(hipStream_t s, void *p, uint32_t value, int64_t n_words) {
+    if (n_words > 0) fill_u32_k<<<blocks_for(n_words, TPB), TPB, 0, s>>>((uint32_t *)p, value, n_words);
+}
+
+void convert_from_f32(hipStream_t s, int dtype, const float *src, void *dst, int64_t n) {
+    TIO_DISPATCH(dtype, { convert_k<T><<<blocks_for(n, TPB), TPB, 0, s>>>(src, (T *)dst, n); });
+}
+
+void pace_begin(hipStream_t s, unsigned long long *slot) { pace_begin_k<<<1, 64, 0, s>>>(slot); }
+void pace_wait(hipStream_t s, const unsigned long long *slot, unsigned long long ticks) {
+    pace_wait_k<<<1, 64, 0, s>>>(slot, ticks);
+}
+
+}  // namespace k
+}  // namespace tio

@@ -1,0 +1,317 @@
+// Dense contractions of the training step: C[M,N] = A . B^T (+bias) (+residual).
+//
+// bf16: MFMA kernel for gfx950 (v_mfma_f32_32x32x16_bf16, fp32 accumulate).  A workgroup owns a
+// BM x BN tile of C; both operand tiles are staged through LDS in [row][k] order with a 16-byte row
+// pad, so that every MFMA operand is one 16-byte LDS read.  Operands that are stored with the
+// contraction index as the slow dimension ("k-major": the weight in dX = dY.W, both operands in
+// dW = dY^T.X) are transposed in registers in 8x8 blocks on their way into LDS, so no transposed
+// copy of any tensor ever exists in HBM.  The global loads of tile k+1 are issued before the MFMAs
+// of tile k.  The accumulator layout is chosen so that each lane owns 4 consecutive columns of a
+// row of C: the epilogue (bias, residual, rounding to bf16) writes 8 bytes per store.
+//
+// fp32: plain LDS-tiled FMA kernel (used by the small fp32 configurations, which are launch bound).
+#include "../../include/teraio.h"
+#include "device_common.h"
+#include "kernels.h"
+
+namespace tio {
+namespace k {
+
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+constexpr int LDS_PAD = 8;     // bf16 elements (16 bytes) appended to every LDS row
+
+union Frag {
+    uint4 u;
+    bf16x8 v;
+};
+
+// ---- staging of one operand tile: global -> registers -> LDS ([row][k], row stride BK+LDS_PAD)
+template <int ROWS, int BK, int NT, bool KM> struct Stage;
+
+// contraction index contiguous in memory: 16-byte chunks along k
+template <int ROWS, int BK, int NT> struct Stage<ROWS, BK, NT, false> {
+    static constexpr int CPR = BK / 8, TOTAL = ROWS * CPR, PER = (TOTAL + NT - 1) / NT;
+    uint4 r[PER];
+    __device__ __forceinline__ void load(const uint16_t *__restrict__ base, int64_t ld, int64_t row0, int64_t rows,
+                                         int64_t k0, int64_t K, int tid) {
+#pragma unroll
+        for (int i = 0; i < PER; ++i) {
+            const int c = tid + i * NT;
+            const int row = c / CPR, kc = c % CPR;
+            const int64_t gr = row0 + row, gk = k0 + kc * 8;
+            uint4 v = make_uint4(0, 0, 0, 0);
+            if (c < TOTAL && gr < rows && gk < K) {
+                v = *reinterpret_cast<const uint4 *>(base + gr * ld + gk);
+                if (gk + 8 > K) {                       // ragged end of the contraction: zero the tail
+                    uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+                    for (int j = 0; j < 8; ++j)
+                        if (gk + j >= K) w[j >> 1] &= (j & 1) ? 0x0000ffffu : 0xffff0000u;
+                    v = make_uint4(w[0], w[1], w[2], w[3]);
+                }
+            }
+            r[i] = v;
+        }
+    }
+    __device__ __forceinline__ void store(uint16_t *lds, int tid) const {
+#pragma unroll
+        for (int i = 0; i < PER; ++i) {
+            const int c = tid + i * NT;
+            if (c < TOTAL) {
+                const int row = c / CPR, kc = c % CPR;
+                *reinterpret_cast<uint4 *>(lds + row * (BK + LDS_PAD) + kc * 8) = r[i];
+            }
+        }
+    }
+};
+
+// contraction index is the slow dimension: 8(k) x 8(rows) blocks, transposed in registers
+template <int ROWS, int BK, int NT> struct Stage<ROWS, BK, NT, true> {
+    static constexpr int RB = ROWS / 8, TOTAL = RB * (BK / 8), PER = (TOTAL + NT - 1) / NT;
+    uint4 r[PER][8];
+    __device__ __forceinline__ void load(const uint16_t *__restrict__ base, int64_t ld, int64_t row0, int64_t rows,
+                                         int64_t k0, int64_t K, int tid) {
+#pragma unroll
+        for (int i = 0; i < PER; ++i) {
+            const int c = tid + i * NT;
+            const int rb = c % RB, kb = c / RB;
+            const int64_t gr = row0 + rb * 8;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const int64_t gk = k0 + kb * 8 + j;
+                uint4 v = make_uint4(0, 0, 0, 0);
+                if (c < TOTAL && gr < rows && gk < K) v = *reinterpret_cast<const uint4 *>(base + gk * ld + gr);
+                r[i][j] = v;
+            }
+        }
+    }
+    __device__ __forceinline__ void store(uint16_t *lds, int tid) const {
+#pragma unroll
+        for (int i = 0; i < PER; ++i) {
+            const int c = tid + i * NT;
+            if (c < TOTAL) {
+                const int rb = c % RB, kb = c / RB;
+#pragma unroll
+                for (int rr = 0; rr < 8; ++rr) {       // output row rr of the 8x8 block: k = 0..7
+                    uint32_t w[4];
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const uint4 &lo = r[i][2 * j], &hi = r[i][2 * j + 1];
+                        const uint32_t a = rr < 2 ? lo.x : rr < 4 ? lo.y : rr < 6 ? lo.z : lo.w;
+                        const uint32_t b = rr < 2 ? hi.x : rr < 4 ? hi.y : rr < 6 ? hi.z : hi.w;
+                        // even row: low halves; odd row: high halves
+                        w[j] = (rr & 1) ? ((a >> 16) | (b & 0xffff0000u)) : ((a & 0x0000ffffu) | (b << 16));
+                    }
+                    *reinterpret_cast<uint4 *>(lds + (rb * 8 + rr) * (BK + LDS_PAD) + kb * 8) = make_uint4(w[0], w[1], w[2], w[3]);
+                }
+            }
+        }
+    }
+};
+
+template <int BM, int BN, int BK, int WGM, int WGN, bool AKM, bool BKM>
+__global__ void __launch_bounds__(WGM *WGN * 64)
+    gemm_bf16_k(const uint16_t *__restrict__ A, int64_t lda, const uint16_t *__restrict__ B, int64_t ldb,
+                const uint16_t *__restrict__ bias, const uint16_t *__restrict__ resid, int64_t ldr,
+                uint16_t *__restrict__ C, int64_t ldc, int64_t M, int64_t N, int64_t K, int tiles_m, int tiles_n) {
+    constexpr int NT = WGM * WGN * 64;
+    constexpr int WM = BM / WGM, WN = BN / WGN, TM = WM / 32, TN = WN / 32;
+    constexpr int LS = BK + LDS_PAD;
+    __shared__ __attribute__((aligned(16))) uint16_t As[BM * LS];
+    __shared__ __attribute__((aligned(16))) uint16_t Bs[BN * LS];
+
+    // tile order: groups of 8 tile rows walk the columns together, so that workgroups that run at the
+    // same time share operand tiles in L2
+    const int tid = threadIdx.x;
+    int bid = blockIdx.x;
+    constexpr int GROUP = 8;
+    const int per_group = GROUP * tiles_n;
+    const int g = bid / per_group;
+    const int gm0 = g * GROUP;
+    const int gsz = tiles_m - gm0 < GROUP ? tiles_m - gm0 : GROUP;
+    const int tm = gm0 + (bid % per_group) % gsz;
+    const int tn = (bid % per_group) / gsz;
+    const int64_t m0 = (int64_t)tm * BM, n0 = (int64_t)tn * BN;
+
+    const int wave = tid >> 6, lane = tid & 63;
+    const int wm = wave / WGN, wn = wave % WGN;
+    const int l32 = lane & 31, lhi = lane >> 5;
+
+    floatx16 acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+    Stage<BM, BK, NT, AKM> sa;
+    Stage<BN, BK, NT, BKM> sb;
+    const int nk = (int)((K + BK - 1) / BK);
+    sa.load(A, lda, m0, M, 0, K, tid);
+    sb.load(B, ldb, n0, N, 0, K, tid);
+    sa.store(As, tid);
+    sb.store(Bs, tid);
+    __syncthreads();
+    for (int kt = 0; kt < nk; ++kt) {
+        if (kt + 1 < nk) {
+            sa.load(A, lda, m0, M, (int64_t)(kt + 1) * BK, K, tid);
+            sb.load(B, ldb, n0, N, (int64_t)(kt + 1) * BK, K, tid);
+        }
+#pragma unroll
+        for (int ks = 0; ks < BK / 16; ++ks) {
+            Frag fa[TM], fb[TN];
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+                fa[i].u = *reinterpret_cast<const uint4 *>(As + (wm * WM + i * 32 + l32) * LS + ks * 16 + lhi * 8);
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+                fb[j].u = *reinterpret_cast<const uint4 *>(Bs + (wn * WN + j * 32 + l32) * LS + ks * 16 + lhi * 8);
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    // first operand indexes the accumulator's register dimension (n), second its lane dimension (m)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j].v, fa[i].v, acc[i][j], 0, 0, 0);
+        }
+        __syncthreads();
+        if (kt + 1 < nk) {
+            sa.store(As, tid);
+            sb.store(Bs, tid);
+            __syncthreads();
+        }
+    }
+
+    // epilogue: lane holds C[m][n .. n+3] for 4 groups of columns per 32x32 tile
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+        const int64_t m = m0 + wm * WM + i * 32 + l32;
+        if (m >= M) continue;
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int64_t n = n0 + wn * WN + j * 32 + q * 8 + lhi * 4;
+                if (n >= N) continue;
+                float v[4] = {acc[i][j][q * 4 + 0], acc[i][j][q * 4 + 1], acc[i][j][q * 4 + 2], acc[i][j][q * 4 + 3]};
+                if (n + 4 <= N) {
+                    if (bias) {
+                        const uint2 t = *reinterpret_cast<const uint2 *>(bias + n);
+                        v[0] += __uint_as_float(t.x << 16); v[1] += __uint_as_float(t.x & 0xffff0000u);
+                        v[2] += __uint_as_float(t.y << 16); v[3] += __uint_as_float(t.y & 0xffff0000u);
+                    }
+                    if (resid) {
+                        const uint2 t = *reinterpret_cast<const uint2 *>(resid + m * ldr + n);
+                        v[0] += __uint_as_float(t.x << 16); v[1] += __uint_as_float(t.x & 0xffff0000u);
+                        v[2] += __uint_as_float(t.y << 16); v[3] += __uint_as_float(t.y & 0xffff0000u);
+                    }
+                    uint2 o;
+                    o.x = f32_to_bf16_bits(v[0]) | (f32_to_bf16_bits(v[1]) << 16);
+                    o.y = f32_to_bf16_bits(v[2]) | (f32_to_bf16_bits(v[3]) << 16);
+                    *reinterpret_cast<uint2 *>(C + m * ldc + n) = o;
+                } else {
+                    for (int e = 0; e < 4 && n + e < N; ++e) {
+                        float x = v[e];
+                        if (bias) x += bf16_bits_to_f32(bias[n + e]);
+                        if (resid) x += bf16_bits_to_f32(resid[m * ldr + n + e]);
+                        C[m * ldc + n + e] = (uint16_t)f32_to_bf16_bits(x);
+                    }
+                }
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------- fp32
+template <bool AKM, bool BKM>
+__global__ void __launch_bounds__(256) gemm_f32_k(const float *__restrict__ A, int64_t lda, const float *__restrict__ B,
+                                                  int64_t ldb, const float *__restrict__ bias,
+                                                  const float *__restrict__ resid, int64_t ldr, float *__restrict__ C,
+                                                  int64_t ldc, int64_t M, int64_t N, int64_t K) {
+    constexpr int BT = 64, BKK = 16;
+    __shared__ float As[BKK][BT + 1];
+    __shared__ float Bs[BKK][BT + 1];
+    const int tid = threadIdx.x;
+    const int64_t m0 = (int64_t)blockIdx.y * BT, n0 = (int64_t)blockIdx.x * BT;
+    const int ty = tid / 16, tx = tid % 16;             // thread computes rows ty*4.., cols tx*4..
+    float acc[4][4] = {};
+    for (int64_t k0 = 0; k0 < K; k0 += BKK) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int e = tid + i * 256;                 // 0..1023
+            int r, kk;
+            if (AKM) { r = e % BT; kk = e / BT; } else { kk = e % BKK; r = e / BKK; }
+            const int64_t gm = m0 + r, gk = k0 + kk;
+            As[kk][r] = (gm < M && gk < K) ? (AKM ? A[gk * lda + gm] : A[gm * lda + gk]) : 0.f;
+            if (BKM) { r = e % BT; kk = e / BT; } else { kk = e % BKK; r = e / BKK; }
+            const int64_t gn = n0 + r, gkb = k0 + kk;
+            Bs[kk][r] = (gn < N && gkb < K) ? (BKM ? B[gkb * ldb + gn] : B[gn * ldb + gkb]) : 0.f;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int kk = 0; kk < BKK; ++kk) {
+            float a[4], b[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) { a[i] = As[kk][ty * 4 + i]; b[i] = Bs[kk][tx * 4 + i]; }
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) acc[i][j] = fmaf(a[i], b[j], acc[i][j]);
+        }
+        __syncthreads();
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int64_t m = m0 + ty * 4 + i;
+        if (m >= M) continue;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int64_t n = n0 + tx * 4 + j;
+            if (n >= N) continue;
+            float x = acc[i][j];
+            if (bias) x += bias[n];
+            if (resid) x += resid[m * ldr + n];
+            C[m * ldc + n] = x;
+        }
+    }
+}
+
+}  // namespace
+
+template <int BM, int BN, int BK, int WGM, int WGN>
+static void launch_bf16(hipStream_t s, bool a_km, bool b_km, int64_t M, int64_t N, int64_t K, const void *A, int64_t lda,
+                        const void *B, int64_t ldb, const void *bias, const void *resid, int64_t ldr, void *C, int64_t ldc) {
+    const int tiles_m = (int)((M + BM - 1) / BM), tiles_n = (int)((N + BN - 1) / BN);
+    const dim3 grid((unsigned)(tiles_m * tiles_n));
+    const dim3 block(WGM * WGN * 64);
+#define TIO_GEMM_ARGS (const uint16_t *)A, lda, (const uint16_t *)B, ldb, (const uint16_t *)bias, (const uint16_t *)resid, ldr, \
+                      (uint16_t *)C, ldc, M, N, K, tiles_m, tiles_n
+    if (!a_km && !b_km) gemm_bf16_k<BM, BN, BK, WGM, WGN, false, false><<<grid, block, 0, s>>>(TIO_GEMM_ARGS);
+    else if (!a_km && b_km) gemm_bf16_k<BM, BN, BK, WGM, WGN, false, true><<<grid, block, 0, s>>>(TIO_GEMM_ARGS);
+    else if (a_km && b_km) gemm_bf16_k<BM, BN, BK, WGM, WGN, true, true><<<grid, block, 0, s>>>(TIO_GEMM_ARGS);
+    else gemm_bf16_k<BM, BN, BK, WGM, WGN, true, false><<<grid, block, 0, s>>>(TIO_GEMM_ARGS);
+#undef TIO_GEMM_ARGS
+}
+
+void gemm(hipStream_t s, int dtype, bool a_km, bool b_km, int64_t M, int64_t N, int64_t K, const void *A, int64_t lda,
+          const void *B, int64_t ldb, const void *bias, const void *resid, int64_t ldr, void *C, int64_t ldc) {
+    if (M <= 0 || N <= 0 || K <= 0) return;
+    if (dtype == TIO_PREC_BF16) {
+        launch_bf16<128, 128, 64, 2, 2>(s, a_km, b_km, M, N, K, A, lda, B, ldb, bias, resid, ldr, C, ldc);
+    } else {
+        const dim3 grid((unsigned)((N + 63) / 64), (unsigned)((M + 63) / 64));
+#define TIO_GEMM_ARGS (const float *)A, lda, (const float *)B, ldb, (const float *)bias, (const float *)resid, ldr, (float *)C, ldc, M, N, K
+        if (!a_km && !b_km) gemm_f32_k<false, false><<<grid, 256, 0, s>>>(TIO_GEMM_ARGS);
+        else if (!a_km && b_km) gemm_f32_k<false, true><<<grid, 256, 0, s>>>(TIO_GEMM_ARGS);
+        else if (a_km && b_km) gemm_f32_k<true, true><<<grid, 256, 0, s>>>(TIO_GEMM_ARGS);
+        else gemm_f32_k<true, false><<<grid, 256, 0, s>>>(TIO_GEMM_ARGS);
+#undef TIO_GEMM_ARGS
+    }
+}
+
+}  // namespace k
+}  // namespace tio

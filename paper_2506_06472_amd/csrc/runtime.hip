@@ -1,0 +1,517 @@
+// Runtime of the training step: context, tensor location table, plan installation and the
+// migration engine (Section 3.3 of the paper).  The host walks the kernel schedule once per
+// iteration; before kernel k it issues the plan entries triggered at k (offloads on the
+// device-to-host stream, prefetches on the host-to-device stream), then makes the compute stream
+// wait for exactly the events kernel k depends on (its prefetched operands, and the offloads that
+// empty address ranges its outputs reuse), then launches kernel k.  A late migration therefore
+// stalls the kernel that needs it and nothing else, which is the paper's "kernel stall".  Urgent
+// entries come first within each direction at every trigger point.  The slow tier is pinned host
+// memory; its bandwidth is enforced on the copy streams by a stamp kernel before and a bounded wait
+// kernel after each copy.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <chrono>
+#include <cmath>
+#include <cstring>
+#include <string>
+#include <vector>
+
+#include "analysis.h"
+#include "handles.h"
+#include "kernels.h"
+
+using namespace tio;
+
+namespace {
+
+constexpr uint64_t kReservedTail = 4096;     // end of the arena kept for the runtime (pacing stamps)
+
+struct HipError { hipError_t e; const char *what; };
+#define HIPCHK(x)                                   \
+    do {                                            \
+        hipError_t _e = (x);                        \
+        if (_e != hipSuccess) throw HipError{_e, #x}; \
+    } while (0)
+
+inline uint16_t host_f32_to_bf16(float f) {
+    uint32_t u;
+    std::memcpy(&u, &f, 4);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return 0x7fc0;
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+inline float host_bf16_to_f32(uint16_t b) {
+    uint32_t u = (uint32_t)b << 16;
+    float f;
+    std::memcpy(&f, &u, 4);
+    return f;
+}
+
+}  // namespace
+
+struct tio_ctx {
+    tio_model_cfg cfg;
+    tio_runtime_cfg rt;
+    Program prog;
+    Trace trace;
+    Lifetimes life;
+    hipStream_t sc = nullptr, sd = nullptr, sh = nullptr;
+    uint8_t *arena = nullptr, *host = nullptr;
+    uint64_t arena_usable = 0;
+    unsigned long long *pace_slots = nullptr;            // device: [0] d2h stamp, [1] h2d stamp
+    std::vector<uint64_t> home;                          // host offset of every persistent tensor
+    uint64_t home_bytes = 0;
+    uint64_t bw = 0;
+    double clock_hz = 1e8;
+
+    Plan plan;                                           // installed plan (copy)
+    bool installed = false, params_dirty = true;
+    std::vector<uint8_t> on_dev;                         // per persistent tensor: latest version is in the arena
+    std::vector<uint64_t> dev_addr;
+    std::vector<std::vector<uint64_t>> ptrs;             // per kernel, per role: arena offset (UINT64_MAX = absent)
+    std::vector<hipEvent_t> ev_kernel, ev_off, ev_pre, ev_t0, ev_t1;
+    std::vector<uint8_t> rec_kernel, rec_off, rec_pre;
+    int step = 0;
+    float *loss_pinned = nullptr;                         // 4 KiB of pinned host memory owned by the context
+    std::vector<std::vector<float>> grads;
+    Plan uncapped;
+    bool have_uncapped = false;
+};
+
+namespace {
+
+void destroy_events(std::vector<hipEvent_t> &v) {
+    for (hipEvent_t e : v) if (e) (void)hipEventDestroy(e);
+    v.clear();
+}
+void make_events(std::vector<hipEvent_t> &v, size_t n, bool timing) {
+    destroy_events(v);
+    v.assign(n, nullptr);
+    for (size_t i = 0; i < n; ++i) HIPCHK(hipEventCreateWithFlags(&v[i], timing ? hipEventDefault : hipEventDisableTiming));
+}
+
+void sync_all(tio_ctx *c) {
+    HIPCHK(hipStreamSynchronize(c->sc));
+    HIPCHK(hipStreamSynchronize(c->sd));
+    HIPCHK(hipStreamSynchronize(c->sh));
+}
+
+// brings the latest version of every persistent tensor into its home slot on the slow tier
+void gather_to_home(tio_ctx *c) {
+    sync_all(c);
+    if (!c->installed) return;
+    for (int t = 0; t < c->prog.n_persistent; ++t)
+        if (c->on_dev[t])
+            HIPCHK(hipMemcpy(c->host + c->home[t], c->arena + c->dev_addr[t], c->prog.tensors[t].bytes, hipMemcpyDeviceToHost));
+}
+
+void install_plan(tio_ctx *c, const Plan &p) {
+    const int N = c->trace.n_kernels;
+    if (p.structure_hash != c->trace.structure_hash || p.n_kernels != N)
+        throw PlanError{TIO_ERR_PLAN_STALE, "plan was built from a different trace"};
+    if (p.arena_needed > c->arena_usable)
+        throw PlanError{TIO_ERR_ARENA_TOO_SMALL, "plan needs " + std::to_string(p.arena_needed) + " arena bytes, context has " +
+                                                     std::to_string(c->arena_usable)};
+    if (p.host_needed > c->rt.host_bytes)
+        throw PlanError{TIO_ERR_OOM_HOST, "plan needs " + std::to_string(p.host_needed) + " slow-tier bytes, pool has " +
+                                              std::to_string(c->rt.host_bytes)};
+    gather_to_home(c);
+    c->plan = p;
+    c->installed = true;
+    const int np = c->prog.n_persistent;
+    c->on_dev.assign(np, 0);
+    c->dev_addr.assign(np, 0);
+    for (int t = 0; t < np; ++t) {
+        if (p.persistent_home[t] != c->home[t]) throw PlanError{TIO_ERR_PLAN_INVALID, "home slot mismatch"};
+        const uint64_t a = address_at(p, t, 0);
+        if (a == UINT64_MAX) continue;
+        // resident at the iteration boundary unless a prefetch issued at trigger 0 brings it in
+        bool by_prefetch_at_0 = false;
+        for (int ai : p.alloc_of[t]) {
+            const Alloc &al = p.allocs[ai];
+            if (!al.whole_cycle && al.born_by_pair >= 0 && al.first == 0) by_prefetch_at_0 = true;
+        }
+        if (by_prefetch_at_0) continue;
+        HIPCHK(hipMemcpy(c->arena + a, c->host + c->home[t], c->prog.tensors[t].bytes, hipMemcpyHostToDevice));
+        c->on_dev[t] = 1;
+        c->dev_addr[t] = a;
+    }
+    c->ptrs.assign(N, std::vector<uint64_t>(kMaxRoles, UINT64_MAX));
+    for (int k = 0; k < N; ++k)
+        for (int r = 0; r < kMaxRoles; ++r) {
+            const int t = c->prog.kernels[k].t[r];
+            if (t < 0) continue;
+            const uint64_t a = address_at(p, t, k);
+            if (a == UINT64_MAX) throw PlanError{TIO_ERR_PLAN_INVALID, "operand not resident at kernel " + std::to_string(k)};
+            if (a + c->prog.tensors[t].bytes > c->arena_usable) throw PlanError{TIO_ERR_PLAN_INVALID, "address outside the arena"};
+            c->ptrs[k][r] = a;
+        }
+    make_events(c->ev_kernel, N, false);
+    make_events(c->ev_off, p.pairs.size(), false);
+    make_events(c->ev_pre, p.pairs.size(), false);
+    c->rec_kernel.assign(N, 0);
+    c->rec_off.assign(p.pairs.size(), 0);
+    c->rec_pre.assign(p.pairs.size(), 0);
+    c->params_dirty = false;
+}
+
+void launch(tio_ctx *c, int k) {
+    const KernelRec &r = c->prog.kernels[k];
+    const tio_model_cfg &m = c->cfg;
+    auto P = [&](int role) -> void * { return c->ptrs[k][role] == UINT64_MAX ? nullptr : (void *)(c->arena + c->ptrs[k][role]); };
+    const int dt = m.precision;
+    const bool rms = m.arch == TIO_ARCH_LLAMA;
+    const int64_t B = m.batch, T = m.seq_len, H = m.n_heads, dh = m.d_model / m.n_heads;
+    hipStream_t s = c->sc;
+    switch (r.op) {
+    case OP_EMBED_FWD: k::embed_fwd(s, dt, (const int32_t *)P(0), P(1), P(2), P(3), r.p[0], r.p[1], r.p[2]); break;
+    case OP_NORM_FWD: k::norm_fwd(s, dt, rms, P(0), P(1), P(2), P(3), (float *)P(4), r.p[0], r.p[1], m.norm_eps); break;
+    case OP_GEMM:
+        k::gemm(s, dt, false, false, r.p[0], r.p[1], r.p[2], P(0), r.p[2], P(1), r.p[2], P(2), P(3), r.p[3], P(4), r.p[3]);
+        break;
+    case OP_ROPE_FWD: k::rope(s, dt, P(0), B, T, H, dh, m.rope_theta, false); break;
+    case OP_ROPE_BWD: k::rope(s, dt, P(0), B, T, H, dh, m.rope_theta, true); break;
+    case OP_ATTN_FWD: k::attn_fwd(s, dt, P(0), P(1), (float *)P(2), B, T, H, dh); break;
+    case OP_GELU_FWD: k::gelu_fwd(s, dt, P(0), P(1), r.p[0]); break;
+    case OP_SWIGLU_FWD: k::swiglu_fwd(s, dt, P(0), P(1), r.p[0], r.p[1]); break;
+    case OP_CE_FWD_BWD: k::ce_fwd_bwd(s, dt, P(0), (const int32_t *)P(1), (float *)P(2), r.p[0], r.p[1], r.p[2]); break;
+    case OP_LOSS_REDUCE: k::loss_reduce(s, (const float *)P(0), (float *)P(1), r.p[0]); break;
+    case OP_GEMM_DX:   // dX[S,n_in] = dY[S,n_out] . W[n_out,n_in]: the weight has the contraction index slow
+        k::gemm(s, dt, false, true, r.p[0], r.p[1], r.p[2], P(0), r.p[3], P(1), r.p[1], nullptr, nullptr, 0, P(2), r.p[1]);
+        break;
+    case OP_GEMM_DW:   // dW[n_out,n_in] = dY^T . X: both operands have the contraction index (tokens) slow
+        k::gemm(s, dt, true, true, r.p[0], r.p[1], r.p[2], P(0), r.p[3], P(1), r.p[1], nullptr, nullptr, 0, P(2), r.p[1]);
+        break;
+    case OP_BIAS_GRAD: k::bias_grad(s, dt, P(0), P(1), r.p[0], r.p[1], r.p[1]); break;
+    case OP_GELU_BWD: k::gelu_bwd(s, dt, P(0), P(1), r.p[0]); break;
+    case OP_SWIGLU_BWD: k::swiglu_bwd(s, dt, P(0), P(1), P(2), r.p[0], r.p[1]); break;
+    case OP_NORM_BWD:
+        k::norm_bwd(s, dt, rms, P(0), P(1), (const float *)P(2), P(3), P(4), P(5), (float *)P(6), r.p[0], r.p[1], r.p[2]);
+        break;
+    case OP_NORM_BWD_PARAMS: k::norm_bwd_params(s, dt, rms, (const float *)P(0), P(1), P(2), r.p[0], r.p[1]); break;
+    case OP_ATTN_BWD_PRE: k::attn_bwd_pre(s, dt, P(0), P(1), (float *)P(2), B, T, H, dh); break;
+    case OP_ATTN_BWD: k::attn_bwd(s, dt, P(0), P(1), (const float *)P(2), (const float *)P(3), P(4), B, T, H, dh); break;
+    case OP_EMBED_BWD: k::embed_bwd(s, dt, P(0), (const int32_t *)P(1), P(2), r.p[0], r.p[1], r.p[2]); break;
+    case OP_POSEMB_BWD: k::posemb_bwd(s, dt, P(0), P(1), r.p[0], r.p[1], r.p[2]); break;
+    case OP_ADAMW: {
+        const double t = (double)(c->step + 1);
+        const float bc1 = (float)(1.0 - std::pow((double)m.beta1, t)), bc2 = (float)(1.0 - std::pow((double)m.beta2, t));
+        k::adamw(s, dt, P(0), P(1), (float *)P(2), (float *)P(3), (float *)P(4), r.p[0], m.lr, m.beta1, m.beta2, m.adam_eps,
+                 m.weight_decay, bc1, bc2);
+        break;
+    }
+    default: throw PlanError{TIO_ERR_INVALID_ARG, "unknown operator"};
+    }
+    HIPCHK(hipGetLastError());
+}
+
+void paced_copy(tio_ctx *c, hipStream_t s, int slot, void *dst, const void *src, uint64_t bytes, hipMemcpyKind kind) {
+    if (c->bw) k::pace_begin(s, c->pace_slots + slot);
+    HIPCHK(hipMemcpyAsync(dst, src, bytes, kind, s));
+    if (c->bw) {
+        double ticks = (double)bytes / (double)c->bw * c->clock_hz;
+        ticks = std::min(ticks, 30.0 * c->clock_hz);         // bounded wait
+        k::pace_wait(s, c->pace_slots + slot, (unsigned long long)ticks);
+    }
+}
+
+void capture_grad(tio_ctx *c, int k) {
+    const KernelRec &r = c->prog.kernels[k];
+    int pi = -1;
+    for (int i = 0; i < (int)c->prog.params.size(); ++i) if (c->prog.params[i].grad == r.t[0]) pi = i;
+    if (pi < 0) return;
+    const int64_t n = r.p[0];
+    HIPCHK(hipStreamSynchronize(c->sc));
+    std::vector<float> &g = c->grads[pi];
+    g.resize(n);
+    if (c->cfg.precision == TIO_PREC_BF16) {
+        std::vector<uint16_t> tmp(n);
+        HIPCHK(hipMemcpy(tmp.data(), c->arena + c->ptrs[k][0], n * 2, hipMemcpyDeviceToHost));
+        for (int64_t i = 0; i < n; ++i) g[i] = host_bf16_to_f32(tmp[i]);
+    } else {
+        HIPCHK(hipMemcpy(g.data(), c->arena + c->ptrs[k][0], n * 4, hipMemcpyDeviceToHost));
+    }
+}
+
+// one iteration; timing != nullptr: per-kernel elapsed ns measured with events
+void run_step(tio_ctx *c, const int32_t *tokens, const int32_t *labels, bool capture, std::vector<int64_t> *timing,
+              tio_step_stats *st) {
+    const int N = c->trace.n_kernels;
+    const Plan &p = c->plan;
+    const int64_t S = (int64_t)c->cfg.batch * c->cfg.seq_len;
+    for (int64_t i = 0; i < S; ++i) {
+        if (tokens[i] < 0 || tokens[i] >= c->cfg.vocab || labels[i] < 0 || labels[i] >= c->cfg.vocab)
+            throw PlanError{TIO_ERR_INVALID_ARG, "token or label id outside the vocabulary"};
+    }
+    if (capture) c->grads.assign(c->prog.params.size(), {});
+    if (timing) { if ((int)c->ev_t0.size() != N) { make_events(c->ev_t0, N, true); make_events(c->ev_t1, N, true); } }
+    const auto w0 = std::chrono::steady_clock::now();
+    HIPCHK(hipMemcpyAsync(c->arena + address_at(p, c->prog.tokens_id, 0), tokens, S * 4, hipMemcpyHostToDevice, c->sc));
+    HIPCHK(hipMemcpyAsync(c->arena + address_at(p, c->prog.labels_id, 0), labels, S * 4, hipMemcpyHostToDevice, c->sc));
+    uint64_t d2h = 0, h2d = 0;
+    int nmig = 0;
+    for (int k = 0; k < N; ++k) {
+        const int prev = (k + N - 1) % N;
+        for (int ei : p.entries_at[k]) {
+            const tio_plan_entry &e = p.entries[ei];
+            const Pair &pr = p.pairs[e.pair];
+            const bool persistent = e.tensor < c->prog.n_persistent;
+            if (e.kind == TIO_OFFLOAD) {
+                // first iteration after a plan is installed: an offload that belongs to the end of the
+                // previous iteration (trigger wraps to the start of this one) has nothing to copy, the
+                // slow-tier home slot already holds the latest version
+                if (persistent && !c->on_dev[e.tensor]) continue;
+                const Alloc &al = p.allocs[pr.alloc_before];
+                if (c->rec_kernel[prev]) HIPCHK(hipStreamWaitEvent(c->sd, c->ev_kernel[prev], 0));
+                paced_copy(c, c->sd, 0, c->host + pr.host_offset, c->arena + al.address, pr.bytes, hipMemcpyDeviceToHost);
+                HIPCHK(hipEventRecord(c->ev_off[e.pair], c->sd));
+                c->rec_off[e.pair] = 1;
+                if (persistent) c->on_dev[e.tensor] = 0;
+                d2h += pr.bytes;
+            } else {
+                const Alloc &al = p.allocs[pr.alloc_after];
+                if (c->rec_kernel[prev]) HIPCHK(hipStreamWaitEvent(c->sh, c->ev_kernel[prev], 0));
+                if (c->rec_off[e.pair]) HIPCHK(hipStreamWaitEvent(c->sh, c->ev_off[e.pair], 0));
+                for (int q : al.wait_pairs) if (c->rec_off[q]) HIPCHK(hipStreamWaitEvent(c->sh, c->ev_off[q], 0));
+                paced_copy(c, c->sh, 1, c->arena + al.address, c->host + pr.host_offset, pr.bytes, hipMemcpyHostToDevice);
+                HIPCHK(hipEventRecord(c->ev_pre[e.pair], c->sh));
+                c->rec_pre[e.pair] = 1;
+                if (persistent) { c->on_dev[e.tensor] = 1; c->dev_addr[e.tensor] = al.address; }
+                h2d += pr.bytes;
+            }
+            ++nmig;
+        }
+        for (int q : p.kernel_wait_pre[k]) if (c->rec_pre[q]) HIPCHK(hipStreamWaitEvent(c->sc, c->ev_pre[q], 0));
+        for (int q : p.kernel_wait_off[k]) if (c->rec_off[q]) HIPCHK(hipStreamWaitEvent(c->sc, c->ev_off[q], 0));
+        if (capture && c->prog.kernels[k].op == OP_ADAMW) capture_grad(c, k);
+        if (timing) HIPCHK(hipEventRecord(c->ev_t0[k], c->sc));
+        launch(c, k);
+        if (timing) HIPCHK(hipEventRecord(c->ev_t1[k], c->sc));
+        // the scalar loss lives only until later kernels reuse its range: copy it out in stream order
+        if (c->prog.kernels[k].op == OP_LOSS_REDUCE)
+            HIPCHK(hipMemcpyAsync(c->loss_pinned, c->arena + c->ptrs[k][1], 4, hipMemcpyDeviceToHost, c->sc));
+        if (p.kernel_needs_event[k]) { HIPCHK(hipEventRecord(c->ev_kernel[k], c->sc)); c->rec_kernel[k] = 1; }
+    }
+    HIPCHK(hipStreamSynchronize(c->sc));
+    const float loss = *c->loss_pinned;
+    const auto w1 = std::chrono::steady_clock::now();
+    c->step += 1;
+    if (timing) {
+        timing->assign(N, 0);
+        for (int k = 0; k < N; ++k) {
+            float ms = 0.f;
+            HIPCHK(hipEventElapsedTime(&ms, c->ev_t0[k], c->ev_t1[k]));
+            (*timing)[k] = std::max<int64_t>(1, (int64_t)std::llround((double)ms * 1e6));
+        }
+    }
+    if (st) {
+        std::memset(st, 0, sizeof(*st));
+        st->loss = loss;
+        st->step = c->step;
+        st->wall_ns = std::chrono::duration_cast<std::chrono::nanoseconds>(w1 - w0).count();
+        st->d2h_bytes = d2h; st->h2d_bytes = h2d;
+        st->n_kernels = N; st->n_migrations = nmig;
+        if (timing) for (int64_t x : *timing) st->kernel_ns += x;
+    }
+}
+
+const Plan &uncapped_plan(tio_ctx *c) {
+    if (!c->have_uncapped) {
+        tio_plan_opts o{1, 0, 0, UINT64_MAX};
+        c->uncapped = build_plan(c->trace, c->life, UINT64_MAX / 2, 0, o);
+        c->uncapped.serial = UINT64_MAX;
+        c->have_uncapped = true;
+    }
+    return c->uncapped;
+}
+
+void ensure_plan(tio_ctx *c, const tio_plan *plan) {
+    const Plan &want = plan ? plan->p : uncapped_plan(c);
+    if (!c->installed || c->params_dirty || c->plan.serial != want.serial) install_plan(c, want);
+}
+
+}  // namespace
+
+#define TIO_RT_BEGIN try {
+#define TIO_RT_END                                                                                              \
+    } catch (const PlanError &e) { return fail(e.code, e.msg);                                                  \
+    } catch (const HipError &e) { return fail(TIO_ERR_HIP, std::string(e.what) + ": " + hipGetErrorString(e.e)); \
+    } catch (const std::exception &e) { return fail(TIO_ERR_INVALID_ARG, e.what()); }
+
+extern "C" {
+
+int tio_ctx_create(const tio_model_cfg *cfg, const tio_runtime_cfg *rt, tio_ctx **out) {
+    if (!cfg || !rt || !out) return fail(TIO_ERR_INVALID_ARG, "null argument");
+    TIO_RT_BEGIN
+    if (!rt->arena || !rt->host_pool || rt->arena_bytes < (1u << 16)) return fail(TIO_ERR_INVALID_ARG, "arena and slow-tier pool are required");
+    if (((uintptr_t)rt->arena & 255) || ((uintptr_t)rt->host_pool & 255)) return fail(TIO_ERR_INVALID_ARG, "arena and pool must be 256-byte aligned");
+    const int dh = cfg->d_model / std::max(1, cfg->n_heads);
+    if (dh != 32 && dh != 64 && dh != 128) return fail(TIO_ERR_INVALID_ARG, "head dimension must be 32, 64 or 128");
+    if (((int64_t)cfg->batch * cfg->seq_len) % 8) return fail(TIO_ERR_INVALID_ARG, "batch * seq_len must be a multiple of 8");
+    int ndev = 0;
+    if (hipGetDeviceCount(&ndev) != hipSuccess || ndev < 1) return fail(TIO_ERR_HIP, "no HIP device");
+    tio_ctx *c = new tio_ctx();
+    c->cfg = *cfg; c->rt = *rt;
+    c->prog = build_program(*cfg);
+    c->trace = trace_from_program(c->prog);
+    c->life = analyze(c->trace);
+    c->sc = (hipStream_t)rt->compute_stream; c->sd = (hipStream_t)rt->d2h_stream; c->sh = (hipStream_t)rt->h2d_stream;
+    c->arena = (uint8_t *)rt->arena; c->host = (uint8_t *)rt->host_pool;
+    c->arena_usable = (rt->arena_bytes - kReservedTail) / 256 * 256;
+    c->pace_slots = (unsigned long long *)(c->arena + c->arena_usable);
+    c->bw = rt->slow_tier_bw;
+    int khz = 0;
+    if (hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, 0) == hipSuccess && khz > 0) c->clock_hz = khz * 1000.0;
+    uint64_t h = 0;
+    c->home.assign(c->prog.n_persistent, 0);
+    for (int t = 0; t < c->prog.n_persistent; ++t) { c->home[t] = h; h += c->prog.tensors[t].bytes; }
+    c->home_bytes = h;
+    if (h > rt->host_bytes) { delete c; return fail(TIO_ERR_OOM_HOST, "slow-tier pool smaller than the persistent tensors"); }
+    std::memset(c->host, 0, h);
+    if (hipHostMalloc((void **)&c->loss_pinned, 4096, hipHostMallocDefault) != hipSuccess) { delete c; return fail(TIO_ERR_HIP, "hipHostMalloc failed"); }
+    *out = c;
+    return TIO_OK;
+    TIO_RT_END
+}
+
+int tio_ctx_destroy(tio_ctx *c) {
+    if (!c) return TIO_OK;
+    (void)hipStreamSynchronize(c->sc); (void)hipStreamSynchronize(c->sd); (void)hipStreamSynchronize(c->sh);
+    destroy_events(c->ev_kernel); destroy_events(c->ev_off); destroy_events(c->ev_pre);
+    destroy_events(c->ev_t0); destroy_events(c->ev_t1);
+    if (c->loss_pinned) (void)hipHostFree(c->loss_pinned);
+    delete c;
+    return TIO_OK;
+}
+
+int tio_params_load(tio_ctx *c, int32_t index, const float *v, int64_t numel) {
+    if (!c || !v) return fail(TIO_ERR_INVALID_ARG, "null argument");
+    TIO_RT_BEGIN
+    if (index < 0 || index >= (int)c->prog.params.size()) return fail(TIO_ERR_INVALID_ARG, "parameter index out of range");
+    const ParamInfo &p = c->prog.params[index];
+    if (numel != p.rows * p.cols) return fail(TIO_ERR_INVALID_ARG, "element count differs from the parameter's shape");
+    if (!c->params_dirty) {            // keep the other parameters' latest values, then treat the arena as empty
+        gather_to_home(c);
+        c->params_dirty = true;
+        c->installed = false;
+    }
+    const bool bf = c->cfg.precision == TIO_PREC_BF16;
+    if (bf) {
+        uint16_t *w = (uint16_t *)(c->host + c->home[p.w]);
+        float *ms = (float *)(c->host + c->home[p.master]);
+        for (int64_t i = 0; i < numel; ++i) { w[i] = host_f32_to_bf16(v[i]); ms[i] = host_bf16_to_f32(w[i]); }
+    } else {
+        std::memcpy(c->host + c->home[p.w], v, numel * 4);
+    }
+    std::memset(c->host + c->home[p.m], 0, numel * 4);
+    std::memset(c->host + c->home[p.v], 0, numel * 4);
+    c->step = 0;
+    return TIO_OK;
+    TIO_RT_END
+}
+
+int tio_params_read(tio_ctx *c, int32_t index, int32_t which, float *dst, int64_t numel) {
+    if (!c || !dst) return fail(TIO_ERR_INVALID_ARG, "null argument");
+    TIO_RT_BEGIN
+    if (index < 0 || index >= (int)c->prog.params.size()) return fail(TIO_ERR_INVALID_ARG, "parameter index out of range");
+    const ParamInfo &p = c->prog.params[index];
+    if (numel != p.rows * p.cols) return fail(TIO_ERR_INVALID_ARG, "element count differs from the parameter's shape");
+    const int t = which == 0 ? p.w : which == 1 ? p.master : which == 2 ? p.m : which == 3 ? p.v : -1;
+    if (t < 0) return fail(TIO_ERR_INVALID_ARG, "no such state tensor for this precision");
+    sync_all(c);
+    const bool half = which == 0 && c->cfg.precision == TIO_PREC_BF16;
+    const uint64_t nbytes = (uint64_t)numel * (half ? 2 : 4);
+    std::vector<uint8_t> tmp(nbytes);
+    if (c->installed && !c->params_dirty && c->on_dev[t]) HIPCHK(hipMemcpy(tmp.data(), c->arena + c->dev_addr[t], nbytes, hipMemcpyDeviceToHost));
+    else std::memcpy(tmp.data(), c->host + c->home[t], nbytes);
+    if (half) for (int64_t i = 0; i < numel; ++i) dst[i] = host_bf16_to_f32(((uint16_t *)tmp.data())[i]);
+    else std::memcpy(dst, tmp.data(), nbytes);
+    return TIO_OK;
+    TIO_RT_END
+}
+
+int tio_grads_read(tio_ctx *c, int32_t index, float *dst, int64_t numel) {
+    if (!c || !dst) return fail(TIO_ERR_INVALID_ARG, "null argument");
+    if (index < 0 || index >= (int)c->grads.size() || (int64_t)c->grads[index].size() != numel)
+        return fail(TIO_ERR_INVALID_ARG, "no captured gradient of that size (run a step with capture_grads)");
+    std::memcpy(dst, c->grads[index].data(), numel * 4);
+    return TIO_OK;
+}
+
+int tio_set_slow_tier_bw(tio_ctx *c, uint64_t bw) {
+    if (!c) return fail(TIO_ERR_INVALID_ARG, "null argument");
+    c->bw = bw;
+    return TIO_OK;
+}
+
+int tio_train_step(tio_ctx *c, const int32_t *tokens, const int32_t *labels, const tio_plan *plan, int32_t capture,
+                   tio_step_stats *out) {
+    if (!c || !tokens || !labels) return fail(TIO_ERR_INVALID_ARG, "null argument");
+    TIO_RT_BEGIN
+    ensure_plan(c, plan);
+    run_step(c, tokens, labels, capture != 0, nullptr, out);
+    return TIO_OK;
+    TIO_RT_END
+}
+
+int tio_profile_iteration(tio_ctx *c, const int32_t *tokens, const int32_t *labels, int mode, tio_trace **out) {
+    if (!c || !out) return fail(TIO_ERR_INVALID_ARG, "null argument");
+    TIO_RT_BEGIN
+    tio_trace *h = new tio_trace{c->trace};
+    if (mode == TIO_PROFILE_MEASURED) {
+        if (!tokens || !labels) { delete h; return fail(TIO_ERR_INVALID_ARG, "null argument"); }
+        try {
+            ensure_plan(c, nullptr);
+            const int N = c->trace.n_kernels;
+            std::vector<std::vector<int64_t>> runs(3);
+            run_step(c, tokens, labels, false, nullptr, nullptr);          // warm-up
+            for (auto &r : runs) run_step(c, tokens, labels, false, &r, nullptr);
+            for (int k = 0; k < N; ++k) {
+                int64_t a = runs[0][k], b = runs[1][k], d = runs[2][k];
+                h->t.tau[k] = std::max(std::min(a, b), std::min(std::max(a, b), d));   // median of three
+            }
+        } catch (...) { delete h; throw; }
+    }
+    *out = h;
+    return TIO_OK;
+    TIO_RT_END
+}
+
+int tio_op_gemm(void *stream, int32_t dtype, int32_t a_km, int32_t b_km, int64_t M, int64_t N, int64_t K, const void *A,
+                int64_t lda, const void *B, int64_t ldb, const void *bias, const void *resid, int64_t ldr, void *C, int64_t ldc) {
+    TIO_RT_BEGIN
+    if (!A || !B || !C) return fail(TIO_ERR_INVALID_ARG, "null argument");
+    const int64_t al = dtype == TIO_PREC_BF16 ? 8 : 4;
+    if (lda % al || ldb % al || ldc % 4 || (resid && ldr % 4)) return fail(TIO_ERR_INVALID_ARG, "leading dimensions must be multiples of 8 elements");
+    if (((uintptr_t)A | (uintptr_t)B | (uintptr_t)C | (uintptr_t)bias | (uintptr_t)resid) & 15) return fail(TIO_ERR_INVALID_ARG, "pointers must be 16-byte aligned");
+    const int64_t ka = (K + al - 1) / al * al, ma = (M + al - 1) / al * al, na = (N + al - 1) / al * al;
+    if ((a_km ? lda < ma : lda < ka) || (b_km ? ldb < na : ldb < ka) || ldc < N)
+        return fail(TIO_ERR_INVALID_ARG, "leading dimension smaller than the (8-element padded) extent");
+    k::gemm((hipStream_t)stream, dtype, a_km != 0, b_km != 0, M, N, K, A, lda, B, ldb, bias, resid, ldr, C, ldc);
+    HIPCHK(hipGetLastError());
+    return TIO_OK;
+    TIO_RT_END
+}
+
+int tio_op_bench(tio_ctx *c, int32_t kernel_index, int32_t reps, double *out_avg_ns) {
+    if (!c || !out_avg_ns || reps < 1) return fail(TIO_ERR_INVALID_ARG, "bad argument");
+    TIO_RT_BEGIN
+    if (kernel_index < 0 || kernel_index >= c->trace.n_kernels) return fail(TIO_ERR_INVALID_ARG, "kernel index out of range");
+    ensure_plan(c, nullptr);
+    hipEvent_t e0, e1;
+    HIPCHK(hipEventCreate(&e0)); HIPCHK(hipEventCreate(&e1));
+    launch(c, kernel_index);                                  // warm-up
+    HIPCHK(hipEventRecord(e0, c->sc));
+    for (int i = 0; i < reps; ++i) launch(c, kernel_index);
+    HIPCHK(hipEventRecord(e1, c->sc));
+    HIPCHK(hipEventSynchronize(e1));
+    float ms = 0.f;
+    HIPCHK(hipEventElapsedTime(&ms, e0, e1));
+    (void)hipEventDestroy(e0); (void)hipEventDestroy(e1);
+    *out_avg_ns = (double)ms * 1e6 / reps;
+    return TIO_OK;
+    TIO_RT_END
+}
+
+}  // extern "C"

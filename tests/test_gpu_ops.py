@@ -1,0 +1,76 @@
+"""GPU parity of single operators against plain numpy float64 (C ABI entry point tio_op_gemm)."""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+
+def _dev(a, dtype):
+    import torch
+    t = torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda()
+    return t.to(torch.bfloat16) if dtype == "bf16" else t
+
+
+def _host(t):
+    return t.float().cpu().numpy().astype(np.float64)
+
+
+CASES = [  # M, N, K, pad of ld
+    (128, 128, 64, 0), (200, 136, 72, 0), (256, 384, 256, 0), (130, 1000, 96, 24), (64, 72, 1000, 8),
+    (513, 257, 130, 7), (8, 8, 8, 0), (1024, 768, 768, 0),
+]
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "fp32"])
+@pytest.mark.parametrize("a_km,b_km", [(0, 0), (0, 1), (1, 1), (1, 0)])
+@pytest.mark.parametrize("M,N,K,pad", CASES)
+def test_gemm_all_layouts(dtype, a_km, b_km, M, N, K, pad):
+    import torch
+    import paper_2506_06472_amd as tio
+    print(f"gemm {dtype} a_km={a_km} b_km={b_km} M={M} N={N} K={K} pad={pad}", flush=True)
+    rng = np.random.default_rng(M * 7 + N * 3 + K + a_km * 2 + b_km)
+    r8 = lambda n: (n + 7) // 8 * 8
+    # logical operands A[M,K], B[N,K]; stored [rows, ld] or [K, ld]
+    lda = (r8(M) if a_km else r8(K)) + 8 * (pad > 0)
+    ldb = (r8(N) if b_km else r8(K)) + 8 * (pad > 0)
+    ldc = r8(N) + 8 * (pad > 0)
+    A = rng.standard_normal((M, K)).astype(np.float32)
+    B = rng.standard_normal((N, K)).astype(np.float32)
+    bias = rng.standard_normal(r8(N)).astype(np.float32)
+    R = rng.standard_normal((M, ldc)).astype(np.float32)
+    As = np.full((K, lda) if a_km else (M, lda), np.nan, np.float32)     # NaN padding must never leak
+    Bs = np.full((K, ldb) if b_km else (N, ldb), np.nan, np.float32)
+    if a_km: As[:, :M] = A.T
+    else: As[:, :K] = A
+    if b_km: Bs[:, :N] = B.T
+    else: Bs[:, :K] = B
+    dA, dB, dbias, dR = _dev(As, dtype), _dev(Bs, dtype), _dev(bias, dtype), _dev(R, dtype)
+    dC = torch.full((M, ldc), 7.0, device="cuda", dtype=dA.dtype)
+    torch.cuda.synchronize()
+    for use_bias, use_res in ((0, 0), (1, 1)):
+        tio.tio_op_gemm(0, dtype, a_km, b_km, M, N, K, dA.data_ptr(), lda, dB.data_ptr(), ldb,
+                        dbias.data_ptr() if use_bias else 0, dR.data_ptr() if use_res else 0, ldc, dC.data_ptr(), ldc)
+        torch.cuda.synchronize()
+        An = np.nan_to_num(_host(dA)); Bn = np.nan_to_num(_host(dB))
+        A64 = An[:, :M].T if a_km else An[:, :K]
+        B64 = Bn[:, :N].T if b_km else Bn[:, :K]
+        ref = A64 @ B64.T
+        if use_bias: ref = ref + _host(dbias)[:N]
+        if use_res: ref = ref + _host(dR)[:, :N]
+        got = _host(dC)
+        assert np.all(got[:, N:] == 7.0), "wrote outside the N columns"
+        err = np.abs(got[:, :N] - ref)
+        tol = (2.0 ** -8 * np.abs(ref) + 1e-3 * np.sqrt(K)) if dtype == "bf16" else (1e-5 * np.sqrt(K) * (1 + np.abs(ref)))
+        assert np.all(err <= tol), (float(err.max()), np.unravel_index(err.argmax(), err.shape))
+
+
+def test_gemm_rejects_bad_arguments():
+    import torch
+    import paper_2506_06472_amd as tio
+    x = torch.zeros(64, 64, device="cuda", dtype=torch.bfloat16)
+    with pytest.raises(tio.TioError):
+        tio.tio_op_gemm(0, "bf16", 0, 0, 64, 64, 64, x.data_ptr(), 60, x.data_ptr(), 64, 0, 0, 0, x.data_ptr(), 64)
+    with pytest.raises(tio.TioError):
+        tio.tio_op_gemm(0, "bf16", 0, 0, 64, 64, 64, x.data_ptr() + 2, 64, x.data_ptr(), 64, 0, 0, 0, x.data_ptr(), 64)
+    with pytest.raises(tio.TioError):
+        tio.tio_op_gemm(0, "bf16", 0, 0, 64, 64, 64, x.data_ptr(), 64, x.data_ptr(), 64, 0, 0, 0, x.data_ptr(), 32)

@@ -1,0 +1,173 @@
+"""GPU parity of whole training steps (C ABI: tio_ctx_create, tio_params_load, tio_train_step, ...)
+against the CPU oracle, and bitwise equality of runs with and without offloading."""
+import numpy as np
+import pytest
+
+from oracle import model as om
+from synth import CONFIGS
+from gpulib import make_inputs, plans_for, read_state
+
+pytestmark = pytest.mark.gpu
+
+SMALL_BF16 = dict(arch="gpt", L=2, d=256, H=4, f=1024, V=1000, T=128, B=2, precision="bf16", lr=3e-4)
+SMALL_LLAMA_BF16 = dict(arch="llama", L=2, d=256, H=2, f=688, V=520, T=96, B=2, precision="bf16", lr=3e-4)
+
+
+def _ctx(cfg, plan_export, extra_arena=0, bw=0):
+    import paper_2506_06472_amd as tio
+    return tio.tio_ctx_create(cfg, plan_export["arena_needed"] + extra_arena, plan_export["host_needed"] + (1 << 20), bw)
+
+
+@pytest.mark.parametrize("name", ["tiny_gpt_fp32", "tiny_llama_fp32"])
+def test_fp32_steps_match_oracle(name):
+    cfg = CONFIGS[name]
+    params, tok, lab = make_inputs(cfg, seed=0)
+    lt, ll, up, _, peak = plans_for(cfg)
+    ctx = _ctx(cfg, up.export())
+    ctx.tio_params_load(params)
+    ref = om.Trainer(cfg, params)
+    for step in range(3):
+        print(f"{name} step {step}", flush=True)
+        st = ctx.tio_train_step(tok, lab, None, capture_grads=True)
+        rl = ref.step(tok, lab)
+        assert abs(st["loss"] - rl) <= 1e-5 * abs(rl), (step, st["loss"], rl)
+        for n, _, _ in ctx.params:
+            g = ctx.tio_grads_read(n).astype(np.float64)
+            gr = ref.last_grads[n].reshape(g.shape)
+            scale = np.abs(gr).max()
+            if scale < 1e-12:       # e.g. the key bias: its exact gradient is zero
+                assert np.abs(g).max() <= 1e-7, n
+            else:
+                assert np.abs(g - gr).max() <= 1e-4 * scale, (step, n, np.abs(g - gr).max() / scale)
+    # parameters after three steps: tight where the update is well conditioned, 2*lr per step elsewhere
+    for n, _, _ in ctx.params:
+        w = ctx.tio_params_read(n, 0).astype(np.float64)
+        wr = ref.p[n].reshape(w.shape)
+        assert np.abs(w - wr).max() <= 3 * 2 * cfg["lr"] + 1e-6, n
+        m = ctx.tio_params_read(n, 2).astype(np.float64)
+        mr = ref.m[n].reshape(m.shape)
+        assert np.abs(m - mr).max() <= 1e-4 * max(np.abs(mr).max(), 1e-12) + 1e-9, n
+    frac_close = np.mean([np.mean(np.abs(ctx.tio_params_read(n, 0) - ref.p[n].reshape(-1).reshape(ctx.tio_params_read(n, 0).shape)) < 1e-5)
+                          for n, _, _ in ctx.params if n.startswith("l0.w_")])
+    assert frac_close > 0.99
+    ctx.close()
+
+
+@pytest.mark.parametrize("name,cap_frac,bw,min_bytes", [
+    ("tiny_gpt_fp32", 0.5, 25 * 10**9, 0), ("tiny_gpt_fp32", 0.3, 10**9, 0), ("tiny_llama_fp32", 0.5, 25 * 10**9, 0),
+    ("tiny_llama_fp32", 0.45, 0, 16384)])
+def test_offloading_leaves_numerics_bitwise_unchanged(name, cap_frac, bw, min_bytes):
+    cfg = CONFIGS[name]
+    params, tok, lab = make_inputs(cfg, seed=1)
+    lt, ll, up, cp, peak = plans_for(cfg, cap_frac, bw, min_bytes)
+    ce = cp.export()
+    print(f"{name}: peak {peak} cap {ce['cap']} planning cap {ce['planning_cap']} entries {len(ce['entries'])} "
+          f"forced {ce['n_forced']} arena {ce['arena_needed']}", flush=True)
+    assert ce["arena_needed"] <= ce["cap"] < peak
+    names = [n for n, _, _ in __import__("paper_2506_06472_amd").tio_param_list(cfg)]
+    runs = []
+    for plan, arena in ((None, up.export()), (cp, ce)):
+        ctx = _ctx(cfg, dict(arena_needed=arena["arena_needed"] if plan is None else ce["cap"],
+                             host_needed=max(arena["host_needed"], ce["host_needed"])), bw=bw)
+        ctx.tio_params_load(params)
+        losses = []
+        for step in range(4):
+            print(f"  plan={'capped' if plan else 'none'} step {step}", flush=True)
+            st = ctx.tio_train_step(tok, lab, plan)
+            losses.append(st["loss"])
+            if plan is not None:
+                # steady state moves exactly the planned bytes; the first iteration after the plan is
+                # installed skips offloads that belong to the end of a previous iteration
+                assert st["h2d_bytes"] == ce["bytes_per_direction"]
+                assert (st["d2h_bytes"] == ce["bytes_per_direction"]) if step else (st["d2h_bytes"] <= ce["bytes_per_direction"])
+        state = read_state(ctx, names, cfg["precision"] == "bf16")
+        runs.append((losses, state))
+        ctx.close()
+    (l0, s0), (l1, s1) = runs
+    assert np.array(l0, dtype=np.float32).tobytes() == np.array(l1, dtype=np.float32).tobytes(), (l0, l1)
+    for key in s0:
+        assert s0[key].tobytes() == s1[key].tobytes(), key
+    assert l0[-1] < l0[0]
+
+
+@pytest.mark.parametrize("cfg", [SMALL_BF16, SMALL_LLAMA_BF16], ids=["gpt", "llama"])
+def test_bf16_loss_and_grads_against_oracle_and_bitwise_offload(cfg):
+    import paper_2506_06472_amd as tio
+    params, tok, lab = make_inputs(cfg, seed=2)
+    lt, ll, up, cp, peak = plans_for(cfg, 0.4, 25 * 10**9, 0)
+    ce = cp.export()
+    ctx = _ctx(cfg, up.export())
+    ctx.tio_params_load(params)
+    ref = om.Trainer(cfg, params)
+    losses = []
+    for step in range(3):
+        print(f"bf16 {cfg['arch']} step {step}", flush=True)
+        st = ctx.tio_train_step(tok, lab, None, capture_grads=(step == 0))
+        rl = ref.step(tok, lab)
+        losses.append(st["loss"])
+        assert abs(st["loss"] - rl) <= 2e-2 * abs(rl), (step, st["loss"], rl)
+        if step == 0:
+            for n, _, _ in ctx.params:
+                g = ctx.tio_grads_read(n).astype(np.float64)
+                gr = ref.last_grads[n].reshape(g.shape)
+                scale = np.abs(gr).max()
+                if scale > 1e-9:
+                    assert np.abs(g - gr).max() <= 6e-2 * scale, (n, np.abs(g - gr).max() / scale)
+    names = [n for n, _, _ in ctx.params]
+    s0 = read_state(ctx, names, True)
+    ctx.close()
+    ctx = tio.tio_ctx_create(cfg, ce["cap"], ce["host_needed"] + (1 << 20), 25 * 10**9)
+    ctx.tio_params_load(params)
+    l1 = [ctx.tio_train_step(tok, lab, cp)["loss"] for _ in range(3)]
+    s1 = read_state(ctx, names, True)
+    ctx.close()
+    assert np.array(losses, dtype=np.float32).tobytes() == np.array(l1, dtype=np.float32).tobytes(), (losses, l1)
+    for key in s0:
+        assert s0[key].tobytes() == s1[key].tobytes(), key
+
+
+def test_measured_profile_gives_the_same_structure_and_positive_times():
+    import paper_2506_06472_amd as tio
+    cfg = CONFIGS["tiny_gpt_fp32"]
+    params, tok, lab = make_inputs(cfg, seed=0)
+    lt, ll, up, _, peak = plans_for(cfg)
+    ctx = _ctx(cfg, up.export())
+    ctx.tio_params_load(params)
+    tr = ctx.tio_profile_iteration(tok, lab, tio.PROFILE_MEASURED).export()
+    ref = lt.export()
+    for key in ("op", "operand_off", "operand_tensor", "operand_flags", "tensor_bytes", "tensor_kind"):
+        assert np.array_equal(tr[key], ref[key]), key
+    assert tr["tau"].min() > 0 and tr["tau"].sum() < 10**9
+    # a plan built from measured times runs and still matches the uncapped numerics
+    ctx.tio_params_load(params)
+    l0 = [ctx.tio_train_step(tok, lab, None)["loss"] for _ in range(2)]
+    lt.set_tau(tr["tau"])
+    cap = int(peak * 0.5) // 256 * 256
+    cp = tio.tio_build_plan(lt, ll, cap, 25 * 10**9, arena_bytes=up.export()["arena_needed"])
+    ctx2 = tio.tio_ctx_create(cfg, up.export()["arena_needed"], cp.export()["host_needed"] + (1 << 20), 0)
+    ctx2.tio_params_load(params)
+    l1 = [ctx2.tio_train_step(tok, lab, cp)["loss"] for _ in range(2)]
+    assert l0 == l1
+    ctx.close(); ctx2.close()
+
+
+def test_errors_are_reported_not_faulted():
+    import paper_2506_06472_amd as tio
+    cfg = CONFIGS["tiny_gpt_fp32"]
+    params, tok, lab = make_inputs(cfg, seed=0)
+    lt, ll, up, cp, peak = plans_for(cfg, 0.5)
+    ctx = tio.tio_ctx_create(cfg, cp.export()["cap"], cp.export()["host_needed"] + (1 << 20), 0)
+    ctx.tio_params_load(params)
+    with pytest.raises(tio.TioError) as e:            # uncapped layout does not fit a capped arena
+        ctx.tio_train_step(tok, lab, None)
+    assert e.value.code == -7
+    bad = tok.copy(); bad[0, 0] = cfg["V"]
+    with pytest.raises(tio.TioError):
+        ctx.tio_train_step(bad, lab, cp)
+    other = tio.tio_trace_build(CONFIGS["tiny_llama_fp32"])
+    ol = tio.tio_analyze_lifetimes(other)
+    with pytest.raises(tio.TioError) as e:
+        ctx.tio_train_step(tok, lab, tio.tio_build_plan(other, ol, 2**62, 0))
+    assert e.value.code == -5
+    assert ctx.tio_train_step(tok, lab, cp)["loss"] > 0
+    ctx.close()
