@@ -1,0 +1,177 @@
+#!/usr/bin/env python3
+"""Benchmark of the capped-memory training step on one MI355X.
+
+Workload: GPT-2-small-shaped decoder, bf16 mixed precision with fp32 master weights and AdamW,
+12 layers, d=768, seq 1024, batch 8 (8192 tokens per step), memory cap = 40 % of the uncapped
+peak, synthetic seeded weights and tokens.  One step = forward, backward, AdamW under the plan,
+with the slow tier (pinned host memory) paced to --bw bytes/s per direction.
+
+Prints one JSON line: tokens/s under the cap (value), the uncapped ideal and the migration bound
+beside it, the MFMA roofline of the GEMM kernel measured with HIP events in the timed region, and
+the CPU oracle timed on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+GEMM_OPS = (2, 9, 10)          # forward, dX, dW contractions (one kernel template)
+ATTN_OPS = (4, 17)
+PEAK_BF16_TFLOPS = 2500.0
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="gpt2_small_bf16")
+    ap.add_argument("--bw", type=float, default=25e9, help="slow-tier bytes/s per direction; 0 = unthrottled")
+    ap.add_argument("--min-bytes", type=int, default=1 << 20)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--modelled-tau", action="store_true", help="plan from modelled instead of measured kernel times")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2506_06472_amd as tio
+    from synth import CONFIGS, gen_params, gen_tokens, to_bf16_round
+
+    cfg = CONFIGS[args.workload]
+    log = lambda *a: print(*a, file=sys.stderr, flush=True)
+    bw = int(args.bw)
+    S = cfg["B"] * cfg["T"]
+    plist = tio.tio_param_list(cfg)
+    specs = [(n, (r, c) if r > 1 else (c,), "normal" if (r > 1) else ("ones" if n.endswith("_g") else "zeros"))
+             for n, r, c in plist]
+    params = gen_params(specs, 0)
+    if cfg["precision"] == "bf16":
+        params = {k: to_bf16_round(v) for k, v in params.items()}
+    tok, lab = gen_tokens(cfg["B"], cfg["T"], cfg["V"], 0)
+
+    # ---- profile on the uncapped layout, measure the ideal
+    lt = tio.tio_trace_build(cfg)
+    ll = tio.tio_analyze_lifetimes(lt)
+    M = ll.export()["M"]
+    peak = int(M.max())
+    cap = int(cfg["cap_bytes"]) if "cap_bytes" in cfg else int(peak * cfg["cap_frac"]) // 256 * 256
+    up = tio.tio_build_plan(lt, ll, 2**62, 0)
+    upe = up.export()
+    ctx = tio.tio_ctx_create(cfg, upe["arena_needed"], upe["host_needed"] + (1 << 20), 0)
+    ctx.tio_params_load(params)
+    log('profiling on the uncapped layout: arena', upe['arena_needed'])
+    measured = ctx.tio_profile_iteration(tok, lab, tio.PROFILE_MEASURED)
+    tau = measured.export()["tau"]
+    log('sum of kernel times ms', tau.sum() / 1e6)
+    for _ in range(args.warmup):
+        ctx.tio_train_step(tok, lab, None)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        ctx.tio_train_step(tok, lab, None)
+    torch.cuda.synchronize()
+    ideal_s = (time.perf_counter() - t0) / args.steps
+    ctx.close()
+    del ctx
+    torch.cuda.empty_cache()
+
+    # ---- plan under the cap
+    if not args.modelled_tau:
+        lt.set_tau(tau)
+    tp0 = time.perf_counter()
+    plan = tio.tio_build_plan(lt, ll, cap, bw, min_bytes=args.min_bytes)
+    plan_s = time.perf_counter() - tp0
+    pe = plan.export()
+    log('ideal ms', ideal_s * 1e3, 'plan: entries', len(pe['entries']), 'moved GB', pe['bytes_per_direction'] / 1e9, 'planner s', plan_s)
+
+    # ---- capped run
+    ctx = tio.tio_ctx_create(cfg, cap, pe["host_needed"] + (1 << 20), bw)
+    ctx.tio_params_load(params)
+    for _ in range(args.warmup):
+        ctx.tio_train_step(tok, lab, plan)
+    torch.cuda.synchronize()
+    N = len(M)
+    ops = lt.export()["op"]
+    flops = lt.export()["flops"].astype(np.float64)
+    ktimes = np.zeros(N, dtype=np.float64)
+    d2h = h2d = 0
+    loss = None
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        st = ctx.tio_train_step(tok, lab, plan, time_kernels=True)
+        ktimes += ctx.tio_kernel_times(N)
+        d2h += st["d2h_bytes"]
+        h2d += st["h2d_bytes"]
+        loss = st["loss"]
+    torch.cuda.synchronize()
+    step_s = (time.perf_counter() - t0) / args.steps
+    ctx.close()
+    ktimes /= args.steps
+
+    gemm = np.isin(ops, GEMM_OPS)
+    attn = np.isin(ops, ATTN_OPS)
+    gemm_ns, gemm_flops, n_gemm = ktimes[gemm].sum(), flops[gemm].sum(), int(gemm.sum())
+    gemm_tflops = gemm_flops / gemm_ns / 1e3
+    attn_tflops = flops[attn].sum() / ktimes[attn].sum() / 1e3
+    comp_s = ktimes.sum() / 1e9
+    mig_bound_s = (pe["bytes_per_direction"] / bw) if bw else 0.0
+    bound_s = max(ideal_s, mig_bound_s)
+
+    out = {
+        "metric": "train tokens/s on 1 MI355X under GPU-mem cap", "value": S / step_s, "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": step_s * 1e3,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": cfg["precision"],
+        "data": "synthetic",
+        "config": {"workload": args.workload, "tokens_per_step": S, "mem_cap_bytes": cap, "uncapped_peak_bytes": peak,
+                   "cap_frac_of_peak": cap / peak, "slow_tier_bw_bytes_per_s": bw, "min_bytes": args.min_bytes,
+                   "kernel_times": "modelled" if args.modelled_tau else "measured"},
+        "ideal_tokens_per_s": S / ideal_s, "ideal_ms_per_step": ideal_s * 1e3,
+        "frac_of_ideal": ideal_s / step_s,
+        "migration_bound_ms": mig_bound_s * 1e3, "frac_of_min_ideal_migration_bound": bound_s / step_s,
+        "plan": {"entries": len(pe["entries"]), "greedy_pairs": pe["n_greedy"], "urgent_pairs": pe["n_forced"],
+                 "bytes_per_direction": pe["bytes_per_direction"], "planning_cap_bytes": pe["planning_cap"],
+                 "arena_bytes_needed": pe["arena_needed"], "planner_seconds": plan_s},
+        "copy": {"d2h_GBps": d2h / args.steps / step_s / 1e9, "h2d_GBps": h2d / args.steps / step_s / 1e9,
+                 "cap_GBps": bw / 1e9},
+        "kernel_ms_per_step": comp_s * 1e3, "overlap": 1.0 - max(0.0, step_s - comp_s) / step_s,
+        "attention_tflops": attn_tflops, "loss": loss,
+        "roofline": {"bound": "mfma", "kernel": "gemm_bf16_k (forward, dX and dW contractions)",
+                     "achieved": gemm_tflops, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                     "frac": gemm_tflops / PEAK_BF16_TFLOPS, "traffic": None,
+                     "launches_per_step": n_gemm, "avg_launch_us": gemm_ns / n_gemm / 1e3,
+                     "flops_per_step": gemm_flops},
+    }
+
+    log('capped ms/step', step_s * 1e3, 'loss', loss)
+    if not args.no_cpu_baseline:
+        from oracle import model as om
+        sample = dict(cfg, B=1)
+        stok, slab = tok[:1], lab[:1]
+        tr = om.Trainer(sample, params, dtype=np.float64)
+        tc = time.perf_counter()
+        tr.step(stok, slab)
+        cpu_s = time.perf_counter() - tc
+        try:
+            from threadpoolctl import threadpool_info
+            cores = max([p.get("num_threads", 1) for p in threadpool_info() if p.get("user_api") == "blas"] or [1])
+        except Exception:
+            cores = len(os.sched_getaffinity(0))
+        out["cpu_baseline"] = {"value": cfg["T"] / cpu_s, "unit": "tokens/s", "cores": cores,
+                               "kind": "oracle",
+                               "sample": f"one full step (forward, backward, AdamW, fp64 numpy) of the same model on 1 of the "
+                                         f"{cfg['B']} sequences ({cfg['T']} tokens), {cpu_s:.1f} s"}
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

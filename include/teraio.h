@@ -185,16 +185,23 @@ int tio_params_load(tio_ctx *ctx, int32_t index, const float *host_values, int64
 /* which: 0 compute weight, 1 master copy (bf16 mode only), 2 first moment, 3 second moment;
  * values are returned as fp32 wherever the tensor currently lives (GPU or slow tier). */
 int tio_params_read(tio_ctx *ctx, int32_t index, int32_t which, float *host_dst, int64_t numel);
-/* Gradient of parameter `index` as captured during the last step run with capture_grads != 0. */
+/* Gradient of parameter `index` as captured during the last step run with TIO_STEP_CAPTURE_GRADS. */
 int tio_grads_read(tio_ctx *ctx, int32_t index, float *host_dst, int64_t numel);
 /* Bandwidth enforced on the copy streams from the next step on (0 = unthrottled). */
 int tio_set_slow_tier_bw(tio_ctx *ctx, uint64_t bytes_per_s);
 
 /* One training iteration: forward, backward, AdamW, with the plan's migrations on the copy
  * streams.  plan == NULL runs the uncapped layout with no migration.  tokens/labels: host int32.
+ * flags: TIO_STEP_CAPTURE_GRADS keeps a host copy of every parameter gradient (debug: it
+ * synchronises before each optimizer launch); TIO_STEP_TIME_KERNELS brackets every launch with HIP
+ * events on the compute stream (see tio_kernel_times).
  * Blocks until the compute stream has finished the iteration (copies may still be in flight). */
+enum { TIO_STEP_CAPTURE_GRADS = 1, TIO_STEP_TIME_KERNELS = 2 };
 int tio_train_step(tio_ctx *ctx, const int32_t *tokens, const int32_t *labels,
-                   const tio_plan *plan, int32_t capture_grads, tio_step_stats *out);
+                   const tio_plan *plan, int32_t flags, tio_step_stats *out);
+/* Per-launch durations (ns, HIP events) of the last step run with TIO_STEP_TIME_KERNELS;
+ * n must equal the kernel count of the trace. */
+int tio_kernel_times(tio_ctx *ctx, int64_t *out_ns, int32_t n);
 
 /* ---- single operators on caller-provided device buffers (kernel parity tests, benchmarks) ---- */
 /* C[M,N] = A . B^T (+ bias[N]) (+ resid[M,N]); a_kmajor/b_kmajor: operand stored [K, rows]

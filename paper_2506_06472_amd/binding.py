@@ -307,13 +307,19 @@ class Context:
     def tio_set_slow_tier_bw(self, bw: int):
         _check(lib().tio_set_slow_tier_bw(self.h, C.c_uint64(int(bw))))
 
-    def tio_train_step(self, tokens, labels, plan: Plan | None = None, capture_grads=False):
+    def tio_train_step(self, tokens, labels, plan: Plan | None = None, capture_grads=False, time_kernels=False):
         t = np.ascontiguousarray(tokens, dtype=np.int32)
         l = np.ascontiguousarray(labels, dtype=np.int32)
         st = StepStats()
+        flags = (1 if capture_grads else 0) | (2 if time_kernels else 0)
         _check(lib().tio_train_step(self.h, t.ctypes.data_as(C.POINTER(C.c_int32)), l.ctypes.data_as(C.POINTER(C.c_int32)),
-                                    plan.h if plan is not None else None, 1 if capture_grads else 0, C.byref(st)))
+                                    plan.h if plan is not None else None, flags, C.byref(st)))
         return {f: getattr(st, f) for f, _ in StepStats._fields_}
+
+    def tio_kernel_times(self, n_kernels: int):
+        out = np.empty(n_kernels, dtype=np.int64)
+        _check(lib().tio_kernel_times(self.h, out.ctypes.data_as(C.POINTER(C.c_int64)), n_kernels))
+        return out
 
     def tio_profile_iteration(self, tokens, labels, mode=PROFILE_MEASURED) -> Trace:
         t = np.ascontiguousarray(tokens, dtype=np.int32)

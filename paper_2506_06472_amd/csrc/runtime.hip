@@ -75,6 +75,7 @@ struct tio_ctx {
     int step = 0;
     float *loss_pinned = nullptr;                         // 4 KiB of pinned host memory owned by the context
     std::vector<std::vector<float>> grads;
+    std::vector<int64_t> last_times;                      // per-kernel ns of the last step run with timing
     Plan uncapped;
     bool have_uncapped = false;
 };
@@ -445,14 +446,21 @@ int tio_set_slow_tier_bw(tio_ctx *c, uint64_t bw) {
     return TIO_OK;
 }
 
-int tio_train_step(tio_ctx *c, const int32_t *tokens, const int32_t *labels, const tio_plan *plan, int32_t capture,
+int tio_train_step(tio_ctx *c, const int32_t *tokens, const int32_t *labels, const tio_plan *plan, int32_t flags,
                    tio_step_stats *out) {
     if (!c || !tokens || !labels) return fail(TIO_ERR_INVALID_ARG, "null argument");
     TIO_RT_BEGIN
     ensure_plan(c, plan);
-    run_step(c, tokens, labels, capture != 0, nullptr, out);
+    run_step(c, tokens, labels, (flags & TIO_STEP_CAPTURE_GRADS) != 0, (flags & TIO_STEP_TIME_KERNELS) ? &c->last_times : nullptr, out);
     return TIO_OK;
     TIO_RT_END
+}
+
+int tio_kernel_times(tio_ctx *c, int64_t *out_ns, int32_t n) {
+    if (!c || !out_ns) return fail(TIO_ERR_INVALID_ARG, "null argument");
+    if (n != (int32_t)c->last_times.size()) return fail(TIO_ERR_INVALID_ARG, "no timed step, or wrong kernel count");
+    std::memcpy(out_ns, c->last_times.data(), (size_t)n * 8);
+    return TIO_OK;
 }
 
 int tio_profile_iteration(tio_ctx *c, const int32_t *tokens, const int32_t *labels, int mode, tio_trace **out) {
