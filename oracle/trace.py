@@ -182,10 +182,11 @@ def build_trace(cfg):
         grd(p + "dact", S * f)
         b.kernel(GEMM_DX, reads=[dx, w2], writes=[p + "dact"], flops=2 * S * d * f)
         pgrad(w2)
-        b.kernel(GEMM_DW, reads=[dx, p + "act"], writes=["g." + w2], flops=2 * S * d * f)
         if gpt:
             pgrad(p + "b_fc2")
-            b.kernel(BIAS_GRAD, reads=[dx], writes=["g." + p + "b_fc2"])
+        b.kernel(GEMM_DW, reads=[dx, p + "act"], writes=["g." + w2] + (["g." + p + "b_fc2"] if gpt else []),
+                 flops=2 * S * d * f)
+        if gpt:
             b.kernel(GELU_BWD, reads=[p + "u"], inouts=[p + "dact"])
             du = p + "dact"
         else:
@@ -195,18 +196,18 @@ def build_trace(cfg):
         grd(p + "dh2", S * d)
         b.kernel(GEMM_DX, reads=[du, w1], writes=[p + "dh2"], flops=2 * S * f1 * d)
         pgrad(w1)
-        b.kernel(GEMM_DW, reads=[du, p + "h2"], writes=["g." + w1], flops=2 * S * f1 * d)
         if gpt:
             pgrad(p + "b_fc1")
-            b.kernel(BIAS_GRAD, reads=[du], writes=["g." + p + "b_fc1"])
+        b.kernel(GEMM_DW, reads=[du, p + "h2"], writes=["g." + w1] + (["g." + p + "b_fc1"] if gpt else []),
+                 flops=2 * S * f1 * d)
         norm_bwd(p + "dh2", p + "xm", p + "st2", norm_p(p, nk + "2"), dx, p + "dxm", p + "part2")
         grd(p + "dao", S * d)
         b.kernel(GEMM_DX, reads=[p + "dxm", p + "w_o"], writes=[p + "dao"], flops=2 * S * d * d)
         pgrad(p + "w_o")
-        b.kernel(GEMM_DW, reads=[p + "dxm", p + "ao"], writes=["g." + p + "w_o"], flops=2 * S * d * d)
         if gpt:
             pgrad(p + "b_o")
-            b.kernel(BIAS_GRAD, reads=[p + "dxm"], writes=["g." + p + "b_o"])
+        b.kernel(GEMM_DW, reads=[p + "dxm", p + "ao"], writes=["g." + p + "w_o"] + (["g." + p + "b_o"] if gpt else []),
+                 flops=2 * S * d * d)
         grd(p + "delta", B * H * T, 4)
         b.kernel(ATTN_BWD_PRE, reads=[p + "dao", p + "ao"], writes=[p + "delta"])
         grd(p + "dqkv", S * 3 * d)
@@ -217,10 +218,10 @@ def build_trace(cfg):
         grd(p + "dh1", S * d)
         b.kernel(GEMM_DX, reads=[p + "dqkv", p + "w_qkv"], writes=[p + "dh1"], flops=2 * S * 3 * d * d)
         pgrad(p + "w_qkv")
-        b.kernel(GEMM_DW, reads=[p + "dqkv", p + "h1"], writes=["g." + p + "w_qkv"], flops=2 * S * 3 * d * d)
         if gpt:
             pgrad(p + "b_qkv")
-            b.kernel(BIAS_GRAD, reads=[p + "dqkv"], writes=["g." + p + "b_qkv"])
+        b.kernel(GEMM_DW, reads=[p + "dqkv", p + "h1"], writes=["g." + p + "w_qkv"] + (["g." + p + "b_qkv"] if gpt else []),
+                 flops=2 * S * 3 * d * d)
         norm_bwd(p + "dh1", xin, p + "st1", norm_p(p, nk + "1"), p + "dxm", p + "dx", p + "part1")
         dx = p + "dx"
     pgrad("wte")

@@ -213,19 +213,31 @@ __global__ void __launch_bounds__(TPB) norm_bwd_k(const T *__restrict__ dy, cons
     for (int64_t i = threadIdx.x; i < NP * d; i += TPB) p[i] = acc[i];
 }
 
+// column sums of the per-workgroup partial rows: 32 columns x 8 row groups per workgroup, each
+// thread adds its rows in order and the eight groups are combined in order
 template <typename T, bool RMS>
 __global__ void __launch_bounds__(TPB) norm_bwd_params_k(const float *__restrict__ part, T *__restrict__ dg,
                                                          T *__restrict__ db, int64_t nb, int64_t d) {
     constexpr int NP = RMS ? 1 : 2;
-    const int64_t col = (int64_t)blockIdx.x * TPB + threadIdx.x;
-    if (col >= d) return;
+    __shared__ float red[2][8][33];
+    const int c = threadIdx.x & 31, rg = threadIdx.x >> 5;
+    const int64_t col = (int64_t)blockIdx.x * 32 + c;
     float sg = 0.f, sb = 0.f;
-    for (int64_t b = 0; b < nb; ++b) {
-        sg += part[b * NP * d + col];
-        if (!RMS) sb += part[b * NP * d + d + col];
+    if (col < d)
+        for (int64_t b = rg; b < nb; b += 8) {
+            sg += part[b * NP * d + col];
+            if (!RMS) sb += part[b * NP * d + d + col];
+        }
+    red[0][rg][c] = sg;
+    red[1][rg][c] = sb;
+    __syncthreads();
+    if (rg == 0 && col < d) {
+        float tg = 0.f, tb = 0.f;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) { tg += red[0][i][c]; tb += red[1][i][c]; }
+        dg[col] = from_f32<T>(tg);
+        if (!RMS) db[col] = from_f32<T>(tb);
     }
-    dg[col] = from_f32<T>(sg);
-    if (!RMS) db[col] = from_f32<T>(sb);
 }
 
 // ---------------------------------------------------------------- activations
@@ -520,8 +532,8 @@ void norm_bwd(hipStream_t s, int dtype, bool rms, const void *dy, const void *x,
 
 void norm_bwd_params(hipStream_t s, int dtype, bool rms, const float *part, void *dg, void *db, int64_t nb, int64_t d) {
     TIO_DISPATCH(dtype, {
-        if (rms) norm_bwd_params_k<T, true><<<blocks_for(d, TPB), TPB, 0, s>>>(part, (T *)dg, nullptr, nb, d);
-        else norm_bwd_params_k<T, false><<<blocks_for(d, TPB), TPB, 0, s>>>(part, (T *)dg, (T *)db, nb, d);
+        if (rms) norm_bwd_params_k<T, true><<<blocks_for(d, 32), TPB, 0, s>>>(part, (T *)dg, nullptr, nb, d);
+        else norm_bwd_params_k<T, false><<<blocks_for(d, 32), TPB, 0, s>>>(part, (T *)dg, (T *)db, nb, d);
     });
 }
 

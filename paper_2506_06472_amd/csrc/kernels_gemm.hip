@@ -117,8 +117,11 @@ template <int BM, int BN, int BK, int WGM, int WGN, bool AKM, bool BKM>
 __global__ void __launch_bounds__(WGM *WGN * 64)
     gemm_bf16_k(const uint16_t *__restrict__ A, int64_t lda, const uint16_t *__restrict__ B, int64_t ldb,
                 const uint16_t *__restrict__ bias, const uint16_t *__restrict__ resid, int64_t ldr,
-                uint16_t *__restrict__ C, int64_t ldc, int64_t M, int64_t N, int64_t K, int tiles_m, int tiles_n) {
+                uint16_t *__restrict__ C, int64_t ldc, int64_t M, int64_t N, int64_t K, int tiles_m, int tiles_n,
+                uint16_t *__restrict__ rowsum) {
     constexpr int NT = WGM * WGN * 64;
+    constexpr int TPR = NT / BM;           // threads that share one row of the A tile for the row sums
+    static_assert(NT % BM == 0 && (TPR & (TPR - 1)) == 0 && TPR <= 64 && BK % (8 * TPR) == 0, "row-sum mapping");
     constexpr int WM = BM / WGM, WN = BN / WGN, TM = WM / 32, TN = WN / 32;
     constexpr int LS = BK + LDS_PAD;
     __shared__ __attribute__((aligned(16))) uint16_t As[BM * LS];
@@ -157,10 +160,24 @@ __global__ void __launch_bounds__(WGM *WGN * 64)
     sa.store(As, tid);
     sb.store(Bs, tid);
     __syncthreads();
+    // optional fused row sums of A over the whole contraction (the bias gradient when A = dY^T):
+    // done by the workgroups of the first tile column, TPR threads per row, in k order
+    const bool do_rowsum = rowsum != nullptr && tn == 0;
+    float rsum = 0.f;
     for (int kt = 0; kt < nk; ++kt) {
         if (kt + 1 < nk) {
             sa.load(A, lda, m0, M, (int64_t)(kt + 1) * BK, K, tid);
             sb.load(B, ldb, n0, N, (int64_t)(kt + 1) * BK, K, tid);
+        }
+        if (do_rowsum) {
+            const uint16_t *row = As + (tid / TPR) * LS + (tid % TPR) * (BK / TPR);
+#pragma unroll
+            for (int c = 0; c < BK / TPR; c += 8) {
+                const uint4 v = *reinterpret_cast<const uint4 *>(row + c);
+                const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+                for (int e = 0; e < 4; ++e) rsum += __uint_as_float(w[e] << 16) + __uint_as_float(w[e] & 0xffff0000u);
+            }
         }
 #pragma unroll
         for (int ks = 0; ks < BK / 16; ++ks) {
@@ -186,6 +203,12 @@ __global__ void __launch_bounds__(WGM *WGN * 64)
         }
     }
 
+    if (do_rowsum) {
+#pragma unroll
+        for (int o = 1; o < TPR; o <<= 1) rsum += __shfl_xor(rsum, o, 64);
+        const int64_t m = m0 + tid / TPR;
+        if (tid % TPR == 0 && m < M) rowsum[m] = (uint16_t)f32_to_bf16_bits(rsum);
+    }
     // epilogue: lane holds C[m][n .. n+3] for 4 groups of columns per 32x32 tile
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
@@ -231,7 +254,8 @@ template <bool AKM, bool BKM>
 __global__ void __launch_bounds__(256) gemm_f32_k(const float *__restrict__ A, int64_t lda, const float *__restrict__ B,
                                                   int64_t ldb, const float *__restrict__ bias,
                                                   const float *__restrict__ resid, int64_t ldr, float *__restrict__ C,
-                                                  int64_t ldc, int64_t M, int64_t N, int64_t K) {
+                                                  int64_t ldc, int64_t M, int64_t N, int64_t K,
+                                                  float *__restrict__ rowsum) {
     constexpr int BT = 64, BKK = 16;
     __shared__ float As[BKK][BT + 1];
     __shared__ float Bs[BKK][BT + 1];
@@ -239,6 +263,8 @@ __global__ void __launch_bounds__(256) gemm_f32_k(const float *__restrict__ A, i
     const int64_t m0 = (int64_t)blockIdx.y * BT, n0 = (int64_t)blockIdx.x * BT;
     const int ty = tid / 16, tx = tid % 16;             // thread computes rows ty*4.., cols tx*4..
     float acc[4][4] = {};
+    float rsum = 0.f;                                     // fused row sums of A (first tile column, thread = row)
+    const bool do_rowsum = rowsum != nullptr && blockIdx.x == 0 && tid < BT;
     for (int64_t k0 = 0; k0 < K; k0 += BKK) {
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
@@ -252,6 +278,9 @@ __global__ void __launch_bounds__(256) gemm_f32_k(const float *__restrict__ A, i
             Bs[kk][r] = (gn < N && gkb < K) ? (BKM ? B[gkb * ldb + gn] : B[gn * ldb + gkb]) : 0.f;
         }
         __syncthreads();
+        if (do_rowsum)
+#pragma unroll
+            for (int kk = 0; kk < BKK; ++kk) rsum += As[kk][tid];
 #pragma unroll
         for (int kk = 0; kk < BKK; ++kk) {
             float a[4], b[4];
@@ -264,6 +293,7 @@ __global__ void __launch_bounds__(256) gemm_f32_k(const float *__restrict__ A, i
         }
         __syncthreads();
     }
+    if (do_rowsum && m0 + tid < M) rowsum[m0 + tid] = rsum;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         const int64_t m = m0 + ty * 4 + i;
@@ -284,12 +314,13 @@ __global__ void __launch_bounds__(256) gemm_f32_k(const float *__restrict__ A, i
 
 template <int BM, int BN, int BK, int WGM, int WGN>
 static void launch_bf16(hipStream_t s, bool a_km, bool b_km, int64_t M, int64_t N, int64_t K, const void *A, int64_t lda,
-                        const void *B, int64_t ldb, const void *bias, const void *resid, int64_t ldr, void *C, int64_t ldc) {
+                        const void *B, int64_t ldb, const void *bias, const void *resid, int64_t ldr, void *C, int64_t ldc,
+                        void *rowsum) {
     const int tiles_m = (int)((M + BM - 1) / BM), tiles_n = (int)((N + BN - 1) / BN);
     const dim3 grid((unsigned)(tiles_m * tiles_n));
     const dim3 block(WGM * WGN * 64);
 #define TIO_GEMM_ARGS (const uint16_t *)A, lda, (const uint16_t *)B, ldb, (const uint16_t *)bias, (const uint16_t *)resid, ldr, \
-                      (uint16_t *)C, ldc, M, N, K, tiles_m, tiles_n
+                      (uint16_t *)C, ldc, M, N, K, tiles_m, tiles_n, (uint16_t *)rowsum
     if (!a_km && !b_km) gemm_bf16_k<BM, BN, BK, WGM, WGN, false, false><<<grid, block, 0, s>>>(TIO_GEMM_ARGS);
     else if (!a_km && b_km) gemm_bf16_k<BM, BN, BK, WGM, WGN, false, true><<<grid, block, 0, s>>>(TIO_GEMM_ARGS);
     else if (a_km && b_km) gemm_bf16_k<BM, BN, BK, WGM, WGN, true, true><<<grid, block, 0, s>>>(TIO_GEMM_ARGS);
@@ -298,13 +329,14 @@ static void launch_bf16(hipStream_t s, bool a_km, bool b_km, int64_t M, int64_t 
 }
 
 void gemm(hipStream_t s, int dtype, bool a_km, bool b_km, int64_t M, int64_t N, int64_t K, const void *A, int64_t lda,
-          const void *B, int64_t ldb, const void *bias, const void *resid, int64_t ldr, void *C, int64_t ldc) {
+          const void *B, int64_t ldb, const void *bias, const void *resid, int64_t ldr, void *C, int64_t ldc,
+          void *rowsum) {
     if (M <= 0 || N <= 0 || K <= 0) return;
     if (dtype == TIO_PREC_BF16) {
-        launch_bf16<128, 128, 64, 2, 2>(s, a_km, b_km, M, N, K, A, lda, B, ldb, bias, resid, ldr, C, ldc);
+        launch_bf16<128, 128, 64, 2, 2>(s, a_km, b_km, M, N, K, A, lda, B, ldb, bias, resid, ldr, C, ldc, rowsum);
     } else {
         const dim3 grid((unsigned)((N + 63) / 64), (unsigned)((M + 63) / 64));
-#define TIO_GEMM_ARGS (const float *)A, lda, (const float *)B, ldb, (const float *)bias, (const float *)resid, ldr, (float *)C, ldc, M, N, K
+#define TIO_GEMM_ARGS (const float *)A, lda, (const float *)B, ldb, (const float *)bias, (const float *)resid, ldr, (float *)C, ldc, M, N, K, (float *)rowsum
         if (!a_km && !b_km) gemm_f32_k<false, false><<<grid, 256, 0, s>>>(TIO_GEMM_ARGS);
         else if (!a_km && b_km) gemm_f32_k<false, true><<<grid, 256, 0, s>>>(TIO_GEMM_ARGS);
         else if (a_km && b_km) gemm_f32_k<true, true><<<grid, 256, 0, s>>>(TIO_GEMM_ARGS);

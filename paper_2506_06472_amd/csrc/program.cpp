@@ -221,18 +221,15 @@ Program build_program(const tio_model_cfg &c) {
         k.p[0] = S; k.p[1] = n_in; k.p[2] = n_out; k.p[3] = ld_dy;
         k.flops = 2 * S * n_in * n_out;
     };
-    auto gemm_dw = [&](int dY, int X, ParamInfo &Wt, int64_t n_in, int64_t n_out, int64_t ld_dy) {
+    // the bias gradient (column sums of dY) is produced by the same launch as the weight gradient
+    auto gemm_dw = [&](int dY, int X, ParamInfo &Wt, ParamInfo *bias, int64_t n_in, int64_t n_out, int64_t ld_dy) {
         pgrad(Wt);
+        if (bias) pgrad(*bias);
         KernelRec &k = b.kernel(OP_GEMM_DW);
         set(k, 0, dY, R); set(k, 1, X, R); set(k, 2, Wt.grad, W);
+        if (bias) set(k, 3, bias->grad, W);
         k.p[0] = n_out; k.p[1] = n_in; k.p[2] = S; k.p[3] = ld_dy;
         k.flops = 2 * S * n_in * n_out;
-    };
-    auto bias_grad = [&](int dY, ParamInfo &bp, int64_t n) {
-        pgrad(bp);
-        KernelRec &k = b.kernel(OP_BIAS_GRAD);
-        set(k, 0, dY, R); set(k, 1, bp.grad, W);
-        k.p[0] = S; k.p[1] = n;
     };
     auto norm_bwd = [&](int dy, int xin, int st, ParamInfo &g, ParamInfo *bias, int dres, const std::string &dxn,
                         const std::string &pn) {
@@ -255,7 +252,7 @@ Program build_program(const tio_model_cfg &c) {
 
     int dhf = b.grd("dhf", S * d);
     gemm_dx(logits, head, dhf, d, V, Vp);
-    gemm_dw(logits, hf, head, d, V, Vp);
+    gemm_dw(logits, hf, head, nullptr, d, V, Vp);
     int dx = norm_bwd(dhf, x, stf, fin_g, fin_b, -1, "dxf", "partf");
     for (int i = (int)L - 1; i >= 0; --i) {
         std::string p = "l" + std::to_string(i) + ".";
@@ -265,10 +262,9 @@ Program build_program(const tio_model_cfg &c) {
         const int64_t f1 = gpt ? f : 2 * f;
         int dact = b.grd(p + "dact", S * f);
         gemm_dx(dx, w2, dact, f, d, d);
-        gemm_dw(dx, t.act, w2, f, d, d);
+        gemm_dw(dx, t.act, w2, gpt ? &LP(i, 11) : nullptr, f, d, d);
         int du;
         if (gpt) {
-            bias_grad(dx, LP(i, 11), d);
             KernelRec &k = b.kernel(OP_GELU_BWD);
             set(k, 0, dact, RW); set(k, 1, t.u, R);
             k.p[0] = S * f;
@@ -281,14 +277,12 @@ Program build_program(const tio_model_cfg &c) {
         }
         int dh2 = b.grd(p + "dh2", S * d);
         gemm_dx(du, w1, dh2, d, f1, f1);
-        gemm_dw(du, t.h2, w1, d, f1, f1);
-        if (gpt) bias_grad(du, LP(i, 9), f);
+        gemm_dw(du, t.h2, w1, gpt ? &LP(i, 9) : nullptr, d, f1, f1);
         int dxm = norm_bwd(dh2, t.xm, t.st2, LP(i, gpt ? 6 : 3), gpt ? &LP(i, 7) : nullptr, dx, p + "dxm", p + "part2");
         ParamInfo &wo = LP(i, gpt ? 4 : 2);
         int dao = b.grd(p + "dao", S * d);
         gemm_dx(dxm, wo, dao, d, d, d);
-        gemm_dw(dxm, t.ao, wo, d, d, d);
-        if (gpt) bias_grad(dxm, LP(i, 5), d);
+        gemm_dw(dxm, t.ao, wo, gpt ? &LP(i, 5) : nullptr, d, d, d);
         int delta = b.grd32(p + "delta", B * H * T);
         {
             KernelRec &k = b.kernel(OP_ATTN_BWD_PRE);
@@ -307,8 +301,7 @@ Program build_program(const tio_model_cfg &c) {
         ParamInfo &wqkv = LP(i, gpt ? 2 : 1);
         int dh1 = b.grd(p + "dh1", S * d);
         gemm_dx(dqkv, wqkv, dh1, d, 3 * d, 3 * d);
-        gemm_dw(dqkv, t.h1, wqkv, d, 3 * d, 3 * d);
-        if (gpt) bias_grad(dqkv, LP(i, 3), 3 * d);
+        gemm_dw(dqkv, t.h1, wqkv, gpt ? &LP(i, 3) : nullptr, d, 3 * d, 3 * d);
         dx = norm_bwd(dh1, t.x_in, t.st1, LP(i, 0), gpt ? &LP(i, 1) : nullptr, dxm, p + "dx", p + "part1");
     }
     {

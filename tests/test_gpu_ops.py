@@ -46,10 +46,12 @@ def test_gemm_all_layouts(dtype, a_km, b_km, M, N, K, pad):
     else: Bs[:, :K] = B
     dA, dB, dbias, dR = _dev(As, dtype), _dev(Bs, dtype), _dev(bias, dtype), _dev(R, dtype)
     dC = torch.full((M, ldc), 7.0, device="cuda", dtype=dA.dtype)
+    dsum = torch.full((r8(M) + 8,), 7.0, device="cuda", dtype=dA.dtype)
     torch.cuda.synchronize()
     for use_bias, use_res in ((0, 0), (1, 1)):
         tio.tio_op_gemm(0, dtype, a_km, b_km, M, N, K, dA.data_ptr(), lda, dB.data_ptr(), ldb,
-                        dbias.data_ptr() if use_bias else 0, dR.data_ptr() if use_res else 0, ldc, dC.data_ptr(), ldc)
+                        dbias.data_ptr() if use_bias else 0, dR.data_ptr() if use_res else 0, ldc, dC.data_ptr(), ldc,
+                        dsum.data_ptr() if use_res else 0)
         torch.cuda.synchronize()
         An = np.nan_to_num(_host(dA)); Bn = np.nan_to_num(_host(dB))
         A64 = An[:, :M].T if a_km else An[:, :K]
@@ -62,6 +64,13 @@ def test_gemm_all_layouts(dtype, a_km, b_km, M, N, K, pad):
         err = np.abs(got[:, :N] - ref)
         tol = (2.0 ** -8 * np.abs(ref) + 1e-3 * np.sqrt(K)) if dtype == "bf16" else (1e-5 * np.sqrt(K) * (1 + np.abs(ref)))
         assert np.all(err <= tol), (float(err.max()), np.unravel_index(err.argmax(), err.shape))
+        rs = _host(dsum)
+        if use_res:      # fused row sums of A (the bias gradient of a weight-gradient GEMM)
+            ref_rs = A64.sum(1)
+            rtol = (2.0 ** -8 * np.abs(ref_rs) + 1e-3 * np.sqrt(K)) if dtype == "bf16" else 1e-5 * np.sqrt(K) * (1 + np.abs(ref_rs))
+            assert np.all(np.abs(rs[:M] - ref_rs) <= rtol) and np.all(rs[M:] == 7.0)
+        else:
+            assert np.all(rs == 7.0)
 
 
 def test_gemm_rejects_bad_arguments():

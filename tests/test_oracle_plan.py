@@ -57,7 +57,7 @@ def test_trace_counts_and_persistent_bytes(name):
     tr = ot.build_trace(cfg)
     L = cfg["L"]
     N = len(tr["kernels"])
-    assert N == (39 * L + 16 if cfg["arch"] == "gpt" else 31 * L + 13)
+    assert N == (35 * L + 16 if cfg["arch"] == "gpt" else 31 * L + 13)
     bpp = 14 if cfg["precision"] == "bf16" else 12
     S = cfg["B"] * cfg["T"]
     pers = sum(t[0] for t in tr["tensors"][:tr["n_persistent"]])
@@ -96,12 +96,12 @@ def test_lifetimes_closed_form_on_the_layer_chain():
         t = tr["ids"][f"l{i}.act"]
         s = tr["tensors"][t][0]
         gelu = 1 + 8 * i + 6
-        assert life["active"][t] == [gelu, gelu + 1, bwd0 + 19 * (L - 1 - i) + 1]
-        assert (t, s, gelu + 1, bwd0 + 19 * (L - 1 - i) + 1) in life["periods"]
+        assert life["active"][t] == [gelu, gelu + 1, bwd0 + 15 * (L - 1 - i) + 1]
+        assert (t, s, gelu + 1, bwd0 + 15 * (L - 1 - i) + 1) in life["periods"]
         # x entering layer i: written by the previous kernel chain, read by ln1, the out-projection
         # residual and ln1's backward (the last kernel of the layer's backward)
         t = tr["ids"][f"l{i - 1}.xo" if i else "x0"]
-        assert life["active"][t][-1] == bwd0 + 19 * (L - 1 - i) + 17
+        assert life["active"][t][-1] == bwd0 + 15 * (L - 1 - i) + 13
     # optimizer moments are touched once per iteration: one wrap-around period of length N
     t = tr["ids"]["l0.w_fc1.m"]
     (k,) = life["active"][t]
