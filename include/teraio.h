@@ -208,11 +208,15 @@ int tio_kernel_times(tio_ctx *ctx, int64_t *out_ns, int32_t n);
  * instead of [rows, K].  dtype TIO_PREC_*.  All leading dimensions in elements, multiples of 8
  * and at least the 8-element padded extent; device pointers, 16-byte aligned; stream is a
  * hipStream_t (NULL = default stream).  rowsum (optional, device, [M] elements): receives
- * sum_k A[m][k] from the same launch (the bias gradient when A = dY^T). */
+ * sum_k A[m][k] from the same launch (the bias gradient when A = dY^T).
+ * splits > 1 (bf16, no bias/resid, N multiple of 4) cuts the contraction into `splits` ranges:
+ * workspace (device, fp32, splits*(M*N+M) floats) receives the partial tiles and a second launch
+ * adds them in range order; splits = 1 ignores workspace. */
 int tio_op_gemm(void *stream, int32_t dtype, int32_t a_kmajor, int32_t b_kmajor,
                 int64_t M, int64_t N, int64_t K,
                 const void *A, int64_t lda, const void *B, int64_t ldb,
-                const void *bias, const void *resid, int64_t ldr, void *C, int64_t ldc, void *rowsum);
+                const void *bias, const void *resid, int64_t ldr, void *C, int64_t ldc, void *rowsum,
+                void *workspace, int32_t splits);
 /* Timed repetitions of one operator on the given stream, HIP events around the launches;
  * returns average ns per launch.  op codes as in the trace; dims as documented per operator. */
 int tio_op_bench(tio_ctx *ctx, int32_t kernel_index, int32_t reps, double *out_avg_ns);

@@ -52,6 +52,16 @@ def _r256(n):
     return (n + 255) // 256 * 256
 
 
+def dw_splits(M, N, K):
+    """Contraction ranges of a bf16 weight-gradient GEMM dW[M,N] over K tokens: doubled (at most 8, at least
+    256 tokens per range) while fewer than about 512 workgroups of 128x128 output tiles would exist."""
+    tiles = ((M + 127) // 128) * ((N + 127) // 128)
+    s = 1
+    while s < 8 and tiles * s * 2 <= 512 and K // (s * 2) >= 256:
+        s *= 2
+    return s
+
+
 def vocab_ld(V):
     """Leading dimension of the logits matrix: vocabulary rounded up to 64 columns."""
     return (V + 63) // 64 * 64
@@ -167,10 +177,21 @@ def build_trace(cfg):
             pgrad(n)
         b.kernel(NORM_BWD_PARAMS, reads=[part], writes=["g." + n for n in pnames])
 
+    def gemm_dw(dy, xin, w, bias, n_out, n_in):
+        pgrad(w)
+        if bias:
+            pgrad(bias)
+        ws = []
+        splits = dw_splits(n_out, n_in, S) if bf16 else 1
+        if splits > 1:                                   # fp32 partial tiles and partial row sums
+            grd("ws." + w, splits * (n_out * n_in + n_out), 4)
+            ws = ["ws." + w]
+        b.kernel(GEMM_DW, reads=[dy, xin], writes=["g." + w] + (["g." + bias] if bias else []), inouts=ws,
+                 flops=2 * S * n_in * n_out)
+
     grd("dhf", S * d)
     b.kernel(GEMM_DX, reads=["logits", "w_head"], writes=["dhf"], flops=2 * S * V * d)
-    pgrad("w_head")
-    b.kernel(GEMM_DW, reads=["logits", "hf"], writes=["g.w_head"], flops=2 * S * V * d)
+    gemm_dw("logits", "hf", "w_head", None, V, d)
     norm_bwd("dhf", x, "stf", fin_p, None, "dxf", "partf")
     dx = "dxf"
     for i in reversed(range(L)):
@@ -181,11 +202,7 @@ def build_trace(cfg):
         f1 = f if gpt else 2 * f
         grd(p + "dact", S * f)
         b.kernel(GEMM_DX, reads=[dx, w2], writes=[p + "dact"], flops=2 * S * d * f)
-        pgrad(w2)
-        if gpt:
-            pgrad(p + "b_fc2")
-        b.kernel(GEMM_DW, reads=[dx, p + "act"], writes=["g." + w2] + (["g." + p + "b_fc2"] if gpt else []),
-                 flops=2 * S * d * f)
+        gemm_dw(dx, p + "act", w2, p + "b_fc2" if gpt else None, d, f)
         if gpt:
             b.kernel(GELU_BWD, reads=[p + "u"], inouts=[p + "dact"])
             du = p + "dact"
@@ -195,19 +212,11 @@ def build_trace(cfg):
             du = p + "du"
         grd(p + "dh2", S * d)
         b.kernel(GEMM_DX, reads=[du, w1], writes=[p + "dh2"], flops=2 * S * f1 * d)
-        pgrad(w1)
-        if gpt:
-            pgrad(p + "b_fc1")
-        b.kernel(GEMM_DW, reads=[du, p + "h2"], writes=["g." + w1] + (["g." + p + "b_fc1"] if gpt else []),
-                 flops=2 * S * f1 * d)
+        gemm_dw(du, p + "h2", w1, p + "b_fc1" if gpt else None, f1, d)
         norm_bwd(p + "dh2", p + "xm", p + "st2", norm_p(p, nk + "2"), dx, p + "dxm", p + "part2")
         grd(p + "dao", S * d)
         b.kernel(GEMM_DX, reads=[p + "dxm", p + "w_o"], writes=[p + "dao"], flops=2 * S * d * d)
-        pgrad(p + "w_o")
-        if gpt:
-            pgrad(p + "b_o")
-        b.kernel(GEMM_DW, reads=[p + "dxm", p + "ao"], writes=["g." + p + "w_o"] + (["g." + p + "b_o"] if gpt else []),
-                 flops=2 * S * d * d)
+        gemm_dw(p + "dxm", p + "ao", p + "w_o", p + "b_o" if gpt else None, d, d)
         grd(p + "delta", B * H * T, 4)
         b.kernel(ATTN_BWD_PRE, reads=[p + "dao", p + "ao"], writes=[p + "delta"])
         grd(p + "dqkv", S * 3 * d)
@@ -217,11 +226,7 @@ def build_trace(cfg):
             b.kernel(ROPE_BWD, inouts=[p + "dqkv"])
         grd(p + "dh1", S * d)
         b.kernel(GEMM_DX, reads=[p + "dqkv", p + "w_qkv"], writes=[p + "dh1"], flops=2 * S * 3 * d * d)
-        pgrad(p + "w_qkv")
-        if gpt:
-            pgrad(p + "b_qkv")
-        b.kernel(GEMM_DW, reads=[p + "dqkv", p + "h1"], writes=["g." + p + "w_qkv"] + (["g." + p + "b_qkv"] if gpt else []),
-                 flops=2 * S * 3 * d * d)
+        gemm_dw(p + "dqkv", p + "h1", p + "w_qkv", p + "b_qkv" if gpt else None, 3 * d, d)
         norm_bwd(p + "dh1", xin, p + "st1", norm_p(p, nk + "1"), p + "dxm", p + "dx", p + "part1")
         dx = p + "dx"
     pgrad("wte")

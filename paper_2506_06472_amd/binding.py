@@ -340,9 +340,9 @@ def tio_ctx_create(cfg, arena_bytes, host_bytes, slow_tier_bw=0, single_copy_str
 
 
 def tio_op_gemm(stream_handle, dtype, a_kmajor, b_kmajor, M, N, K, A_ptr, lda, B_ptr, ldb, bias_ptr, resid_ptr, ldr,
-                C_ptr, ldc, rowsum_ptr=0):
+                C_ptr, ldc, rowsum_ptr=0, workspace_ptr=0, splits=1):
     """Raw pointers (ints) of device buffers; see include/teraio.h."""
     vp = lambda p: C.c_void_p(p) if p else None
     _check(lib().tio_op_gemm(vp(stream_handle), PREC[dtype], int(a_kmajor), int(b_kmajor), C.c_int64(M), C.c_int64(N),
                              C.c_int64(K), vp(A_ptr), C.c_int64(lda), vp(B_ptr), C.c_int64(ldb), vp(bias_ptr),
-                             vp(resid_ptr), C.c_int64(ldr), vp(C_ptr), C.c_int64(ldc), vp(rowsum_ptr)))
+                             vp(resid_ptr), C.c_int64(ldr), vp(C_ptr), C.c_int64(ldc), vp(rowsum_ptr), vp(workspace_ptr), int(splits)))

@@ -14,10 +14,13 @@ void embed_fwd(hipStream_t s, int dtype, const int32_t *tok, const void *wte, co
 void norm_fwd(hipStream_t s, int dtype, bool rms, const void *x, const void *g, const void *b, void *y,
               float *stats, int64_t S, int64_t d, float eps);
 // C[M,N] = A.B^T (+bias[N]) (+resid[M,N]); a_km / b_km: operand stored [K][rows] instead of [rows][K];
-// rowsum (optional, [M]): sum over k of A[m][k], produced by the same launch (bias gradient of dW)
+// rowsum (optional, [M]): sum over k of A[m][k], produced by the same launch (bias gradient of dW);
+// workspace/splits: with splits > 1 and an fp32 workspace of splits*(M*N+M) floats the contraction is
+// cut into `splits` ranges whose partial results are added in order by a second launch
 void gemm(hipStream_t s, int dtype, bool a_km, bool b_km, int64_t M, int64_t N, int64_t K, const void *A,
           int64_t lda, const void *B, int64_t ldb, const void *bias, const void *resid, int64_t ldr, void *C,
-          int64_t ldc, void *rowsum);
+          int64_t ldc, void *rowsum, void *workspace, int splits);
+
 void rope(hipStream_t s, int dtype, void *qkv, int64_t B, int64_t T, int64_t H, int64_t dh, float theta,
           bool inverse);
 void attn_fwd(hipStream_t s, int dtype, const void *qkv, void *o, float *lse, int64_t B, int64_t T, int64_t H,

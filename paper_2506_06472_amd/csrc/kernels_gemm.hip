@@ -71,14 +71,16 @@ template <int ROWS, int BK, int NT> struct Stage<ROWS, BK, NT, false> {
 
 // contraction index is the slow dimension: 8(k) x 8(rows) blocks, transposed in registers
 template <int ROWS, int BK, int NT> struct Stage<ROWS, BK, NT, true> {
-    static constexpr int RB = ROWS / 8, TOTAL = RB * (BK / 8), PER = (TOTAL + NT - 1) / NT;
+    // consecutive lanes take consecutive k-blocks of one row block: with the 144-byte LDS row pitch the
+    // sixteen 16-byte stores of a quarter wavefront then fall into sixteen different bank groups
+    static constexpr int RB = ROWS / 8, KB = BK / 8, TOTAL = RB * KB, PER = (TOTAL + NT - 1) / NT;
     uint4 r[PER][8];
     __device__ __forceinline__ void load(const uint16_t *__restrict__ base, int64_t ld, int64_t row0, int64_t rows,
                                          int64_t k0, int64_t K, int tid) {
 #pragma unroll
         for (int i = 0; i < PER; ++i) {
             const int c = tid + i * NT;
-            const int rb = c % RB, kb = c / RB;
+            const int kb = c % KB, rb = c / KB;
             const int64_t gr = row0 + rb * 8;
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
@@ -94,7 +96,7 @@ template <int ROWS, int BK, int NT> struct Stage<ROWS, BK, NT, true> {
         for (int i = 0; i < PER; ++i) {
             const int c = tid + i * NT;
             if (c < TOTAL) {
-                const int rb = c % RB, kb = c / RB;
+                const int kb = c % KB, rb = c / KB;
 #pragma unroll
                 for (int rr = 0; rr < 8; ++rr) {       // output row rr of the 8x8 block: k = 0..7
                     uint32_t w[4];
@@ -118,7 +120,7 @@ __global__ void __launch_bounds__(WGM *WGN * 64)
     gemm_bf16_k(const uint16_t *__restrict__ A, int64_t lda, const uint16_t *__restrict__ B, int64_t ldb,
                 const uint16_t *__restrict__ bias, const uint16_t *__restrict__ resid, int64_t ldr,
                 uint16_t *__restrict__ C, int64_t ldc, int64_t M, int64_t N, int64_t K, int tiles_m, int tiles_n,
-                uint16_t *__restrict__ rowsum) {
+                uint16_t *__restrict__ rowsum, float *__restrict__ ws, int64_t k_chunk) {
     constexpr int NT = WGM * WGN * 64;
     constexpr int TPR = NT / BM;           // threads that share one row of the A tile for the row sums
     static_assert(NT % BM == 0 && (TPR & (TPR - 1)) == 0 && TPR <= 64 && BK % (8 * TPR) == 0, "row-sum mapping");
@@ -154,9 +156,13 @@ __global__ void __launch_bounds__(WGM *WGN * 64)
 
     Stage<BM, BK, NT, AKM> sa;
     Stage<BN, BK, NT, BKM> sb;
-    const int nk = (int)((K + BK - 1) / BK);
-    sa.load(A, lda, m0, M, 0, K, tid);
-    sb.load(B, ldb, n0, N, 0, K, tid);
+    // split-K: workgroup row blockIdx.y owns the contraction range [kbeg, kend) and writes an fp32
+    // partial tile to the workspace; a second launch adds the partials in split order
+    const int64_t kbeg = (int64_t)blockIdx.y * k_chunk;
+    const int64_t kend = (ws != nullptr && kbeg + k_chunk < K) ? kbeg + k_chunk : K;
+    const int nk = (int)((kend - kbeg + BK - 1) / BK);
+    sa.load(A, lda, m0, M, kbeg, kend, tid);
+    sb.load(B, ldb, n0, N, kbeg, kend, tid);
     sa.store(As, tid);
     sb.store(Bs, tid);
     __syncthreads();
@@ -166,8 +172,8 @@ __global__ void __launch_bounds__(WGM *WGN * 64)
     float rsum = 0.f;
     for (int kt = 0; kt < nk; ++kt) {
         if (kt + 1 < nk) {
-            sa.load(A, lda, m0, M, (int64_t)(kt + 1) * BK, K, tid);
-            sb.load(B, ldb, n0, N, (int64_t)(kt + 1) * BK, K, tid);
+            sa.load(A, lda, m0, M, kbeg + (int64_t)(kt + 1) * BK, kend, tid);
+            sb.load(B, ldb, n0, N, kbeg + (int64_t)(kt + 1) * BK, kend, tid);
         }
         if (do_rowsum) {
             const uint16_t *row = As + (tid / TPR) * LS + (tid % TPR) * (BK / TPR);
@@ -207,7 +213,10 @@ __global__ void __launch_bounds__(WGM *WGN * 64)
 #pragma unroll
         for (int o = 1; o < TPR; o <<= 1) rsum += __shfl_xor(rsum, o, 64);
         const int64_t m = m0 + tid / TPR;
-        if (tid % TPR == 0 && m < M) rowsum[m] = (uint16_t)f32_to_bf16_bits(rsum);
+        if (tid % TPR == 0 && m < M) {
+            if (ws) ws[(int64_t)gridDim.y * M * N + (int64_t)blockIdx.y * M + m] = rsum;
+            else rowsum[m] = (uint16_t)f32_to_bf16_bits(rsum);
+        }
     }
     // epilogue: lane holds C[m][n .. n+3] for 4 groups of columns per 32x32 tile
 #pragma unroll
@@ -221,6 +230,10 @@ __global__ void __launch_bounds__(WGM *WGN * 64)
                 const int64_t n = n0 + wn * WN + j * 32 + q * 8 + lhi * 4;
                 if (n >= N) continue;
                 float v[4] = {acc[i][j][q * 4 + 0], acc[i][j][q * 4 + 1], acc[i][j][q * 4 + 2], acc[i][j][q * 4 + 3]};
+                if (ws) {          // N is a multiple of 4 in split mode
+                    *reinterpret_cast<float4 *>(ws + ((int64_t)blockIdx.y * M + m) * N + n) = make_float4(v[0], v[1], v[2], v[3]);
+                    continue;
+                }
                 if (n + 4 <= N) {
                     if (bias) {
                         const uint2 t = *reinterpret_cast<const uint2 *>(bias + n);
@@ -246,6 +259,31 @@ __global__ void __launch_bounds__(WGM *WGN * 64)
                 }
             }
         }
+    }
+}
+
+// adds the split-K partials in split order and rounds once; also finishes the fused row sums
+__global__ void __launch_bounds__(256) splitk_reduce_k(const float *__restrict__ ws, uint16_t *__restrict__ C, int64_t ldc,
+                                                       uint16_t *__restrict__ rowsum, int64_t M, int64_t N, int splits) {
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t nq = N / 4, total = M * nq;
+    if (idx < total) {
+        const int64_t m = idx / nq, n = (idx % nq) * 4;
+        float4 a = *reinterpret_cast<const float4 *>(ws + m * N + n);
+        for (int sp = 1; sp < splits; ++sp) {
+            const float4 b = *reinterpret_cast<const float4 *>(ws + ((int64_t)sp * M + m) * N + n);
+            a.x += b.x; a.y += b.y; a.z += b.z; a.w += b.w;
+        }
+        uint2 o;
+        o.x = f32_to_bf16_bits(a.x) | (f32_to_bf16_bits(a.y) << 16);
+        o.y = f32_to_bf16_bits(a.z) | (f32_to_bf16_bits(a.w) << 16);
+        *reinterpret_cast<uint2 *>(C + m * ldc + n) = o;
+    } else if (rowsum != nullptr && idx - total < M) {
+        const int64_t m = idx - total;
+        const float *r = ws + (int64_t)splits * M * N;
+        float a = r[m];
+        for (int sp = 1; sp < splits; ++sp) a += r[(int64_t)sp * M + m];
+        rowsum[m] = (uint16_t)f32_to_bf16_bits(a);
     }
 }
 
@@ -315,25 +353,33 @@ __global__ void __launch_bounds__(256) gemm_f32_k(const float *__restrict__ A, i
 template <int BM, int BN, int BK, int WGM, int WGN>
 static void launch_bf16(hipStream_t s, bool a_km, bool b_km, int64_t M, int64_t N, int64_t K, const void *A, int64_t lda,
                         const void *B, int64_t ldb, const void *bias, const void *resid, int64_t ldr, void *C, int64_t ldc,
-                        void *rowsum) {
+                        void *rowsum, void *workspace, int splits) {
     const int tiles_m = (int)((M + BM - 1) / BM), tiles_n = (int)((N + BN - 1) / BN);
-    const dim3 grid((unsigned)(tiles_m * tiles_n));
+    float *ws = splits > 1 ? (float *)workspace : nullptr;
+    const int64_t k_chunk = splits > 1 ? ((K + splits - 1) / splits + BK - 1) / BK * BK : K;
+    const dim3 grid((unsigned)(tiles_m * tiles_n), (unsigned)(splits > 1 ? splits : 1));
     const dim3 block(WGM * WGN * 64);
 #define TIO_GEMM_ARGS (const uint16_t *)A, lda, (const uint16_t *)B, ldb, (const uint16_t *)bias, (const uint16_t *)resid, ldr, \
-                      (uint16_t *)C, ldc, M, N, K, tiles_m, tiles_n, (uint16_t *)rowsum
+                      (uint16_t *)C, ldc, M, N, K, tiles_m, tiles_n, (uint16_t *)rowsum, ws, k_chunk
     if (!a_km && !b_km) gemm_bf16_k<BM, BN, BK, WGM, WGN, false, false><<<grid, block, 0, s>>>(TIO_GEMM_ARGS);
     else if (!a_km && b_km) gemm_bf16_k<BM, BN, BK, WGM, WGN, false, true><<<grid, block, 0, s>>>(TIO_GEMM_ARGS);
     else if (a_km && b_km) gemm_bf16_k<BM, BN, BK, WGM, WGN, true, true><<<grid, block, 0, s>>>(TIO_GEMM_ARGS);
     else gemm_bf16_k<BM, BN, BK, WGM, WGN, true, false><<<grid, block, 0, s>>>(TIO_GEMM_ARGS);
 #undef TIO_GEMM_ARGS
+    if (ws) {
+        const int64_t n = M * (N / 4) + (rowsum ? M : 0);
+        splitk_reduce_k<<<(unsigned)((n + 255) / 256), 256, 0, s>>>(ws, (uint16_t *)C, ldc, (uint16_t *)rowsum, M, N, splits);
+    }
 }
 
 void gemm(hipStream_t s, int dtype, bool a_km, bool b_km, int64_t M, int64_t N, int64_t K, const void *A, int64_t lda,
           const void *B, int64_t ldb, const void *bias, const void *resid, int64_t ldr, void *C, int64_t ldc,
-          void *rowsum) {
+          void *rowsum, void *workspace, int splits) {
     if (M <= 0 || N <= 0 || K <= 0) return;
+    // split-K needs the fp32 workspace, no epilogue operands and whole float4 rows
+    if (dtype != TIO_PREC_BF16 || !workspace || bias || resid || (N % 4) || splits < 2) splits = 1;
     if (dtype == TIO_PREC_BF16) {
-        launch_bf16<128, 128, 64, 2, 2>(s, a_km, b_km, M, N, K, A, lda, B, ldb, bias, resid, ldr, C, ldc, rowsum);
+        launch_bf16<128, 128, 64, 2, 2>(s, a_km, b_km, M, N, K, A, lda, B, ldb, bias, resid, ldr, C, ldc, rowsum, workspace, splits);
     } else {
         const dim3 grid((unsigned)((N + 63) / 64), (unsigned)((M + 63) / 64));
 #define TIO_GEMM_ARGS (const float *)A, lda, (const float *)B, ldb, (const float *)bias, (const float *)resid, ldr, (float *)C, ldc, M, N, K, (float *)rowsum

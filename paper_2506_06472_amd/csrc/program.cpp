@@ -225,10 +225,14 @@ Program build_program(const tio_model_cfg &c) {
     auto gemm_dw = [&](int dY, int X, ParamInfo &Wt, ParamInfo *bias, int64_t n_in, int64_t n_out, int64_t ld_dy) {
         pgrad(Wt);
         if (bias) pgrad(*bias);
+        const int splits = bf16 ? dw_splits(n_out, n_in, S) : 1;
+        int ws = -1;
+        if (splits > 1) ws = b.grd32("ws." + Wt.name, splits * (n_out * n_in + n_out));   // fp32 partials + row sums
         KernelRec &k = b.kernel(OP_GEMM_DW);
         set(k, 0, dY, R); set(k, 1, X, R); set(k, 2, Wt.grad, W);
         if (bias) set(k, 3, bias->grad, W);
-        k.p[0] = n_out; k.p[1] = n_in; k.p[2] = S; k.p[3] = ld_dy;
+        if (ws >= 0) set(k, 4, ws, RW);
+        k.p[0] = n_out; k.p[1] = n_in; k.p[2] = S; k.p[3] = ld_dy; k.p[4] = splits;
         k.flops = 2 * S * n_in * n_out;
     };
     auto norm_bwd = [&](int dy, int xin, int st, ParamInfo &g, ParamInfo *bias, int dres, const std::string &dxn,

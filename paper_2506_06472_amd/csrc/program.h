@@ -58,5 +58,14 @@ struct Program {
 Program build_program(const tio_model_cfg &cfg);
 std::vector<ParamInfo> list_params(const tio_model_cfg &cfg);
 inline int64_t vocab_ld(int64_t V) { return (V + 63) / 64 * 64; }
+// Number of contraction ranges of a bf16 weight-gradient GEMM dW[M,N] = dY^T.X over K tokens: small
+// weight matrices give too few 128x128 output tiles to fill the GPU, so the token dimension is
+// split (powers of two, at most 8, at least 256 tokens per range) until about 512 workgroups exist.
+inline int dw_splits(int64_t M, int64_t N, int64_t K) {
+    const int64_t tiles = ((M + 127) / 128) * ((N + 127) / 128);
+    int s = 1;
+    while (s < 8 && tiles * s * 2 <= 512 && K / (s * 2) >= 256) s *= 2;
+    return s;
+}
 
 }  // namespace tio

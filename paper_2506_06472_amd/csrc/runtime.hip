@@ -169,7 +169,7 @@ void launch(tio_ctx *c, int k) {
     case OP_EMBED_FWD: k::embed_fwd(s, dt, (const int32_t *)P(0), P(1), P(2), P(3), r.p[0], r.p[1], r.p[2]); break;
     case OP_NORM_FWD: k::norm_fwd(s, dt, rms, P(0), P(1), P(2), P(3), (float *)P(4), r.p[0], r.p[1], m.norm_eps); break;
     case OP_GEMM:
-        k::gemm(s, dt, false, false, r.p[0], r.p[1], r.p[2], P(0), r.p[2], P(1), r.p[2], P(2), P(3), r.p[3], P(4), r.p[3], nullptr);
+        k::gemm(s, dt, false, false, r.p[0], r.p[1], r.p[2], P(0), r.p[2], P(1), r.p[2], P(2), P(3), r.p[3], P(4), r.p[3], nullptr, nullptr, 1);
         break;
     case OP_ROPE_FWD: k::rope(s, dt, P(0), B, T, H, dh, m.rope_theta, false); break;
     case OP_ROPE_BWD: k::rope(s, dt, P(0), B, T, H, dh, m.rope_theta, true); break;
@@ -179,11 +179,11 @@ void launch(tio_ctx *c, int k) {
     case OP_CE_FWD_BWD: k::ce_fwd_bwd(s, dt, P(0), (const int32_t *)P(1), (float *)P(2), r.p[0], r.p[1], r.p[2]); break;
     case OP_LOSS_REDUCE: k::loss_reduce(s, (const float *)P(0), (float *)P(1), r.p[0]); break;
     case OP_GEMM_DX:   // dX[S,n_in] = dY[S,n_out] . W[n_out,n_in]: the weight has the contraction index slow
-        k::gemm(s, dt, false, true, r.p[0], r.p[1], r.p[2], P(0), r.p[3], P(1), r.p[1], nullptr, nullptr, 0, P(2), r.p[1], nullptr);
+        k::gemm(s, dt, false, true, r.p[0], r.p[1], r.p[2], P(0), r.p[3], P(1), r.p[1], nullptr, nullptr, 0, P(2), r.p[1], nullptr, nullptr, 1);
         break;
     case OP_GEMM_DW:   // dW[n_out,n_in] = dY^T . X: both operands have the contraction index (tokens) slow;
                        // the row sums of dY^T are the bias gradient
-        k::gemm(s, dt, true, true, r.p[0], r.p[1], r.p[2], P(0), r.p[3], P(1), r.p[1], nullptr, nullptr, 0, P(2), r.p[1], P(3));
+        k::gemm(s, dt, true, true, r.p[0], r.p[1], r.p[2], P(0), r.p[3], P(1), r.p[1], nullptr, nullptr, 0, P(2), r.p[1], P(3), P(4), (int)r.p[4]);
         break;
     case OP_BIAS_GRAD: k::bias_grad(s, dt, P(0), P(1), r.p[0], r.p[1], r.p[1]); break;
     case OP_GELU_BWD: k::gelu_bwd(s, dt, P(0), P(1), r.p[0]); break;
@@ -489,16 +489,18 @@ int tio_profile_iteration(tio_ctx *c, const int32_t *tokens, const int32_t *labe
 
 int tio_op_gemm(void *stream, int32_t dtype, int32_t a_km, int32_t b_km, int64_t M, int64_t N, int64_t K, const void *A,
                 int64_t lda, const void *B, int64_t ldb, const void *bias, const void *resid, int64_t ldr, void *C, int64_t ldc,
-                void *rowsum) {
+                void *rowsum, void *workspace, int32_t splits) {
     TIO_RT_BEGIN
     if (!A || !B || !C) return fail(TIO_ERR_INVALID_ARG, "null argument");
     const int64_t al = dtype == TIO_PREC_BF16 ? 8 : 4;
     if (lda % al || ldb % al || ldc % 4 || (resid && ldr % 4)) return fail(TIO_ERR_INVALID_ARG, "leading dimensions must be multiples of 8 elements");
     if (((uintptr_t)A | (uintptr_t)B | (uintptr_t)C | (uintptr_t)bias | (uintptr_t)resid) & 15) return fail(TIO_ERR_INVALID_ARG, "pointers must be 16-byte aligned");
     const int64_t ka = (K + al - 1) / al * al, ma = (M + al - 1) / al * al, na = (N + al - 1) / al * al;
+    if (splits < 1 || splits > 64 || (splits > 1 && (!workspace || ((uintptr_t)workspace & 15))))
+        return fail(TIO_ERR_INVALID_ARG, "splits > 1 needs a 16-byte aligned fp32 workspace of splits*(M*N+M) floats");
     if ((a_km ? lda < ma : lda < ka) || (b_km ? ldb < na : ldb < ka) || ldc < N)
         return fail(TIO_ERR_INVALID_ARG, "leading dimension smaller than the (8-element padded) extent");
-    k::gemm((hipStream_t)stream, dtype, a_km != 0, b_km != 0, M, N, K, A, lda, B, ldb, bias, resid, ldr, C, ldc, rowsum);
+    k::gemm((hipStream_t)stream, dtype, a_km != 0, b_km != 0, M, N, K, A, lda, B, ldb, bias, resid, ldr, C, ldc, rowsum, workspace, splits);
     HIPCHK(hipGetLastError());
     return TIO_OK;
     TIO_RT_END

@@ -83,3 +83,36 @@ def test_gemm_rejects_bad_arguments():
         tio.tio_op_gemm(0, "bf16", 0, 0, 64, 64, 64, x.data_ptr() + 2, 64, x.data_ptr(), 64, 0, 0, 0, x.data_ptr(), 64)
     with pytest.raises(tio.TioError):
         tio.tio_op_gemm(0, "bf16", 0, 0, 64, 64, 64, x.data_ptr(), 64, x.data_ptr(), 64, 0, 0, 0, x.data_ptr(), 32)
+
+
+@pytest.mark.parametrize("M,N,K,splits", [(256, 128, 1024, 4), (200, 136, 1000, 3), (768, 768, 2048, 8), (130, 64, 4096, 2)])
+def test_gemm_split_contraction_matches_single_pass(M, N, K, splits):
+    """dW-shaped product (both operands k-major) with the contraction cut into ranges: same result as the
+    oracle product within bf16 rounding, row sums included, nothing written outside the output."""
+    import torch
+    import paper_2506_06472_amd as tio
+    print(f"split gemm M={M} N={N} K={K} splits={splits}", flush=True)
+    rng = np.random.default_rng(M + N + K)
+    r8 = lambda n: (n + 7) // 8 * 8
+    lda, ldb, ldc = r8(M), r8(N), r8(N)
+    A = rng.standard_normal((M, K)).astype(np.float32)
+    B = rng.standard_normal((N, K)).astype(np.float32)
+    As = np.zeros((K, lda), np.float32); As[:, :M] = A.T
+    Bs = np.zeros((K, ldb), np.float32); Bs[:, :N] = B.T
+    dA, dB = _dev(As, "bf16"), _dev(Bs, "bf16")
+    dC = torch.full((M, ldc), 7.0, device="cuda", dtype=torch.bfloat16)
+    dsum = torch.full((r8(M) + 8,), 7.0, device="cuda", dtype=torch.bfloat16)
+    ws = torch.full((splits * (M * N + M) + 64,), float("nan"), device="cuda", dtype=torch.float32)
+    torch.cuda.synchronize()
+    tio.tio_op_gemm(0, "bf16", 1, 1, M, N, K, dA.data_ptr(), lda, dB.data_ptr(), ldb, 0, 0, 0, dC.data_ptr(), ldc,
+                    dsum.data_ptr(), ws.data_ptr(), splits)
+    torch.cuda.synchronize()
+    A64, B64 = _host(dA)[:, :M].T, _host(dB)[:, :N].T
+    ref = A64 @ B64.T
+    got = _host(dC)
+    assert np.all(got[:, N:] == 7.0)
+    assert np.all(np.abs(got[:, :N] - ref) <= 2.0 ** -8 * np.abs(ref) + 1e-3 * np.sqrt(K))
+    rs = _host(dsum)
+    ref_rs = A64.sum(1)
+    assert np.all(np.abs(rs[:M] - ref_rs) <= 2.0 ** -8 * np.abs(ref_rs) + 1e-3 * np.sqrt(K)) and np.all(rs[M:] == 7.0)
+    assert torch.isnan(ws[splits * (M * N + M):]).all()

@@ -9,7 +9,8 @@ from gpulib import make_inputs, plans_for, read_state
 
 pytestmark = pytest.mark.gpu
 
-SMALL_BF16 = dict(arch="gpt", L=2, d=256, H=4, f=1024, V=1000, T=128, B=2, precision="bf16", lr=3e-4)
+# 512 tokens: the weight-gradient GEMMs of this shape run with a split contraction
+SMALL_BF16 = dict(arch="gpt", L=2, d=256, H=4, f=1024, V=1000, T=256, B=2, precision="bf16", lr=3e-4)
 SMALL_LLAMA_BF16 = dict(arch="llama", L=2, d=256, H=2, f=688, V=520, T=96, B=2, precision="bf16", lr=3e-4)
 
 
