@@ -217,6 +217,12 @@ int tio_op_gemm(void *stream, int32_t dtype, int32_t a_kmajor, int32_t b_kmajor,
                 const void *A, int64_t lda, const void *B, int64_t ldb,
                 const void *bias, const void *resid, int64_t ldr, void *C, int64_t ldc, void *rowsum,
                 void *workspace, int32_t splits);
+/* Causal self-attention on a packed qkv buffer [B*T, 3*H*dh] (q | k | v, heads side by side):
+ * o [B*T, H*dh] = softmax(q k^T / sqrt(dh)) v per head, lse [B*H*T] fp32 = log-sum-exp of the scaled
+ * scores.  With dO != NULL also the backward pass: delta [B*H*T] fp32 (work buffer, receives
+ * rowsum(dO * o)) and dqkv [B*T, 3*H*dh].  Device pointers, 16-byte aligned; dh in {32, 64, 128}. */
+int tio_op_attention(void *stream, int32_t dtype, int64_t B, int64_t T, int64_t H, int64_t dh,
+                     const void *qkv, void *o, float *lse, const void *dO, float *delta, void *dqkv);
 /* Timed repetitions of one operator on the given stream, HIP events around the launches;
  * returns average ns per launch.  op codes as in the trace; dims as documented per operator. */
 int tio_op_bench(tio_ctx *ctx, int32_t kernel_index, int32_t reps, double *out_avg_ns);

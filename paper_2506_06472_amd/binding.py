@@ -346,3 +346,9 @@ def tio_op_gemm(stream_handle, dtype, a_kmajor, b_kmajor, M, N, K, A_ptr, lda, B
     _check(lib().tio_op_gemm(vp(stream_handle), PREC[dtype], int(a_kmajor), int(b_kmajor), C.c_int64(M), C.c_int64(N),
                              C.c_int64(K), vp(A_ptr), C.c_int64(lda), vp(B_ptr), C.c_int64(ldb), vp(bias_ptr),
                              vp(resid_ptr), C.c_int64(ldr), vp(C_ptr), C.c_int64(ldc), vp(rowsum_ptr), vp(workspace_ptr), int(splits)))
+
+
+def tio_op_attention(stream_handle, dtype, B, T, H, dh, qkv_ptr, o_ptr, lse_ptr, dO_ptr=0, delta_ptr=0, dqkv_ptr=0):
+    vp = lambda p: C.c_void_p(p) if p else None
+    _check(lib().tio_op_attention(vp(stream_handle), PREC[dtype], C.c_int64(B), C.c_int64(T), C.c_int64(H), C.c_int64(dh),
+                                  vp(qkv_ptr), vp(o_ptr), vp(lse_ptr), vp(dO_ptr), vp(delta_ptr), vp(dqkv_ptr)))

@@ -25,6 +25,11 @@ void rope(hipStream_t s, int dtype, void *qkv, int64_t B, int64_t T, int64_t H, 
           bool inverse);
 void attn_fwd(hipStream_t s, int dtype, const void *qkv, void *o, float *lse, int64_t B, int64_t T, int64_t H,
               int64_t dh);
+// matrix-core attention (bf16, head dimension 64 or 128); attn_fwd / attn_bwd dispatch to it
+bool attn_mfma_supported(int dtype, int64_t dh);
+void attn_fwd_mfma(hipStream_t s, const void *qkv, void *o, float *lse, int64_t B, int64_t T, int64_t H, int64_t dh);
+void attn_bwd_mfma(hipStream_t s, const void *dO, const void *qkv, const float *lse, const float *delta, void *dqkv,
+                   int64_t B, int64_t T, int64_t H, int64_t dh);
 void gelu_fwd(hipStream_t s, int dtype, const void *u, void *y, int64_t n);
 void swiglu_fwd(hipStream_t s, int dtype, const void *gu, void *y, int64_t S, int64_t f);
 void ce_fwd_bwd(hipStream_t s, int dtype, void *logits, const int32_t *labels, float *losses, int64_t S,

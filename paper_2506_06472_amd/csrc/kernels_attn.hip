@@ -1,5 +1,7 @@
 // Causal self-attention, forward and backward, on the packed [S, 3d] q|k|v layout (no head
-// transposes ever touch HBM).  Row-parallel formulation: a query row (forward, dQ) or a key row
+// transposes ever touch HBM).  This file holds the fp32-ALU formulation used by the fp32 workloads and
+// by head dimension 32; bf16 with head dimension 64 or 128 runs on the matrix cores
+// (kernels_attn_mfma.hip).  Row-parallel formulation: a query row (forward, dQ) or a key row
 // (dK, dV) is owned by G = dh/32 adjacent lanes, each holding a 32-wide slice of the head dimension
 // in registers; the opposite side streams through LDS in tiles of 32 rows.  Softmax statistics are
 // fp32 (row maximum and log-sum-exp saved for the backward pass); every sum has a fixed order, so
@@ -259,6 +261,7 @@ __global__ void __launch_bounds__(TPB) attn_bwd_dkv_k(const T *__restrict__ dO, 
     } while (0)
 
 void attn_fwd(hipStream_t s, int dtype, const void *qkv, void *o, float *lse, int64_t B, int64_t Tn, int64_t H, int64_t dh) {
+    if (attn_mfma_supported(dtype, dh)) { attn_fwd_mfma(s, qkv, o, lse, B, Tn, H, dh); return; }
     const float scale = 1.0f / sqrtf((float)dh);
     TIO_ATTN_DISPATCH(dtype, dh, {
         constexpr int R = TPB / (DH / 32);
@@ -278,6 +281,7 @@ void attn_bwd_pre(hipStream_t s, int dtype, const void *dO, const void *O, float
 
 void attn_bwd(hipStream_t s, int dtype, const void *dO, const void *qkv, const float *lse, const float *delta, void *dqkv,
               int64_t B, int64_t Tn, int64_t H, int64_t dh) {
+    if (attn_mfma_supported(dtype, dh)) { attn_bwd_mfma(s, dO, qkv, lse, delta, dqkv, B, Tn, H, dh); return; }
     const float scale = 1.0f / sqrtf((float)dh);
     TIO_ATTN_DISPATCH(dtype, dh, {
         constexpr int R = TPB / (DH / 32);

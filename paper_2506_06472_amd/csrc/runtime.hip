@@ -506,6 +506,25 @@ int tio_op_gemm(void *stream, int32_t dtype, int32_t a_km, int32_t b_km, int64_t
     TIO_RT_END
 }
 
+int tio_op_attention(void *stream, int32_t dtype, int64_t B, int64_t T, int64_t H, int64_t dh, const void *qkv, void *o,
+                     float *lse, const void *dO, float *delta, void *dqkv) {
+    TIO_RT_BEGIN
+    if (!qkv || !o || !lse) return fail(TIO_ERR_INVALID_ARG, "null argument");
+    if (dh != 32 && dh != 64 && dh != 128) return fail(TIO_ERR_INVALID_ARG, "head dimension must be 32, 64 or 128");
+    if (B < 1 || T < 1 || H < 1) return fail(TIO_ERR_INVALID_ARG, "non-positive dimension");
+    if (((uintptr_t)qkv | (uintptr_t)o | (uintptr_t)dO | (uintptr_t)dqkv) & 15) return fail(TIO_ERR_INVALID_ARG, "pointers must be 16-byte aligned");
+    hipStream_t s = (hipStream_t)stream;
+    k::attn_fwd(s, dtype, qkv, o, lse, B, T, H, dh);
+    if (dO) {
+        if (!delta || !dqkv) return fail(TIO_ERR_INVALID_ARG, "backward needs delta and dqkv");
+        k::attn_bwd_pre(s, dtype, dO, o, delta, B, T, H, dh);
+        k::attn_bwd(s, dtype, dO, qkv, lse, delta, dqkv, B, T, H, dh);
+    }
+    HIPCHK(hipGetLastError());
+    return TIO_OK;
+    TIO_RT_END
+}
+
 int tio_op_bench(tio_ctx *c, int32_t kernel_index, int32_t reps, double *out_avg_ns) {
     if (!c || !out_avg_ns || reps < 1) return fail(TIO_ERR_INVALID_ARG, "bad argument");
     TIO_RT_BEGIN
