@@ -10,6 +10,8 @@
 // row of C: the epilogue (bias, residual, rounding to bf16) writes 8 bytes per store.
 //
 // fp32: plain LDS-tiled FMA kernel (used by the small fp32 configurations, which are launch bound).
+#include <cstdlib>
+
 #include "../../include/teraio.h"
 #include "device_common.h"
 #include "kernels.h"
@@ -20,7 +22,7 @@ namespace k {
 
 namespace {
 
-template <int BM, int BN, int BK, int WGM, int WGN, bool AKM, bool BKM>
+template <int BM, int BN, int BK, int WGM, int WGN, int NBUF, bool AKM, bool BKM>
 __global__ void __launch_bounds__(WGM *WGN * 64)
     gemm_bf16_k(const uint16_t *__restrict__ A, int64_t lda, const uint16_t *__restrict__ B, int64_t ldb,
                 const uint16_t *__restrict__ bias, const uint16_t *__restrict__ resid, int64_t ldr,
@@ -31,8 +33,11 @@ __global__ void __launch_bounds__(WGM *WGN * 64)
     static_assert(NT % BM == 0 && (TPR & (TPR - 1)) == 0 && TPR <= 64 && BK % (8 * TPR) == 0, "row-sum mapping");
     constexpr int WM = BM / WGM, WN = BN / WGN, TM = WM / 32, TN = WN / 32;
     constexpr int LS = BK + LDS_PAD;
-    __shared__ __attribute__((aligned(16))) uint16_t As[BM * LS];
-    __shared__ __attribute__((aligned(16))) uint16_t Bs[BN * LS];
+    // NBUF operand tile pairs in LDS: with two, the stores of tile k+1 overlap the MFMAs of tile k and
+    // one barrier per tile suffices
+    extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
+    constexpr int TILE = (BM + BN) * LS;
+    uint16_t *As = smem, *Bs = smem + BM * LS;
 
     // tile order: groups of 8 tile rows walk the columns together, so that workgroups that run at the
     // same time share operand tiles in L2
@@ -80,6 +85,7 @@ __global__ void __launch_bounds__(WGM *WGN * 64)
             sa.load(A, lda, m0, M, kbeg + (int64_t)(kt + 1) * BK, kend, tid);
             sb.load(B, ldb, n0, N, kbeg + (int64_t)(kt + 1) * BK, kend, tid);
         }
+        if (NBUF == 2) { As = smem + (kt & 1) * TILE; Bs = As + BM * LS; }
         if (do_rowsum) {
             const uint16_t *row = As + (tid / TPR) * LS + (tid % TPR) * (BK / TPR);
 #pragma unroll
@@ -106,11 +112,19 @@ __global__ void __launch_bounds__(WGM *WGN * 64)
                     // first operand indexes the accumulator's register dimension (n), second its lane dimension (m)
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j].v, fa[i].v, acc[i][j], 0, 0, 0);
         }
-        __syncthreads();
-        if (kt + 1 < nk) {
-            sa.store(As, tid);
-            sb.store(Bs, tid);
+        if (NBUF == 2) {
+            if (kt + 1 < nk) {
+                sa.store(smem + ((kt + 1) & 1) * TILE, tid);
+                sb.store(smem + ((kt + 1) & 1) * TILE + BM * LS, tid);
+            }
             __syncthreads();
+        } else {
+            __syncthreads();
+            if (kt + 1 < nk) {
+                sa.store(As, tid);
+                sb.store(Bs, tid);
+                __syncthreads();
+            }
         }
     }
 
@@ -255,7 +269,7 @@ __global__ void __launch_bounds__(256) gemm_f32_k(const float *__restrict__ A, i
 
 }  // namespace
 
-template <int BM, int BN, int BK, int WGM, int WGN>
+template <int BM, int BN, int BK, int WGM, int WGN, int NBUF>
 static void launch_bf16(hipStream_t s, bool a_km, bool b_km, int64_t M, int64_t N, int64_t K, const void *A, int64_t lda,
                         const void *B, int64_t ldb, const void *bias, const void *resid, int64_t ldr, void *C, int64_t ldc,
                         void *rowsum, void *workspace, int splits) {
@@ -264,17 +278,32 @@ static void launch_bf16(hipStream_t s, bool a_km, bool b_km, int64_t M, int64_t 
     const int64_t k_chunk = splits > 1 ? ((K + splits - 1) / splits + BK - 1) / BK * BK : K;
     const dim3 grid((unsigned)(tiles_m * tiles_n), (unsigned)(splits > 1 ? splits : 1));
     const dim3 block(WGM * WGN * 64);
+    constexpr size_t lds = (size_t)NBUF * (BM + BN) * (BK + LDS_PAD) * 2;
+    static bool attr_done = false;           // tiles above 64 KiB of LDS need the limit raised once per kernel
+    if (!attr_done) {
+        (void)hipFuncSetAttribute((const void *)gemm_bf16_k<BM, BN, BK, WGM, WGN, NBUF, false, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        (void)hipFuncSetAttribute((const void *)gemm_bf16_k<BM, BN, BK, WGM, WGN, NBUF, false, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        (void)hipFuncSetAttribute((const void *)gemm_bf16_k<BM, BN, BK, WGM, WGN, NBUF, true, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        (void)hipFuncSetAttribute((const void *)gemm_bf16_k<BM, BN, BK, WGM, WGN, NBUF, true, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        attr_done = true;
+    }
 #define TIO_GEMM_ARGS (const uint16_t *)A, lda, (const uint16_t *)B, ldb, (const uint16_t *)bias, (const uint16_t *)resid, ldr, \
                       (uint16_t *)C, ldc, M, N, K, tiles_m, tiles_n, (uint16_t *)rowsum, ws, k_chunk
-    if (!a_km && !b_km) gemm_bf16_k<BM, BN, BK, WGM, WGN, false, false><<<grid, block, 0, s>>>(TIO_GEMM_ARGS);
-    else if (!a_km && b_km) gemm_bf16_k<BM, BN, BK, WGM, WGN, false, true><<<grid, block, 0, s>>>(TIO_GEMM_ARGS);
-    else if (a_km && b_km) gemm_bf16_k<BM, BN, BK, WGM, WGN, true, true><<<grid, block, 0, s>>>(TIO_GEMM_ARGS);
-    else gemm_bf16_k<BM, BN, BK, WGM, WGN, true, false><<<grid, block, 0, s>>>(TIO_GEMM_ARGS);
+    if (!a_km && !b_km) gemm_bf16_k<BM, BN, BK, WGM, WGN, NBUF, false, false><<<grid, block, lds, s>>>(TIO_GEMM_ARGS);
+    else if (!a_km && b_km) gemm_bf16_k<BM, BN, BK, WGM, WGN, NBUF, false, true><<<grid, block, lds, s>>>(TIO_GEMM_ARGS);
+    else if (a_km && b_km) gemm_bf16_k<BM, BN, BK, WGM, WGN, NBUF, true, true><<<grid, block, lds, s>>>(TIO_GEMM_ARGS);
+    else gemm_bf16_k<BM, BN, BK, WGM, WGN, NBUF, true, false><<<grid, block, lds, s>>>(TIO_GEMM_ARGS);
 #undef TIO_GEMM_ARGS
     if (ws) {
         const int64_t n = M * (N / 4) + (rowsum ? M : 0);
         splitk_reduce_k<<<(unsigned)((n + 255) / 256), 256, 0, s>>>(ws, (uint16_t *)C, ldc, (uint16_t *)rowsum, M, N, splits);
     }
+}
+
+static int gemm_cfg_override() {
+    static int v = -2;
+    if (v == -2) { const char *e = getenv("TIO_GEMM_CFG"); v = e ? atoi(e) : -1; }
+    return v;
 }
 
 void gemm(hipStream_t s, int dtype, bool a_km, bool b_km, int64_t M, int64_t N, int64_t K, const void *A, int64_t lda,
@@ -284,7 +313,14 @@ void gemm(hipStream_t s, int dtype, bool a_km, bool b_km, int64_t M, int64_t N, 
     // split-K needs the fp32 workspace, no epilogue operands and whole float4 rows
     if (dtype != TIO_PREC_BF16 || !workspace || bias || resid || (N % 4) || splits < 2) splits = 1;
     if (dtype == TIO_PREC_BF16) {
-        launch_bf16<128, 128, 64, 2, 2>(s, a_km, b_km, M, N, K, A, lda, B, ldb, bias, resid, ldr, C, ldc, rowsum, workspace, splits);
+#define TIO_L(BM, BN, BK, WGM, WGN, NBUF) launch_bf16<BM, BN, BK, WGM, WGN, NBUF>(s, a_km, b_km, M, N, K, A, lda, B, ldb, bias, resid, ldr, C, ldc, rowsum, workspace, splits)
+        // 256x256 tiles (128x128 per wavefront: half the LDS traffic per MFMA) pay off once they fill the
+        // GPU and the contraction is long enough to amortise their prologue and epilogue; otherwise 128x128
+        const int64_t big_tiles = ((M + 255) / 256) * ((N + 255) / 256);
+        const int cfg = gemm_cfg_override() >= 0 ? gemm_cfg_override() : ((big_tiles >= 256 && K >= 2048 && splits == 1) ? 4 : 0);
+        if (cfg == 4) TIO_L(256, 256, 64, 2, 2, 1);
+        else TIO_L(128, 128, 64, 2, 2, 1);
+#undef TIO_L
     } else {
         const dim3 grid((unsigned)((N + 63) / 64), (unsigned)((M + 63) / 64));
 #define TIO_GEMM_ARGS (const float *)A, lda, (const float *)B, ldb, (const float *)bias, (const float *)resid, ldr, (float *)C, ldc, M, N, K, (float *)rowsum
