@@ -194,14 +194,20 @@ int tio_set_slow_tier_bw(tio_ctx *ctx, uint64_t bytes_per_s);
  * streams.  plan == NULL runs the uncapped layout with no migration.  tokens/labels: host int32.
  * flags: TIO_STEP_CAPTURE_GRADS keeps a host copy of every parameter gradient (debug: it
  * synchronises before each optimizer launch); TIO_STEP_TIME_KERNELS brackets every launch with HIP
- * events on the compute stream (see tio_kernel_times).
+ * events on the compute stream (see tio_kernel_times); TIO_STEP_TIMELINE additionally stamps every
+ * migration (see tio_step_timeline).
  * Blocks until the compute stream has finished the iteration (copies may still be in flight). */
-enum { TIO_STEP_CAPTURE_GRADS = 1, TIO_STEP_TIME_KERNELS = 2 };
+enum { TIO_STEP_CAPTURE_GRADS = 1, TIO_STEP_TIME_KERNELS = 2, TIO_STEP_TIMELINE = 4 };
 int tio_train_step(tio_ctx *ctx, const int32_t *tokens, const int32_t *labels,
                    const tio_plan *plan, int32_t flags, tio_step_stats *out);
 /* Per-launch durations (ns, HIP events) of the last step run with TIO_STEP_TIME_KERNELS;
  * n must equal the kernel count of the trace. */
 int tio_kernel_times(tio_ctx *ctx, int64_t *out_ns, int32_t n);
+/* Timeline of the last step run with TIO_STEP_TIMELINE (it synchronises all streams before and
+ * after the step): begin and end of every kernel and of every plan entry's copy, in ns from the
+ * start of the step (HIP events on the stream the work ran on); -1 for entries not issued. */
+int tio_step_timeline(tio_ctx *ctx, int64_t *kernel_begin, int64_t *kernel_end, int32_t n_kernels,
+                      int64_t *copy_begin, int64_t *copy_end, int32_t n_entries);
 
 /* ---- single operators on caller-provided device buffers (kernel parity tests, benchmarks) ---- */
 /* C[M,N] = A . B^T (+ bias[N]) (+ resid[M,N]); a_kmajor/b_kmajor: operand stored [K, rows]

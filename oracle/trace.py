@@ -170,12 +170,20 @@ def build_trace(cfg):
         idx = b.ids[name]
         return b.tensor("g." + name, b.tensors[idx][0] if not bf16 else b.tensors[idx][0], K_PGRAD)
 
+    def adamw(name):
+        # the update of a parameter follows the launch that completes its gradient (no later kernel of the
+        # iteration reads the parameter), so gradients die at once and optimizer traffic overlaps the backward pass
+        state = [name] + ([name + ".master"] if bf16 else []) + [name + ".m", name + ".v"]
+        b.kernel(ADAMW, reads=["g." + name], inouts=state)
+
     def norm_bwd(dy, xin, st, pnames, dres, dx, part):
         grd(dx, S * d); grd(part, nb * len(pnames) * d, 4)
         b.kernel(NORM_BWD, reads=[dy, xin, st, pnames[0]] + ([dres] if dres else []), writes=[dx, part])
         for n in pnames:
             pgrad(n)
         b.kernel(NORM_BWD_PARAMS, reads=[part], writes=["g." + n for n in pnames])
+        for n in pnames:
+            adamw(n)
 
     def gemm_dw(dy, xin, w, bias, n_out, n_in):
         pgrad(w)
@@ -188,6 +196,9 @@ def build_trace(cfg):
             ws = ["ws." + w]
         b.kernel(GEMM_DW, reads=[dy, xin], writes=["g." + w] + (["g." + bias] if bias else []), inouts=ws,
                  flops=2 * S * n_in * n_out)
+        adamw(w)
+        if bias:
+            adamw(bias)
 
     grd("dhf", S * d)
     b.kernel(GEMM_DX, reads=["logits", "w_head"], writes=["dhf"], flops=2 * S * V * d)
@@ -231,14 +242,11 @@ def build_trace(cfg):
         dx = p + "dx"
     pgrad("wte")
     b.kernel(EMBED_BWD, reads=[dx, "tokens"], writes=["g.wte"])
+    adamw("wte")
     if gpt:
         pgrad("wpe")
         b.kernel(POSEMB_BWD, reads=[dx], writes=["g.wpe"])
-
-    # ---- optimizer: one launch per parameter tensor
-    for name, _, _ in specs:
-        state = [name] + ([name + ".master"] if bf16 else []) + [name + ".m", name + ".v"]
-        b.kernel(ADAMW, reads=["g." + name], inouts=state)
+        adamw("wpe")
 
     tau = []
     for op, operands, flops in b.kernels:

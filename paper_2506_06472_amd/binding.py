@@ -307,14 +307,21 @@ class Context:
     def tio_set_slow_tier_bw(self, bw: int):
         _check(lib().tio_set_slow_tier_bw(self.h, C.c_uint64(int(bw))))
 
-    def tio_train_step(self, tokens, labels, plan: Plan | None = None, capture_grads=False, time_kernels=False):
+    def tio_train_step(self, tokens, labels, plan: Plan | None = None, capture_grads=False, time_kernels=False,
+                       timeline=False):
         t = np.ascontiguousarray(tokens, dtype=np.int32)
         l = np.ascontiguousarray(labels, dtype=np.int32)
         st = StepStats()
-        flags = (1 if capture_grads else 0) | (2 if time_kernels else 0)
+        flags = (1 if capture_grads else 0) | (2 if time_kernels else 0) | (4 if timeline else 0)
         _check(lib().tio_train_step(self.h, t.ctypes.data_as(C.POINTER(C.c_int32)), l.ctypes.data_as(C.POINTER(C.c_int32)),
                                     plan.h if plan is not None else None, flags, C.byref(st)))
         return {f: getattr(st, f) for f, _ in StepStats._fields_}
+
+    def tio_step_timeline(self, n_kernels: int, n_entries: int):
+        a = [np.empty(n_kernels, dtype=np.int64) for _ in range(2)] + [np.empty(max(n_entries, 1), dtype=np.int64) for _ in range(2)]
+        p = [x.ctypes.data_as(C.POINTER(C.c_int64)) for x in a]
+        _check(lib().tio_step_timeline(self.h, p[0], p[1], n_kernels, p[2], p[3], n_entries))
+        return a[0], a[1], a[2][:n_entries], a[3][:n_entries]
 
     def tio_kernel_times(self, n_kernels: int):
         out = np.empty(n_kernels, dtype=np.int64)

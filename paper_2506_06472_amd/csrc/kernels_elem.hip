@@ -471,15 +471,32 @@ __global__ void __launch_bounds__(TPB) convert_k(const float *__restrict__ src, 
     if (i < n) dst[i] = from_f32<T>(src[i]);
 }
 
-__global__ void pace_begin_k(unsigned long long *slot) {
-    if (threadIdx.x == 0) *slot = wall_clock64();
-}
-// waits until `ticks` of the constant-rate clock have passed since the stamp; the tick count is
-// bounded by the host, so the loop always ends
-__global__ void pace_wait_k(const unsigned long long *slot, unsigned long long ticks) {
-    if (threadIdx.x != 0) return;
-    const unsigned long long t0 = *slot;
-    while (wall_clock64() - t0 < ticks) __builtin_amdgcn_s_sleep(32);
+// Copy at a fixed rate between the arena and the pinned slow-tier pool (both mapped into the GPU's
+// address space): the range is cut into one slice per workgroup, each slice moves in 64 KiB chunks,
+// and after every chunk the workgroup sleeps until its share of `ticks` (constant-rate wall clock,
+// bounded by the host) has passed, so the whole transfer takes bytes / bandwidth and the link sees a
+// steady stream.  One launch per migration: no engine switches on the copy stream.
+constexpr int PACED_WG = 32;
+__global__ void __launch_bounds__(TPB) paced_copy_k(uint4 *__restrict__ dst, const uint4 *__restrict__ src, int64_t n16,
+                                                    unsigned long long ticks) {
+    const unsigned long long t0 = wall_clock64();
+    const int64_t per = (n16 + gridDim.x - 1) / gridDim.x;
+    const int64_t beg = (int64_t)blockIdx.x * per;
+    const int64_t end = beg + per < n16 ? beg + per : n16;
+    constexpr int64_t CHUNK = TPB * 16;                  // uint4 elements per chunk (64 KiB)
+    for (int64_t c0 = beg; c0 < end; c0 += CHUNK) {
+#pragma unroll 4
+        for (int u = 0; u < 16; ++u) {
+            const int64_t i = c0 + (int64_t)u * TPB + threadIdx.x;
+            if (i < end) dst[i] = src[i];
+        }
+        const int64_t done = (c0 + CHUNK < end ? c0 + CHUNK : end) - beg;
+        if (threadIdx.x == 0) {
+            const unsigned long long due = (unsigned long long)((double)ticks * (double)done / (double)(end - beg));
+            while (wall_clock64() - t0 < due) __builtin_amdgcn_s_sleep(16);
+        }
+        __syncthreads();
+    }
 }
 
 }  // namespace
@@ -602,9 +619,12 @@ void convert_from_f32(hipStream_t s, int dtype, const float *src, void *dst, int
     TIO_DISPATCH(dtype, { convert_k<T><<<blocks_for(n, TPB), TPB, 0, s>>>(src, (T *)dst, n); });
 }
 
-void pace_begin(hipStream_t s, unsigned long long *slot) { pace_begin_k<<<1, 64, 0, s>>>(slot); }
-void pace_wait(hipStream_t s, const unsigned long long *slot, unsigned long long ticks) {
-    pace_wait_k<<<1, 64, 0, s>>>(slot, ticks);
+void paced_copy(hipStream_t s, void *dst, const void *src, int64_t bytes, unsigned long long ticks) {
+    const int64_t n16 = bytes / 16;
+    int wg = (int)((n16 + TPB * 16 - 1) / (TPB * 16));
+    if (wg > PACED_WG) wg = PACED_WG;
+    if (wg < 1) wg = 1;
+    paced_copy_k<<<wg, TPB, 0, s>>>((uint4 *)dst, (const uint4 *)src, n16, ticks);
 }
 
 }  // namespace k

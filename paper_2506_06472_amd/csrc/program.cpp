@@ -215,6 +215,14 @@ Program build_program(const tio_model_cfg &c) {
         p.grad = b.tensor("g." + p.name, p.rows * p.cols * b.e, KIND_PGRAD);
         return p.grad;
     };
+    // A parameter is updated right after the launch that completes its gradient: nothing later in the
+    // iteration reads it, the gradient dies at once, and the optimizer-state traffic overlaps the backward pass.
+    auto adamw = [&](ParamInfo &p) {
+        KernelRec &k = b.kernel(OP_ADAMW);
+        set(k, 0, p.grad, R); set(k, 1, p.w, RW); if (bf16) set(k, 2, p.master, RW);
+        set(k, 3, p.m, RW); set(k, 4, p.v, RW);
+        k.p[0] = p.rows * p.cols;
+    };
     auto gemm_dx = [&](int dY, ParamInfo &Wt, int dX, int64_t n_in, int64_t n_out, int64_t ld_dy) {
         KernelRec &k = b.kernel(OP_GEMM_DX);
         set(k, 0, dY, R); set(k, 1, Wt.w, R); set(k, 2, dX, W);
@@ -234,6 +242,8 @@ Program build_program(const tio_model_cfg &c) {
         if (ws >= 0) set(k, 4, ws, RW);
         k.p[0] = n_out; k.p[1] = n_in; k.p[2] = S; k.p[3] = ld_dy; k.p[4] = splits;
         k.flops = 2 * S * n_in * n_out;
+        adamw(Wt);
+        if (bias) adamw(*bias);
     };
     auto norm_bwd = [&](int dy, int xin, int st, ParamInfo &g, ParamInfo *bias, int dres, const std::string &dxn,
                         const std::string &pn) {
@@ -248,9 +258,13 @@ Program build_program(const tio_model_cfg &c) {
         }
         pgrad(g);
         if (bias) pgrad(*bias);
-        KernelRec &k = b.kernel(OP_NORM_BWD_PARAMS);
-        set(k, 0, part, R); set(k, 1, g.grad, W); if (bias) set(k, 2, bias->grad, W);
-        k.p[0] = nb; k.p[1] = d;
+        {
+            KernelRec &k = b.kernel(OP_NORM_BWD_PARAMS);
+            set(k, 0, part, R); set(k, 1, g.grad, W); if (bias) set(k, 2, bias->grad, W);
+            k.p[0] = nb; k.p[1] = d;
+        }
+        adamw(g);
+        if (bias) adamw(*bias);
         return dx;
     };
 
@@ -311,25 +325,24 @@ Program build_program(const tio_model_cfg &c) {
     {
         ParamInfo &wte = pidx("wte");
         pgrad(wte);
-        KernelRec &k = b.kernel(OP_EMBED_BWD);
-        set(k, 0, dx, R); set(k, 1, b.P.tokens_id, R); set(k, 2, wte.grad, W);
-        k.p[0] = S; k.p[1] = d; k.p[2] = V;
+        {
+            KernelRec &k = b.kernel(OP_EMBED_BWD);
+            set(k, 0, dx, R); set(k, 1, b.P.tokens_id, R); set(k, 2, wte.grad, W);
+            k.p[0] = S; k.p[1] = d; k.p[2] = V;
+        }
+        adamw(wte);
     }
     if (gpt) {
         ParamInfo &wpe = pidx("wpe");
         pgrad(wpe);
-        KernelRec &k = b.kernel(OP_POSEMB_BWD);
-        set(k, 0, dx, R); set(k, 1, wpe.grad, W);
-        k.p[0] = B; k.p[1] = T; k.p[2] = d;
+        {
+            KernelRec &k = b.kernel(OP_POSEMB_BWD);
+            set(k, 0, dx, R); set(k, 1, wpe.grad, W);
+            k.p[0] = B; k.p[1] = T; k.p[2] = d;
+        }
+        adamw(wpe);
     }
 
-    // ---- optimizer
-    for (auto &p : b.P.params) {
-        KernelRec &k = b.kernel(OP_ADAMW);
-        set(k, 0, p.grad, R); set(k, 1, p.w, RW); if (bf16) set(k, 2, p.master, RW);
-        set(k, 3, p.m, RW); set(k, 4, p.v, RW);
-        k.p[0] = p.rows * p.cols;
-    }
     return b.P;
 }
 

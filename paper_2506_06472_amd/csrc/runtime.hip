@@ -6,8 +6,8 @@
 // empty address ranges its outputs reuse), then launches kernel k.  A late migration therefore
 // stalls the kernel that needs it and nothing else, which is the paper's "kernel stall".  Urgent
 // entries come first within each direction at every trigger point.  The slow tier is pinned host
-// memory; its bandwidth is enforced on the copy streams by a stamp kernel before and a bounded wait
-// kernel after each copy.
+// memory; its bandwidth is enforced by a copy kernel that moves each tensor at the stated rate (one
+// launch per migration on the copy stream); unthrottled runs use hipMemcpyAsync.
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
@@ -76,6 +76,10 @@ struct tio_ctx {
     float *loss_pinned = nullptr;                         // 4 KiB of pinned host memory owned by the context
     std::vector<std::vector<float>> grads;
     std::vector<int64_t> last_times;                      // per-kernel ns of the last step run with timing
+    std::vector<hipEvent_t> ev_c0, ev_c1;                 // timeline mode: begin / end of every migration
+    hipEvent_t ev_step0 = nullptr;
+    std::vector<int64_t> tl_k0, tl_k1, tl_c0, tl_c1;      // timeline of the last step run in timeline mode (ns from step start)
+    bool timeline = false;
     Plan uncapped;
     bool have_uncapped = false;
 };
@@ -209,12 +213,13 @@ void launch(tio_ctx *c, int k) {
 }
 
 void paced_copy(tio_ctx *c, hipStream_t s, int slot, void *dst, const void *src, uint64_t bytes, hipMemcpyKind kind) {
-    if (c->bw) k::pace_begin(s, c->pace_slots + slot);
-    HIPCHK(hipMemcpyAsync(dst, src, bytes, kind, s));
+    (void)slot;
     if (c->bw) {
         double ticks = (double)bytes / (double)c->bw * c->clock_hz;
         ticks = std::min(ticks, 30.0 * c->clock_hz);         // bounded wait
-        k::pace_wait(s, c->pace_slots + slot, (unsigned long long)ticks);
+        k::paced_copy(s, dst, src, (int64_t)bytes, (unsigned long long)ticks);
+    } else {
+        HIPCHK(hipMemcpyAsync(dst, src, bytes, kind, s));
     }
 }
 
@@ -248,6 +253,14 @@ void run_step(tio_ctx *c, const int32_t *tokens, const int32_t *labels, bool cap
     }
     if (capture) c->grads.assign(c->prog.params.size(), {});
     if (timing) { if ((int)c->ev_t0.size() != N) { make_events(c->ev_t0, N, true); make_events(c->ev_t1, N, true); } }
+    const bool tl = c->timeline && timing;
+    if (tl) {
+        if (c->ev_c0.size() != p.entries.size()) { make_events(c->ev_c0, p.entries.size(), true); make_events(c->ev_c1, p.entries.size(), true); }
+        if (!c->ev_step0) HIPCHK(hipEventCreate(&c->ev_step0));
+        sync_all(c);
+        HIPCHK(hipEventRecord(c->ev_step0, c->sc));
+    }
+    std::vector<uint8_t> issued(tl ? p.entries.size() : 0, 0);
     const auto w0 = std::chrono::steady_clock::now();
     HIPCHK(hipMemcpyAsync(c->arena + address_at(p, c->prog.tokens_id, 0), tokens, S * 4, hipMemcpyHostToDevice, c->sc));
     HIPCHK(hipMemcpyAsync(c->arena + address_at(p, c->prog.labels_id, 0), labels, S * 4, hipMemcpyHostToDevice, c->sc));
@@ -266,7 +279,9 @@ void run_step(tio_ctx *c, const int32_t *tokens, const int32_t *labels, bool cap
                 if (persistent && !c->on_dev[e.tensor]) continue;
                 const Alloc &al = p.allocs[pr.alloc_before];
                 if (c->rec_kernel[prev]) HIPCHK(hipStreamWaitEvent(c->sd, c->ev_kernel[prev], 0));
+                if (tl) { HIPCHK(hipEventRecord(c->ev_c0[ei], c->sd)); issued[ei] = 1; }
                 paced_copy(c, c->sd, 0, c->host + pr.host_offset, c->arena + al.address, pr.bytes, hipMemcpyDeviceToHost);
+                if (tl) HIPCHK(hipEventRecord(c->ev_c1[ei], c->sd));
                 HIPCHK(hipEventRecord(c->ev_off[e.pair], c->sd));
                 c->rec_off[e.pair] = 1;
                 if (persistent) c->on_dev[e.tensor] = 0;
@@ -276,7 +291,9 @@ void run_step(tio_ctx *c, const int32_t *tokens, const int32_t *labels, bool cap
                 if (c->rec_kernel[prev]) HIPCHK(hipStreamWaitEvent(c->sh, c->ev_kernel[prev], 0));
                 if (c->rec_off[e.pair]) HIPCHK(hipStreamWaitEvent(c->sh, c->ev_off[e.pair], 0));
                 for (int q : al.wait_pairs) if (c->rec_off[q]) HIPCHK(hipStreamWaitEvent(c->sh, c->ev_off[q], 0));
+                if (tl) { HIPCHK(hipEventRecord(c->ev_c0[ei], c->sh)); issued[ei] = 1; }
                 paced_copy(c, c->sh, 1, c->arena + al.address, c->host + pr.host_offset, pr.bytes, hipMemcpyHostToDevice);
+                if (tl) HIPCHK(hipEventRecord(c->ev_c1[ei], c->sh));
                 HIPCHK(hipEventRecord(c->ev_pre[e.pair], c->sh));
                 c->rec_pre[e.pair] = 1;
                 if (persistent) { c->on_dev[e.tensor] = 1; c->dev_addr[e.tensor] = al.address; }
@@ -299,6 +316,14 @@ void run_step(tio_ctx *c, const int32_t *tokens, const int32_t *labels, bool cap
     const float loss = *c->loss_pinned;
     const auto w1 = std::chrono::steady_clock::now();
     c->step += 1;
+    if (tl) {
+        sync_all(c);
+        auto rel = [&](hipEvent_t e) { float ms = 0.f; HIPCHK(hipEventElapsedTime(&ms, c->ev_step0, e)); return (int64_t)std::llround((double)ms * 1e6); };
+        c->tl_k0.assign(N, 0); c->tl_k1.assign(N, 0);
+        c->tl_c0.assign(p.entries.size(), -1); c->tl_c1.assign(p.entries.size(), -1);
+        for (int k = 0; k < N; ++k) { c->tl_k0[k] = rel(c->ev_t0[k]); c->tl_k1[k] = rel(c->ev_t1[k]); }
+        for (size_t i = 0; i < p.entries.size(); ++i) if (issued[i]) { c->tl_c0[i] = rel(c->ev_c0[i]); c->tl_c1[i] = rel(c->ev_c1[i]); }
+    }
     if (timing) {
         timing->assign(N, 0);
         for (int k = 0; k < N; ++k) {
@@ -382,6 +407,8 @@ int tio_ctx_destroy(tio_ctx *c) {
     (void)hipStreamSynchronize(c->sc); (void)hipStreamSynchronize(c->sd); (void)hipStreamSynchronize(c->sh);
     destroy_events(c->ev_kernel); destroy_events(c->ev_off); destroy_events(c->ev_pre);
     destroy_events(c->ev_t0); destroy_events(c->ev_t1);
+    destroy_events(c->ev_c0); destroy_events(c->ev_c1);
+    if (c->ev_step0) (void)hipEventDestroy(c->ev_step0);
     if (c->loss_pinned) (void)hipHostFree(c->loss_pinned);
     delete c;
     return TIO_OK;
@@ -452,7 +479,10 @@ int tio_train_step(tio_ctx *c, const int32_t *tokens, const int32_t *labels, con
     if (!c || !tokens || !labels) return fail(TIO_ERR_INVALID_ARG, "null argument");
     TIO_RT_BEGIN
     ensure_plan(c, plan);
-    run_step(c, tokens, labels, (flags & TIO_STEP_CAPTURE_GRADS) != 0, (flags & TIO_STEP_TIME_KERNELS) ? &c->last_times : nullptr, out);
+    c->timeline = (flags & TIO_STEP_TIMELINE) != 0;
+    run_step(c, tokens, labels, (flags & TIO_STEP_CAPTURE_GRADS) != 0,
+             (flags & (TIO_STEP_TIME_KERNELS | TIO_STEP_TIMELINE)) ? &c->last_times : nullptr, out);
+    c->timeline = false;
     return TIO_OK;
     TIO_RT_END
 }
@@ -504,6 +534,15 @@ int tio_op_gemm(void *stream, int32_t dtype, int32_t a_km, int32_t b_km, int64_t
     HIPCHK(hipGetLastError());
     return TIO_OK;
     TIO_RT_END
+}
+
+int tio_step_timeline(tio_ctx *c, int64_t *k0, int64_t *k1, int32_t n_kernels, int64_t *c0, int64_t *c1, int32_t n_entries) {
+    if (!c || !k0 || !k1 || (n_entries > 0 && (!c0 || !c1))) return fail(TIO_ERR_INVALID_ARG, "null argument");
+    if (n_kernels != (int32_t)c->tl_k0.size() || n_entries != (int32_t)c->tl_c0.size())
+        return fail(TIO_ERR_INVALID_ARG, "no step was run in timeline mode, or the counts differ");
+    std::memcpy(k0, c->tl_k0.data(), (size_t)n_kernels * 8); std::memcpy(k1, c->tl_k1.data(), (size_t)n_kernels * 8);
+    if (n_entries) { std::memcpy(c0, c->tl_c0.data(), (size_t)n_entries * 8); std::memcpy(c1, c->tl_c1.data(), (size_t)n_entries * 8); }
+    return TIO_OK;
 }
 
 int tio_op_attention(void *stream, int32_t dtype, int64_t B, int64_t T, int64_t H, int64_t dh, const void *qkv, void *o,

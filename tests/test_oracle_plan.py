@@ -91,17 +91,17 @@ def test_lifetimes_closed_form_on_the_layer_chain():
     tr = ot.build_trace(cfg)
     life = op.analyze_lifetimes(tr)
     L, N = cfg["L"], len(tr["kernels"])
-    bwd0 = 1 + 8 * L + 4 + 4               # first kernel of the last layer's backward
+    bwd0 = 1 + 8 * L + 4 + 7               # first kernel of the last layer's backward (head: dX, dW, AdamW; final norm: 2 + 2 AdamW)
     for i in range(L):
         t = tr["ids"][f"l{i}.act"]
         s = tr["tensors"][t][0]
         gelu = 1 + 8 * i + 6
-        assert life["active"][t] == [gelu, gelu + 1, bwd0 + 15 * (L - 1 - i) + 1]
-        assert (t, s, gelu + 1, bwd0 + 15 * (L - 1 - i) + 1) in life["periods"]
+        assert life["active"][t] == [gelu, gelu + 1, bwd0 + 27 * (L - 1 - i) + 1]
+        assert (t, s, gelu + 1, bwd0 + 27 * (L - 1 - i) + 1) in life["periods"]
         # x entering layer i: written by the previous kernel chain, read by ln1, the out-projection
         # residual and ln1's backward (the last kernel of the layer's backward)
         t = tr["ids"][f"l{i - 1}.xo" if i else "x0"]
-        assert life["active"][t][-1] == bwd0 + 15 * (L - 1 - i) + 13
+        assert life["active"][t][-1] == bwd0 + 27 * (L - 1 - i) + 23
     # optimizer moments are touched once per iteration: one wrap-around period of length N
     t = tr["ids"]["l0.w_fc1.m"]
     (k,) = life["active"][t]
