@@ -34,7 +34,7 @@ def main():
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="gpt2_small_bf16")
-    ap.add_argument("--bw", type=float, default=25e9, help="slow-tier bytes/s per direction; 0 = unthrottled")
+    ap.add_argument("--bw", type=float, default=-1, help="slow-tier bytes/s per direction; 0 = unthrottled; default: the workload's (25e9)")
     ap.add_argument("--min-bytes", type=int, default=1 << 20)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--modelled-tau", action="store_true", help="plan from modelled instead of measured kernel times")
@@ -45,21 +45,33 @@ def main():
 
     import torch
     import paper_2506_06472_amd as tio
-    from synth import CONFIGS, gen_params, gen_tokens, to_bf16_round
+    from synth import CONFIGS, gen_params, gen_tokens, iter_params_pooled, to_bf16_round
 
     cfg = CONFIGS[args.workload]
-    log = lambda *a: print(*a, file=sys.stderr, flush=True)
-    bw = int(args.bw)
+    t_start = time.perf_counter()
+    log = lambda *a: print(f"[{time.perf_counter() - t_start:7.1f}s]", *a, file=sys.stderr, flush=True)
+    bw = int(args.bw if args.bw >= 0 else cfg.get("slow_tier_bw", 25e9))
     S = cfg["B"] * cfg["T"]
     plist = tio.tio_param_list(cfg)
+    n_params = sum(r * c for _, r, c in plist)
     specs = [(n, (r, c) if r > 1 else (c,), "normal" if (r > 1) else ("ones" if n.endswith("_g") else "zeros"))
              for n, r, c in plist]
-    params = gen_params(specs, 0)
-    if cfg["precision"] == "bf16":
-        params = {k: to_bf16_round(v) for k, v in params.items()}
     tok, lab = gen_tokens(cfg["B"], cfg["T"], cfg["V"], 0)
+    small = n_params <= 10**9
+    params = None
+    if small:
+        params = gen_params(specs, 0)
+        if cfg["precision"] == "bf16":
+            params = {k: to_bf16_round(v) for k, v in params.items()}
 
-    # ---- profile on the uncapped layout, measure the ideal
+    def load_params(ctx):
+        if small:
+            ctx.tio_params_load(params)
+        else:                       # one tensor at a time from a seeded pool (the library rounds to bf16 itself)
+            for name, arr in iter_params_pooled(specs, 0):
+                ctx.tio_params_load({name: arr})
+
+    # ---- sizes: uncapped layout, and a preliminary capped plan (modelled kernel times) for the pool size
     lt = tio.tio_trace_build(cfg)
     ll = tio.tio_analyze_lifetimes(lt)
     M = ll.export()["M"]
@@ -67,12 +79,22 @@ def main():
     cap = int(cfg["cap_bytes"]) if "cap_bytes" in cfg else int(peak * cfg["cap_frac"]) // 256 * 256
     up = tio.tio_build_plan(lt, ll, 2**62, 0)
     upe = up.export()
-    ctx = tio.tio_ctx_create(cfg, upe["arena_needed"], upe["host_needed"] + (1 << 20), 0)
-    ctx.tio_params_load(params)
-    log('profiling on the uncapped layout: arena', upe['arena_needed'])
+    prelim = tio.tio_build_plan(lt, ll, cap, bw, min_bytes=args.min_bytes).export()
+    host_bytes = int(max(upe["host_needed"], prelim["host_needed"] * 1.15)) + (1 << 20)
+    arena_bytes = max(upe["arena_needed"], cap)
+    log(f"{args.workload}: {n_params / 1e9:.3f} B parameters, uncapped peak {peak / 1e9:.2f} GB, cap {cap / 1e9:.2f} GB, "
+        f"slow-tier pool {host_bytes / 1e9:.2f} GB at {bw / 1e9:.1f} GB/s")
+    arena = torch.empty(arena_bytes + 8192, dtype=torch.uint8, device="cuda:0")
+    host = torch.empty(host_bytes, dtype=torch.uint8, pin_memory=True)
+    log("buffers allocated")
+
+    # ---- profile on the uncapped layout, measure the ideal
+    ctx = tio.tio_ctx_create(cfg, upe["arena_needed"], host_bytes, 0, arena=arena, host=host)
+    load_params(ctx)
+    log("parameters loaded; profiling on the uncapped layout")
     measured = ctx.tio_profile_iteration(tok, lab, tio.PROFILE_MEASURED)
     tau = measured.export()["tau"]
-    log('sum of kernel times ms', tau.sum() / 1e6)
+    log("sum of kernel times ms", tau.sum() / 1e6)
     for _ in range(args.warmup):
         ctx.tio_train_step(tok, lab, None)
     torch.cuda.synchronize()
@@ -83,7 +105,6 @@ def main():
     ideal_s = (time.perf_counter() - t0) / args.steps
     ctx.close()
     del ctx
-    torch.cuda.empty_cache()
 
     # ---- plan under the cap
     if not args.modelled_tau:
@@ -93,11 +114,18 @@ def main():
     plan_s = time.perf_counter() - tp0
     pe = plan.export()
     log('ideal ms', ideal_s * 1e3, 'plan: entries', len(pe['entries']), 'moved GB', pe['bytes_per_direction'] / 1e9, 'planner s', plan_s)
+    if pe["host_needed"] + (1 << 20) > host_bytes:
+        host = None
+        host_bytes = pe["host_needed"] + (1 << 20)
+        host = torch.empty(host_bytes, dtype=torch.uint8, pin_memory=True)
 
-    # ---- capped run
-    ctx = tio.tio_ctx_create(cfg, cap, pe["host_needed"] + (1 << 20), bw)
-    ctx.tio_params_load(params)
-    for _ in range(args.warmup):
+    # ---- capped run: the context sees only `cap` bytes of the arena
+    ctx = tio.tio_ctx_create(cfg, cap, host_bytes, bw, arena=arena, host=host)
+    load_params(ctx)
+    first = ctx.tio_train_step(tok, lab, plan)
+    if abs(first["loss"] - np.log(cfg["V"])) > 0.5:
+        raise RuntimeError(f"loss at initialisation {first['loss']} is not ln(V) = {np.log(cfg['V'])}")
+    for _ in range(max(0, args.warmup - 1)):
         ctx.tio_train_step(tok, lab, plan)
     torch.cuda.synchronize()
     N = len(M)
@@ -155,6 +183,8 @@ def main():
     log('capped ms/step', step_s * 1e3, 'loss', loss)
     if not args.no_cpu_baseline:
         from oracle import model as om
+        if not small:
+            raise SystemExit("the CPU oracle baseline is only timed for workloads below 1e9 parameters: pass --no-cpu-baseline")
         sample = dict(cfg, B=1)
         stok, slab = tok[:1], lab[:1]
         tr = om.Trainer(sample, params, dtype=np.float64)

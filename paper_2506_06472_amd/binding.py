@@ -253,7 +253,8 @@ class Context:
     """Owns the arena (GPU), the slow-tier pool (pinned host) and three streams via torch,
     and a tio_ctx handle created on them."""
 
-    def __init__(self, cfg: dict, arena_bytes: int, host_bytes: int, slow_tier_bw: int = 0, single_copy_stream=False):
+    def __init__(self, cfg: dict, arena_bytes: int, host_bytes: int, slow_tier_bw: int = 0, single_copy_stream=False,
+                 arena=None, host=None):
         import torch
         if not torch.cuda.is_available():
             raise RuntimeError("a GPU is required for the runtime part of the library")
@@ -262,8 +263,13 @@ class Context:
         self.params = tio_param_list(cfg)
         self.index = {n: i for i, (n, _, _) in enumerate(self.params)}
         arena_bytes = (int(arena_bytes) + 4096 + 255) // 256 * 256     # the library keeps the last 4 KiB for itself
-        self.arena = torch.empty(arena_bytes, dtype=torch.uint8, device="cuda:0")
-        self.host = torch.empty(int(host_bytes), dtype=torch.uint8, pin_memory=True)
+        # buffers may be handed in (uint8 tensors, device / pinned) so that several contexts reuse them
+        if arena is not None and arena.numel() < arena_bytes:
+            raise ValueError("arena tensor too small")
+        if host is not None and host.numel() < host_bytes:
+            raise ValueError("host tensor too small")
+        self.arena = arena if arena is not None else torch.empty(arena_bytes, dtype=torch.uint8, device="cuda:0")
+        self.host = host if host is not None else torch.empty(int(host_bytes), dtype=torch.uint8, pin_memory=True)
         self.s_compute = torch.cuda.Stream(device="cuda:0")
         self.s_d2h = torch.cuda.Stream(device="cuda:0")
         self.s_h2d = self.s_d2h if single_copy_stream else torch.cuda.Stream(device="cuda:0")
@@ -285,6 +291,7 @@ class Context:
         self.close()
 
     def tio_params_load(self, params: dict):
+        """params: {name: array}; every parameter must be loaded before the first step."""
         for name, arr in params.items():
             a = np.ascontiguousarray(arr, dtype=np.float32).reshape(-1)
             _check(lib().tio_params_load(self.h, self.index[name], a.ctypes.data_as(C.POINTER(C.c_float)),
@@ -342,8 +349,8 @@ class Context:
         return out.value
 
 
-def tio_ctx_create(cfg, arena_bytes, host_bytes, slow_tier_bw=0, single_copy_stream=False) -> Context:
-    return Context(cfg, arena_bytes, host_bytes, slow_tier_bw, single_copy_stream)
+def tio_ctx_create(cfg, arena_bytes, host_bytes, slow_tier_bw=0, single_copy_stream=False, arena=None, host=None) -> Context:
+    return Context(cfg, arena_bytes, host_bytes, slow_tier_bw, single_copy_stream, arena, host)
 
 
 def tio_op_gemm(stream_handle, dtype, a_kmajor, b_kmajor, M, N, K, A_ptr, lda, B_ptr, ldb, bias_ptr, resid_ptr, ldr,

@@ -15,6 +15,7 @@
 #include <cmath>
 #include <cstring>
 #include <string>
+#include <thread>
 #include <vector>
 
 #include "analysis.h"
@@ -67,6 +68,7 @@ struct tio_ctx {
 
     Plan plan;                                           // installed plan (copy)
     bool installed = false, params_dirty = true;
+    std::vector<uint8_t> loaded;                         // per parameter: tio_params_load has been called
     std::vector<uint8_t> on_dev;                         // per persistent tensor: latest version is in the arena
     std::vector<uint64_t> dev_addr;
     std::vector<std::vector<uint64_t>> ptrs;             // per kernel, per role: arena offset (UINT64_MAX = absent)
@@ -395,7 +397,7 @@ int tio_ctx_create(const tio_model_cfg *cfg, const tio_runtime_cfg *rt, tio_ctx 
     for (int t = 0; t < c->prog.n_persistent; ++t) { c->home[t] = h; h += c->prog.tensors[t].bytes; }
     c->home_bytes = h;
     if (h > rt->host_bytes) { delete c; return fail(TIO_ERR_OOM_HOST, "slow-tier pool smaller than the persistent tensors"); }
-    std::memset(c->host, 0, h);
+    c->loaded.assign(c->prog.params.size(), 0);
     if (hipHostMalloc((void **)&c->loss_pinned, 4096, hipHostMallocDefault) != hipSuccess) { delete c; return fail(TIO_ERR_HIP, "hipHostMalloc failed"); }
     *out = c;
     return TIO_OK;
@@ -426,15 +428,28 @@ int tio_params_load(tio_ctx *c, int32_t index, const float *v, int64_t numel) {
         c->installed = false;
     }
     const bool bf = c->cfg.precision == TIO_PREC_BF16;
-    if (bf) {
-        uint16_t *w = (uint16_t *)(c->host + c->home[p.w]);
-        float *ms = (float *)(c->host + c->home[p.master]);
-        for (int64_t i = 0; i < numel; ++i) { w[i] = host_f32_to_bf16(v[i]); ms[i] = host_bf16_to_f32(w[i]); }
-    } else {
-        std::memcpy(c->host + c->home[p.w], v, numel * 4);
+    uint8_t *hw = c->host + c->home[p.w], *hm = c->host + c->home[p.m], *hv = c->host + c->home[p.v];
+    uint8_t *hms = bf ? c->host + c->home[p.master] : nullptr;
+    auto fill = [=](int64_t i0, int64_t i1) {
+        if (bf) {
+            uint16_t *w = (uint16_t *)hw;
+            float *ms = (float *)hms;
+            for (int64_t i = i0; i < i1; ++i) { w[i] = host_f32_to_bf16(v[i]); ms[i] = host_bf16_to_f32(w[i]); }
+        } else {
+            std::memcpy(hw + i0 * 4, v + i0, (size_t)(i1 - i0) * 4);
+        }
+        std::memset(hm + i0 * 4, 0, (size_t)(i1 - i0) * 4);
+        std::memset(hv + i0 * 4, 0, (size_t)(i1 - i0) * 4);
+    };
+    const int nthr = numel >= (1 << 22) ? 8 : 1;          // large tensors: split the conversion over host threads
+    if (nthr == 1) fill(0, numel);
+    else {
+        std::vector<std::thread> th;
+        const int64_t per = (numel + nthr - 1) / nthr;
+        for (int t = 0; t < nthr; ++t) th.emplace_back(fill, t * per, std::min(numel, (t + 1) * per));
+        for (auto &x : th) x.join();
     }
-    std::memset(c->host + c->home[p.m], 0, numel * 4);
-    std::memset(c->host + c->home[p.v], 0, numel * 4);
+    c->loaded[index] = 1;
     c->step = 0;
     return TIO_OK;
     TIO_RT_END
@@ -478,6 +493,8 @@ int tio_train_step(tio_ctx *c, const int32_t *tokens, const int32_t *labels, con
                    tio_step_stats *out) {
     if (!c || !tokens || !labels) return fail(TIO_ERR_INVALID_ARG, "null argument");
     TIO_RT_BEGIN
+    for (size_t i = 0; i < c->loaded.size(); ++i)
+        if (!c->loaded[i]) return fail(TIO_ERR_INVALID_ARG, "parameter " + c->prog.params[i].name + " was never loaded");
     ensure_plan(c, plan);
     c->timeline = (flags & TIO_STEP_TIMELINE) != 0;
     run_step(c, tokens, labels, (flags & TIO_STEP_CAPTURE_GRADS) != 0,
@@ -500,6 +517,8 @@ int tio_profile_iteration(tio_ctx *c, const int32_t *tokens, const int32_t *labe
     tio_trace *h = new tio_trace{c->trace};
     if (mode == TIO_PROFILE_MEASURED) {
         if (!tokens || !labels) { delete h; return fail(TIO_ERR_INVALID_ARG, "null argument"); }
+        for (size_t i = 0; i < c->loaded.size(); ++i)
+            if (!c->loaded[i]) { delete h; return fail(TIO_ERR_INVALID_ARG, "parameter " + c->prog.params[i].name + " was never loaded"); }
         try {
             ensure_plan(c, nullptr);
             const int N = c->trace.n_kernels;

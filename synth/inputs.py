@@ -66,3 +66,32 @@ def to_bf16_round(x: np.ndarray) -> np.ndarray:
     lsb = (u >> 16) & 1
     u = (u + 0x7FFF + lsb) & 0xFFFF0000
     return u.astype(np.uint32).view(np.float32).reshape(x.shape)
+
+
+def iter_params_pooled(specs, seed: int, pool_elems: int = 1 << 27):
+    """Yields (name, float32 array) one tensor at a time for very large models.
+
+    Normal tensors are cut from one seeded pool of N(0, 0.02^2) values at a rotating offset (wrapping
+    around), so a 30-billion-parameter model needs seconds, not minutes, of host time.  The values of
+    different tensors are then not independent, which is irrelevant for what these workloads measure
+    (throughput and tensor traffic depend on shapes only).
+    """
+    rng = np.random.default_rng(seed)
+    pool = rng.standard_normal(pool_elems, dtype=np.float32) * np.float32(0.02)
+    off = 0
+    for name, shape, init in specs:
+        n = int(np.prod(shape))
+        if init == "ones":
+            yield name, np.ones(shape, dtype=np.float32)
+        elif init == "zeros":
+            yield name, np.zeros(shape, dtype=np.float32)
+        else:
+            out = np.empty(n, dtype=np.float32)
+            done = 0
+            while done < n:
+                take = min(n - done, pool_elems - off)
+                out[done:done + take] = pool[off:off + take]
+                done += take
+                off = (off + take) % pool_elems
+            off = (off + 7919) % pool_elems
+            yield name, out.reshape(shape)
