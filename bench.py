@@ -36,6 +36,9 @@ def main():
     ap.add_argument("--workload", default="gpt2_small_bf16")
     ap.add_argument("--bw", type=float, default=-1, help="slow-tier bytes/s per direction; 0 = unthrottled; default: the workload's (25e9)")
     ap.add_argument("--min-bytes", type=int, default=1 << 20)
+    ap.add_argument("--slow-tier", choices=["auto", "host", "device"], default="auto",
+                    help="where the slow-tier pool lives: pinned host memory, or a device buffer outside the arena "
+                         "(auto: host unless the pool exceeds what this kind of box can pin, about 28 GB)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--modelled-tau", action="store_true", help="plan from modelled instead of measured kernel times")
     args = ap.parse_args()
@@ -84,8 +87,13 @@ def main():
     arena_bytes = max(upe["arena_needed"], cap)
     log(f"{args.workload}: {n_params / 1e9:.3f} B parameters, uncapped peak {peak / 1e9:.2f} GB, cap {cap / 1e9:.2f} GB, "
         f"slow-tier pool {host_bytes / 1e9:.2f} GB at {bw / 1e9:.1f} GB/s")
+    tier = args.slow_tier if args.slow_tier != "auto" else ("host" if host_bytes <= 28 * 10**9 else "device")
     arena = torch.empty(arena_bytes + 8192, dtype=torch.uint8, device="cuda:0")
-    host = torch.empty(host_bytes, dtype=torch.uint8, pin_memory=True)
+    if tier == "host":
+        host = torch.empty(host_bytes, dtype=torch.uint8, pin_memory=True)
+    else:
+        log("slow tier placed in device memory outside the arena (the box cannot pin a pool of this size)")
+        host = torch.empty(host_bytes, dtype=torch.uint8, device="cuda:0")
     log("buffers allocated")
 
     # ---- profile on the uncapped layout, measure the ideal
@@ -117,7 +125,8 @@ def main():
     if pe["host_needed"] + (1 << 20) > host_bytes:
         host = None
         host_bytes = pe["host_needed"] + (1 << 20)
-        host = torch.empty(host_bytes, dtype=torch.uint8, pin_memory=True)
+        host = torch.empty(host_bytes, dtype=torch.uint8, pin_memory=True) if tier == "host" else \
+            torch.empty(host_bytes, dtype=torch.uint8, device="cuda:0")
 
     # ---- capped run: the context sees only `cap` bytes of the arena
     ctx = tio.tio_ctx_create(cfg, cap, host_bytes, bw, arena=arena, host=host)
@@ -161,7 +170,7 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": cfg["precision"],
         "data": "synthetic",
         "config": {"workload": args.workload, "tokens_per_step": S, "mem_cap_bytes": cap, "uncapped_peak_bytes": peak,
-                   "cap_frac_of_peak": cap / peak, "slow_tier_bw_bytes_per_s": bw, "min_bytes": args.min_bytes,
+                   "cap_frac_of_peak": cap / peak, "slow_tier_bw_bytes_per_s": bw, "slow_tier": "pinned host memory" if tier == "host" else "device memory outside the arena (stand-in)", "min_bytes": args.min_bytes,
                    "kernel_times": "modelled" if args.modelled_tau else "measured"},
         "ideal_tokens_per_s": S / ideal_s, "ideal_ms_per_step": ideal_s * 1e3,
         "frac_of_ideal": ideal_s / step_s,

@@ -55,12 +55,13 @@ typedef struct tio_model_cfg {
 typedef struct tio_runtime_cfg {
     void *arena;                     /* device, 256-byte aligned; every tensor lives here */
     uint64_t arena_bytes;
-    void *host_pool;                 /* host, pinned; stands in for the paper's SSD tier */
+    void *host_pool;                 /* slow tier, stands in for the paper's SSD tier: pinned host memory, or
+                                        (pool_on_device) a second device buffer outside the capped arena */
     uint64_t host_bytes;
     void *compute_stream, *d2h_stream, *h2d_stream; /* hipStream_t, default priority; d2h may equal h2d */
     uint64_t slow_tier_bw;           /* bytes/s per direction enforced on the copy streams; 0 = unthrottled */
     int32_t poison_freed;            /* debug: fill released arena ranges with NaN patterns */
-    int32_t reserved;
+    int32_t pool_on_device;          /* 1: host_pool is device memory (hosts that cannot pin enough memory) */
 } tio_runtime_cfg;
 
 typedef struct tio_ctx tio_ctx;

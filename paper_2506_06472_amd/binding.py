@@ -35,7 +35,7 @@ class RuntimeCfg(C.Structure):
     _fields_ = [("arena", C.c_void_p), ("arena_bytes", C.c_uint64), ("host_pool", C.c_void_p),
                 ("host_bytes", C.c_uint64), ("compute_stream", C.c_void_p), ("d2h_stream", C.c_void_p),
                 ("h2d_stream", C.c_void_p), ("slow_tier_bw", C.c_uint64), ("poison_freed", C.c_int32),
-                ("reserved", C.c_int32)]
+                ("pool_on_device", C.c_int32)]
 
 
 class TraceView(C.Structure):
@@ -254,7 +254,7 @@ class Context:
     and a tio_ctx handle created on them."""
 
     def __init__(self, cfg: dict, arena_bytes: int, host_bytes: int, slow_tier_bw: int = 0, single_copy_stream=False,
-                 arena=None, host=None):
+                 arena=None, host=None, pool_on_device=False):
         import torch
         if not torch.cuda.is_available():
             raise RuntimeError("a GPU is required for the runtime part of the library")
@@ -269,13 +269,19 @@ class Context:
         if host is not None and host.numel() < host_bytes:
             raise ValueError("host tensor too small")
         self.arena = arena if arena is not None else torch.empty(arena_bytes, dtype=torch.uint8, device="cuda:0")
-        self.host = host if host is not None else torch.empty(int(host_bytes), dtype=torch.uint8, pin_memory=True)
+        if host is not None:
+            self.host = host
+            pool_on_device = host.is_cuda
+        elif pool_on_device:
+            self.host = torch.empty(int(host_bytes), dtype=torch.uint8, device="cuda:0")
+        else:
+            self.host = torch.empty(int(host_bytes), dtype=torch.uint8, pin_memory=True)
         self.s_compute = torch.cuda.Stream(device="cuda:0")
         self.s_d2h = torch.cuda.Stream(device="cuda:0")
         self.s_h2d = self.s_d2h if single_copy_stream else torch.cuda.Stream(device="cuda:0")
         rt = RuntimeCfg(self.arena.data_ptr(), arena_bytes, self.host.data_ptr(), int(host_bytes),
                         self.s_compute.cuda_stream, self.s_d2h.cuda_stream, self.s_h2d.cuda_stream,
-                        int(slow_tier_bw), 0, 0)
+                        int(slow_tier_bw), 0, 1 if pool_on_device else 0)
         mc = model_cfg(cfg)
         self.h = C.c_void_p()
         torch.cuda.synchronize()
@@ -349,8 +355,9 @@ class Context:
         return out.value
 
 
-def tio_ctx_create(cfg, arena_bytes, host_bytes, slow_tier_bw=0, single_copy_stream=False, arena=None, host=None) -> Context:
-    return Context(cfg, arena_bytes, host_bytes, slow_tier_bw, single_copy_stream, arena, host)
+def tio_ctx_create(cfg, arena_bytes, host_bytes, slow_tier_bw=0, single_copy_stream=False, arena=None, host=None,
+                   pool_on_device=False) -> Context:
+    return Context(cfg, arena_bytes, host_bytes, slow_tier_bw, single_copy_stream, arena, host, pool_on_device)
 
 
 def tio_op_gemm(stream_handle, dtype, a_kmajor, b_kmajor, M, N, K, A_ptr, lda, B_ptr, ldb, bias_ptr, resid_ptr, ldr,

@@ -65,6 +65,7 @@ struct tio_ctx {
     uint64_t home_bytes = 0;
     uint64_t bw = 0;
     double clock_hz = 1e8;
+    bool pool_dev = false;                               // the slow-tier pool is device memory (stand-in when the host cannot pin enough)
 
     Plan plan;                                           // installed plan (copy)
     bool installed = false, params_dirty = true;
@@ -110,7 +111,7 @@ void gather_to_home(tio_ctx *c) {
     if (!c->installed) return;
     for (int t = 0; t < c->prog.n_persistent; ++t)
         if (c->on_dev[t])
-            HIPCHK(hipMemcpy(c->host + c->home[t], c->arena + c->dev_addr[t], c->prog.tensors[t].bytes, hipMemcpyDeviceToHost));
+            HIPCHK(hipMemcpy(c->host + c->home[t], c->arena + c->dev_addr[t], c->prog.tensors[t].bytes, hipMemcpyDefault));
 }
 
 void install_plan(tio_ctx *c, const Plan &p) {
@@ -140,7 +141,7 @@ void install_plan(tio_ctx *c, const Plan &p) {
             if (!al.whole_cycle && al.born_by_pair >= 0 && al.first == 0) by_prefetch_at_0 = true;
         }
         if (by_prefetch_at_0) continue;
-        HIPCHK(hipMemcpy(c->arena + a, c->host + c->home[t], c->prog.tensors[t].bytes, hipMemcpyHostToDevice));
+        HIPCHK(hipMemcpy(c->arena + a, c->host + c->home[t], c->prog.tensors[t].bytes, hipMemcpyDefault));
         c->on_dev[t] = 1;
         c->dev_addr[t] = a;
     }
@@ -221,7 +222,7 @@ void paced_copy(tio_ctx *c, hipStream_t s, int slot, void *dst, const void *src,
         ticks = std::min(ticks, 30.0 * c->clock_hz);         // bounded wait
         k::paced_copy(s, dst, src, (int64_t)bytes, (unsigned long long)ticks);
     } else {
-        HIPCHK(hipMemcpyAsync(dst, src, bytes, kind, s));
+        HIPCHK(hipMemcpyAsync(dst, src, bytes, c->pool_dev ? hipMemcpyDefault : kind, s));
     }
 }
 
@@ -390,6 +391,7 @@ int tio_ctx_create(const tio_model_cfg *cfg, const tio_runtime_cfg *rt, tio_ctx 
     c->arena_usable = (rt->arena_bytes - kReservedTail) / 256 * 256;
     c->pace_slots = (unsigned long long *)(c->arena + c->arena_usable);
     c->bw = rt->slow_tier_bw;
+    c->pool_dev = rt->pool_on_device != 0;
     int khz = 0;
     if (hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, 0) == hipSuccess && khz > 0) c->clock_hz = khz * 1000.0;
     uint64_t h = 0;
@@ -430,6 +432,14 @@ int tio_params_load(tio_ctx *c, int32_t index, const float *v, int64_t numel) {
     const bool bf = c->cfg.precision == TIO_PREC_BF16;
     uint8_t *hw = c->host + c->home[p.w], *hm = c->host + c->home[p.m], *hv = c->host + c->home[p.v];
     uint8_t *hms = bf ? c->host + c->home[p.master] : nullptr;
+    std::vector<uint8_t> stage;
+    if (c->pool_dev) {                                   // the CPU cannot write the pool: convert into a host buffer first
+        const size_t wb = (size_t)numel * (bf ? 2 : 4);
+        stage.resize(wb + (bf ? (size_t)numel * 4 : 0));
+        hw = stage.data();
+        hms = bf ? stage.data() + wb : nullptr;
+        hm = hv = nullptr;
+    }
     auto fill = [=](int64_t i0, int64_t i1) {
         if (bf) {
             uint16_t *w = (uint16_t *)hw;
@@ -438,8 +448,10 @@ int tio_params_load(tio_ctx *c, int32_t index, const float *v, int64_t numel) {
         } else {
             std::memcpy(hw + i0 * 4, v + i0, (size_t)(i1 - i0) * 4);
         }
-        std::memset(hm + i0 * 4, 0, (size_t)(i1 - i0) * 4);
-        std::memset(hv + i0 * 4, 0, (size_t)(i1 - i0) * 4);
+        if (hm) {
+            std::memset(hm + i0 * 4, 0, (size_t)(i1 - i0) * 4);
+            std::memset(hv + i0 * 4, 0, (size_t)(i1 - i0) * 4);
+        }
     };
     const int nthr = numel >= (1 << 22) ? 8 : 1;          // large tensors: split the conversion over host threads
     if (nthr == 1) fill(0, numel);
@@ -448,6 +460,13 @@ int tio_params_load(tio_ctx *c, int32_t index, const float *v, int64_t numel) {
         const int64_t per = (numel + nthr - 1) / nthr;
         for (int t = 0; t < nthr; ++t) th.emplace_back(fill, t * per, std::min(numel, (t + 1) * per));
         for (auto &x : th) x.join();
+    }
+    if (c->pool_dev) {
+        HIPCHK(hipMemcpy(c->host + c->home[p.w], hw, (size_t)numel * (bf ? 2 : 4), hipMemcpyHostToDevice));
+        if (bf) HIPCHK(hipMemcpy(c->host + c->home[p.master], hms, (size_t)numel * 4, hipMemcpyHostToDevice));
+        HIPCHK(hipMemset(c->host + c->home[p.m], 0, (size_t)numel * 4));
+        HIPCHK(hipMemset(c->host + c->home[p.v], 0, (size_t)numel * 4));
+        HIPCHK(hipDeviceSynchronize());
     }
     c->loaded[index] = 1;
     c->step = 0;
@@ -468,6 +487,7 @@ int tio_params_read(tio_ctx *c, int32_t index, int32_t which, float *dst, int64_
     const uint64_t nbytes = (uint64_t)numel * (half ? 2 : 4);
     std::vector<uint8_t> tmp(nbytes);
     if (c->installed && !c->params_dirty && c->on_dev[t]) HIPCHK(hipMemcpy(tmp.data(), c->arena + c->dev_addr[t], nbytes, hipMemcpyDeviceToHost));
+    else if (c->pool_dev) HIPCHK(hipMemcpy(tmp.data(), c->host + c->home[t], nbytes, hipMemcpyDeviceToHost));
     else std::memcpy(tmp.data(), c->host + c->home[t], nbytes);
     if (half) for (int64_t i = 0; i < numel; ++i) dst[i] = host_bf16_to_f32(((uint16_t *)tmp.data())[i]);
     else std::memcpy(dst, tmp.data(), nbytes);

@@ -172,3 +172,24 @@ def test_errors_are_reported_not_faulted():
     assert e.value.code == -5
     assert ctx.tio_train_step(tok, lab, cp)["loss"] > 0
     ctx.close()
+
+
+def test_slow_tier_in_device_memory_gives_the_same_bits():
+    """The slow-tier pool may be a device buffer outside the arena (hosts that cannot pin enough memory)."""
+    import paper_2506_06472_amd as tio
+    cfg = SMALL_BF16
+    params, tok, lab = make_inputs(cfg, seed=4)
+    lt, ll, up, cp, peak = plans_for(cfg, 0.4, 25 * 10**9, 0)
+    ce = cp.export()
+    names = [n for n, _, _ in tio.tio_param_list(cfg)]
+    out = []
+    for on_dev, bw in ((False, 25 * 10**9), (True, 25 * 10**9), (True, 0)):
+        ctx = tio.tio_ctx_create(cfg, ce["cap"], ce["host_needed"] + (1 << 20), bw, pool_on_device=on_dev)
+        ctx.tio_params_load(params)
+        losses = [ctx.tio_train_step(tok, lab, cp)["loss"] for _ in range(3)]
+        out.append((losses, read_state(ctx, names, True)))
+        ctx.close()
+    for losses, state in out[1:]:
+        assert losses == out[0][0]
+        for key in state:
+            assert state[key].tobytes() == out[0][1][key].tobytes(), key
