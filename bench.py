@@ -26,6 +26,9 @@ sys.path.insert(0, ROOT)
 GEMM_OPS = (2, 9, 10)          # forward, dX, dW contractions (one kernel template)
 ATTN_OPS = (4, 17)
 PEAK_BF16_TFLOPS = 2500.0
+# L2 <-> fabric bytes per GEMM launch from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this command
+# (profiles/gpt2_small_bf16_step_pmc_traffic.txt); None where no such run has been made
+GEMM_TRAFFIC_BYTES_PER_LAUNCH = {"gpt2_small_bf16": 152.59e6}
 
 
 def main():
@@ -158,6 +161,9 @@ def main():
     gemm = np.isin(ops, GEMM_OPS)
     attn = np.isin(ops, ATTN_OPS)
     gemm_ns, gemm_flops, n_gemm = ktimes[gemm].sum(), flops[gemm].sum(), int(gemm.sum())
+    tv = lt.export()
+    gemm_bytes = sum(int(tv["tensor_bytes"][tv["operand_tensor"][tv["operand_off"][k]:tv["operand_off"][k + 1]]].sum())
+                     for k in np.nonzero(gemm)[0])
     gemm_tflops = gemm_flops / gemm_ns / 1e3
     attn_tflops = flops[attn].sum() / ktimes[attn].sum() / 1e3
     comp_s = ktimes.sum() / 1e9
@@ -184,7 +190,9 @@ def main():
         "attention_tflops": attn_tflops, "loss": loss,
         "roofline": {"bound": "mfma", "kernel": "gemm_bf16_k (forward, dX and dW contractions)",
                      "achieved": gemm_tflops, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": gemm_tflops / PEAK_BF16_TFLOPS, "traffic": None,
+                     "frac": gemm_tflops / PEAK_BF16_TFLOPS, "traffic": GEMM_TRAFFIC_BYTES_PER_LAUNCH.get(args.workload),
+                     "traffic_unit": "bytes per launch missing the L2 (rocprofv3 FETCH_SIZE + WRITE_SIZE, calibrated)",
+                     "algorithmic_bytes_per_launch": gemm_bytes / n_gemm,
                      "launches_per_step": n_gemm, "avg_launch_us": gemm_ns / n_gemm / 1e3,
                      "flops_per_step": gemm_flops},
     }

@@ -39,10 +39,16 @@ __global__ void __launch_bounds__(WGM *WGN * 64)
     constexpr int TILE = (BM + BN) * LS;
     uint16_t *As = smem, *Bs = smem + BM * LS;
 
-    // tile order: groups of 8 tile rows walk the columns together, so that workgroups that run at the
-    // same time share operand tiles in L2
+    // Tile order.  Workgroups are dealt to the 8 XCDs round-robin and every XCD has its own L2, so the
+    // launch index is first turned into (xcd, index within the xcd) and each XCD gets one contiguous
+    // eighth of the tile sequence; within the sequence groups of 8 tile rows walk the columns together.
+    // The workgroups that share an L2 then work on neighbouring tiles: the 8 A tiles of the group stay in
+    // that L2 and every B tile is fetched into it once per group, instead of once per XCD per group.
     const int tid = threadIdx.x;
-    int bid = blockIdx.x;
+    const int total_tiles = tiles_m * tiles_n;
+    const int xcd_chunk = (total_tiles + 7) / 8;
+    const int bid = (int)(blockIdx.x % 8) * xcd_chunk + (int)(blockIdx.x / 8);
+    if (bid >= total_tiles) return;          // padding workgroups of the last chunk (whole workgroup, before any barrier)
     constexpr int GROUP = 8;
     const int per_group = GROUP * tiles_n;
     const int g = bid / per_group;
@@ -276,7 +282,7 @@ static void launch_bf16(hipStream_t s, bool a_km, bool b_km, int64_t M, int64_t 
     const int tiles_m = (int)((M + BM - 1) / BM), tiles_n = (int)((N + BN - 1) / BN);
     float *ws = splits > 1 ? (float *)workspace : nullptr;
     const int64_t k_chunk = splits > 1 ? ((K + splits - 1) / splits + BK - 1) / BK * BK : K;
-    const dim3 grid((unsigned)(tiles_m * tiles_n), (unsigned)(splits > 1 ? splits : 1));
+    const dim3 grid((unsigned)(8 * ((tiles_m * tiles_n + 7) / 8)), (unsigned)(splits > 1 ? splits : 1));
     const dim3 block(WGM * WGN * 64);
     constexpr size_t lds = (size_t)NBUF * (BM + BN) * (BK + LDS_PAD) * 2;
     static bool attr_done = false;           // tiles above 64 KiB of LDS need the limit raised once per kernel
