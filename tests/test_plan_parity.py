@@ -144,6 +144,19 @@ def test_stale_and_invalid_arguments_are_reported():
         lt.set_tau([1, 2, 3])
 
 
+@pytest.mark.parametrize("name", ["llama_7b_bf16", "llama_13b_bf16", "llama_30b_bf16"])
+def test_large_configurations_plan_bit_exact_at_full_size(name):
+    """The three Llama-shaped workloads at their stated capacities and bandwidth (modelled kernel times)."""
+    cfg = CONFIGS[name]
+    tr = ot.build_trace(cfg)
+    lt = tio.tio_trace_build(cfg)
+    ll = tio.tio_analyze_lifetimes(lt)
+    life = op.analyze_lifetimes(tr)
+    pl = assert_same_plan(tr, lt, ll, cfg["cap_bytes"], cfg.get("slow_tier_bw", 25 * 10**9), min_bytes=1 << 20)
+    assert pl["bytes_per_direction"] >= max(life["M"]) - cfg["cap_bytes"]
+    assert pl["arena_needed"] <= cfg["cap_bytes"]
+
+
 @pytest.mark.slow
 def test_gpt2_small_plan_bit_exact_at_full_size():
     cfg = CONFIGS["gpt2_small_bf16"]
