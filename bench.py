@@ -188,7 +188,7 @@ def main():
                  "cap_GBps": bw / 1e9},
         "kernel_ms_per_step": comp_s * 1e3, "overlap": 1.0 - max(0.0, step_s - comp_s) / step_s,
         "attention_tflops": attn_tflops, "loss": loss,
-        "roofline": {"bound": "mfma", "kernel": "gemm_bf16_k (forward, dX and dW contractions)",
+        "roofline": {"bound": "mfma", "kernel": "gemm_bf16_pipe_k (forward, dX and dW contractions)",
                      "achieved": gemm_tflops, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": gemm_tflops / PEAK_BF16_TFLOPS, "traffic": GEMM_TRAFFIC_BYTES_PER_LAUNCH.get(args.workload),
                      "traffic_unit": "bytes per launch missing the L2 (rocprofv3 FETCH_SIZE + WRITE_SIZE, calibrated)",

@@ -17,6 +17,12 @@ void norm_fwd(hipStream_t s, int dtype, bool rms, const void *x, const void *g, 
 // rowsum (optional, [M]): sum over k of A[m][k], produced by the same launch (bias gradient of dW);
 // workspace/splits: with splits > 1 and an fp32 workspace of splits*(M*N+M) floats the contraction is
 // cut into `splits` ranges whose partial results are added in order by a second launch
+// pipelined bf16 MFMA GEMM (kernels_gemm_pipe.hip); cfg 0: 128x128 tiles, 1: 256x256 tiles.  Returns false
+// without launching when an operand is too large for its 32-bit buffer offsets.  With ws != nullptr the
+// fp32 split-K partials go to ws and the caller runs the reduction.
+bool gemm_bf16_pipelined(hipStream_t s, int cfg, bool a_km, bool b_km, int64_t M, int64_t N, int64_t K, const void *A,
+                         int64_t lda, const void *B, int64_t ldb, const void *bias, const void *resid, int64_t ldr,
+                         void *C, int64_t ldc, void *rowsum, float *ws, int splits);
 void gemm(hipStream_t s, int dtype, bool a_km, bool b_km, int64_t M, int64_t N, int64_t K, const void *A,
           int64_t lda, const void *B, int64_t ldb, const void *bias, const void *resid, int64_t ldr, void *C,
           int64_t ldc, void *rowsum, void *workspace, int splits);

@@ -1,13 +1,15 @@
 // Dense contractions of the training step: C[M,N] = A . B^T (+bias) (+residual).
 //
-// bf16: MFMA kernel for gfx950 (v_mfma_f32_32x32x16_bf16, fp32 accumulate).  A workgroup owns a
+// bf16: the pipelined MFMA kernel of kernels_gemm_pipe.hip does the work; this file holds the dispatch,
+// the split-K reduction and a plain MFMA kernel with 64-bit addressing that takes over when an operand is
+// too large for the pipelined kernel's 32-bit buffer offsets.  In the plain kernel a workgroup owns a
 // BM x BN tile of C; both operand tiles are staged through LDS in [row][k] order with a 16-byte row
 // pad, so that every MFMA operand is one 16-byte LDS read.  Operands that are stored with the
 // contraction index as the slow dimension ("k-major": the weight in dX = dY.W, both operands in
 // dW = dY^T.X) are transposed in registers in 8x8 blocks on their way into LDS, so no transposed
-// copy of any tensor ever exists in HBM.  The global loads of tile k+1 are issued before the MFMAs
-// of tile k.  The accumulator layout is chosen so that each lane owns 4 consecutive columns of a
-// row of C: the epilogue (bias, residual, rounding to bf16) writes 8 bytes per store.
+// copy of any tensor ever exists in HBM.  The accumulator layout is chosen so that each lane owns
+// 4 consecutive columns of a row of C: the epilogue (bias, residual, rounding to bf16) writes 8 bytes
+// per store.
 //
 // fp32: plain LDS-tiled FMA kernel (used by the small fp32 configurations, which are launch bound).
 #include <cstdlib>
@@ -319,14 +321,23 @@ void gemm(hipStream_t s, int dtype, bool a_km, bool b_km, int64_t M, int64_t N, 
     // split-K needs the fp32 workspace, no epilogue operands and whole float4 rows
     if (dtype != TIO_PREC_BF16 || !workspace || bias || resid || (N % 4) || splits < 2) splits = 1;
     if (dtype == TIO_PREC_BF16) {
-#define TIO_L(BM, BN, BK, WGM, WGN, NBUF) launch_bf16<BM, BN, BK, WGM, WGN, NBUF>(s, a_km, b_km, M, N, K, A, lda, B, ldb, bias, resid, ldr, C, ldc, rowsum, workspace, splits)
-        // 256x256 tiles (128x128 per wavefront: half the LDS traffic per MFMA) pay off once they fill the
-        // GPU and the contraction is long enough to amortise their prologue and epilogue; otherwise 128x128
+        // The pipelined kernel is the default.  Its 256x256 tiles (eight wavefronts, 128x64 each: fewer LDS
+        // bytes per MFMA) pay off once there are at least two rounds of them over the 256 CUs; below that
+        // 128x128 tiles fill the GPU better.  TIO_GEMM_CFG forces a choice: 0 plain kernel, 1 pipelined
+        // 128x128, 2 pipelined 256x256.
         const int64_t big_tiles = ((M + 255) / 256) * ((N + 255) / 256);
-        const int cfg = gemm_cfg_override() >= 0 ? gemm_cfg_override() : ((big_tiles >= 256 && K >= 2048 && splits == 1) ? 4 : 0);
-        if (cfg == 4) TIO_L(256, 256, 64, 2, 2, 1);
-        else TIO_L(128, 128, 64, 2, 2, 1);
-#undef TIO_L
+        const int ov = gemm_cfg_override();
+        const int pipe_cfg = ov == 1 ? 0 : ov == 2 ? 1 : (big_tiles >= 512 ? 1 : 0);
+        if (ov != 0 && gemm_bf16_pipelined(s, pipe_cfg, a_km, b_km, M, N, K, A, lda, B, ldb, bias, resid, ldr, C, ldc, rowsum,
+                                           splits > 1 ? (float *)workspace : nullptr, splits)) {
+            if (splits > 1) {
+                const int64_t n = M * (N / 4) + (rowsum ? M : 0);
+                splitk_reduce_k<<<(unsigned)((n + 255) / 256), 256, 0, s>>>((const float *)workspace, (uint16_t *)C, ldc, (uint16_t *)rowsum, M, N, splits);
+            }
+            return;
+        }
+        // operands too large for 32-bit buffer offsets: plain kernel with 64-bit addressing
+        launch_bf16<128, 128, 64, 2, 2, 1>(s, a_km, b_km, M, N, K, A, lda, B, ldb, bias, resid, ldr, C, ldc, rowsum, workspace, splits);
     } else {
         const dim3 grid((unsigned)((N + 63) / 64), (unsigned)((M + 63) / 64));
 #define TIO_GEMM_ARGS (const float *)A, lda, (const float *)B, ldb, (const float *)bias, (const float *)resid, ldr, (float *)C, ldc, M, N, K, (float *)rowsum

@@ -73,6 +73,58 @@ def test_gemm_all_layouts(dtype, a_km, b_km, M, N, K, pad):
             assert np.all(rs == 7.0)
 
 
+@pytest.mark.parametrize("a_km,b_km", [(0, 0), (0, 1), (1, 1), (1, 0)])
+def test_gemm_large_tile_configuration(a_km, b_km):
+    """Enough 256x256 output tiles for the dispatch to pick the large-tile kernel; ragged in M, N and K."""
+    import torch
+    import paper_2506_06472_amd as tio
+    M, N, K = 5900, 5650, 200
+    print(f"large-tile gemm a_km={a_km} b_km={b_km}", flush=True)
+    g = torch.Generator(device="cuda").manual_seed(11 + 2 * a_km + b_km)
+    r8 = lambda n: (n + 7) // 8 * 8
+    lda, ldb, ldc = (r8(M) if a_km else r8(K)), (r8(N) if b_km else r8(K)), r8(N)
+    dA = torch.randn((K, lda) if a_km else (M, lda), device="cuda", generator=g).to(torch.bfloat16)
+    dB = torch.randn((K, ldb) if b_km else (N, ldb), device="cuda", generator=g).to(torch.bfloat16)
+    # padding must never leak into the result
+    if a_km: dA[:, M:] = float("nan")
+    else: dA[:, K:] = float("nan")
+    if b_km: dB[:, N:] = float("nan")
+    else: dB[:, K:] = float("nan")
+    dC = torch.full((M, ldc), 7.0, device="cuda", dtype=torch.bfloat16)
+    dsum = torch.full((r8(M) + 8,), 7.0, device="cuda", dtype=torch.bfloat16)
+    torch.cuda.synchronize()
+    tio.tio_op_gemm(0, "bf16", a_km, b_km, M, N, K, dA.data_ptr(), lda, dB.data_ptr(), ldb, 0, 0, 0, dC.data_ptr(), ldc,
+                    dsum.data_ptr())
+    torch.cuda.synchronize()
+    A64 = _host(dA)[:, :M].T if a_km else _host(dA)[:, :K]
+    B64 = _host(dB)[:, :N].T if b_km else _host(dB)[:, :K]
+    ref = A64 @ B64.T
+    got = _host(dC)
+    assert np.all(got[:, N:] == 7.0)
+    err = np.abs(got[:, :N] - ref)
+    assert np.all(err <= 2.0 ** -8 * np.abs(ref) + 1e-3 * np.sqrt(K)), float(err.max())
+    rs, ref_rs = _host(dsum), A64.sum(1)
+    assert np.all(np.abs(rs[:M] - ref_rs) <= 2.0 ** -8 * np.abs(ref_rs) + 1e-3 * np.sqrt(K)) and np.all(rs[M:] == 7.0)
+
+
+def test_gemm_operand_beyond_32bit_offsets():
+    """A k-major operand spanning more than 1 GiB takes the kernel with 64-bit addressing."""
+    import torch
+    import paper_2506_06472_amd as tio
+    M, N, K, lda = 136, 72, 8200, 65544
+    g = torch.Generator(device="cuda").manual_seed(5)
+    dA = torch.zeros((K, lda), device="cuda", dtype=torch.bfloat16)
+    dA[:, :M] = torch.randn((K, M), device="cuda", generator=g).to(torch.bfloat16)
+    dB = torch.randn((N, K), device="cuda", generator=g).to(torch.bfloat16)
+    dC = torch.full((M, N), 7.0, device="cuda", dtype=torch.bfloat16)
+    torch.cuda.synchronize()
+    tio.tio_op_gemm(0, "bf16", 1, 0, M, N, K, dA.data_ptr(), lda, dB.data_ptr(), K, 0, 0, 0, dC.data_ptr(), N)
+    torch.cuda.synchronize()
+    ref = _host(dA[:, :M]).T @ _host(dB).T
+    err = np.abs(_host(dC) - ref)
+    assert np.all(err <= 2.0 ** -8 * np.abs(ref) + 1e-3 * np.sqrt(K)), float(err.max())
+
+
 def test_gemm_rejects_bad_arguments():
     import torch
     import paper_2506_06472_amd as tio
