@@ -32,7 +32,7 @@ void rope(hipStream_t s, int dtype, void *qkv, int64_t B, int64_t T, int64_t H, 
 void attn_fwd(hipStream_t s, int dtype, const void *qkv, void *o, float *lse, int64_t B, int64_t T, int64_t H,
               int64_t dh);
 // matrix-core attention (bf16, head dimension 64 or 128); attn_fwd / attn_bwd dispatch to it
-bool attn_mfma_supported(int dtype, int64_t dh);
+bool attn_mfma_supported(int dtype, int64_t T, int64_t H, int64_t dh);
 void attn_fwd_mfma(hipStream_t s, const void *qkv, void *o, float *lse, int64_t B, int64_t T, int64_t H, int64_t dh);
 void attn_bwd_mfma(hipStream_t s, const void *dO, const void *qkv, const float *lse, const float *delta, void *dqkv,
                    int64_t B, int64_t T, int64_t H, int64_t dh);

@@ -142,23 +142,28 @@ __global__ void __launch_bounds__(TPB) attn_fwd_k(const T *__restrict__ qkv, T *
 }
 
 // ---------------------------------------------------------------- backward
+// delta[b,h,t] = sum_e dO[s,h,e] * O[s,h,e].  dh / (elements per 16 bytes) consecutive lanes share one (s, h):
+// the wavefront reads consecutive 16-byte chunks, and the partial sums meet in a fixed xor-shuffle order.
 template <typename T>
 __global__ void __launch_bounds__(TPB) attn_bwd_pre_k(const T *__restrict__ dO, const T *__restrict__ O,
                                                       float *__restrict__ delta, int64_t Bn, int64_t Tn, int64_t H, int64_t dh) {
     constexpr int V = Vec16<T>::N;
-    const int64_t idx = (int64_t)blockIdx.x * TPB + threadIdx.x;    // (s, h)
-    if (idx >= Bn * Tn * H) return;
-    const int64_t s = idx / H, h = idx % H;
-    const int64_t b = s / Tn, t = s % Tn;
-    const T *a = dO + s * H * dh + h * dh, *c = O + s * H * dh + h * dh;
+    const int G = (int)(dh / V);                                     // lanes per (s, h): a power of two, at most 64
+    const int64_t idx = (int64_t)blockIdx.x * TPB + threadIdx.x;    // chunk index = ((s * H + h) * G + g)
+    const bool ok = idx < Bn * Tn * H * G;
     float sum = 0.f;
-    for (int64_t e = 0; e < dh; e += V) {
-        Vec16<T> x, y; x.load(a + e); y.load(c + e);
+    if (ok) {
+        Vec16<T> x, y; x.load(dO + idx * V); y.load(O + idx * V);
         float fx[V], fy[V]; x.get(fx); y.get(fy);
 #pragma unroll
         for (int i = 0; i < V; ++i) sum = fmaf(fx[i], fy[i], sum);
     }
-    delta[(b * H + h) * Tn + t] = sum;
+    for (int o = 1; o < G; o <<= 1) sum += __shfl_xor(sum, o, 64);
+    if (ok && idx % G == 0) {
+        const int64_t sh = idx / G, s = sh / H, h = sh % H;
+        const int64_t b = s / Tn, t = s % Tn;
+        delta[(b * H + h) * Tn + t] = sum;
+    }
 }
 
 // dQ: a query row per lane group, keys and values stream through LDS
@@ -261,7 +266,7 @@ __global__ void __launch_bounds__(TPB) attn_bwd_dkv_k(const T *__restrict__ dO, 
     } while (0)
 
 void attn_fwd(hipStream_t s, int dtype, const void *qkv, void *o, float *lse, int64_t B, int64_t Tn, int64_t H, int64_t dh) {
-    if (attn_mfma_supported(dtype, dh)) { attn_fwd_mfma(s, qkv, o, lse, B, Tn, H, dh); return; }
+    if (attn_mfma_supported(dtype, Tn, H, dh)) { attn_fwd_mfma(s, qkv, o, lse, B, Tn, H, dh); return; }
     const float scale = 1.0f / sqrtf((float)dh);
     TIO_ATTN_DISPATCH(dtype, dh, {
         constexpr int R = TPB / (DH / 32);
@@ -272,7 +277,7 @@ void attn_fwd(hipStream_t s, int dtype, const void *qkv, void *o, float *lse, in
 
 void attn_bwd_pre(hipStream_t s, int dtype, const void *dO, const void *O, float *delta, int64_t B, int64_t Tn, int64_t H,
                   int64_t dh) {
-    const int64_t n = B * Tn * H;
+    const int64_t n = B * Tn * H * (dh / (dtype == TIO_PREC_BF16 ? 8 : 4));
     if (dtype == TIO_PREC_BF16)
         attn_bwd_pre_k<bf16_t><<<(unsigned)((n + TPB - 1) / TPB), TPB, 0, s>>>((const bf16_t *)dO, (const bf16_t *)O, delta, B, Tn, H, dh);
     else
@@ -281,7 +286,7 @@ void attn_bwd_pre(hipStream_t s, int dtype, const void *dO, const void *O, float
 
 void attn_bwd(hipStream_t s, int dtype, const void *dO, const void *qkv, const float *lse, const float *delta, void *dqkv,
               int64_t B, int64_t Tn, int64_t H, int64_t dh) {
-    if (attn_mfma_supported(dtype, dh)) { attn_bwd_mfma(s, dO, qkv, lse, delta, dqkv, B, Tn, H, dh); return; }
+    if (attn_mfma_supported(dtype, Tn, H, dh)) { attn_bwd_mfma(s, dO, qkv, lse, delta, dqkv, B, Tn, H, dh); return; }
     const float scale = 1.0f / sqrtf((float)dh);
     TIO_ATTN_DISPATCH(dtype, dh, {
         constexpr int R = TPB / (DH / 32);

@@ -2,15 +2,18 @@
 // on the packed [S, 3d] q|k|v layout.
 //
 // Each wavefront owns 32 query rows (forward, dQ) or 32 key rows (dK/dV) and keeps their operand
-// fragments in registers for the whole kernel; the other side streams through LDS in tiles of 64 rows.
-// Scores are produced transposed (keys x queries in the forward and dQ kernels, queries x keys in the
-// dK/dV kernel) so that in the accumulator layout of v_mfma_f32_32x32x16_bf16 the row owned by the
+// fragments in registers for the whole kernel; the other side streams through LDS in row-major tiles of
+// 64 rows.  Scores are produced transposed (keys x queries in the forward and dQ kernels, queries x keys
+// in the dK/dV kernel) so that in the accumulator layout of v_mfma_f32_32x32x16_bf16 the row owned by the
 // wavefront is the lane index: the softmax statistics of a row live in one lane (plus one exchange with
 // lane+32), and the probabilities can be fed to the second product straight from registers as its B
 // operand.  The operand whose contraction index is the sequence position (V in P.V, K in dS.K, Q and dO
-// in the dK/dV products) is staged into LDS transposed (8x8 register transposes), and its fragments are
-// read with the slot order the accumulator registers dictate.  Statistics are fp32, exp2 with the
-// 1/sqrt(dh) scale folded into the exponent; the backward pass recomputes P from the saved
+// in the dK/dV products) is read from the same row-major tile with the transposing LDS read
+// (ds_read_b64_tr_b16), in the slot order the accumulator registers dictate: no transposed copies.
+// Tiles are fetched with raw buffer loads (rows past the end of the sequence read as zero) one tile
+// ahead into registers and written to the other half of a double LDS buffer, so a tile costs one barrier.
+// Statistics are fp32, exp2 with the 1/sqrt(dh) scale folded into the exponent; the causal mask is
+// applied only on tiles that cross the diagonal; the backward pass recomputes P from the saved
 // log-sum-exp; dQ and dK/dV are separate launches, so every sum has a fixed order and no atomics.
 #include "../../include/teraio.h"
 #include "device_common.h"
@@ -25,9 +28,18 @@ namespace {
 constexpr int NT = 256;
 constexpr float LOG2E = 1.4426950408889634f;
 constexpr float LN2 = 0.6931471805599453f;
-constexpr int PT = 64 + LDS_PAD;          // row pitch (elements) of the transposed tiles: 64 sequence positions
 
-__device__ __forceinline__ uint32_t pack2(float a, float b) { return f32_to_bf16_bits(a) | (f32_to_bf16_bits(b) << 16); }
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+
+// two floats -> packed bf16 pair, round to nearest even (one v_cvt_pk_bf16_f32)
+__device__ __forceinline__ uint32_t pack2(float a, float b) {
+    union { bf16x2 h; uint32_t u; } c;
+    c.h = __builtin_convertvector((f32x2){a, b}, bf16x2);
+    return c.u;
+}
 
 // B operand of a 16-deep product from accumulator registers R0..R0+7 (the contraction index is the
 // accumulator's row index: slots 0..3 = rows base+4*lhi+0..3, slots 4..7 = rows base+8+4*lhi+0..3)
@@ -42,12 +54,17 @@ __device__ __forceinline__ bf16x8 row_frag(const uint16_t *lds, int pitch, int r
     f.u = *reinterpret_cast<const uint4 *>(lds + row * pitch + col);
     return f.v;
 }
-// A operand from a transposed LDS tile with the slot order of pack8
-__device__ __forceinline__ bf16x8 t_frag(const uint16_t *lds, int row, int colbase, int lhi) {
-    const uint2 a = *reinterpret_cast<const uint2 *>(lds + row * PT + colbase + 4 * lhi);
-    const uint2 b = *reinterpret_cast<const uint2 *>(lds + row * PT + colbase + 8 + 4 * lhi);
-    Frag f;
-    f.u = make_uint4(a.x, a.y, b.x, b.y);
+// A operand "column c0 + lane%32, contraction over rows r0 .. r0+15 in the slot order of pack8" from a
+// row-major LDS tile.  `base` is the per-lane part of the address (see tr_lane_base).
+__device__ __forceinline__ int tr_lane_base(int pitch, int lane) {
+    return (4 * (lane >> 5) + ((lane & 15) >> 2)) * pitch + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
+}
+__device__ __forceinline__ bf16x8 tr_frag(const uint16_t *lds, int pitch, int base, int r0, int c0) {
+    typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+    const uint16_t *p = lds + base + r0 * pitch + c0;
+    union { s16x4 h[2]; bf16x8 v; } f;
+    f.h[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(p));
+    f.h[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(p + 8 * pitch));
     return f.v;
 }
 __device__ __forceinline__ floatx16 zero16() {
@@ -56,47 +73,102 @@ __device__ __forceinline__ floatx16 zero16() {
     for (int i = 0; i < 16; ++i) z[i] = 0.f;
     return z;
 }
-__device__ __forceinline__ bf16x8 global_frag(const uint16_t *p, bool ok) {
-    Frag f;
-    f.u = ok ? *reinterpret_cast<const uint4 *>(p) : make_uint4(0, 0, 0, 0);
-    return f.v;
-}
 // row index inside a 32x32 accumulator tile of register r for lane half lhi
 __device__ __forceinline__ int acc_row(int r, int lhi) { return 8 * (r >> 2) + 4 * lhi + (r & 3); }
 
+__device__ __forceinline__ u32x4 buf_load(__amdgpu_buffer_rsrc_t rsrc, uint32_t off) {
+    return __builtin_amdgcn_raw_buffer_load_b128(rsrc, (int)off, 0, 0);
+}
+// descriptor over rows [0, Tn) of one head's slice: rows at or past Tn read as zero
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t head_rsrc(const uint16_t *base, int64_t Tn, int64_t ld, int dh) {
+    return __builtin_amdgcn_make_buffer_rsrc((void *)base, 0, (int)(((Tn - 1) * ld + dh) * 2), 0x00020000);
+}
+__device__ __forceinline__ bf16x8 buf_frag(__amdgpu_buffer_rsrc_t rsrc, uint32_t off) {
+    union { u32x4 u; bf16x8 v; } f;
+    f.u = buf_load(rsrc, off);
+    return f.v;
+}
+
+// Row pitch of the LDS tiles.  A tile is read both row-wise (16-byte fragments, 16 consecutive rows at a
+// time: the pitch must be an odd multiple of 16 bytes) and through transposing reads (four consecutive
+// rows, 32 bytes each: these must not overlap modulo the 256 bytes the banks span).  144 bytes does both
+// for 128-byte rows; for 256-byte rows 272 would make neighbouring rows overlap, 304 does not.
+template <int DH> constexpr int tile_pitch() { return DH == 128 ? DH + 24 : DH + LDS_PAD; }
+
+// a [64][DH] tile of rows row0.. of one head: registers on the way from memory to LDS ([row][pitch])
+template <int DH> struct RowTile {
+    static constexpr int PITCH = tile_pitch<DH>(), CPR = DH / 8, PER = 64 * CPR / NT, ELEMS = 64 * PITCH;
+    u32x4 r[PER];
+    __device__ __forceinline__ void load(__amdgpu_buffer_rsrc_t rsrc, int64_t row0, uint32_t ld_bytes, int tid) {
+#pragma unroll
+        for (int i = 0; i < PER; ++i) {
+            const int c = tid + i * NT, row = c / CPR, kc = c % CPR;
+            r[i] = buf_load(rsrc, (uint32_t)(row0 + row) * ld_bytes + kc * 16);
+        }
+    }
+    __device__ __forceinline__ void store(uint16_t *lds, int tid) const {
+#pragma unroll
+        for (int i = 0; i < PER; ++i) {
+            const int c = tid + i * NT, row = c / CPR, kc = c % CPR;
+            *reinterpret_cast<u32x4 *>(lds + row * PITCH + kc * 8) = r[i];
+        }
+    }
+};
+
 // ------------------------------------------------------------------------------------------ forward
 template <int DH>
-__global__ void __launch_bounds__(NT) attn_fwd_mfma_k(const uint16_t *__restrict__ qkv, uint16_t *__restrict__ o,
+__global__ void __launch_bounds__(NT, 2) attn_fwd_mfma_k(const uint16_t *__restrict__ qkv, uint16_t *__restrict__ o,
                                                       float *__restrict__ lse, int64_t Tn, int64_t H, float scale) {
-    constexpr int KS = DH / 16, DT = DH / 32, PK = DH + LDS_PAD;
-    __shared__ __attribute__((aligned(16))) uint16_t Ks[64 * PK];
-    __shared__ __attribute__((aligned(16))) uint16_t Vt[DH * PT];
+    constexpr int KS = DH / 16, DT = DH / 32, PK = tile_pitch<DH>(), TE = RowTile<DH>::ELEMS;
+    extern __shared__ __attribute__((aligned(16))) uint16_t smem[];      // [2 buffers][K tile | V tile]
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, l32 = lane & 31, lhi = lane >> 5;
     const int64_t d = H * DH, ld = 3 * d;
+    const uint32_t ldb = (uint32_t)(ld * 2);
     const int64_t bh = blockIdx.y, b = bh / H, h = bh % H;
-    const int64_t q0 = (int64_t)(gridDim.x - 1 - blockIdx.x) * 128;      // longest rows first
-    const int64_t q0w = q0 + wave * 32, q = q0w + l32;
-    const uint16_t *qb = qkv + b * Tn * ld + h * DH, *kb = qb + d, *vb = qb + 2 * d;
+    const int q0 = (int)(gridDim.x - 1 - blockIdx.x) * 128;              // longest rows first
+    const int q0w = q0 + wave * 32, q = q0w + l32;
+    const uint16_t *qb = qkv + b * Tn * ld + h * DH;
+    const __amdgpu_buffer_rsrc_t rsQ = head_rsrc(qb, Tn, ld, DH), rsK = head_rsrc(qb + d, Tn, ld, DH), rsV = head_rsrc(qb + 2 * d, Tn, ld, DH);
     const float c = scale * LOG2E;
+    const int trb = tr_lane_base(PK, lane);
 
     bf16x8 qf[KS];
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) qf[ks] = global_frag(qb + q * ld + ks * 16 + lhi * 8, q < Tn);
+    for (int ks = 0; ks < KS; ++ks) qf[ks] = buf_frag(rsQ, (uint32_t)q * ldb + (ks * 16 + lhi * 8) * 2);
     floatx16 oacc[DT];
 #pragma unroll
     for (int i = 0; i < DT; ++i) oacc[i] = zero16();
-    float m = -INFINITY, l = 0.f;
-    const int64_t kv_end = q0 + 128 < Tn ? q0 + 128 : Tn;
-    for (int64_t j0 = 0; j0 < kv_end; j0 += 64) {
-        Stage<64, DH, NT, false> sk;
-        Stage<DH, 64, NT, true> sv;
-        sk.load(kb, ld, j0, Tn, 0, DH, tid);
-        sv.load(vb, ld, 0, DH, j0, Tn, tid);
-        __syncthreads();
-        sk.store(Ks, tid);
-        sv.store(Vt, tid);
-        __syncthreads();
+    float m = -INFINITY, l = 0.f;                       // reference exponent (log2 domain, scaled) and sum
+    const int kv_end = q0 + 128 < (int)Tn ? q0 + 128 : (int)Tn;
+    const int ntiles = (kv_end + 63) / 64;
+
+    RowTile<DH> tk, tv;
+    tk.load(rsK, 0, ldb, tid);
+    tv.load(rsV, 0, ldb, tid);
+    tk.store(smem, tid);
+    tv.store(smem + TE, tid);
+    if (ntiles > 1) {
+        tk.load(rsK, 64, ldb, tid);
+        tv.load(rsV, 64, ldb, tid);
+    }
+    __syncthreads();
+    for (int t = 0; t < ntiles; ++t) {
+        const int j0 = t * 64;
+        const uint16_t *Ks = smem + (t & 1) * 2 * TE, *Vs = Ks + TE;
+        if (t + 1 < ntiles) {
+            uint16_t *nx = smem + ((t + 1) & 1) * 2 * TE;
+            tk.store(nx, tid);
+            tv.store(nx + TE, tid);
+            if (t + 2 < ntiles) {
+                tk.load(rsK, j0 + 128, ldb, tid);
+                tv.load(rsV, j0 + 128, ldb, tid);
+            }
+        }
         if (j0 <= q0w + 31) {
+            // The tile is handled as two groups of 32 keys.  Both score products are issued first; the
+            // softmax arithmetic of the first group then runs on the vector ALU while the matrix cores
+            // are still busy with the second group's scores, and that of the second group while they
+            // accumulate the first group's P.V.
             floatx16 s[2];
 #pragma unroll
             for (int kt = 0; kt < 2; ++kt) {
@@ -105,44 +177,49 @@ __global__ void __launch_bounds__(NT) attn_fwd_mfma_k(const uint16_t *__restrict
                 for (int ks = 0; ks < KS; ++ks)
                     s[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(row_frag(Ks, PK, kt * 32 + l32, ks * 16 + lhi * 8), qf[ks], s[kt], 0, 0, 0);
             }
-            float tmax = -INFINITY;
-#pragma unroll
-            for (int kt = 0; kt < 2; ++kt)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int64_t kv = j0 + kt * 32 + acc_row(r, lhi);
-                    const float x = kv <= q ? s[kt][r] * c : -INFINITY;
-                    s[kt][r] = x;
-                    tmax = fmaxf(tmax, x);
-                }
-            tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
-            const float mn = fmaxf(m, tmax);
-            const bool dead = mn == -INFINITY;                 // nothing visible to this row yet
-            const float corr = dead ? 1.0f : __builtin_amdgcn_exp2f(m - mn);
-            l *= corr;
-#pragma unroll
-            for (int i = 0; i < DT; ++i)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) oacc[i][r] *= corr;
-#pragma unroll
-            for (int kt = 0; kt < 2; ++kt)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const float p = dead ? 0.0f : __builtin_amdgcn_exp2f(s[kt][r] - mn);
-                    l += p;
-                    s[kt][r] = p;
-                }
-            m = mn;
+            const bool diag = j0 + 63 > q0w;           // the tile crosses the diagonal of some row of this wavefront
 #pragma unroll
             for (int kt = 0; kt < 2; ++kt) {
+                if (diag) {
+#pragma unroll
+                    for (int r = 0; r < 16; ++r)
+                        if (j0 + kt * 32 + acc_row(r, lhi) > q) s[kt][r] = -INFINITY;
+                }
+                float tmax = -INFINITY;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) tmax = fmaxf(tmax, s[kt][r]);
+                tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64)) * c;
+                // The reference exponent m only has to keep exp2(x - m) in range, it need not be the exact
+                // running maximum: it is raised (and the accumulators rescaled) only when some row of the
+                // wavefront exceeds it by more than 2^8, which after the first keys is rare.  Key 0 is
+                // visible to every row, so from the first group on m is finite.
+                if (__any(tmax > m + 8.0f)) {
+                    const float mn = fmaxf(m, tmax);
+                    const float corr = __builtin_amdgcn_exp2f(m - mn);
+                    l *= corr;
+                    m = mn;
+#pragma unroll
+                    for (int i = 0; i < DT; ++i)
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) oacc[i][r] *= corr;
+                }
+                float psum = 0.f;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const float p = __builtin_amdgcn_exp2f(fmaf(s[kt][r], c, -m));
+                    psum += p;
+                    s[kt][r] = p;
+                }
+                l += psum;
                 const bf16x8 p0 = pack8<0>(s[kt]), p1 = pack8<8>(s[kt]);
 #pragma unroll
                 for (int i = 0; i < DT; ++i) {
-                    oacc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(t_frag(Vt, i * 32 + l32, kt * 32, lhi), p0, oacc[i], 0, 0, 0);
-                    oacc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(t_frag(Vt, i * 32 + l32, kt * 32 + 16, lhi), p1, oacc[i], 0, 0, 0);
+                    oacc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tr_frag(Vs, PK, trb, kt * 32, i * 32), p0, oacc[i], 0, 0, 0);
+                    oacc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tr_frag(Vs, PK, trb, kt * 32 + 16, i * 32), p1, oacc[i], 0, 0, 0);
                 }
             }
         }
+        __syncthreads();
     }
     l += __shfl_xor(l, 32, 64);
     if (q < Tn) {
@@ -163,50 +240,60 @@ __global__ void __launch_bounds__(NT) attn_fwd_mfma_k(const uint16_t *__restrict
 
 // ------------------------------------------------------------------------------------------ dQ
 template <int DH>
-__global__ void __launch_bounds__(NT) attn_bwd_dq_mfma_k(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ qkv,
+__global__ void __launch_bounds__(NT, 2) attn_bwd_dq_mfma_k(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ qkv,
                                                          const float *__restrict__ lse, const float *__restrict__ delta,
                                                          uint16_t *__restrict__ dqkv, int64_t Tn, int64_t H, float scale) {
-    constexpr int KS = DH / 16, DT = DH / 32, PK = DH + LDS_PAD;
-    __shared__ __attribute__((aligned(16))) uint16_t Ks[64 * PK];
-    __shared__ __attribute__((aligned(16))) uint16_t Vs[64 * PK];
-    __shared__ __attribute__((aligned(16))) uint16_t Kt[DH * PT];
+    constexpr int KS = DH / 16, DT = DH / 32, PK = tile_pitch<DH>(), TE = RowTile<DH>::ELEMS;
+    extern __shared__ __attribute__((aligned(16))) uint16_t smem[];      // [2 buffers][K tile | V tile]
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, l32 = lane & 31, lhi = lane >> 5;
     const int64_t d = H * DH, ld = 3 * d;
+    const uint32_t ldb = (uint32_t)(ld * 2);
     const int64_t bh = blockIdx.y, b = bh / H, h = bh % H;
-    const int64_t q0 = (int64_t)(gridDim.x - 1 - blockIdx.x) * 128;
-    const int64_t q0w = q0 + wave * 32, q = q0w + l32;
-    const uint16_t *qb = qkv + b * Tn * ld + h * DH, *kb = qb + d, *vb = qb + 2 * d;
-    const uint16_t *gb = dO + b * Tn * d + h * DH;
+    const int q0 = (int)(gridDim.x - 1 - blockIdx.x) * 128;
+    const int q0w = q0 + wave * 32, q = q0w + l32;
+    const uint16_t *qb = qkv + b * Tn * ld + h * DH;
+    const __amdgpu_buffer_rsrc_t rsQ = head_rsrc(qb, Tn, ld, DH), rsK = head_rsrc(qb + d, Tn, ld, DH), rsV = head_rsrc(qb + 2 * d, Tn, ld, DH);
+    const __amdgpu_buffer_rsrc_t rsG = head_rsrc(dO + b * Tn * d + h * DH, Tn, d, DH);
     const float c = scale * LOG2E;
     const bool live = q < Tn;
+    const int trb = tr_lane_base(PK, lane);
 
     bf16x8 qf[KS], gf[KS];
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
-        qf[ks] = global_frag(qb + q * ld + ks * 16 + lhi * 8, live);
-        gf[ks] = global_frag(gb + q * d + ks * 16 + lhi * 8, live);
+        qf[ks] = buf_frag(rsQ, (uint32_t)q * ldb + (ks * 16 + lhi * 8) * 2);
+        gf[ks] = buf_frag(rsG, (uint32_t)q * (uint32_t)(d * 2) + (ks * 16 + lhi * 8) * 2);
     }
     const float lse2 = live ? lse[bh * Tn + q] * LOG2E : 0.f;
     const float dl = live ? delta[bh * Tn + q] : 0.f;
     floatx16 dq[DT];
 #pragma unroll
     for (int i = 0; i < DT; ++i) dq[i] = zero16();
-    const int64_t kv_end = q0 + 128 < Tn ? q0 + 128 : Tn;
-    for (int64_t j0 = 0; j0 < kv_end; j0 += 64) {
-        __syncthreads();
-        {
-            Stage<64, DH, NT, false> sk, sv;
-            sk.load(kb, ld, j0, Tn, 0, DH, tid);
-            sv.load(vb, ld, j0, Tn, 0, DH, tid);
-            sk.store(Ks, tid);
-            sv.store(Vs, tid);
+    const int kv_end = q0 + 128 < (int)Tn ? q0 + 128 : (int)Tn;
+    const int ntiles = (kv_end + 63) / 64;
+
+    RowTile<DH> tk, tv;
+    tk.load(rsK, 0, ldb, tid);
+    tv.load(rsV, 0, ldb, tid);
+    tk.store(smem, tid);
+    tv.store(smem + TE, tid);
+    if (ntiles > 1) {
+        tk.load(rsK, 64, ldb, tid);
+        tv.load(rsV, 64, ldb, tid);
+    }
+    __syncthreads();
+    for (int t = 0; t < ntiles; ++t) {
+        const int j0 = t * 64;
+        const uint16_t *Ks = smem + (t & 1) * 2 * TE, *Vs = Ks + TE;
+        if (t + 1 < ntiles) {
+            uint16_t *nx = smem + ((t + 1) & 1) * 2 * TE;
+            tk.store(nx, tid);
+            tv.store(nx + TE, tid);
+            if (t + 2 < ntiles) {
+                tk.load(rsK, j0 + 128, ldb, tid);
+                tv.load(rsV, j0 + 128, ldb, tid);
+            }
         }
-        {
-            Stage<DH, 64, NT, true> st;
-            st.load(kb, ld, 0, DH, j0, Tn, tid);
-            st.store(Kt, tid);
-        }
-        __syncthreads();
         if (j0 <= q0w + 31) {
             floatx16 s[2], dp[2];
 #pragma unroll
@@ -218,24 +305,25 @@ __global__ void __launch_bounds__(NT) attn_bwd_dq_mfma_k(const uint16_t *__restr
                     dp[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(row_frag(Vs, PK, kt * 32 + l32, ks * 16 + lhi * 8), gf[ks], dp[kt], 0, 0, 0);
                 }
             }
-#pragma unroll
-            for (int kt = 0; kt < 2; ++kt)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int64_t kv = j0 + kt * 32 + acc_row(r, lhi);
-                    const float p = kv <= q ? __builtin_amdgcn_exp2f(s[kt][r] * c - lse2) : 0.0f;
-                    s[kt][r] = p * (dp[kt][r] - dl) * scale;
-                }
+            const bool diag = j0 + 63 > q0w;
+            // per group of 32 keys: the element-wise part of one group overlaps the other group's products
 #pragma unroll
             for (int kt = 0; kt < 2; ++kt) {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    float p = __builtin_amdgcn_exp2f(fmaf(s[kt][r], c, -lse2));
+                    if (diag && j0 + kt * 32 + acc_row(r, lhi) > q) p = 0.0f;
+                    s[kt][r] = p * (dp[kt][r] - dl);          // the 1/sqrt(dh) factor is applied once, to the sums
+                }
                 const bf16x8 d0 = pack8<0>(s[kt]), d1 = pack8<8>(s[kt]);
 #pragma unroll
                 for (int i = 0; i < DT; ++i) {
-                    dq[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(t_frag(Kt, i * 32 + l32, kt * 32, lhi), d0, dq[i], 0, 0, 0);
-                    dq[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(t_frag(Kt, i * 32 + l32, kt * 32 + 16, lhi), d1, dq[i], 0, 0, 0);
+                    dq[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tr_frag(Ks, PK, trb, kt * 32, i * 32), d0, dq[i], 0, 0, 0);
+                    dq[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tr_frag(Ks, PK, trb, kt * 32 + 16, i * 32), d1, dq[i], 0, 0, 0);
                 }
             }
         }
+        __syncthreads();
     }
     if (live) {
         uint16_t *orow = dqkv + (b * Tn + q) * ld + h * DH;
@@ -244,91 +332,131 @@ __global__ void __launch_bounds__(NT) attn_bwd_dq_mfma_k(const uint16_t *__restr
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
                 uint2 w;
-                w.x = pack2(dq[i][4 * g], dq[i][4 * g + 1]);
-                w.y = pack2(dq[i][4 * g + 2], dq[i][4 * g + 3]);
+                w.x = pack2(dq[i][4 * g] * scale, dq[i][4 * g + 1] * scale);
+                w.y = pack2(dq[i][4 * g + 2] * scale, dq[i][4 * g + 3] * scale);
                 *reinterpret_cast<uint2 *>(orow + i * 32 + 8 * g + 4 * lhi) = w;
             }
     }
 }
 
 // ------------------------------------------------------------------------------------------ dK, dV
-template <int DH>
-__global__ void __launch_bounds__(NT) attn_bwd_dkv_mfma_k(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ qkv,
+// MODE 0 produces both gradients in one pass.  With head dimension 128 the two accumulators, the K and V
+// fragments and the prefetch registers do not fit the 256 registers that two wavefronts per SIMD allow, so
+// there the work is split: MODE 1 computes dV only (needs S), MODE 2 dK only (needs S and dP).
+template <int DH, int MODE>
+__global__ void __launch_bounds__(NT, 2) attn_bwd_dkv_mfma_k(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ qkv,
                                                           const float *__restrict__ lse, const float *__restrict__ delta,
                                                           uint16_t *__restrict__ dqkv, int64_t Tn, int64_t H, float scale) {
-    constexpr int KS = DH / 16, DT = DH / 32, PK = DH + LDS_PAD;
+    constexpr int KS = DH / 16, DT = DH / 32, PK = tile_pitch<DH>(), TE = RowTile<DH>::ELEMS;
+    constexpr int BUF = 2 * TE + 256;                                    // Q tile | dO tile | 64 lse | 64 delta (floats)
     extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
-    uint16_t *Qs = smem, *Gs = Qs + 64 * PK, *Qt = Gs + 64 * PK, *Gt = Qt + DH * PT;
-    float *L2s = reinterpret_cast<float *>(Gt + DH * PT), *Ds = L2s + 64;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, l32 = lane & 31, lhi = lane >> 5;
     const int64_t d = H * DH, ld = 3 * d;
+    const uint32_t ldb = (uint32_t)(ld * 2), ldg = (uint32_t)(d * 2);
     const int64_t bh = blockIdx.y, b = bh / H, h = bh % H;
-    const int64_t kv0 = (int64_t)blockIdx.x * 128;                        // earliest keys see the most queries: first
-    const int64_t kv0w = kv0 + wave * 32, kv = kv0w + l32;
-    const uint16_t *qb = qkv + b * Tn * ld + h * DH, *kb = qb + d, *vb = qb + 2 * d;
-    const uint16_t *gb = dO + b * Tn * d + h * DH;
+    const int kv0 = (int)blockIdx.x * 128;                                // earliest keys see the most queries: first
+    const int kv0w = kv0 + wave * 32, kv = kv0w + l32;
+    const uint16_t *qb = qkv + b * Tn * ld + h * DH;
+    const __amdgpu_buffer_rsrc_t rsQ = head_rsrc(qb, Tn, ld, DH), rsK = head_rsrc(qb + d, Tn, ld, DH), rsV = head_rsrc(qb + 2 * d, Tn, ld, DH);
+    const __amdgpu_buffer_rsrc_t rsG = head_rsrc(dO + b * Tn * d + h * DH, Tn, d, DH);
     const float c = scale * LOG2E;
     const bool live = kv < Tn;
+    const int trb = tr_lane_base(PK, lane);
+    constexpr bool DO_DV = MODE != 2, DO_DK = MODE != 1;
+    constexpr int NDK = DO_DK ? DT : 1, NDV = DO_DV ? DT : 1, NVF = DO_DK ? KS : 1;
 
-    bf16x8 kf[KS], vf[KS];
+    bf16x8 kf[KS], vf[NVF];
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
-        kf[ks] = global_frag(kb + kv * ld + ks * 16 + lhi * 8, live);
-        vf[ks] = global_frag(vb + kv * ld + ks * 16 + lhi * 8, live);
+        kf[ks] = buf_frag(rsK, (uint32_t)kv * ldb + (ks * 16 + lhi * 8) * 2);
+        if (DO_DK) vf[ks] = buf_frag(rsV, (uint32_t)kv * ldb + (ks * 16 + lhi * 8) * 2);
     }
-    floatx16 dk[DT], dv[DT];
+    floatx16 dk[NDK], dv[NDV];
 #pragma unroll
-    for (int i = 0; i < DT; ++i) { dk[i] = zero16(); dv[i] = zero16(); }
-    for (int64_t i0 = kv0; i0 < Tn; i0 += 64) {
-        __syncthreads();
-        {
-            Stage<64, DH, NT, false> sq, sg;
-            sq.load(qb, ld, i0, Tn, 0, DH, tid);
-            sg.load(gb, d, i0, Tn, 0, DH, tid);
-            sq.store(Qs, tid);
-            sg.store(Gs, tid);
-        }
-        {
-            Stage<DH, 64, NT, true> st;                       // the two transposed tiles use different waves
-            st.load(qb, ld, 0, DH, i0, Tn, tid);
-            st.store(Qt, tid);
-            const int tid2 = (tid + 128) & 255;
-            st.load(gb, d, 0, DH, i0, Tn, tid2);
-            st.store(Gt, tid2);
-        }
+    for (int i = 0; i < NDK; ++i) dk[i] = zero16();
+#pragma unroll
+    for (int i = 0; i < NDV; ++i) dv[i] = zero16();
+    const int ntiles = ((int)Tn - kv0 + 63) / 64;
+
+    RowTile<DH> tq, tg;
+    float st_l = 0.f, st_d = 0.f;                       // statistics of row i0 + tid (threads 0..63)
+    auto load_tile = [&](int i0) {
+        tq.load(rsQ, i0, ldb, tid);
+        tg.load(rsG, i0, ldg, tid);
         if (tid < 64) {
             const bool ok = i0 + tid < Tn;
-            L2s[tid] = ok ? lse[bh * Tn + i0 + tid] * LOG2E : 0.f;
-            Ds[tid] = ok ? delta[bh * Tn + i0 + tid] : 0.f;
+            st_l = ok ? lse[bh * Tn + i0 + tid] * LOG2E : 0.f;
+            st_d = ok ? delta[bh * Tn + i0 + tid] : 0.f;
         }
-        __syncthreads();
+    };
+    auto store_tile = [&](uint16_t *buf) {
+        tq.store(buf, tid);
+        tg.store(buf + TE, tid);
+        if (tid < 64) {
+            float *st = reinterpret_cast<float *>(buf + 2 * TE);
+            st[tid] = st_l;
+            st[64 + tid] = st_d;
+        }
+    };
+    load_tile(kv0);
+    store_tile(smem);
+    if (ntiles > 1) load_tile(kv0 + 64);
+    __syncthreads();
+    for (int t = 0; t < ntiles; ++t) {
+        const int i0 = kv0 + t * 64;
+        const uint16_t *Qs = smem + (t & 1) * BUF, *Gs = Qs + TE;
+        const float *L2s = reinterpret_cast<const float *>(Qs + 2 * TE), *Ds = L2s + 64;
+        if (t + 1 < ntiles) {
+            store_tile(smem + ((t + 1) & 1) * BUF);
+            if (t + 2 < ntiles) load_tile(i0 + 128);
+        }
         if (i0 + 63 >= kv0w) {
+            // masking is needed where some query of the tile precedes some key of this wavefront, and for
+            // rows past the end of the sequence (zero Q and dO, but a zero statistic too)
+            const bool edge = i0 < kv0w + 31 || i0 + 64 > (int)Tn;
 #pragma unroll
             for (int qt = 0; qt < 2; ++qt) {
                 floatx16 s = zero16(), dp = zero16();
 #pragma unroll
                 for (int ks = 0; ks < KS; ++ks) {
                     s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(row_frag(Qs, PK, qt * 32 + l32, ks * 16 + lhi * 8), kf[ks], s, 0, 0, 0);
-                    dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(row_frag(Gs, PK, qt * 32 + l32, ks * 16 + lhi * 8), vf[ks], dp, 0, 0, 0);
+                    if (DO_DK) dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(row_frag(Gs, PK, qt * 32 + l32, ks * 16 + lhi * 8), vf[ks], dp, 0, 0, 0);
                 }
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int ql = qt * 32 + acc_row(r, lhi);
-                    const int64_t qi = i0 + ql;
-                    const float p = (qi >= kv && qi < Tn) ? __builtin_amdgcn_exp2f(s[r] * c - L2s[ql]) : 0.0f;
-                    dp[r] = p * (dp[r] - Ds[ql]) * scale;
-                    s[r] = p;
-                }
-                const bf16x8 p0 = pack8<0>(s), p1 = pack8<8>(s), d0 = pack8<0>(dp), d1 = pack8<8>(dp);
+                for (int r4 = 0; r4 < 4; ++r4) {
+                    // rows 8*r4 + 4*lhi + 0..3 of this 32-row group: their statistics are 16 contiguous bytes
+                    const int ql = qt * 32 + 8 * r4 + 4 * lhi;
+                    const float4 l4 = *reinterpret_cast<const float4 *>(L2s + ql);
+                    const float4 d4 = DO_DK ? *reinterpret_cast<const float4 *>(Ds + ql) : make_float4(0.f, 0.f, 0.f, 0.f);
+                    const float lv[4] = {l4.x, l4.y, l4.z, l4.w}, dvv[4] = {d4.x, d4.y, d4.z, d4.w};
 #pragma unroll
-                for (int i = 0; i < DT; ++i) {
-                    dv[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(t_frag(Gt, i * 32 + l32, qt * 32, lhi), p0, dv[i], 0, 0, 0);
-                    dv[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(t_frag(Gt, i * 32 + l32, qt * 32 + 16, lhi), p1, dv[i], 0, 0, 0);
-                    dk[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(t_frag(Qt, i * 32 + l32, qt * 32, lhi), d0, dk[i], 0, 0, 0);
-                    dk[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(t_frag(Qt, i * 32 + l32, qt * 32 + 16, lhi), d1, dk[i], 0, 0, 0);
+                    for (int e = 0; e < 4; ++e) {
+                        const int r = 4 * r4 + e;
+                        float p = __builtin_amdgcn_exp2f(fmaf(s[r], c, -lv[e]));
+                        if (edge && (i0 + ql + e < kv || i0 + ql + e >= (int)Tn)) p = 0.0f;
+                        if (DO_DK) dp[r] = p * (dp[r] - dvv[e]);     // the 1/sqrt(dh) factor is applied once, to the sums
+                        s[r] = p;
+                    }
+                }
+                if (DO_DV) {
+                    const bf16x8 p0 = pack8<0>(s), p1 = pack8<8>(s);
+#pragma unroll
+                    for (int i = 0; i < NDV; ++i) {
+                        dv[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tr_frag(Gs, PK, trb, qt * 32, i * 32), p0, dv[i], 0, 0, 0);
+                        dv[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tr_frag(Gs, PK, trb, qt * 32 + 16, i * 32), p1, dv[i], 0, 0, 0);
+                    }
+                }
+                if (DO_DK) {
+                    const bf16x8 d0 = pack8<0>(dp), d1 = pack8<8>(dp);
+#pragma unroll
+                    for (int i = 0; i < NDK; ++i) {
+                        dk[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tr_frag(Qs, PK, trb, qt * 32, i * 32), d0, dk[i], 0, 0, 0);
+                        dk[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tr_frag(Qs, PK, trb, qt * 32 + 16, i * 32), d1, dk[i], 0, 0, 0);
+                    }
                 }
             }
         }
+        __syncthreads();
     }
     if (live) {
         uint16_t *krow = dqkv + (b * Tn + kv) * ld + d + h * DH, *vrow = krow + d;
@@ -337,27 +465,42 @@ __global__ void __launch_bounds__(NT) attn_bwd_dkv_mfma_k(const uint16_t *__rest
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
                 uint2 w;
-                w.x = pack2(dk[i][4 * g], dk[i][4 * g + 1]);
-                w.y = pack2(dk[i][4 * g + 2], dk[i][4 * g + 3]);
-                *reinterpret_cast<uint2 *>(krow + i * 32 + 8 * g + 4 * lhi) = w;
-                w.x = pack2(dv[i][4 * g], dv[i][4 * g + 1]);
-                w.y = pack2(dv[i][4 * g + 2], dv[i][4 * g + 3]);
-                *reinterpret_cast<uint2 *>(vrow + i * 32 + 8 * g + 4 * lhi) = w;
+                if (DO_DK) {
+                    w.x = pack2(dk[i % NDK][4 * g] * scale, dk[i % NDK][4 * g + 1] * scale);
+                    w.y = pack2(dk[i % NDK][4 * g + 2] * scale, dk[i % NDK][4 * g + 3] * scale);
+                    *reinterpret_cast<uint2 *>(krow + i * 32 + 8 * g + 4 * lhi) = w;
+                }
+                if (DO_DV) {
+                    w.x = pack2(dv[i % NDV][4 * g], dv[i % NDV][4 * g + 1]);
+                    w.y = pack2(dv[i % NDV][4 * g + 2], dv[i % NDV][4 * g + 3]);
+                    *reinterpret_cast<uint2 *>(vrow + i * 32 + 8 * g + 4 * lhi) = w;
+                }
             }
     }
 }
 
-template <int DH> constexpr size_t dkv_smem() { return (size_t)(2 * 64 * (DH + LDS_PAD) + 2 * DH * PT) * 2 + 128 * 4; }
+template <int DH> constexpr size_t kv_smem() { return (size_t)2 * 2 * RowTile<DH>::ELEMS * 2; }
+template <int DH> constexpr size_t dkv_smem() { return (size_t)2 * (2 * RowTile<DH>::ELEMS + 256) * 2; }
+
+// 32-bit buffer offsets: one head's rows must span less than 2 GiB
+bool fits(int64_t Tn, int64_t H, int64_t dh) { return (Tn + 192) * 3 * H * dh * 2 < ((int64_t)1 << 31); }
 
 }  // namespace
 
-bool attn_mfma_supported(int dtype, int64_t dh) { return dtype == TIO_PREC_BF16 && (dh == 64 || dh == 128); }
+bool attn_mfma_supported(int dtype, int64_t Tn, int64_t H, int64_t dh) {
+    return dtype == TIO_PREC_BF16 && (dh == 64 || dh == 128) && fits(Tn, H, dh);
+}
 
 void attn_fwd_mfma(hipStream_t s, const void *qkv, void *o, float *lse, int64_t B, int64_t Tn, int64_t H, int64_t dh) {
     const dim3 grid((unsigned)((Tn + 127) / 128), (unsigned)(B * H));
     const float scale = 1.0f / sqrtf((float)dh);
-    if (dh == 64) attn_fwd_mfma_k<64><<<grid, NT, 0, s>>>((const uint16_t *)qkv, (uint16_t *)o, lse, Tn, H, scale);
-    else attn_fwd_mfma_k<128><<<grid, NT, 0, s>>>((const uint16_t *)qkv, (uint16_t *)o, lse, Tn, H, scale);
+    static bool attr_set = false;
+    if (!attr_set) {       // head dimension 128 needs more than the default 64 KiB of LDS
+        (void)hipFuncSetAttribute((const void *)attn_fwd_mfma_k<128>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kv_smem<128>());
+        attr_set = true;
+    }
+    if (dh == 64) attn_fwd_mfma_k<64><<<grid, NT, kv_smem<64>(), s>>>((const uint16_t *)qkv, (uint16_t *)o, lse, Tn, H, scale);
+    else attn_fwd_mfma_k<128><<<grid, NT, kv_smem<128>(), s>>>((const uint16_t *)qkv, (uint16_t *)o, lse, Tn, H, scale);
 }
 
 void attn_bwd_mfma(hipStream_t s, const void *dO, const void *qkv, const float *lse, const float *delta, void *dqkv,
@@ -365,17 +508,19 @@ void attn_bwd_mfma(hipStream_t s, const void *dO, const void *qkv, const float *
     const dim3 grid((unsigned)((Tn + 127) / 128), (unsigned)(B * H));
     const float scale = 1.0f / sqrtf((float)dh);
     static bool attr_set = false;
-    if (!attr_set) {       // the dK/dV kernel for head dimension 128 needs more than the default 64 KiB of LDS
-        (void)hipFuncSetAttribute((const void *)attn_bwd_dkv_mfma_k<64>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)dkv_smem<64>());
-        (void)hipFuncSetAttribute((const void *)attn_bwd_dkv_mfma_k<128>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)dkv_smem<128>());
+    if (!attr_set) {
+        (void)hipFuncSetAttribute((const void *)attn_bwd_dq_mfma_k<128>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kv_smem<128>());
+        (void)hipFuncSetAttribute((const void *)attn_bwd_dkv_mfma_k<128, 1>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)dkv_smem<128>());
+        (void)hipFuncSetAttribute((const void *)attn_bwd_dkv_mfma_k<128, 2>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)dkv_smem<128>());
         attr_set = true;
     }
     if (dh == 64) {
-        attn_bwd_dq_mfma_k<64><<<grid, NT, 0, s>>>((const uint16_t *)dO, (const uint16_t *)qkv, lse, delta, (uint16_t *)dqkv, Tn, H, scale);
-        attn_bwd_dkv_mfma_k<64><<<grid, NT, dkv_smem<64>(), s>>>((const uint16_t *)dO, (const uint16_t *)qkv, lse, delta, (uint16_t *)dqkv, Tn, H, scale);
+        attn_bwd_dq_mfma_k<64><<<grid, NT, kv_smem<64>(), s>>>((const uint16_t *)dO, (const uint16_t *)qkv, lse, delta, (uint16_t *)dqkv, Tn, H, scale);
+        attn_bwd_dkv_mfma_k<64, 0><<<grid, NT, dkv_smem<64>(), s>>>((const uint16_t *)dO, (const uint16_t *)qkv, lse, delta, (uint16_t *)dqkv, Tn, H, scale);
     } else {
-        attn_bwd_dq_mfma_k<128><<<grid, NT, 0, s>>>((const uint16_t *)dO, (const uint16_t *)qkv, lse, delta, (uint16_t *)dqkv, Tn, H, scale);
-        attn_bwd_dkv_mfma_k<128><<<grid, NT, dkv_smem<128>(), s>>>((const uint16_t *)dO, (const uint16_t *)qkv, lse, delta, (uint16_t *)dqkv, Tn, H, scale);
+        attn_bwd_dq_mfma_k<128><<<grid, NT, kv_smem<128>(), s>>>((const uint16_t *)dO, (const uint16_t *)qkv, lse, delta, (uint16_t *)dqkv, Tn, H, scale);
+        attn_bwd_dkv_mfma_k<128, 1><<<grid, NT, dkv_smem<128>(), s>>>((const uint16_t *)dO, (const uint16_t *)qkv, lse, delta, (uint16_t *)dqkv, Tn, H, scale);
+        attn_bwd_dkv_mfma_k<128, 2><<<grid, NT, dkv_smem<128>(), s>>>((const uint16_t *)dO, (const uint16_t *)qkv, lse, delta, (uint16_t *)dqkv, Tn, H, scale);
     }
 }
 
