@@ -40,47 +40,83 @@ __global__ void __launch_bounds__(TPB) embed_fwd_k(const int32_t *__restrict__ t
     a.store(x + row * d + c * V);
 }
 
-// One launch: workgroups [0,S) accumulate the rows of repeated tokens in position order (the
-// workgroup of the first occurrence does the work), workgroups [S,S+V) zero the rows of unused ids.
+// The gradient table is zero-filled by a separate launch; then workgroup s, if position s holds the first
+// occurrence of its token id, adds the rows of all occurrences of that id in position order and writes
+// the sum: one writer per row, a fixed order, no atomics.  All threads scan the token array together
+// (a contiguous range each); the occurrences found are collected in LDS in position order.
 template <typename T>
 __global__ void __launch_bounds__(TPB) embed_bwd_k(const T *__restrict__ dx, const int32_t *__restrict__ tok,
-                                                   T *__restrict__ dw, int64_t S, int64_t d, int64_t Vn) {
+                                                   T *__restrict__ dw, int64_t S, int64_t d) {
     constexpr int V = Vec16<T>::N;
+    constexpr int CAP = 1024;                              // occurrences handled per round
+    __shared__ int cnt[TPB + 1];
+    __shared__ int list[CAP];
     const int64_t cpr = d / V;
     const int64_t blk = blockIdx.x;
-    if (blk >= S) {
-        const int32_t id = (int32_t)(blk - S);
-        int found = 0;
-        for (int64_t i = threadIdx.x; i < S; i += TPB) found |= (tok[i] == id);
-        if (__syncthreads_or(found)) return;
-        Vec16<T> z;
-        float f[V];
-#pragma unroll
-        for (int i = 0; i < V; ++i) f[i] = 0.f;
-        z.set(f);
-        for (int64_t c = threadIdx.x; c < cpr; c += TPB) z.store(dw + (int64_t)id * d + c * V);
-        return;
-    }
     const int32_t id = tok[blk];
-    int earlier = 0;
-    for (int64_t i = threadIdx.x; i < blk; i += TPB) earlier |= (tok[i] == id);
-    if (__syncthreads_or(earlier)) return;
-    for (int64_t c = threadIdx.x; c < cpr; c += TPB) {
-        float acc[V];
-#pragma unroll
-        for (int i = 0; i < V; ++i) acc[i] = 0.f;
-        for (int64_t s = blk; s < S; ++s) {
-            if (tok[s] != id) continue;
-            Vec16<T> g;
-            g.load(dx + s * d + c * V);
-            float f[V];
-            g.get(f);
-#pragma unroll
-            for (int i = 0; i < V; ++i) acc[i] += f[i];
+    const int tid = threadIdx.x;
+    const int64_t per = ((S + TPB - 1) / TPB + 3) / 4 * 4;       // a multiple of 4: 16-byte loads of token ids
+    const int64_t lo = tid * per, hi = lo + per < S ? lo + per : S;
+    int n = 0, earlier = 0;
+    {
+        int64_t i = lo;
+        for (; i + 4 <= hi; i += 4) {
+            const int4 t4 = *reinterpret_cast<const int4 *>(tok + i);
+            const int hit = (t4.x == id) + (t4.y == id) + (t4.z == id) + (t4.w == id);
+            n += hit;
+            earlier |= (hit != 0) & ((t4.x == id ? i : t4.y == id ? i + 1 : t4.z == id ? i + 2 : i + 3) < blk);
         }
-        Vec16<T> o;
-        o.set(acc);
-        o.store(dw + (int64_t)id * d + c * V);
+        for (; i < hi; ++i)
+            if (tok[i] == id) { ++n; earlier |= (i < blk); }
+    }
+    if (__syncthreads_or(earlier)) return;
+    cnt[tid] = n;
+    __syncthreads();
+    if (tid == 0) {                                        // exclusive prefix over the threads' counts
+        int run = 0;
+        for (int t = 0; t < TPB; ++t) { const int c = cnt[t]; cnt[t] = run; run += c; }
+        cnt[TPB] = run;
+    }
+    __syncthreads();
+    const int total = cnt[TPB], first = cnt[tid];
+    constexpr int NC = 2;                                  // column chunks a thread owns per pass
+    for (int64_t cb0 = 0; cb0 < cpr; cb0 += (int64_t)NC * TPB) {
+        float acc[NC][V];
+#pragma unroll
+        for (int c = 0; c < NC; ++c)
+#pragma unroll
+            for (int e = 0; e < V; ++e) acc[c][e] = 0.f;
+        for (int base = 0; base < total; base += CAP) {
+            if (total > CAP || cb0 == 0) {                 // (re)build the list of this round's occurrences
+                __syncthreads();
+                int rank = first;
+                for (int64_t i = lo; i < hi; ++i)
+                    if (tok[i] == id) {
+                        if (rank >= base && rank < base + CAP) list[rank - base] = (int)i;
+                        ++rank;
+                    }
+                __syncthreads();
+            }
+            const int m = total - base < CAP ? total - base : CAP;
+            for (int k = 0; k < m; ++k) {
+                const int64_t row = list[k];
+#pragma unroll
+                for (int c = 0; c < NC; ++c) {
+                    const int64_t ch = cb0 + tid + (int64_t)c * TPB;
+                    if (ch < cpr) {
+                        Vec16<T> gvec; gvec.load(dx + row * d + ch * V);
+                        float fv[V]; gvec.get(fv);
+#pragma unroll
+                        for (int e = 0; e < V; ++e) acc[c][e] += fv[e];
+                    }
+                }
+            }
+        }
+#pragma unroll
+        for (int c = 0; c < NC; ++c) {
+            const int64_t ch = cb0 + tid + (int64_t)c * TPB;
+            if (ch < cpr) { Vec16<T> o; o.set(acc[c]); o.store(dw + (int64_t)id * d + ch * V); }
+        }
     }
 }
 
@@ -213,6 +249,91 @@ __global__ void __launch_bounds__(TPB) norm_bwd_k(const T *__restrict__ dy, cons
     for (int64_t i = threadIdx.x; i < NP * d; i += TPB) p[i] = acc[i];
 }
 
+// Same contract as norm_bwd_k, for rows of at most 64*NCH 16-byte chunks: a wavefront owns a row and
+// keeps it in registers between the statistics pass and the output pass (one read of dy and x, no
+// barriers per row); the wavefronts of a workgroup take its rows round-robin, each adds its rows'
+// contributions to the gain / bias gradients in registers in row order, and the four register sets
+// are then added through LDS in wavefront order.
+template <typename T, bool RMS, int NCH>
+__global__ void __launch_bounds__(TPB) norm_bwd_wave_k(const T *__restrict__ dy, const T *__restrict__ x,
+                                                       const float *__restrict__ stats, const T *__restrict__ g,
+                                                       const T *__restrict__ dres, T *__restrict__ dx,
+                                                       float *__restrict__ part, int64_t S, int64_t d, int rows_per_blk) {
+    constexpr int V = Vec16<T>::N;
+    constexpr int NP = RMS ? 1 : 2, NW = TPB / 64;
+    extern __shared__ float lds[];          // NP*d accumulators
+    const int cpr = (int)(d / V);
+    const int64_t r0 = (int64_t)blockIdx.x * rows_per_blk;
+    const int64_t r1 = r0 + rows_per_blk < S ? r0 + rows_per_blk : S;
+    const int w = threadIdx.x >> 6, l = threadIdx.x & 63;
+    constexpr bool KEEP_G = NCH <= 8;       // wider rows re-read the gain (it stays in cache) to save registers
+    float cg[NCH][V], cb[RMS ? 1 : NCH][V];
+    Vec16<T> gv[KEEP_G ? NCH : 1];
+#pragma unroll
+    for (int i = 0; i < NCH; ++i) {
+        if (KEEP_G && l + 64 * i < cpr) gv[i].load(g + (l + 64 * i) * V);
+#pragma unroll
+        for (int e = 0; e < V; ++e) { cg[i][e] = 0.f; if (!RMS) cb[i][e] = 0.f; }
+    }
+    const float inv_d = 1.0f / (float)d;
+    for (int64_t row = r0 + w; row < r1; row += NW) {
+        const float mean = RMS ? 0.f : stats[2 * row];
+        const float rstd = RMS ? stats[row] : stats[2 * row + 1];
+        Vec16<T> a[NCH], b[NCH];
+        float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+        for (int i = 0; i < NCH; ++i) {
+            if (l + 64 * i < cpr) {
+                a[i].load(dy + row * d + (l + 64 * i) * V);
+                b[i].load(x + row * d + (l + 64 * i) * V);
+                if (!KEEP_G) gv[0].load(g + (l + 64 * i) * V);
+                float fa[V], fb[V], fg[V]; a[i].get(fa); b[i].get(fb); gv[KEEP_G ? i : 0].get(fg);
+#pragma unroll
+                for (int e = 0; e < V; ++e) {
+                    const float xh = (fb[e] - mean) * rstd, dxh = fa[e] * fg[e];
+                    s1 += dxh; s2 += dxh * xh;
+                }
+            }
+        }
+        s1 = RMS ? 0.f : wave_sum(s1) * inv_d;
+        s2 = wave_sum(s2) * inv_d;
+#pragma unroll
+        for (int i = 0; i < NCH; ++i) {
+            if (l + 64 * i < cpr) {
+                if (!KEEP_G) gv[0].load(g + (l + 64 * i) * V);
+                float fa[V], fb[V], fg[V], fr[V], out[V]; a[i].get(fa); b[i].get(fb); gv[KEEP_G ? i : 0].get(fg);
+                if (dres) { Vec16<T> r; r.load(dres + row * d + (l + 64 * i) * V); r.get(fr); }
+#pragma unroll
+                for (int e = 0; e < V; ++e) {
+                    const float xh = (fb[e] - mean) * rstd, dxh = fa[e] * fg[e];
+                    out[e] = rstd * (dxh - s1 - xh * s2) + (dres ? fr[e] : 0.f);
+                    cg[i][e] += fa[e] * xh;
+                    if (!RMS) cb[i][e] += fa[e];
+                }
+                Vec16<T> o; o.set(out); o.store(dx + row * d + (l + 64 * i) * V);
+            }
+        }
+    }
+    for (int ww = 0; ww < NW; ++ww) {
+        if (w == ww) {
+#pragma unroll
+            for (int i = 0; i < NCH; ++i) {
+                if (l + 64 * i < cpr) {
+#pragma unroll
+                    for (int e = 0; e < V; ++e) {
+                        const int col = (l + 64 * i) * V + e;
+                        lds[col] = (ww ? lds[col] : 0.f) + cg[i][e];
+                        if (!RMS) lds[d + col] = (ww ? lds[d + col] : 0.f) + cb[i][e];
+                    }
+                }
+            }
+        }
+        __syncthreads();
+    }
+    float *p = part + (int64_t)blockIdx.x * NP * d;
+    for (int64_t i = threadIdx.x; i < NP * d; i += TPB) p[i] = lds[i];
+}
+
 // column sums of the per-workgroup partial rows: 32 columns x 8 row groups per workgroup, each
 // thread adds its rows in order and the eight groups are combined in order
 template <typename T, bool RMS>
@@ -223,11 +344,24 @@ __global__ void __launch_bounds__(TPB) norm_bwd_params_k(const float *__restrict
     const int c = threadIdx.x & 31, rg = threadIdx.x >> 5;
     const int64_t col = (int64_t)blockIdx.x * 32 + c;
     float sg = 0.f, sb = 0.f;
-    if (col < d)
-        for (int64_t b = rg; b < nb; b += 8) {
+    if (col < d) {
+        // eight loads in flight per sum; the additions stay in row order
+        int64_t b = rg;
+        for (; b + 56 < nb; b += 64) {
+            float tg[8], tb[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                tg[u] = part[(b + 8 * u) * NP * d + col];
+                tb[u] = RMS ? 0.f : part[(b + 8 * u) * NP * d + d + col];
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) { sg += tg[u]; sb += tb[u]; }
+        }
+        for (; b < nb; b += 8) {
             sg += part[b * NP * d + col];
             if (!RMS) sb += part[b * NP * d + d + col];
         }
+    }
     red[0][rg][c] = sg;
     red[1][rg][c] = sb;
     __syncthreads();
@@ -464,6 +598,16 @@ __global__ void __launch_bounds__(TPB) fill_u32_k(uint32_t *p, uint32_t value, i
     const int64_t i = (int64_t)blockIdx.x * TPB + threadIdx.x;
     if (i < n) p[i] = value;
 }
+// 16-byte stores, four per thread (p 16-byte aligned, n16 chunks)
+__global__ void __launch_bounds__(TPB) fill_u128_k(uint4 *p, uint32_t value, int64_t n16) {
+    const uint4 v = make_uint4(value, value, value, value);
+    const int64_t base = (int64_t)blockIdx.x * TPB * 4 + threadIdx.x;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        const int64_t i = base + (int64_t)u * TPB;
+        if (i < n16) p[i] = v;
+    }
+}
 
 template <typename T>
 __global__ void __launch_bounds__(TPB) convert_k(const float *__restrict__ src, T *__restrict__ dst, int64_t n) {
@@ -516,7 +660,10 @@ void embed_fwd(hipStream_t s, int dtype, const int32_t *tok, const void *wte, co
 }
 
 void embed_bwd(hipStream_t s, int dtype, const void *dx, const int32_t *tok, void *dwte, int64_t S, int64_t d, int64_t V) {
-    TIO_DISPATCH(dtype, { embed_bwd_k<T><<<(unsigned)(S + V), TPB, 0, s>>>((const T *)dx, tok, (T *)dwte, S, d, V); });
+    // rows of ids that do not occur stay zero
+    const int64_t words = V * d * (dtype == TIO_PREC_BF16 ? 2 : 4) / 4;
+    fill_u32(s, dwte, 0u, words);
+    TIO_DISPATCH(dtype, { embed_bwd_k<T><<<(unsigned)S, TPB, 0, s>>>((const T *)dx, tok, (T *)dwte, S, d); });
 }
 
 void posemb_bwd(hipStream_t s, int dtype, const void *dx, void *dwpe, int64_t B, int64_t Tn, int64_t d) {
@@ -535,13 +682,25 @@ void norm_fwd(hipStream_t s, int dtype, bool rms, const void *x, const void *g, 
     });
 }
 
+#define TIO_NORM_BWD_WAVE(NCH)                                                                                          \
+    do {                                                                                                            \
+        if (rms) norm_bwd_wave_k<T, true, NCH><<<(unsigned)nb, TPB, lds, s>>>((const T *)dy, (const T *)x, stats, (const T *)g, \
+                                                                              (const T *)dres, (T *)dx, part, S, d, rows); \
+        else norm_bwd_wave_k<T, false, NCH><<<(unsigned)nb, TPB, lds, s>>>((const T *)dy, (const T *)x, stats, (const T *)g, \
+                                                                           (const T *)dres, (T *)dx, part, S, d, rows); \
+    } while (0)
+
 void norm_bwd(hipStream_t s, int dtype, bool rms, const void *dy, const void *x, const float *stats, const void *g,
               const void *dres, void *dx, float *part, int64_t S, int64_t d, int64_t nb) {
     const int rows = (int)((S + nb - 1) / nb);
     const size_t lds = ((rms ? 1 : 2) * d + 16) * sizeof(float);
     TIO_DISPATCH(dtype, {
-        if (rms) norm_bwd_k<T, true><<<(unsigned)nb, TPB, lds, s>>>((const T *)dy, (const T *)x, stats, (const T *)g,
-                                                                    (const T *)dres, (T *)dx, part, S, d, rows);
+        const int64_t chunks = d / Vec16<T>::N;          // 16-byte chunks per row; 64 lanes take NCH each
+        if (chunks <= 64 * 2) TIO_NORM_BWD_WAVE(2);
+        else if (chunks <= 64 * 8) TIO_NORM_BWD_WAVE(8);
+        else if (chunks <= 64 * 13 && lds <= 48 * 1024) TIO_NORM_BWD_WAVE(13);   // up to d = 6656 in bf16
+        else if (rms) norm_bwd_k<T, true><<<(unsigned)nb, TPB, lds, s>>>((const T *)dy, (const T *)x, stats, (const T *)g,
+                                                                         (const T *)dres, (T *)dx, part, S, d, rows);
         else norm_bwd_k<T, false><<<(unsigned)nb, TPB, lds, s>>>((const T *)dy, (const T *)x, stats, (const T *)g,
                                                                  (const T *)dres, (T *)dx, part, S, d, rows);
     });
@@ -612,7 +771,14 @@ void adamw(hipStream_t s, int dtype, const void *g, void *w, float *master, floa
 }
 
 void fill_u32(hipStream_t s, void *p, uint32_t value, int64_t n_words) {
-    if (n_words > 0) fill_u32_k<<<blocks_for(n_words, TPB), TPB, 0, s>>>((uint32_t *)p, value, n_words);
+    if (n_words <= 0) return;
+    int64_t done = 0;
+    if ((reinterpret_cast<uintptr_t>(p) & 15) == 0 && n_words >= 1024) {
+        const int64_t n16 = n_words / 4;
+        fill_u128_k<<<blocks_for(n16, TPB * 4), TPB, 0, s>>>((uint4 *)p, value, n16);
+        done = n16 * 4;
+    }
+    if (done < n_words) fill_u32_k<<<blocks_for(n_words - done, TPB), TPB, 0, s>>>((uint32_t *)p + done, value, n_words - done);
 }
 
 void convert_from_f32(hipStream_t s, int dtype, const float *src, void *dst, int64_t n) {

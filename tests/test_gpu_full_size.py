@@ -76,3 +76,43 @@ def test_switching_plans_mid_training_keeps_the_bits():
     for key in a:
         assert a[key].tobytes() == b[key].tobytes(), key
     ref.close(); ctx.close()
+
+
+@pytest.mark.parametrize("d,H,f", [(4096, 32, 11008), (5120, 40, 13824), (6656, 52, 17920)],
+                         ids=["llama7b_width", "llama13b_width", "llama30b_width"])
+def test_one_decoder_layer_at_real_widths_against_oracle(d, H, f):
+    """One Llama decoder layer at the real model width, FFN width and head dimension of the three large
+    workloads, with the token count and the vocabulary reduced so that the CPU oracle finishes in seconds:
+    loss and every gradient tensor against the oracle (float32), under the uncapped plan and bitwise the
+    same under a 60 % cap.  The vocabulary is smaller than the token count, so token ids repeat."""
+    import paper_2506_06472_amd as tio
+    cfg = dict(arch="llama", L=1, d=d, H=H, f=f, V=320, T=200, B=2, precision="bf16", lr=3e-4)
+    print(f"width {d} heads {H} ffn {f}", flush=True)
+    params, tok, lab = make_inputs(cfg, seed=7)
+    bw = 25 * 10**9
+    lt, ll, up, cp, peak = plans_for(cfg, 0.6, bw, 1 << 20)
+    ue, ce = up.export(), cp.export()
+    ctx = tio.tio_ctx_create(cfg, ue["arena_needed"], ue["host_needed"] + (1 << 20), 0)
+    ctx.tio_params_load(params)
+    st = ctx.tio_train_step(tok, lab, None, capture_grads=True)
+    names = [n for n, _, _ in ctx.params]
+    g_gpu = {n: ctx.tio_grads_read(n).astype(np.float64) for n in names}
+    l_unc = [st["loss"], ctx.tio_train_step(tok, lab, None)["loss"]]
+    s_unc = read_state(ctx, names, True)
+    ctx.close()
+    ctx = tio.tio_ctx_create(cfg, ce["cap"], ce["host_needed"] + (1 << 20), bw)
+    ctx.tio_params_load(params)
+    l_cap = [ctx.tio_train_step(tok, lab, cp)["loss"] for _ in range(2)]
+    s_cap = read_state(ctx, names, True)
+    ctx.close()
+    assert np.array(l_unc, np.float32).tobytes() == np.array(l_cap, np.float32).tobytes(), (l_unc, l_cap)
+    for key in s_unc:
+        assert s_unc[key].tobytes() == s_cap[key].tobytes(), key
+    print("oracle forward/backward in float32", flush=True)
+    loss_ref, G = om.forward_backward(cfg, params, tok, lab, dtype=np.float32)
+    assert abs(l_unc[0] - loss_ref) <= 2e-2 * abs(loss_ref), (l_unc[0], loss_ref)
+    for n in names:
+        ref = G[n].astype(np.float64).reshape(g_gpu[n].shape)
+        scale = np.abs(ref).max()
+        if scale > 1e-9:
+            assert np.abs(g_gpu[n] - ref).max() <= 6e-2 * scale, (n, np.abs(g_gpu[n] - ref).max() / scale)
