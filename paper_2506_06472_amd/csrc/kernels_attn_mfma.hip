@@ -115,17 +115,32 @@ template <int DH> struct RowTile {
     }
 };
 
+// Workgroup index -> (batch*head, block of 128 rows).  Workgroups are dealt to the 8 XCDs round-robin and
+// each XCD has its own L2, so all row blocks of one head are given to one XCD (head = 8*i + xcd): the K and
+// V rows of a head are then fetched into one L2 only, and reused there by the head's other row blocks.
+// Returns false for the padding workgroups when the head count is not a multiple of 8.
+__device__ __forceinline__ bool head_and_block(int64_t n_heads, int n_blocks, int64_t &bh, int &blk) {
+    const int id = (int)blockIdx.x, xcd = id & 7, slot = id >> 3;
+    bh = (int64_t)(slot / n_blocks) * 8 + xcd;
+    blk = slot % n_blocks;
+    return bh < n_heads;
+}
+
 // ------------------------------------------------------------------------------------------ forward
 template <int DH>
 __global__ void __launch_bounds__(NT, 2) attn_fwd_mfma_k(const uint16_t *__restrict__ qkv, uint16_t *__restrict__ o,
-                                                      float *__restrict__ lse, int64_t Tn, int64_t H, float scale) {
+                                                      float *__restrict__ lse, int64_t Bn, int64_t Tn, int64_t H, float scale) {
     constexpr int KS = DH / 16, DT = DH / 32, PK = tile_pitch<DH>(), TE = RowTile<DH>::ELEMS;
     extern __shared__ __attribute__((aligned(16))) uint16_t smem[];      // [2 buffers][K tile | V tile]
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, l32 = lane & 31, lhi = lane >> 5;
     const int64_t d = H * DH, ld = 3 * d;
     const uint32_t ldb = (uint32_t)(ld * 2);
-    const int64_t bh = blockIdx.y, b = bh / H, h = bh % H;
-    const int q0 = (int)(gridDim.x - 1 - blockIdx.x) * 128;              // longest rows first
+    const int nblk = (int)((Tn + 127) / 128);
+    int64_t bh;
+    int blk;
+    if (!head_and_block(Bn * H, nblk, bh, blk)) return;
+    const int64_t b = bh / H, h = bh % H;
+    const int q0 = (nblk - 1 - blk) * 128;                               // longest rows first
     const int q0w = q0 + wave * 32, q = q0w + l32;
     const uint16_t *qb = qkv + b * Tn * ld + h * DH;
     const __amdgpu_buffer_rsrc_t rsQ = head_rsrc(qb, Tn, ld, DH), rsK = head_rsrc(qb + d, Tn, ld, DH), rsV = head_rsrc(qb + 2 * d, Tn, ld, DH);
@@ -242,14 +257,18 @@ __global__ void __launch_bounds__(NT, 2) attn_fwd_mfma_k(const uint16_t *__restr
 template <int DH>
 __global__ void __launch_bounds__(NT, 2) attn_bwd_dq_mfma_k(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ qkv,
                                                          const float *__restrict__ lse, const float *__restrict__ delta,
-                                                         uint16_t *__restrict__ dqkv, int64_t Tn, int64_t H, float scale) {
+                                                         uint16_t *__restrict__ dqkv, int64_t Bn, int64_t Tn, int64_t H, float scale) {
     constexpr int KS = DH / 16, DT = DH / 32, PK = tile_pitch<DH>(), TE = RowTile<DH>::ELEMS;
     extern __shared__ __attribute__((aligned(16))) uint16_t smem[];      // [2 buffers][K tile | V tile]
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, l32 = lane & 31, lhi = lane >> 5;
     const int64_t d = H * DH, ld = 3 * d;
     const uint32_t ldb = (uint32_t)(ld * 2);
-    const int64_t bh = blockIdx.y, b = bh / H, h = bh % H;
-    const int q0 = (int)(gridDim.x - 1 - blockIdx.x) * 128;
+    const int nblk = (int)((Tn + 127) / 128);
+    int64_t bh;
+    int blk;
+    if (!head_and_block(Bn * H, nblk, bh, blk)) return;
+    const int64_t b = bh / H, h = bh % H;
+    const int q0 = (nblk - 1 - blk) * 128;
     const int q0w = q0 + wave * 32, q = q0w + l32;
     const uint16_t *qb = qkv + b * Tn * ld + h * DH;
     const __amdgpu_buffer_rsrc_t rsQ = head_rsrc(qb, Tn, ld, DH), rsK = head_rsrc(qb + d, Tn, ld, DH), rsV = head_rsrc(qb + 2 * d, Tn, ld, DH);
@@ -346,15 +365,18 @@ __global__ void __launch_bounds__(NT, 2) attn_bwd_dq_mfma_k(const uint16_t *__re
 template <int DH, int MODE>
 __global__ void __launch_bounds__(NT, 2) attn_bwd_dkv_mfma_k(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ qkv,
                                                           const float *__restrict__ lse, const float *__restrict__ delta,
-                                                          uint16_t *__restrict__ dqkv, int64_t Tn, int64_t H, float scale) {
+                                                          uint16_t *__restrict__ dqkv, int64_t Bn, int64_t Tn, int64_t H, float scale) {
     constexpr int KS = DH / 16, DT = DH / 32, PK = tile_pitch<DH>(), TE = RowTile<DH>::ELEMS;
     constexpr int BUF = 2 * TE + 256;                                    // Q tile | dO tile | 64 lse | 64 delta (floats)
     extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, l32 = lane & 31, lhi = lane >> 5;
     const int64_t d = H * DH, ld = 3 * d;
     const uint32_t ldb = (uint32_t)(ld * 2), ldg = (uint32_t)(d * 2);
-    const int64_t bh = blockIdx.y, b = bh / H, h = bh % H;
-    const int kv0 = (int)blockIdx.x * 128;                                // earliest keys see the most queries: first
+    int64_t bh;
+    int blk;
+    if (!head_and_block(Bn * H, (int)((Tn + 127) / 128), bh, blk)) return;
+    const int64_t b = bh / H, h = bh % H;
+    const int kv0 = blk * 128;                                            // earliest keys see the most queries: first
     const int kv0w = kv0 + wave * 32, kv = kv0w + l32;
     const uint16_t *qb = qkv + b * Tn * ld + h * DH;
     const __amdgpu_buffer_rsrc_t rsQ = head_rsrc(qb, Tn, ld, DH), rsK = head_rsrc(qb + d, Tn, ld, DH), rsV = head_rsrc(qb + 2 * d, Tn, ld, DH);
@@ -492,20 +514,20 @@ bool attn_mfma_supported(int dtype, int64_t Tn, int64_t H, int64_t dh) {
 }
 
 void attn_fwd_mfma(hipStream_t s, const void *qkv, void *o, float *lse, int64_t B, int64_t Tn, int64_t H, int64_t dh) {
-    const dim3 grid((unsigned)((Tn + 127) / 128), (unsigned)(B * H));
+    const dim3 grid((unsigned)(((Tn + 127) / 128) * ((B * H + 7) / 8) * 8));
     const float scale = 1.0f / sqrtf((float)dh);
     static bool attr_set = false;
     if (!attr_set) {       // head dimension 128 needs more than the default 64 KiB of LDS
         (void)hipFuncSetAttribute((const void *)attn_fwd_mfma_k<128>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kv_smem<128>());
         attr_set = true;
     }
-    if (dh == 64) attn_fwd_mfma_k<64><<<grid, NT, kv_smem<64>(), s>>>((const uint16_t *)qkv, (uint16_t *)o, lse, Tn, H, scale);
-    else attn_fwd_mfma_k<128><<<grid, NT, kv_smem<128>(), s>>>((const uint16_t *)qkv, (uint16_t *)o, lse, Tn, H, scale);
+    if (dh == 64) attn_fwd_mfma_k<64><<<grid, NT, kv_smem<64>(), s>>>((const uint16_t *)qkv, (uint16_t *)o, lse, B, Tn, H, scale);
+    else attn_fwd_mfma_k<128><<<grid, NT, kv_smem<128>(), s>>>((const uint16_t *)qkv, (uint16_t *)o, lse, B, Tn, H, scale);
 }
 
 void attn_bwd_mfma(hipStream_t s, const void *dO, const void *qkv, const float *lse, const float *delta, void *dqkv,
                    int64_t B, int64_t Tn, int64_t H, int64_t dh) {
-    const dim3 grid((unsigned)((Tn + 127) / 128), (unsigned)(B * H));
+    const dim3 grid((unsigned)(((Tn + 127) / 128) * ((B * H + 7) / 8) * 8));
     const float scale = 1.0f / sqrtf((float)dh);
     static bool attr_set = false;
     if (!attr_set) {
@@ -515,12 +537,12 @@ void attn_bwd_mfma(hipStream_t s, const void *dO, const void *qkv, const float *
         attr_set = true;
     }
     if (dh == 64) {
-        attn_bwd_dq_mfma_k<64><<<grid, NT, kv_smem<64>(), s>>>((const uint16_t *)dO, (const uint16_t *)qkv, lse, delta, (uint16_t *)dqkv, Tn, H, scale);
-        attn_bwd_dkv_mfma_k<64, 0><<<grid, NT, dkv_smem<64>(), s>>>((const uint16_t *)dO, (const uint16_t *)qkv, lse, delta, (uint16_t *)dqkv, Tn, H, scale);
+        attn_bwd_dq_mfma_k<64><<<grid, NT, kv_smem<64>(), s>>>((const uint16_t *)dO, (const uint16_t *)qkv, lse, delta, (uint16_t *)dqkv, B, Tn, H, scale);
+        attn_bwd_dkv_mfma_k<64, 0><<<grid, NT, dkv_smem<64>(), s>>>((const uint16_t *)dO, (const uint16_t *)qkv, lse, delta, (uint16_t *)dqkv, B, Tn, H, scale);
     } else {
-        attn_bwd_dq_mfma_k<128><<<grid, NT, kv_smem<128>(), s>>>((const uint16_t *)dO, (const uint16_t *)qkv, lse, delta, (uint16_t *)dqkv, Tn, H, scale);
-        attn_bwd_dkv_mfma_k<128, 1><<<grid, NT, dkv_smem<128>(), s>>>((const uint16_t *)dO, (const uint16_t *)qkv, lse, delta, (uint16_t *)dqkv, Tn, H, scale);
-        attn_bwd_dkv_mfma_k<128, 2><<<grid, NT, dkv_smem<128>(), s>>>((const uint16_t *)dO, (const uint16_t *)qkv, lse, delta, (uint16_t *)dqkv, Tn, H, scale);
+        attn_bwd_dq_mfma_k<128><<<grid, NT, kv_smem<128>(), s>>>((const uint16_t *)dO, (const uint16_t *)qkv, lse, delta, (uint16_t *)dqkv, B, Tn, H, scale);
+        attn_bwd_dkv_mfma_k<128, 1><<<grid, NT, dkv_smem<128>(), s>>>((const uint16_t *)dO, (const uint16_t *)qkv, lse, delta, (uint16_t *)dqkv, B, Tn, H, scale);
+        attn_bwd_dkv_mfma_k<128, 2><<<grid, NT, dkv_smem<128>(), s>>>((const uint16_t *)dO, (const uint16_t *)qkv, lse, delta, (uint16_t *)dqkv, B, Tn, H, scale);
     }
 }
 
