@@ -444,32 +444,46 @@ __global__ void __launch_bounds__(TPB) swiglu_bwd_k(const T *__restrict__ dy, co
     b.set(fu); b.store(dgu + row * 2 * f + f + c * V);
 }
 
-// rotation of adjacent pairs of q and k, in place; angle = pos * theta^(-2i/dh), in double
+// rotation of adjacent pairs of q and k, in place; angle = pos * theta^(-2i/dh).  A thread owns one
+// 16-byte column chunk for ROPE_ROWS consecutive rows: the inverse frequencies of its pairs are computed
+// once, in double; per row the angle is formed and reduced to [-pi, pi] in double (two operations), and
+// sine / cosine of the reduced angle are evaluated in float.
+constexpr int ROPE_ROWS = 16;
 template <typename T>
 __global__ void __launch_bounds__(TPB) rope_k(T *__restrict__ qkv, int64_t S, int64_t Tn, int64_t d, int64_t dh,
                                               double log_theta, float sign) {
     constexpr int V = Vec16<T>::N;
     const int64_t cpr = 2 * d / V;                         // q and k columns only
-    const int64_t idx = (int64_t)blockIdx.x * TPB + threadIdx.x;
-    if (idx >= S * cpr) return;
-    const int64_t row = idx / cpr, c = idx % cpr;
+    const int64_t c = (int64_t)blockIdx.x * TPB + threadIdx.x;
+    if (c >= cpr) return;
     const int64_t col = c * V;                             // column in [0, 2d)
-    T *p = qkv + row * 3 * d + col;
-    Vec16<T> a; a.load(p);
-    float f[V]; a.get(f);
-    const double pos = (double)(row % Tn);
+    double inv[V / 2];
 #pragma unroll
     for (int j = 0; j < V; j += 2) {
         const int64_t i = ((col + j) % dh) / 2;
-        const double ang = pos * exp(-2.0 * (double)i / (double)dh * log_theta);
-        double sn, cs;
-        sincos(ang, &sn, &cs);
-        const float cf = (float)cs, sf = sign * (float)sn;
-        const float x0 = f[j], x1 = f[j + 1];
-        f[j] = x0 * cf - x1 * sf;
-        f[j + 1] = x0 * sf + x1 * cf;
+        inv[j / 2] = exp(-2.0 * (double)i / (double)dh * log_theta);
     }
-    a.set(f); a.store(p);
+    const int64_t r0 = (int64_t)blockIdx.y * ROPE_ROWS;
+    const int64_t r1 = r0 + ROPE_ROWS < S ? r0 + ROPE_ROWS : S;
+    constexpr double TWO_PI = 6.283185307179586476925, INV_TWO_PI = 0.15915494309189533577;
+    for (int64_t row = r0; row < r1; ++row) {
+        T *p = qkv + row * 3 * d + col;
+        Vec16<T> a; a.load(p);
+        float f[V]; a.get(f);
+        const double pos = (double)(row % Tn);
+#pragma unroll
+        for (int j = 0; j < V; j += 2) {
+            const double ang = pos * inv[j / 2];
+            const float r = (float)fma(-TWO_PI, rint(ang * INV_TWO_PI), ang);
+            float sn, cs;
+            sincosf(r, &sn, &cs);
+            const float cf = cs, sf = sign * sn;
+            const float x0 = f[j], x1 = f[j + 1];
+            f[j] = x0 * cf - x1 * sf;
+            f[j + 1] = x0 * sf + x1 * cf;
+        }
+        a.set(f); a.store(p);
+    }
 }
 
 // ---------------------------------------------------------------- cross entropy
@@ -744,8 +758,8 @@ void swiglu_bwd(hipStream_t s, int dtype, const void *dact, const void *gu, void
 void rope(hipStream_t s, int dtype, void *qkv, int64_t B, int64_t Tn, int64_t H, int64_t dh, float theta, bool inverse) {
     const int64_t S = B * Tn, d = H * dh;
     TIO_DISPATCH(dtype, {
-        const int64_t n = S * (2 * d / Vec16<T>::N);
-        rope_k<T><<<blocks_for(n, TPB), TPB, 0, s>>>((T *)qkv, S, Tn, d, dh, log((double)theta), inverse ? -1.0f : 1.0f);
+        const dim3 grid(blocks_for(2 * d / Vec16<T>::N, TPB), (unsigned)((S + ROPE_ROWS - 1) / ROPE_ROWS));
+        rope_k<T><<<grid, TPB, 0, s>>>((T *)qkv, S, Tn, d, dh, log((double)theta), inverse ? -1.0f : 1.0f);
     });
 }
 
