@@ -135,7 +135,7 @@ def main():
     ctx = tio.tio_ctx_create(cfg, cap, host_bytes, bw, arena=arena, host=host)
     load_params(ctx)
     first = ctx.tio_train_step(tok, lab, plan)
-    if abs(first["loss"] - np.log(cfg["V"])) > 0.5:
+    if abs(first["loss"] - np.log(cfg["V"])) > 0.03 * np.log(cfg["V"]):      # logits are nearly zero at initialisation
         raise RuntimeError(f"loss at initialisation {first['loss']} is not ln(V) = {np.log(cfg['V'])}")
     for _ in range(max(0, args.warmup - 1)):
         ctx.tio_train_step(tok, lab, plan)

@@ -4,6 +4,7 @@
 // orders (no floating-point atomics) so that results do not depend on timing or addresses.
 #include <stdexcept>
 
+#include <cstdlib>
 #include "../../include/teraio.h"
 #include "device_common.h"
 #include "kernels.h"
@@ -657,6 +658,32 @@ __global__ void __launch_bounds__(TPB) paced_copy_k(uint4 *__restrict__ dst, con
     }
 }
 
+// Pacing of DMA transfers: a copy stream carries a virtual clock in device memory (the time at which the
+// slow-tier channel of that stream becomes free).  channel_open_k, first on the stream for a migration,
+// moves it up to the present if the channel has been idle; channel_wait_k, after each chunk has been
+// copied, advances it by the chunk's transfer time at the emulated bandwidth and holds the stream until
+// that time.  A backlogged stream therefore moves bytes at exactly the emulated rate, whatever the copy
+// engine's own speed and the launch overheads in between.  `limit` bounds every wait.
+__global__ void channel_open_k(unsigned long long *clock, unsigned long long limit) {
+    if (threadIdx.x == 0) {
+        const unsigned long long now = wall_clock64();
+        const unsigned long long v = *clock;
+        if (v < now || v - now > limit) *clock = now;
+    }
+}
+__global__ void channel_wait_k(unsigned long long *clock, unsigned long long ticks, unsigned long long limit) {
+    if (threadIdx.x == 0) {
+        const unsigned long long start = wall_clock64();
+        const unsigned long long due = *clock + ticks;
+        *clock = due;
+        unsigned long long now = start;
+        while (now < due && now - start < limit) {
+            __builtin_amdgcn_s_sleep(16);
+            now = wall_clock64();
+        }
+    }
+}
+
 }  // namespace
 
 #define TIO_DISPATCH(dtype, ...)                                  \
@@ -802,9 +829,18 @@ void convert_from_f32(hipStream_t s, int dtype, const float *src, void *dst, int
 void paced_copy(hipStream_t s, void *dst, const void *src, int64_t bytes, unsigned long long ticks) {
     const int64_t n16 = bytes / 16;
     int wg = (int)((n16 + TPB * 16 - 1) / (TPB * 16));
-    if (wg > PACED_WG) wg = PACED_WG;
+    static int max_wg = 0;
+    if (!max_wg) { const char *e = getenv("TIO_PACED_WG"); max_wg = e ? atoi(e) : PACED_WG; if (max_wg < 1) max_wg = 1; }
+    if (wg > max_wg) wg = max_wg;
     if (wg < 1) wg = 1;
     paced_copy_k<<<wg, TPB, 0, s>>>((uint4 *)dst, (const uint4 *)src, n16, ticks);
+}
+
+void channel_open(hipStream_t s, unsigned long long *clock, unsigned long long limit) {
+    channel_open_k<<<1, 64, 0, s>>>(clock, limit);
+}
+void channel_wait(hipStream_t s, unsigned long long *clock, unsigned long long ticks, unsigned long long limit) {
+    channel_wait_k<<<1, 64, 0, s>>>(clock, ticks, limit);
 }
 
 }  // namespace k

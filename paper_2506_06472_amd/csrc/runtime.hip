@@ -13,6 +13,7 @@
 #include <algorithm>
 #include <chrono>
 #include <cmath>
+#include <cstdlib>
 #include <cstring>
 #include <string>
 #include <thread>
@@ -76,6 +77,12 @@ struct tio_ctx {
     std::vector<hipEvent_t> ev_kernel, ev_off, ev_pre, ev_t0, ev_t1;
     std::vector<uint8_t> rec_kernel, rec_off, rec_pre;
     int step = 0;
+    // Emulated slow-tier bandwidth with a pinned host pool: the copies go through the DMA engines and a
+    // per-stream virtual clock paces them (copy kernels reading or writing host memory were measured to
+    // slow every concurrent compute kernel by about half).  With the pool in device memory the paced
+    // copy kernel is used.
+    bool dma_pacing = false;
+    unsigned long long *chan_clock = nullptr;            // two device words: offload stream, prefetch stream
     float *loss_pinned = nullptr;                         // 4 KiB of pinned host memory owned by the context
     std::vector<std::vector<float>> grads;
     std::vector<int64_t> last_times;                      // per-kernel ns of the last step run with timing
@@ -112,6 +119,9 @@ void gather_to_home(tio_ctx *c) {
     for (int t = 0; t < c->prog.n_persistent; ++t)
         if (c->on_dev[t])
             HIPCHK(hipMemcpy(c->host + c->home[t], c->arena + c->dev_addr[t], c->prog.tensors[t].bytes, hipMemcpyDefault));
+    // a device-to-device hipMemcpy may return before the copy has run, and the context's streams do not
+    // wait for the null stream
+    if (c->pool_dev) HIPCHK(hipDeviceSynchronize());
 }
 
 void install_plan(tio_ctx *c, const Plan &p) {
@@ -145,6 +155,7 @@ void install_plan(tio_ctx *c, const Plan &p) {
         c->on_dev[t] = 1;
         c->dev_addr[t] = a;
     }
+    if (c->pool_dev) HIPCHK(hipDeviceSynchronize());     // see gather_to_home
     c->ptrs.assign(N, std::vector<uint64_t>(kMaxRoles, UINT64_MAX));
     for (int k = 0; k < N; ++k)
         for (int r = 0; r < kMaxRoles; ++r) {
@@ -216,8 +227,18 @@ void launch(tio_ctx *c, int k) {
 }
 
 void paced_copy(tio_ctx *c, hipStream_t s, int slot, void *dst, const void *src, uint64_t bytes, hipMemcpyKind kind) {
-    (void)slot;
-    if (c->bw) {
+    if (c->bw && c->dma_pacing) {
+        // the DMA engine moves the bytes in chunks; after each chunk the stream is held until the emulated
+        // channel would have delivered it
+        const unsigned long long limit = (unsigned long long)(30.0 * c->clock_hz);
+        k::channel_open(s, c->chan_clock + slot, limit);
+        constexpr uint64_t CHUNK = (uint64_t)8 << 20;
+        for (uint64_t off = 0; off < bytes; off += CHUNK) {
+            const uint64_t n = std::min(CHUNK, bytes - off);
+            HIPCHK(hipMemcpyAsync((uint8_t *)dst + off, (const uint8_t *)src + off, n, kind, s));
+            k::channel_wait(s, c->chan_clock + slot, (unsigned long long)((double)n / (double)c->bw * c->clock_hz), limit);
+        }
+    } else if (c->bw) {
         double ticks = (double)bytes / (double)c->bw * c->clock_hz;
         ticks = std::min(ticks, 30.0 * c->clock_hz);         // bounded wait
         k::paced_copy(s, dst, src, (int64_t)bytes, (unsigned long long)ticks);
@@ -401,6 +422,15 @@ int tio_ctx_create(const tio_model_cfg *cfg, const tio_runtime_cfg *rt, tio_ctx 
     if (h > rt->host_bytes) { delete c; return fail(TIO_ERR_OOM_HOST, "slow-tier pool smaller than the persistent tensors"); }
     c->loaded.assign(c->prog.params.size(), 0);
     if (hipHostMalloc((void **)&c->loss_pinned, 4096, hipHostMallocDefault) != hipSuccess) { delete c; return fail(TIO_ERR_HIP, "hipHostMalloc failed"); }
+    if (hipMalloc((void **)&c->chan_clock, 256) != hipSuccess || hipMemset(c->chan_clock, 0, 256) != hipSuccess) {
+        (void)hipHostFree(c->loss_pinned);
+        delete c;
+        return fail(TIO_ERR_HIP, "hipMalloc failed");
+    }
+    {
+        const char *e = getenv("TIO_PACING");             // "kernel" forces the paced copy kernel
+        c->dma_pacing = !c->pool_dev && !(e && std::string(e) == "kernel");
+    }
     *out = c;
     return TIO_OK;
     TIO_RT_END
@@ -414,6 +444,7 @@ int tio_ctx_destroy(tio_ctx *c) {
     destroy_events(c->ev_c0); destroy_events(c->ev_c1);
     if (c->ev_step0) (void)hipEventDestroy(c->ev_step0);
     if (c->loss_pinned) (void)hipHostFree(c->loss_pinned);
+    if (c->chan_clock) (void)hipFree(c->chan_clock);
     delete c;
     return TIO_OK;
 }

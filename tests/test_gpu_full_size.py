@@ -116,3 +116,26 @@ def test_one_decoder_layer_at_real_widths_against_oracle(d, H, f):
         scale = np.abs(ref).max()
         if scale > 1e-9:
             assert np.abs(g_gpu[n] - ref).max() <= 6e-2 * scale, (n, np.abs(g_gpu[n] - ref).max() / scale)
+
+
+def test_gpt2_small_slow_tier_in_device_memory_unpaced():
+    """Full-size tensors with the slow-tier pool in device memory and unthrottled copies: the staging of
+    the initial residency and every migration are device-to-device copies, which complete asynchronously;
+    the losses must still be the bits of the run with a pinned host pool."""
+    import paper_2506_06472_amd as tio
+    cfg = CONFIGS["gpt2_small_bf16"]
+    params, tok, lab = make_inputs(cfg, seed=0)
+    lt, ll, up, cp, peak = plans_for(cfg, cfg["cap_frac"], 25 * 10**9, 1 << 20)
+    ue, ce = up.export(), cp.export()
+    hb = max(ue["host_needed"], ce["host_needed"]) + (1 << 20)
+    runs = {}
+    for label, on_dev, plan, arena_bytes in (("host uncapped", False, None, ue["arena_needed"]),
+                                             ("device uncapped", True, None, ue["arena_needed"]),
+                                             ("device capped", True, cp, ce["cap"])):
+        print(label, flush=True)
+        ctx = tio.tio_ctx_create(cfg, arena_bytes, hb, 0, pool_on_device=on_dev)
+        ctx.tio_params_load(params)
+        runs[label] = [ctx.tio_train_step(tok, lab, plan)["loss"] for _ in range(2)]
+        ctx.close()
+    assert runs["device uncapped"] == runs["host uncapped"], runs
+    assert runs["device capped"] == runs["host uncapped"], runs
