@@ -635,7 +635,9 @@ __global__ void __launch_bounds__(TPB) convert_k(const float *__restrict__ src, 
 // and after every chunk the workgroup sleeps until its share of `ticks` (constant-rate wall clock,
 // bounded by the host) has passed, so the whole transfer takes bytes / bandwidth and the link sees a
 // steady stream.  One launch per migration: no engine switches on the copy stream.
-constexpr int PACED_WG = 32;
+// few workgroups: a resident copy workgroup, even asleep, keeps a compute workgroup that needs the whole
+// register file of a CU (the large GEMM tiles) off that CU
+constexpr int PACED_WG = 8;
 __global__ void __launch_bounds__(TPB) paced_copy_k(uint4 *__restrict__ dst, const uint4 *__restrict__ src, int64_t n16,
                                                     unsigned long long ticks) {
     const unsigned long long t0 = wall_clock64();
