@@ -6,8 +6,10 @@
 // empty address ranges its outputs reuse), then launches kernel k.  A late migration therefore
 // stalls the kernel that needs it and nothing else, which is the paper's "kernel stall".  Urgent
 // entries come first within each direction at every trigger point.  The slow tier is pinned host
-// memory; its bandwidth is enforced by a copy kernel that moves each tensor at the stated rate (one
-// launch per migration on the copy stream); unthrottled runs use hipMemcpyAsync.
+// memory (or a device buffer outside the arena); its bandwidth is enforced per copy stream: DMA copies in
+// chunks, each followed by a one-wavefront kernel that holds the stream until the emulated channel would
+// have delivered the chunk (host pool), or a copy kernel that moves each tensor at the stated rate (device
+// pool); unthrottled runs use plain hipMemcpyAsync.
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
@@ -27,7 +29,7 @@ using namespace tio;
 
 namespace {
 
-constexpr uint64_t kReservedTail = 4096;     // end of the arena kept for the runtime (pacing stamps)
+constexpr uint64_t kReservedTail = 4096;     // end of the arena kept for the runtime
 
 struct HipError { hipError_t e; const char *what; };
 #define HIPCHK(x)                                   \
