@@ -44,6 +44,9 @@ def main():
                          "(auto: host unless the pool exceeds what this kind of box can pin, about 28 GB)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--modelled-tau", action="store_true", help="plan from modelled instead of measured kernel times")
+    ap.add_argument("--micro-batches", type=int, default=1,
+                    help="n > 1: a step is n micro-batches of the workload's batch with gradient accumulation and one "
+                         "AdamW update (n times the tokens per step, same memory cap); not the headline configuration")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -53,7 +56,14 @@ def main():
     import paper_2506_06472_amd as tio
     from synth import CONFIGS, gen_params, gen_tokens, iter_params_pooled, to_bf16_round
 
-    cfg = CONFIGS[args.workload]
+    cfg = dict(CONFIGS[args.workload])
+    base_peak = None
+    if args.micro_batches > 1:
+        # the cap stays that of the workload itself (a fraction of the single-batch peak, or its byte figure)
+        if "cap_frac" in cfg:
+            base_peak = int(tio.tio_analyze_lifetimes(tio.tio_trace_build(cfg)).export()["M"].max())
+        cfg["B"] *= args.micro_batches
+        cfg["micro_batches"] = args.micro_batches
     t_start = time.perf_counter()
     log = lambda *a: print(f"[{time.perf_counter() - t_start:7.1f}s]", *a, file=sys.stderr, flush=True)
     bw = int(args.bw if args.bw >= 0 else cfg.get("slow_tier_bw", 25e9))
@@ -82,7 +92,7 @@ def main():
     ll = tio.tio_analyze_lifetimes(lt)
     M = ll.export()["M"]
     peak = int(M.max())
-    cap = int(cfg["cap_bytes"]) if "cap_bytes" in cfg else int(peak * cfg["cap_frac"]) // 256 * 256
+    cap = int(cfg["cap_bytes"]) if "cap_bytes" in cfg else int((base_peak or peak) * cfg["cap_frac"]) // 256 * 256
     up = tio.tio_build_plan(lt, ll, 2**62, 0)
     upe = up.export()
     prelim = tio.tio_build_plan(lt, ll, cap, bw, min_bytes=args.min_bytes).export()
@@ -178,7 +188,7 @@ def main():
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": step_s * 1e3,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": cfg["precision"],
         "data": "synthetic",
-        "config": {"workload": args.workload, "tokens_per_step": S, "mem_cap_bytes": cap, "uncapped_peak_bytes": peak,
+        "config": {"workload": args.workload, "micro_batches": args.micro_batches, "tokens_per_step": S, "mem_cap_bytes": cap, "uncapped_peak_bytes": peak,
                    "cap_frac_of_peak": cap / peak, "slow_tier_bw_bytes_per_s": bw, "slow_tier": "pinned host memory" if tier == "host" else "device memory outside the arena (stand-in)", "min_bytes": args.min_bytes,
                    "kernel_times": "modelled" if args.modelled_tau else "measured"},
         "ideal_tokens_per_s": S / ideal_s, "ideal_ms_per_step": ideal_s * 1e3,

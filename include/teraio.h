@@ -50,6 +50,9 @@ typedef struct tio_model_cfg {
     int32_t arch, n_layers, d_model, n_heads, d_ff, vocab, seq_len, batch;
     int32_t precision;               /* TIO_PREC_* : element type of weights, activations, gradients */
     float lr, beta1, beta2, adam_eps, weight_decay, norm_eps, rope_theta;
+    int32_t micro_batches;           /* 0 or 1: the whole batch in one pass; n > 1: the batch (a multiple of n) is run as
+                                        n groups of batch/n sequences with gradient accumulation, one AdamW update per step
+                                        (the paper trains with micro-batches, Sections 4.1 and 4.2) */
 } tio_model_cfg;
 
 typedef struct tio_runtime_cfg {

@@ -185,8 +185,35 @@ def forward_backward(cfg, params, tokens, labels, dtype=np.float64, want_grads=T
                      return_logits=False):
     """One forward (and backward) pass.  params: {name: array}; tokens/labels [B,T] int.
 
-    Returns (loss, grads) with grads {name: array} in `dtype`.
+    Returns (loss, grads) with grads {name: array} in `dtype`.  With cfg["micro_batches"] = n > 1 the batch
+    is cut into n groups of B/n sequences that are run one after the other; the loss is the mean over all
+    tokens, so every group contributes its mean loss and mean gradient weighted by its share of the tokens,
+    and the gradients are added up group by group (gradient accumulation; Section 4.1 of the paper trains
+    with micro-batches).
     """
+    n_mb = int(cfg.get("micro_batches", 1) or 1)
+    if n_mb == 1:
+        return _forward_backward_batch(cfg, params, tokens, labels, dtype, want_grads, return_logits)
+    assert not return_logits
+    B = tokens.shape[0]
+    assert B % n_mb == 0
+    g = B // n_mb
+    loss, grads = dtype(0.0), None
+    for j in range(n_mb):
+        lj, gj = _forward_backward_batch(cfg, params, tokens[j * g:(j + 1) * g], labels[j * g:(j + 1) * g], dtype,
+                                         want_grads, False)
+        share = dtype(1.0) / dtype(n_mb)
+        loss = loss + lj * share
+        if want_grads:
+            if grads is None:
+                grads = {k: v * share for k, v in gj.items()}
+            else:
+                for k, v in gj.items():
+                    grads[k] = grads[k] + v * share
+    return loss, grads
+
+
+def _forward_backward_batch(cfg, params, tokens, labels, dtype, want_grads, return_logits):
     a, L, d, H, V = cfg["arch"], cfg["L"], cfg["d"], cfg["H"], cfg["V"]
     eps = cfg.get("eps", 1e-5)
     B, T = tokens.shape

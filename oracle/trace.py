@@ -21,6 +21,14 @@ compute weight, then the fp32 master copy when the precision is bf16, then the
 two AdamW moments), then the token and label buffers, then transient tensors
 in order of first write.
 
+Micro-batches (cfg["micro_batches"] = n > 1; the paper splits each batch into
+micro-batches, Section 4.1 and 4.2): the batch is cut into n groups of B/n
+sequences; the forward and backward schedule runs once per group on tensors of
+that group's size (one token and one label buffer per group, all listed after
+the persistent tensors); parameter gradients and the scalar loss are written by
+the first group and accumulated in place by the later ones; the AdamW launches
+follow the gradient-completing launches of the last group only.
+
 Pins (tests/test_oracle_plan.py): kernel and tensor counts in closed form,
 persistent bytes = 12 or 14 bytes per parameter, every transient written before
 read, peak memory at the loss kernel in closed form.  The exact schedule is a
@@ -90,6 +98,9 @@ class _Builder:
 
 def build_trace(cfg):
     a, L, d, H, f, V, T, B = (cfg[k] for k in ("arch", "L", "d", "H", "f", "V", "T", "B"))
+    n_mb = int(cfg.get("micro_batches", 1) or 1)
+    assert n_mb >= 1 and B % n_mb == 0, "batch must divide into the micro-batches"
+    B //= n_mb                           # from here on: sequences and tokens of one micro-batch
     gpt = a == "gpt"
     bf16 = cfg["precision"] == "bf16"
     e = 2 if bf16 else 4                 # element size of weights, activations, gradients
@@ -108,8 +119,55 @@ def build_trace(cfg):
             b.tensor(name + ".master", n * 4, K_MASTER)
         b.tensor(name + ".m", n * 4, K_M)
         b.tensor(name + ".v", n * 4, K_V)
-    b.tensor("tokens", S * 4, K_INPUT)
-    b.tensor("labels", S * 4, K_INPUT)
+    for j in range(n_mb):
+        pre = "" if n_mb == 1 else f"mb{j}."
+        b.tensor(pre + "tokens", S * 4, K_INPUT)
+        b.tensor(pre + "labels", S * 4, K_INPUT)
+    n_persistent = len(b.tensors)
+    for j in range(n_mb):
+        _micro_batch(b, cfg, j, n_mb, B, S, Vp, e, specs)
+
+    tau = []
+    for op, operands, flops in b.kernels:
+        nbytes = sum(b.tensors[t][0] for t, _ in operands)
+        tf = -(-flops * 10**9 // MODEL_FLOPS_PER_S)
+        tb = -(-nbytes * 10**9 // MODEL_BYTES_PER_S)
+        tau.append(max(tf, tb) + MODEL_LAUNCH_NS)
+    return dict(tensors=b.tensors, kernels=b.kernels, tau=tau, ids=b.ids, n_persistent=n_persistent)
+
+
+def _micro_batch(b, cfg, j, n_mb, B, S, Vp, e, specs):
+    """Appends the forward and backward launches of micro-batch j (B sequences, S tokens)."""
+    a, L, d, H, f, V, T = (cfg[k] for k in ("arch", "L", "d", "H", "f", "V", "T"))
+    gpt = a == "gpt"
+    bf16 = cfg["precision"] == "bf16"
+    first, last = j == 0, j == n_mb - 1
+    pre = "" if n_mb == 1 else f"mb{j}."          # transient tensors of this micro-batch
+    shared = set()
+    for name, _, _ in specs:
+        shared.update((name, name + ".master", name + ".m", name + ".v"))
+    # names of persistent tensors, gradients and the loss are shared by all micro-batches
+    q = lambda n: n if (n in shared or n.startswith("g.") or n == "loss") else pre + n
+
+    class _Scoped:
+        ids = b.ids
+        tensors = b.tensors
+
+        @staticmethod
+        def tensor(name, nbytes, kind):
+            return b.tensor(q(name), nbytes, kind)
+
+        @staticmethod
+        def kernel(op, reads=(), writes=(), inouts=(), flops=0):
+            b.kernel(op, [q(n) for n in reads], [q(n) for n in writes], [q(n) for n in inouts], flops)
+
+    _schedule(_Scoped, cfg, first, last, B, S, Vp, e)
+
+
+def _schedule(b, cfg, first, last, B, S, Vp, e):
+    a, L, d, H, f, V, T = (cfg[k] for k in ("arch", "L", "d", "H", "f", "V", "T"))
+    gpt = a == "gpt"
+    bf16 = cfg["precision"] == "bf16"
 
     act = lambda name, n, es=e: b.tensor(name, n * es, K_ACT)
     grd = lambda name, n, es=e: b.tensor(name, n * es, K_GRAD)
@@ -162,17 +220,27 @@ def build_trace(cfg):
     b.kernel(GEMM, reads=["hf", "w_head"], writes=["logits"], flops=2 * S * V * d)
     act("losses", S, 4)
     b.kernel(CE_FWD_BWD, reads=["labels"], inouts=["logits"], writes=["losses"])
-    act("loss", 1, 4)
-    b.kernel(LOSS_REDUCE, reads=["losses"], writes=["loss"])
+    if first:
+        act("loss", 1, 4)
+        b.kernel(LOSS_REDUCE, reads=["losses"], writes=["loss"])
+    else:                                # adds this micro-batch's share to the running loss
+        b.kernel(LOSS_REDUCE, reads=["losses"], inouts=["loss"])
 
     # ---- backward
     def pgrad(name):
-        idx = b.ids[name]
-        return b.tensor("g." + name, b.tensors[idx][0] if not bf16 else b.tensors[idx][0], K_PGRAD)
+        # gradient tensor of a parameter: created by the first micro-batch, accumulated into by the others
+        if first:
+            b.tensor("g." + name, b.tensors[b.ids[name]][0], K_PGRAD)
+
+    def gout(names):
+        """operand lists of a launch that produces parameter gradients: (writes, inouts)"""
+        return (names, []) if first else ([], names)
 
     def adamw(name):
         # the update of a parameter follows the launch that completes its gradient (no later kernel of the
         # iteration reads the parameter), so gradients die at once and optimizer traffic overlaps the backward pass
+        if not last:
+            return
         state = [name] + ([name + ".master"] if bf16 else []) + [name + ".m", name + ".v"]
         b.kernel(ADAMW, reads=["g." + name], inouts=state)
 
@@ -181,7 +249,8 @@ def build_trace(cfg):
         b.kernel(NORM_BWD, reads=[dy, xin, st, pnames[0]] + ([dres] if dres else []), writes=[dx, part])
         for n in pnames:
             pgrad(n)
-        b.kernel(NORM_BWD_PARAMS, reads=[part], writes=["g." + n for n in pnames])
+        gw, gio = gout(["g." + n for n in pnames])
+        b.kernel(NORM_BWD_PARAMS, reads=[part], writes=gw, inouts=gio)
         for n in pnames:
             adamw(n)
 
@@ -194,8 +263,8 @@ def build_trace(cfg):
         if splits > 1:                                   # fp32 partial tiles and partial row sums
             grd("ws." + w, splits * (n_out * n_in + n_out), 4)
             ws = ["ws." + w]
-        b.kernel(GEMM_DW, reads=[dy, xin], writes=["g." + w] + (["g." + bias] if bias else []), inouts=ws,
-                 flops=2 * S * n_in * n_out)
+        gw, gio = gout(["g." + w] + (["g." + bias] if bias else []))
+        b.kernel(GEMM_DW, reads=[dy, xin], writes=gw, inouts=ws + gio, flops=2 * S * n_in * n_out)
         adamw(w)
         if bias:
             adamw(bias)
@@ -241,18 +310,11 @@ def build_trace(cfg):
         norm_bwd(p + "dh1", xin, p + "st1", norm_p(p, nk + "1"), p + "dxm", p + "dx", p + "part1")
         dx = p + "dx"
     pgrad("wte")
-    b.kernel(EMBED_BWD, reads=[dx, "tokens"], writes=["g.wte"])
+    gw, gio = gout(["g.wte"])
+    b.kernel(EMBED_BWD, reads=[dx, "tokens"], writes=gw, inouts=gio)
     adamw("wte")
     if gpt:
         pgrad("wpe")
-        b.kernel(POSEMB_BWD, reads=[dx], writes=["g.wpe"])
+        gw, gio = gout(["g.wpe"])
+        b.kernel(POSEMB_BWD, reads=[dx], writes=gw, inouts=gio)
         adamw("wpe")
-
-    tau = []
-    for op, operands, flops in b.kernels:
-        nbytes = sum(b.tensors[t][0] for t, _ in operands)
-        tf = -(-flops * 10**9 // MODEL_FLOPS_PER_S)
-        tb = -(-nbytes * 10**9 // MODEL_BYTES_PER_S)
-        tau.append(max(tf, tb) + MODEL_LAUNCH_NS)
-    return dict(tensors=b.tensors, kernels=b.kernels, tau=tau, ids=b.ids,
-                n_persistent=b.ids["labels"] + 1)

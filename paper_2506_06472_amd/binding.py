@@ -28,7 +28,8 @@ class TioError(RuntimeError):
 class ModelCfg(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("arch", "n_layers", "d_model", "n_heads", "d_ff", "vocab", "seq_len",
                                           "batch", "precision")] + \
-               [(n, C.c_float) for n in ("lr", "beta1", "beta2", "adam_eps", "weight_decay", "norm_eps", "rope_theta")]
+               [(n, C.c_float) for n in ("lr", "beta1", "beta2", "adam_eps", "weight_decay", "norm_eps", "rope_theta")] + \
+               [("micro_batches", C.c_int32)]
 
 
 class RuntimeCfg(C.Structure):
@@ -109,7 +110,7 @@ def model_cfg(cfg: dict) -> ModelCfg:
     return ModelCfg(ARCH[cfg["arch"]], cfg["L"], cfg["d"], cfg["H"], cfg["f"], cfg["V"], cfg["T"], cfg["B"],
                     PREC[cfg["precision"]], cfg.get("lr", 1e-3), cfg.get("beta1", 0.9), cfg.get("beta2", 0.999),
                     cfg.get("adam_eps", 1e-8), cfg.get("weight_decay", 0.01), cfg.get("eps", 1e-5),
-                    cfg.get("rope_theta", 10000.0))
+                    cfg.get("rope_theta", 10000.0), int(cfg.get("micro_batches", 1) or 1))
 
 
 def _arr(ptr, n, dtype):

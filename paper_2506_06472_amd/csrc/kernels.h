@@ -22,10 +22,10 @@ void norm_fwd(hipStream_t s, int dtype, bool rms, const void *x, const void *g, 
 // fp32 split-K partials go to ws and the caller runs the reduction.
 bool gemm_bf16_pipelined(hipStream_t s, int cfg, bool a_km, bool b_km, int64_t M, int64_t N, int64_t K, const void *A,
                          int64_t lda, const void *B, int64_t ldb, const void *bias, const void *resid, int64_t ldr,
-                         void *C, int64_t ldc, void *rowsum, float *ws, int splits);
+                         void *C, int64_t ldc, void *rowsum, float *ws, int splits, bool rowsum_accumulate);
 void gemm(hipStream_t s, int dtype, bool a_km, bool b_km, int64_t M, int64_t N, int64_t K, const void *A,
           int64_t lda, const void *B, int64_t ldb, const void *bias, const void *resid, int64_t ldr, void *C,
-          int64_t ldc, void *rowsum, void *workspace, int splits);
+          int64_t ldc, void *rowsum, void *workspace, int splits, bool accumulate = false);
 
 void rope(hipStream_t s, int dtype, void *qkv, int64_t B, int64_t T, int64_t H, int64_t dh, float theta,
           bool inverse);
@@ -38,23 +38,26 @@ void attn_bwd_mfma(hipStream_t s, const void *dO, const void *qkv, const float *
                    int64_t B, int64_t T, int64_t H, int64_t dh);
 void gelu_fwd(hipStream_t s, int dtype, const void *u, void *y, int64_t n);
 void swiglu_fwd(hipStream_t s, int dtype, const void *gu, void *y, int64_t S, int64_t f);
+// S rows of this launch; S_total: tokens of the whole batch (the loss is their mean)
 void ce_fwd_bwd(hipStream_t s, int dtype, void *logits, const int32_t *labels, float *losses, int64_t S,
-                int64_t V, int64_t ld);
-void loss_reduce(hipStream_t s, const float *losses, float *loss, int64_t S);
+                int64_t V, int64_t ld, int64_t S_total);
+// loss[0] (+)= sum(losses[0..S)) / S_total
+void loss_reduce(hipStream_t s, const float *losses, float *loss, int64_t S, int64_t S_total, bool accumulate);
 void bias_grad(hipStream_t s, int dtype, const void *dy, void *db, int64_t S, int64_t n, int64_t ld);
 void gelu_bwd(hipStream_t s, int dtype, void *dact, const void *u, int64_t n);
 void swiglu_bwd(hipStream_t s, int dtype, const void *dact, const void *gu, void *dgu, int64_t S, int64_t f);
 void norm_bwd(hipStream_t s, int dtype, bool rms, const void *dy, const void *x, const float *stats,
               const void *g, const void *dres, void *dx, float *part, int64_t S, int64_t d, int64_t nb);
+// accumulate (here and below): add to the gradient already in the output (later micro-batches)
 void norm_bwd_params(hipStream_t s, int dtype, bool rms, const float *part, void *dg, void *db, int64_t nb,
-                     int64_t d);
+                     int64_t d, bool accumulate);
 void attn_bwd_pre(hipStream_t s, int dtype, const void *dO, const void *O, float *delta, int64_t B, int64_t T,
                   int64_t H, int64_t dh);
 void attn_bwd(hipStream_t s, int dtype, const void *dO, const void *qkv, const float *lse, const float *delta,
               void *dqkv, int64_t B, int64_t T, int64_t H, int64_t dh);
 void embed_bwd(hipStream_t s, int dtype, const void *dx, const int32_t *tok, void *dwte, int64_t S, int64_t d,
-               int64_t V);
-void posemb_bwd(hipStream_t s, int dtype, const void *dx, void *dwpe, int64_t B, int64_t T, int64_t d);
+               int64_t V, bool accumulate);
+void posemb_bwd(hipStream_t s, int dtype, const void *dx, void *dwpe, int64_t B, int64_t T, int64_t d, bool accumulate);
 void adamw(hipStream_t s, int dtype, const void *g, void *w, float *master, float *m, float *v, int64_t n,
            float lr, float beta1, float beta2, float eps, float wd, float bc1, float bc2);
 void fill_u32(hipStream_t s, void *p, uint32_t value, int64_t n_words);

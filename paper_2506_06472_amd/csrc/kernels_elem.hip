@@ -47,7 +47,7 @@ __global__ void __launch_bounds__(TPB) embed_fwd_k(const int32_t *__restrict__ t
 // (a contiguous range each); the occurrences found are collected in LDS in position order.
 template <typename T>
 __global__ void __launch_bounds__(TPB) embed_bwd_k(const T *__restrict__ dx, const int32_t *__restrict__ tok,
-                                                   T *__restrict__ dw, int64_t S, int64_t d) {
+                                                   T *__restrict__ dw, int64_t S, int64_t d, bool accumulate) {
     constexpr int V = Vec16<T>::N;
     constexpr int CAP = 1024;                              // occurrences handled per round
     __shared__ int cnt[TPB + 1];
@@ -84,9 +84,12 @@ __global__ void __launch_bounds__(TPB) embed_bwd_k(const T *__restrict__ dx, con
     for (int64_t cb0 = 0; cb0 < cpr; cb0 += (int64_t)NC * TPB) {
         float acc[NC][V];
 #pragma unroll
-        for (int c = 0; c < NC; ++c)
+        for (int c = 0; c < NC; ++c) {
 #pragma unroll
             for (int e = 0; e < V; ++e) acc[c][e] = 0.f;
+            const int64_t ch = cb0 + tid + (int64_t)c * TPB;
+            if (accumulate && ch < cpr) { Vec16<T> o; o.load(dw + (int64_t)id * d + ch * V); o.get(acc[c]); }   // earlier micro-batches
+        }
         for (int base = 0; base < total; base += CAP) {
             if (total > CAP || cb0 == 0) {                 // (re)build the list of this round's occurrences
                 __syncthreads();
@@ -123,7 +126,7 @@ __global__ void __launch_bounds__(TPB) embed_bwd_k(const T *__restrict__ dx, con
 
 template <typename T>
 __global__ void __launch_bounds__(TPB) posemb_bwd_k(const T *__restrict__ dx, T *__restrict__ dw, int64_t B,
-                                                    int64_t Tn, int64_t d) {
+                                                    int64_t Tn, int64_t d, bool accumulate) {
     constexpr int V = Vec16<T>::N;
     const int64_t cpr = d / V;
     const int64_t idx = (int64_t)blockIdx.x * TPB + threadIdx.x;
@@ -132,6 +135,7 @@ __global__ void __launch_bounds__(TPB) posemb_bwd_k(const T *__restrict__ dx, T 
     float acc[V];
 #pragma unroll
     for (int i = 0; i < V; ++i) acc[i] = 0.f;
+    if (accumulate) { Vec16<T> o; o.load(dw + t * d + c * V); o.get(acc); }      // earlier micro-batches
     for (int64_t b = 0; b < B; ++b) {
         Vec16<T> g;
         g.load(dx + (b * Tn + t) * d + c * V);
@@ -339,7 +343,7 @@ __global__ void __launch_bounds__(TPB) norm_bwd_wave_k(const T *__restrict__ dy,
 // thread adds its rows in order and the eight groups are combined in order
 template <typename T, bool RMS>
 __global__ void __launch_bounds__(TPB) norm_bwd_params_k(const float *__restrict__ part, T *__restrict__ dg,
-                                                         T *__restrict__ db, int64_t nb, int64_t d) {
+                                                         T *__restrict__ db, int64_t nb, int64_t d, bool accumulate) {
     constexpr int NP = RMS ? 1 : 2;
     __shared__ float red[2][8][33];
     const int c = threadIdx.x & 31, rg = threadIdx.x >> 5;
@@ -370,6 +374,7 @@ __global__ void __launch_bounds__(TPB) norm_bwd_params_k(const float *__restrict
         float tg = 0.f, tb = 0.f;
 #pragma unroll
         for (int i = 0; i < 8; ++i) { tg += red[0][i][c]; tb += red[1][i][c]; }
+        if (accumulate) { tg += to_f32(dg[col]); if (!RMS) tb += to_f32(db[col]); }      // earlier micro-batches
         dg[col] = from_f32<T>(tg);
         if (!RMS) db[col] = from_f32<T>(tb);
     }
@@ -491,7 +496,7 @@ __global__ void __launch_bounds__(TPB) rope_k(T *__restrict__ qkv, int64_t S, in
 // one workgroup per row: online max / sum-of-exponentials, then dlogits written in place
 template <typename T>
 __global__ void __launch_bounds__(TPB) ce_k(T *__restrict__ logits, const int32_t *__restrict__ labels,
-                                            float *__restrict__ losses, int64_t S, int64_t Vn, int64_t ld) {
+                                            float *__restrict__ losses, int64_t S, int64_t Vn, int64_t ld, int64_t S_total) {
     constexpr int V = Vec16<T>::N;
     __shared__ float red[8];
     const int64_t row = blockIdx.x;
@@ -517,7 +522,7 @@ __global__ void __launch_bounds__(TPB) ce_k(T *__restrict__ logits, const int32_
     const int32_t lab = labels[row];
     if (threadIdx.x == 0) losses[row] = lse - to_f32(xr[lab]);
     __syncthreads();                                       // the label logit is read before it is overwritten
-    const float invS = 1.0f / (float)S;
+    const float invS = 1.0f / (float)S_total;          // the loss is the mean over the whole batch
     for (int64_t c = threadIdx.x; c < nchunk; c += TPB) {
         Vec16<T> a; a.load(xr + c * V);
         float f[V]; a.get(f);
@@ -530,12 +535,13 @@ __global__ void __launch_bounds__(TPB) ce_k(T *__restrict__ logits, const int32_
     }
 }
 
-__global__ void __launch_bounds__(TPB) loss_reduce_k(const float *__restrict__ losses, float *__restrict__ loss, int64_t S) {
+__global__ void __launch_bounds__(TPB) loss_reduce_k(const float *__restrict__ losses, float *__restrict__ loss, int64_t S,
+                                                     int64_t S_total, bool accumulate) {
     __shared__ float red[8];
     float s = 0.f;
     for (int64_t i = threadIdx.x; i < S; i += TPB) s += losses[i];
     const float t = block_sum<TPB / 64>(s, red);
-    if (threadIdx.x == 0) loss[0] = t / (float)S;
+    if (threadIdx.x == 0) loss[0] = (accumulate ? loss[0] : 0.f) + t / (float)S_total;
 }
 
 // ---------------------------------------------------------------- bias gradient: column sums
@@ -702,17 +708,18 @@ void embed_fwd(hipStream_t s, int dtype, const int32_t *tok, const void *wte, co
     });
 }
 
-void embed_bwd(hipStream_t s, int dtype, const void *dx, const int32_t *tok, void *dwte, int64_t S, int64_t d, int64_t V) {
-    // rows of ids that do not occur stay zero
+void embed_bwd(hipStream_t s, int dtype, const void *dx, const int32_t *tok, void *dwte, int64_t S, int64_t d, int64_t V,
+               bool accumulate) {
+    // rows of ids that do not occur stay zero (or, when accumulating over micro-batches, what they were)
     const int64_t words = V * d * (dtype == TIO_PREC_BF16 ? 2 : 4) / 4;
-    fill_u32(s, dwte, 0u, words);
-    TIO_DISPATCH(dtype, { embed_bwd_k<T><<<(unsigned)S, TPB, 0, s>>>((const T *)dx, tok, (T *)dwte, S, d); });
+    if (!accumulate) fill_u32(s, dwte, 0u, words);
+    TIO_DISPATCH(dtype, { embed_bwd_k<T><<<(unsigned)S, TPB, 0, s>>>((const T *)dx, tok, (T *)dwte, S, d, accumulate); });
 }
 
-void posemb_bwd(hipStream_t s, int dtype, const void *dx, void *dwpe, int64_t B, int64_t Tn, int64_t d) {
+void posemb_bwd(hipStream_t s, int dtype, const void *dx, void *dwpe, int64_t B, int64_t Tn, int64_t d, bool accumulate) {
     TIO_DISPATCH(dtype, {
         const int64_t n = Tn * (d / Vec16<T>::N);
-        posemb_bwd_k<T><<<blocks_for(n, TPB), TPB, 0, s>>>((const T *)dx, (T *)dwpe, B, Tn, d);
+        posemb_bwd_k<T><<<blocks_for(n, TPB), TPB, 0, s>>>((const T *)dx, (T *)dwpe, B, Tn, d, accumulate);
     });
 }
 
@@ -749,10 +756,11 @@ void norm_bwd(hipStream_t s, int dtype, bool rms, const void *dy, const void *x,
     });
 }
 
-void norm_bwd_params(hipStream_t s, int dtype, bool rms, const float *part, void *dg, void *db, int64_t nb, int64_t d) {
+void norm_bwd_params(hipStream_t s, int dtype, bool rms, const float *part, void *dg, void *db, int64_t nb, int64_t d,
+                     bool accumulate) {
     TIO_DISPATCH(dtype, {
-        if (rms) norm_bwd_params_k<T, true><<<blocks_for(d, 32), TPB, 0, s>>>(part, (T *)dg, nullptr, nb, d);
-        else norm_bwd_params_k<T, false><<<blocks_for(d, 32), TPB, 0, s>>>(part, (T *)dg, (T *)db, nb, d);
+        if (rms) norm_bwd_params_k<T, true><<<blocks_for(d, 32), TPB, 0, s>>>(part, (T *)dg, nullptr, nb, d, accumulate);
+        else norm_bwd_params_k<T, false><<<blocks_for(d, 32), TPB, 0, s>>>(part, (T *)dg, (T *)db, nb, d, accumulate);
     });
 }
 
@@ -793,12 +801,12 @@ void rope(hipStream_t s, int dtype, void *qkv, int64_t B, int64_t Tn, int64_t H,
 }
 
 void ce_fwd_bwd(hipStream_t s, int dtype, void *logits, const int32_t *labels, float *losses, int64_t S, int64_t V,
-                int64_t ld) {
-    TIO_DISPATCH(dtype, { ce_k<T><<<(unsigned)S, TPB, 0, s>>>((T *)logits, labels, losses, S, V, ld); });
+                int64_t ld, int64_t S_total) {
+    TIO_DISPATCH(dtype, { ce_k<T><<<(unsigned)S, TPB, 0, s>>>((T *)logits, labels, losses, S, V, ld, S_total); });
 }
 
-void loss_reduce(hipStream_t s, const float *losses, float *loss, int64_t S) {
-    loss_reduce_k<<<1, TPB, 0, s>>>(losses, loss, S);
+void loss_reduce(hipStream_t s, const float *losses, float *loss, int64_t S, int64_t S_total, bool accumulate) {
+    loss_reduce_k<<<1, TPB, 0, s>>>(losses, loss, S, S_total, accumulate);
 }
 
 void bias_grad(hipStream_t s, int dtype, const void *dy, void *db, int64_t S, int64_t n, int64_t ld) {

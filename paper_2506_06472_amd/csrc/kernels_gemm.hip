@@ -13,6 +13,7 @@
 //
 // fp32: plain LDS-tiled FMA kernel (used by the small fp32 configurations, which are launch bound).
 #include <cstdlib>
+#include <stdexcept>
 
 #include "../../include/teraio.h"
 #include "device_common.h"
@@ -29,7 +30,7 @@ __global__ void __launch_bounds__(WGM *WGN * 64)
     gemm_bf16_k(const uint16_t *__restrict__ A, int64_t lda, const uint16_t *__restrict__ B, int64_t ldb,
                 const uint16_t *__restrict__ bias, const uint16_t *__restrict__ resid, int64_t ldr,
                 uint16_t *__restrict__ C, int64_t ldc, int64_t M, int64_t N, int64_t K, int tiles_m, int tiles_n,
-                uint16_t *__restrict__ rowsum, float *__restrict__ ws, int64_t k_chunk) {
+                uint16_t *__restrict__ rowsum, float *__restrict__ ws, int64_t k_chunk, int rowsum_acc) {
     constexpr int NT = WGM * WGN * 64;
     constexpr int TPR = NT / BM;           // threads that share one row of the A tile for the row sums
     static_assert(NT % BM == 0 && (TPR & (TPR - 1)) == 0 && TPR <= 64 && BK % (8 * TPR) == 0, "row-sum mapping");
@@ -142,7 +143,7 @@ __global__ void __launch_bounds__(WGM *WGN * 64)
         const int64_t m = m0 + tid / TPR;
         if (tid % TPR == 0 && m < M) {
             if (ws) ws[(int64_t)gridDim.y * M * N + (int64_t)blockIdx.y * M + m] = rsum;
-            else rowsum[m] = (uint16_t)f32_to_bf16_bits(rsum);
+            else rowsum[m] = (uint16_t)f32_to_bf16_bits(rsum + (rowsum_acc ? bf16_bits_to_f32(rowsum[m]) : 0.f));
         }
     }
     // epilogue: lane holds C[m][n .. n+3] for 4 groups of columns per 32x32 tile
@@ -191,7 +192,8 @@ __global__ void __launch_bounds__(WGM *WGN * 64)
 
 // adds the split-K partials in split order and rounds once; also finishes the fused row sums
 __global__ void __launch_bounds__(256) splitk_reduce_k(const float *__restrict__ ws, uint16_t *__restrict__ C, int64_t ldc,
-                                                       uint16_t *__restrict__ rowsum, int64_t M, int64_t N, int splits) {
+                                                       uint16_t *__restrict__ rowsum, int64_t M, int64_t N, int splits,
+                                                       int accumulate) {
     const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
     const int64_t nq = N / 4, total = M * nq;
     if (idx < total) {
@@ -200,6 +202,11 @@ __global__ void __launch_bounds__(256) splitk_reduce_k(const float *__restrict__
         for (int sp = 1; sp < splits; ++sp) {
             const float4 b = *reinterpret_cast<const float4 *>(ws + ((int64_t)sp * M + m) * N + n);
             a.x += b.x; a.y += b.y; a.z += b.z; a.w += b.w;
+        }
+        if (accumulate) {          // earlier micro-batches' sum is in C
+            const uint2 t = *reinterpret_cast<const uint2 *>(C + m * ldc + n);
+            a.x += __uint_as_float(t.x << 16); a.y += __uint_as_float(t.x & 0xffff0000u);
+            a.z += __uint_as_float(t.y << 16); a.w += __uint_as_float(t.y & 0xffff0000u);
         }
         uint2 o;
         o.x = f32_to_bf16_bits(a.x) | (f32_to_bf16_bits(a.y) << 16);
@@ -210,6 +217,7 @@ __global__ void __launch_bounds__(256) splitk_reduce_k(const float *__restrict__
         const float *r = ws + (int64_t)splits * M * N;
         float a = r[m];
         for (int sp = 1; sp < splits; ++sp) a += r[(int64_t)sp * M + m];
+        if (accumulate) a += bf16_bits_to_f32(rowsum[m]);
         rowsum[m] = (uint16_t)f32_to_bf16_bits(a);
     }
 }
@@ -220,7 +228,7 @@ __global__ void __launch_bounds__(256) gemm_f32_k(const float *__restrict__ A, i
                                                   int64_t ldb, const float *__restrict__ bias,
                                                   const float *__restrict__ resid, int64_t ldr, float *__restrict__ C,
                                                   int64_t ldc, int64_t M, int64_t N, int64_t K,
-                                                  float *__restrict__ rowsum) {
+                                                  float *__restrict__ rowsum, int rowsum_acc) {
     constexpr int BT = 64, BKK = 16;
     __shared__ float As[BKK][BT + 1];
     __shared__ float Bs[BKK][BT + 1];
@@ -258,7 +266,7 @@ __global__ void __launch_bounds__(256) gemm_f32_k(const float *__restrict__ A, i
         }
         __syncthreads();
     }
-    if (do_rowsum && m0 + tid < M) rowsum[m0 + tid] = rsum;
+    if (do_rowsum && m0 + tid < M) rowsum[m0 + tid] = rsum + (rowsum_acc ? rowsum[m0 + tid] : 0.f);
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         const int64_t m = m0 + ty * 4 + i;
@@ -280,7 +288,7 @@ __global__ void __launch_bounds__(256) gemm_f32_k(const float *__restrict__ A, i
 template <int BM, int BN, int BK, int WGM, int WGN, int NBUF>
 static void launch_bf16(hipStream_t s, bool a_km, bool b_km, int64_t M, int64_t N, int64_t K, const void *A, int64_t lda,
                         const void *B, int64_t ldb, const void *bias, const void *resid, int64_t ldr, void *C, int64_t ldc,
-                        void *rowsum, void *workspace, int splits) {
+                        void *rowsum, void *workspace, int splits, bool accumulate) {
     const int tiles_m = (int)((M + BM - 1) / BM), tiles_n = (int)((N + BN - 1) / BN);
     float *ws = splits > 1 ? (float *)workspace : nullptr;
     const int64_t k_chunk = splits > 1 ? ((K + splits - 1) / splits + BK - 1) / BK * BK : K;
@@ -296,7 +304,7 @@ static void launch_bf16(hipStream_t s, bool a_km, bool b_km, int64_t M, int64_t 
         attr_done = true;
     }
 #define TIO_GEMM_ARGS (const uint16_t *)A, lda, (const uint16_t *)B, ldb, (const uint16_t *)bias, (const uint16_t *)resid, ldr, \
-                      (uint16_t *)C, ldc, M, N, K, tiles_m, tiles_n, (uint16_t *)rowsum, ws, k_chunk
+                      (uint16_t *)C, ldc, M, N, K, tiles_m, tiles_n, (uint16_t *)rowsum, ws, k_chunk, (int)accumulate
     if (!a_km && !b_km) gemm_bf16_k<BM, BN, BK, WGM, WGN, NBUF, false, false><<<grid, block, lds, s>>>(TIO_GEMM_ARGS);
     else if (!a_km && b_km) gemm_bf16_k<BM, BN, BK, WGM, WGN, NBUF, false, true><<<grid, block, lds, s>>>(TIO_GEMM_ARGS);
     else if (a_km && b_km) gemm_bf16_k<BM, BN, BK, WGM, WGN, NBUF, true, true><<<grid, block, lds, s>>>(TIO_GEMM_ARGS);
@@ -304,7 +312,7 @@ static void launch_bf16(hipStream_t s, bool a_km, bool b_km, int64_t M, int64_t 
 #undef TIO_GEMM_ARGS
     if (ws) {
         const int64_t n = M * (N / 4) + (rowsum ? M : 0);
-        splitk_reduce_k<<<(unsigned)((n + 255) / 256), 256, 0, s>>>(ws, (uint16_t *)C, ldc, (uint16_t *)rowsum, M, N, splits);
+        splitk_reduce_k<<<(unsigned)((n + 255) / 256), 256, 0, s>>>(ws, (uint16_t *)C, ldc, (uint16_t *)rowsum, M, N, splits, (int)accumulate);
     }
 }
 
@@ -316,10 +324,18 @@ static int gemm_cfg_override() {
 
 void gemm(hipStream_t s, int dtype, bool a_km, bool b_km, int64_t M, int64_t N, int64_t K, const void *A, int64_t lda,
           const void *B, int64_t ldb, const void *bias, const void *resid, int64_t ldr, void *C, int64_t ldc,
-          void *rowsum, void *workspace, int splits) {
+          void *rowsum, void *workspace, int splits, bool accumulate) {
     if (M <= 0 || N <= 0 || K <= 0) return;
     // split-K needs the fp32 workspace, no epilogue operands and whole float4 rows
     if (dtype != TIO_PREC_BF16 || !workspace || bias || resid || (N % 4) || splits < 2) splits = 1;
+    // accumulate: C += A.B^T and rowsum += row sums (gradient accumulation over micro-batches).  In a single
+    // pass the old C is the residual operand (every element is read and then written by the same lane); with
+    // split-K the reduction launch adds it.
+    if (accumulate && splits == 1) {
+        if (resid) throw std::invalid_argument("gemm: accumulate cannot be combined with a residual operand");
+        resid = C;
+        ldr = ldc;
+    }
     if (dtype == TIO_PREC_BF16) {
         // The pipelined kernel is the default.  Its 256x256 tiles (eight wavefronts, 128x64 each: fewer LDS
         // bytes per MFMA) pay off once there are at least two rounds of them over the 256 CUs; below that
@@ -329,18 +345,18 @@ void gemm(hipStream_t s, int dtype, bool a_km, bool b_km, int64_t M, int64_t N, 
         const int ov = gemm_cfg_override();
         const int pipe_cfg = ov == 1 ? 0 : ov == 2 ? 1 : (big_tiles >= 512 ? 1 : 0);
         if (ov != 0 && gemm_bf16_pipelined(s, pipe_cfg, a_km, b_km, M, N, K, A, lda, B, ldb, bias, resid, ldr, C, ldc, rowsum,
-                                           splits > 1 ? (float *)workspace : nullptr, splits)) {
+                                           splits > 1 ? (float *)workspace : nullptr, splits, accumulate)) {
             if (splits > 1) {
                 const int64_t n = M * (N / 4) + (rowsum ? M : 0);
-                splitk_reduce_k<<<(unsigned)((n + 255) / 256), 256, 0, s>>>((const float *)workspace, (uint16_t *)C, ldc, (uint16_t *)rowsum, M, N, splits);
+                splitk_reduce_k<<<(unsigned)((n + 255) / 256), 256, 0, s>>>((const float *)workspace, (uint16_t *)C, ldc, (uint16_t *)rowsum, M, N, splits, (int)accumulate);
             }
             return;
         }
         // operands too large for 32-bit buffer offsets: plain kernel with 64-bit addressing
-        launch_bf16<128, 128, 64, 2, 2, 1>(s, a_km, b_km, M, N, K, A, lda, B, ldb, bias, resid, ldr, C, ldc, rowsum, workspace, splits);
+        launch_bf16<128, 128, 64, 2, 2, 1>(s, a_km, b_km, M, N, K, A, lda, B, ldb, bias, resid, ldr, C, ldc, rowsum, workspace, splits, accumulate);
     } else {
         const dim3 grid((unsigned)((N + 63) / 64), (unsigned)((M + 63) / 64));
-#define TIO_GEMM_ARGS (const float *)A, lda, (const float *)B, ldb, (const float *)bias, (const float *)resid, ldr, (float *)C, ldc, M, N, K, (float *)rowsum
+#define TIO_GEMM_ARGS (const float *)A, lda, (const float *)B, ldb, (const float *)bias, (const float *)resid, ldr, (float *)C, ldc, M, N, K, (float *)rowsum, (int)accumulate
         if (!a_km && !b_km) gemm_f32_k<false, false><<<grid, 256, 0, s>>>(TIO_GEMM_ARGS);
         else if (!a_km && b_km) gemm_f32_k<false, true><<<grid, 256, 0, s>>>(TIO_GEMM_ARGS);
         else if (a_km && b_km) gemm_f32_k<true, true><<<grid, 256, 0, s>>>(TIO_GEMM_ARGS);

@@ -167,7 +167,7 @@ __global__ void __launch_bounds__(WGM *WGN * 64)
     gemm_bf16_pipe_k(const uint16_t *__restrict__ A, int64_t lda, const uint16_t *__restrict__ B, int64_t ldb,
                      const uint16_t *__restrict__ bias, const uint16_t *__restrict__ resid, int64_t ldr,
                      uint16_t *__restrict__ C, int64_t ldc, int64_t M, int64_t N, int64_t K, int tiles_m, int tiles_n,
-                     uint16_t *__restrict__ rowsum, float *__restrict__ ws, int64_t k_chunk) {
+                     uint16_t *__restrict__ rowsum, float *__restrict__ ws, int64_t k_chunk, int rowsum_acc) {
     constexpr int NT = WGM * WGN * 64;
     constexpr int TPR = NT / BM;           // threads that share one row of the A tile for the row sums
     static_assert(NT % BM == 0 && (TPR & (TPR - 1)) == 0 && TPR <= 64 && BK % (8 * TPR) == 0, "row-sum mapping");
@@ -318,7 +318,7 @@ __global__ void __launch_bounds__(WGM *WGN * 64)
         const int64_t m = m0 + tid / TPR;
         if (tid % TPR == 0 && m < M) {
             if (ws) ws[(int64_t)gridDim.y * M * N + (int64_t)blockIdx.y * M + m] = rsum;
-            else rowsum[m] = (uint16_t)f32_to_bf16_bits(rsum);
+            else rowsum[m] = (uint16_t)f32_to_bf16_bits(rsum + (rowsum_acc ? bf16_bits_to_f32(rowsum[m]) : 0.f));
         }
     }
     // epilogue: lane holds C[m][n .. n+3] for 4 groups of columns per 32x32 tile
@@ -368,7 +368,7 @@ __global__ void __launch_bounds__(WGM *WGN * 64)
 template <int BM, int BN, int BK, int WGM, int WGN>
 bool launch_pipe(hipStream_t s, bool a_km, bool b_km, int64_t M, int64_t N, int64_t K, const void *A, int64_t lda,
                  const void *B, int64_t ldb, const void *bias, const void *resid, int64_t ldr, void *C, int64_t ldc,
-                 void *rowsum, float *ws, int splits) {
+                 void *rowsum, float *ws, int splits, bool rowsum_acc) {
     const int64_t k_chunk = splits > 1 ? ((K + splits - 1) / splits + BK - 1) / BK * BK : K;
     // every byte offset a lane can form must stay below 2^30 (see OOB)
     const int64_t kspan = splits > 1 ? k_chunk : K;
@@ -393,7 +393,7 @@ bool launch_pipe(hipStream_t s, bool a_km, bool b_km, int64_t M, int64_t N, int6
         attr_done = true;
     }
 #define TIO_GEMM_ARGS (const uint16_t *)A, lda, (const uint16_t *)B, ldb, (const uint16_t *)bias, (const uint16_t *)resid, ldr, \
-                      (uint16_t *)C, ldc, M, N, K, tiles_m, tiles_n, (uint16_t *)rowsum, ws, k_chunk
+                      (uint16_t *)C, ldc, M, N, K, tiles_m, tiles_n, (uint16_t *)rowsum, ws, k_chunk, (int)rowsum_acc
     if (!a_km && !b_km) gemm_bf16_pipe_k<BM, BN, BK, WGM, WGN, false, false><<<grid, block, lds, s>>>(TIO_GEMM_ARGS);
     else if (!a_km && b_km) gemm_bf16_pipe_k<BM, BN, BK, WGM, WGN, false, true><<<grid, block, lds, s>>>(TIO_GEMM_ARGS);
     else if (a_km && b_km) gemm_bf16_pipe_k<BM, BN, BK, WGM, WGN, true, true><<<grid, block, lds, s>>>(TIO_GEMM_ARGS);
@@ -406,8 +406,8 @@ bool launch_pipe(hipStream_t s, bool a_km, bool b_km, int64_t M, int64_t N, int6
 
 bool gemm_bf16_pipelined(hipStream_t s, int cfg, bool a_km, bool b_km, int64_t M, int64_t N, int64_t K, const void *A,
                          int64_t lda, const void *B, int64_t ldb, const void *bias, const void *resid, int64_t ldr,
-                         void *C, int64_t ldc, void *rowsum, float *ws, int splits) {
-#define TIO_P(BM, BN, BK, WGM, WGN) launch_pipe<BM, BN, BK, WGM, WGN>(s, a_km, b_km, M, N, K, A, lda, B, ldb, bias, resid, ldr, C, ldc, rowsum, ws, splits)
+                         void *C, int64_t ldc, void *rowsum, float *ws, int splits, bool rowsum_accumulate) {
+#define TIO_P(BM, BN, BK, WGM, WGN) launch_pipe<BM, BN, BK, WGM, WGN>(s, a_km, b_km, M, N, K, A, lda, B, ldb, bias, resid, ldr, C, ldc, rowsum, ws, splits, rowsum_accumulate)
     if (cfg == 1) return TIO_P(256, 256, 64, 2, 4);
     return TIO_P(128, 128, 64, 2, 2);
 #undef TIO_P

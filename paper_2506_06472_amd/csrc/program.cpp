@@ -2,6 +2,12 @@
 // GPT-shaped and Llama-shaped decoders.  One KernelRec per HIP launch, in launch order; tensor
 // ids: persistent tensors first (parameter-list order; weight, [master], m, v), then the token and
 // label buffers, then transient tensors in order of first write.
+//
+// Micro-batches (cfg.micro_batches = n > 1; Sections 4.1 and 4.2 of the paper train with micro-batches):
+// the batch is cut into n groups of batch/n sequences; the forward and backward schedule runs once per
+// group on tensors of that group's size (one token and one label buffer per group); parameter gradients
+// and the scalar loss are written by the first group and accumulated in place by the later ones; the
+// AdamW launches follow the gradient-completing launches of the last group only.
 #include "program.h"
 
 #include <stdexcept>
@@ -86,14 +92,17 @@ Program build_program(const tio_model_cfg &c) {
     if (c.d_model % c.n_heads) throw std::invalid_argument("d_model must be a multiple of n_heads");
     if (c.d_model % 8 || c.d_ff % 8 || (c.d_model / c.n_heads) % 8)
         throw std::invalid_argument("d_model, d_ff and the head dimension must be multiples of 8");
+    const int nmb = c.micro_batches > 1 ? c.micro_batches : 1;
+    if (c.micro_batches < 0 || c.batch % nmb) throw std::invalid_argument("batch must be a multiple of micro_batches");
 
     Builder b;
     b.P.cfg = c;
     const bool gpt = c.arch == TIO_ARCH_GPT;
     const bool bf16 = c.precision == TIO_PREC_BF16;
     b.e = bf16 ? 2 : 4;
-    const int64_t L = c.n_layers, d = c.d_model, H = c.n_heads, f = c.d_ff, V = c.vocab, T = c.seq_len, B = c.batch;
-    const int64_t S = B * T, Vp = vocab_ld(V), dh = d / H;
+    // B, S: sequences and tokens of one micro-batch
+    const int64_t L = c.n_layers, d = c.d_model, H = c.n_heads, f = c.d_ff, V = c.vocab, T = c.seq_len, B = c.batch / nmb;
+    const int64_t S = B * T, Vp = vocab_ld(V), dh = d / H, S_total = S * nmb;
 
     // ---- persistent tensors
     b.P.params = list_params(c);
@@ -104,9 +113,14 @@ Program build_program(const tio_model_cfg &c) {
         p.m = b.tensor(p.name + ".m", n * 4, KIND_M);
         p.v = b.tensor(p.name + ".v", n * 4, KIND_V);
     }
-    b.P.tokens_id = b.tensor("tokens", S * 4, KIND_INPUT);
-    b.P.labels_id = b.tensor("labels", S * 4, KIND_INPUT);
+    for (int j = 0; j < nmb; ++j) {
+        const std::string pre = nmb == 1 ? "" : "mb" + std::to_string(j) + ".";
+        b.P.tokens_ids.push_back(b.tensor(pre + "tokens", S * 4, KIND_INPUT));
+        b.P.labels_ids.push_back(b.tensor(pre + "labels", S * 4, KIND_INPUT));
+    }
     b.P.n_persistent = (int)b.P.tensors.size();
+    b.P.tokens_id = b.P.tokens_ids[0];
+    b.P.labels_id = b.P.labels_ids[0];
 
     auto pidx = [&](const std::string &name) -> ParamInfo & {
         for (auto &p : b.P.params) if (p.name == name) return p;
@@ -123,6 +137,12 @@ Program build_program(const tio_model_cfg &c) {
     const int64_t attn_flops = 2 * B * H * T * T * dh;
 
     struct LayerT { int x_in, h1, st1, qkv, ao, lse, xm, h2, st2, u, act, xo; };
+    int loss = -1;
+    for (int mb = 0; mb < nmb; ++mb) {
+    const bool first = mb == 0, last = mb == nmb - 1;
+    const std::string pre = nmb == 1 ? "" : "mb" + std::to_string(mb) + ".";   // transient tensors of this micro-batch
+    const int tokens_id = b.P.tokens_ids[mb], labels_id = b.P.labels_ids[mb];
+    const int GW = first ? W : RW;            // gradient outputs: written by the first micro-batch, accumulated by the rest
     std::vector<LayerT> LT(L);
 
     auto norm_fwd = [&](int x, ParamInfo &g, ParamInfo *bias, int y, int st) {
@@ -140,16 +160,16 @@ Program build_program(const tio_model_cfg &c) {
     };
 
     // ---- forward
-    int x0 = b.act("x0", S * d);
+    int x0 = b.act(pre + "x0", S * d);
     {
         KernelRec &k = b.kernel(OP_EMBED_FWD);
-        set(k, 0, b.P.tokens_id, R); set(k, 1, pidx("wte").w, R); if (gpt) set(k, 2, pidx("wpe").w, R);
+        set(k, 0, tokens_id, R); set(k, 1, pidx("wte").w, R); if (gpt) set(k, 2, pidx("wpe").w, R);
         set(k, 3, x0, W);
         k.p[0] = S; k.p[1] = d; k.p[2] = T;
     }
     int x = x0;
     for (int i = 0; i < L; ++i) {
-        std::string p = "l" + std::to_string(i) + ".";
+        std::string p = pre + "l" + std::to_string(i) + ".";
         LayerT &t = LT[i];
         t.x_in = x;
         t.h1 = b.act(p + "h1", S * d); t.st1 = b.act32(p + "st1", S * nstat);
@@ -192,32 +212,35 @@ Program build_program(const tio_model_cfg &c) {
     ParamInfo &fin_g = pidx(gpt ? "lnf_g" : "rmsf_g");
     ParamInfo *fin_b = gpt ? &pidx("lnf_b") : nullptr;
     ParamInfo &head = pidx("w_head");
-    int hf = b.act("hf", S * d), stf = b.act32("stf", S * nstat);
+    int hf = b.act(pre + "hf", S * d), stf = b.act32(pre + "stf", S * nstat);
     norm_fwd(x, fin_g, fin_b, hf, stf);
-    int logits = b.act("logits", S * Vp);
+    int logits = b.act(pre + "logits", S * Vp);
     gemm(hf, head, nullptr, -1, logits, V, d, Vp);
-    int losses = b.act32("losses", S);
+    int losses = b.act32(pre + "losses", S);
     {
         KernelRec &k = b.kernel(OP_CE_FWD_BWD);
-        set(k, 0, logits, RW); set(k, 1, b.P.labels_id, R); set(k, 2, losses, W);
-        k.p[0] = S; k.p[1] = V; k.p[2] = Vp;
+        set(k, 0, logits, RW); set(k, 1, labels_id, R); set(k, 2, losses, W);
+        k.p[0] = S; k.p[1] = V; k.p[2] = Vp; k.p[3] = S_total;      // the loss is the mean over the whole batch
     }
-    int loss = b.act32("loss", 1);
-    b.P.loss_id = loss;
+    if (first) {
+        loss = b.act32("loss", 1);
+        b.P.loss_id = loss;
+    }
     {
         KernelRec &k = b.kernel(OP_LOSS_REDUCE);
-        set(k, 0, losses, R); set(k, 1, loss, W);
-        k.p[0] = S;
+        set(k, 0, losses, R); set(k, 1, loss, GW);
+        k.p[0] = S; k.p[1] = S_total; k.p[2] = first ? 0 : 1;       // later micro-batches add their share
     }
 
     // ---- backward
     auto pgrad = [&](ParamInfo &p) {
-        p.grad = b.tensor("g." + p.name, p.rows * p.cols * b.e, KIND_PGRAD);
+        if (first) p.grad = b.tensor("g." + p.name, p.rows * p.cols * b.e, KIND_PGRAD);
         return p.grad;
     };
     // A parameter is updated right after the launch that completes its gradient: nothing later in the
     // iteration reads it, the gradient dies at once, and the optimizer-state traffic overlaps the backward pass.
     auto adamw = [&](ParamInfo &p) {
+        if (!last) return;
         KernelRec &k = b.kernel(OP_ADAMW);
         set(k, 0, p.grad, R); set(k, 1, p.w, RW); if (bf16) set(k, 2, p.master, RW);
         set(k, 3, p.m, RW); set(k, 4, p.v, RW);
@@ -235,12 +258,12 @@ Program build_program(const tio_model_cfg &c) {
         if (bias) pgrad(*bias);
         const int splits = bf16 ? dw_splits(n_out, n_in, S) : 1;
         int ws = -1;
-        if (splits > 1) ws = b.grd32("ws." + Wt.name, splits * (n_out * n_in + n_out));   // fp32 partials + row sums
+        if (splits > 1) ws = b.grd32(pre + "ws." + Wt.name, splits * (n_out * n_in + n_out));   // fp32 partials + row sums
         KernelRec &k = b.kernel(OP_GEMM_DW);
-        set(k, 0, dY, R); set(k, 1, X, R); set(k, 2, Wt.grad, W);
-        if (bias) set(k, 3, bias->grad, W);
+        set(k, 0, dY, R); set(k, 1, X, R); set(k, 2, Wt.grad, GW);
+        if (bias) set(k, 3, bias->grad, GW);
         if (ws >= 0) set(k, 4, ws, RW);
-        k.p[0] = n_out; k.p[1] = n_in; k.p[2] = S; k.p[3] = ld_dy; k.p[4] = splits;
+        k.p[0] = n_out; k.p[1] = n_in; k.p[2] = S; k.p[3] = ld_dy; k.p[4] = splits; k.p[5] = first ? 0 : 1;
         k.flops = 2 * S * n_in * n_out;
         adamw(Wt);
         if (bias) adamw(*bias);
@@ -260,20 +283,20 @@ Program build_program(const tio_model_cfg &c) {
         if (bias) pgrad(*bias);
         {
             KernelRec &k = b.kernel(OP_NORM_BWD_PARAMS);
-            set(k, 0, part, R); set(k, 1, g.grad, W); if (bias) set(k, 2, bias->grad, W);
-            k.p[0] = nb; k.p[1] = d;
+            set(k, 0, part, R); set(k, 1, g.grad, GW); if (bias) set(k, 2, bias->grad, GW);
+            k.p[0] = nb; k.p[1] = d; k.p[2] = first ? 0 : 1;
         }
         adamw(g);
         if (bias) adamw(*bias);
         return dx;
     };
 
-    int dhf = b.grd("dhf", S * d);
+    int dhf = b.grd(pre + "dhf", S * d);
     gemm_dx(logits, head, dhf, d, V, Vp);
     gemm_dw(logits, hf, head, nullptr, d, V, Vp);
-    int dx = norm_bwd(dhf, x, stf, fin_g, fin_b, -1, "dxf", "partf");
+    int dx = norm_bwd(dhf, x, stf, fin_g, fin_b, -1, pre + "dxf", pre + "partf");
     for (int i = (int)L - 1; i >= 0; --i) {
-        std::string p = "l" + std::to_string(i) + ".";
+        std::string p = pre + "l" + std::to_string(i) + ".";
         LayerT &t = LT[i];
         ParamInfo &w2 = LP(i, gpt ? 10 : 5);
         ParamInfo &w1 = LP(i, gpt ? 8 : 4);
@@ -327,8 +350,8 @@ Program build_program(const tio_model_cfg &c) {
         pgrad(wte);
         {
             KernelRec &k = b.kernel(OP_EMBED_BWD);
-            set(k, 0, dx, R); set(k, 1, b.P.tokens_id, R); set(k, 2, wte.grad, W);
-            k.p[0] = S; k.p[1] = d; k.p[2] = V;
+            set(k, 0, dx, R); set(k, 1, tokens_id, R); set(k, 2, wte.grad, GW);
+            k.p[0] = S; k.p[1] = d; k.p[2] = V; k.p[3] = first ? 0 : 1;
         }
         adamw(wte);
     }
@@ -337,11 +360,12 @@ Program build_program(const tio_model_cfg &c) {
         pgrad(wpe);
         {
             KernelRec &k = b.kernel(OP_POSEMB_BWD);
-            set(k, 0, dx, R); set(k, 1, wpe.grad, W);
-            k.p[0] = B; k.p[1] = T; k.p[2] = d;
+            set(k, 0, dx, R); set(k, 1, wpe.grad, GW);
+            k.p[0] = B; k.p[1] = T; k.p[2] = d; k.p[3] = first ? 0 : 1;
         }
         adamw(wpe);
     }
+    }   // micro-batches
 
     return b.P;
 }

@@ -52,6 +52,7 @@ struct Program {
     std::vector<ParamInfo> params;
     int32_t n_persistent = 0;
     int32_t tokens_id = -1, labels_id = -1, loss_id = -1;
+    std::vector<int32_t> tokens_ids, labels_ids;     // one buffer per micro-batch (tokens_id / labels_id = the first)
 };
 
 // Throws std::invalid_argument on a bad configuration.

@@ -183,7 +183,8 @@ void launch(tio_ctx *c, int k) {
     auto P = [&](int role) -> void * { return c->ptrs[k][role] == UINT64_MAX ? nullptr : (void *)(c->arena + c->ptrs[k][role]); };
     const int dt = m.precision;
     const bool rms = m.arch == TIO_ARCH_LLAMA;
-    const int64_t B = m.batch, T = m.seq_len, H = m.n_heads, dh = m.d_model / m.n_heads;
+    // B: sequences of one micro-batch
+    const int64_t B = m.batch / (m.micro_batches > 1 ? m.micro_batches : 1), T = m.seq_len, H = m.n_heads, dh = m.d_model / m.n_heads;
     hipStream_t s = c->sc;
     switch (r.op) {
     case OP_EMBED_FWD: k::embed_fwd(s, dt, (const int32_t *)P(0), P(1), P(2), P(3), r.p[0], r.p[1], r.p[2]); break;
@@ -196,14 +197,14 @@ void launch(tio_ctx *c, int k) {
     case OP_ATTN_FWD: k::attn_fwd(s, dt, P(0), P(1), (float *)P(2), B, T, H, dh); break;
     case OP_GELU_FWD: k::gelu_fwd(s, dt, P(0), P(1), r.p[0]); break;
     case OP_SWIGLU_FWD: k::swiglu_fwd(s, dt, P(0), P(1), r.p[0], r.p[1]); break;
-    case OP_CE_FWD_BWD: k::ce_fwd_bwd(s, dt, P(0), (const int32_t *)P(1), (float *)P(2), r.p[0], r.p[1], r.p[2]); break;
-    case OP_LOSS_REDUCE: k::loss_reduce(s, (const float *)P(0), (float *)P(1), r.p[0]); break;
+    case OP_CE_FWD_BWD: k::ce_fwd_bwd(s, dt, P(0), (const int32_t *)P(1), (float *)P(2), r.p[0], r.p[1], r.p[2], r.p[3]); break;
+    case OP_LOSS_REDUCE: k::loss_reduce(s, (const float *)P(0), (float *)P(1), r.p[0], r.p[1], r.p[2] != 0); break;
     case OP_GEMM_DX:   // dX[S,n_in] = dY[S,n_out] . W[n_out,n_in]: the weight has the contraction index slow
         k::gemm(s, dt, false, true, r.p[0], r.p[1], r.p[2], P(0), r.p[3], P(1), r.p[1], nullptr, nullptr, 0, P(2), r.p[1], nullptr, nullptr, 1);
         break;
     case OP_GEMM_DW:   // dW[n_out,n_in] = dY^T . X: both operands have the contraction index (tokens) slow;
                        // the row sums of dY^T are the bias gradient
-        k::gemm(s, dt, true, true, r.p[0], r.p[1], r.p[2], P(0), r.p[3], P(1), r.p[1], nullptr, nullptr, 0, P(2), r.p[1], P(3), P(4), (int)r.p[4]);
+        k::gemm(s, dt, true, true, r.p[0], r.p[1], r.p[2], P(0), r.p[3], P(1), r.p[1], nullptr, nullptr, 0, P(2), r.p[1], P(3), P(4), (int)r.p[4], r.p[5] != 0);
         break;
     case OP_BIAS_GRAD: k::bias_grad(s, dt, P(0), P(1), r.p[0], r.p[1], r.p[1]); break;
     case OP_GELU_BWD: k::gelu_bwd(s, dt, P(0), P(1), r.p[0]); break;
@@ -211,11 +212,11 @@ void launch(tio_ctx *c, int k) {
     case OP_NORM_BWD:
         k::norm_bwd(s, dt, rms, P(0), P(1), (const float *)P(2), P(3), P(4), P(5), (float *)P(6), r.p[0], r.p[1], r.p[2]);
         break;
-    case OP_NORM_BWD_PARAMS: k::norm_bwd_params(s, dt, rms, (const float *)P(0), P(1), P(2), r.p[0], r.p[1]); break;
+    case OP_NORM_BWD_PARAMS: k::norm_bwd_params(s, dt, rms, (const float *)P(0), P(1), P(2), r.p[0], r.p[1], r.p[2] != 0); break;
     case OP_ATTN_BWD_PRE: k::attn_bwd_pre(s, dt, P(0), P(1), (float *)P(2), B, T, H, dh); break;
     case OP_ATTN_BWD: k::attn_bwd(s, dt, P(0), P(1), (const float *)P(2), (const float *)P(3), P(4), B, T, H, dh); break;
-    case OP_EMBED_BWD: k::embed_bwd(s, dt, P(0), (const int32_t *)P(1), P(2), r.p[0], r.p[1], r.p[2]); break;
-    case OP_POSEMB_BWD: k::posemb_bwd(s, dt, P(0), P(1), r.p[0], r.p[1], r.p[2]); break;
+    case OP_EMBED_BWD: k::embed_bwd(s, dt, P(0), (const int32_t *)P(1), P(2), r.p[0], r.p[1], r.p[2], r.p[3] != 0); break;
+    case OP_POSEMB_BWD: k::posemb_bwd(s, dt, P(0), P(1), r.p[0], r.p[1], r.p[2], r.p[3] != 0); break;
     case OP_ADAMW: {
         const double t = (double)(c->step + 1);
         const float bc1 = (float)(1.0 - std::pow((double)m.beta1, t)), bc2 = (float)(1.0 - std::pow((double)m.beta2, t));
@@ -288,8 +289,13 @@ void run_step(tio_ctx *c, const int32_t *tokens, const int32_t *labels, bool cap
     }
     std::vector<uint8_t> issued(tl ? p.entries.size() : 0, 0);
     const auto w0 = std::chrono::steady_clock::now();
-    HIPCHK(hipMemcpyAsync(c->arena + address_at(p, c->prog.tokens_id, 0), tokens, S * 4, hipMemcpyHostToDevice, c->sc));
-    HIPCHK(hipMemcpyAsync(c->arena + address_at(p, c->prog.labels_id, 0), labels, S * 4, hipMemcpyHostToDevice, c->sc));
+    {   // one token and one label buffer per micro-batch (consecutive groups of sequences)
+        const int64_t nmb = (int64_t)c->prog.tokens_ids.size(), Sm = S / nmb;
+        for (int64_t j = 0; j < nmb; ++j) {
+            HIPCHK(hipMemcpyAsync(c->arena + address_at(p, c->prog.tokens_ids[j], 0), tokens + j * Sm, Sm * 4, hipMemcpyHostToDevice, c->sc));
+            HIPCHK(hipMemcpyAsync(c->arena + address_at(p, c->prog.labels_ids[j], 0), labels + j * Sm, Sm * 4, hipMemcpyHostToDevice, c->sc));
+        }
+    }
     uint64_t d2h = 0, h2d = 0;
     int nmig = 0;
     for (int k = 0; k < N; ++k) {
