@@ -192,6 +192,7 @@ def main():
                    "cap_frac_of_peak": cap / peak, "slow_tier_bw_bytes_per_s": bw, "slow_tier": "pinned host memory" if tier == "host" else "device memory outside the arena (stand-in)", "min_bytes": args.min_bytes,
                    "kernel_times": "modelled" if args.modelled_tau else "measured"},
         "ideal_tokens_per_s": S / ideal_s, "ideal_ms_per_step": ideal_s * 1e3,
+        "model_predicted_ms_per_step": tio.tio_plan_simulate(lt, plan, bw)[0] / 1e6,
         "frac_of_ideal": ideal_s / step_s,
         "migration_bound_ms": mig_bound_s * 1e3, "frac_of_min_ideal_migration_bound": bound_s / step_s,
         "plan": {"entries": len(pe["entries"]), "greedy_pairs": pe["n_greedy"], "urgent_pairs": pe["n_forced"],

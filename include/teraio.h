@@ -178,6 +178,15 @@ int tio_plan_export(const tio_plan *plan, tio_plan_view *out);
 /* Structural re-check of a plan against trace and lifetimes: residency of every operand,
  * residency <= cap at every kernel, non-overlapping addresses. */
 int tio_plan_validate(const tio_trace *trace, const tio_lifetimes *life, const tio_plan *plan);
+/* Performance model of the migration engine for a plan (Section 2.2 of the paper studies throughput against
+ * migration bandwidth with such a model): kernel k takes the trace's tau[k]; each direction moves bytes at
+ * slow_tier_bw bytes/s (0 = instantly; duplex = 0: one shared channel) in the plan's issue order; an entry is
+ * issued when the kernel before its trigger completes; a prefetch also waits for its own offload and for the
+ * offloads whose deadline has passed; a kernel starts when its predecessor and the migrations due at it have
+ * completed.  `iterations` >= 1 consecutive iterations are simulated; out_step_ns receives the duration of the
+ * last one (the steady state), out_compute_ns the sum of tau.  Pure CPU, integer arithmetic. */
+int tio_plan_simulate(const tio_trace *trace, const tio_plan *plan, uint64_t slow_tier_bw, int32_t duplex,
+                      int32_t iterations, int64_t *out_step_ns, int64_t *out_compute_ns);
 void tio_plan_free(tio_plan *plan);
 
 /* ---- Section 3.3: runtime ---------------------------------------------------------------------- */

@@ -249,6 +249,14 @@ def tio_plan_validate(trace: Trace, life: Lifetimes, plan: Plan):
     _check(lib().tio_plan_validate(trace.h, life.h, plan.h))
 
 
+def tio_plan_simulate(trace: Trace, plan: Plan, slow_tier_bw: int, duplex=True, iterations=3):
+    """Performance model: (ns of a steady-state iteration under the plan, ns of the kernels alone)."""
+    step, comp = C.c_int64(), C.c_int64()
+    _check(lib().tio_plan_simulate(trace.h, plan.h, C.c_uint64(int(slow_tier_bw)), 1 if duplex else 0, int(iterations),
+                                   C.byref(step), C.byref(comp)))
+    return step.value, comp.value
+
+
 # ------------------------------------------------------------------ runtime (needs a GPU)
 class Context:
     """Owns the arena (GPU), the slow-tier pool (pinned host) and three streams via torch,

@@ -443,6 +443,46 @@ bool assign_addresses(const Trace &t, const Lifetimes &life, uint64_t arena_byte
     return top <= arena_bytes;
 }
 
+SimResult simulate_plan(const Trace &t, const Plan &plan, uint64_t bw, bool duplex, int iterations) {
+    const int N = t.n_kernels;
+    const size_t np = plan.pairs.size();
+    std::vector<std::vector<int32_t>> pre_deadline(N), off_deadline(N);
+    for (const tio_plan_entry &e : plan.entries)
+        (e.kind == TIO_OFFLOAD ? off_deadline : pre_deadline)[e.deadline % N].push_back(e.pair);
+    auto dur = [&](uint64_t bytes) -> int64_t { return bw ? (int64_t)((bytes * 1000000000ull + bw - 1) / bw) : 0; };
+    std::vector<int64_t> off_done(np, 0), pre_done(np, 0);
+    int64_t d2h_free = 0, h2d_free = 0;
+    int64_t done_prev = 0;          // completion of the previous kernel
+    int64_t mem_ready = 0;          // completion of every offload whose deadline has been passed
+    int64_t last = 0, compute = 0;
+    for (int k = 0; k < N; ++k) compute += t.tau[k];
+    for (int it = 0; it < iterations; ++it) {
+        const int64_t t0 = done_prev;
+        for (int k = 0; k < N; ++k) {
+            for (int32_t p : off_deadline[k]) mem_ready = std::max(mem_ready, off_done[p]);
+            for (int32_t ei : plan.entries_at[k]) {
+                const tio_plan_entry &e = plan.entries[ei];
+                const int64_t d = dur(plan.pairs[e.pair].bytes);
+                if (e.kind == TIO_OFFLOAD) {
+                    const int64_t st = std::max(d2h_free, done_prev);
+                    off_done[e.pair] = d2h_free = st + d;
+                    if (!duplex) h2d_free = d2h_free;
+                } else {
+                    const int64_t st = std::max(std::max(h2d_free, done_prev), std::max(off_done[e.pair], mem_ready));
+                    pre_done[e.pair] = h2d_free = st + d;
+                    if (!duplex) d2h_free = h2d_free;
+                }
+            }
+            int64_t st = std::max(done_prev, mem_ready);
+            for (int32_t p : pre_deadline[k]) st = std::max(st, pre_done[p]);
+            for (int32_t p : off_deadline[k]) st = std::max(st, off_done[p]);     // offloads issued at this very trigger point
+            done_prev = st + t.tau[k];
+        }
+        last = done_prev - t0;
+    }
+    return SimResult{last, compute};
+}
+
 uint64_t address_at(const Plan &plan, int32_t tensor, int32_t k) {
     const int N = plan.n_kernels;
     for (int ai : plan.alloc_of[tensor]) {

@@ -87,6 +87,15 @@ void select_periods(const Trace &t, const Lifetimes &life, uint64_t cap, uint64_
 bool assign_addresses(const Trace &t, const Lifetimes &life, uint64_t arena_bytes, Plan &plan);
 void validate_plan(const Trace &t, const Lifetimes &life, const Plan &plan);   // throws PlanError
 
+// Performance model of the executor (Section 2.2 of the paper asks how fast the slow tier must be; this
+// answers it for a given plan): kernels take tau, each direction's channel moves bytes at `bw` (0 =
+// instantly) in issue order, a migration is issued when the kernel before its trigger completes, a
+// prefetch also waits for its own offload and for every offload whose deadline has passed, and a kernel
+// starts when its predecessor, the prefetches due at it and the offloads due at it have completed.
+// Returns the duration of the last of `iterations` consecutive iterations (steady state) in ns.
+struct SimResult { int64_t step_ns, compute_ns; };
+SimResult simulate_plan(const Trace &t, const Plan &plan, uint64_t bw, bool duplex, int iterations);
+
 // Address of tensor `id` while kernel k (0..N-1) runs, or UINT64_MAX when it is not resident.
 uint64_t address_at(const Plan &plan, int32_t tensor, int32_t k);
 

@@ -1,0 +1,111 @@
+"""Performance-model sweeps from the library's own trace, lifetimes, planner and model (CPU only).
+
+  python -m paper_2506_06472_amd.sweep --workload llama_7b_bf16 --bw 8 16 25 32 48 64
+
+For every slow-tier bandwidth: build the plan under the workload's memory cap, run tio_plan_simulate, and
+print the predicted step time, tokens/s and fraction of the uncapped ideal (the study of Section 2.2 and
+Figure 3 of the paper: training throughput against migration bandwidth).  --characterize adds what Figures
+1 and 2 of the paper show for their models: the share of the allocated bytes that a kernel actually
+touches, and the distribution of the tensors' inactive periods.  Kernel times are the library's modelled
+ones unless --tau FILE gives measured times (one integer of nanoseconds per kernel, e.g. written from
+tio_profile_iteration).
+"""
+from __future__ import annotations
+
+import argparse
+import sys
+
+import numpy as np
+
+from . import binding as tio
+
+
+def _cfg(name, micro_batches):
+    from synth import CONFIGS
+    cfg = dict(CONFIGS[name])
+    base_peak = None
+    if micro_batches > 1:
+        if "cap_frac" in cfg:
+            base_peak = int(tio.tio_analyze_lifetimes(tio.tio_trace_build(cfg)).export()["M"].max())
+        cfg["B"] *= micro_batches
+        cfg["micro_batches"] = micro_batches
+    return cfg, base_peak
+
+
+def sweep(name, bws, micro_batches=1, tau=None, min_bytes=1 << 20, out=sys.stdout):
+    cfg, base_peak = _cfg(name, micro_batches)
+    lt = tio.tio_trace_build(cfg)
+    if tau is not None:
+        lt.set_tau(tau)
+    ll = tio.tio_analyze_lifetimes(lt)
+    M = ll.export()["M"]
+    peak = int(M.max())
+    cap = int(cfg["cap_bytes"]) if "cap_bytes" in cfg else int((base_peak or peak) * cfg["cap_frac"]) // 256 * 256
+    tokens = cfg["B"] * cfg["T"]
+    print(f"{name}: {len(M)} kernels, uncapped peak {peak / 1e9:.2f} GB, cap {cap / 1e9:.2f} GB, {tokens} tokens/step, "
+          f"micro-batches {micro_batches}, kernel times {'measured' if tau is not None else 'modelled'}", file=out)
+    print(f"{'GB/s':>7} {'step ms':>10} {'tokens/s':>10} {'of ideal':>9} {'GB/direction':>13} {'bound ms':>9} {'pairs':>6} {'urgent':>7}", file=out)
+    rows = []
+    for bw in bws:
+        plan = tio.tio_build_plan(lt, ll, cap, int(bw), min_bytes=min_bytes)
+        pe = plan.export()
+        step, comp = tio.tio_plan_simulate(lt, plan, int(bw))
+        gb = pe["bytes_per_direction"] / 1e9
+        bound = pe["bytes_per_direction"] / bw * 1e3 if bw else 0.0
+        rows.append((bw, step, comp, pe))
+        print(f"{bw / 1e9:7.1f} {step / 1e6:10.1f} {tokens / (step / 1e9):10.0f} {comp / step:9.3f} {gb:13.2f} {bound:9.1f} "
+              f"{pe['n_greedy'] + pe['n_forced']:6d} {pe['n_forced']:7d}", file=out)
+    return rows
+
+
+def characterize(name, micro_batches=1, out=sys.stdout):
+    cfg, _ = _cfg(name, micro_batches)
+    lt = tio.tio_trace_build(cfg)
+    tv = lt.export()
+    ll = tio.tio_analyze_lifetimes(lt).export()
+    M = ll["M"].astype(np.float64)
+    size = tv["tensor_bytes"].astype(np.float64)
+    off = tv["operand_off"]
+    act = np.array([size[tv["operand_tensor"][off[k]:off[k + 1]]].sum() for k in range(tv["n_kernels"])])
+    share = act / M
+    tau = tv["tau"].astype(np.float64)
+    w = tau / tau.sum()
+    print(f"{name}: share of the allocated bytes a kernel touches (time-weighted mean {np.sum(share * w):.4f}, "
+          f"median {np.median(share):.4f}, 90th percentile {np.quantile(share, 0.9):.4f}, max {share.max():.4f})", file=out)
+    # inactive periods in time: from the end of the bounding kernel `start` to the start of kernel `end`
+    t_end = np.cumsum(tau)
+    t_beg = t_end - tau
+    total = tau.sum()
+    N = tv["n_kernels"]
+    s, e, b = ll["start"], ll["end"], ll["bytes"].astype(np.float64)
+    length = np.where(e < N, t_beg[e % N] - t_end[s], total - t_end[s] + t_beg[e % N])
+    edges = [0, 1e4, 1e5, 1e6, 1e7, 1e8, 1e9, 1e10, np.inf]
+    labels = ["<10us", "10-100us", "0.1-1ms", "1-10ms", "10-100ms", "0.1-1s", "1-10s", ">10s"]
+    print(f"  {len(length)} inactive periods; by length (modelled kernel times): count, share of the period bytes", file=out)
+    for lo, hi, lab in zip(edges[:-1], edges[1:], labels):
+        m = (length >= lo) & (length < hi)
+        if m.any():
+            print(f"    {lab:>9}: {int(m.sum()):6d}  {b[m].sum() / b.sum():6.3f}", file=out)
+    big = b >= 10e6
+    print(f"  periods of tensors of at least 10 MB: {int(big.sum())} of {len(b)}, {b[big].sum() / b.sum():.3f} of the bytes", file=out)
+
+
+def main(argv=None):
+    ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
+    ap.add_argument("--workload", nargs="+", default=["gpt2_small_bf16"])
+    ap.add_argument("--bw", nargs="+", type=float, default=[8, 16, 25, 32, 48, 64], help="GB/s per direction")
+    ap.add_argument("--micro-batches", type=int, default=1)
+    ap.add_argument("--min-bytes", type=int, default=1 << 20)
+    ap.add_argument("--tau", help="file with measured kernel times in ns, one per line")
+    ap.add_argument("--characterize", action="store_true")
+    a = ap.parse_args(argv)
+    tau = np.loadtxt(a.tau, dtype=np.int64) if a.tau else None
+    for name in a.workload:
+        sweep(name, [int(b * 1e9) for b in a.bw], a.micro_batches, tau, a.min_bytes)
+        if a.characterize:
+            characterize(name, a.micro_batches)
+        print()
+
+
+if __name__ == "__main__":
+    main()

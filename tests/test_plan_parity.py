@@ -166,3 +166,74 @@ def test_gpt2_small_plan_bit_exact_at_full_size():
     cap = int(max(op.analyze_lifetimes(tr)["M"]) * cfg["cap_frac"])
     pl = assert_same_plan(tr, lt, ll, cap, 25 * 10**9, min_bytes=1 << 20)
     assert pl["bytes_per_direction"] >= max(op.analyze_lifetimes(tr)["M"]) - cap
+
+
+def test_library_exports_every_declared_symbol():
+    import os
+    import re
+    hdr = open(os.path.join(os.path.dirname(__file__), "..", "include", "teraio.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    names = sorted(set(re.findall(r"\b(tio_[a-z0-9_]+)\s*\(", hdr)))
+    assert len(names) >= 30 and "tio_train_step" in names and "tio_plan_simulate" in names
+    lib = tio.binding.lib()
+    missing = [n for n in names if not hasattr(lib, n)]
+    assert not missing, missing
+
+
+@pytest.mark.parametrize("name,frac", [("tiny_gpt_fp32", 0.5), ("tiny_llama_fp32", 0.4), ("gpt2_small_bf16", 0.4)])
+def test_performance_model_bit_exact(name, frac):
+    """tio_plan_simulate against the oracle's model (itself pinned by the hand-worked examples): same integer
+    nanoseconds for every bandwidth, duplex or not, and for one to three iterations."""
+    cfg = CONFIGS[name] if name != "gpt2_small_bf16" else dict(CONFIGS[name], L=3)
+    tr = ot.build_trace(cfg)
+    lt = tio.tio_trace_build(cfg)
+    ll = tio.tio_analyze_lifetimes(lt)
+    life = op.analyze_lifetimes(tr)
+    cap = int(max(life["M"]) * frac) // 256 * 256
+    for bw in (10**9, 25 * 10**9, 0):
+        for duplex in (True, False):
+            pl = tio.tio_build_plan(lt, ll, cap, bw, duplex=duplex)
+            pe = pl.export()
+            ref = op.build_plan(tr, life, pe["planning_cap"], bw, duplex=duplex)
+            assert pe["entries"] == ref["entries"]
+            for sim_bw in (bw, 5 * 10**9):
+                for it in (1, 3):
+                    want = orp.simulate(tr, ref, sim_bw, duplex=duplex, iterations=it)
+                    got = tio.tio_plan_simulate(lt, pl, sim_bw, duplex=duplex, iterations=it)
+                    assert got == (want["step_ns"], want["compute_ns"]), (bw, duplex, sim_bw, it)
+
+
+def test_performance_model_golden_through_the_c_abi():
+    tr, cap, bw, entries, Mp, _ = load_golden("plan_example_c.txt")
+    lt = lib_trace_from_oracle(tr)
+    ll = tio.tio_analyze_lifetimes(lt)
+    pl = tio.tio_build_plan(lt, ll, cap, bw, arena_bytes=1 << 20)
+    # the one pair is fully exposed: 8 kernels of 100 ns + 150 ns offload + 150 ns prefetch
+    assert tio.tio_plan_simulate(lt, pl, bw) == (1100, 800)
+    assert tio.tio_plan_simulate(lt, tio.tio_build_plan(lt, ll, 10**6, bw, arena_bytes=1 << 21), bw) == (800, 800)
+    with pytest.raises(tio.TioError):
+        tio.tio_plan_simulate(lt, pl, bw, iterations=0)
+
+
+def test_performance_model_invariants_and_sweep_tool():
+    """For a fixed plan the predicted step time never grows with bandwidth, equals the compute time when
+    transfers are instantaneous, and is at least max(compute, bytes / bandwidth); the sweep tool runs."""
+    import io
+    from paper_2506_06472_amd import sweep as sw
+    cfg = dict(CONFIGS["gpt2_small_bf16"], L=4, V=8192)
+    lt = tio.tio_trace_build(cfg)
+    ll = tio.tio_analyze_lifetimes(lt)
+    cap = int(ll.export()["M"].max() * 0.5) // 256 * 256
+    pl = tio.tio_build_plan(lt, ll, cap, 25 * 10**9)
+    moved = pl.export()["bytes_per_direction"]
+    prev = None
+    for bw in (10**9, 4 * 10**9, 25 * 10**9, 10**11, 10**13):
+        step, comp = tio.tio_plan_simulate(lt, pl, bw)
+        assert step >= comp and step >= moved * 10**9 // bw
+        assert prev is None or step <= prev
+        prev = step
+    assert tio.tio_plan_simulate(lt, pl, 0) == (comp, comp)
+    out = io.StringIO()
+    rows = sw.sweep("tiny_gpt_fp32", [10**9, 25 * 10**9], out=out)
+    sw.characterize("tiny_gpt_fp32", out=out)
+    assert len(rows) == 2 and rows[0][1] >= rows[0][2] and "inactive periods" in out.getvalue()
