@@ -17,6 +17,16 @@ still above capacity, the forced pass realises the "kernel stalls / urgent
 migrations" paragraph of Section 3.2: at each over-capacity kernel the
 inactive tensor whose next use is furthest away is evicted and marked urgent.
 
+Two destinations ("Decide offloading destination", Section 3.2): with host_bw > 0 there is, besides the
+slow tier (the paper's SSDs: preferred, unlimited), a host-memory tier with its own pair of channels, its
+own bandwidth and a byte budget.  Reading: the slow tier is saturated for a candidate when the transfers
+already planned on its channels displace the candidate (its offload cannot begin when the tensor becomes
+inactive, or its prefetch cannot end when it becomes active again, or it does not fit at all); only then
+is the candidate also evaluated on the host tier, provided the budget still has room for it during its
+whole inactive period, and it goes to the host when that gives the larger benefit.  Forced (urgent)
+evictions of periods not selected before go to the host when the budget has room, because a stalled
+kernel waits for exactly these transfers.
+
 Pins (tests/test_oracle_plan.py): hand-worked cases under tests/golden/,
 capacity >= peak gives the empty plan, traffic lower bound, invariance under
 permutation of the period list, exhaustive search on tiny traces, and the
@@ -148,8 +158,9 @@ class Channel:
 # ----------------------------------------------------------------------------
 # Section 3.2: Algorithm 1 and the forced (urgent) pass
 # ----------------------------------------------------------------------------
-def build_plan(trace, life, cap, bw, duplex=True, min_bytes=0):
-    """Returns dict(entries=[(tensor, kind, trigger, deadline, urgent, pair)], Mp=[...], n_greedy, n_forced).
+def build_plan(trace, life, cap, bw, duplex=True, min_bytes=0, host_bw=0, host_budget=0):
+    """Returns dict(entries=[(tensor, kind, trigger, deadline, urgent, pair)], Mp=[...], n_greedy, n_forced,
+    tier=[0 slow tier | 1 host tier, per pair], host_peak=bytes).
 
     trigger/deadline are unrolled kernel indices in [0, 2N]: an entry is issued
     just before kernel (trigger mod N) is launched, after kernel trigger-1 has
@@ -169,10 +180,47 @@ def build_plan(trace, life, cap, bw, duplex=True, min_bytes=0):
     small = sorted(p for p in life["periods"] if p[1] < min_bytes)
     ch_off = Channel(Ttot)
     ch_pre = ch_off if not duplex else Channel(Ttot)
+    two_tier = host_bw > 0 and host_budget > 0
+    hch_off = Channel(Ttot)                                # the host tier's own channels
+    hch_pre = hch_off if not duplex else Channel(Ttot)
+    Mh = [0] * N                                           # bytes held in host memory while kernel k runs
     sel = []                     # [t, s, start, end, k_off, k_pre, urgent_off, urgent_pre] in selection order
+    tier = []                    # destination of each selected period
 
     def dur(s):                                            # bw == 0 stands for unlimited bandwidth
         return -(-s * 10**9 // bw) if bw else 0
+
+    def hdur(s):
+        return -(-s * 10**9 // host_bw)
+
+    def host_fits(s, start, end):
+        """room in the host budget while the tensor is away: kernels start+1 .. end-1"""
+        return all(Mh[k % N] + s <= host_budget for k in range(start + 1, end))
+
+    def host_take(s, start, end):
+        for k in range(start + 1, end):
+            Mh[k % N] += s
+
+    def evaluate(c_off, c_pre, lo, hi, d, over):
+        """(score, g, t_offloaded, t_prefetch, k_off, k_pre) of a candidate on one tier's channels, or None"""
+        g = c_off.earliest_gap(lo, hi, d)
+        if g is None:
+            return None
+        t_offloaded = g + d
+        g2 = c_pre.latest_gap(lo, hi, d)
+        if g2 is None:
+            return None
+        t_prefetch = g2
+        if not t_offloaded < t_prefetch:
+            return None
+        k_off = bisect.bisect_left(T, t_offloaded)               # first kernel starting at or after
+        k_pre = bisect.bisect_right(T, t_prefetch) - 2           # last kernel ending at or before
+        if k_off > k_pre:
+            return None
+        score = over[k_pre + 1] - over[k_off]                    # B / s = sum of tau over C
+        if score <= 0:
+            return None
+        return score, g, t_offloaded, t_prefetch, k_off, k_pre
 
     # ---- Algorithm 1
     while max(Mp) > cap:
@@ -183,35 +231,35 @@ def build_plan(trace, life, cap, bw, duplex=True, min_bytes=0):
         for (t, s, start, end) in I:
             d = dur(s)
             lo, hi = T[start + 1], T[end]
-            g = ch_off.earliest_gap(lo, hi, d)
-            if g is None:
+            ev, where = evaluate(ch_off, ch_pre, lo, hi, d, over), 0
+            if two_tier:
+                # slow tier saturated for this candidate: planned transfers displace it (or leave it no room)
+                displaced = ev is None or ev[1] > lo or ev[3] + d < hi
+                if displaced and host_fits(s, start, end):
+                    hev = evaluate(hch_off, hch_pre, lo, hi, hdur(s), over)
+                    if hev is not None and (ev is None or hev[0] > ev[0]):
+                        ev, where, d = hev, 1, hdur(s)
+            if ev is None:
                 continue
-            t_offloaded = g + d
-            g2 = ch_pre.latest_gap(lo, hi, d)
-            if g2 is None:
-                continue
-            t_prefetch = g2
-            if not t_offloaded < t_prefetch:
-                continue
-            k_off = bisect.bisect_left(T, t_offloaded)               # first kernel starting at or after
-            k_pre = bisect.bisect_right(T, t_prefetch) - 2           # last kernel ending at or before
-            if k_off > k_pre:
-                continue
-            score = over[k_pre + 1] - over[k_off]                    # B / s = sum of tau over C
-            if score <= 0:
-                continue
+            score, g, t_offloaded, t_prefetch, k_off, k_pre = ev
             key = (score, s, -start, -t, -end)
             if best is None or key > best[0]:
-                best = (key, (t, s, start, end), g, t_offloaded, t_prefetch, k_off, k_pre, d)
+                best = (key, (t, s, start, end), g, t_offloaded, t_prefetch, k_off, k_pre, d, where)
         if best is None:
             break
-        _, per, g, t_offloaded, t_prefetch, k_off, k_pre, d = best
+        _, per, g, t_offloaded, t_prefetch, k_off, k_pre, d, where = best
         t, s, start, end = per
         sel.append([t, s, start, end, k_off, k_pre, 0, 0])
+        tier.append(where)
         for k in range(k_off, k_pre + 1):
             Mp[k % N] -= s
-        ch_off.insert(g, t_offloaded)
-        ch_pre.insert(t_prefetch, t_prefetch + d)
+        if where == 0:
+            ch_off.insert(g, t_offloaded)
+            ch_pre.insert(t_prefetch, t_prefetch + d)
+        else:
+            hch_off.insert(g, t_offloaded)
+            hch_pre.insert(t_prefetch, t_prefetch + d)
+            host_take(s, start, end)
         I.remove(per)
     n_greedy = len(sel)
 
@@ -265,6 +313,11 @@ def build_plan(trace, life, cap, bw, duplex=True, min_bytes=0):
                 (I if ref in I else small).remove(ref)
                 rec = [t, s, start, end, kk, kk - 1, 1, 1]          # empty window, grown below
                 sel.append(rec)
+                if two_tier and host_fits(s, start, end):           # a stalled kernel waits for these transfers
+                    tier.append(1)
+                    host_take(s, start, end)
+                else:
+                    tier.append(0)
             else:
                 rec = sel[ref]
             t, s, start, end, k_off, k_pre = rec[:6]
@@ -286,4 +339,4 @@ def build_plan(trace, life, cap, bw, duplex=True, min_bytes=0):
         entries.append((t, OFFLOAD, start + 1, k_off, u_off, pair))
         entries.append((t, PREFETCH, k_pre + 1, end, u_pre, pair))
     entries.sort(key=lambda e: (e[2] % N, e[1], -e[4], e[0], e[5]))
-    return dict(entries=entries, Mp=Mp, n_greedy=n_greedy, n_forced=len(sel) - n_greedy)
+    return dict(entries=entries, Mp=Mp, n_greedy=n_greedy, n_forced=len(sel) - n_greedy, tier=tier, host_peak=max(Mh))

@@ -38,7 +38,9 @@ def absent_windows(entries, N):
     return out
 
 
-def check_plan(trace, life, plan, cap):
+def check_plan(trace, life, plan, cap, host_budget=None):
+    """With host_budget: also recounts the bytes held by the host tier at every kernel (a host-tier pair
+    occupies it for its whole inactive period) and checks them against the budget."""
     N = len(trace["kernels"])
     entries = plan["entries"]
     win = absent_windows(entries, N)
@@ -58,16 +60,30 @@ def check_plan(trace, life, plan, cap):
         moved += s
     assert M2 == list(plan["Mp"]), "planner's memory estimate differs from a recount"
     assert max(M2) <= cap, "resident bytes exceed the capacity"
+    tier = plan.get("tier") or [0] * len(win)
+    assert len(tier) == len(win) and all(x in (0, 1) for x in tier)
+    Mh = [0] * N
+    for pair, (t, k_off, k_pre, start, end) in win.items():
+        if tier[pair]:
+            for k in range(start + 1, end):
+                Mh[k % N] += trace["tensors"][t][0]
+    if host_budget is not None:
+        assert max(Mh) <= host_budget, "host tier holds more than its budget"
+        assert max(Mh) == plan.get("host_peak", 0)
+    else:
+        assert not any(tier), "host-tier pairs in a single-tier plan"
     if entries:
         assert moved >= max(life["M"]) - cap, "moved fewer bytes than peak - capacity"
     # sorted in issue order
     key = lambda e: (e[2] % N, e[1], -e[4], e[0], e[5])
     assert list(entries) == sorted(entries, key=key)
-    return dict(bytes_per_direction=moved, pairs=len(win))
+    return dict(bytes_per_direction=moved, pairs=len(win), host_pairs=sum(tier), host_peak=max(Mh),
+                host_bytes_per_direction=sum(trace["tensors"][win[p][0]][0] for p in win if tier[p]))
 
 
-def simulate(trace, plan, bw, duplex=True, iterations=3):
-    """Predicted duration (ns) of the last simulated iteration, and the compute-only time."""
+def simulate(trace, plan, bw, duplex=True, iterations=3, host_bw=0):
+    """Predicted duration (ns) of the last simulated iteration, and the compute-only time.  Pairs of the
+    host tier move on that tier's own two channels at host_bw."""
     tau = trace["tau"]
     N = len(tau)
     entries = plan["entries"]
@@ -79,9 +95,15 @@ def simulate(trace, plan, bw, duplex=True, iterations=3):
     for (t, kind, trig, dl, urgent, pair) in entries:
         (off_deadline if kind == OFFLOAD else pre_deadline)[dl % N].append(pair)
     size = {e[5]: trace["tensors"][e[0]][0] for e in entries}
-    dur = lambda s: -(-s * 10**9 // bw) if bw else 0
+    tier = plan.get("tier") or [0] * (len(entries) // 2)
+    rate = (bw, host_bw)
+
+    def dur(pair):
+        r = rate[tier[pair]]
+        return -(-size[pair] * 10**9 // r) if r else 0
+
     off_done, pre_done = {}, {}
-    d2h_free = h2d_free = 0
+    d2h_free, h2d_free = [0, 0], [0, 0]      # per tier
     done_prev = 0            # completion of the previous kernel
     mem_ready = 0            # completion of every offload whose deadline has been passed
     t_iter = []
@@ -91,17 +113,18 @@ def simulate(trace, plan, bw, duplex=True, iterations=3):
             for p in off_deadline[k]:
                 mem_ready = max(mem_ready, off_done.get(p, 0))
             for (t, kind, trig, dl, urgent, pair) in by_trigger[k]:
-                d = dur(size[pair])
+                d = dur(pair)
+                w = tier[pair]
                 if kind == OFFLOAD:
-                    st = max(d2h_free, done_prev)
-                    off_done[pair] = d2h_free = st + d
+                    st = max(d2h_free[w], done_prev)
+                    off_done[pair] = d2h_free[w] = st + d
                     if not duplex:
-                        h2d_free = d2h_free
+                        h2d_free[w] = d2h_free[w]
                 else:
-                    st = max(h2d_free, done_prev, off_done.get(pair, 0), mem_ready)
-                    pre_done[pair] = h2d_free = st + d
+                    st = max(h2d_free[w], done_prev, off_done.get(pair, 0), mem_ready)
+                    pre_done[pair] = h2d_free[w] = st + d
                     if not duplex:
-                        d2h_free = h2d_free
+                        d2h_free[w] = h2d_free[w]
             st = max(done_prev, mem_ready)
             for p in pre_deadline[k]:
                 st = max(st, pre_done.get(p, 0))

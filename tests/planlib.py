@@ -51,6 +51,19 @@ def load_golden(name):
     return tr, cap, bw, entries, Mp, err
 
 
+def load_golden_two_tier(name):
+    """Golden file with a host tier: the fields of load_golden plus host_bw, host_budget and the tier of each pair."""
+    tr, cap, bw, entries, Mp, err = load_golden(name)
+    extra = {}
+    for line in open(os.path.join(GOLDEN, name)):
+        w = line.split("#")[0].split()
+        if w and w[0] in ("host_bw", "host_budget"):
+            extra[w[0]] = int(w[1])
+        elif w and w[0] == "tier":
+            extra["tier"] = [int(x) for x in w[1:]]
+    return dict(trace=tr, cap=cap, bw=bw, entries=entries, Mp=Mp, **extra)
+
+
 def random_trace(rng, N, n_pers, n_trans, max_bytes=1000):
     """Random small trace: every kernel has at least one operand, sizes multiples of 8."""
     tensors = []
