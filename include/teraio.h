@@ -115,6 +115,12 @@ typedef struct tio_plan_view {
     uint64_t arena_bytes_needed;     /* highest address used + size */
     uint64_t host_bytes_needed;
     uint64_t bytes_per_direction;    /* sum of sizes of migrated periods */
+    /* host-memory tier (all zero / tier 0 everywhere when the plan was built without one) */
+    int32_t n_pairs, reserved2;
+    const int32_t *pair_tier;        /* [n_pairs] destination of each selected period (entry.pair): 0 slow tier, 1 host tier */
+    uint64_t host_tier_bytes_needed; /* pool size of the host-memory tier (slots are reused over time) */
+    uint64_t host_tier_peak_bytes;   /* most bytes the planner counts in host memory at any kernel (<= the budget) */
+    uint64_t host_tier_bw;
 } tio_plan_view;
 
 typedef struct tio_plan_opts {
@@ -122,6 +128,14 @@ typedef struct tio_plan_opts {
     int32_t layout_retries;          /* how many times the planning capacity may be lowered (default 24) */
     uint64_t min_bytes;              /* periods of smaller tensors are candidates of last resort only (default 0) */
     uint64_t arena_bytes;            /* arena the layout must fit; 0 = cap_bytes */
+    /* Destination choice (Section 3.2, "Decide offloading destination"): a second, faster tier in host memory
+     * with its own two channels.  The slow tier stays the preferred destination; a period goes to the host tier
+     * when the transfers already planned on the slow tier displace it (the slow tier is saturated for it), the
+     * host tier gives the larger benefit, and the bytes held in host memory stay within host_budget during its
+     * whole inactive period.  Forced (urgent) evictions go to the host tier while the budget has room.
+     * host_bw = 0 or host_budget = 0: no host tier (default). */
+    uint64_t host_bw;                /* bytes/s per direction of the host-memory tier */
+    uint64_t host_budget;            /* most bytes host memory may hold for migrated tensors */
 } tio_plan_opts;
 
 typedef struct tio_step_stats {

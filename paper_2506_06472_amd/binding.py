@@ -67,12 +67,14 @@ class PlanView(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("n_kernels", "n_entries", "n_greedy", "n_forced", "n_allocs", "reserved")] + \
                [("entries", C.POINTER(PlanEntry)), ("Mp", C.POINTER(C.c_uint64)), ("allocs", C.POINTER(Alloc))] + \
                [(n, C.c_uint64) for n in ("cap_bytes", "planning_cap_bytes", "arena_bytes_needed",
-                                          "host_bytes_needed", "bytes_per_direction")]
+                                          "host_bytes_needed", "bytes_per_direction")] + \
+               [("n_pairs", C.c_int32), ("reserved2", C.c_int32), ("pair_tier", C.POINTER(C.c_int32))] + \
+               [(n, C.c_uint64) for n in ("host_tier_bytes_needed", "host_tier_peak_bytes", "host_tier_bw")]
 
 
 class PlanOpts(C.Structure):
     _fields_ = [("duplex", C.c_int32), ("layout_retries", C.c_int32), ("min_bytes", C.c_uint64),
-                ("arena_bytes", C.c_uint64)]
+                ("arena_bytes", C.c_uint64), ("host_bw", C.c_uint64), ("host_budget", C.c_uint64)]
 
 
 class StepStats(C.Structure):
@@ -233,12 +235,14 @@ class Plan:
         return dict(entries=entries, Mp=[int(x) for x in _arr(v.Mp, v.n_kernels, np.uint64)], allocs=allocs,
                     n_greedy=v.n_greedy, n_forced=v.n_forced, cap=v.cap_bytes, planning_cap=v.planning_cap_bytes,
                     arena_needed=v.arena_bytes_needed, host_needed=v.host_bytes_needed,
-                    bytes_per_direction=v.bytes_per_direction)
+                    bytes_per_direction=v.bytes_per_direction,
+                    tier=[int(x) for x in _arr(v.pair_tier, v.n_pairs, np.int32)],
+                    host_tier_needed=v.host_tier_bytes_needed, host_peak=v.host_tier_peak_bytes, host_bw=v.host_tier_bw)
 
 
 def tio_build_plan(trace: Trace, life: Lifetimes, mem_cap_bytes: int, slow_tier_bw: int, duplex=True,
-                   min_bytes=0, arena_bytes=0, layout_retries=24) -> Plan:
-    o = PlanOpts(1 if duplex else 0, layout_retries, min_bytes, arena_bytes)
+                   min_bytes=0, arena_bytes=0, layout_retries=24, host_bw=0, host_budget=0) -> Plan:
+    o = PlanOpts(1 if duplex else 0, layout_retries, min_bytes, arena_bytes, int(host_bw), int(host_budget))
     h = C.c_void_p()
     _check(lib().tio_build_plan(trace.h, life.h, C.c_uint64(mem_cap_bytes), C.c_uint64(slow_tier_bw), C.byref(o),
                                 C.byref(h)))

@@ -168,7 +168,7 @@ struct ForcedKey {
 }  // namespace
 
 void select_periods(const Trace &t, const Lifetimes &life, uint64_t cap, uint64_t bw, bool duplex,
-                    uint64_t min_bytes, Plan &out) {
+                    uint64_t min_bytes, uint64_t host_bw, uint64_t host_budget, Plan &out) {
     const int N = t.n_kernels;
     const std::vector<int64_t> &tau = t.tau;
     std::vector<int64_t> T(2 * N + 1, 0);
@@ -180,8 +180,26 @@ void select_periods(const Trace &t, const Lifetimes &life, uint64_t cap, uint64_
         (p.bytes >= min_bytes ? I : small).push_back({p.tensor, p.bytes, p.start, p.end, true});
     Channel ch_off{Ttot, {}, {}}, ch_pre_own{Ttot, {}, {}};
     Channel &ch_pre = duplex ? ch_pre_own : ch_off;
+    // Destination choice (Section 3.2): besides the slow tier a host-memory tier with its own channels, its own
+    // bandwidth and a byte budget.  The slow tier is saturated for a candidate when the transfers already planned
+    // on its channels displace it (or leave it no room); only then is the candidate also evaluated on the host
+    // tier, provided the budget has room for it during its whole inactive period, and it goes there when that
+    // gives the larger benefit.
+    const bool two_tier = host_bw > 0 && host_budget > 0;
+    Channel hch_off{Ttot, {}, {}}, hch_pre_own{Ttot, {}, {}};
+    Channel &hch_pre = duplex ? hch_pre_own : hch_off;
+    std::vector<uint64_t> Mh(N, 0);                     // bytes held in host memory while kernel k runs
+    auto host_fits = [&](uint64_t s, int32_t start, int32_t end) {
+        for (int k = start + 1; k < end; ++k) if (Mh[k % N] + s > host_budget) return false;
+        return true;
+    };
+    auto host_take = [&](uint64_t s, int32_t start, int32_t end) {
+        for (int k = start + 1; k < end; ++k) Mh[k % N] += s;
+    };
     std::vector<Pair> sel;
     auto dur = [&](uint64_t s) -> int64_t { return bw ? (int64_t)(((u128)s * 1000000000ull + bw - 1) / bw) : 0; };
+    auto hdur = [&](uint64_t s) -> int64_t { return (int64_t)(((u128)s * 1000000000ull + host_bw - 1) / host_bw); };
+    struct Eval { bool ok; int64_t score, g, t_offloaded, t_prefetch; int32_t k_off, k_pre; };
 
     // ---- Algorithm 1
     std::vector<int64_t> over(2 * N + 1);
@@ -191,34 +209,60 @@ void select_periods(const Trace &t, const Lifetimes &life, uint64_t cap, uint64_
         int best = -1;
         int64_t best_score = 0, bg = 0, bto = 0, btp = 0, bd = 0;
         int32_t bko = 0, bkp = 0;
+        // benefit of a candidate on one tier's channels
+        auto evaluate = [&](Channel &c_off, Channel &c_pre, int64_t lo, int64_t hi, int64_t d) -> Eval {
+            Eval e{false, 0, 0, 0, 0, 0, 0};
+            e.g = c_off.earliest(lo, hi, d);
+            if (e.g < 0) return e;
+            e.t_offloaded = e.g + d;
+            e.t_prefetch = c_pre.latest(lo, hi, d);
+            if (e.t_prefetch < 0 || !(e.t_offloaded < e.t_prefetch)) return e;
+            e.k_off = (int32_t)(std::lower_bound(T.begin(), T.end(), e.t_offloaded) - T.begin());
+            e.k_pre = (int32_t)(std::upper_bound(T.begin(), T.end(), e.t_prefetch) - T.begin()) - 2;
+            if (e.k_off > e.k_pre) return e;
+            e.score = over[e.k_pre + 1] - over[e.k_off];             // B / s = sum of tau over the region C
+            e.ok = e.score > 0;
+            return e;
+        };
+        int best_tier = 0;
         for (int i = 0; i < (int)I.size(); ++i) {
             const Cand &c = I[i];
             if (!c.alive) continue;
-            const int64_t d = dur(c.bytes), lo = T[c.start + 1], hi = T[c.end];
-            const int64_t g = ch_off.earliest(lo, hi, d);
-            if (g < 0) continue;
-            const int64_t t_offloaded = g + d;
-            const int64_t t_prefetch = ch_pre.latest(lo, hi, d);
-            if (t_prefetch < 0 || !(t_offloaded < t_prefetch)) continue;
-            const int32_t k_off = (int32_t)(std::lower_bound(T.begin(), T.end(), t_offloaded) - T.begin());
-            const int32_t k_pre = (int32_t)(std::upper_bound(T.begin(), T.end(), t_prefetch) - T.begin()) - 2;
-            if (k_off > k_pre) continue;
-            const int64_t score = over[k_pre + 1] - over[k_off];     // B / s = sum of tau over the region C
-            if (score <= 0) continue;
+            int64_t d = dur(c.bytes);
+            const int64_t lo = T[c.start + 1], hi = T[c.end];
+            Eval ev = evaluate(ch_off, ch_pre, lo, hi, d);
+            int where = 0;
+            if (two_tier) {
+                const bool displaced = !ev.ok || ev.g > lo || ev.t_prefetch + d < hi;
+                if (displaced && host_fits(c.bytes, c.start, c.end)) {
+                    const Eval hev = evaluate(hch_off, hch_pre, lo, hi, hdur(c.bytes));
+                    if (hev.ok && (!ev.ok || hev.score > ev.score)) { ev = hev; where = 1; d = hdur(c.bytes); }
+                }
+            }
+            if (!ev.ok) continue;
+            const int64_t score = ev.score, g = ev.g, t_offloaded = ev.t_offloaded, t_prefetch = ev.t_prefetch;
+            const int32_t k_off = ev.k_off, k_pre = ev.k_pre;
             bool take = best < 0;
             if (!take) {
                 const Cand &o = I[best];
                 take = std::make_tuple(score, c.bytes, -c.start, -c.tensor, -c.end) >
                        std::make_tuple(best_score, o.bytes, -o.start, -o.tensor, -o.end);
             }
-            if (take) { best = i; best_score = score; bg = g; bto = t_offloaded; btp = t_prefetch; bd = d; bko = k_off; bkp = k_pre; }
+            if (take) { best = i; best_score = score; bg = g; bto = t_offloaded; btp = t_prefetch; bd = d; bko = k_off; bkp = k_pre; best_tier = where; }
         }
         if (best < 0) break;
         Cand &c = I[best];
         sel.push_back({c.tensor, c.bytes, c.start, c.end, bko, bkp, 0, 0});
+        sel.back().tier = best_tier;
         for (int k = bko; k <= bkp; ++k) Mp[k % N] -= c.bytes;
-        ch_off.insert(bg, bto);
-        ch_pre.insert(btp, btp + bd);
+        if (best_tier == 0) {
+            ch_off.insert(bg, bto);
+            ch_pre.insert(btp, btp + bd);
+        } else {
+            hch_off.insert(bg, bto);
+            hch_pre.insert(btp, btp + bd);
+            host_take(c.bytes, c.start, c.end);
+        }
         c.alive = false;
     }
     out.n_greedy = (int32_t)sel.size();
@@ -264,6 +308,11 @@ void select_periods(const Trace &t, const Lifetimes &life, uint64_t cap, uint64_
                 c.alive = false;
                 sel.push_back({c.tensor, c.bytes, c.start, c.end, bkk, bkk - 1, 1, 1});   // empty window, grown below
                 idx = (int)sel.size() - 1;
+                // a stalled kernel waits for exactly these transfers: the faster tier when its budget has room
+                if (two_tier && host_fits(c.bytes, c.start, c.end)) {
+                    sel.back().tier = 1;
+                    host_take(c.bytes, c.start, c.end);
+                }
             }
             Pair &p = sel[idx];
             if (bkk < p.k_off) {                       // pull the offload deadline forward
@@ -278,6 +327,8 @@ void select_periods(const Trace &t, const Lifetimes &life, uint64_t cap, uint64_
         }
     }
     out.n_forced = (int32_t)sel.size() - out.n_greedy;
+    out.host_peak = *std::max_element(Mh.begin(), Mh.end());
+    out.host_bw = host_bw;
     out.n_kernels = N;
     out.Mp = Mp;
     out.pairs = sel;
@@ -384,10 +435,40 @@ bool assign_addresses(const Trace &t, const Lifetimes &life, uint64_t arena_byte
     plan.persistent_home.assign(t.n_persistent, 0);
     for (int id = 0; id < t.n_persistent; ++id) { plan.persistent_home[id] = h; h += t.tensor_bytes[id]; }
     for (Pair &p : plan.pairs) {
+        if (p.tier != 0) continue;
         if (p.tensor < t.n_persistent) p.host_offset = plan.persistent_home[p.tensor];
         else { p.host_offset = h; h += p.bytes; }
     }
     plan.host_needed = h;
+    // host-memory tier: a pair holds its slot during its whole inactive period; slots are reused over time
+    // (first fit, selection order), so the pool stays close to the peak the budget allows
+    {
+        std::vector<int> placed;
+        uint64_t top = 0;
+        auto overlap = [&](const Pair &x, const Pair &y) {
+            auto ov = [](int a0, int a1, int b0, int b1) { return a0 <= b1 && b0 <= a1; };
+            const int x0 = x.start + 1, x1 = x.end - 1, y0 = y.start + 1, y1 = y.end - 1;
+            return ov(x0, x1, y0, y1) || ov(x0, x1, y0 + N, y1 + N) || ov(x0 + N, x1 + N, y0, y1);
+        };
+        for (int i = 0; i < (int)plan.pairs.size(); ++i) {
+            Pair &p = plan.pairs[i];
+            if (p.tier != 1) continue;
+            std::vector<std::pair<uint64_t, uint64_t>> busy;
+            for (int j : placed) if (overlap(p, plan.pairs[j])) busy.push_back({plan.pairs[j].host_offset, plan.pairs[j].host_offset + plan.pairs[j].bytes});
+            std::sort(busy.begin(), busy.end());
+            uint64_t addr = 0;
+            for (auto &iv : busy) {
+                if (addr + p.bytes <= iv.first) break;
+                addr = std::max(addr, iv.second);
+            }
+            p.host_offset = addr;
+            top = std::max(top, addr + p.bytes);
+            placed.push_back(i);
+        }
+        plan.host_tier_needed = top;
+    }
+    plan.pair_tier.clear();
+    for (const Pair &p : plan.pairs) plan.pair_tier.push_back(p.tier);
 
     // address reuse: the first writer of an allocation waits for the offload that emptied the range.
     // Sweep two cycles of the issue order with a map "address range -> last occupant".
@@ -449,9 +530,13 @@ SimResult simulate_plan(const Trace &t, const Plan &plan, uint64_t bw, bool dupl
     std::vector<std::vector<int32_t>> pre_deadline(N), off_deadline(N);
     for (const tio_plan_entry &e : plan.entries)
         (e.kind == TIO_OFFLOAD ? off_deadline : pre_deadline)[e.deadline % N].push_back(e.pair);
-    auto dur = [&](uint64_t bytes) -> int64_t { return bw ? (int64_t)((bytes * 1000000000ull + bw - 1) / bw) : 0; };
+    // pairs of the host-memory tier move on that tier's own two channels at the plan's host bandwidth
+    auto dur = [&](const Pair &p) -> int64_t {
+        const uint64_t r = p.tier ? plan.host_bw : bw;
+        return r ? (int64_t)(((u128)p.bytes * 1000000000ull + r - 1) / r) : 0;
+    };
     std::vector<int64_t> off_done(np, 0), pre_done(np, 0);
-    int64_t d2h_free = 0, h2d_free = 0;
+    int64_t d2h_free[2] = {0, 0}, h2d_free[2] = {0, 0};
     int64_t done_prev = 0;          // completion of the previous kernel
     int64_t mem_ready = 0;          // completion of every offload whose deadline has been passed
     int64_t last = 0, compute = 0;
@@ -462,15 +547,16 @@ SimResult simulate_plan(const Trace &t, const Plan &plan, uint64_t bw, bool dupl
             for (int32_t p : off_deadline[k]) mem_ready = std::max(mem_ready, off_done[p]);
             for (int32_t ei : plan.entries_at[k]) {
                 const tio_plan_entry &e = plan.entries[ei];
-                const int64_t d = dur(plan.pairs[e.pair].bytes);
+                const int64_t d = dur(plan.pairs[e.pair]);
+                const int w = plan.pairs[e.pair].tier;
                 if (e.kind == TIO_OFFLOAD) {
-                    const int64_t st = std::max(d2h_free, done_prev);
-                    off_done[e.pair] = d2h_free = st + d;
-                    if (!duplex) h2d_free = d2h_free;
+                    const int64_t st = std::max(d2h_free[w], done_prev);
+                    off_done[e.pair] = d2h_free[w] = st + d;
+                    if (!duplex) h2d_free[w] = d2h_free[w];
                 } else {
-                    const int64_t st = std::max(std::max(h2d_free, done_prev), std::max(off_done[e.pair], mem_ready));
-                    pre_done[e.pair] = h2d_free = st + d;
-                    if (!duplex) d2h_free = h2d_free;
+                    const int64_t st = std::max(std::max(h2d_free[w], done_prev), std::max(off_done[e.pair], mem_ready));
+                    pre_done[e.pair] = h2d_free[w] = st + d;
+                    if (!duplex) d2h_free[w] = h2d_free[w];
                 }
             }
             int64_t st = std::max(done_prev, mem_ready);
@@ -505,7 +591,7 @@ Plan build_plan(const Trace &t, const Lifetimes &life, uint64_t cap, uint64_t bw
     for (int r = 0; r <= retries; ++r) {
         Plan p;
         p.cap = cap; p.planning_cap = pc; p.bw = bw; p.structure_hash = t.structure_hash;
-        select_periods(t, life, pc, bw, o.duplex != 0, o.min_bytes, p);
+        select_periods(t, life, pc, bw, o.duplex != 0, o.min_bytes, o.host_bw, o.host_budget, p);
         if (assign_addresses(t, life, arena, p)) return p;
         if (pc <= step) break;
         pc -= step;

@@ -38,7 +38,8 @@ struct Pair {
     int32_t tensor; uint64_t bytes;
     int32_t start, end, k_off, k_pre;
     int32_t urgent_off, urgent_pre;
-    uint64_t host_offset = 0;          // slot in the slow-tier pool
+    int32_t tier = 0;                  // 0: slow tier, 1: host-memory tier
+    uint64_t host_offset = 0;          // slot in the pool of its tier
     int32_t alloc_before = -1;         // allocation that ends with this pair's offload
     int32_t alloc_after = -1;          // allocation that begins with this pair's prefetch
 };
@@ -57,6 +58,8 @@ struct Plan {
     int32_t n_kernels = 0;
     uint64_t cap = 0, planning_cap = 0, arena_needed = 0, host_needed = 0, bytes_moved = 0, bw = 0;
     int32_t n_greedy = 0, n_forced = 0;
+    uint64_t host_peak = 0, host_bw = 0, host_tier_needed = 0;   // host-memory tier: peak bytes held, bandwidth, pool bytes
+    std::vector<int32_t> pair_tier;              // exported view of Pair::tier
     uint64_t structure_hash = 0;
     uint64_t serial = 0;               // unique per built plan; the runtime uses it to notice a plan change
     std::vector<uint64_t> Mp;
@@ -82,7 +85,7 @@ struct PlanError { int code; std::string msg; };
 Plan build_plan(const Trace &t, const Lifetimes &life, uint64_t cap, uint64_t bw, const tio_plan_opts &opts);
 // Algorithm 1 + urgent pass only (no layout); fills pairs, Mp, n_greedy, n_forced.
 void select_periods(const Trace &t, const Lifetimes &life, uint64_t cap, uint64_t bw, bool duplex,
-                    uint64_t min_bytes, Plan &out);
+                    uint64_t min_bytes, uint64_t host_bw, uint64_t host_budget, Plan &out);
 // Address assignment and executor tables; returns false when the arena is too small.
 bool assign_addresses(const Trace &t, const Lifetimes &life, uint64_t arena_bytes, Plan &plan);
 void validate_plan(const Trace &t, const Lifetimes &life, const Plan &plan);   // throws PlanError

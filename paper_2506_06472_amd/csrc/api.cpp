@@ -145,7 +145,7 @@ int tio_build_plan(const tio_trace *trace, const tio_lifetimes *life, uint64_t c
     if (!trace || !life || !out) return fail(TIO_ERR_INVALID_ARG, "null argument");
     if (cap == 0) return fail(TIO_ERR_INVALID_ARG, "capacity must be positive");
     TIO_GUARD_BEGIN
-    tio_plan_opts o{1, 24, 0, 0};
+    tio_plan_opts o{1, 24, 0, 0, 0, 0};
     if (opts) o = *opts;
     static std::atomic<uint64_t> serial{1};
     tio_plan *h = new tio_plan{build_plan(trace->t, life->l, cap, bw, o)};
@@ -165,6 +165,9 @@ int tio_plan_export(const tio_plan *plan, tio_plan_view *out) {
     out->cap_bytes = p.cap; out->planning_cap_bytes = p.planning_cap;
     out->arena_bytes_needed = p.arena_needed; out->host_bytes_needed = p.host_needed;
     out->bytes_per_direction = p.bytes_moved;
+    out->n_pairs = (int32_t)p.pair_tier.size(); out->reserved2 = 0;
+    out->pair_tier = p.pair_tier.data();
+    out->host_tier_bytes_needed = p.host_tier_needed; out->host_tier_peak_bytes = p.host_peak; out->host_tier_bw = p.host_bw;
     return TIO_OK;
 }
 

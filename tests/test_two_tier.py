@@ -83,3 +83,81 @@ def test_random_traces_respect_the_host_budget(duplex):
         sim = orp.simulate(tr, pl, bw, duplex=duplex, host_bw=4 * bw)
         assert sim["step_ns"] >= sim["compute_ns"]
     assert used > 10
+
+
+# ------------------------------------------------------------------ library against the oracle
+import paper_2506_06472_amd as tio  # noqa: E402
+from test_plan_parity import lib_trace_from_oracle  # noqa: E402
+
+
+def _same(tr, lt, ll, cap, bw, hbw, budget, duplex=True, arena=None):
+    pl = tio.tio_build_plan(lt, ll, cap, bw, duplex=duplex, host_bw=hbw, host_budget=budget, arena_bytes=arena or 0)
+    pe = pl.export()
+    life = op.analyze_lifetimes(tr)
+    ref = op.build_plan(tr, life, pe["planning_cap"], bw, duplex=duplex, host_bw=hbw, host_budget=budget)
+    assert pe["entries"] == ref["entries"] and pe["Mp"] == ref["Mp"] and pe["tier"] == ref["tier"]
+    assert (pe["n_greedy"], pe["n_forced"], pe["host_peak"]) == (ref["n_greedy"], ref["n_forced"], ref["host_peak"])
+    st = orp.check_plan(tr, life, ref, pe["planning_cap"], host_budget=budget if hbw and budget else None)
+    # the host pool the library asks for holds every host-tier pair without overlap in time
+    assert pe["host_tier_needed"] >= pe["host_peak"]
+    for it in (1, 3):
+        want = orp.simulate(tr, ref, bw, duplex=duplex, iterations=it, host_bw=hbw)
+        assert tio.tio_plan_simulate(lt, pl, bw, duplex=duplex, iterations=it) == (want["step_ns"], want["compute_ns"])
+    return pe, st
+
+
+def test_library_golden_two_tier():
+    g = load_golden_two_tier("plan_example_d.txt")
+    lt = lib_trace_from_oracle(g["trace"])
+    ll = tio.tio_analyze_lifetimes(lt)
+    pl = tio.tio_build_plan(lt, ll, g["cap"], g["bw"], host_bw=g["host_bw"], host_budget=g["host_budget"], arena_bytes=1 << 20)
+    pe = pl.export()
+    assert pe["planning_cap"] == g["cap"] and pe["entries"] == g["entries"] and pe["tier"] == g["tier"] and pe["Mp"] == g["Mp"]
+    assert pe["host_peak"] == 1000 and pe["host_tier_needed"] == 1000
+    assert tio.tio_plan_simulate(lt, pl, g["bw"]) == (1000, 800)
+
+
+@pytest.mark.parametrize("name", ["tiny_gpt_fp32", "tiny_llama_fp32"])
+def test_library_model_plans_bit_exact_with_a_host_tier(name):
+    cfg = CONFIGS[name]
+    tr = ot.build_trace(cfg)
+    lt = tio.tio_trace_build(cfg)
+    ll = tio.tio_analyze_lifetimes(lt)
+    peak = int(ll.export()["M"].max())
+    used = 0
+    for frac, bw, hbw, bfrac, duplex in ((0.5, 2 * 10**9, 2 * 10**10, 0.25, True), (0.4, 10**9, 4 * 10**9, 1.0, True),
+                                         (0.5, 5 * 10**9, 10**10, 0.1, False), (0.6, 25 * 10**9, 50 * 10**9, 0.5, True)):
+        pe, st = _same(tr, lt, ll, int(peak * frac) // 256 * 256, bw, hbw, int(peak * bfrac), duplex)
+        used += st["host_pairs"] > 0
+    assert used >= 2
+
+
+def test_library_random_traces_bit_exact_with_a_host_tier():
+    rng = np.random.default_rng(23)
+    n = 0
+    for _ in range(120):
+        tr = random_trace(rng, int(rng.integers(6, 20)), int(rng.integers(1, 4)), int(rng.integers(3, 12)))
+        life = op.analyze_lifetimes(tr)
+        peak = max(life["M"])
+        cap = int(peak * rng.uniform(0.5, 0.95))
+        bw = int(rng.integers(1, 20)) * 10**8
+        budget = int(peak * rng.uniform(0.05, 0.6))
+        lt = lib_trace_from_oracle(tr)
+        ll = tio.tio_analyze_lifetimes(lt)
+        try:
+            op.build_plan(tr, life, cap, bw, host_bw=4 * bw, host_budget=budget)
+        except ValueError:
+            continue
+        _same(tr, lt, ll, cap, bw, 4 * bw, budget, duplex=bool(rng.integers(0, 2)), arena=1 << 20)
+        n += 1
+    assert n > 60
+
+
+def test_library_gpt2_small_bit_exact_with_a_host_tier():
+    cfg = dict(CONFIGS["gpt2_small_bf16"], L=4)
+    tr = ot.build_trace(cfg)
+    lt = tio.tio_trace_build(cfg)
+    ll = tio.tio_analyze_lifetimes(lt)
+    peak = int(ll.export()["M"].max())
+    pe, st = _same(tr, lt, ll, int(peak * 0.5) // 256 * 256, 16 * 10**9, 48 * 10**9, peak // 4)
+    assert st["host_pairs"] > 0
