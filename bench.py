@@ -44,6 +44,10 @@ def main():
                          "(auto: host unless the pool exceeds what this kind of box can pin, about 28 GB)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--modelled-tau", action="store_true", help="plan from modelled instead of measured kernel times")
+    ap.add_argument("--host-tier-bw", type=float, default=0,
+                    help="bytes/s per direction of a second, host-memory destination beside the slow tier (the paper's "
+                         "mixed mode); 0 = none; not the headline configuration")
+    ap.add_argument("--host-budget", type=float, default=0, help="bytes of host memory the second destination may hold")
     ap.add_argument("--micro-batches", type=int, default=1,
                     help="n > 1: a step is n micro-batches of the workload's batch with gradient accumulation and one "
                          "AdamW update (n times the tokens per step, same memory cap); not the headline configuration")
@@ -131,7 +135,8 @@ def main():
     if not args.modelled_tau:
         lt.set_tau(tau)
     tp0 = time.perf_counter()
-    plan = tio.tio_build_plan(lt, ll, cap, bw, min_bytes=args.min_bytes)
+    plan = tio.tio_build_plan(lt, ll, cap, bw, min_bytes=args.min_bytes, host_bw=int(args.host_tier_bw),
+                              host_budget=int(args.host_budget))
     plan_s = time.perf_counter() - tp0
     pe = plan.export()
     log('ideal ms', ideal_s * 1e3, 'plan: entries', len(pe['entries']), 'moved GB', pe['bytes_per_direction'] / 1e9, 'planner s', plan_s)
@@ -142,7 +147,9 @@ def main():
             torch.empty(host_bytes, dtype=torch.uint8, device="cuda:0")
 
     # ---- capped run: the context sees only `cap` bytes of the arena
-    ctx = tio.tio_ctx_create(cfg, cap, host_bytes, bw, arena=arena, host=host)
+    ctx = tio.tio_ctx_create(cfg, cap, host_bytes, bw, arena=arena, host=host,
+                             host_tier_bytes=pe["host_tier_needed"] + 4096 if pe["host_tier_needed"] else 0,
+                             host_tier_bw=int(args.host_tier_bw))
     load_params(ctx)
     first = ctx.tio_train_step(tok, lab, plan)
     # at initialisation the normalised hidden state has unit entries and the head weights are N(0, 0.02^2):
@@ -196,6 +203,8 @@ def main():
         "frac_of_ideal": ideal_s / step_s,
         "migration_bound_ms": mig_bound_s * 1e3, "frac_of_min_ideal_migration_bound": bound_s / step_s,
         "plan": {"entries": len(pe["entries"]), "greedy_pairs": pe["n_greedy"], "urgent_pairs": pe["n_forced"],
+                 "host_tier_pairs": sum(pe["tier"]), "host_tier_peak_bytes": pe["host_peak"],
+                 "host_tier_bw_bytes_per_s": int(args.host_tier_bw), "host_tier_budget_bytes": int(args.host_budget),
                  "bytes_per_direction": pe["bytes_per_direction"], "planning_cap_bytes": pe["planning_cap"],
                  "arena_bytes_needed": pe["arena_needed"], "planner_seconds": plan_s},
         "copy": {"d2h_GBps": d2h / args.steps / step_s / 1e9, "h2d_GBps": h2d / args.steps / step_s / 1e9,

@@ -65,6 +65,12 @@ typedef struct tio_runtime_cfg {
     uint64_t slow_tier_bw;           /* bytes/s per direction enforced on the copy streams; 0 = unthrottled */
     int32_t poison_freed;            /* debug: fill released arena ranges with NaN patterns */
     int32_t pool_on_device;          /* 1: host_pool is device memory (hosts that cannot pin enough memory) */
+    /* Optional second destination (plans built with a host-memory tier, tio_plan_opts.host_bw / host_budget):
+     * pinned host memory with its own two copy streams.  All NULL / 0 when no such plan will be run. */
+    void *host_tier_pool;            /* pinned host memory, 256-byte aligned */
+    uint64_t host_tier_bytes;
+    void *host_tier_d2h_stream, *host_tier_h2d_stream;   /* hipStream_t, default priority */
+    uint64_t host_tier_bw;           /* bytes/s per direction enforced on those streams; 0 = unthrottled */
 } tio_runtime_cfg;
 
 typedef struct tio_ctx tio_ctx;

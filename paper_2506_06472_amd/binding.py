@@ -36,7 +36,8 @@ class RuntimeCfg(C.Structure):
     _fields_ = [("arena", C.c_void_p), ("arena_bytes", C.c_uint64), ("host_pool", C.c_void_p),
                 ("host_bytes", C.c_uint64), ("compute_stream", C.c_void_p), ("d2h_stream", C.c_void_p),
                 ("h2d_stream", C.c_void_p), ("slow_tier_bw", C.c_uint64), ("poison_freed", C.c_int32),
-                ("pool_on_device", C.c_int32)]
+                ("pool_on_device", C.c_int32), ("host_tier_pool", C.c_void_p), ("host_tier_bytes", C.c_uint64),
+                ("host_tier_d2h_stream", C.c_void_p), ("host_tier_h2d_stream", C.c_void_p), ("host_tier_bw", C.c_uint64)]
 
 
 class TraceView(C.Structure):
@@ -267,7 +268,10 @@ class Context:
     and a tio_ctx handle created on them."""
 
     def __init__(self, cfg: dict, arena_bytes: int, host_bytes: int, slow_tier_bw: int = 0, single_copy_stream=False,
-                 arena=None, host=None, pool_on_device=False):
+                 arena=None, host=None, pool_on_device=False, host_tier_bytes: int = 0, host_tier_bw: int = 0,
+                 host_tier=None):
+        """host_tier_bytes > 0 (or a pinned uint8 tensor host_tier): a second, host-memory destination with its own
+        two copy streams, for plans built with host_bw / host_budget."""
         import torch
         if not torch.cuda.is_available():
             raise RuntimeError("a GPU is required for the runtime part of the library")
@@ -292,9 +296,20 @@ class Context:
         self.s_compute = torch.cuda.Stream(device="cuda:0")
         self.s_d2h = torch.cuda.Stream(device="cuda:0")
         self.s_h2d = self.s_d2h if single_copy_stream else torch.cuda.Stream(device="cuda:0")
+        self.host_tier = host_tier
+        if host_tier is None and host_tier_bytes > 0:
+            self.host_tier = torch.empty((int(host_tier_bytes) + 255) // 256 * 256, dtype=torch.uint8, pin_memory=True)
+        self.s_d2h1 = self.s_h2d1 = None
+        if self.host_tier is not None:
+            self.s_d2h1 = torch.cuda.Stream(device="cuda:0")
+            self.s_h2d1 = torch.cuda.Stream(device="cuda:0")
         rt = RuntimeCfg(self.arena.data_ptr(), arena_bytes, self.host.data_ptr(), int(host_bytes),
                         self.s_compute.cuda_stream, self.s_d2h.cuda_stream, self.s_h2d.cuda_stream,
-                        int(slow_tier_bw), 0, 1 if pool_on_device else 0)
+                        int(slow_tier_bw), 0, 1 if pool_on_device else 0,
+                        self.host_tier.data_ptr() if self.host_tier is not None else None,
+                        self.host_tier.numel() if self.host_tier is not None else 0,
+                        self.s_d2h1.cuda_stream if self.s_d2h1 else None, self.s_h2d1.cuda_stream if self.s_h2d1 else None,
+                        int(host_tier_bw))
         mc = model_cfg(cfg)
         self.h = C.c_void_p()
         torch.cuda.synchronize()
@@ -304,7 +319,7 @@ class Context:
         if getattr(self, "h", None):
             lib().tio_ctx_destroy(self.h)
             self.h = None
-            self.arena = self.host = None
+            self.arena = self.host = self.host_tier = None
 
     def __del__(self):
         self.close()
@@ -369,8 +384,9 @@ class Context:
 
 
 def tio_ctx_create(cfg, arena_bytes, host_bytes, slow_tier_bw=0, single_copy_stream=False, arena=None, host=None,
-                   pool_on_device=False) -> Context:
-    return Context(cfg, arena_bytes, host_bytes, slow_tier_bw, single_copy_stream, arena, host, pool_on_device)
+                   pool_on_device=False, host_tier_bytes=0, host_tier_bw=0, host_tier=None) -> Context:
+    return Context(cfg, arena_bytes, host_bytes, slow_tier_bw, single_copy_stream, arena, host, pool_on_device,
+                   host_tier_bytes, host_tier_bw, host_tier)
 
 
 def tio_op_gemm(stream_handle, dtype, a_kmajor, b_kmajor, M, N, K, A_ptr, lda, B_ptr, ldb, bias_ptr, resid_ptr, ldr,

@@ -61,7 +61,9 @@ struct tio_ctx {
     Trace trace;
     Lifetimes life;
     hipStream_t sc = nullptr, sd = nullptr, sh = nullptr;
-    uint8_t *arena = nullptr, *host = nullptr;
+    hipStream_t sd1 = nullptr, sh1 = nullptr;            // copy streams of the host-memory tier
+    uint8_t *arena = nullptr, *host = nullptr, *host1 = nullptr;
+    uint64_t bw1 = 0;                                    // bandwidth enforced on the host-memory tier
     uint64_t arena_usable = 0;
     unsigned long long *pace_slots = nullptr;            // device: [0] d2h stamp, [1] h2d stamp
     std::vector<uint64_t> home;                          // host offset of every persistent tensor
@@ -75,6 +77,8 @@ struct tio_ctx {
     std::vector<uint8_t> loaded;                         // per parameter: tio_params_load has been called
     std::vector<uint8_t> on_dev;                         // per persistent tensor: latest version is in the arena
     std::vector<uint64_t> dev_addr;
+    std::vector<uint8_t> in_host1;                       // per persistent tensor: latest version is in a host-tier slot
+    std::vector<uint64_t> host1_off;
     std::vector<std::vector<uint64_t>> ptrs;             // per kernel, per role: arena offset (UINT64_MAX = absent)
     std::vector<hipEvent_t> ev_kernel, ev_off, ev_pre, ev_t0, ev_t1;
     std::vector<uint8_t> rec_kernel, rec_off, rec_pre;
@@ -112,15 +116,21 @@ void sync_all(tio_ctx *c) {
     HIPCHK(hipStreamSynchronize(c->sc));
     HIPCHK(hipStreamSynchronize(c->sd));
     HIPCHK(hipStreamSynchronize(c->sh));
+    if (c->sd1) HIPCHK(hipStreamSynchronize(c->sd1));
+    if (c->sh1) HIPCHK(hipStreamSynchronize(c->sh1));
 }
 
 // brings the latest version of every persistent tensor into its home slot on the slow tier
 void gather_to_home(tio_ctx *c) {
     sync_all(c);
     if (!c->installed) return;
-    for (int t = 0; t < c->prog.n_persistent; ++t)
+    for (int t = 0; t < c->prog.n_persistent; ++t) {
         if (c->on_dev[t])
             HIPCHK(hipMemcpy(c->host + c->home[t], c->arena + c->dev_addr[t], c->prog.tensors[t].bytes, hipMemcpyDefault));
+        else if (c->in_host1[t])      // offloaded to the host-memory tier: that slot holds the latest version
+            HIPCHK(hipMemcpy(c->host + c->home[t], c->host1 + c->host1_off[t], c->prog.tensors[t].bytes, hipMemcpyDefault));
+        c->in_host1[t] = 0;
+    }
     // a device-to-device hipMemcpy may return before the copy has run, and the context's streams do not
     // wait for the null stream
     if (c->pool_dev) HIPCHK(hipDeviceSynchronize());
@@ -136,12 +146,18 @@ void install_plan(tio_ctx *c, const Plan &p) {
     if (p.host_needed > c->rt.host_bytes)
         throw PlanError{TIO_ERR_OOM_HOST, "plan needs " + std::to_string(p.host_needed) + " slow-tier bytes, pool has " +
                                               std::to_string(c->rt.host_bytes)};
+    if (p.host_tier_needed > 0 && (!c->host1 || !c->sd1 || !c->sh1 || p.host_tier_needed > c->rt.host_tier_bytes))
+        throw PlanError{TIO_ERR_OOM_HOST, "plan needs " + std::to_string(p.host_tier_needed) +
+                                              " bytes of a host-memory tier with its two streams, context has " +
+                                              std::to_string(c->host1 ? c->rt.host_tier_bytes : 0)};
     gather_to_home(c);
     c->plan = p;
     c->installed = true;
     const int np = c->prog.n_persistent;
     c->on_dev.assign(np, 0);
     c->dev_addr.assign(np, 0);
+    c->in_host1.assign(np, 0);
+    c->host1_off.assign(np, 0);
     for (int t = 0; t < np; ++t) {
         if (p.persistent_home[t] != c->home[t]) throw PlanError{TIO_ERR_PLAN_INVALID, "home slot mismatch"};
         const uint64_t a = address_at(p, t, 0);
@@ -229,8 +245,9 @@ void launch(tio_ctx *c, int k) {
     HIPCHK(hipGetLastError());
 }
 
-void paced_copy(tio_ctx *c, hipStream_t s, int slot, void *dst, const void *src, uint64_t bytes, hipMemcpyKind kind) {
-    if (c->bw && c->dma_pacing) {
+void paced_copy(tio_ctx *c, hipStream_t s, int slot, void *dst, const void *src, uint64_t bytes, hipMemcpyKind kind,
+                uint64_t rate) {
+    if (rate && (c->dma_pacing || slot >= 2)) {          // slots 2, 3: host-memory tier, always pinned host memory
         // the DMA engine moves the bytes in chunks; after each chunk the stream is held until the emulated
         // channel would have delivered it
         const unsigned long long limit = (unsigned long long)(30.0 * c->clock_hz);
@@ -239,14 +256,14 @@ void paced_copy(tio_ctx *c, hipStream_t s, int slot, void *dst, const void *src,
         for (uint64_t off = 0; off < bytes; off += CHUNK) {
             const uint64_t n = std::min(CHUNK, bytes - off);
             HIPCHK(hipMemcpyAsync((uint8_t *)dst + off, (const uint8_t *)src + off, n, kind, s));
-            k::channel_wait(s, c->chan_clock + slot, (unsigned long long)((double)n / (double)c->bw * c->clock_hz), limit);
+            k::channel_wait(s, c->chan_clock + slot, (unsigned long long)((double)n / (double)rate * c->clock_hz), limit);
         }
-    } else if (c->bw) {
-        double ticks = (double)bytes / (double)c->bw * c->clock_hz;
+    } else if (rate) {
+        double ticks = (double)bytes / (double)rate * c->clock_hz;
         ticks = std::min(ticks, 30.0 * c->clock_hz);         // bounded wait
         k::paced_copy(s, dst, src, (int64_t)bytes, (unsigned long long)ticks);
     } else {
-        HIPCHK(hipMemcpyAsync(dst, src, bytes, c->pool_dev ? hipMemcpyDefault : kind, s));
+        HIPCHK(hipMemcpyAsync(dst, src, bytes, (c->pool_dev && slot < 2) ? hipMemcpyDefault : kind, s));
     }
 }
 
@@ -304,31 +321,44 @@ void run_step(tio_ctx *c, const int32_t *tokens, const int32_t *labels, bool cap
             const tio_plan_entry &e = p.entries[ei];
             const Pair &pr = p.pairs[e.pair];
             const bool persistent = e.tensor < c->prog.n_persistent;
+            // destination of this pair: the slow tier's pool and streams, or the host-memory tier's
+            const bool t1 = pr.tier == 1;
+            hipStream_t so = t1 ? c->sd1 : c->sd, sp = t1 ? c->sh1 : c->sh;
+            uint8_t *pool = t1 ? c->host1 : c->host;
+            const uint64_t rate = t1 ? c->bw1 : c->bw;
             if (e.kind == TIO_OFFLOAD) {
                 // first iteration after a plan is installed: an offload that belongs to the end of the
                 // previous iteration (trigger wraps to the start of this one) has nothing to copy, the
                 // slow-tier home slot already holds the latest version
                 if (persistent && !c->on_dev[e.tensor]) continue;
                 const Alloc &al = p.allocs[pr.alloc_before];
-                if (c->rec_kernel[prev]) HIPCHK(hipStreamWaitEvent(c->sd, c->ev_kernel[prev], 0));
-                if (tl) { HIPCHK(hipEventRecord(c->ev_c0[ei], c->sd)); issued[ei] = 1; }
-                paced_copy(c, c->sd, 0, c->host + pr.host_offset, c->arena + al.address, pr.bytes, hipMemcpyDeviceToHost);
-                if (tl) HIPCHK(hipEventRecord(c->ev_c1[ei], c->sd));
-                HIPCHK(hipEventRecord(c->ev_off[e.pair], c->sd));
+                if (c->rec_kernel[prev]) HIPCHK(hipStreamWaitEvent(so, c->ev_kernel[prev], 0));
+                if (tl) { HIPCHK(hipEventRecord(c->ev_c0[ei], so)); issued[ei] = 1; }
+                paced_copy(c, so, t1 ? 2 : 0, pool + pr.host_offset, c->arena + al.address, pr.bytes, hipMemcpyDeviceToHost, rate);
+                if (tl) HIPCHK(hipEventRecord(c->ev_c1[ei], so));
+                HIPCHK(hipEventRecord(c->ev_off[e.pair], so));
                 c->rec_off[e.pair] = 1;
-                if (persistent) c->on_dev[e.tensor] = 0;
+                if (persistent) {
+                    c->on_dev[e.tensor] = 0;
+                    c->in_host1[e.tensor] = t1 ? 1 : 0;
+                    c->host1_off[e.tensor] = pr.host_offset;
+                }
                 d2h += pr.bytes;
             } else {
                 const Alloc &al = p.allocs[pr.alloc_after];
-                if (c->rec_kernel[prev]) HIPCHK(hipStreamWaitEvent(c->sh, c->ev_kernel[prev], 0));
-                if (c->rec_off[e.pair]) HIPCHK(hipStreamWaitEvent(c->sh, c->ev_off[e.pair], 0));
-                for (int q : al.wait_pairs) if (c->rec_off[q]) HIPCHK(hipStreamWaitEvent(c->sh, c->ev_off[q], 0));
-                if (tl) { HIPCHK(hipEventRecord(c->ev_c0[ei], c->sh)); issued[ei] = 1; }
-                paced_copy(c, c->sh, 1, c->arena + al.address, c->host + pr.host_offset, pr.bytes, hipMemcpyHostToDevice);
-                if (tl) HIPCHK(hipEventRecord(c->ev_c1[ei], c->sh));
-                HIPCHK(hipEventRecord(c->ev_pre[e.pair], c->sh));
+                // a persistent tensor whose offload to the host-memory tier belongs to an iteration that never
+                // ran (first iteration after the plan was installed) is still in its slow-tier home slot
+                const uint8_t *src = (t1 && persistent && !c->in_host1[e.tensor]) ? c->host + c->home[e.tensor] : pool + pr.host_offset;
+                if (c->rec_kernel[prev]) HIPCHK(hipStreamWaitEvent(sp, c->ev_kernel[prev], 0));
+                if (c->rec_off[e.pair]) HIPCHK(hipStreamWaitEvent(sp, c->ev_off[e.pair], 0));
+                for (int q : al.wait_pairs) if (c->rec_off[q]) HIPCHK(hipStreamWaitEvent(sp, c->ev_off[q], 0));
+                if (tl) { HIPCHK(hipEventRecord(c->ev_c0[ei], sp)); issued[ei] = 1; }
+                paced_copy(c, sp, t1 ? 3 : 1, c->arena + al.address, src, pr.bytes,
+                           (c->pool_dev && src != pool + pr.host_offset) ? hipMemcpyDefault : hipMemcpyHostToDevice, rate);
+                if (tl) HIPCHK(hipEventRecord(c->ev_c1[ei], sp));
+                HIPCHK(hipEventRecord(c->ev_pre[e.pair], sp));
                 c->rec_pre[e.pair] = 1;
-                if (persistent) { c->on_dev[e.tensor] = 1; c->dev_addr[e.tensor] = al.address; }
+                if (persistent) { c->on_dev[e.tensor] = 1; c->dev_addr[e.tensor] = al.address; c->in_host1[e.tensor] = 0; }
                 h2d += pr.bytes;
             }
             ++nmig;
@@ -421,6 +451,10 @@ int tio_ctx_create(const tio_model_cfg *cfg, const tio_runtime_cfg *rt, tio_ctx 
     c->pace_slots = (unsigned long long *)(c->arena + c->arena_usable);
     c->bw = rt->slow_tier_bw;
     c->pool_dev = rt->pool_on_device != 0;
+    c->host1 = (uint8_t *)rt->host_tier_pool;
+    c->sd1 = (hipStream_t)rt->host_tier_d2h_stream; c->sh1 = (hipStream_t)rt->host_tier_h2d_stream;
+    c->bw1 = rt->host_tier_bw;
+    if (c->host1 && ((uintptr_t)c->host1 & 255)) { delete c; return fail(TIO_ERR_INVALID_ARG, "host-memory tier pool must be 256-byte aligned"); }
     int khz = 0;
     if (hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, 0) == hipSuccess && khz > 0) c->clock_hz = khz * 1000.0;
     uint64_t h = 0;
@@ -526,6 +560,7 @@ int tio_params_read(tio_ctx *c, int32_t index, int32_t which, float *dst, int64_
     const uint64_t nbytes = (uint64_t)numel * (half ? 2 : 4);
     std::vector<uint8_t> tmp(nbytes);
     if (c->installed && !c->params_dirty && c->on_dev[t]) HIPCHK(hipMemcpy(tmp.data(), c->arena + c->dev_addr[t], nbytes, hipMemcpyDeviceToHost));
+    else if (c->installed && !c->params_dirty && c->in_host1[t]) std::memcpy(tmp.data(), c->host1 + c->host1_off[t], nbytes);
     else if (c->pool_dev) HIPCHK(hipMemcpy(tmp.data(), c->host + c->home[t], nbytes, hipMemcpyDeviceToHost));
     else std::memcpy(tmp.data(), c->host + c->home[t], nbytes);
     if (half) for (int64_t i = 0; i < numel; ++i) dst[i] = host_bf16_to_f32(((uint16_t *)tmp.data())[i]);
