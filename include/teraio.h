@@ -41,7 +41,7 @@ typedef enum tio_status {
 
 enum { TIO_ARCH_GPT = 0, TIO_ARCH_LLAMA = 1 };
 enum { TIO_PREC_FP32 = 0, TIO_PREC_BF16 = 1 };
-enum { TIO_PROFILE_MEASURED = 0, TIO_PROFILE_MODELLED = 1 };
+enum { TIO_PROFILE_MEASURED = 0, TIO_PROFILE_MODELLED = 1, TIO_PROFILE_OFFLOADED = 2 };
 enum { TIO_OFFLOAD = 0, TIO_PREFETCH = 1 };
 
 /* Model and optimizer shape.  GPT: LayerNorm, GELU (tanh form), biases, learned positions.
@@ -176,7 +176,11 @@ void tio_trace_free(tio_trace *trace);
 /* Runs iterations of the real kernels (uncapped layout: the arena must hold the whole
  * iteration), marks every operand of every launch active and times each launch with HIP events;
  * tau = median of three iterations.  tokens/labels: host int32 [batch, seq_len].
- * mode TIO_PROFILE_MODELLED skips the GPU and equals tio_trace_build. */
+ * mode TIO_PROFILE_MODELLED skips the GPU and equals tio_trace_build.
+ * mode TIO_PROFILE_OFFLOADED is for iterations that need more memory than the arena has (Section 2 of the
+ * paper profiles such models by offloading tensors the current kernel does not need): the library plans
+ * from the modelled times with the arena as the capacity and the context's slow-tier bandwidth, runs the
+ * same measurement under that plan, and returns the measured times; plan again with them. */
 int tio_profile_iteration(tio_ctx *ctx, const int32_t *tokens, const int32_t *labels, int mode,
                           tio_trace **out);
 

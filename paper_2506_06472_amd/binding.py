@@ -15,7 +15,7 @@ LIB_PATH = os.path.join(_HERE, "libteraio.so")
 
 ARCH = {"gpt": 0, "llama": 1}
 PREC = {"fp32": 0, "bf16": 1}
-PROFILE_MEASURED, PROFILE_MODELLED = 0, 1
+PROFILE_MEASURED, PROFILE_MODELLED, PROFILE_OFFLOADED = 0, 1, 2
 OFFLOAD, PREFETCH = 0, 1
 
 

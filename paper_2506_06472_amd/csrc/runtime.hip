@@ -609,11 +609,20 @@ int tio_profile_iteration(tio_ctx *c, const int32_t *tokens, const int32_t *labe
     if (!c || !out) return fail(TIO_ERR_INVALID_ARG, "null argument");
     TIO_RT_BEGIN
     tio_trace *h = new tio_trace{c->trace};
-    if (mode == TIO_PROFILE_MEASURED) {
+    if (mode == TIO_PROFILE_MEASURED || mode == TIO_PROFILE_OFFLOADED) {
         if (!tokens || !labels) { delete h; return fail(TIO_ERR_INVALID_ARG, "null argument"); }
         for (size_t i = 0; i < c->loaded.size(); ++i)
             if (!c->loaded[i]) { delete h; return fail(TIO_ERR_INVALID_ARG, "parameter " + c->prog.params[i].name + " was never loaded"); }
         try {
+            tio_plan under_cap;
+            if (mode == TIO_PROFILE_OFFLOADED) {
+                // the iteration does not fit the arena: run it under a plan made from the modelled times
+                const tio_plan_opts o{1, 24, 0, 0, 0, 0};
+                under_cap.p = build_plan(c->trace, c->life, c->arena_usable, c->bw, o);
+                static uint64_t serial = (uint64_t)1 << 62;      // apart from the serials of plans built by callers
+                under_cap.p.serial = serial++;
+                ensure_plan(c, &under_cap);
+            } else
             ensure_plan(c, nullptr);
             const int N = c->trace.n_kernels;
             std::vector<std::vector<int64_t>> runs(3);

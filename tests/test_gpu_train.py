@@ -152,6 +152,39 @@ def test_measured_profile_gives_the_same_structure_and_positive_times():
     ctx.close(); ctx2.close()
 
 
+def test_profile_of_an_iteration_that_does_not_fit_the_arena():
+    """A context whose arena holds 55 % of the iteration's peak: the plain measured profile is refused, the
+    offloaded profile runs the iteration under a plan of its own and returns positive times for every launch;
+    the state it leaves is the state four plain steps leave (warm-up and three measured iterations)."""
+    import paper_2506_06472_amd as tio
+    cfg = CONFIGS["tiny_llama_fp32"]
+    params, tok, lab = make_inputs(cfg, seed=0)
+    lt, ll, up, cp, peak = plans_for(cfg, 0.55, 25 * 10**9, 0)
+    ce, ue = cp.export(), up.export()
+    hb = 2 * max(ue["host_needed"], ce["host_needed"]) + (1 << 20)
+    ctx = tio.tio_ctx_create(cfg, ce["cap"], hb, 25 * 10**9)
+    ctx.tio_params_load(params)
+    with pytest.raises(tio.TioError) as ei:
+        ctx.tio_profile_iteration(tok, lab, tio.PROFILE_MEASURED)
+    assert ei.value.code == -7
+    tr = ctx.tio_profile_iteration(tok, lab, tio.PROFILE_OFFLOADED).export()
+    ref = lt.export()
+    for key in ("op", "operand_off", "operand_tensor", "operand_flags", "tensor_bytes", "tensor_kind"):
+        assert np.array_equal(tr[key], ref[key]), key
+    assert tr["tau"].min() > 0 and tr["tau"].sum() < 10**9
+    names = [n for n, _, _ in tio.tio_param_list(cfg)]
+    s1 = read_state(ctx, names, False)
+    ctx.close()
+    ctx = _ctx(cfg, ue)
+    ctx.tio_params_load(params)
+    for _ in range(4):
+        ctx.tio_train_step(tok, lab, None)
+    s0 = read_state(ctx, names, False)
+    ctx.close()
+    for key in s0:
+        assert s0[key].tobytes() == s1[key].tobytes(), key
+
+
 def test_errors_are_reported_not_faulted():
     import paper_2506_06472_amd as tio
     cfg = CONFIGS["tiny_gpt_fp32"]
