@@ -43,7 +43,6 @@ void ce_fwd_bwd(hipStream_t s, int dtype, void *logits, const int32_t *labels, f
                 int64_t V, int64_t ld, int64_t S_total);
 // loss[0] (+)= sum(losses[0..S)) / S_total
 void loss_reduce(hipStream_t s, const float *losses, float *loss, int64_t S, int64_t S_total, bool accumulate);
-void bias_grad(hipStream_t s, int dtype, const void *dy, void *db, int64_t S, int64_t n, int64_t ld);
 void gelu_bwd(hipStream_t s, int dtype, void *dact, const void *u, int64_t n);
 void swiglu_bwd(hipStream_t s, int dtype, const void *dact, const void *gu, void *dgu, int64_t S, int64_t f);
 void norm_bwd(hipStream_t s, int dtype, bool rms, const void *dy, const void *x, const float *stats,

@@ -544,27 +544,6 @@ __global__ void __launch_bounds__(TPB) loss_reduce_k(const float *__restrict__ l
     if (threadIdx.x == 0) loss[0] = (accumulate ? loss[0] : 0.f) + t / (float)S_total;
 }
 
-// ---------------------------------------------------------------- bias gradient: column sums
-// workgroup = 32 columns x 8 row groups; each thread adds its rows in order, groups are combined in order
-template <typename T>
-__global__ void __launch_bounds__(TPB) bias_grad_k(const T *__restrict__ dy, T *__restrict__ db, int64_t S,
-                                                   int64_t n, int64_t ld) {
-    __shared__ float red[8][33];
-    const int c = threadIdx.x & 31, rg = threadIdx.x >> 5;
-    const int64_t col = (int64_t)blockIdx.x * 32 + c;
-    float s = 0.f;
-    if (col < n)
-        for (int64_t r = rg; r < S; r += 8) s += to_f32(dy[r * ld + col]);
-    red[rg][c] = s;
-    __syncthreads();
-    if (rg == 0 && col < n) {
-        float t = 0.f;
-#pragma unroll
-        for (int i = 0; i < 8; ++i) t += red[i][c];
-        db[col] = from_f32<T>(t);
-    }
-}
-
 // ---------------------------------------------------------------- AdamW
 // reads g, theta (fp32 master), m, v; writes theta, m, v and, in bf16 mode, the bf16 compute weight
 template <typename T>
@@ -809,10 +788,6 @@ void loss_reduce(hipStream_t s, const float *losses, float *loss, int64_t S, int
     loss_reduce_k<<<1, TPB, 0, s>>>(losses, loss, S, S_total, accumulate);
 }
 
-void bias_grad(hipStream_t s, int dtype, const void *dy, void *db, int64_t S, int64_t n, int64_t ld) {
-    TIO_DISPATCH(dtype, { bias_grad_k<T><<<blocks_for(n, 32), TPB, 0, s>>>((const T *)dy, (T *)db, S, n, ld); });
-}
-
 void adamw(hipStream_t s, int dtype, const void *g, void *w, float *master, float *m, float *v, int64_t n, float lr,
            float beta1, float beta2, float eps, float wd, float bc1, float bc2) {
     TIO_DISPATCH(dtype, {
@@ -839,9 +814,7 @@ void convert_from_f32(hipStream_t s, int dtype, const float *src, void *dst, int
 void paced_copy(hipStream_t s, void *dst, const void *src, int64_t bytes, unsigned long long ticks) {
     const int64_t n16 = bytes / 16;
     int wg = (int)((n16 + TPB * 16 - 1) / (TPB * 16));
-    static int max_wg = 0;
-    if (!max_wg) { const char *e = getenv("TIO_PACED_WG"); max_wg = e ? atoi(e) : PACED_WG; if (max_wg < 1) max_wg = 1; }
-    if (wg > max_wg) wg = max_wg;
+    if (wg > PACED_WG) wg = PACED_WG;
     if (wg < 1) wg = 1;
     paced_copy_k<<<wg, TPB, 0, s>>>((uint4 *)dst, (const uint4 *)src, n16, ticks);
 }

@@ -16,7 +16,7 @@ enum Op : int32_t {
     OP_CE_FWD_BWD, OP_LOSS_REDUCE, OP_GEMM_DX, OP_GEMM_DW, OP_BIAS_GRAD, OP_GELU_BWD, OP_SWIGLU_BWD,
     OP_NORM_BWD, OP_NORM_BWD_PARAMS, OP_ATTN_BWD_PRE, OP_ATTN_BWD, OP_ROPE_BWD, OP_EMBED_BWD,
     OP_POSEMB_BWD, OP_ADAMW, OP_COUNT
-};
+};   // OP_BIAS_GRAD is a reserved code: the bias gradient comes out of the weight-gradient GEMM
 
 enum Kind : int32_t { KIND_WEIGHT = 0, KIND_MASTER, KIND_M, KIND_V, KIND_INPUT, KIND_ACT, KIND_GRAD, KIND_PGRAD };
 

@@ -222,7 +222,6 @@ void launch(tio_ctx *c, int k) {
                        // the row sums of dY^T are the bias gradient
         k::gemm(s, dt, true, true, r.p[0], r.p[1], r.p[2], P(0), r.p[3], P(1), r.p[1], nullptr, nullptr, 0, P(2), r.p[1], P(3), P(4), (int)r.p[4], r.p[5] != 0);
         break;
-    case OP_BIAS_GRAD: k::bias_grad(s, dt, P(0), P(1), r.p[0], r.p[1], r.p[1]); break;
     case OP_GELU_BWD: k::gelu_bwd(s, dt, P(0), P(1), r.p[0]); break;
     case OP_SWIGLU_BWD: k::swiglu_bwd(s, dt, P(0), P(1), P(2), r.p[0], r.p[1]); break;
     case OP_NORM_BWD:
