@@ -36,7 +36,8 @@ typedef enum tio_status {
     TIO_ERR_PLAN_STALE = -5,          /* plan was built from a different trace */
     TIO_ERR_HIP = -6,
     TIO_ERR_ARENA_TOO_SMALL = -7,     /* address assignment does not fit the arena */
-    TIO_ERR_NO_GPU_CODE = -8
+    TIO_ERR_NO_GPU_CODE = -8,
+    TIO_ERR_IO = -9                   /* the slow-tier file could not be opened, grown, read or written */
 } tio_status;
 
 enum { TIO_ARCH_GPT = 0, TIO_ARCH_LLAMA = 1 };
@@ -71,6 +72,15 @@ typedef struct tio_runtime_cfg {
     uint64_t host_tier_bytes;
     void *host_tier_d2h_stream, *host_tier_h2d_stream;   /* hipStream_t, default priority */
     uint64_t host_tier_bw;           /* bytes/s per direction enforced on those streams; 0 = unthrottled */
+    /* Optional: the slow tier is a file (the paper's storage tier, Section 3.3) instead of a memory pool.  Then
+     * host_pool is NULL, pool_on_device 0, and host_bytes is the largest size the file may grow to.  The file is
+     * created if missing, opened for direct I/O where the file system supports it, grown as plans need and never
+     * deleted by the library.  Transfers go through `staging` in chunks (there is no direct storage-to-GPU path on
+     * this platform); slow_tier_bw is ignored for this tier: the file system sets the pace. */
+    const char *slow_tier_file;      /* host, NUL-terminated path, read only during tio_ctx_create; NULL = no file tier */
+    void *staging;                   /* pinned host memory, 4096-byte aligned, owned by the caller for the context's lifetime */
+    uint64_t staging_bytes;          /* at least 4 chunks (two per direction) */
+    uint64_t file_chunk_bytes;       /* multiple of 4096; 0 = 8 MiB */
 } tio_runtime_cfg;
 
 typedef struct tio_ctx tio_ctx;
@@ -224,6 +234,14 @@ int tio_params_load(tio_ctx *ctx, int32_t index, const float *host_values, int64
 int tio_params_read(tio_ctx *ctx, int32_t index, int32_t which, float *host_dst, int64_t numel);
 /* Gradient of parameter `index` as captured during the last step run with TIO_STEP_CAPTURE_GRADS. */
 int tio_grads_read(tio_ctx *ctx, int32_t index, float *host_dst, int64_t numel);
+/* State of the file-backed slow tier (Section 3.3): whether direct I/O is in use, the current file size, and the
+ * payload bytes written to and read from the file by migrations since the context was created (it waits for
+ * the transfers in flight).  TIO_ERR_INVALID_ARG if the context has no file tier. */
+typedef struct tio_file_tier_stats {
+    int32_t direct_io;
+    uint64_t file_bytes, bytes_written, bytes_read;
+} tio_file_tier_stats;
+int tio_file_tier_info(tio_ctx *ctx, tio_file_tier_stats *out);
 /* Bandwidth enforced on the copy streams from the next step on (0 = unthrottled). */
 int tio_set_slow_tier_bw(tio_ctx *ctx, uint64_t bytes_per_s);
 

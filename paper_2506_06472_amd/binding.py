@@ -37,7 +37,14 @@ class RuntimeCfg(C.Structure):
                 ("host_bytes", C.c_uint64), ("compute_stream", C.c_void_p), ("d2h_stream", C.c_void_p),
                 ("h2d_stream", C.c_void_p), ("slow_tier_bw", C.c_uint64), ("poison_freed", C.c_int32),
                 ("pool_on_device", C.c_int32), ("host_tier_pool", C.c_void_p), ("host_tier_bytes", C.c_uint64),
-                ("host_tier_d2h_stream", C.c_void_p), ("host_tier_h2d_stream", C.c_void_p), ("host_tier_bw", C.c_uint64)]
+                ("host_tier_d2h_stream", C.c_void_p), ("host_tier_h2d_stream", C.c_void_p), ("host_tier_bw", C.c_uint64),
+                ("slow_tier_file", C.c_char_p), ("staging", C.c_void_p), ("staging_bytes", C.c_uint64),
+                ("file_chunk_bytes", C.c_uint64)]
+
+
+class FileTierStats(C.Structure):
+    _fields_ = [("direct_io", C.c_int32), ("file_bytes", C.c_uint64), ("bytes_written", C.c_uint64),
+                ("bytes_read", C.c_uint64)]
 
 
 class TraceView(C.Structure):
@@ -269,9 +276,11 @@ class Context:
 
     def __init__(self, cfg: dict, arena_bytes: int, host_bytes: int, slow_tier_bw: int = 0, single_copy_stream=False,
                  arena=None, host=None, pool_on_device=False, host_tier_bytes: int = 0, host_tier_bw: int = 0,
-                 host_tier=None):
+                 host_tier=None, slow_tier_file=None, staging_bytes: int = 256 << 20, file_chunk_bytes: int = 0):
         """host_tier_bytes > 0 (or a pinned uint8 tensor host_tier): a second, host-memory destination with its own
-        two copy streams, for plans built with host_bw / host_budget."""
+        two copy streams, for plans built with host_bw / host_budget.
+        slow_tier_file: path of a file that is the slow tier instead of a memory pool (host_bytes is then the
+        largest size it may grow to); transfers go through a pinned staging buffer of staging_bytes."""
         import torch
         if not torch.cuda.is_available():
             raise RuntimeError("a GPU is required for the runtime part of the library")
@@ -286,7 +295,15 @@ class Context:
         if host is not None and host.numel() < host_bytes:
             raise ValueError("host tensor too small")
         self.arena = arena if arena is not None else torch.empty(arena_bytes, dtype=torch.uint8, device="cuda:0")
-        if host is not None:
+        self.staging = None
+        if slow_tier_file is not None:
+            if host is not None or pool_on_device:
+                raise ValueError("the slow tier is either a pool or a file")
+            self.host = None
+            staging_bytes = (int(staging_bytes) + 4095) // 4096 * 4096
+            self.staging = torch.empty(staging_bytes + 4096, dtype=torch.uint8, pin_memory=True)
+            self._staging_off = (-self.staging.data_ptr()) % 4096
+        elif host is not None:
             self.host = host
             pool_on_device = host.is_cuda
         elif pool_on_device:
@@ -303,13 +320,16 @@ class Context:
         if self.host_tier is not None:
             self.s_d2h1 = torch.cuda.Stream(device="cuda:0")
             self.s_h2d1 = torch.cuda.Stream(device="cuda:0")
-        rt = RuntimeCfg(self.arena.data_ptr(), arena_bytes, self.host.data_ptr(), int(host_bytes),
+        rt = RuntimeCfg(self.arena.data_ptr(), arena_bytes, self.host.data_ptr() if self.host is not None else None, int(host_bytes),
                         self.s_compute.cuda_stream, self.s_d2h.cuda_stream, self.s_h2d.cuda_stream,
                         int(slow_tier_bw), 0, 1 if pool_on_device else 0,
                         self.host_tier.data_ptr() if self.host_tier is not None else None,
                         self.host_tier.numel() if self.host_tier is not None else 0,
                         self.s_d2h1.cuda_stream if self.s_d2h1 else None, self.s_h2d1.cuda_stream if self.s_h2d1 else None,
-                        int(host_tier_bw))
+                        int(host_tier_bw),
+                        os.fsencode(slow_tier_file) if slow_tier_file is not None else None,
+                        self.staging.data_ptr() + self._staging_off if self.staging is not None else None,
+                        staging_bytes if self.staging is not None else 0, int(file_chunk_bytes))
         mc = model_cfg(cfg)
         self.h = C.c_void_p()
         torch.cuda.synchronize()
@@ -319,7 +339,7 @@ class Context:
         if getattr(self, "h", None):
             lib().tio_ctx_destroy(self.h)
             self.h = None
-            self.arena = self.host = self.host_tier = None
+            self.arena = self.host = self.host_tier = self.staging = None
 
     def __del__(self):
         self.close()
@@ -344,6 +364,11 @@ class Context:
         _check(lib().tio_grads_read(self.h, self.index[name], out.ctypes.data_as(C.POINTER(C.c_float)),
                                     C.c_int64(out.size)))
         return out.reshape((r, c) if r > 1 else (c,))
+
+    def tio_file_tier_info(self) -> dict:
+        st = FileTierStats()
+        _check(lib().tio_file_tier_info(self.h, C.byref(st)))
+        return {f: getattr(st, f) for f, _ in FileTierStats._fields_}
 
     def tio_set_slow_tier_bw(self, bw: int):
         _check(lib().tio_set_slow_tier_bw(self.h, C.c_uint64(int(bw))))
@@ -384,9 +409,10 @@ class Context:
 
 
 def tio_ctx_create(cfg, arena_bytes, host_bytes, slow_tier_bw=0, single_copy_stream=False, arena=None, host=None,
-                   pool_on_device=False, host_tier_bytes=0, host_tier_bw=0, host_tier=None) -> Context:
+                   pool_on_device=False, host_tier_bytes=0, host_tier_bw=0, host_tier=None, slow_tier_file=None,
+                   staging_bytes=256 << 20, file_chunk_bytes=0) -> Context:
     return Context(cfg, arena_bytes, host_bytes, slow_tier_bw, single_copy_stream, arena, host, pool_on_device,
-                   host_tier_bytes, host_tier_bw, host_tier)
+                   host_tier_bytes, host_tier_bw, host_tier, slow_tier_file, staging_bytes, file_chunk_bytes)
 
 
 def tio_op_gemm(stream_handle, dtype, a_kmajor, b_kmajor, M, N, K, A_ptr, lda, B_ptr, ldb, bias_ptr, resid_ptr, ldr,

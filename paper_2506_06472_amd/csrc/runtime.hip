@@ -9,7 +9,9 @@
 // memory (or a device buffer outside the arena); its bandwidth is enforced per copy stream: DMA copies in
 // chunks, each followed by a one-wavefront kernel that holds the stream until the emulated channel would
 // have delivered the chunk (host pool), or a copy kernel that moves each tensor at the stated rate (device
-// pool); unthrottled runs use plain hipMemcpyAsync.
+// pool); unthrottled runs use plain hipMemcpyAsync.  With a file as the slow tier the two directions are
+// run by the threads of the file tier (file_tier.h): the host then blocks, before kernel k, until the
+// completion events kernel k depends on have been recorded by those threads.
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
@@ -17,11 +19,13 @@
 #include <cmath>
 #include <cstdlib>
 #include <cstring>
+#include <memory>
 #include <string>
 #include <thread>
 #include <vector>
 
 #include "analysis.h"
+#include "file_tier.h"
 #include "handles.h"
 #include "kernels.h"
 
@@ -98,6 +102,15 @@ struct tio_ctx {
     bool timeline = false;
     Plan uncapped;
     bool have_uncapped = false;
+    // slow tier in a file: persistent tensors and migrated periods have 4096-byte aligned file ranges
+    std::unique_ptr<FileTier> ft;
+    std::vector<uint64_t> home_file;                      // per persistent tensor
+    uint64_t home_file_bytes = 0;
+    std::vector<uint64_t> pair_file;                      // per pair of the installed plan (slow-tier pairs only)
+    std::vector<hipEvent_t> ev_req;                       // per plan entry: compute progress at submission
+    std::vector<uint64_t> req_seq;                        // per plan entry: sequence number of its last request
+    std::vector<uint64_t> off_seq, pre_seq;               // per pair: sequence number of its last offload / prefetch request
+    std::vector<uint64_t> ev_off_user;                    // per pair: last file prefetch that waits for ev_off[pair] of another tier
 };
 
 namespace {
@@ -113,6 +126,7 @@ void make_events(std::vector<hipEvent_t> &v, size_t n, bool timing) {
 }
 
 void sync_all(tio_ctx *c) {
+    if (c->ft) c->ft->drain();
     HIPCHK(hipStreamSynchronize(c->sc));
     HIPCHK(hipStreamSynchronize(c->sd));
     HIPCHK(hipStreamSynchronize(c->sh));
@@ -120,15 +134,34 @@ void sync_all(tio_ctx *c) {
     if (c->sh1) HIPCHK(hipStreamSynchronize(c->sh1));
 }
 
+// set-up path: the home slot of persistent tensor t on the slow tier (pinned pool, device pool or file)
+void home_from_dev(tio_ctx *c, int t, const void *dev) {
+    if (c->ft) c->ft->from_device(c->home_file[t], dev, c->prog.tensors[t].bytes);
+    else HIPCHK(hipMemcpy(c->host + c->home[t], dev, c->prog.tensors[t].bytes, hipMemcpyDefault));
+}
+void home_to_dev(tio_ctx *c, int t, void *dev) {
+    if (c->ft) c->ft->to_device(c->home_file[t], dev, c->prog.tensors[t].bytes);
+    else HIPCHK(hipMemcpy(dev, c->host + c->home[t], c->prog.tensors[t].bytes, hipMemcpyDefault));
+}
+void home_from_host(tio_ctx *c, int t, const void *src, uint64_t bytes) {
+    if (c->ft) c->ft->write_host(c->home_file[t], src, bytes);
+    else if (c->pool_dev) HIPCHK(hipMemcpy(c->host + c->home[t], src, bytes, hipMemcpyHostToDevice));
+    else std::memcpy(c->host + c->home[t], src, bytes);
+}
+void home_to_host(tio_ctx *c, int t, void *dst, uint64_t bytes) {
+    if (c->ft) c->ft->read_host(c->home_file[t], dst, bytes);
+    else if (c->pool_dev) HIPCHK(hipMemcpy(dst, c->host + c->home[t], bytes, hipMemcpyDeviceToHost));
+    else std::memcpy(dst, c->host + c->home[t], bytes);
+}
+
 // brings the latest version of every persistent tensor into its home slot on the slow tier
 void gather_to_home(tio_ctx *c) {
     sync_all(c);
     if (!c->installed) return;
     for (int t = 0; t < c->prog.n_persistent; ++t) {
-        if (c->on_dev[t])
-            HIPCHK(hipMemcpy(c->host + c->home[t], c->arena + c->dev_addr[t], c->prog.tensors[t].bytes, hipMemcpyDefault));
+        if (c->on_dev[t]) home_from_dev(c, t, c->arena + c->dev_addr[t]);
         else if (c->in_host1[t])      // offloaded to the host-memory tier: that slot holds the latest version
-            HIPCHK(hipMemcpy(c->host + c->home[t], c->host1 + c->host1_off[t], c->prog.tensors[t].bytes, hipMemcpyDefault));
+            home_from_host(c, t, c->host1 + c->host1_off[t], c->prog.tensors[t].bytes);
         c->in_host1[t] = 0;
     }
     // a device-to-device hipMemcpy may return before the copy has run, and the context's streams do not
@@ -143,14 +176,29 @@ void install_plan(tio_ctx *c, const Plan &p) {
     if (p.arena_needed > c->arena_usable)
         throw PlanError{TIO_ERR_ARENA_TOO_SMALL, "plan needs " + std::to_string(p.arena_needed) + " arena bytes, context has " +
                                                      std::to_string(c->arena_usable)};
-    if (p.host_needed > c->rt.host_bytes)
-        throw PlanError{TIO_ERR_OOM_HOST, "plan needs " + std::to_string(p.host_needed) + " slow-tier bytes, pool has " +
-                                              std::to_string(c->rt.host_bytes)};
+    std::vector<uint64_t> pair_file(p.pairs.size(), 0);
+    uint64_t file_needed = c->home_file_bytes;
+    if (c->ft) {
+        for (size_t i = 0; i < p.pairs.size(); ++i) {
+            const Pair &pr = p.pairs[i];
+            if (pr.tier != 0) continue;
+            if (pr.tensor < c->prog.n_persistent) pair_file[i] = c->home_file[pr.tensor];
+            else { pair_file[i] = file_needed; file_needed += (pr.bytes + FileTier::kAlign - 1) / FileTier::kAlign * FileTier::kAlign; }
+        }
+    }
+    if ((c->ft ? file_needed : p.host_needed) > c->rt.host_bytes)
+        throw PlanError{TIO_ERR_OOM_HOST, "plan needs " + std::to_string(c->ft ? file_needed : p.host_needed) +
+                                              " slow-tier bytes, pool has " + std::to_string(c->rt.host_bytes)};
     if (p.host_tier_needed > 0 && (!c->host1 || !c->sd1 || !c->sh1 || p.host_tier_needed > c->rt.host_tier_bytes))
         throw PlanError{TIO_ERR_OOM_HOST, "plan needs " + std::to_string(p.host_tier_needed) +
                                               " bytes of a host-memory tier with its two streams, context has " +
                                               std::to_string(c->host1 ? c->rt.host_tier_bytes : 0)};
     gather_to_home(c);
+    if (c->ft) {
+        c->ft->resize(file_needed);
+        c->ft->set_pairs((int)p.pairs.size());
+        c->pair_file = pair_file;
+    }
     c->plan = p;
     c->installed = true;
     const int np = c->prog.n_persistent;
@@ -169,7 +217,7 @@ void install_plan(tio_ctx *c, const Plan &p) {
             if (!al.whole_cycle && al.born_by_pair >= 0 && al.first == 0) by_prefetch_at_0 = true;
         }
         if (by_prefetch_at_0) continue;
-        HIPCHK(hipMemcpy(c->arena + a, c->host + c->home[t], c->prog.tensors[t].bytes, hipMemcpyDefault));
+        home_to_dev(c, t, c->arena + a);
         c->on_dev[t] = 1;
         c->dev_addr[t] = a;
     }
@@ -190,6 +238,13 @@ void install_plan(tio_ctx *c, const Plan &p) {
     c->rec_kernel.assign(N, 0);
     c->rec_off.assign(p.pairs.size(), 0);
     c->rec_pre.assign(p.pairs.size(), 0);
+    if (c->ft) {
+        make_events(c->ev_req, p.entries.size(), false);
+        c->req_seq.assign(p.entries.size(), 0);
+        c->off_seq.assign(p.pairs.size(), 0);
+        c->pre_seq.assign(p.pairs.size(), 0);
+        c->ev_off_user.assign(p.pairs.size(), 0);
+    }
     c->params_dirty = false;
 }
 
@@ -325,17 +380,33 @@ void run_step(tio_ctx *c, const int32_t *tokens, const int32_t *labels, bool cap
             hipStream_t so = t1 ? c->sd1 : c->sd, sp = t1 ? c->sh1 : c->sh;
             uint8_t *pool = t1 ? c->host1 : c->host;
             const uint64_t rate = t1 ? c->bw1 : c->bw;
+            const bool in_file = c->ft && !t1;           // this pair moves through the file tier's threads
+            auto progress_event = [&]() {                // compute progress at this trigger point, for the file tier
+                if (c->req_seq[ei]) c->ft->wait_consumed(e.kind == TIO_OFFLOAD ? 0 : 1, c->req_seq[ei]);
+                HIPCHK(hipEventRecord(c->ev_req[ei], c->sc));
+                return c->ev_req[ei];
+            };
             if (e.kind == TIO_OFFLOAD) {
                 // first iteration after a plan is installed: an offload that belongs to the end of the
                 // previous iteration (trigger wraps to the start of this one) has nothing to copy, the
                 // slow-tier home slot already holds the latest version
                 if (persistent && !c->on_dev[e.tensor]) continue;
                 const Alloc &al = p.allocs[pr.alloc_before];
-                if (c->rec_kernel[prev]) HIPCHK(hipStreamWaitEvent(so, c->ev_kernel[prev], 0));
-                if (tl) { HIPCHK(hipEventRecord(c->ev_c0[ei], so)); issued[ei] = 1; }
-                paced_copy(c, so, t1 ? 2 : 0, pool + pr.host_offset, c->arena + al.address, pr.bytes, hipMemcpyDeviceToHost, rate);
-                if (tl) HIPCHK(hipEventRecord(c->ev_c1[ei], so));
-                HIPCHK(hipEventRecord(c->ev_off[e.pair], so));
+                if (in_file) {
+                    const uint64_t seq = c->ft->submit_offload(e.pair, progress_event(), c->arena + al.address, c->pair_file[e.pair],
+                                                               pr.bytes, c->ev_off[e.pair], tl ? c->ev_c0[ei] : nullptr,
+                                                               tl ? c->ev_c1[ei] : nullptr);
+                    c->req_seq[ei] = c->off_seq[e.pair] = seq;
+                    if (tl) issued[ei] = 1;
+                } else {
+                    // a prefetch of the file tier may still have to take over this pair's previous event
+                    if (c->ft && c->ev_off_user[e.pair]) { c->ft->wait_consumed(1, c->ev_off_user[e.pair]); c->ev_off_user[e.pair] = 0; }
+                    if (c->rec_kernel[prev]) HIPCHK(hipStreamWaitEvent(so, c->ev_kernel[prev], 0));
+                    if (tl) { HIPCHK(hipEventRecord(c->ev_c0[ei], so)); issued[ei] = 1; }
+                    paced_copy(c, so, t1 ? 2 : 0, pool + pr.host_offset, c->arena + al.address, pr.bytes, hipMemcpyDeviceToHost, rate);
+                    if (tl) HIPCHK(hipEventRecord(c->ev_c1[ei], so));
+                    HIPCHK(hipEventRecord(c->ev_off[e.pair], so));
+                }
                 c->rec_off[e.pair] = 1;
                 if (persistent) {
                     c->on_dev[e.tensor] = 0;
@@ -347,23 +418,57 @@ void run_step(tio_ctx *c, const int32_t *tokens, const int32_t *labels, bool cap
                 const Alloc &al = p.allocs[pr.alloc_after];
                 // a persistent tensor whose offload to the host-memory tier belongs to an iteration that never
                 // ran (first iteration after the plan was installed) is still in its slow-tier home slot
-                const uint8_t *src = (t1 && persistent && !c->in_host1[e.tensor]) ? c->host + c->home[e.tensor] : pool + pr.host_offset;
-                if (c->rec_kernel[prev]) HIPCHK(hipStreamWaitEvent(sp, c->ev_kernel[prev], 0));
-                if (c->rec_off[e.pair]) HIPCHK(hipStreamWaitEvent(sp, c->ev_off[e.pair], 0));
-                for (int q : al.wait_pairs) if (c->rec_off[q]) HIPCHK(hipStreamWaitEvent(sp, c->ev_off[q], 0));
-                if (tl) { HIPCHK(hipEventRecord(c->ev_c0[ei], sp)); issued[ei] = 1; }
-                paced_copy(c, sp, t1 ? 3 : 1, c->arena + al.address, src, pr.bytes,
-                           (c->pool_dev && src != pool + pr.host_offset) ? hipMemcpyDefault : hipMemcpyHostToDevice, rate);
-                if (tl) HIPCHK(hipEventRecord(c->ev_c1[ei], sp));
-                HIPCHK(hipEventRecord(c->ev_pre[e.pair], sp));
+                const bool from_home = t1 && persistent && !c->in_host1[e.tensor];
+                if (in_file) {
+                    FileTier::Dep written{e.pair, c->rec_off[e.pair] ? c->off_seq[e.pair] : 0};
+                    std::vector<FileTier::Dep> landed;
+                    std::vector<hipEvent_t> more;
+                    for (int q : al.wait_pairs) {
+                        if (!c->rec_off[q]) continue;
+                        if (p.pairs[q].tier == 0) landed.push_back({q, c->off_seq[q]});
+                        else more.push_back(c->ev_off[q]);       // recorded above by this thread, on the other tier's stream
+                    }
+                    const uint64_t seq = c->ft->submit_prefetch(e.pair, progress_event(), c->arena + al.address, c->pair_file[e.pair],
+                                                                pr.bytes, written, landed, more, c->ev_pre[e.pair],
+                                                                tl ? c->ev_c0[ei] : nullptr, tl ? c->ev_c1[ei] : nullptr);
+                    c->req_seq[ei] = c->pre_seq[e.pair] = seq;
+                    for (int q : al.wait_pairs) if (c->rec_off[q] && p.pairs[q].tier != 0) c->ev_off_user[q] = seq;
+                    if (tl) issued[ei] = 1;
+                } else if (c->ft && from_home) {
+                    // rare (first iteration under a new plan): the source is the tensor's home range in the file.
+                    // Everything issued so far is allowed to finish, then the tensor is read synchronously.
+                    sync_all(c);
+                    c->ft->to_device(c->home_file[e.tensor], c->arena + al.address, pr.bytes);
+                    HIPCHK(hipEventRecord(c->ev_pre[e.pair], sp));
+                } else {
+                    const uint8_t *src = from_home ? c->host + c->home[e.tensor] : pool + pr.host_offset;
+                    if (c->rec_kernel[prev]) HIPCHK(hipStreamWaitEvent(sp, c->ev_kernel[prev], 0));
+                    if (c->rec_off[e.pair]) HIPCHK(hipStreamWaitEvent(sp, c->ev_off[e.pair], 0));
+                    for (int q : al.wait_pairs) {
+                        if (!c->rec_off[q]) continue;
+                        if (c->ft && p.pairs[q].tier == 0) c->ft->wait_offload_recorded(q, c->off_seq[q]);
+                        HIPCHK(hipStreamWaitEvent(sp, c->ev_off[q], 0));
+                    }
+                    if (tl) { HIPCHK(hipEventRecord(c->ev_c0[ei], sp)); issued[ei] = 1; }
+                    paced_copy(c, sp, t1 ? 3 : 1, c->arena + al.address, src, pr.bytes,
+                               (c->pool_dev && src != pool + pr.host_offset) ? hipMemcpyDefault : hipMemcpyHostToDevice, rate);
+                    if (tl) HIPCHK(hipEventRecord(c->ev_c1[ei], sp));
+                    HIPCHK(hipEventRecord(c->ev_pre[e.pair], sp));
+                }
                 c->rec_pre[e.pair] = 1;
                 if (persistent) { c->on_dev[e.tensor] = 1; c->dev_addr[e.tensor] = al.address; c->in_host1[e.tensor] = 0; }
                 h2d += pr.bytes;
             }
             ++nmig;
         }
-        for (int q : p.kernel_wait_pre[k]) if (c->rec_pre[q]) HIPCHK(hipStreamWaitEvent(c->sc, c->ev_pre[q], 0));
-        for (int q : p.kernel_wait_off[k]) if (c->rec_off[q]) HIPCHK(hipStreamWaitEvent(c->sc, c->ev_off[q], 0));
+        for (int q : p.kernel_wait_pre[k]) if (c->rec_pre[q]) {
+            if (c->ft && p.pairs[q].tier == 0 && c->pre_seq[q]) c->ft->wait_prefetch_recorded(q, c->pre_seq[q]);
+            HIPCHK(hipStreamWaitEvent(c->sc, c->ev_pre[q], 0));
+        }
+        for (int q : p.kernel_wait_off[k]) if (c->rec_off[q]) {
+            if (c->ft && p.pairs[q].tier == 0) c->ft->wait_offload_recorded(q, c->off_seq[q]);
+            HIPCHK(hipStreamWaitEvent(c->sc, c->ev_off[q], 0));
+        }
         if (capture && c->prog.kernels[k].op == OP_ADAMW) capture_grad(c, k);
         if (timing) HIPCHK(hipEventRecord(c->ev_t0[k], c->sc));
         launch(c, k);
@@ -374,6 +479,7 @@ void run_step(tio_ctx *c, const int32_t *tokens, const int32_t *labels, bool cap
         if (p.kernel_needs_event[k]) { HIPCHK(hipEventRecord(c->ev_kernel[k], c->sc)); c->rec_kernel[k] = 1; }
     }
     HIPCHK(hipStreamSynchronize(c->sc));
+    if (c->ft) c->ft->check();
     const float loss = *c->loss_pinned;
     const auto w1 = std::chrono::steady_clock::now();
     c->step += 1;
@@ -425,6 +531,7 @@ void ensure_plan(tio_ctx *c, const tio_plan *plan) {
 #define TIO_RT_END                                                                                              \
     } catch (const PlanError &e) { return fail(e.code, e.msg);                                                  \
     } catch (const HipError &e) { return fail(TIO_ERR_HIP, std::string(e.what) + ": " + hipGetErrorString(e.e)); \
+    } catch (const FileTierError &e) { return fail(TIO_ERR_IO, e.msg);                                          \
     } catch (const std::exception &e) { return fail(TIO_ERR_INVALID_ARG, e.what()); }
 
 extern "C" {
@@ -432,7 +539,10 @@ extern "C" {
 int tio_ctx_create(const tio_model_cfg *cfg, const tio_runtime_cfg *rt, tio_ctx **out) {
     if (!cfg || !rt || !out) return fail(TIO_ERR_INVALID_ARG, "null argument");
     TIO_RT_BEGIN
-    if (!rt->arena || !rt->host_pool || rt->arena_bytes < (1u << 16)) return fail(TIO_ERR_INVALID_ARG, "arena and slow-tier pool are required");
+    const bool file_tier = rt->slow_tier_file != nullptr;
+    if (!rt->arena || (!rt->host_pool && !file_tier) || rt->arena_bytes < (1u << 16))
+        return fail(TIO_ERR_INVALID_ARG, "arena and slow-tier pool (or file) are required");
+    if (file_tier && (rt->host_pool || rt->pool_on_device)) return fail(TIO_ERR_INVALID_ARG, "the slow tier is either a pool or a file");
     if (((uintptr_t)rt->arena & 255) || ((uintptr_t)rt->host_pool & 255)) return fail(TIO_ERR_INVALID_ARG, "arena and pool must be 256-byte aligned");
     const int dh = cfg->d_model / std::max(1, cfg->n_heads);
     if (dh != 32 && dh != 64 && dh != 128) return fail(TIO_ERR_INVALID_ARG, "head dimension must be 32, 64 or 128");
@@ -460,6 +570,15 @@ int tio_ctx_create(const tio_model_cfg *cfg, const tio_runtime_cfg *rt, tio_ctx 
     c->home.assign(c->prog.n_persistent, 0);
     for (int t = 0; t < c->prog.n_persistent; ++t) { c->home[t] = h; h += c->prog.tensors[t].bytes; }
     c->home_bytes = h;
+    if (file_tier) {                                     // every range of the file starts on a direct-I/O boundary
+        uint64_t f = 0;
+        c->home_file.assign(c->prog.n_persistent, 0);
+        for (int t = 0; t < c->prog.n_persistent; ++t) {
+            c->home_file[t] = f;
+            f += (c->prog.tensors[t].bytes + FileTier::kAlign - 1) / FileTier::kAlign * FileTier::kAlign;
+        }
+        c->home_file_bytes = h = f;
+    }
     if (h > rt->host_bytes) { delete c; return fail(TIO_ERR_OOM_HOST, "slow-tier pool smaller than the persistent tensors"); }
     c->loaded.assign(c->prog.params.size(), 0);
     if (hipHostMalloc((void **)&c->loss_pinned, 4096, hipHostMallocDefault) != hipSuccess) { delete c; return fail(TIO_ERR_HIP, "hipHostMalloc failed"); }
@@ -472,6 +591,12 @@ int tio_ctx_create(const tio_model_cfg *cfg, const tio_runtime_cfg *rt, tio_ctx 
         const char *e = getenv("TIO_PACING");             // "kernel" forces the paced copy kernel
         c->dma_pacing = !c->pool_dev && !(e && std::string(e) == "kernel");
     }
+    if (file_tier) {
+        try {
+            c->ft.reset(new FileTier(rt->slow_tier_file, rt->staging, rt->staging_bytes, rt->file_chunk_bytes, c->sd, c->sh, 0));
+            c->ft->resize(c->home_file_bytes);
+        } catch (...) { tio_ctx_destroy(c); throw; }
+    }
     *out = c;
     return TIO_OK;
     TIO_RT_END
@@ -479,7 +604,10 @@ int tio_ctx_create(const tio_model_cfg *cfg, const tio_runtime_cfg *rt, tio_ctx 
 
 int tio_ctx_destroy(tio_ctx *c) {
     if (!c) return TIO_OK;
+    if (c->ft) { try { c->ft->drain(); } catch (...) {} }
     (void)hipStreamSynchronize(c->sc); (void)hipStreamSynchronize(c->sd); (void)hipStreamSynchronize(c->sh);
+    c->ft.reset();                                       // joins the file tier's threads before their events go
+    destroy_events(c->ev_req);
     destroy_events(c->ev_kernel); destroy_events(c->ev_off); destroy_events(c->ev_pre);
     destroy_events(c->ev_t0); destroy_events(c->ev_t1);
     destroy_events(c->ev_c0); destroy_events(c->ev_c1);
@@ -502,10 +630,12 @@ int tio_params_load(tio_ctx *c, int32_t index, const float *v, int64_t numel) {
         c->installed = false;
     }
     const bool bf = c->cfg.precision == TIO_PREC_BF16;
-    uint8_t *hw = c->host + c->home[p.w], *hm = c->host + c->home[p.m], *hv = c->host + c->home[p.v];
-    uint8_t *hms = bf ? c->host + c->home[p.master] : nullptr;
+    const bool staged = c->pool_dev || c->ft;
+    uint8_t *hw = staged ? nullptr : c->host + c->home[p.w], *hm = staged ? nullptr : c->host + c->home[p.m];
+    uint8_t *hv = staged ? nullptr : c->host + c->home[p.v];
+    uint8_t *hms = bf && !staged ? c->host + c->home[p.master] : nullptr;
     std::vector<uint8_t> stage;
-    if (c->pool_dev) {                                   // the CPU cannot write the pool: convert into a host buffer first
+    if (staged) {                                        // the CPU cannot write the pool: convert into a host buffer first
         const size_t wb = (size_t)numel * (bf ? 2 : 4);
         stage.resize(wb + (bf ? (size_t)numel * 4 : 0));
         hw = stage.data();
@@ -533,7 +663,12 @@ int tio_params_load(tio_ctx *c, int32_t index, const float *v, int64_t numel) {
         for (int t = 0; t < nthr; ++t) th.emplace_back(fill, t * per, std::min(numel, (t + 1) * per));
         for (auto &x : th) x.join();
     }
-    if (c->pool_dev) {
+    if (c->ft) {
+        home_from_host(c, p.w, hw, (uint64_t)numel * (bf ? 2 : 4));
+        if (bf) home_from_host(c, p.master, hms, (uint64_t)numel * 4);
+        c->ft->zero(c->home_file[p.m], (uint64_t)numel * 4);
+        c->ft->zero(c->home_file[p.v], (uint64_t)numel * 4);
+    } else if (c->pool_dev) {
         HIPCHK(hipMemcpy(c->host + c->home[p.w], hw, (size_t)numel * (bf ? 2 : 4), hipMemcpyHostToDevice));
         if (bf) HIPCHK(hipMemcpy(c->host + c->home[p.master], hms, (size_t)numel * 4, hipMemcpyHostToDevice));
         HIPCHK(hipMemset(c->host + c->home[p.m], 0, (size_t)numel * 4));
@@ -560,8 +695,7 @@ int tio_params_read(tio_ctx *c, int32_t index, int32_t which, float *dst, int64_
     std::vector<uint8_t> tmp(nbytes);
     if (c->installed && !c->params_dirty && c->on_dev[t]) HIPCHK(hipMemcpy(tmp.data(), c->arena + c->dev_addr[t], nbytes, hipMemcpyDeviceToHost));
     else if (c->installed && !c->params_dirty && c->in_host1[t]) std::memcpy(tmp.data(), c->host1 + c->host1_off[t], nbytes);
-    else if (c->pool_dev) HIPCHK(hipMemcpy(tmp.data(), c->host + c->home[t], nbytes, hipMemcpyDeviceToHost));
-    else std::memcpy(tmp.data(), c->host + c->home[t], nbytes);
+    else home_to_host(c, t, tmp.data(), nbytes);
     if (half) for (int64_t i = 0; i < numel; ++i) dst[i] = host_bf16_to_f32(((uint16_t *)tmp.data())[i]);
     else std::memcpy(dst, tmp.data(), nbytes);
     return TIO_OK;
@@ -574,6 +708,19 @@ int tio_grads_read(tio_ctx *c, int32_t index, float *dst, int64_t numel) {
         return fail(TIO_ERR_INVALID_ARG, "no captured gradient of that size (run a step with capture_grads)");
     std::memcpy(dst, c->grads[index].data(), numel * 4);
     return TIO_OK;
+}
+
+int tio_file_tier_info(tio_ctx *c, tio_file_tier_stats *out) {
+    if (!c || !out) return fail(TIO_ERR_INVALID_ARG, "null argument");
+    if (!c->ft) return fail(TIO_ERR_INVALID_ARG, "the context has no file tier");
+    TIO_RT_BEGIN
+    sync_all(c);
+    out->direct_io = c->ft->direct() ? 1 : 0;
+    out->file_bytes = c->ft->file_bytes();
+    out->bytes_written = c->ft->bytes_written();
+    out->bytes_read = c->ft->bytes_read();
+    return TIO_OK;
+    TIO_RT_END
 }
 
 int tio_set_slow_tier_bw(tio_ctx *c, uint64_t bw) {

@@ -1,0 +1,178 @@
+"""GPU: the slow tier as a file (the storage tier of Section 3.3).  Training under a capped plan with every
+migration going through the file leaves the loss and all optimizer state bit-for-bit as the uncapped run with a
+memory pool produces them; small staging rings and chunk sizes make every tensor span several chunks with a
+ragged tail and keep the rings full; the file tier combines with the host-memory tier and survives plan changes;
+bad files, staging buffers and size limits are refused with an error code."""
+import os
+
+import numpy as np
+import pytest
+
+from synth import CONFIGS
+from gpulib import make_inputs, read_state
+
+pytestmark = pytest.mark.gpu
+
+BF16 = dict(arch="gpt", L=2, d=256, H=4, f=1024, V=1000, T=256, B=2, precision="bf16", lr=3e-4)
+FILE_LIMIT = 1 << 30
+
+
+def _plans(cfg, frac, bw, hbw=0, bfrac=0.0, min_bytes=0):
+    import paper_2506_06472_amd as tio
+    lt = tio.tio_trace_build(cfg)
+    ll = tio.tio_analyze_lifetimes(lt)
+    peak = int(ll.export()["M"].max())
+    up = tio.tio_build_plan(lt, ll, 2**62, 0)
+    cp = tio.tio_build_plan(lt, ll, int(peak * frac) // 256 * 256, bw, min_bytes=min_bytes, host_bw=hbw,
+                            host_budget=int(peak * bfrac))
+    return lt, ll, up, cp, peak
+
+
+def _reference(cfg, params, tok, lab, up, steps):
+    import paper_2506_06472_amd as tio
+    ue = up.export()
+    names = [n for n, _, _ in tio.tio_param_list(cfg)]
+    ctx = tio.tio_ctx_create(cfg, ue["arena_needed"], ue["host_needed"] + (1 << 20), 0)
+    ctx.tio_params_load(params)
+    losses = [ctx.tio_train_step(tok, lab, None)["loss"] for _ in range(steps)]
+    state = read_state(ctx, names, cfg["precision"] == "bf16")
+    ctx.close()
+    return losses, state
+
+
+def _same(l0, s0, l1, s1):
+    assert np.array(l0, np.float32).tobytes() == np.array(l1, np.float32).tobytes(), (l0, l1)
+    for key in s0:
+        assert s0[key].tobytes() == s1[key].tobytes(), key
+
+
+@pytest.mark.parametrize("cfg,frac,chunk,staging", [
+    (CONFIGS["tiny_gpt_fp32"], 0.5, 4096, 4 * 4096),             # smallest legal ring: two one-page chunks per direction
+    (CONFIGS["tiny_llama_fp32"], 0.45, 64 << 10, 1 << 20),
+    (BF16, 0.4, 256 << 10, 4 << 20),
+    (BF16, 0.4, 0, 64 << 20),                                    # default chunk (8 MiB): most tensors are one ragged chunk
+], ids=["gpt_fp32_page_chunks", "llama_fp32", "gpt_bf16", "gpt_bf16_default_chunk"])
+def test_file_tier_is_bitwise_neutral(cfg, frac, chunk, staging, tmp_path):
+    import paper_2506_06472_amd as tio
+    params, tok, lab = make_inputs(cfg, seed=3)
+    lt, ll, up, cp, peak = _plans(cfg, frac, 2 * 10**9)
+    ce = cp.export()
+    assert ce["bytes_per_direction"] > 0
+    names = [n for n, _, _ in tio.tio_param_list(cfg)]
+    l0, s0 = _reference(cfg, params, tok, lab, up, 4)
+    path = str(tmp_path / "slow_tier.bin")
+    ctx = tio.tio_ctx_create(cfg, ce["cap"], FILE_LIMIT, 0, slow_tier_file=path, staging_bytes=staging, file_chunk_bytes=chunk)
+    ctx.tio_params_load(params)
+    # parameters come back from the file before any step has run
+    w = ctx.tio_params_read(names[0], 0)
+    assert w.tobytes() == np.asarray(params[names[0]], np.float32).reshape(w.shape).tobytes()
+    l1 = []
+    for step in range(4):
+        st = ctx.tio_train_step(tok, lab, cp)
+        l1.append(st["loss"])
+        assert st["h2d_bytes"] == ce["bytes_per_direction"]
+    info = ctx.tio_file_tier_info()
+    print(f"direct I/O {info['direct_io']} file {info['file_bytes']} written {info['bytes_written']} read {info['bytes_read']}", flush=True)
+    # the first iteration skips offloads of tensors that start on the slow tier; afterwards every migration is file traffic
+    assert 3 * ce["bytes_per_direction"] <= info["bytes_written"] <= 4 * ce["bytes_per_direction"]
+    assert info["bytes_read"] == 4 * ce["bytes_per_direction"]
+    assert info["file_bytes"] % 4096 == 0 and os.path.getsize(path) == info["file_bytes"]
+    s1 = read_state(ctx, names, cfg["precision"] == "bf16")
+    ctx.close()
+    _same(l0, s0, l1, s1)
+
+
+def test_file_tier_with_host_memory_tier(tmp_path):
+    import paper_2506_06472_amd as tio
+    cfg = BF16
+    params, tok, lab = make_inputs(cfg, seed=4)
+    lt, ll, up, cp, peak = _plans(cfg, 0.4, 4 * 10**9, 4 * 10**10, 0.25)
+    ce = cp.export()
+    n1 = sum(ce["tier"])
+    assert 0 < n1 < len(ce["tier"])
+    names = [n for n, _, _ in tio.tio_param_list(cfg)]
+    l0, s0 = _reference(cfg, params, tok, lab, up, 4)
+    ctx = tio.tio_ctx_create(cfg, ce["cap"], FILE_LIMIT, 0, host_tier_bytes=ce["host_tier_needed"] + 4096,
+                             slow_tier_file=str(tmp_path / "slow_tier.bin"), staging_bytes=2 << 20, file_chunk_bytes=128 << 10)
+    ctx.tio_params_load(params)
+    l1 = [ctx.tio_train_step(tok, lab, cp)["loss"] for _ in range(4)]
+    info = ctx.tio_file_tier_info()
+    assert 0 < info["bytes_read"] < 4 * ce["bytes_per_direction"]       # the rest went to the host-memory tier
+    s1 = read_state(ctx, names, True)
+    ctx.close()
+    _same(l0, s0, l1, s1)
+
+
+def test_plan_changes_with_a_file_tier(tmp_path):
+    import paper_2506_06472_amd as tio
+    cfg = BF16
+    params, tok, lab = make_inputs(cfg, seed=5)
+    lt, ll, up, cp2, peak = _plans(cfg, 0.4, 4 * 10**9, 4 * 10**10, 0.25)
+    cp1 = tio.tio_build_plan(lt, ll, int(peak * 0.5) // 256 * 256, 4 * 10**9)
+    ue, e2 = up.export(), cp2.export()
+    names = [n for n, _, _ in tio.tio_param_list(cfg)]
+    l0, s0 = _reference(cfg, params, tok, lab, up, 6)
+    ctx = tio.tio_ctx_create(cfg, ue["arena_needed"], FILE_LIMIT, 0, host_tier_bytes=e2["host_tier_needed"] + 4096,
+                             slow_tier_file=str(tmp_path / "slow_tier.bin"), staging_bytes=2 << 20, file_chunk_bytes=128 << 10)
+    ctx.tio_params_load(params)
+    l1 = [ctx.tio_train_step(tok, lab, pl)["loss"] for pl in (cp2, cp2, cp1, cp2, None, cp1)]
+    s1 = read_state(ctx, names, True)
+    ctx.close()
+    _same(l0, s0, l1, s1)
+
+
+def test_timeline_of_a_step_on_the_file_tier(tmp_path):
+    import paper_2506_06472_amd as tio
+    cfg = BF16
+    params, tok, lab = make_inputs(cfg, seed=6)
+    lt, ll, up, cp, peak = _plans(cfg, 0.4, 2 * 10**9)
+    ce = cp.export()
+    ctx = tio.tio_ctx_create(cfg, ce["cap"], FILE_LIMIT, 0, slow_tier_file=str(tmp_path / "slow_tier.bin"),
+                             staging_bytes=4 << 20, file_chunk_bytes=256 << 10)
+    ctx.tio_params_load(params)
+    ctx.tio_train_step(tok, lab, cp)
+    ctx.tio_train_step(tok, lab, cp, timeline=True)
+    n, ne = lt.export()["n_kernels"], len(ce["entries"])
+    k0, k1, c0, c1 = ctx.tio_step_timeline(n, ne)
+    ctx.close()
+    assert (k1 >= k0).all() and (np.diff(k0) >= 0).all()
+    issued = c0 >= 0
+    assert issued.mean() > 0.9 and (c1[issued] >= c0[issued]).all()
+
+
+def test_file_tier_errors(tmp_path):
+    import paper_2506_06472_amd as tio
+    cfg = CONFIGS["tiny_gpt_fp32"]
+    params, tok, lab = make_inputs(cfg, seed=0)
+    lt, ll, up, cp, peak = _plans(cfg, 0.5, 2 * 10**9)
+    ce = cp.export()
+    with pytest.raises(tio.TioError) as ei:        # directory that does not exist
+        tio.tio_ctx_create(cfg, ce["cap"], FILE_LIMIT, 0, slow_tier_file=str(tmp_path / "missing" / "f.bin"))
+    assert ei.value.code == -9
+    with pytest.raises(tio.TioError) as ei:        # staging buffer below two chunks per direction
+        tio.tio_ctx_create(cfg, ce["cap"], FILE_LIMIT, 0, slow_tier_file=str(tmp_path / "a.bin"), staging_bytes=8192,
+                           file_chunk_bytes=4096)
+    assert ei.value.code == -9
+    with pytest.raises(tio.TioError) as ei:        # chunk size that is not a multiple of the direct-I/O block
+        tio.tio_ctx_create(cfg, ce["cap"], FILE_LIMIT, 0, slow_tier_file=str(tmp_path / "a.bin"), file_chunk_bytes=5000)
+    assert ei.value.code == -9
+    with pytest.raises(tio.TioError) as ei:        # size limit below the persistent tensors
+        tio.tio_ctx_create(cfg, ce["cap"], 4096, 0, slow_tier_file=str(tmp_path / "b.bin"))
+    assert ei.value.code == -2
+    # a limit that holds the persistent tensors but not the plan's migrated activations
+    np_ = lt.export()["n_persistent"]
+    assert any(t >= np_ for t, *_ in ce["entries"])
+    ctx = tio.tio_ctx_create(cfg, ce["cap"], FILE_LIMIT, 0, slow_tier_file=str(tmp_path / "c.bin"))
+    home = ctx.tio_file_tier_info()["file_bytes"]      # the file holds exactly the persistent tensors so far
+    ctx.close()
+    ctx = tio.tio_ctx_create(cfg, ce["cap"], home, 0, slow_tier_file=str(tmp_path / "c.bin"))
+    ctx.tio_params_load(params)
+    with pytest.raises(tio.TioError) as ei:
+        ctx.tio_train_step(tok, lab, cp)
+    assert ei.value.code == -2
+    ctx.close()
+    # a context without a file tier has no file statistics
+    ctx = tio.tio_ctx_create(cfg, ce["cap"], ce["host_needed"] + (1 << 20), 0)
+    with pytest.raises(tio.TioError):
+        ctx.tio_file_tier_info()
+    ctx.close()
