@@ -4,7 +4,8 @@
 Workload: GPT-2-small-shaped decoder, bf16 mixed precision with fp32 master weights and AdamW,
 12 layers, d=768, seq 1024, batch 8 (8192 tokens per step), memory cap = 40 % of the uncapped
 peak, synthetic seeded weights and tokens.  One step = forward, backward, AdamW under the plan,
-with the slow tier (pinned host memory) paced to --bw bytes/s per direction.
+with the slow tier (pinned host memory) paced to --bw bytes/s per direction.  --slow-tier file puts the
+slow tier into a file instead (direct I/O at whatever the file system delivers; probed first).
 
 Prints one JSON line: tokens/s under the cap (value), the uncapped ideal and the migration bound
 beside it, the MFMA roofline of the GEMM kernel measured with HIP events in the timed region, and
@@ -31,6 +32,68 @@ PEAK_BF16_TFLOPS = 2500.0
 GEMM_TRAFFIC_BYTES_PER_LAUNCH = {"gpt2_small_bf16": 177.94e6}
 
 
+def probe_file_bw(path, total=2 << 30, block=8 << 20, threads=4):
+    """Sequential write then read of `total` bytes in `block` pieces from `threads` threads, direct I/O if the file
+    system has it: the bandwidth the file tier can expect.  Returns bytes/s per direction."""
+    import mmap
+    import threading
+    flags = os.O_RDWR | os.O_CREAT
+    try:
+        fd = os.open(path, flags | os.O_DIRECT, 0o600)
+        direct = True
+    except OSError:
+        fd = os.open(path, flags, 0o600)
+        direct = False
+    try:
+        os.ftruncate(fd, total)
+        try:
+            os.posix_fallocate(fd, 0, total)
+        except OSError:
+            pass
+        bufs = [mmap.mmap(-1, block) for _ in range(threads)]      # page aligned
+        for b in bufs:
+            b.write(os.urandom(4096) * (block // 4096))
+        nblk = total // block
+
+        def run(fn):
+            def body(i):
+                for j in range(i, nblk, threads):
+                    fn(bufs[i], j * block)
+            th = [threading.Thread(target=body, args=(i,)) for i in range(threads)]
+            t0 = time.perf_counter()
+            for t in th:
+                t.start()
+            for t in th:
+                t.join()
+            return total / (time.perf_counter() - t0)
+        w = run(lambda b, off: os.pwrite(fd, b, off))
+        if not direct:
+            os.fsync(fd)
+        r = run(lambda b, off: os.preadv(fd, [b], off))
+        # both directions at once, as in a training step: even blocks are written while odd blocks are read
+        bufs2 = [mmap.mmap(-1, block) for _ in range(threads)]
+        res = {}
+
+        def both(kind):
+            def body(i):
+                for j in range(2 * i + (kind == "r"), nblk, 2 * threads):
+                    (os.pwrite(fd, bufs[i], j * block) if kind == "w" else os.preadv(fd, [bufs2[i]], j * block))
+            th = [threading.Thread(target=body, args=(i,)) for i in range(threads)]
+            t0 = time.perf_counter()
+            for t in th:
+                t.start()
+            for t in th:
+                t.join()
+            res[kind] = (total / 2) / (time.perf_counter() - t0)
+        tw, tr = threading.Thread(target=both, args=("w",)), threading.Thread(target=both, args=("r",))
+        tw.start(); tr.start(); tw.join(); tr.join()
+    finally:
+        os.close(fd)
+        if os.path.exists(path):
+            os.remove(path)
+    return {"write_Bps": w, "read_Bps": r, "duplex_write_Bps": res["w"], "duplex_read_Bps": res["r"], "direct": direct}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -39,9 +102,15 @@ def main():
     ap.add_argument("--workload", default="gpt2_small_bf16")
     ap.add_argument("--bw", type=float, default=-1, help="slow-tier bytes/s per direction; 0 = unthrottled; default: the workload's (25e9)")
     ap.add_argument("--min-bytes", type=int, default=1 << 20)
-    ap.add_argument("--slow-tier", choices=["auto", "host", "device"], default="auto",
+    ap.add_argument("--file", default="/tmp/teraio_slow_tier.bin", help="--slow-tier file: path of the file (created, removed at the end)")
+    ap.add_argument("--staging-mb", type=int, default=256, help="--slow-tier file: pinned staging buffer, MiB")
+    ap.add_argument("--chunk-mb", type=int, default=8, help="--slow-tier file: transfer chunk, MiB")
+    ap.add_argument("--slow-tier", choices=["auto", "host", "device", "file"], default="auto",
                     help="where the slow-tier pool lives: pinned host memory, or a device buffer outside the arena "
                          "(auto: host unless the pool exceeds what this kind of box can pin, about 28 GB)")
+    ap.add_argument("--shared-channel", choices=["auto", "yes", "no"], default="auto",
+                    help="plan with one channel shared by offloads and prefetches instead of one per direction "
+                         "(auto: yes for the file tier, whose two directions share the device's bandwidth)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--modelled-tau", action="store_true", help="plan from modelled instead of measured kernel times")
     ap.add_argument("--host-tier-bw", type=float, default=0,
@@ -71,6 +140,18 @@ def main():
     t_start = time.perf_counter()
     log = lambda *a: print(f"[{time.perf_counter() - t_start:7.1f}s]", *a, file=sys.stderr, flush=True)
     bw = int(args.bw if args.bw >= 0 else cfg.get("slow_tier_bw", 25e9))
+    file_probe = None
+    shared = args.shared_channel == "yes" or (args.shared_channel == "auto" and args.slow_tier == "file")
+    if args.slow_tier == "file":
+        # the file system sets the pace: plan with what it delivers to four concurrent direct-I/O streams
+        file_probe = probe_file_bw(args.file + ".probe")
+        if args.bw <= 0:
+            both = file_probe["duplex_write_Bps"] + file_probe["duplex_read_Bps"]
+            bw = int(min(both, file_probe["write_Bps"], file_probe["read_Bps"])) if shared else \
+                int(min(file_probe["duplex_write_Bps"], file_probe["duplex_read_Bps"]))
+        log(f"file tier probe: write {file_probe['write_Bps'] / 1e9:.2f} GB/s, read {file_probe['read_Bps'] / 1e9:.2f} GB/s alone; "
+            f"{file_probe['duplex_write_Bps'] / 1e9:.2f} + {file_probe['duplex_read_Bps'] / 1e9:.2f} GB/s together; "
+            f"direct I/O {file_probe['direct']}; planning with {bw / 1e9:.2f} GB/s {'shared by both directions' if shared else 'per direction'}")
     S = cfg["B"] * cfg["T"]
     plist = tio.tio_param_list(cfg)
     n_params = sum(r * c for _, r, c in plist)
@@ -99,14 +180,19 @@ def main():
     cap = int(cfg["cap_bytes"]) if "cap_bytes" in cfg else int((base_peak or peak) * cfg["cap_frac"]) // 256 * 256
     up = tio.tio_build_plan(lt, ll, 2**62, 0)
     upe = up.export()
-    prelim = tio.tio_build_plan(lt, ll, cap, bw, min_bytes=args.min_bytes).export()
+    prelim = tio.tio_build_plan(lt, ll, cap, bw, duplex=not shared, min_bytes=args.min_bytes).export()
     host_bytes = int(max(upe["host_needed"], prelim["host_needed"] * 1.15)) + (1 << 20)
     arena_bytes = max(upe["arena_needed"], cap)
     log(f"{args.workload}: {n_params / 1e9:.3f} B parameters, uncapped peak {peak / 1e9:.2f} GB, cap {cap / 1e9:.2f} GB, "
         f"slow-tier pool {host_bytes / 1e9:.2f} GB at {bw / 1e9:.1f} GB/s")
     tier = args.slow_tier if args.slow_tier != "auto" else ("host" if host_bytes <= 28 * 10**9 else "device")
     arena = torch.empty(arena_bytes + 8192, dtype=torch.uint8, device="cuda:0")
-    if tier == "host":
+    file_kw = {}
+    if tier == "file":
+        host = None
+        host_bytes = int(host_bytes * 1.05) + (64 << 20)          # every range of the file is padded to 4 KiB
+        file_kw = dict(slow_tier_file=args.file, staging_bytes=args.staging_mb << 20, file_chunk_bytes=args.chunk_mb << 20)
+    elif tier == "host":
         host = torch.empty(host_bytes, dtype=torch.uint8, pin_memory=True)
     else:
         log("slow tier placed in device memory outside the arena (the box cannot pin a pool of this size)")
@@ -114,7 +200,7 @@ def main():
     log("buffers allocated")
 
     # ---- profile on the uncapped layout, measure the ideal
-    ctx = tio.tio_ctx_create(cfg, upe["arena_needed"], host_bytes, 0, arena=arena, host=host)
+    ctx = tio.tio_ctx_create(cfg, upe["arena_needed"], host_bytes, 0, arena=arena, host=host, **file_kw)
     load_params(ctx)
     log("parameters loaded; profiling on the uncapped layout")
     measured = ctx.tio_profile_iteration(tok, lab, tio.PROFILE_MEASURED)
@@ -135,12 +221,14 @@ def main():
     if not args.modelled_tau:
         lt.set_tau(tau)
     tp0 = time.perf_counter()
-    plan = tio.tio_build_plan(lt, ll, cap, bw, min_bytes=args.min_bytes, host_bw=int(args.host_tier_bw),
+    plan = tio.tio_build_plan(lt, ll, cap, bw, duplex=not shared, min_bytes=args.min_bytes, host_bw=int(args.host_tier_bw),
                               host_budget=int(args.host_budget))
     plan_s = time.perf_counter() - tp0
     pe = plan.export()
     log('ideal ms', ideal_s * 1e3, 'plan: entries', len(pe['entries']), 'moved GB', pe['bytes_per_direction'] / 1e9, 'planner s', plan_s)
-    if pe["host_needed"] + (1 << 20) > host_bytes:
+    if tier == "file":
+        host_bytes = max(host_bytes, int(pe["host_needed"] * 1.05) + (64 << 20))
+    elif pe["host_needed"] + (1 << 20) > host_bytes:
         host = None
         host_bytes = pe["host_needed"] + (1 << 20)
         host = torch.empty(host_bytes, dtype=torch.uint8, pin_memory=True) if tier == "host" else \
@@ -149,7 +237,7 @@ def main():
     # ---- capped run: the context sees only `cap` bytes of the arena
     ctx = tio.tio_ctx_create(cfg, cap, host_bytes, bw, arena=arena, host=host,
                              host_tier_bytes=pe["host_tier_needed"] + 4096 if pe["host_tier_needed"] else 0,
-                             host_tier_bw=int(args.host_tier_bw))
+                             host_tier_bw=int(args.host_tier_bw), **file_kw)
     load_params(ctx)
     first = ctx.tio_train_step(tok, lab, plan)
     # at initialisation the normalised hidden state has unit entries and the head weights are N(0, 0.02^2):
@@ -175,7 +263,10 @@ def main():
         loss = st["loss"]
     torch.cuda.synchronize()
     step_s = (time.perf_counter() - t0) / args.steps
+    file_info = ctx.tio_file_tier_info() if tier == "file" else None
     ctx.close()
+    if tier == "file" and os.path.exists(args.file):
+        os.remove(args.file)
     ktimes /= args.steps
 
     gemm = np.isin(ops, GEMM_OPS)
@@ -187,7 +278,7 @@ def main():
     gemm_tflops = gemm_flops / gemm_ns / 1e3
     attn_tflops = flops[attn].sum() / ktimes[attn].sum() / 1e3
     comp_s = ktimes.sum() / 1e9
-    mig_bound_s = (pe["bytes_per_direction"] / bw) if bw else 0.0
+    mig_bound_s = (pe["bytes_per_direction"] * (2 if shared else 1) / bw) if bw else 0.0
     bound_s = max(ideal_s, mig_bound_s)
 
     out = {
@@ -196,10 +287,12 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": cfg["precision"],
         "data": "synthetic",
         "config": {"workload": args.workload, "micro_batches": args.micro_batches, "tokens_per_step": S, "mem_cap_bytes": cap, "uncapped_peak_bytes": peak,
-                   "cap_frac_of_peak": cap / peak, "slow_tier_bw_bytes_per_s": bw, "slow_tier": "pinned host memory" if tier == "host" else "device memory outside the arena (stand-in)", "min_bytes": args.min_bytes,
+                   "cap_frac_of_peak": cap / peak, "slow_tier_bw_bytes_per_s": bw, "channels": "one shared" if shared else "one per direction", 
+                   "slow_tier": {"host": "pinned host memory", "device": "device memory outside the arena (stand-in)",
+                                 "file": "file, direct I/O through a pinned staging ring"}[tier], "min_bytes": args.min_bytes,
                    "kernel_times": "modelled" if args.modelled_tau else "measured"},
         "ideal_tokens_per_s": S / ideal_s, "ideal_ms_per_step": ideal_s * 1e3,
-        "model_predicted_ms_per_step": tio.tio_plan_simulate(lt, plan, bw)[0] / 1e6,
+        "model_predicted_ms_per_step": tio.tio_plan_simulate(lt, plan, bw, duplex=not shared)[0] / 1e6,
         "frac_of_ideal": ideal_s / step_s,
         "migration_bound_ms": mig_bound_s * 1e3, "frac_of_min_ideal_migration_bound": bound_s / step_s,
         "plan": {"entries": len(pe["entries"]), "greedy_pairs": pe["n_greedy"], "urgent_pairs": pe["n_forced"],
@@ -220,6 +313,12 @@ def main():
                      "flops_per_step": gemm_flops},
     }
 
+    if tier == "file":
+        out["file_tier"] = {"path": args.file, "direct_io": bool(file_info["direct_io"]), "file_bytes": file_info["file_bytes"],
+                            "probe_write_GBps": file_probe["write_Bps"] / 1e9, "probe_read_GBps": file_probe["read_Bps"] / 1e9,
+                            "probe_duplex_write_GBps": file_probe["duplex_write_Bps"] / 1e9,
+                            "probe_duplex_read_GBps": file_probe["duplex_read_Bps"] / 1e9,
+                            "staging_bytes": args.staging_mb << 20, "chunk_bytes": args.chunk_mb << 20}
     log('capped ms/step', step_s * 1e3, 'loss', loss)
     if not args.no_cpu_baseline:
         from oracle import model as om
