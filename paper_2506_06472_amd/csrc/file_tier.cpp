@@ -241,6 +241,30 @@ void FileTier::wait_prefetch_recorded(int pair, uint64_t seq) {
     cv_.wait(lk, [&] { return !error_.empty() || pre_recorded_[pair] >= seq; });
     if (!error_.empty()) throw FileTierError{error_};
 }
+void FileTier::wait_offload_landed(int pair, uint64_t seq) {
+    std::unique_lock<std::mutex> lk(mu_);
+    cv_.wait(lk, [&] { return !error_.empty() || off_landed_[pair] >= seq; });
+    if (!error_.empty()) throw FileTierError{error_};
+}
+void FileTier::wait_offload_written(int pair, uint64_t seq) {
+    std::unique_lock<std::mutex> lk(mu_);
+    cv_.wait(lk, [&] { return !error_.empty() || off_written_[pair] >= seq; });
+    if (!error_.empty()) throw FileTierError{error_};
+}
+// a dependency of a prefetch, on this engine (waited for under the lock) or on another one
+void FileTier::wait_dep(const Dep &d, bool written, std::unique_lock<std::mutex> &lk) {
+    if (!d.seq) return;
+    if (d.eng == this || d.eng == nullptr) {
+        const std::vector<uint64_t> &tab = written ? off_written_ : off_landed_;
+        cv_.wait(lk, [&] { return stop_ || !error_.empty() || tab[d.pair] >= d.seq; });
+        return;
+    }
+    lk.unlock();
+    try {
+        if (written) d.eng->wait_offload_written(d.pair, d.seq); else d.eng->wait_offload_landed(d.pair, d.seq);
+    } catch (...) { lk.lock(); throw; }
+    lk.lock();
+}
 void FileTier::wait_consumed(int dir, uint64_t seq) {
     std::unique_lock<std::mutex> lk(mu_);
     cv_.wait(lk, [&] { return !error_.empty() || dir_[dir].consumed >= seq; });
@@ -356,10 +380,8 @@ void FileTier::prefetch_reader(int) {
             if (stop_ || !error_.empty()) return;
             r = d.queue.front();
             d.queue.pop_front();
-            if (r->written.seq) {                // the tensor's own offload must be in the file before it is read back
-                cv_.wait(lk, [&] { return stop_ || !error_.empty() || off_written_[r->written.pair] >= r->written.seq; });
-                if (stop_ || !error_.empty()) return;
-            }
+            wait_dep(r->written, true, lk);      // the tensor's own offload must be in the file before it is read back
+            if (stop_ || !error_.empty()) return;
         }
         for (uint64_t off = 0; off < r->bytes; off += chunk_) {
             const uint64_t n = std::min(chunk_, r->bytes - off);
@@ -405,7 +427,7 @@ void FileTier::prefetch_issuer(int) {
             d.dma.pop_front();
             if (j.first) {                       // the destination ranges must have been vacated
                 for (const Dep &w : j.req->landed) {
-                    cv_.wait(lk, [&] { return stop_ || !error_.empty() || off_landed_[w.pair] >= w.seq; });
+                    wait_dep(w, false, lk);
                     if (stop_ || !error_.empty()) return;
                 }
             }

@@ -13,6 +13,8 @@
 #pragma once
 #include <hip/hip_runtime_api.h>
 
+#include "migration_engine.h"
+
 #include <condition_variable>
 #include <cstdint>
 #include <deque>
@@ -24,23 +26,23 @@
 
 namespace tio {
 
-struct FileTierError { std::string msg; };
+using FileTierError = EngineError;
 
-class FileTier {
+class FileTier : public MigrationEngine {
    public:
     static constexpr uint64_t kAlign = 4096;     // direct I/O: file offsets, lengths and buffers
 
     // staging: pinned host memory, 4096-byte aligned, split evenly between the two directions
     FileTier(const char *path, void *staging, uint64_t staging_bytes, uint64_t chunk_bytes, hipStream_t d2h,
              hipStream_t h2d, int n_pairs_hint);
-    ~FileTier();
+    ~FileTier() override;
     FileTier(const FileTier &) = delete;
     FileTier &operator=(const FileTier &) = delete;
 
     bool direct() const { return direct_; }
     uint64_t file_bytes() const { return file_bytes_; }
     void resize(uint64_t bytes);                  // grows the file to at least `bytes`
-    void set_pairs(int n_pairs);                  // sequence tables for a newly installed plan (engine idle)
+    void set_pairs(int n_pairs) override;
 
     // ---- synchronous set-up path (the engine must be idle: call drain() first) ----
     void write_host(uint64_t file_off, const void *src, uint64_t bytes);
@@ -49,26 +51,19 @@ class FileTier {
     void from_device(uint64_t file_off, const void *dev, uint64_t bytes);
     void to_device(uint64_t file_off, void *dev, uint64_t bytes);
 
-    // ---- asynchronous migration path ----
-    struct Dep { int pair; uint64_t seq; };
-    // `after`: event recorded by the caller on the compute stream (the copy may not start before it);
-    // `done`: recorded on the direction's stream after the request's last DMA copy; t0/t1 optional
-    // timing events recorded around the request's copies.  Returns the request's sequence number.
-    uint64_t submit_offload(int pair, hipEvent_t after, const void *dev, uint64_t file_off, uint64_t bytes,
-                            hipEvent_t done, hipEvent_t t0, hipEvent_t t1);
-    // written: offload that must be in the file before the read starts (seq 0 = none);
-    // landed: offloads of this tier whose DMA copies must have finished (their arena ranges are the destination);
-    // after_more: further events, already recorded by the caller, that the copies must wait for
-    uint64_t submit_prefetch(int pair, hipEvent_t after, void *dev, uint64_t file_off, uint64_t bytes, Dep written,
+    // ---- asynchronous migration path (MigrationEngine); `where` is a 4096-byte aligned file offset ----
+    uint64_t submit_offload(int pair, hipEvent_t after, const void *dev, uint64_t where, uint64_t bytes, hipEvent_t done,
+                            hipEvent_t t0, hipEvent_t t1) override;
+    uint64_t submit_prefetch(int pair, hipEvent_t after, void *dev, uint64_t where, uint64_t bytes, Dep written,
                              std::vector<Dep> landed, std::vector<hipEvent_t> after_more, hipEvent_t done, hipEvent_t t0,
-                             hipEvent_t t1);
-    // block until `done` of that request has been recorded (it can then be waited on by a stream)
-    void wait_offload_recorded(int pair, uint64_t seq);
-    void wait_prefetch_recorded(int pair, uint64_t seq);
-    // block until the engine has taken over the `after` event of that request (the caller may re-record it)
-    void wait_consumed(int dir, uint64_t seq);
-    void drain();                                 // every submitted request has completed, file I/O included
-    void check();                                 // throws FileTierError if any thread met an error
+                             hipEvent_t t1) override;
+    void wait_offload_recorded(int pair, uint64_t seq) override;
+    void wait_prefetch_recorded(int pair, uint64_t seq) override;
+    void wait_offload_landed(int pair, uint64_t seq) override;
+    void wait_offload_written(int pair, uint64_t seq) override;
+    void wait_consumed(int dir, uint64_t seq) override;
+    void drain() override;                        // every submitted request has completed, file I/O included
+    void check() override;
     uint64_t bytes_written() const { return bytes_written_; }
     uint64_t bytes_read() const { return bytes_read_; }
 
@@ -86,7 +81,7 @@ class FileTier {
         hipEvent_t after = nullptr, done = nullptr, t0 = nullptr, t1 = nullptr;
         uint8_t *dev = nullptr;
         uint64_t file_off = 0, bytes = 0;
-        Dep written{-1, 0};
+        Dep written{nullptr, -1, 0};
         std::vector<Dep> landed;
         std::vector<hipEvent_t> after_more;
         uint64_t chunks_left = 0;   // offload: chunks not yet in the file
@@ -116,6 +111,7 @@ class FileTier {
     void chunk_io(bool write, uint8_t *staging, uint64_t n, uint64_t file_off, uint8_t *bounce);
     int acquire(Dir &d, std::unique_lock<std::mutex> &lk, bool prefetch);
     void fail_locked(const std::string &msg);
+    void wait_dep(const Dep &d, bool written, std::unique_lock<std::mutex> &lk);
     void io_all(bool write, uint8_t *buf, uint64_t n, uint64_t file_off);
     void guard(const char *what, hipError_t e);
 

@@ -60,13 +60,6 @@ void posemb_bwd(hipStream_t s, int dtype, const void *dx, void *dwpe, int64_t B,
 void adamw(hipStream_t s, int dtype, const void *g, void *w, float *master, float *m, float *v, int64_t n,
            float lr, float beta1, float beta2, float eps, float wd, float bc1, float bc2);
 void fill_u32(hipStream_t s, void *p, uint32_t value, int64_t n_words);
-// slow-tier transfer at a fixed rate: copies `bytes` (multiple of 16) between device-visible buffers so
-// that the launch lasts `ticks` of the constant-rate wall clock (bounded by the caller, always terminates)
-void paced_copy(hipStream_t s, void *dst, const void *src, int64_t bytes, unsigned long long ticks);
-// pacing of DMA transfers through a per-stream virtual clock in device memory (see kernels_elem.hip);
-// ticks of the constant-rate wall clock, every wait bounded by `limit`
-void channel_open(hipStream_t s, unsigned long long *clock, unsigned long long limit);
-void channel_wait(hipStream_t s, unsigned long long *clock, unsigned long long ticks, unsigned long long limit);
 // fp32 <-> storage conversion helpers used when parameters are loaded and read back
 void convert_from_f32(hipStream_t s, int dtype, const float *src, void *dst, int64_t n);
 

@@ -615,62 +615,6 @@ __global__ void __launch_bounds__(TPB) convert_k(const float *__restrict__ src, 
     if (i < n) dst[i] = from_f32<T>(src[i]);
 }
 
-// Copy at a fixed rate between the arena and the pinned slow-tier pool (both mapped into the GPU's
-// address space): the range is cut into one slice per workgroup, each slice moves in 64 KiB chunks,
-// and after every chunk the workgroup sleeps until its share of `ticks` (constant-rate wall clock,
-// bounded by the host) has passed, so the whole transfer takes bytes / bandwidth and the link sees a
-// steady stream.  One launch per migration: no engine switches on the copy stream.
-// few workgroups: a resident copy workgroup, even asleep, keeps a compute workgroup that needs the whole
-// register file of a CU (the large GEMM tiles) off that CU
-constexpr int PACED_WG = 8;
-__global__ void __launch_bounds__(TPB) paced_copy_k(uint4 *__restrict__ dst, const uint4 *__restrict__ src, int64_t n16,
-                                                    unsigned long long ticks) {
-    const unsigned long long t0 = wall_clock64();
-    const int64_t per = (n16 + gridDim.x - 1) / gridDim.x;
-    const int64_t beg = (int64_t)blockIdx.x * per;
-    const int64_t end = beg + per < n16 ? beg + per : n16;
-    constexpr int64_t CHUNK = TPB * 16;                  // uint4 elements per chunk (64 KiB)
-    for (int64_t c0 = beg; c0 < end; c0 += CHUNK) {
-#pragma unroll 4
-        for (int u = 0; u < 16; ++u) {
-            const int64_t i = c0 + (int64_t)u * TPB + threadIdx.x;
-            if (i < end) dst[i] = src[i];
-        }
-        const int64_t done = (c0 + CHUNK < end ? c0 + CHUNK : end) - beg;
-        if (threadIdx.x == 0) {
-            const unsigned long long due = (unsigned long long)((double)ticks * (double)done / (double)(end - beg));
-            while (wall_clock64() - t0 < due) __builtin_amdgcn_s_sleep(16);
-        }
-        __syncthreads();
-    }
-}
-
-// Pacing of DMA transfers: a copy stream carries a virtual clock in device memory (the time at which the
-// slow-tier channel of that stream becomes free).  channel_open_k, first on the stream for a migration,
-// moves it up to the present if the channel has been idle; channel_wait_k, after each chunk has been
-// copied, advances it by the chunk's transfer time at the emulated bandwidth and holds the stream until
-// that time.  A backlogged stream therefore moves bytes at exactly the emulated rate, whatever the copy
-// engine's own speed and the launch overheads in between.  `limit` bounds every wait.
-__global__ void channel_open_k(unsigned long long *clock, unsigned long long limit) {
-    if (threadIdx.x == 0) {
-        const unsigned long long now = wall_clock64();
-        const unsigned long long v = *clock;
-        if (v < now || v - now > limit) *clock = now;
-    }
-}
-__global__ void channel_wait_k(unsigned long long *clock, unsigned long long ticks, unsigned long long limit) {
-    if (threadIdx.x == 0) {
-        const unsigned long long start = wall_clock64();
-        const unsigned long long due = *clock + ticks;
-        *clock = due;
-        unsigned long long now = start;
-        while (now < due && now - start < limit) {
-            __builtin_amdgcn_s_sleep(16);
-            now = wall_clock64();
-        }
-    }
-}
-
 }  // namespace
 
 #define TIO_DISPATCH(dtype, ...)                                  \
@@ -809,21 +753,6 @@ void fill_u32(hipStream_t s, void *p, uint32_t value, int64_t n_words) {
 
 void convert_from_f32(hipStream_t s, int dtype, const float *src, void *dst, int64_t n) {
     TIO_DISPATCH(dtype, { convert_k<T><<<blocks_for(n, TPB), TPB, 0, s>>>(src, (T *)dst, n); });
-}
-
-void paced_copy(hipStream_t s, void *dst, const void *src, int64_t bytes, unsigned long long ticks) {
-    const int64_t n16 = bytes / 16;
-    int wg = (int)((n16 + TPB * 16 - 1) / (TPB * 16));
-    if (wg > PACED_WG) wg = PACED_WG;
-    if (wg < 1) wg = 1;
-    paced_copy_k<<<wg, TPB, 0, s>>>((uint4 *)dst, (const uint4 *)src, n16, ticks);
-}
-
-void channel_open(hipStream_t s, unsigned long long *clock, unsigned long long limit) {
-    channel_open_k<<<1, 64, 0, s>>>(clock, limit);
-}
-void channel_wait(hipStream_t s, unsigned long long *clock, unsigned long long ticks, unsigned long long limit) {
-    channel_wait_k<<<1, 64, 0, s>>>(clock, ticks, limit);
 }
 
 }  // namespace k

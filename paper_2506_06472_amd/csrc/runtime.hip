@@ -6,12 +6,10 @@
 // empty address ranges its outputs reuse), then launches kernel k.  A late migration therefore
 // stalls the kernel that needs it and nothing else, which is the paper's "kernel stall".  Urgent
 // entries come first within each direction at every trigger point.  The slow tier is pinned host
-// memory (or a device buffer outside the arena); its bandwidth is enforced per copy stream: DMA copies in
-// chunks, each followed by a one-wavefront kernel that holds the stream until the emulated channel would
-// have delivered the chunk (host pool), or a copy kernel that moves each tensor at the stated rate (device
-// pool); unthrottled runs use plain hipMemcpyAsync.  With a file as the slow tier the two directions are
-// run by the threads of the file tier (file_tier.h): the host then blocks, before kernel k, until the
-// completion events kernel k depends on have been recorded by those threads.
+// memory (or a device buffer outside the arena, or a file).  Unthrottled memory tiers are plain hipMemcpyAsync
+// on the tier's two streams.  A tier with an emulated bandwidth (paced_pool.h) or in a file (file_tier.h) is
+// run by threads of its own: the host then blocks, before kernel k, until the completion events kernel k
+// depends on have been recorded by those threads.
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
@@ -28,6 +26,7 @@
 #include "file_tier.h"
 #include "handles.h"
 #include "kernels.h"
+#include "paced_pool.h"
 
 using namespace tio;
 
@@ -69,11 +68,9 @@ struct tio_ctx {
     uint8_t *arena = nullptr, *host = nullptr, *host1 = nullptr;
     uint64_t bw1 = 0;                                    // bandwidth enforced on the host-memory tier
     uint64_t arena_usable = 0;
-    unsigned long long *pace_slots = nullptr;            // device: [0] d2h stamp, [1] h2d stamp
     std::vector<uint64_t> home;                          // host offset of every persistent tensor
     uint64_t home_bytes = 0;
     uint64_t bw = 0;
-    double clock_hz = 1e8;
     bool pool_dev = false;                               // the slow-tier pool is device memory (stand-in when the host cannot pin enough)
 
     Plan plan;                                           // installed plan (copy)
@@ -87,12 +84,6 @@ struct tio_ctx {
     std::vector<hipEvent_t> ev_kernel, ev_off, ev_pre, ev_t0, ev_t1;
     std::vector<uint8_t> rec_kernel, rec_off, rec_pre;
     int step = 0;
-    // Emulated slow-tier bandwidth with a pinned host pool: the copies go through the DMA engines and a
-    // per-stream virtual clock paces them (copy kernels reading or writing host memory were measured to
-    // slow every concurrent compute kernel by about half).  With the pool in device memory the paced
-    // copy kernel is used.
-    bool dma_pacing = false;
-    unsigned long long *chan_clock = nullptr;            // two device words: offload stream, prefetch stream
     float *loss_pinned = nullptr;                         // 4 KiB of pinned host memory owned by the context
     std::vector<std::vector<float>> grads;
     std::vector<int64_t> last_times;                      // per-kernel ns of the last step run with timing
@@ -110,7 +101,9 @@ struct tio_ctx {
     std::vector<hipEvent_t> ev_req;                       // per plan entry: compute progress at submission
     std::vector<uint64_t> req_seq;                        // per plan entry: sequence number of its last request
     std::vector<uint64_t> off_seq, pre_seq;               // per pair: sequence number of its last offload / prefetch request
-    std::vector<uint64_t> ev_off_user;                    // per pair: last file prefetch that waits for ev_off[pair] of another tier
+    std::vector<MigrationEngine::Dep> ev_off_user;        // per pair: last engine prefetch that waits for ev_off[pair], recorded by this thread
+    // memory tiers with an emulated bandwidth: slow tier, host-memory tier
+    std::unique_ptr<PacedPool> pp0, pp1;
 };
 
 namespace {
@@ -125,8 +118,18 @@ void make_events(std::vector<hipEvent_t> &v, size_t n, bool timing) {
     for (size_t i = 0; i < n; ++i) HIPCHK(hipEventCreateWithFlags(&v[i], timing ? hipEventDefault : hipEventDisableTiming));
 }
 
+// the engine that moves the pairs of a tier, or nullptr when they are plain copies on the tier's streams
+MigrationEngine *engine_of(tio_ctx *c, int tier) {
+    if (tier == 1) return c->pp1 && c->bw1 ? c->pp1.get() : nullptr;
+    if (c->ft) return c->ft.get();
+    return c->pp0 && c->bw ? c->pp0.get() : nullptr;
+}
+
 void sync_all(tio_ctx *c) {
+    // an engine's request may depend on another engine's, never on work that is not yet submitted
     if (c->ft) c->ft->drain();
+    if (c->pp0) c->pp0->drain();
+    if (c->pp1) c->pp1->drain();
     HIPCHK(hipStreamSynchronize(c->sc));
     HIPCHK(hipStreamSynchronize(c->sd));
     HIPCHK(hipStreamSynchronize(c->sh));
@@ -199,6 +202,8 @@ void install_plan(tio_ctx *c, const Plan &p) {
         c->ft->set_pairs((int)p.pairs.size());
         c->pair_file = pair_file;
     }
+    if (c->pp0) c->pp0->set_pairs((int)p.pairs.size());
+    if (c->pp1) c->pp1->set_pairs((int)p.pairs.size());
     c->plan = p;
     c->installed = true;
     const int np = c->prog.n_persistent;
@@ -238,13 +243,11 @@ void install_plan(tio_ctx *c, const Plan &p) {
     c->rec_kernel.assign(N, 0);
     c->rec_off.assign(p.pairs.size(), 0);
     c->rec_pre.assign(p.pairs.size(), 0);
-    if (c->ft) {
-        make_events(c->ev_req, p.entries.size(), false);
-        c->req_seq.assign(p.entries.size(), 0);
-        c->off_seq.assign(p.pairs.size(), 0);
-        c->pre_seq.assign(p.pairs.size(), 0);
-        c->ev_off_user.assign(p.pairs.size(), 0);
-    }
+    make_events(c->ev_req, p.entries.size(), false);
+    c->req_seq.assign(p.entries.size(), 0);
+    c->off_seq.assign(p.pairs.size(), 0);
+    c->pre_seq.assign(p.pairs.size(), 0);
+    c->ev_off_user.assign(p.pairs.size(), MigrationEngine::Dep{nullptr, -1, 0});
     c->params_dirty = false;
 }
 
@@ -297,28 +300,6 @@ void launch(tio_ctx *c, int k) {
     default: throw PlanError{TIO_ERR_INVALID_ARG, "unknown operator"};
     }
     HIPCHK(hipGetLastError());
-}
-
-void paced_copy(tio_ctx *c, hipStream_t s, int slot, void *dst, const void *src, uint64_t bytes, hipMemcpyKind kind,
-                uint64_t rate) {
-    if (rate && (c->dma_pacing || slot >= 2)) {          // slots 2, 3: host-memory tier, always pinned host memory
-        // the DMA engine moves the bytes in chunks; after each chunk the stream is held until the emulated
-        // channel would have delivered it
-        const unsigned long long limit = (unsigned long long)(30.0 * c->clock_hz);
-        k::channel_open(s, c->chan_clock + slot, limit);
-        constexpr uint64_t CHUNK = (uint64_t)8 << 20;
-        for (uint64_t off = 0; off < bytes; off += CHUNK) {
-            const uint64_t n = std::min(CHUNK, bytes - off);
-            HIPCHK(hipMemcpyAsync((uint8_t *)dst + off, (const uint8_t *)src + off, n, kind, s));
-            k::channel_wait(s, c->chan_clock + slot, (unsigned long long)((double)n / (double)rate * c->clock_hz), limit);
-        }
-    } else if (rate) {
-        double ticks = (double)bytes / (double)rate * c->clock_hz;
-        ticks = std::min(ticks, 30.0 * c->clock_hz);         // bounded wait
-        k::paced_copy(s, dst, src, (int64_t)bytes, (unsigned long long)ticks);
-    } else {
-        HIPCHK(hipMemcpyAsync(dst, src, bytes, (c->pool_dev && slot < 2) ? hipMemcpyDefault : kind, s));
-    }
 }
 
 void capture_grad(tio_ctx *c, int k) {
@@ -375,16 +356,18 @@ void run_step(tio_ctx *c, const int32_t *tokens, const int32_t *labels, bool cap
             const tio_plan_entry &e = p.entries[ei];
             const Pair &pr = p.pairs[e.pair];
             const bool persistent = e.tensor < c->prog.n_persistent;
-            // destination of this pair: the slow tier's pool and streams, or the host-memory tier's
+            // destination of this pair: the slow tier's pool (or file) and streams, or the host-memory tier's
             const bool t1 = pr.tier == 1;
             hipStream_t so = t1 ? c->sd1 : c->sd, sp = t1 ? c->sh1 : c->sh;
             uint8_t *pool = t1 ? c->host1 : c->host;
-            const uint64_t rate = t1 ? c->bw1 : c->bw;
-            const bool in_file = c->ft && !t1;           // this pair moves through the file tier's threads
-            auto progress_event = [&]() {                // compute progress at this trigger point, for the file tier
-                if (c->req_seq[ei]) c->ft->wait_consumed(e.kind == TIO_OFFLOAD ? 0 : 1, c->req_seq[ei]);
+            MigrationEngine *eng = engine_of(c, pr.tier);     // nullptr: plain copies on the tier's streams
+            auto progress_event = [&]() {                     // compute progress at this trigger point, for an engine
+                if (c->req_seq[ei]) eng->wait_consumed(e.kind == TIO_OFFLOAD ? 0 : 1, c->req_seq[ei]);
                 HIPCHK(hipEventRecord(c->ev_req[ei], c->sc));
                 return c->ev_req[ei];
+            };
+            auto place = [&]() -> uint64_t {                  // the pair's place on its tier, as its engine addresses it
+                return (c->ft && !t1) ? c->pair_file[e.pair] : (uint64_t)(uintptr_t)(pool + pr.host_offset);
             };
             if (e.kind == TIO_OFFLOAD) {
                 // first iteration after a plan is installed: an offload that belongs to the end of the
@@ -392,18 +375,20 @@ void run_step(tio_ctx *c, const int32_t *tokens, const int32_t *labels, bool cap
                 // slow-tier home slot already holds the latest version
                 if (persistent && !c->on_dev[e.tensor]) continue;
                 const Alloc &al = p.allocs[pr.alloc_before];
-                if (in_file) {
-                    const uint64_t seq = c->ft->submit_offload(e.pair, progress_event(), c->arena + al.address, c->pair_file[e.pair],
-                                                               pr.bytes, c->ev_off[e.pair], tl ? c->ev_c0[ei] : nullptr,
-                                                               tl ? c->ev_c1[ei] : nullptr);
+                if (eng) {
+                    const uint64_t seq = eng->submit_offload(e.pair, progress_event(), c->arena + al.address, place(), pr.bytes,
+                                                             c->ev_off[e.pair], tl ? c->ev_c0[ei] : nullptr, tl ? c->ev_c1[ei] : nullptr);
                     c->req_seq[ei] = c->off_seq[e.pair] = seq;
                     if (tl) issued[ei] = 1;
                 } else {
-                    // a prefetch of the file tier may still have to take over this pair's previous event
-                    if (c->ft && c->ev_off_user[e.pair]) { c->ft->wait_consumed(1, c->ev_off_user[e.pair]); c->ev_off_user[e.pair] = 0; }
+                    // a prefetch run by an engine may still have to take over this pair's previous event
+                    if (c->ev_off_user[e.pair].eng) {
+                        c->ev_off_user[e.pair].eng->wait_consumed(1, c->ev_off_user[e.pair].seq);
+                        c->ev_off_user[e.pair] = {nullptr, -1, 0};
+                    }
                     if (c->rec_kernel[prev]) HIPCHK(hipStreamWaitEvent(so, c->ev_kernel[prev], 0));
                     if (tl) { HIPCHK(hipEventRecord(c->ev_c0[ei], so)); issued[ei] = 1; }
-                    paced_copy(c, so, t1 ? 2 : 0, pool + pr.host_offset, c->arena + al.address, pr.bytes, hipMemcpyDeviceToHost, rate);
+                    HIPCHK(hipMemcpyAsync(pool + pr.host_offset, c->arena + al.address, pr.bytes, hipMemcpyDefault, so));
                     if (tl) HIPCHK(hipEventRecord(c->ev_c1[ei], so));
                     HIPCHK(hipEventRecord(c->ev_off[e.pair], so));
                 }
@@ -419,41 +404,44 @@ void run_step(tio_ctx *c, const int32_t *tokens, const int32_t *labels, bool cap
                 // a persistent tensor whose offload to the host-memory tier belongs to an iteration that never
                 // ran (first iteration after the plan was installed) is still in its slow-tier home slot
                 const bool from_home = t1 && persistent && !c->in_host1[e.tensor];
-                if (in_file) {
-                    FileTier::Dep written{e.pair, c->rec_off[e.pair] ? c->off_seq[e.pair] : 0};
-                    std::vector<FileTier::Dep> landed;
-                    std::vector<hipEvent_t> more;
-                    for (int q : al.wait_pairs) {
-                        if (!c->rec_off[q]) continue;
-                        if (p.pairs[q].tier == 0) landed.push_back({q, c->off_seq[q]});
-                        else more.push_back(c->ev_off[q]);       // recorded above by this thread, on the other tier's stream
-                    }
-                    const uint64_t seq = c->ft->submit_prefetch(e.pair, progress_event(), c->arena + al.address, c->pair_file[e.pair],
-                                                                pr.bytes, written, landed, more, c->ev_pre[e.pair],
-                                                                tl ? c->ev_c0[ei] : nullptr, tl ? c->ev_c1[ei] : nullptr);
-                    c->req_seq[ei] = c->pre_seq[e.pair] = seq;
-                    for (int q : al.wait_pairs) if (c->rec_off[q] && p.pairs[q].tier != 0) c->ev_off_user[q] = seq;
-                    if (tl) issued[ei] = 1;
-                } else if (c->ft && from_home) {
-                    // rare (first iteration under a new plan): the source is the tensor's home range in the file.
-                    // Everything issued so far is allowed to finish, then the tensor is read synchronously.
+                if (from_home && c->ft) {
+                    // rare: that home is a range of the file.  Everything issued so far is allowed to finish,
+                    // then the tensor is read synchronously.
                     sync_all(c);
                     c->ft->to_device(c->home_file[e.tensor], c->arena + al.address, pr.bytes);
                     HIPCHK(hipEventRecord(c->ev_pre[e.pair], sp));
+                    c->pre_seq[e.pair] = 0;
+                } else if (eng) {
+                    MigrationEngine::Dep written{eng, e.pair, c->rec_off[e.pair] ? c->off_seq[e.pair] : 0};
+                    std::vector<MigrationEngine::Dep> landed;
+                    std::vector<hipEvent_t> more;
+                    for (int q : al.wait_pairs) {
+                        if (!c->rec_off[q]) continue;
+                        if (MigrationEngine *eq = engine_of(c, p.pairs[q].tier)) landed.push_back({eq, q, c->off_seq[q]});
+                        else more.push_back(c->ev_off[q]);   // recorded above by this thread, on the other tier's stream
+                    }
+                    const uint64_t where = from_home ? (uint64_t)(uintptr_t)(c->host + c->home[e.tensor]) : place();
+                    const uint64_t seq = eng->submit_prefetch(e.pair, progress_event(), c->arena + al.address, where, pr.bytes,
+                                                              written, landed, more, c->ev_pre[e.pair],
+                                                              tl ? c->ev_c0[ei] : nullptr, tl ? c->ev_c1[ei] : nullptr);
+                    c->req_seq[ei] = c->pre_seq[e.pair] = seq;
+                    for (int q : al.wait_pairs)
+                        if (c->rec_off[q] && !engine_of(c, p.pairs[q].tier)) c->ev_off_user[q] = {eng, q, seq};
+                    if (tl) issued[ei] = 1;
                 } else {
                     const uint8_t *src = from_home ? c->host + c->home[e.tensor] : pool + pr.host_offset;
                     if (c->rec_kernel[prev]) HIPCHK(hipStreamWaitEvent(sp, c->ev_kernel[prev], 0));
                     if (c->rec_off[e.pair]) HIPCHK(hipStreamWaitEvent(sp, c->ev_off[e.pair], 0));
                     for (int q : al.wait_pairs) {
                         if (!c->rec_off[q]) continue;
-                        if (c->ft && p.pairs[q].tier == 0) c->ft->wait_offload_recorded(q, c->off_seq[q]);
+                        if (MigrationEngine *eq = engine_of(c, p.pairs[q].tier)) eq->wait_offload_recorded(q, c->off_seq[q]);
                         HIPCHK(hipStreamWaitEvent(sp, c->ev_off[q], 0));
                     }
                     if (tl) { HIPCHK(hipEventRecord(c->ev_c0[ei], sp)); issued[ei] = 1; }
-                    paced_copy(c, sp, t1 ? 3 : 1, c->arena + al.address, src, pr.bytes,
-                               (c->pool_dev && src != pool + pr.host_offset) ? hipMemcpyDefault : hipMemcpyHostToDevice, rate);
+                    HIPCHK(hipMemcpyAsync(c->arena + al.address, src, pr.bytes, hipMemcpyDefault, sp));
                     if (tl) HIPCHK(hipEventRecord(c->ev_c1[ei], sp));
                     HIPCHK(hipEventRecord(c->ev_pre[e.pair], sp));
+                    c->pre_seq[e.pair] = 0;
                 }
                 c->rec_pre[e.pair] = 1;
                 if (persistent) { c->on_dev[e.tensor] = 1; c->dev_addr[e.tensor] = al.address; c->in_host1[e.tensor] = 0; }
@@ -462,11 +450,11 @@ void run_step(tio_ctx *c, const int32_t *tokens, const int32_t *labels, bool cap
             ++nmig;
         }
         for (int q : p.kernel_wait_pre[k]) if (c->rec_pre[q]) {
-            if (c->ft && p.pairs[q].tier == 0 && c->pre_seq[q]) c->ft->wait_prefetch_recorded(q, c->pre_seq[q]);
+            if (c->pre_seq[q]) if (MigrationEngine *eq = engine_of(c, p.pairs[q].tier)) eq->wait_prefetch_recorded(q, c->pre_seq[q]);
             HIPCHK(hipStreamWaitEvent(c->sc, c->ev_pre[q], 0));
         }
         for (int q : p.kernel_wait_off[k]) if (c->rec_off[q]) {
-            if (c->ft && p.pairs[q].tier == 0) c->ft->wait_offload_recorded(q, c->off_seq[q]);
+            if (c->off_seq[q]) if (MigrationEngine *eq = engine_of(c, p.pairs[q].tier)) eq->wait_offload_recorded(q, c->off_seq[q]);
             HIPCHK(hipStreamWaitEvent(c->sc, c->ev_off[q], 0));
         }
         if (capture && c->prog.kernels[k].op == OP_ADAMW) capture_grad(c, k);
@@ -480,6 +468,8 @@ void run_step(tio_ctx *c, const int32_t *tokens, const int32_t *labels, bool cap
     }
     HIPCHK(hipStreamSynchronize(c->sc));
     if (c->ft) c->ft->check();
+    if (c->pp0) c->pp0->check();
+    if (c->pp1) c->pp1->check();
     const float loss = *c->loss_pinned;
     const auto w1 = std::chrono::steady_clock::now();
     c->step += 1;
@@ -531,7 +521,7 @@ void ensure_plan(tio_ctx *c, const tio_plan *plan) {
 #define TIO_RT_END                                                                                              \
     } catch (const PlanError &e) { return fail(e.code, e.msg);                                                  \
     } catch (const HipError &e) { return fail(TIO_ERR_HIP, std::string(e.what) + ": " + hipGetErrorString(e.e)); \
-    } catch (const FileTierError &e) { return fail(TIO_ERR_IO, e.msg);                                          \
+    } catch (const EngineError &e) { return fail(TIO_ERR_IO, e.msg);                                            \
     } catch (const std::exception &e) { return fail(TIO_ERR_INVALID_ARG, e.what()); }
 
 extern "C" {
@@ -557,15 +547,12 @@ int tio_ctx_create(const tio_model_cfg *cfg, const tio_runtime_cfg *rt, tio_ctx 
     c->sc = (hipStream_t)rt->compute_stream; c->sd = (hipStream_t)rt->d2h_stream; c->sh = (hipStream_t)rt->h2d_stream;
     c->arena = (uint8_t *)rt->arena; c->host = (uint8_t *)rt->host_pool;
     c->arena_usable = (rt->arena_bytes - kReservedTail) / 256 * 256;
-    c->pace_slots = (unsigned long long *)(c->arena + c->arena_usable);
     c->bw = rt->slow_tier_bw;
     c->pool_dev = rt->pool_on_device != 0;
     c->host1 = (uint8_t *)rt->host_tier_pool;
     c->sd1 = (hipStream_t)rt->host_tier_d2h_stream; c->sh1 = (hipStream_t)rt->host_tier_h2d_stream;
     c->bw1 = rt->host_tier_bw;
     if (c->host1 && ((uintptr_t)c->host1 & 255)) { delete c; return fail(TIO_ERR_INVALID_ARG, "host-memory tier pool must be 256-byte aligned"); }
-    int khz = 0;
-    if (hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, 0) == hipSuccess && khz > 0) c->clock_hz = khz * 1000.0;
     uint64_t h = 0;
     c->home.assign(c->prog.n_persistent, 0);
     for (int t = 0; t < c->prog.n_persistent; ++t) { c->home[t] = h; h += c->prog.tensors[t].bytes; }
@@ -582,20 +569,16 @@ int tio_ctx_create(const tio_model_cfg *cfg, const tio_runtime_cfg *rt, tio_ctx 
     if (h > rt->host_bytes) { delete c; return fail(TIO_ERR_OOM_HOST, "slow-tier pool smaller than the persistent tensors"); }
     c->loaded.assign(c->prog.params.size(), 0);
     if (hipHostMalloc((void **)&c->loss_pinned, 4096, hipHostMallocDefault) != hipSuccess) { delete c; return fail(TIO_ERR_HIP, "hipHostMalloc failed"); }
-    if (hipMalloc((void **)&c->chan_clock, 256) != hipSuccess || hipMemset(c->chan_clock, 0, 256) != hipSuccess) {
-        (void)hipHostFree(c->loss_pinned);
-        delete c;
-        return fail(TIO_ERR_HIP, "hipMalloc failed");
-    }
-    {
-        const char *e = getenv("TIO_PACING");             // "kernel" forces the paced copy kernel
-        c->dma_pacing = !c->pool_dev && !(e && std::string(e) == "kernel");
-    }
     if (file_tier) {
         try {
             c->ft.reset(new FileTier(rt->slow_tier_file, rt->staging, rt->staging_bytes, rt->file_chunk_bytes, c->sd, c->sh, 0));
             c->ft->resize(c->home_file_bytes);
         } catch (...) { tio_ctx_destroy(c); throw; }
+    } else {
+        try { c->pp0.reset(new PacedPool(c->sd, c->sh, c->bw)); } catch (...) { tio_ctx_destroy(c); throw; }
+    }
+    if (c->host1 && c->sd1 && c->sh1) {
+        try { c->pp1.reset(new PacedPool(c->sd1, c->sh1, c->bw1)); } catch (...) { tio_ctx_destroy(c); throw; }
     }
     *out = c;
     return TIO_OK;
@@ -604,16 +587,17 @@ int tio_ctx_create(const tio_model_cfg *cfg, const tio_runtime_cfg *rt, tio_ctx 
 
 int tio_ctx_destroy(tio_ctx *c) {
     if (!c) return TIO_OK;
-    if (c->ft) { try { c->ft->drain(); } catch (...) {} }
+    try { sync_all(c); } catch (...) {}
     (void)hipStreamSynchronize(c->sc); (void)hipStreamSynchronize(c->sd); (void)hipStreamSynchronize(c->sh);
-    c->ft.reset();                                       // joins the file tier's threads before their events go
+    c->ft.reset();                                       // joins the engines' threads before their events go
+    c->pp0.reset();
+    c->pp1.reset();
     destroy_events(c->ev_req);
     destroy_events(c->ev_kernel); destroy_events(c->ev_off); destroy_events(c->ev_pre);
     destroy_events(c->ev_t0); destroy_events(c->ev_t1);
     destroy_events(c->ev_c0); destroy_events(c->ev_c1);
     if (c->ev_step0) (void)hipEventDestroy(c->ev_step0);
     if (c->loss_pinned) (void)hipHostFree(c->loss_pinned);
-    if (c->chan_clock) (void)hipFree(c->chan_clock);
     delete c;
     return TIO_OK;
 }
@@ -725,8 +709,12 @@ int tio_file_tier_info(tio_ctx *c, tio_file_tier_stats *out) {
 
 int tio_set_slow_tier_bw(tio_ctx *c, uint64_t bw) {
     if (!c) return fail(TIO_ERR_INVALID_ARG, "null argument");
+    TIO_RT_BEGIN
+    sync_all(c);                                         // the change may move the tier between plain copies and its paced engine
     c->bw = bw;
+    if (c->pp0) c->pp0->set_bandwidth(bw);
     return TIO_OK;
+    TIO_RT_END
 }
 
 int tio_train_step(tio_ctx *c, const int32_t *tokens, const int32_t *labels, const tio_plan *plan, int32_t flags,
