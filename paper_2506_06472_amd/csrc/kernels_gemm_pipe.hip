@@ -167,7 +167,7 @@ __global__ void __launch_bounds__(WGM *WGN * 64)
     gemm_bf16_pipe_k(const uint16_t *__restrict__ A, int64_t lda, const uint16_t *__restrict__ B, int64_t ldb,
                      const uint16_t *__restrict__ bias, const uint16_t *__restrict__ resid, int64_t ldr,
                      uint16_t *__restrict__ C, int64_t ldc, int64_t M, int64_t N, int64_t K, int tiles_m, int tiles_n,
-                     uint16_t *__restrict__ rowsum, float *__restrict__ ws, int64_t k_chunk, int rowsum_acc) {
+                     uint16_t *__restrict__ rowsum, float *__restrict__ ws, int64_t k_chunk, int rowsum_acc, int xsplits) {
     constexpr int NT = WGM * WGN * 64;
     constexpr int TPR = NT / BM;           // threads that share one row of the A tile for the row sums
     static_assert(NT % BM == 0 && (TPR & (TPR - 1)) == 0 && TPR <= 64 && BK % (8 * TPR) == 0, "row-sum mapping");
@@ -178,11 +178,24 @@ __global__ void __launch_bounds__(WGM *WGN * 64)
     constexpr int TILE = OpA::LDS_ELEMS + OpB::LDS_ELEMS;
     extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
 
-    // tile order: see gemm_bf16_k (each XCD works on one contiguous eighth of the tile sequence)
+    // tile order: see gemm_bf16_k (each XCD works on one contiguous eighth of the tile sequence).  With 2, 4 or 8
+    // contraction ranges (xsplits, one-dimensional grid) an XCD owns one range and one part of the tile sequence,
+    // so that its L2 fetches only that range of the two operands.
     const int tid = threadIdx.x;
     const int total_tiles = tiles_m * tiles_n;
-    const int xcd_chunk = (total_tiles + 7) / 8;
-    const int bid = (int)(blockIdx.x % 8) * xcd_chunk + (int)(blockIdx.x / 8);
+    int split, nsplit, bid;
+    if (xsplits) {
+        const int x = (int)(blockIdx.x % 8), i = (int)(blockIdx.x / 8);
+        const int parts = 8 / xsplits, chunk = (total_tiles + parts - 1) / parts;
+        nsplit = xsplits;
+        split = x % xsplits;
+        if (i >= chunk) return;
+        bid = (x / xsplits) * chunk + i;
+    } else {
+        nsplit = (int)gridDim.y;
+        split = (int)blockIdx.y;
+        bid = (int)(blockIdx.x % 8) * ((total_tiles + 7) / 8) + (int)(blockIdx.x / 8);
+    }
     if (bid >= total_tiles) return;
     constexpr int GROUP = 8;
     const int per_group = GROUP * tiles_n;
@@ -197,7 +210,7 @@ __global__ void __launch_bounds__(WGM *WGN * 64)
     const int wm = wave / WGN, wn = wave % WGN;
     const int l32 = lane & 31, lhi = lane >> 5;
 
-    const int64_t kbeg = (int64_t)blockIdx.y * k_chunk;
+    const int64_t kbeg = (int64_t)split * k_chunk;
     const int64_t kend = (ws != nullptr && kbeg + k_chunk < K) ? kbeg + k_chunk : K;
     const int kspan = kend > kbeg ? (int)(kend - kbeg) : 0;     // a trailing split may be empty
     const int nkf = kspan / BK, rem = kspan % BK, nk = nkf + (rem ? 1 : 0);
@@ -317,7 +330,7 @@ __global__ void __launch_bounds__(WGM *WGN * 64)
         for (int o = 1; o < TPR; o <<= 1) rsum += __shfl_xor(rsum, o, 64);
         const int64_t m = m0 + tid / TPR;
         if (tid % TPR == 0 && m < M) {
-            if (ws) ws[(int64_t)gridDim.y * M * N + (int64_t)blockIdx.y * M + m] = rsum;
+            if (ws) ws[(int64_t)nsplit * M * N + (int64_t)split * M + m] = rsum;
             else rowsum[m] = (uint16_t)f32_to_bf16_bits(rsum + (rowsum_acc ? bf16_bits_to_f32(rowsum[m]) : 0.f));
         }
     }
@@ -334,7 +347,7 @@ __global__ void __launch_bounds__(WGM *WGN * 64)
                 if (n >= N) continue;
                 float v[4] = {acc[i][j][q * 4 + 0], acc[i][j][q * 4 + 1], acc[i][j][q * 4 + 2], acc[i][j][q * 4 + 3]};
                 if (ws) {          // N is a multiple of 4 in split mode
-                    *reinterpret_cast<float4 *>(ws + ((int64_t)blockIdx.y * M + m) * N + n) = make_float4(v[0], v[1], v[2], v[3]);
+                    *reinterpret_cast<float4 *>(ws + ((int64_t)split * M + m) * N + n) = make_float4(v[0], v[1], v[2], v[3]);
                     continue;
                 }
                 if (n + 4 <= N) {
@@ -377,7 +390,10 @@ bool launch_pipe(hipStream_t s, bool a_km, bool b_km, int64_t M, int64_t N, int6
     constexpr int64_t LIMIT = (int64_t)1 << 30;
     if (spanA >= LIMIT || spanB >= LIMIT) return false;
     const int tiles_m = (int)((M + BM - 1) / BM), tiles_n = (int)((N + BN - 1) / BN);
-    const dim3 grid((unsigned)(8 * ((tiles_m * tiles_n + 7) / 8)), (unsigned)(splits > 1 ? splits : 1));
+    const int tiles = tiles_m * tiles_n;
+    const int xsplits = (splits == 2 || splits == 4 || splits == 8) ? splits : 0;
+    const dim3 grid = xsplits ? dim3((unsigned)(8 * ((tiles + 8 / xsplits - 1) / (8 / xsplits))))
+                              : dim3((unsigned)(8 * ((tiles + 7) / 8)), (unsigned)(splits > 1 ? splits : 1));
     const dim3 block(WGM * WGN * 64);
     constexpr int NT = WGM * WGN * 64;
     const size_t lds = (size_t)2 * 2 * ((a_km ? Operand<BM, BK, NT, true>::LDS_ELEMS : Operand<BM, BK, NT, false>::LDS_ELEMS) +
@@ -393,7 +409,7 @@ bool launch_pipe(hipStream_t s, bool a_km, bool b_km, int64_t M, int64_t N, int6
         attr_done = true;
     }
 #define TIO_GEMM_ARGS (const uint16_t *)A, lda, (const uint16_t *)B, ldb, (const uint16_t *)bias, (const uint16_t *)resid, ldr, \
-                      (uint16_t *)C, ldc, M, N, K, tiles_m, tiles_n, (uint16_t *)rowsum, ws, k_chunk, (int)rowsum_acc
+                      (uint16_t *)C, ldc, M, N, K, tiles_m, tiles_n, (uint16_t *)rowsum, ws, k_chunk, (int)rowsum_acc, xsplits
     if (!a_km && !b_km) gemm_bf16_pipe_k<BM, BN, BK, WGM, WGN, false, false><<<grid, block, lds, s>>>(TIO_GEMM_ARGS);
     else if (!a_km && b_km) gemm_bf16_pipe_k<BM, BN, BK, WGM, WGN, false, true><<<grid, block, lds, s>>>(TIO_GEMM_ARGS);
     else if (a_km && b_km) gemm_bf16_pipe_k<BM, BN, BK, WGM, WGN, true, true><<<grid, block, lds, s>>>(TIO_GEMM_ARGS);
