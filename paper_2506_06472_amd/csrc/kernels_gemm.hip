@@ -338,12 +338,16 @@ void gemm(hipStream_t s, int dtype, bool a_km, bool b_km, int64_t M, int64_t N, 
     }
     if (dtype == TIO_PREC_BF16) {
         // The pipelined kernel is the default.  Its 256x256 tiles (eight wavefronts, 128x64 each: fewer LDS
-        // bytes per MFMA) pay off once there are at least two rounds of them over the 256 CUs; below that
-        // 128x128 tiles fill the GPU better.  TIO_GEMM_CFG forces a choice: 0 plain kernel, 1 pipelined
-        // 128x128, 2 pipelined 256x256.
+        // bytes per MFMA) run one per CU, its 128x128 tiles two per CU at about 0.8 of the large tile's rate
+        // (measured on 768- to 5120-wide products); the choice goes to the one that loses less to the last,
+        // partly filled round over the 256 CUs.  TIO_GEMM_CFG forces a choice: 0 plain kernel, 1 pipelined 128x128,
+        // 2 pipelined 256x256.
         const int64_t big_tiles = ((M + 255) / 256) * ((N + 255) / 256);
+        const int64_t small_tiles = ((M + 127) / 128) * ((N + 127) / 128) * (splits > 1 ? splits : 1);
+        auto fill = [](int64_t tiles, int64_t slots) { return (double)tiles / (double)((tiles + slots - 1) / slots * slots); };
+        const bool large = splits <= 1 && fill(big_tiles, 256) >= 0.8 * fill(small_tiles, 512);
         const int ov = gemm_cfg_override();
-        const int pipe_cfg = ov == 1 ? 0 : ov == 2 ? 1 : (big_tiles >= 512 ? 1 : 0);
+        const int pipe_cfg = ov == 1 ? 0 : ov == 2 ? 1 : (large ? 1 : 0);
         if (ov != 0 && gemm_bf16_pipelined(s, pipe_cfg, a_km, b_km, M, N, K, A, lda, B, ldb, bias, resid, ldr, C, ldc, rowsum,
                                            splits > 1 ? (float *)workspace : nullptr, splits, accumulate)) {
             if (splits > 1) {
