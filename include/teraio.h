@@ -81,6 +81,7 @@ typedef struct tio_runtime_cfg {
     void *staging;                   /* pinned host memory, 4096-byte aligned, owned by the caller for the context's lifetime */
     uint64_t staging_bytes;          /* at least 4 chunks (two per direction) */
     uint64_t file_chunk_bytes;       /* multiple of 4096; 0 = 8 MiB */
+    int32_t file_buffered_io;        /* 1: go through the page cache even where direct I/O is available */
 } tio_runtime_cfg;
 
 typedef struct tio_ctx tio_ctx;

@@ -39,7 +39,7 @@ class RuntimeCfg(C.Structure):
                 ("pool_on_device", C.c_int32), ("host_tier_pool", C.c_void_p), ("host_tier_bytes", C.c_uint64),
                 ("host_tier_d2h_stream", C.c_void_p), ("host_tier_h2d_stream", C.c_void_p), ("host_tier_bw", C.c_uint64),
                 ("slow_tier_file", C.c_char_p), ("staging", C.c_void_p), ("staging_bytes", C.c_uint64),
-                ("file_chunk_bytes", C.c_uint64)]
+                ("file_chunk_bytes", C.c_uint64), ("file_buffered_io", C.c_int32)]
 
 
 class FileTierStats(C.Structure):
@@ -276,7 +276,8 @@ class Context:
 
     def __init__(self, cfg: dict, arena_bytes: int, host_bytes: int, slow_tier_bw: int = 0, single_copy_stream=False,
                  arena=None, host=None, pool_on_device=False, host_tier_bytes: int = 0, host_tier_bw: int = 0,
-                 host_tier=None, slow_tier_file=None, staging_bytes: int = 256 << 20, file_chunk_bytes: int = 0):
+                 host_tier=None, slow_tier_file=None, staging_bytes: int = 256 << 20, file_chunk_bytes: int = 0,
+                 file_buffered_io: bool = False):
         """host_tier_bytes > 0 (or a pinned uint8 tensor host_tier): a second, host-memory destination with its own
         two copy streams, for plans built with host_bw / host_budget.
         slow_tier_file: path of a file that is the slow tier instead of a memory pool (host_bytes is then the
@@ -329,7 +330,8 @@ class Context:
                         int(host_tier_bw),
                         os.fsencode(slow_tier_file) if slow_tier_file is not None else None,
                         self.staging.data_ptr() + self._staging_off if self.staging is not None else None,
-                        staging_bytes if self.staging is not None else 0, int(file_chunk_bytes))
+                        staging_bytes if self.staging is not None else 0, int(file_chunk_bytes),
+                        1 if file_buffered_io else 0)
         mc = model_cfg(cfg)
         self.h = C.c_void_p()
         torch.cuda.synchronize()
@@ -410,9 +412,10 @@ class Context:
 
 def tio_ctx_create(cfg, arena_bytes, host_bytes, slow_tier_bw=0, single_copy_stream=False, arena=None, host=None,
                    pool_on_device=False, host_tier_bytes=0, host_tier_bw=0, host_tier=None, slow_tier_file=None,
-                   staging_bytes=256 << 20, file_chunk_bytes=0) -> Context:
+                   staging_bytes=256 << 20, file_chunk_bytes=0, file_buffered_io=False) -> Context:
     return Context(cfg, arena_bytes, host_bytes, slow_tier_bw, single_copy_stream, arena, host, pool_on_device,
-                   host_tier_bytes, host_tier_bw, host_tier, slow_tier_file, staging_bytes, file_chunk_bytes)
+                   host_tier_bytes, host_tier_bw, host_tier, slow_tier_file, staging_bytes, file_chunk_bytes,
+                   file_buffered_io)
 
 
 def tio_op_gemm(stream_handle, dtype, a_kmajor, b_kmajor, M, N, K, A_ptr, lda, B_ptr, ldb, bias_ptr, resid_ptr, ldr,

@@ -24,16 +24,16 @@ void FileTier::guard(const char *what, hipError_t e) {
 }
 
 FileTier::FileTier(const char *path, void *staging, uint64_t staging_bytes, uint64_t chunk_bytes, hipStream_t d2h,
-                   hipStream_t h2d, int n_pairs_hint) {
+                   hipStream_t h2d, bool buffered) {
     if (!path || !*path) throw FileTierError{"empty file name"};
     chunk_ = chunk_bytes ? chunk_bytes : ((uint64_t)8 << 20);
     if (chunk_ % kAlign || chunk_ < kAlign) throw FileTierError{"chunk size must be a multiple of 4096 bytes"};
     if (!staging || ((uintptr_t)staging % kAlign)) throw FileTierError{"staging buffer must be 4096-byte aligned pinned host memory"};
     const uint64_t per_dir = std::min(kMaxSlots, staging_bytes / 2 / chunk_);
     if (per_dir < 2) throw FileTierError{"staging buffer must hold at least two chunks per direction (" + std::to_string(4 * chunk_) + " bytes)"};
-    fd_ = ::open(path, O_RDWR | O_CREAT | O_DIRECT | O_CLOEXEC, 0600);
+    if (!buffered) fd_ = ::open(path, O_RDWR | O_CREAT | O_DIRECT | O_CLOEXEC, 0600);
     direct_ = fd_ >= 0;
-    if (fd_ < 0 && errno == EINVAL) fd_ = ::open(path, O_RDWR | O_CREAT | O_CLOEXEC, 0600);   // file system without direct I/O
+    if (buffered || (fd_ < 0 && errno == EINVAL)) fd_ = ::open(path, O_RDWR | O_CREAT | O_CLOEXEC, 0600);   // or: file system without direct I/O
     if (fd_ < 0) throw FileTierError{std::string("cannot open ") + path + ": " + std::strerror(errno)};
     struct stat sb;
     if (::fstat(fd_, &sb) == 0) file_bytes_ = (uint64_t)sb.st_size;
@@ -69,7 +69,7 @@ FileTier::FileTier(const char *path, void *staging, uint64_t staging_bytes, uint
             b = (uint8_t *)q;
         }
     }
-    set_pairs(n_pairs_hint);
+    set_pairs(0);
     int dev = 0;
     (void)hipGetDevice(&dev);
     auto run = [this, dev](void (FileTier::*body)(int), int w) {

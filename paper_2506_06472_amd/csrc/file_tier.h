@@ -34,7 +34,7 @@ class FileTier : public MigrationEngine {
 
     // staging: pinned host memory, 4096-byte aligned, split evenly between the two directions
     FileTier(const char *path, void *staging, uint64_t staging_bytes, uint64_t chunk_bytes, hipStream_t d2h,
-             hipStream_t h2d, int n_pairs_hint);
+             hipStream_t h2d, bool buffered);
     ~FileTier() override;
     FileTier(const FileTier &) = delete;
     FileTier &operator=(const FileTier &) = delete;

@@ -571,7 +571,7 @@ int tio_ctx_create(const tio_model_cfg *cfg, const tio_runtime_cfg *rt, tio_ctx 
     if (hipHostMalloc((void **)&c->loss_pinned, 4096, hipHostMallocDefault) != hipSuccess) { delete c; return fail(TIO_ERR_HIP, "hipHostMalloc failed"); }
     if (file_tier) {
         try {
-            c->ft.reset(new FileTier(rt->slow_tier_file, rt->staging, rt->staging_bytes, rt->file_chunk_bytes, c->sd, c->sh, 0));
+            c->ft.reset(new FileTier(rt->slow_tier_file, rt->staging, rt->staging_bytes, rt->file_chunk_bytes, c->sd, c->sh, rt->file_buffered_io != 0));
             c->ft->resize(c->home_file_bytes);
         } catch (...) { tio_ctx_destroy(c); throw; }
     } else {

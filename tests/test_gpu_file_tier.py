@@ -82,6 +82,27 @@ def test_file_tier_is_bitwise_neutral(cfg, frac, chunk, staging, tmp_path):
     _same(l0, s0, l1, s1)
 
 
+def test_buffered_file_io(tmp_path):
+    """file_buffered_io: reads and writes go through the page cache, straight from and into the staging ring
+    (also what the library falls back to on a file system that refuses direct I/O)."""
+    import paper_2506_06472_amd as tio
+    cfg = CONFIGS["tiny_llama_fp32"]
+    params, tok, lab = make_inputs(cfg, seed=8)
+    lt, ll, up, cp, peak = _plans(cfg, 0.45, 2 * 10**9)
+    ce = cp.export()
+    names = [n for n, _, _ in tio.tio_param_list(cfg)]
+    l0, s0 = _reference(cfg, params, tok, lab, up, 3)
+    ctx = tio.tio_ctx_create(cfg, ce["cap"], FILE_LIMIT, 0, slow_tier_file=str(tmp_path / "slow_tier.bin"),
+                             staging_bytes=1 << 20, file_chunk_bytes=64 << 10, file_buffered_io=True)
+    ctx.tio_params_load(params)
+    l1 = [ctx.tio_train_step(tok, lab, cp)["loss"] for _ in range(3)]
+    info = ctx.tio_file_tier_info()
+    s1 = read_state(ctx, names, False)
+    ctx.close()
+    assert info["direct_io"] == 0 and info["bytes_read"] == 3 * ce["bytes_per_direction"]
+    _same(l0, s0, l1, s1)
+
+
 def test_file_tier_with_host_memory_tier(tmp_path):
     import paper_2506_06472_amd as tio
     cfg = BF16
