@@ -64,7 +64,8 @@ typedef struct tio_runtime_cfg {
     uint64_t host_bytes;
     void *compute_stream, *d2h_stream, *h2d_stream; /* hipStream_t, default priority; d2h may equal h2d */
     uint64_t slow_tier_bw;           /* bytes/s per direction enforced on the copy streams; 0 = unthrottled */
-    int32_t poison_freed;            /* debug: fill released arena ranges with NaN patterns */
+    int32_t poison_freed;            /* debug: every arena range vacated by an offload is overwritten with NaN
+                                        patterns once its copy has left, so a kernel that read it would show */
     int32_t pool_on_device;          /* 1: host_pool is device memory (hosts that cannot pin enough memory) */
     /* Optional second destination (plans built with a host-memory tier, tio_plan_opts.host_bw / host_budget):
      * pinned host memory with its own two copy streams.  All NULL / 0 when no such plan will be run. */
@@ -161,7 +162,8 @@ typedef struct tio_step_stats {
     int64_t wall_ns;                 /* host clock, launch of the first kernel to completion of the last */
     int64_t kernel_ns;               /* sum of kernel times (only when measured) */
     uint64_t d2h_bytes, h2d_bytes;
-    int64_t d2h_busy_ns, h2d_busy_ns;/* copy-stream time incl. pacing (only when measured) */
+    int64_t d2h_busy_ns, h2d_busy_ns;/* sum over the step's offloads / prefetches of begin-to-end time, pacing
+                                        included (only with TIO_STEP_TIMELINE) */
     int32_t n_kernels, n_migrations;
 } tio_step_stats;
 

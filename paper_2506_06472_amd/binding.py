@@ -277,7 +277,7 @@ class Context:
     def __init__(self, cfg: dict, arena_bytes: int, host_bytes: int, slow_tier_bw: int = 0, single_copy_stream=False,
                  arena=None, host=None, pool_on_device=False, host_tier_bytes: int = 0, host_tier_bw: int = 0,
                  host_tier=None, slow_tier_file=None, staging_bytes: int = 256 << 20, file_chunk_bytes: int = 0,
-                 file_buffered_io: bool = False):
+                 file_buffered_io: bool = False, poison_freed: bool = False):
         """host_tier_bytes > 0 (or a pinned uint8 tensor host_tier): a second, host-memory destination with its own
         two copy streams, for plans built with host_bw / host_budget.
         slow_tier_file: path of a file that is the slow tier instead of a memory pool (host_bytes is then the
@@ -323,7 +323,7 @@ class Context:
             self.s_h2d1 = torch.cuda.Stream(device="cuda:0")
         rt = RuntimeCfg(self.arena.data_ptr(), arena_bytes, self.host.data_ptr() if self.host is not None else None, int(host_bytes),
                         self.s_compute.cuda_stream, self.s_d2h.cuda_stream, self.s_h2d.cuda_stream,
-                        int(slow_tier_bw), 0, 1 if pool_on_device else 0,
+                        int(slow_tier_bw), 1 if poison_freed else 0, 1 if pool_on_device else 0,
                         self.host_tier.data_ptr() if self.host_tier is not None else None,
                         self.host_tier.numel() if self.host_tier is not None else 0,
                         self.s_d2h1.cuda_stream if self.s_d2h1 else None, self.s_h2d1.cuda_stream if self.s_h2d1 else None,
@@ -412,10 +412,10 @@ class Context:
 
 def tio_ctx_create(cfg, arena_bytes, host_bytes, slow_tier_bw=0, single_copy_stream=False, arena=None, host=None,
                    pool_on_device=False, host_tier_bytes=0, host_tier_bw=0, host_tier=None, slow_tier_file=None,
-                   staging_bytes=256 << 20, file_chunk_bytes=0, file_buffered_io=False) -> Context:
+                   staging_bytes=256 << 20, file_chunk_bytes=0, file_buffered_io=False, poison_freed=False) -> Context:
     return Context(cfg, arena_bytes, host_bytes, slow_tier_bw, single_copy_stream, arena, host, pool_on_device,
                    host_tier_bytes, host_tier_bw, host_tier, slow_tier_file, staging_bytes, file_chunk_bytes,
-                   file_buffered_io)
+                   file_buffered_io, poison_freed)
 
 
 def tio_op_gemm(stream_handle, dtype, a_kmajor, b_kmajor, M, N, K, A_ptr, lda, B_ptr, ldb, bias_ptr, resid_ptr, ldr,

@@ -330,6 +330,7 @@ void FileTier::offload_thread(int) {
             guard("hipMemcpyAsync", hipMemcpyAsync(d.ring[s].buf, r->dev + off, n, hipMemcpyDeviceToHost, d.stream));
             guard("hipEventRecord", hipEventRecord(d.ring[s].ev, d.stream));
             if (last) {
+                if (poison_) poison_(d.stream, r->dev, r->bytes);
                 if (r->t1) guard("hipEventRecord", hipEventRecord(r->t1, d.stream));
                 guard("hipEventRecord", hipEventRecord(r->done, d.stream));
             }

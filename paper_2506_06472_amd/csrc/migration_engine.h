@@ -20,6 +20,10 @@ class MigrationEngine {
 
     virtual ~MigrationEngine() {}
     virtual void set_pairs(int n_pairs) = 0;      // sequence tables for a newly installed plan (engine idle)
+    // debugging aid: called on the offload stream after a tensor's last copy out of the arena has been
+    // enqueued and before `done` is recorded, to overwrite the vacated range (nullptr = off)
+    using PoisonFn = void (*)(hipStream_t stream, void *dev, uint64_t bytes);
+    void set_poison(PoisonFn fn) { poison_ = fn; }
     // `where`: the tensor's place on the slow tier (a file offset, or a host or device address);
     // `after`: event recorded by the caller on the compute stream (the copy may not start before it);
     // `done`: recorded on the direction's stream when the transfer counts as complete; t0/t1: optional
@@ -43,6 +47,9 @@ class MigrationEngine {
     virtual void wait_consumed(int dir, uint64_t seq) = 0;
     virtual void drain() = 0;                     // every submitted request has completed
     virtual void check() = 0;                     // throws EngineError if any thread met an error
+
+   protected:
+    PoisonFn poison_ = nullptr;
 };
 
 }  // namespace tio

@@ -170,6 +170,7 @@ void PacedPool::run(int ch) {
             }
         }
         c.free_at = end;
+        if (poison_ && !r->prefetch) poison_(s, r->dev, r->bytes);
         if (r->t1) guard("hipEventRecord", hipEventRecord(r->t1, s));
         guard("hipEventRecord", hipEventRecord(r->done, s));
         std::lock_guard<std::mutex> lk(mu_);

@@ -118,6 +118,10 @@ void make_events(std::vector<hipEvent_t> &v, size_t n, bool timing) {
     for (size_t i = 0; i < n; ++i) HIPCHK(hipEventCreateWithFlags(&v[i], timing ? hipEventDefault : hipEventDisableTiming));
 }
 
+// debugging aid (tio_runtime_cfg.poison_freed): a vacated arena range is overwritten with NaN patterns, so that a
+// kernel that wrongly read it would poison the loss
+void poison_range(hipStream_t s, void *dev, uint64_t bytes) { k::fill_u32(s, dev, 0xFFFFFFFFu, (int64_t)(bytes / 4)); }
+
 // the engine that moves the pairs of a tier, or nullptr when they are plain copies on the tier's streams
 MigrationEngine *engine_of(tio_ctx *c, int tier) {
     if (tier == 1) return c->pp1 && c->bw1 ? c->pp1.get() : nullptr;
@@ -389,6 +393,7 @@ void run_step(tio_ctx *c, const int32_t *tokens, const int32_t *labels, bool cap
                     if (c->rec_kernel[prev]) HIPCHK(hipStreamWaitEvent(so, c->ev_kernel[prev], 0));
                     if (tl) { HIPCHK(hipEventRecord(c->ev_c0[ei], so)); issued[ei] = 1; }
                     HIPCHK(hipMemcpyAsync(pool + pr.host_offset, c->arena + al.address, pr.bytes, hipMemcpyDefault, so));
+                    if (c->rt.poison_freed) poison_range(so, c->arena + al.address, pr.bytes);
                     if (tl) HIPCHK(hipEventRecord(c->ev_c1[ei], so));
                     HIPCHK(hipEventRecord(c->ev_off[e.pair], so));
                 }
@@ -497,6 +502,9 @@ void run_step(tio_ctx *c, const int32_t *tokens, const int32_t *labels, bool cap
         st->d2h_bytes = d2h; st->h2d_bytes = h2d;
         st->n_kernels = N; st->n_migrations = nmig;
         if (timing) for (int64_t x : *timing) st->kernel_ns += x;
+        if (tl)
+            for (size_t i = 0; i < p.entries.size(); ++i)
+                if (issued[i]) (p.entries[i].kind == TIO_OFFLOAD ? st->d2h_busy_ns : st->h2d_busy_ns) += c->tl_c1[i] - c->tl_c0[i];
     }
 }
 
@@ -580,6 +588,9 @@ int tio_ctx_create(const tio_model_cfg *cfg, const tio_runtime_cfg *rt, tio_ctx 
     if (c->host1 && c->sd1 && c->sh1) {
         try { c->pp1.reset(new PacedPool(c->sd1, c->sh1, c->bw1)); } catch (...) { tio_ctx_destroy(c); throw; }
     }
+    if (rt->poison_freed)
+        for (MigrationEngine *e : {(MigrationEngine *)c->ft.get(), (MigrationEngine *)c->pp0.get(), (MigrationEngine *)c->pp1.get()})
+            if (e) e->set_poison(poison_range);
     *out = c;
     return TIO_OK;
     TIO_RT_END

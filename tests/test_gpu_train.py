@@ -226,3 +226,49 @@ def test_slow_tier_in_device_memory_gives_the_same_bits():
         assert losses == out[0][0]
         for key in state:
             assert state[key].tobytes() == out[0][1][key].tobytes(), key
+
+
+@pytest.mark.parametrize("mode", ["plain", "paced", "two_tier", "file"])
+def test_vacated_ranges_can_be_poisoned(mode, tmp_path):
+    """poison_freed overwrites every arena range an offload has vacated with NaN patterns: a kernel that still
+    read such a range would turn the loss into NaN.  The run stays bitwise equal to the uncapped one for every
+    kind of slow tier, and the timeline statistics of a step add up."""
+    import paper_2506_06472_amd as tio
+    cfg = dict(arch="gpt", L=2, d=256, H=4, f=1024, V=1000, T=256, B=2, precision="bf16", lr=3e-4)
+    params, tok, lab = make_inputs(cfg, seed=9)
+    lt = tio.tio_trace_build(cfg)
+    ll = tio.tio_analyze_lifetimes(lt)
+    peak = int(ll.export()["M"].max())
+    up = tio.tio_build_plan(lt, ll, 2**62, 0)
+    two = mode == "two_tier"
+    cp = tio.tio_build_plan(lt, ll, int(peak * 0.4) // 256 * 256, 4 * 10**9, host_bw=4 * 10**10 if two else 0,
+                            host_budget=peak // 4 if two else 0)
+    ue, ce = up.export(), cp.export()
+    names = [n for n, _, _ in tio.tio_param_list(cfg)]
+    ctx = tio.tio_ctx_create(cfg, ue["arena_needed"], ue["host_needed"] + (1 << 20), 0)
+    ctx.tio_params_load(params)
+    l0 = [ctx.tio_train_step(tok, lab, None)["loss"] for _ in range(4)]
+    s0 = read_state(ctx, names, True)
+    ctx.close()
+    kw = dict(poison_freed=True)
+    if two:
+        kw.update(host_tier_bytes=ce["host_tier_needed"] + 4096, host_tier_bw=4 * 10**10)
+    if mode == "file":
+        ctx = tio.tio_ctx_create(cfg, ce["cap"], 1 << 30, 0, slow_tier_file=str(tmp_path / "slow_tier.bin"),
+                                 staging_bytes=2 << 20, file_chunk_bytes=128 << 10, **kw)
+    else:
+        ctx = tio.tio_ctx_create(cfg, ce["cap"], ce["host_needed"] + (1 << 20), 0 if mode == "plain" else 4 * 10**9, **kw)
+    ctx.tio_params_load(params)
+    l1 = [ctx.tio_train_step(tok, lab, cp)["loss"] for _ in range(3)]
+    st = ctx.tio_train_step(tok, lab, cp, timeline=True)
+    l1.append(st["loss"])
+    s1 = read_state(ctx, names, True)
+    ctx.close()
+    assert np.isfinite(l1).all()
+    assert np.array(l0, np.float32).tobytes() == np.array(l1, np.float32).tobytes(), (l0, l1)
+    for key in s0:
+        assert s0[key].tobytes() == s1[key].tobytes(), key
+    # begin-to-end time of the step's transfers: positive, and at a paced tier at least bytes / bandwidth
+    assert st["d2h_busy_ns"] > 0 and st["h2d_busy_ns"] > 0
+    if mode == "paced":
+        assert st["h2d_busy_ns"] >= 0.98 * ce["bytes_per_direction"] / 4e9 * 1e9
