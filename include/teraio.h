@@ -287,8 +287,9 @@ int tio_op_gemm(void *stream, int32_t dtype, int32_t a_kmajor, int32_t b_kmajor,
  * rowsum(dO * o)) and dqkv [B*T, 3*H*dh].  Device pointers, 16-byte aligned; dh in {32, 64, 128}. */
 int tio_op_attention(void *stream, int32_t dtype, int64_t B, int64_t T, int64_t H, int64_t dh,
                      const void *qkv, void *o, float *lse, const void *dO, float *delta, void *dqkv);
-/* Timed repetitions of one operator on the given stream, HIP events around the launches;
- * returns average ns per launch.  op codes as in the trace; dims as documented per operator. */
+/* Measuring aid: launch number kernel_index of the schedule, repeated reps times on the compute stream with the
+ * uncapped layout (the arena must hold it) and whatever the arena contains, HIP events around the repetitions;
+ * returns average ns per launch.  It overwrites that launch's outputs: not for use between training steps. */
 int tio_op_bench(tio_ctx *ctx, int32_t kernel_index, int32_t reps, double *out_avg_ns);
 
 #ifdef __cplusplus

@@ -272,3 +272,40 @@ def test_vacated_ranges_can_be_poisoned(mode, tmp_path):
     assert st["d2h_busy_ns"] > 0 and st["h2d_busy_ns"] > 0
     if mode == "paced":
         assert st["h2d_busy_ns"] >= 0.98 * ce["bytes_per_direction"] / 4e9 * 1e9
+
+
+def test_bandwidth_can_change_between_steps_and_one_launch_can_be_timed():
+    """tio_set_slow_tier_bw moves the slow tier between plain copies and its paced engine without touching the
+    numbers; a lower bandwidth makes the capped step slower; tio_op_bench times one launch of the schedule."""
+    import paper_2506_06472_amd as tio
+    cfg = dict(arch="gpt", L=2, d=256, H=4, f=1024, V=1000, T=256, B=2, precision="bf16", lr=3e-4)
+    params, tok, lab = make_inputs(cfg, seed=10)
+    lt, ll, up, cp, peak = plans_for(cfg, 0.4, 2 * 10**9)
+    ue, ce = up.export(), cp.export()
+    ctx = _ctx(cfg, dict(arena_needed=ue["arena_needed"], host_needed=max(ue["host_needed"], ce["host_needed"])), bw=0)
+    ctx.tio_params_load(params)
+    l0 = [ctx.tio_train_step(tok, lab, None)["loss"] for _ in range(6)]
+    ctx.tio_params_load(params)
+    l1, wall = [], []
+    for bw in (0, 2 * 10**9, 2 * 10**9, 0, 10**9, 10**9):
+        ctx.tio_set_slow_tier_bw(bw)
+        st = ctx.tio_train_step(tok, lab, cp)
+        l1.append(st["loss"])
+        wall.append(st["wall_ns"])
+    assert np.array(l0, np.float32).tobytes() == np.array(l1, np.float32).tobytes(), (l0, l1)
+    # steady-state steps: half the bandwidth, about twice the transfer time
+    floor = ce["bytes_per_direction"] / 2e9 * 1e9
+    assert wall[2] >= 0.9 * floor and wall[5] >= 1.8 * floor and wall[3] < wall[2]
+    ops = lt.export()["op"]
+    k = int(np.nonzero(ops == 2)[0][0])                # first GEMM launch of the schedule
+    ns = ctx.tio_op_bench(k, 5)
+    assert 0 < ns < 1e8
+    with pytest.raises(tio.TioError):
+        ctx.tio_op_bench(len(ops), 1)
+    ctx.close()
+    small = _ctx(cfg, dict(arena_needed=ce["cap"], host_needed=ce["host_needed"]), bw=0)
+    small.tio_params_load(params)
+    with pytest.raises(tio.TioError) as ei:            # the uncapped layout does not fit this arena
+        small.tio_op_bench(k, 1)
+    assert ei.value.code == -7
+    small.close()

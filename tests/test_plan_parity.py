@@ -178,6 +178,7 @@ def test_library_exports_every_declared_symbol():
     lib = tio.binding.lib()
     missing = [n for n in names if not hasattr(lib, n)]
     assert not missing, missing
+    assert lib.tio_version().decode().strip() and lib.tio_last_error() is not None
 
 
 @pytest.mark.parametrize("name,frac", [("tiny_gpt_fp32", 0.5), ("tiny_llama_fp32", 0.4), ("gpt2_small_bf16", 0.4)])
