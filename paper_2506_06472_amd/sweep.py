@@ -32,7 +32,8 @@ def _cfg(name, micro_batches):
     return cfg, base_peak
 
 
-def sweep(name, bws, micro_batches=1, tau=None, min_bytes=1 << 20, out=sys.stdout):
+def sweep(name, bws, micro_batches=1, tau=None, min_bytes=1 << 20, out=sys.stdout, host_bw=0, host_budgets=(0,),
+          shared_channel=False):
     cfg, base_peak = _cfg(name, micro_batches)
     lt = tio.tio_trace_build(cfg)
     if tau is not None:
@@ -43,18 +44,21 @@ def sweep(name, bws, micro_batches=1, tau=None, min_bytes=1 << 20, out=sys.stdou
     cap = int(cfg["cap_bytes"]) if "cap_bytes" in cfg else int((base_peak or peak) * cfg["cap_frac"]) // 256 * 256
     tokens = cfg["B"] * cfg["T"]
     print(f"{name}: {len(M)} kernels, uncapped peak {peak / 1e9:.2f} GB, cap {cap / 1e9:.2f} GB, {tokens} tokens/step, "
-          f"micro-batches {micro_batches}, kernel times {'measured' if tau is not None else 'modelled'}", file=out)
-    print(f"{'GB/s':>7} {'step ms':>10} {'tokens/s':>10} {'of ideal':>9} {'GB/direction':>13} {'bound ms':>9} {'pairs':>6} {'urgent':>7}", file=out)
+          f"micro-batches {micro_batches}, kernel times {'measured' if tau is not None else 'modelled'}"
+          f"{', one channel shared by both directions' if shared_channel else ''}"
+          f"{f', host-memory tier at {host_bw / 1e9:.0f} GB/s' if host_bw else ''}", file=out)
+    print(f"{'GB/s':>7} {'host GB':>8} {'step ms':>10} {'tokens/s':>10} {'of ideal':>9} {'GB/direction':>13} {'pairs':>6} {'urgent':>7} {'to host':>8}", file=out)
     rows = []
     for bw in bws:
-        plan = tio.tio_build_plan(lt, ll, cap, int(bw), min_bytes=min_bytes)
-        pe = plan.export()
-        step, comp = tio.tio_plan_simulate(lt, plan, int(bw))
-        gb = pe["bytes_per_direction"] / 1e9
-        bound = pe["bytes_per_direction"] / bw * 1e3 if bw else 0.0
-        rows.append((bw, step, comp, pe))
-        print(f"{bw / 1e9:7.1f} {step / 1e6:10.1f} {tokens / (step / 1e9):10.0f} {comp / step:9.3f} {gb:13.2f} {bound:9.1f} "
-              f"{pe['n_greedy'] + pe['n_forced']:6d} {pe['n_forced']:7d}", file=out)
+        for hb in host_budgets:
+            plan = tio.tio_build_plan(lt, ll, cap, int(bw), duplex=not shared_channel, min_bytes=min_bytes,
+                                      host_bw=int(host_bw) if hb else 0, host_budget=int(hb))
+            pe = plan.export()
+            step, comp = tio.tio_plan_simulate(lt, plan, int(bw), duplex=not shared_channel)
+            gb = pe["bytes_per_direction"] / 1e9
+            rows.append((bw, hb, step, comp, pe))
+            print(f"{bw / 1e9:7.1f} {hb / 1e9:8.1f} {step / 1e6:10.1f} {tokens / (step / 1e9):10.0f} {comp / step:9.3f} {gb:13.2f} "
+                  f"{pe['n_greedy'] + pe['n_forced']:6d} {pe['n_forced']:7d} {sum(pe['tier']):8d}", file=out)
     return rows
 
 
@@ -98,10 +102,14 @@ def main(argv=None):
     ap.add_argument("--min-bytes", type=int, default=1 << 20)
     ap.add_argument("--tau", help="file with measured kernel times in ns, one per line")
     ap.add_argument("--characterize", action="store_true")
+    ap.add_argument("--host-bw", type=float, default=0, help="GB/s per direction of a host-memory tier beside the slow tier")
+    ap.add_argument("--host-budget", nargs="+", type=float, default=[0], help="GB of host memory that tier may hold (one row each)")
+    ap.add_argument("--shared-channel", action="store_true", help="offloads and prefetches share one channel (a single storage device)")
     a = ap.parse_args(argv)
     tau = np.loadtxt(a.tau, dtype=np.int64) if a.tau else None
     for name in a.workload:
-        sweep(name, [int(b * 1e9) for b in a.bw], a.micro_batches, tau, a.min_bytes)
+        sweep(name, [int(b * 1e9) for b in a.bw], a.micro_batches, tau, a.min_bytes, host_bw=a.host_bw * 1e9,
+              host_budgets=[h * 1e9 for h in a.host_budget], shared_channel=a.shared_channel)
         if a.characterize:
             characterize(name, a.micro_batches)
         print()

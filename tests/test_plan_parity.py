@@ -237,4 +237,9 @@ def test_performance_model_invariants_and_sweep_tool():
     out = io.StringIO()
     rows = sw.sweep("tiny_gpt_fp32", [10**9, 25 * 10**9], out=out)
     sw.characterize("tiny_gpt_fp32", out=out)
-    assert len(rows) == 2 and rows[0][1] >= rows[0][2] and "inactive periods" in out.getvalue()
+    assert len(rows) == 2 and rows[0][2] >= rows[0][3] and "inactive periods" in out.getvalue()
+    # a host-memory tier beside the slow tier, and one channel shared by both directions
+    rows = sw.sweep("tiny_gpt_fp32", [10**9], out=out, host_bw=2 * 10**10, host_budgets=(0, 10**5, 10**7))
+    assert [r[1] for r in rows] == [0, 10**5, 10**7] and rows[2][2] <= rows[0][2] and sum(rows[2][4]["tier"]) > 0
+    shared = sw.sweep("tiny_gpt_fp32", [10**9], out=out, shared_channel=True)
+    assert shared[0][2] >= rows[0][2]
