@@ -310,6 +310,7 @@ def main():
                      "traffic_unit": "bytes per launch missing the L2 (rocprofv3 FETCH_SIZE + WRITE_SIZE, calibrated)",
                      "algorithmic_bytes_per_launch": gemm_bytes / n_gemm,
                      "launches_per_step": n_gemm, "avg_launch_us": gemm_ns / n_gemm / 1e3,
+                     "achieved_without_migration": gemm_flops / float(tau[gemm].sum()) / 1e3,
                      "flops_per_step": gemm_flops},
     }
 

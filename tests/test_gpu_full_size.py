@@ -139,3 +139,47 @@ def test_gpt2_small_slow_tier_in_device_memory_unpaced():
         ctx.close()
     assert runs["device uncapped"] == runs["host uncapped"], runs
     assert runs["device capped"] == runs["host uncapped"], runs
+
+
+def test_gpt2_small_slow_tier_in_a_file(tmp_path):
+    """Benchmark size with the slow tier in a file (default 8 MiB chunks, 256 MiB staging ring, direct I/O where
+    the file system has it) and a host-memory tier beside it: the losses and sampled optimizer state are the bits
+    of the run with a pinned host pool, and the file carries the planned bytes."""
+    import paper_2506_06472_amd as tio
+    cfg = CONFIGS["gpt2_small_bf16"]
+    params, tok, lab = make_inputs(cfg, seed=0)
+    lt = tio.tio_trace_build(cfg)
+    ll = tio.tio_analyze_lifetimes(lt)
+    peak = int(ll.export()["M"].max())
+    cap = int(peak * cfg["cap_frac"]) // 256 * 256
+    up = tio.tio_build_plan(lt, ll, 2**62, 0)
+    plans = {"file": tio.tio_build_plan(lt, ll, cap, 8 * 10**9, duplex=False, min_bytes=1 << 20),
+             "file and host memory": tio.tio_build_plan(lt, ll, cap, 8 * 10**9, duplex=False, min_bytes=1 << 20,
+                                                        host_bw=25 * 10**9, host_budget=10**9)}
+    ue = up.export()
+    sample = ["lnf_g", "l0.w_qkv", "l11.b_fc1", "w_head"]
+    ctx = tio.tio_ctx_create(cfg, ue["arena_needed"], ue["host_needed"] + (1 << 20), 0)
+    ctx.tio_params_load(params)
+    l0 = [ctx.tio_train_step(tok, lab, None)["loss"] for _ in range(3)]
+    s0 = read_state(ctx, sample, True)
+    ctx.close()
+    for label, cp in plans.items():
+        print(label, flush=True)
+        ce = cp.export()
+        assert (sum(ce["tier"]) > 0) == (label != "file")
+        ctx = tio.tio_ctx_create(cfg, ce["cap"], 8 << 30, 0, slow_tier_file=str(tmp_path / "slow_tier.bin"),
+                                 host_tier_bytes=ce["host_tier_needed"] + 4096 if ce["host_tier_needed"] else 0,
+                                 host_tier_bw=25 * 10**9)
+        ctx.tio_params_load(params)
+        l1 = [ctx.tio_train_step(tok, lab, cp)["loss"] for _ in range(3)]
+        info = ctx.tio_file_tier_info()
+        s1 = read_state(ctx, sample, True)
+        ctx.close()
+        print(f"  direct I/O {info['direct_io']}, file {info['file_bytes'] / 1e9:.2f} GB, read {info['bytes_read'] / 1e9:.2f} GB", flush=True)
+        assert np.array(l0, np.float32).tobytes() == np.array(l1, np.float32).tobytes(), (label, l0, l1)
+        for key in s0:
+            assert s0[key].tobytes() == s1[key].tobytes(), (label, key)
+        if label == "file":
+            assert info["bytes_read"] == 3 * ce["bytes_per_direction"]
+        else:
+            assert 0 < info["bytes_read"] < 3 * ce["bytes_per_direction"]
