@@ -117,6 +117,9 @@ def main():
                     help="bytes/s per direction of a second, host-memory destination beside the slow tier (the paper's "
                          "mixed mode); 0 = none; not the headline configuration")
     ap.add_argument("--host-budget", type=float, default=0, help="bytes of host memory the second destination may hold")
+    ap.add_argument("--split-batch", action="store_true",
+                    help="with --micro-batches n: split the workload's own batch into n groups instead of running n "
+                         "batches per step (same tokens per step as the headline, smaller activations)")
     ap.add_argument("--micro-batches", type=int, default=1,
                     help="n > 1: a step is n micro-batches of the workload's batch with gradient accumulation and one "
                          "AdamW update (n times the tokens per step, same memory cap); not the headline configuration")
@@ -135,7 +138,10 @@ def main():
         # the cap stays that of the workload itself (a fraction of the single-batch peak, or its byte figure)
         if "cap_frac" in cfg:
             base_peak = int(tio.tio_analyze_lifetimes(tio.tio_trace_build(cfg)).export()["M"].max())
-        cfg["B"] *= args.micro_batches
+        if not args.split_batch:
+            cfg["B"] *= args.micro_batches
+        elif cfg["B"] % args.micro_batches:
+            raise SystemExit("--split-batch: the batch is not a multiple of --micro-batches")
         cfg["micro_batches"] = args.micro_batches
     t_start = time.perf_counter()
     log = lambda *a: print(f"[{time.perf_counter() - t_start:7.1f}s]", *a, file=sys.stderr, flush=True)
@@ -286,7 +292,7 @@ def main():
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": step_s * 1e3,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": cfg["precision"],
         "data": "synthetic",
-        "config": {"workload": args.workload, "micro_batches": args.micro_batches, "tokens_per_step": S, "mem_cap_bytes": cap, "uncapped_peak_bytes": peak,
+        "config": {"workload": args.workload, "micro_batches": args.micro_batches, "batch_split": bool(args.split_batch), "tokens_per_step": S, "mem_cap_bytes": cap, "uncapped_peak_bytes": peak,
                    "cap_frac_of_peak": cap / peak, "slow_tier_bw_bytes_per_s": bw, "channels": "one shared" if shared else "one per direction", 
                    "slow_tier": {"host": "pinned host memory", "device": "device memory outside the arena (stand-in)",
                                  "file": "file, direct I/O through a pinned staging ring"}[tier], "min_bytes": args.min_bytes,
