@@ -334,39 +334,63 @@ __global__ void __launch_bounds__(WGM *WGN * 64)
             else rowsum[m] = (uint16_t)f32_to_bf16_bits(rsum + (rowsum_acc ? bf16_bits_to_f32(rowsum[m]) : 0.f));
         }
     }
-    // epilogue: lane holds C[m][n .. n+3] for 4 groups of columns per 32x32 tile
+    // epilogue: lane holds C[m][n .. n+3] for 4 groups of columns per 32x32 tile.
+    // Results pass through LDS (the tile buffer that the last contraction tile did not use: every wavefront finished
+    // reading it before the last barrier, so no further barrier is needed), one 32-row block of the wavefront's tile at
+    // a time, as fp32: a lane then owns eight consecutive columns of one
+    // row, so the bias and residual are read and the output is written in whole 16-byte chunks of full rows
+    // (writing the accumulator layout directly touches 16 bytes of each of 32 rows per instruction).  The fp32 partial
+    // tiles of a split contraction take the same route.
+    {
+        constexpr int SPF = WN + 4, CPR = WN / 8, PASSES = 32 * CPR / 64;
+        static_assert((32 * CPR) % 64 == 0, "a 32-row block is a whole number of wavefront passes");
+        const bool wide = (ldc % 8 == 0) && (resid == nullptr || ldr % 8 == 0);     // 16-byte aligned rows
+        static_assert((size_t)TILE * 2 >= (size_t)WGM * WGN * 32 * SPF * 4, "the staging blocks fit one tile buffer");
+        float *stage = reinterpret_cast<float *>(smem + (nk & 1) * TILE) + wave * (32 * SPF);
 #pragma unroll
-    for (int i = 0; i < TM; ++i) {
-        const int64_t m = m0 + wm * WM + i * 32 + l32;
-        if (m >= M) continue;
+        for (int i = 0; i < TM; ++i) {
 #pragma unroll
-        for (int j = 0; j < TN; ++j) {
+            for (int j = 0; j < TN; ++j)
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const int64_t n = n0 + wn * WN + j * 32 + q * 8 + lhi * 4;
-                if (n >= N) continue;
-                float v[4] = {acc[i][j][q * 4 + 0], acc[i][j][q * 4 + 1], acc[i][j][q * 4 + 2], acc[i][j][q * 4 + 3]};
-                if (ws) {          // N is a multiple of 4 in split mode
-                    *reinterpret_cast<float4 *>(ws + ((int64_t)split * M + m) * N + n) = make_float4(v[0], v[1], v[2], v[3]);
+                for (int q = 0; q < 4; ++q)
+                    *reinterpret_cast<float4 *>(stage + l32 * SPF + j * 32 + q * 8 + lhi * 4) =
+                        make_float4(acc[i][j][q * 4 + 0], acc[i][j][q * 4 + 1], acc[i][j][q * 4 + 2], acc[i][j][q * 4 + 3]);
+            __builtin_amdgcn_wave_barrier();
+#pragma unroll
+            for (int p = 0; p < PASSES; ++p) {
+                const int c = p * 64 + lane, row = c / CPR, ch = c % CPR;
+                const float4 x0 = *reinterpret_cast<const float4 *>(stage + row * SPF + ch * 8);
+                const float4 x1 = *reinterpret_cast<const float4 *>(stage + row * SPF + ch * 8 + 4);
+                const int64_t m = m0 + wm * WM + i * 32 + row, n = n0 + wn * WN + ch * 8;
+                if (m >= M || n >= N) continue;
+                if (ws) {                                   // N is a multiple of 4 in split mode
+                    float *dst = ws + ((int64_t)split * M + m) * N + n;
+                    *reinterpret_cast<float4 *>(dst) = x0;
+                    if (n + 4 < N) *reinterpret_cast<float4 *>(dst + 4) = x1;
                     continue;
                 }
-                if (n + 4 <= N) {
+                float v[8] = {x0.x, x0.y, x0.z, x0.w, x1.x, x1.y, x1.z, x1.w};
+                if (n + 8 <= N && wide) {
                     if (bias) {
-                        const uint2 t = *reinterpret_cast<const uint2 *>(bias + n);
-                        v[0] += __uint_as_float(t.x << 16); v[1] += __uint_as_float(t.x & 0xffff0000u);
-                        v[2] += __uint_as_float(t.y << 16); v[3] += __uint_as_float(t.y & 0xffff0000u);
+                        const uint4 t = *reinterpret_cast<const uint4 *>(bias + n);
+                        const uint32_t u[4] = {t.x, t.y, t.z, t.w};
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) { v[2 * e] += __uint_as_float(u[e] << 16); v[2 * e + 1] += __uint_as_float(u[e] & 0xffff0000u); }
                     }
                     if (resid) {
-                        const uint2 t = *reinterpret_cast<const uint2 *>(resid + m * ldr + n);
-                        v[0] += __uint_as_float(t.x << 16); v[1] += __uint_as_float(t.x & 0xffff0000u);
-                        v[2] += __uint_as_float(t.y << 16); v[3] += __uint_as_float(t.y & 0xffff0000u);
+                        const uint4 t = *reinterpret_cast<const uint4 *>(resid + m * ldr + n);
+                        const uint32_t u[4] = {t.x, t.y, t.z, t.w};
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) { v[2 * e] += __uint_as_float(u[e] << 16); v[2 * e + 1] += __uint_as_float(u[e] & 0xffff0000u); }
                     }
-                    uint2 o;
+                    uint4 o;
                     o.x = f32_to_bf16_bits(v[0]) | (f32_to_bf16_bits(v[1]) << 16);
                     o.y = f32_to_bf16_bits(v[2]) | (f32_to_bf16_bits(v[3]) << 16);
-                    *reinterpret_cast<uint2 *>(C + m * ldc + n) = o;
+                    o.z = f32_to_bf16_bits(v[4]) | (f32_to_bf16_bits(v[5]) << 16);
+                    o.w = f32_to_bf16_bits(v[6]) | (f32_to_bf16_bits(v[7]) << 16);
+                    *reinterpret_cast<uint4 *>(C + m * ldc + n) = o;
                 } else {
-                    for (int e = 0; e < 4 && n + e < N; ++e) {
+                    for (int e = 0; e < 8 && n + e < N; ++e) {
                         float x = v[e];
                         if (bias) x += bf16_bits_to_f32(bias[n + e]);
                         if (resid) x += bf16_bits_to_f32(resid[m * ldr + n + e]);
@@ -374,6 +398,7 @@ __global__ void __launch_bounds__(WGM *WGN * 64)
                     }
                 }
             }
+            __builtin_amdgcn_wave_barrier();
         }
     }
 }
