@@ -26,6 +26,9 @@ sys.path.insert(0, ROOT)
 
 GEMM_OPS = (2, 9, 10)          # forward, dX, dW contractions (one kernel template)
 ATTN_OPS = (4, 17)
+# memory-bound operators by trace op code
+HBM_CLASSES = {"norm": (1, 14, 15), "activation": (5, 6, 12, 13), "rope": (3, 18), "cross_entropy": (7,),
+               "embedding": (0, 19, 20), "adamw": (21,)}
 PEAK_BF16_TFLOPS = 2500.0
 # L2 <-> fabric bytes per GEMM launch from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this command
 # (profiles/gpt2_small_bf16_step_pmc_traffic.txt); None where no such run has been made
@@ -281,6 +284,17 @@ def main():
     tv = lt.export()
     gemm_bytes = sum(int(tv["tensor_bytes"][tv["operand_tensor"][tv["operand_off"][k]:tv["operand_off"][k + 1]]].sum())
                      for k in np.nonzero(gemm)[0])
+    # memory-bound kernels: algorithmic bytes = operand tensor sizes, once per read and once per write
+    kb = np.array([sum(int(tv["tensor_bytes"][t]) * ((int(f) & 1) + ((int(f) >> 1) & 1))
+                       for t, f in zip(tv["operand_tensor"][tv["operand_off"][k]:tv["operand_off"][k + 1]],
+                                       tv["operand_flags"][tv["operand_off"][k]:tv["operand_off"][k + 1]]))
+                   for k in range(N)], dtype=np.float64)
+    hbm = {}
+    for label, codes in HBM_CLASSES.items():
+        sel = np.isin(ops, codes)
+        if sel.any():
+            hbm[label] = {"GBps": kb[sel].sum() / ktimes[sel].sum(), "GBps_without_migration": kb[sel].sum() / float(tau[sel].sum()),
+                          "ms_per_step": ktimes[sel].sum() / 1e6, "launches": int(sel.sum())}
     gemm_tflops = gemm_flops / gemm_ns / 1e3
     attn_tflops = flops[attn].sum() / ktimes[attn].sum() / 1e3
     comp_s = ktimes.sum() / 1e9
@@ -310,6 +324,8 @@ def main():
                  "cap_GBps": bw / 1e9},
         "kernel_ms_per_step": comp_s * 1e3, "overlap": 1.0 - max(0.0, step_s - comp_s) / step_s,
         "attention_tflops": attn_tflops, "loss": loss,
+        "hbm_kernels": {"peak_GBps": 8000.0, "bytes": "operand tensor sizes, counted once per read and once per write",
+                        "classes": hbm},
         "roofline": {"bound": "mfma", "kernel": "gemm_bf16_pipe_k (forward, dX and dW contractions)",
                      "achieved": gemm_tflops, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": gemm_tflops / PEAK_BF16_TFLOPS, "traffic": GEMM_TRAFFIC_BYTES_PER_LAUNCH.get(args.workload),
