@@ -588,11 +588,25 @@ Plan build_plan(const Trace &t, const Lifetimes &life, uint64_t cap, uint64_t bw
     const int retries = o.layout_retries > 0 ? o.layout_retries : 24;
     uint64_t pc = std::min(cap, peak);
     const uint64_t step = std::max<uint64_t>(256, std::min(cap, peak) / 50);
+    auto attempt = [&](uint64_t planning_cap, Plan &p) {
+        p = Plan();
+        p.cap = cap; p.planning_cap = planning_cap; p.bw = bw; p.structure_hash = t.structure_hash;
+        select_periods(t, life, planning_cap, bw, o.duplex != 0, o.min_bytes, o.host_bw, o.host_budget, p);
+        return assign_addresses(t, life, arena, p);
+    };
     for (int r = 0; r <= retries; ++r) {
         Plan p;
-        p.cap = cap; p.planning_cap = pc; p.bw = bw; p.structure_hash = t.structure_hash;
-        select_periods(t, life, pc, bw, o.duplex != 0, o.min_bytes, o.host_bw, o.host_budget, p);
-        if (assign_addresses(t, life, arena, p)) return p;
+        if (attempt(pc, p)) {
+            // the step before did not fit: look between the two for a larger planning capacity that does
+            // (every byte of it is a byte that need not move), halving the interval a few times
+            uint64_t lo = pc, hi = r > 0 ? pc + step : pc;
+            for (int i = 0; i < 4 && hi - lo >= 512; ++i) {
+                const uint64_t mid = (lo + (hi - lo) / 2) / 256 * 256;
+                Plan q;
+                if (attempt(mid, q)) { lo = mid; p = std::move(q); } else hi = mid;
+            }
+            return p;
+        }
         if (pc <= step) break;
         pc -= step;
     }
