@@ -493,7 +493,10 @@ __global__ void __launch_bounds__(TPB) rope_k(T *__restrict__ qkv, int64_t S, in
 }
 
 // ---------------------------------------------------------------- cross entropy
-// one workgroup per row: online max / sum-of-exponentials, then dlogits written in place
+// one workgroup per row: online max / sum-of-exponentials, then dlogits written in place.  Two exponentials per
+// logit make the kernel as much an ALU as a memory problem at a 50k vocabulary, so they are the hardware's
+// base-2 exponential of x*log2(e) (relative error about 1e-6 for |x| up to 20, far inside the loss and gradient bars).
+__device__ __forceinline__ float ce_exp(float x) { return __builtin_amdgcn_exp2f(x * 1.4426950408889634f); }
 template <typename T>
 __global__ void __launch_bounds__(TPB) ce_k(T *__restrict__ logits, const int32_t *__restrict__ labels,
                                             float *__restrict__ losses, int64_t S, int64_t Vn, int64_t ld, int64_t S_total) {
@@ -511,13 +514,13 @@ __global__ void __launch_bounds__(TPB) ce_k(T *__restrict__ logits, const int32_
         for (int j = 0; j < V; ++j) {
             if (c * V + j < Vn) {
                 const float x = f[j];
-                if (x > m) { s = s * expf(m - x) + 1.0f; m = x; }
-                else s += expf(x - m);
+                if (x > m) { s = s * ce_exp(m - x) + 1.0f; m = x; }
+                else s += ce_exp(x - m);
             }
         }
     }
     const float M = block_max<TPB / 64>(m, red);
-    const float tot = block_sum<TPB / 64>(m == -INFINITY ? 0.f : s * expf(m - M), red);
+    const float tot = block_sum<TPB / 64>(m == -INFINITY ? 0.f : s * ce_exp(m - M), red);
     const float lse = M + logf(tot);
     const int32_t lab = labels[row];
     if (threadIdx.x == 0) losses[row] = lse - to_f32(xr[lab]);
@@ -529,7 +532,7 @@ __global__ void __launch_bounds__(TPB) ce_k(T *__restrict__ logits, const int32_
 #pragma unroll
         for (int j = 0; j < V; ++j) {
             const int64_t col = c * V + j;
-            f[j] = col < Vn ? (expf(f[j] - lse) - (col == lab ? 1.0f : 0.0f)) * invS : 0.0f;
+            f[j] = col < Vn ? (ce_exp(f[j] - lse) - (col == lab ? 1.0f : 0.0f)) * invS : 0.0f;
         }
         a.set(f); a.store(xr + c * V);
     }
