@@ -32,7 +32,7 @@ HBM_CLASSES = {"norm": (1, 14, 15), "activation": (5, 6, 12, 13), "rope": (3, 18
 PEAK_BF16_TFLOPS = 2500.0
 # L2 <-> fabric bytes per GEMM launch from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this command
 # (profiles/gpt2_small_bf16_step_pmc_traffic.txt); None where no such run has been made
-GEMM_TRAFFIC_BYTES_PER_LAUNCH = {"gpt2_small_bf16": 149.85e6}
+GEMM_TRAFFIC_BYTES_PER_LAUNCH = {"gpt2_small_bf16": 149.68e6}
 
 
 def probe_file_bw(path, total=2 << 30, block=8 << 20, threads=4):
