@@ -18,6 +18,7 @@ def _host(t):
 CASES = [  # M, N, K, pad of ld
     (128, 128, 64, 0), (200, 136, 72, 0), (256, 384, 256, 0), (130, 1000, 96, 24), (64, 72, 1000, 8),
     (513, 257, 130, 7), (8, 8, 8, 0), (1024, 768, 768, 0),
+    (300, 200, 136, -4),       # output and residual rows start on 8-byte, not 16-byte, boundaries (ldc = 8k + 4)
 ]
 
 
@@ -33,7 +34,7 @@ def test_gemm_all_layouts(dtype, a_km, b_km, M, N, K, pad):
     # logical operands A[M,K], B[N,K]; stored [rows, ld] or [K, ld]
     lda = (r8(M) if a_km else r8(K)) + 8 * (pad > 0)
     ldb = (r8(N) if b_km else r8(K)) + 8 * (pad > 0)
-    ldc = r8(N) + 8 * (pad > 0)
+    ldc = r8(N) + 8 * (pad > 0) + (4 if pad < 0 else 0)
     A = rng.standard_normal((M, K)).astype(np.float32)
     B = rng.standard_normal((N, K)).astype(np.float32)
     bias = rng.standard_normal(r8(N)).astype(np.float32)
