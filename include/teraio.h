@@ -63,7 +63,9 @@ typedef struct tio_runtime_cfg {
                                         (pool_on_device) a second device buffer outside the capped arena */
     uint64_t host_bytes;
     void *compute_stream, *d2h_stream, *h2d_stream; /* hipStream_t, default priority; d2h may equal h2d */
-    uint64_t slow_tier_bw;           /* bytes/s per direction enforced on the copy streams; 0 = unthrottled */
+    uint64_t slow_tier_bw;           /* emulated bandwidth of the slow tier, bytes/s per direction (one shared channel when
+                                        d2h_stream == h2d_stream): a transfer counts as complete bytes/bandwidth after the
+                                        later of "its dependencies are met" and "the channel is free"; 0 = unthrottled */
     int32_t poison_freed;            /* debug: every arena range vacated by an offload is overwritten with NaN
                                         patterns once its copy has left, so a kernel that read it would show */
     int32_t pool_on_device;          /* 1: host_pool is device memory (hosts that cannot pin enough memory) */
@@ -72,7 +74,7 @@ typedef struct tio_runtime_cfg {
     void *host_tier_pool;            /* pinned host memory, 256-byte aligned */
     uint64_t host_tier_bytes;
     void *host_tier_d2h_stream, *host_tier_h2d_stream;   /* hipStream_t, default priority */
-    uint64_t host_tier_bw;           /* bytes/s per direction enforced on those streams; 0 = unthrottled */
+    uint64_t host_tier_bw;           /* emulated bandwidth of that tier, bytes/s per direction; 0 = unthrottled */
     /* Optional: the slow tier is a file (the paper's storage tier, Section 3.3) instead of a memory pool.  Then
      * host_pool is NULL, pool_on_device 0, and host_bytes is the largest size the file may grow to.  The file is
      * created if missing, opened for direct I/O where the file system supports it, grown as plans need and never
