@@ -309,3 +309,36 @@ def test_bandwidth_can_change_between_steps_and_one_launch_can_be_timed():
         small.tio_op_bench(k, 1)
     assert ei.value.code == -7
     small.close()
+
+
+@pytest.mark.parametrize("bw", [0, 2 * 10**9])
+def test_one_copy_stream_shared_by_both_directions(bw):
+    """d2h_stream == h2d_stream: offloads and prefetches form one queue (the planner's duplex = 0 channel).  The
+    numbers stay those of the uncapped run, and at an emulated bandwidth a step takes at least the time of all its
+    bytes, both directions, through the one channel."""
+    import paper_2506_06472_amd as tio
+    cfg = SMALL_BF16
+    params, tok, lab = make_inputs(cfg, seed=11)
+    lt = tio.tio_trace_build(cfg)
+    ll = tio.tio_analyze_lifetimes(lt)
+    peak = int(ll.export()["M"].max())
+    up = tio.tio_build_plan(lt, ll, 2**62, 0)
+    cp = tio.tio_build_plan(lt, ll, int(peak * 0.4) // 256 * 256, bw or 2 * 10**9, duplex=False)
+    ue, ce = up.export(), cp.export()
+    names = [n for n, _, _ in tio.tio_param_list(cfg)]
+    ctx = tio.tio_ctx_create(cfg, ue["arena_needed"], ue["host_needed"] + (1 << 20), 0)
+    ctx.tio_params_load(params)
+    l0 = [ctx.tio_train_step(tok, lab, None)["loss"] for _ in range(4)]
+    s0 = read_state(ctx, names, True)
+    ctx.close()
+    ctx = tio.tio_ctx_create(cfg, ce["cap"], ce["host_needed"] + (1 << 20), bw, single_copy_stream=True)
+    ctx.tio_params_load(params)
+    stats = [ctx.tio_train_step(tok, lab, cp) for _ in range(4)]
+    s1 = read_state(ctx, names, True)
+    ctx.close()
+    l1 = [st["loss"] for st in stats]
+    assert np.array(l0, np.float32).tobytes() == np.array(l1, np.float32).tobytes(), (l0, l1)
+    for key in s0:
+        assert s0[key].tobytes() == s1[key].tobytes(), key
+    if bw:
+        assert stats[-1]["wall_ns"] >= 0.95 * 2 * ce["bytes_per_direction"] / bw * 1e9
