@@ -8,7 +8,9 @@ Figure 3 of the paper: training throughput against migration bandwidth).  --char
 1 and 2 of the paper show for their models: the share of the allocated bytes that a kernel actually
 touches, and the distribution of the tensors' inactive periods.  Kernel times are the library's modelled
 ones unless --tau FILE gives measured times (one integer of nanoseconds per kernel, e.g. written from
-tio_profile_iteration).
+tio_profile_iteration).  --measure-layer (needs the GPU) measures them on a one-layer model of the same widths
+and gives every launch of the full model the time of the launch with the same operator, flops and operand sizes:
+kernel times for configurations whose slow-tier pool no single box can hold.
 """
 from __future__ import annotations
 
@@ -62,6 +64,45 @@ def sweep(name, bws, micro_batches=1, tau=None, min_bytes=1 << 20, out=sys.stdou
     return rows
 
 
+def _signatures(tv):
+    off, ten, size = tv["operand_off"], tv["operand_tensor"], tv["tensor_bytes"]
+    return [(int(tv["op"][k]), int(tv["flops"][k]), tuple(sorted(int(size[t]) for t in ten[off[k]:off[k + 1]])))
+            for k in range(tv["n_kernels"])]
+
+
+def measure_layer_tau(name, micro_batches=1, out=sys.stdout):
+    """Kernel times of workload `name` from a measured iteration of the same model with one layer (GPU): the
+    median-of-three time of each launch, averaged over the launches with the same signature (operator, flops,
+    operand sizes), is given to every launch of the full trace with that signature."""
+    from synth import gen_tokens, iter_params_pooled
+    cfg, _ = _cfg(name, micro_batches)
+    one = dict(cfg, L=1)
+    lt1 = tio.tio_trace_build(one)
+    up = tio.tio_build_plan(lt1, tio.tio_analyze_lifetimes(lt1), 2**62, 0).export()
+    plist = tio.tio_param_list(one)
+    specs = [(n, (r, c) if r > 1 else (c,), "normal" if r > 1 else ("ones" if n.endswith("_g") else "zeros")) for n, r, c in plist]
+    tok, lab = gen_tokens(one["B"], one["T"], one["V"], 0)
+    ctx = tio.tio_ctx_create(one, up["arena_needed"], up["host_needed"] + (1 << 20), 0)
+    try:
+        for pname, arr in iter_params_pooled(specs, 0):
+            ctx.tio_params_load({pname: arr})
+        tau1 = ctx.tio_profile_iteration(tok, lab, tio.PROFILE_MEASURED).export()["tau"]
+    finally:
+        ctx.close()
+    acc = {}
+    for sig, t in zip(_signatures(lt1.export()), tau1):
+        acc.setdefault(sig, []).append(int(t))
+    mean = {sig: int(round(sum(v) / len(v))) for sig, v in acc.items()}
+    full = _signatures(tio.tio_trace_build(cfg).export())
+    missing = sorted({sig[:2] for sig in full if sig not in mean})
+    if missing:
+        raise RuntimeError(f"launches of the full model without a counterpart in the one-layer model: {missing[:5]}")
+    tau = np.array([mean[sig] for sig in full], dtype=np.int64)
+    print(f"{name}: kernel times measured on one layer ({len(tau1)} launches, {len(mean)} distinct), sum over the full model "
+          f"{tau.sum() / 1e6:.1f} ms", file=out)
+    return tau
+
+
 def characterize(name, micro_batches=1, out=sys.stdout):
     cfg, _ = _cfg(name, micro_batches)
     lt = tio.tio_trace_build(cfg)
@@ -102,12 +143,15 @@ def main(argv=None):
     ap.add_argument("--min-bytes", type=int, default=1 << 20)
     ap.add_argument("--tau", help="file with measured kernel times in ns, one per line")
     ap.add_argument("--characterize", action="store_true")
+    ap.add_argument("--measure-layer", action="store_true", help="kernel times measured on a one-layer model (needs the GPU)")
     ap.add_argument("--host-bw", type=float, default=0, help="GB/s per direction of a host-memory tier beside the slow tier")
     ap.add_argument("--host-budget", nargs="+", type=float, default=[0], help="GB of host memory that tier may hold (one row each)")
     ap.add_argument("--shared-channel", action="store_true", help="offloads and prefetches share one channel (a single storage device)")
     a = ap.parse_args(argv)
     tau = np.loadtxt(a.tau, dtype=np.int64) if a.tau else None
     for name in a.workload:
+        if a.measure_layer:
+            tau = measure_layer_tau(name, a.micro_batches)
         sweep(name, [int(b * 1e9) for b in a.bw], a.micro_batches, tau, a.min_bytes, host_bw=a.host_bw * 1e9,
               host_budgets=[h * 1e9 for h in a.host_budget], shared_channel=a.shared_channel)
         if a.characterize:
