@@ -342,3 +342,18 @@ def test_one_copy_stream_shared_by_both_directions(bw):
         assert s0[key].tobytes() == s1[key].tobytes(), key
     if bw:
         assert stats[-1]["wall_ns"] >= 0.95 * 2 * ce["bytes_per_direction"] / bw * 1e9
+
+
+def test_kernel_times_of_the_full_model_from_one_measured_layer():
+    """sweep.measure_layer_tau: every launch of the full trace gets the measured time of a one-layer launch with
+    the same operator, flops and operand sizes; the result drives the planner and the performance model."""
+    import io
+    import paper_2506_06472_amd as tio
+    from paper_2506_06472_amd import sweep as sw
+    name = "tiny_llama_fp32"
+    cfg = CONFIGS[name]
+    tau = sw.measure_layer_tau(name, out=io.StringIO())
+    lt = tio.tio_trace_build(cfg)
+    assert len(tau) == lt.export()["n_kernels"] and (tau > 0).all()
+    rows = sw.sweep(name, [10**9, 10**10], tau=tau, out=io.StringIO())
+    assert rows[0][2] >= rows[1][2] >= int(tau.sum())
