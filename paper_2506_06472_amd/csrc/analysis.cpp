@@ -598,9 +598,11 @@ Plan build_plan(const Trace &t, const Lifetimes &life, uint64_t cap, uint64_t bw
         Plan p;
         if (attempt(pc, p)) {
             // the step before did not fit: look between the two for a larger planning capacity that does
-            // (every byte of it is a byte that need not move), halving the interval a few times
+            // (every byte of it is a byte that need not move), halving the interval a few times; fewer times
+            // for long traces, where one attempt takes seconds
             uint64_t lo = pc, hi = r > 0 ? pc + step : pc;
-            for (int i = 0; i < 4 && hi - lo >= 512; ++i) {
+            const int halvings = t.n_kernels <= 4096 ? 4 : t.n_kernels <= 16384 ? 2 : 0;
+            for (int i = 0; i < halvings && hi - lo >= 512; ++i) {
                 const uint64_t mid = (lo + (hi - lo) / 2) / 256 * 256;
                 Plan q;
                 if (attempt(mid, q)) { lo = mid; p = std::move(q); } else hi = mid;
