@@ -30,6 +30,7 @@ ATTN_OPS = (4, 17)
 HBM_CLASSES = {"norm": (1, 14, 15), "activation": (5, 6, 12, 13), "rope": (3, 18), "cross_entropy": (7,),
                "embedding": (0, 19, 20), "adamw": (21,)}
 PEAK_BF16_TFLOPS = 2500.0
+PEAK_FP32_VECTOR_TFLOPS = 157.3
 # L2 <-> fabric bytes per GEMM launch from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this command
 # (profiles/gpt2_small_bf16_step_pmc_traffic.txt); None where no such run has been made
 GEMM_TRAFFIC_BYTES_PER_LAUNCH = {"gpt2_small_bf16": 149.68e6}
@@ -296,6 +297,8 @@ def main():
             hbm[label] = {"GBps": kb[sel].sum() / ktimes[sel].sum(), "GBps_without_migration": kb[sel].sum() / float(tau[sel].sum()),
                           "ms_per_step": ktimes[sel].sum() / 1e6, "launches": int(sel.sum())}
     gemm_tflops = gemm_flops / gemm_ns / 1e3
+    bf16 = cfg["precision"] == "bf16"
+    gemm_peak = PEAK_BF16_TFLOPS if bf16 else PEAK_FP32_VECTOR_TFLOPS
     attn_tflops = flops[attn].sum() / ktimes[attn].sum() / 1e3
     comp_s = ktimes.sum() / 1e9
     mig_bound_s = (pe["bytes_per_direction"] * (2 if shared else 1) / bw) if bw else 0.0
@@ -326,9 +329,11 @@ def main():
         "attention_tflops": attn_tflops, "loss": loss,
         "hbm_kernels": {"peak_GBps": 8000.0, "bytes": "operand tensor sizes, counted once per read and once per write",
                         "classes": hbm},
-        "roofline": {"bound": "mfma", "kernel": "gemm_bf16_pipe_k (forward, dX and dW contractions)",
-                     "achieved": gemm_tflops, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": gemm_tflops / PEAK_BF16_TFLOPS, "traffic": GEMM_TRAFFIC_BYTES_PER_LAUNCH.get(args.workload),
+        # fp32 workloads (the tiny parity configurations) run the contractions on the fp32 vector ALU
+        "roofline": {"bound": "mfma" if bf16 else "alu",
+                     "kernel": ("gemm_bf16_pipe_k" if bf16 else "gemm_f32_k") + " (forward, dX and dW contractions)",
+                     "achieved": gemm_tflops, "peak": gemm_peak, "unit": "TFLOP/s",
+                     "frac": gemm_tflops / gemm_peak, "traffic": GEMM_TRAFFIC_BYTES_PER_LAUNCH.get(args.workload),
                      "traffic_unit": "bytes per launch missing the L2 (rocprofv3 FETCH_SIZE + WRITE_SIZE, calibrated)",
                      "algorithmic_bytes_per_launch": gemm_bytes / n_gemm,
                      "launches_per_step": n_gemm, "avg_launch_us": gemm_ns / n_gemm / 1e3,
