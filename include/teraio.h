@@ -256,7 +256,11 @@ int tio_set_slow_tier_bw(tio_ctx *ctx, uint64_t bytes_per_s);
  * synchronises before each optimizer launch); TIO_STEP_TIME_KERNELS brackets every launch with HIP
  * events on the compute stream (see tio_kernel_times); TIO_STEP_TIMELINE additionally stamps every
  * migration (see tio_step_timeline).
- * Blocks until the compute stream has finished the iteration (copies may still be in flight). */
+ * Blocks until the compute stream has finished the iteration (copies may still be in flight).
+ * Errors found before the first launch (null or out-of-vocabulary ids, a parameter never loaded, a plan that is
+ * stale, invalid or too large for the arena or the pools) leave the context as it was.  TIO_ERR_HIP or TIO_ERR_IO
+ * from inside the iteration leaves tensors half updated: every later step on the context returns TIO_ERR_HIP and
+ * the caller destroys it. */
 enum { TIO_STEP_CAPTURE_GRADS = 1, TIO_STEP_TIME_KERNELS = 2, TIO_STEP_TIMELINE = 4 };
 int tio_train_step(tio_ctx *ctx, const int32_t *tokens, const int32_t *labels,
                    const tio_plan *plan, int32_t flags, tio_step_stats *out);

@@ -75,6 +75,7 @@ struct tio_ctx {
 
     Plan plan;                                           // installed plan (copy)
     bool installed = false, params_dirty = true;
+    bool failed = false;                                 // a step stopped half-way (HIP or I/O error): tensor state unknown
     std::vector<uint8_t> loaded;                         // per parameter: tio_params_load has been called
     std::vector<uint8_t> on_dev;                         // per persistent tensor: latest version is in the arena
     std::vector<uint64_t> dev_addr;
@@ -200,7 +201,24 @@ void install_plan(tio_ctx *c, const Plan &p) {
         throw PlanError{TIO_ERR_OOM_HOST, "plan needs " + std::to_string(p.host_tier_needed) +
                                               " bytes of a host-memory tier with its two streams, context has " +
                                               std::to_string(c->host1 ? c->rt.host_tier_bytes : 0)};
+    const int np = c->prog.n_persistent;
+    for (int t = 0; t < np; ++t)
+        if (p.persistent_home[t] != c->home[t]) throw PlanError{TIO_ERR_PLAN_INVALID, "home slot mismatch"};
+    std::vector<std::vector<uint64_t>> ptrs(N, std::vector<uint64_t>(kMaxRoles, UINT64_MAX));
+    for (int k = 0; k < N; ++k)
+        for (int r = 0; r < kMaxRoles; ++r) {
+            const int t = c->prog.kernels[k].t[r];
+            if (t < 0) continue;
+            const uint64_t a = address_at(p, t, k);
+            if (a == UINT64_MAX) throw PlanError{TIO_ERR_PLAN_INVALID, "operand not resident at kernel " + std::to_string(k)};
+            if (a + c->prog.tensors[t].bytes > c->arena_usable) throw PlanError{TIO_ERR_PLAN_INVALID, "address outside the arena"};
+            ptrs[k][r] = a;
+        }
+    // Everything that can reject the plan has been checked.  From here on the context has no plan until the new one
+    // is complete: if a step below fails, the latest version of every persistent tensor is in its home slot (that is
+    // what gather_to_home leaves) and the next call installs from there.
     gather_to_home(c);
+    c->installed = false;
     if (c->ft) {
         c->ft->resize(file_needed);
         c->ft->set_pairs((int)p.pairs.size());
@@ -209,14 +227,11 @@ void install_plan(tio_ctx *c, const Plan &p) {
     if (c->pp0) c->pp0->set_pairs((int)p.pairs.size());
     if (c->pp1) c->pp1->set_pairs((int)p.pairs.size());
     c->plan = p;
-    c->installed = true;
-    const int np = c->prog.n_persistent;
     c->on_dev.assign(np, 0);
     c->dev_addr.assign(np, 0);
     c->in_host1.assign(np, 0);
     c->host1_off.assign(np, 0);
     for (int t = 0; t < np; ++t) {
-        if (p.persistent_home[t] != c->home[t]) throw PlanError{TIO_ERR_PLAN_INVALID, "home slot mismatch"};
         const uint64_t a = address_at(p, t, 0);
         if (a == UINT64_MAX) continue;
         // resident at the iteration boundary unless a prefetch issued at trigger 0 brings it in
@@ -231,16 +246,7 @@ void install_plan(tio_ctx *c, const Plan &p) {
         c->dev_addr[t] = a;
     }
     if (c->pool_dev) HIPCHK(hipDeviceSynchronize());     // see gather_to_home
-    c->ptrs.assign(N, std::vector<uint64_t>(kMaxRoles, UINT64_MAX));
-    for (int k = 0; k < N; ++k)
-        for (int r = 0; r < kMaxRoles; ++r) {
-            const int t = c->prog.kernels[k].t[r];
-            if (t < 0) continue;
-            const uint64_t a = address_at(p, t, k);
-            if (a == UINT64_MAX) throw PlanError{TIO_ERR_PLAN_INVALID, "operand not resident at kernel " + std::to_string(k)};
-            if (a + c->prog.tensors[t].bytes > c->arena_usable) throw PlanError{TIO_ERR_PLAN_INVALID, "address outside the arena"};
-            c->ptrs[k][r] = a;
-        }
+    c->ptrs = std::move(ptrs);
     make_events(c->ev_kernel, N, false);
     make_events(c->ev_off, p.pairs.size(), false);
     make_events(c->ev_pre, p.pairs.size(), false);
@@ -252,6 +258,7 @@ void install_plan(tio_ctx *c, const Plan &p) {
     c->off_seq.assign(p.pairs.size(), 0);
     c->pre_seq.assign(p.pairs.size(), 0);
     c->ev_off_user.assign(p.pairs.size(), MigrationEngine::Dep{nullptr, -1, 0});
+    c->installed = true;
     c->params_dirty = false;
 }
 
@@ -325,15 +332,19 @@ void capture_grad(tio_ctx *c, int k) {
 }
 
 // one iteration; timing != nullptr: per-kernel elapsed ns measured with events
-void run_step(tio_ctx *c, const int32_t *tokens, const int32_t *labels, bool capture, std::vector<int64_t> *timing,
-              tio_step_stats *st) {
-    const int N = c->trace.n_kernels;
-    const Plan &p = c->plan;
+void check_ids(const tio_ctx *c, const int32_t *tokens, const int32_t *labels) {
     const int64_t S = (int64_t)c->cfg.batch * c->cfg.seq_len;
     for (int64_t i = 0; i < S; ++i) {
         if (tokens[i] < 0 || tokens[i] >= c->cfg.vocab || labels[i] < 0 || labels[i] >= c->cfg.vocab)
             throw PlanError{TIO_ERR_INVALID_ARG, "token or label id outside the vocabulary"};
     }
+}
+
+void run_step_body(tio_ctx *c, const int32_t *tokens, const int32_t *labels, bool capture, std::vector<int64_t> *timing,
+                   tio_step_stats *st) {
+    const int N = c->trace.n_kernels;
+    const Plan &p = c->plan;
+    const int64_t S = (int64_t)c->cfg.batch * c->cfg.seq_len;
     if (capture) c->grads.assign(c->prog.params.size(), {});
     if (timing) { if ((int)c->ev_t0.size() != N) { make_events(c->ev_t0, N, true); make_events(c->ev_t1, N, true); } }
     const bool tl = c->timeline && timing;
@@ -506,6 +517,24 @@ void run_step(tio_ctx *c, const int32_t *tokens, const int32_t *labels, bool cap
             for (size_t i = 0; i < p.entries.size(); ++i)
                 if (issued[i]) (p.entries[i].kind == TIO_OFFLOAD ? st->d2h_busy_ns : st->h2d_busy_ns) += c->tl_c1[i] - c->tl_c0[i];
     }
+}
+
+// An error after the first launch leaves tensors half updated and transfers in flight: the context refuses further
+// steps from then on.
+void run_step(tio_ctx *c, const int32_t *tokens, const int32_t *labels, bool capture, std::vector<int64_t> *timing,
+              tio_step_stats *st) {
+    try {
+        run_step_body(c, tokens, labels, capture, timing, st);
+    } catch (...) {
+        c->failed = true;
+        throw;
+    }
+}
+
+// ids are validated, and a context that failed earlier is refused, before anything is touched
+void step_preconditions(const tio_ctx *c, const int32_t *tokens, const int32_t *labels) {
+    if (c->failed) throw PlanError{TIO_ERR_HIP, "an earlier step on this context stopped with an error: destroy the context"};
+    check_ids(c, tokens, labels);
 }
 
 const Plan &uncapped_plan(tio_ctx *c) {
@@ -734,6 +763,7 @@ int tio_train_step(tio_ctx *c, const int32_t *tokens, const int32_t *labels, con
     TIO_RT_BEGIN
     for (size_t i = 0; i < c->loaded.size(); ++i)
         if (!c->loaded[i]) return fail(TIO_ERR_INVALID_ARG, "parameter " + c->prog.params[i].name + " was never loaded");
+    step_preconditions(c, tokens, labels);
     ensure_plan(c, plan);
     c->timeline = (flags & TIO_STEP_TIMELINE) != 0;
     run_step(c, tokens, labels, (flags & TIO_STEP_CAPTURE_GRADS) != 0,
@@ -759,6 +789,7 @@ int tio_profile_iteration(tio_ctx *c, const int32_t *tokens, const int32_t *labe
         for (size_t i = 0; i < c->loaded.size(); ++i)
             if (!c->loaded[i]) { delete h; return fail(TIO_ERR_INVALID_ARG, "parameter " + c->prog.params[i].name + " was never loaded"); }
         try {
+            step_preconditions(c, tokens, labels);
             tio_plan under_cap;
             if (mode == TIO_PROFILE_OFFLOADED) {
                 // the iteration does not fit the arena: run it under a plan made from the modelled times

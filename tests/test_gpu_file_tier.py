@@ -197,3 +197,47 @@ def test_file_tier_errors(tmp_path):
     with pytest.raises(tio.TioError):
         ctx.tio_file_tier_info()
     ctx.close()
+
+
+def test_write_failure_inside_a_step(tmp_path):
+    """A write to the slow-tier file that fails while an iteration runs (here: the process's file-size limit is
+    lowered below the ranges of the migrated activations, so the kernel refuses those writes) ends the step with
+    TIO_ERR_IO, every kernel already launched still completes, the context refuses further steps, can be destroyed,
+    and a fresh context on the same file trains normally."""
+    import resource
+    import signal
+    import paper_2506_06472_amd as tio
+    cfg = BF16
+    params, tok, lab = make_inputs(cfg, seed=5)
+    lt, ll, up, cp, peak = _plans(cfg, 0.4, 2 * 10**9)
+    ce = cp.export()
+    np_ = lt.export()["n_persistent"]
+    assert any(t >= np_ for t, *_ in ce["entries"])
+    l0, _ = _reference(cfg, params, tok, lab, up, 1)
+    path = str(tmp_path / "slow_tier.bin")
+    ctx = tio.tio_ctx_create(cfg, ce["cap"], FILE_LIMIT, 0, slow_tier_file=path, staging_bytes=4 << 20,
+                             file_chunk_bytes=256 << 10)
+    ctx.tio_params_load(params)
+    home = ctx.tio_file_tier_info()["file_bytes"]          # persistent tensors only: the activations' ranges follow
+    assert ctx.tio_train_step(tok, lab, cp)["loss"] == l0[0]
+    assert ctx.tio_file_tier_info()["file_bytes"] > home
+    old_limit = resource.getrlimit(resource.RLIMIT_FSIZE)
+    old_handler = signal.signal(signal.SIGXFSZ, signal.SIG_IGN)      # the refused write reports EFBIG instead
+    try:
+        resource.setrlimit(resource.RLIMIT_FSIZE, (home, old_limit[1]))
+        with pytest.raises(tio.TioError) as ei:
+            for _ in range(3):          # the failing write may be noticed only at the next request or at the step's end
+                ctx.tio_train_step(tok, lab, cp)
+        assert ei.value.code == -9, ei.value
+    finally:
+        resource.setrlimit(resource.RLIMIT_FSIZE, old_limit)
+        signal.signal(signal.SIGXFSZ, old_handler)
+    with pytest.raises(tio.TioError) as ei:
+        ctx.tio_train_step(tok, lab, cp)
+    assert ei.value.code == -6 and "destroy" in str(ei.value)
+    ctx.close()
+    ctx = tio.tio_ctx_create(cfg, ce["cap"], FILE_LIMIT, 0, slow_tier_file=path, staging_bytes=4 << 20,
+                             file_chunk_bytes=256 << 10)
+    ctx.tio_params_load(params)
+    assert ctx.tio_train_step(tok, lab, cp)["loss"] == l0[0]
+    ctx.close()
