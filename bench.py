@@ -98,6 +98,44 @@ def probe_file_bw(path, total=2 << 30, block=8 << 20, threads=4):
     return {"write_Bps": w, "read_Bps": r, "duplex_write_Bps": res["w"], "duplex_read_Bps": res["r"], "direct": direct}
 
 
+def planner_times(names=("tiny_gpt_fp32", "gpt2_small_bf16", "llama_7b_bf16", "llama_13b_bf16", "llama_30b_bf16")):
+    """CPU only: wall time of lifetime analysis + Algorithm 1 in the library and in the oracle, on the canonical
+    traces of the five workloads with modelled kernel times, each at its stated capacity and bandwidth.  The
+    library's planner also assigns addresses and lowers the planning capacity until the layout fits the arena
+    (library_search_s: everything); the oracle runs Algorithm 1 once at the capacity the library settled on
+    (oracle_single_s), and the library is timed on that single pass as well (library_single_s: unlimited arena).
+    The single passes must give the same entries.  One JSON line."""
+    import paper_2506_06472_amd as tio
+    from oracle import plan as op, trace as ot
+    from synth import CONFIGS
+    rows = []
+    for name in names:
+        cfg = CONFIGS[name]
+        bw = cfg.get("slow_tier_bw", 25 * 10**9)
+        lt = tio.tio_trace_build(cfg)
+        t0 = time.perf_counter()
+        ll = tio.tio_analyze_lifetimes(lt)
+        cap = cfg.get("cap_bytes") or int(int(ll.export()["M"].max()) * cfg["cap_frac"])
+        pe = tio.tio_build_plan(lt, ll, cap, bw, min_bytes=1 << 20).export()
+        t1 = time.perf_counter()
+        single = tio.tio_build_plan(lt, ll, pe["planning_cap"], bw, min_bytes=1 << 20, arena_bytes=2**62).export()
+        t2 = time.perf_counter()
+        tr = ot.build_trace(cfg)
+        t3 = time.perf_counter()
+        ref = op.build_plan(tr, op.analyze_lifetimes(tr), pe["planning_cap"], bw, min_bytes=1 << 20)
+        t4 = time.perf_counter()
+        same = single["entries"] == ref["entries"] and pe["entries"] == ref["entries"]
+        rows.append({"workload": name, "kernels": int(lt.export()["n_kernels"]), "entries": len(pe["entries"]),
+                     "cap_bytes": int(cap), "planning_cap_bytes": int(pe["planning_cap"]),
+                     "library_search_s": t1 - t0, "library_single_s": t2 - t1, "oracle_single_s": t4 - t3,
+                     "same_plan": bool(same)})
+        print(f"{name}: library {t1 - t0:.3f} s (search) / {t2 - t1:.3f} s (one pass), oracle {t4 - t3:.2f} s (one pass), "
+              f"same plan {same}", file=sys.stderr, flush=True)
+    out = {"planner_wall_time": rows, "cores": 1, "kernel_times": "modelled"}
+    print(json.dumps(out))
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -127,7 +165,12 @@ def main():
     ap.add_argument("--micro-batches", type=int, default=1,
                     help="n > 1: a step is n micro-batches of the workload's batch with gradient accumulation and one "
                          "AdamW update (n times the tokens per step, same memory cap); not the headline configuration")
+    ap.add_argument("--planner-times", action="store_true",
+                    help="no GPU: time the library's and the oracle's planner on the five workloads' traces and exit")
     args = ap.parse_args()
+    if args.planner_times:
+        planner_times()
+        return
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (no collectives, no sharding); use --gpus 1", file=sys.stderr)
         sys.exit(2)

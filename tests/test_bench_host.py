@@ -26,3 +26,16 @@ def test_file_bandwidth_probe(tmp_path):
 def test_more_than_one_gpu_is_refused_without_a_gpu():
     r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "4"], capture_output=True, text=True, timeout=120)
     assert r.returncode == 2 and "one GPU" in r.stderr and r.stdout.strip() == ""
+
+
+def test_planner_times_compare_like_with_like(capsys):
+    """bench.py --planner-times: the library's full search, its single pass and the oracle's single pass at the settled
+    planning capacity give one entry list; times are positive; the line is JSON."""
+    import json
+    import bench
+    out = bench.planner_times(names=("tiny_gpt_fp32", "tiny_llama_fp32"))
+    line = [l for l in capsys.readouterr().out.splitlines() if l.startswith("{")][-1]
+    assert json.loads(line)["planner_wall_time"][0]["workload"] == "tiny_gpt_fp32"
+    for r in out["planner_wall_time"]:
+        assert r["same_plan"] and r["entries"] > 0 and r["planning_cap_bytes"] <= r["cap_bytes"]
+        assert r["library_search_s"] > 0 and r["library_single_s"] > 0 and r["oracle_single_s"] > 0
