@@ -393,14 +393,31 @@ def main():
     log('capped ms/step', step_s * 1e3, 'loss', loss)
     if not args.no_cpu_baseline:
         from oracle import model as om
-        if not small:
-            raise SystemExit("the CPU oracle baseline is only timed for workloads below 1e9 parameters: pass --no-cpu-baseline")
-        sample = dict(cfg, B=1)
-        stok, slab = tok[:1], lab[:1]
-        tr = om.Trainer(sample, params, dtype=np.float64)
-        tc = time.perf_counter()
-        tr.step(stok, slab)
-        cpu_s = time.perf_counter() - tc
+        if small:
+            sample = dict(cfg, B=1)
+            stok, slab = tok[:1], lab[:1]
+            tr = om.Trainer(sample, params, dtype=np.float64)
+            tc = time.perf_counter()
+            tr.step(stok, slab)
+            cpu_s = time.perf_counter() - tc
+            what = (f"one full step (forward, backward, AdamW, fp64 numpy) of the same model on 1 of the "
+                    f"{cfg['B']} sequences ({cfg['T']} tokens), {cpu_s:.1f} s")
+        else:
+            # one decoder layer at the workload's widths (small vocabulary, so that embedding and head are negligible),
+            # one sequence; the step of the whole model is taken as n_layers times that: an extrapolation
+            sample = dict(cfg, L=1, V=1024, B=1)
+            sample.pop("micro_batches", None)
+            sspecs = [(n, (r, c) if r > 1 else (c,), "normal" if (r > 1) else ("ones" if n.endswith("_g") else "zeros"))
+                      for n, r, c in tio.tio_param_list(sample)]
+            sparams = gen_params(sspecs, 0)
+            stok, slab = gen_tokens(1, cfg["T"], 1024, 0)
+            tr = om.Trainer(sample, sparams, dtype=np.float64)
+            tc = time.perf_counter()
+            tr.step(stok, slab)
+            cpu_s = (time.perf_counter() - tc) * cfg["L"]
+            what = (f"EXTRAPOLATED: one decoder layer of the workload's widths (forward, backward, AdamW, fp64 numpy, "
+                    f"vocabulary 1024) on one sequence of {cfg['T']} tokens took {cpu_s / cfg['L']:.1f} s; times "
+                    f"{cfg['L']} layers, embedding and head left out")
         try:
             from threadpoolctl import threadpool_info
             cores = max([p.get("num_threads", 1) for p in threadpool_info() if p.get("user_api") == "blas"] or [1])
@@ -408,8 +425,7 @@ def main():
             cores = len(os.sched_getaffinity(0))
         out["cpu_baseline"] = {"value": cfg["T"] / cpu_s, "unit": "tokens/s", "cores": cores,
                                "kind": "oracle",
-                               "sample": f"one full step (forward, backward, AdamW, fp64 numpy) of the same model on 1 of the "
-                                         f"{cfg['B']} sequences ({cfg['T']} tokens), {cpu_s:.1f} s"}
+                               "sample": what}
     print(json.dumps(out))
 
 
