@@ -287,6 +287,19 @@ int tio_op_gemm(void *stream, int32_t dtype, int32_t a_kmajor, int32_t b_kmajor,
                 const void *A, int64_t lda, const void *B, int64_t ldb,
                 const void *bias, const void *resid, int64_t ldr, void *C, int64_t ldc, void *rowsum,
                 void *workspace, int32_t splits);
+/* For callers that cannot allocate device memory (code under HIP graph capture, tight serving loops, harnesses
+ * that forbid hipMalloc): tio_op_gemm without bias / residual, whose split-contraction partial tiles go to a
+ * fixed 64 MiB (67108864-byte) array in the library's device image instead of a caller workspace.  It allocates
+ * nothing; every GPU the library runs on holds its own copy of that array until the process ends.
+ * TIO_ERR_INVALID_ARG when splits > 1 and splits*(M*N+M) floats exceed the array, otherwise the arguments,
+ * the checks and the result are those of tio_op_gemm (bit for bit: the same kernels run).  Nothing in the array
+ * has to start at zero (every partial tile is written before the reduction launch reads it) and its contents
+ * after the call are unspecified.  All calls on one GPU share the array: calls whose launches may overlap on
+ * that GPU (different streams, different threads) race; serialise them on one stream. */
+int tio_op_gemm_static_ws(void *stream, int32_t dtype, int32_t a_kmajor, int32_t b_kmajor,
+                          int64_t M, int64_t N, int64_t K,
+                          const void *A, int64_t lda, const void *B, int64_t ldb,
+                          void *C, int64_t ldc, void *rowsum, int32_t splits);
 /* Causal self-attention on a packed qkv buffer [B*T, 3*H*dh] (q | k | v, heads side by side):
  * o [B*T, H*dh] = softmax(q k^T / sqrt(dh)) v per head, lse [B*H*T] fp32 = log-sum-exp of the scaled
  * scores.  With dO != NULL also the backward pass: delta [B*H*T] fp32 (work buffer, receives

@@ -427,6 +427,15 @@ def tio_op_gemm(stream_handle, dtype, a_kmajor, b_kmajor, M, N, K, A_ptr, lda, B
                              vp(resid_ptr), C.c_int64(ldr), vp(C_ptr), C.c_int64(ldc), vp(rowsum_ptr), vp(workspace_ptr), int(splits)))
 
 
+def tio_op_gemm_static_ws(stream_handle, dtype, a_kmajor, b_kmajor, M, N, K, A_ptr, lda, B_ptr, ldb, C_ptr, ldc,
+                          rowsum_ptr=0, splits=1):
+    """tio_op_gemm with the split-contraction partials in the library's fixed device array; allocates nothing."""
+    vp = lambda p: C.c_void_p(p) if p else None
+    _check(lib().tio_op_gemm_static_ws(vp(stream_handle), PREC[dtype], int(a_kmajor), int(b_kmajor), C.c_int64(M),
+                                       C.c_int64(N), C.c_int64(K), vp(A_ptr), C.c_int64(lda), vp(B_ptr), C.c_int64(ldb),
+                                       vp(C_ptr), C.c_int64(ldc), vp(rowsum_ptr), int(splits)))
+
+
 def tio_op_attention(stream_handle, dtype, B, T, H, dh, qkv_ptr, o_ptr, lse_ptr, dO_ptr=0, delta_ptr=0, dqkv_ptr=0):
     vp = lambda p: C.c_void_p(p) if p else None
     _check(lib().tio_op_attention(vp(stream_handle), PREC[dtype], C.c_int64(B), C.c_int64(T), C.c_int64(H), C.c_int64(dh),

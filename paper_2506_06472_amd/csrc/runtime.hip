@@ -18,6 +18,7 @@
 #include <cstdlib>
 #include <cstring>
 #include <memory>
+#include <mutex>
 #include <string>
 #include <thread>
 #include <vector>
@@ -831,6 +832,51 @@ int tio_op_gemm(void *stream, int32_t dtype, int32_t a_km, int32_t b_km, int64_t
     k::gemm((hipStream_t)stream, dtype, a_km != 0, b_km != 0, M, N, K, A, lda, B, ldb, bias, resid, ldr, C, ldc, rowsum, workspace, splits);
     HIPCHK(hipGetLastError());
     return TIO_OK;
+    TIO_RT_END
+}
+
+// ---- split-contraction product for callers that cannot allocate ------------------------------------------------
+// The fp32 partial tiles go to a fixed array in device memory instead of a workspace from the caller.  In host
+// code the array's name is only a handle for hipGetSymbolAddress: every device has its own copy at its own address,
+// looked up once per device (with that device current) and kept.
+namespace {
+constexpr uint64_t kStaticWsBytes = (uint64_t)64 << 20;
+constexpr int kMaxDevices = 64;
+}  // namespace
+static __device__ __align__(256) unsigned char scratch[kStaticWsBytes];
+namespace {
+std::mutex g_scratch_mu;
+void *g_scratch_ptr[kMaxDevices] = {};
+
+// device address of `scratch` on the current device
+void *static_workspace() {
+    int dev = -1;
+    HIPCHK(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) throw PlanError{TIO_ERR_HIP, "device ordinal beyond the table of static workspaces"};
+    std::lock_guard<std::mutex> lock(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        HIPCHK(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p) throw PlanError{TIO_ERR_HIP, "hipGetSymbolAddress returned no address for the static workspace"};
+        g_scratch_ptr[dev] = p;
+    }
+    return g_scratch_ptr[dev];
+}
+}  // namespace
+
+extern "C" int tio_op_gemm_static_ws(void *stream, int32_t dtype, int32_t a_km, int32_t b_km, int64_t M, int64_t N, int64_t K,
+                                     const void *A, int64_t lda, const void *B, int64_t ldb, void *C, int64_t ldc, void *rowsum,
+                                     int32_t splits) {
+    TIO_RT_BEGIN
+    if (M < 1 || N < 1 || K < 1) return fail(TIO_ERR_INVALID_ARG, "non-positive dimension");
+    if (splits < 1 || splits > 64) return fail(TIO_ERR_INVALID_ARG, "splits must be in 1..64");
+    // the same layout tio_op_gemm asks of its workspace: splits * (M*N + M) floats
+    const unsigned __int128 need = (unsigned __int128)splits * ((unsigned __int128)M * N + M) * 4;
+    if (splits > 1 && need > kStaticWsBytes)
+        return fail(TIO_ERR_INVALID_ARG, "splits*(M*N+M) floats exceed the static workspace of " + std::to_string(kStaticWsBytes) +
+                                             " bytes: use tio_op_gemm with a workspace of the caller's");
+    void *ws = splits > 1 ? static_workspace() : nullptr;
+    return tio_op_gemm(stream, dtype, a_km, b_km, M, N, K, A, lda, B, ldb, nullptr, nullptr, 0, C, ldc, rowsum, ws, splits);
     TIO_RT_END
 }
 
