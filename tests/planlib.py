@@ -51,6 +51,16 @@ def load_golden(name):
     return tr, cap, bw, entries, Mp, err
 
 
+def golden_options(name):
+    """Planner options a golden file states beside the fields of load_golden (currently: min_bytes)."""
+    out = {}
+    for line in open(os.path.join(GOLDEN, name)):
+        w = line.split("#")[0].split()
+        if w and w[0] == "min_bytes":
+            out["min_bytes"] = int(w[1])
+    return out
+
+
 def load_golden_two_tier(name):
     """Golden file with a host tier: the fields of load_golden plus host_bw, host_budget and the tier of each pair."""
     tr, cap, bw, entries, Mp, err = load_golden(name)

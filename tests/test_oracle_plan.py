@@ -9,19 +9,21 @@ from oracle import replay as orp
 from oracle import trace as ot
 from oracle.model import param_specs
 from synth import CONFIGS
-from planlib import load_golden, mini_trace, random_trace
+from planlib import golden_options, load_golden, mini_trace, random_trace
 
 
 # ------------------------------------------------------------------ hand-worked cases
-@pytest.mark.parametrize("name", ["plan_example_a.txt", "plan_example_b.txt", "plan_example_c.txt"])
+@pytest.mark.parametrize("name", ["plan_example_a.txt", "plan_example_b.txt", "plan_example_c.txt", "plan_example_e.txt",
+                                  "plan_example_f.txt"])
 def test_hand_worked_examples(name):
     tr, cap, bw, entries, Mp, err = load_golden(name)
+    kw = golden_options(name)
     life = op.analyze_lifetimes(tr)
     if err:
         with pytest.raises(ValueError):
-            op.build_plan(tr, life, cap, bw)
+            op.build_plan(tr, life, cap, bw, **kw)
         return
-    pl = op.build_plan(tr, life, cap, bw)
+    pl = op.build_plan(tr, life, cap, bw, **kw)
     assert pl["entries"] == entries
     assert pl["Mp"] == Mp
     orp.check_plan(tr, life, pl, cap)

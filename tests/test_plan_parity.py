@@ -7,7 +7,7 @@ from oracle import plan as op
 from oracle import replay as orp
 from oracle import trace as ot
 from synth import CONFIGS
-from planlib import load_golden, random_trace
+from planlib import golden_options, load_golden, random_trace
 
 
 def lib_trace_from_oracle(tr):
@@ -69,12 +69,12 @@ def test_trace_and_lifetimes_bit_exact(name):
     assert [(n, int(np.prod(s))) for n, s, _ in param_specs(cfg)] == [(n, r * c) for n, r, c in tio.tio_param_list(cfg)]
 
 
-@pytest.mark.parametrize("name", ["plan_example_a.txt", "plan_example_c.txt"])
+@pytest.mark.parametrize("name", ["plan_example_a.txt", "plan_example_c.txt", "plan_example_e.txt", "plan_example_f.txt"])
 def test_golden_examples_through_the_c_abi(name):
     tr, cap, bw, entries, Mp, _ = load_golden(name)
     lt = lib_trace_from_oracle(tr)
     ll = tio.tio_analyze_lifetimes(lt)
-    pl = tio.tio_build_plan(lt, ll, cap, bw, arena_bytes=1 << 20).export()
+    pl = tio.tio_build_plan(lt, ll, cap, bw, arena_bytes=1 << 20, **golden_options(name)).export()
     assert pl["planning_cap"] == cap and pl["entries"] == entries and pl["Mp"] == Mp
 
 
