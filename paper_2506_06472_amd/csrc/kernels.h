@@ -23,6 +23,12 @@ void norm_fwd(hipStream_t s, int dtype, bool rms, const void *x, const void *g, 
 bool gemm_bf16_pipelined(hipStream_t s, int cfg, bool a_km, bool b_km, int64_t M, int64_t N, int64_t K, const void *A,
                          int64_t lda, const void *B, int64_t ldb, const void *bias, const void *resid, int64_t ldr,
                          void *C, int64_t ldc, void *rowsum, float *ws, int splits, bool rowsum_accumulate);
+// bf16 MFMA GEMM whose operand tiles are loaded from global memory straight into LDS (kernels_gemm_dl.hip); same
+// arguments and tile configurations as gemm_bf16_pipelined.  Returns false without launching when K is not a multiple of 8
+// (a partly valid 16-byte chunk cannot be masked on its way into LDS) or an operand is too large for 32-bit offsets.
+bool gemm_bf16_direct(hipStream_t s, int cfg, bool a_km, bool b_km, int64_t M, int64_t N, int64_t K, const void *A,
+                      int64_t lda, const void *B, int64_t ldb, const void *bias, const void *resid, int64_t ldr,
+                      void *C, int64_t ldc, void *rowsum, float *ws, int splits, bool rowsum_accumulate);
 void gemm(hipStream_t s, int dtype, bool a_km, bool b_km, int64_t M, int64_t N, int64_t K, const void *A,
           int64_t lda, const void *B, int64_t ldb, const void *bias, const void *resid, int64_t ldr, void *C,
           int64_t ldc, void *rowsum, void *workspace, int splits, bool accumulate = false);

@@ -1,6 +1,7 @@
 // Dense contractions of the training step: C[M,N] = A . B^T (+bias) (+residual).
 //
-// bf16: the pipelined MFMA kernel of kernels_gemm_pipe.hip does the work; this file holds the dispatch,
+// bf16: the MFMA kernel of kernels_gemm_dl.hip (operand tiles loaded straight into LDS) does the work, the pipelined
+// kernel of kernels_gemm_pipe.hip (tiles staged through registers) where that one does not apply; this file holds the dispatch,
 // the split-K reduction and a plain MFMA kernel with 64-bit addressing that takes over when an operand is
 // too large for the pipelined kernel's 32-bit buffer offsets.  In the plain kernel a workgroup owns a
 // BM x BN tile of C; both operand tiles are staged through LDS in [row][k] order with a 16-byte row
@@ -322,6 +323,12 @@ static int gemm_cfg_override() {
     return v;
 }
 
+static bool gemm_direct_enabled() {
+    static int v = -1;
+    if (v < 0) { const char *e = getenv("TIO_GEMM_DIRECT"); v = e ? (atoi(e) != 0) : 1; }
+    return v != 0;
+}
+
 void gemm(hipStream_t s, int dtype, bool a_km, bool b_km, int64_t M, int64_t N, int64_t K, const void *A, int64_t lda,
           const void *B, int64_t ldb, const void *bias, const void *resid, int64_t ldr, void *C, int64_t ldc,
           void *rowsum, void *workspace, int splits, bool accumulate) {
@@ -348,8 +355,13 @@ void gemm(hipStream_t s, int dtype, bool a_km, bool b_km, int64_t M, int64_t N, 
         const bool large = splits <= 1 && fill(big_tiles, 256) >= 0.8 * fill(small_tiles, 512);
         const int ov = gemm_cfg_override();
         const int pipe_cfg = ov == 1 ? 0 : ov == 2 ? 1 : (large ? 1 : 0);
-        if (ov != 0 && gemm_bf16_pipelined(s, pipe_cfg, a_km, b_km, M, N, K, A, lda, B, ldb, bias, resid, ldr, C, ldc, rowsum,
-                                           splits > 1 ? (float *)workspace : nullptr, splits, accumulate)) {
+        // first choice: operand tiles straight from global memory into LDS; the kernel that stages them through
+        // registers takes the products it refuses (K not a multiple of 8); TIO_GEMM_DIRECT=0 switches the first one off
+        float *const wsp = splits > 1 ? (float *)workspace : nullptr;
+        if (ov != 0 && ((gemm_direct_enabled() && gemm_bf16_direct(s, pipe_cfg, a_km, b_km, M, N, K, A, lda, B, ldb, bias, resid, ldr, C,
+                                                                   ldc, rowsum, wsp, splits, accumulate)) ||
+                        gemm_bf16_pipelined(s, pipe_cfg, a_km, b_km, M, N, K, A, lda, B, ldb, bias, resid, ldr, C, ldc, rowsum, wsp,
+                                            splits, accumulate))) {
             if (splits > 1) {
                 const int64_t n = M * (N / 4) + (rowsum ? M : 0);
                 splitk_reduce_k<<<(unsigned)((n + 255) / 256), 256, 0, s>>>((const float *)workspace, (uint16_t *)C, ldc, (uint16_t *)rowsum, M, N, splits, (int)accumulate);
