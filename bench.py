@@ -1,11 +1,13 @@
 #!/usr/bin/env python3
 """Benchmark of the capped-memory training step on one MI355X.
 
-Workload: GPT-2-small-shaped decoder, bf16 mixed precision with fp32 master weights and AdamW,
-12 layers, d=768, seq 1024, batch 8 (8192 tokens per step), memory cap = 40 % of the uncapped
-peak, synthetic seeded weights and tokens.  One step = forward, backward, AdamW under the plan,
-with the slow tier (pinned host memory) paced to --bw bytes/s per direction.  --slow-tier file puts the
-slow tier into a file instead (direct I/O at whatever the file system delivers; probed first).
+Default workload: the largest of the five that one GPU holds with its slow-tier pool, the Llama-7B-shaped decoder
+(32 layers, d=4096, 32 heads, SwiGLU 11008, vocabulary 32000, seq 2048, batch 4: 8192 tokens per step), bf16 with
+fp32 AdamW state, memory cap 96 GB, synthetic seeded weights and tokens.  One step = forward, backward, AdamW
+under the plan, with the slow tier paced to --bw bytes/s per direction (25 GB/s).  Its 118 GB pool is more than
+these boxes can pin in host memory, so it is a device buffer outside the capped arena (said in config.slow_tier);
+--workload gpt2_small_bf16 runs the GPT-2-small-shaped workload (40 % cap) with the pool in pinned host memory.
+--slow-tier file puts the slow tier into a file instead (direct I/O at whatever the file system delivers; probed first).
 
 Prints one JSON line: tokens/s under the cap (value), the uncapped ideal and the migration bound
 beside it, the MFMA roofline of the GEMM kernel measured with HIP events in the timed region, and
@@ -31,9 +33,17 @@ HBM_CLASSES = {"norm": (1, 14, 15), "activation": (5, 6, 12, 13), "rope": (3, 18
                "embedding": (0, 19, 20), "adamw": (21,)}
 PEAK_BF16_TFLOPS = 2500.0
 PEAK_FP32_VECTOR_TFLOPS = 157.3
-# L2 <-> fabric bytes per GEMM launch from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this command
-# (profiles/gpt2_small_bf16_step_pmc_traffic.txt); None where no such run has been made
-GEMM_TRAFFIC_BYTES_PER_LAUNCH = {"gpt2_small_bf16": 149.68e6}
+
+
+def gemm_traffic(workload):
+    """Bytes per GEMM launch that cross between the L2s and the fabric, measured offline with rocprofv3 --pmc
+    FETCH_SIZE / WRITE_SIZE runs of this command and kept with their provenance in profiles/gemm_traffic.json
+    (workload -> bytes_per_launch, profile file, commit of the kernels measured).  None where no such run exists."""
+    try:
+        with open(os.path.join(ROOT, "profiles", "gemm_traffic.json")) as f:
+            return json.load(f).get(workload)
+    except OSError:
+        return None
 
 
 def probe_file_bw(path, total=2 << 30, block=8 << 20, threads=4):
@@ -98,6 +108,36 @@ def probe_file_bw(path, total=2 << 30, block=8 << 20, threads=4):
     return {"write_Bps": w, "read_Bps": r, "duplex_write_Bps": res["w"], "duplex_read_Bps": res["r"], "direct": direct}
 
 
+def _union(iv):
+    out = []
+    for a, b in sorted(iv):
+        if b <= a:
+            continue
+        if out and a <= out[-1][1]:
+            out[-1][1] = max(out[-1][1], b)
+        else:
+            out.append([a, b])
+    return out
+
+
+def interval_overlap(kernels, copies):
+    """Both arguments: lists of (begin, end).  Returns the length of (union of copies) that lies inside (union of
+    kernels), the length of the union of copies, and their ratio."""
+    K, Cp = _union(kernels), _union(copies)
+    both, i = 0, 0
+    for a, b in Cp:
+        while i < len(K) and K[i][1] <= a:
+            i += 1
+        j = i
+        while j < len(K) and K[j][0] < b:
+            both += max(0, min(b, K[j][1]) - max(a, K[j][0]))
+            j += 1
+    busy = sum(b - a for a, b in Cp)
+    return {"copy_busy_ms": busy / 1e6, "copy_busy_under_kernels_ms": both / 1e6,
+            "frac_of_copy_time_with_a_kernel_running": (both / busy) if busy else None,
+            "kernel_busy_ms": sum(b - a for a, b in K) / 1e6}
+
+
 def planner_times(names=("tiny_gpt_fp32", "gpt2_small_bf16", "llama_7b_bf16", "llama_13b_bf16", "llama_30b_bf16")):
     """CPU only: wall time of lifetime analysis + Algorithm 1 in the library and in the oracle, on the canonical
     traces of the five workloads with modelled kernel times, each at its stated capacity and bandwidth.  The
@@ -141,7 +181,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="gpt2_small_bf16")
+    ap.add_argument("--workload", default="llama_7b_bf16")
     ap.add_argument("--bw", type=float, default=-1, help="slow-tier bytes/s per direction; 0 = unthrottled; default: the workload's (25e9)")
     ap.add_argument("--min-bytes", type=int, default=1 << 20)
     ap.add_argument("--file", default="/tmp/teraio_slow_tier.bin", help="--slow-tier file: path of the file (created, removed at the end)")
@@ -263,8 +303,8 @@ def main():
         ctx.tio_train_step(tok, lab, None)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(args.steps):
-        ctx.tio_train_step(tok, lab, None)
+    for _ in range(args.steps):                      # timed like the capped loop below (events around every launch)
+        ctx.tio_train_step(tok, lab, None, time_kernels=True)
     torch.cuda.synchronize()
     ideal_s = (time.perf_counter() - t0) / args.steps
     ctx.close()
@@ -316,6 +356,11 @@ def main():
         loss = st["loss"]
     torch.cuda.synchronize()
     step_s = (time.perf_counter() - t0) / args.steps
+    # one more step, outside the timed region, with every kernel and every copy stamped on its own stream: the
+    # compute/copy overlap is the share of the time a copy is in flight during which a kernel is running too
+    ctx.tio_train_step(tok, lab, plan, timeline=True)
+    k0, k1, c0, c1 = ctx.tio_step_timeline(N, len(pe["entries"]))
+    overlap = interval_overlap(list(zip(k0.tolist(), k1.tolist())), [(a, b) for a, b in zip(c0.tolist(), c1.tolist()) if a >= 0])
     file_info = ctx.tio_file_tier_info() if tier == "file" else None
     ctx.close()
     if tier == "file" and os.path.exists(args.file):
@@ -340,6 +385,7 @@ def main():
             hbm[label] = {"GBps": kb[sel].sum() / ktimes[sel].sum(), "GBps_without_migration": kb[sel].sum() / float(tau[sel].sum()),
                           "ms_per_step": ktimes[sel].sum() / 1e6, "launches": int(sel.sum())}
     gemm_tflops = gemm_flops / gemm_ns / 1e3
+    traffic = gemm_traffic(args.workload) if args.micro_batches == 1 else None
     bf16 = cfg["precision"] == "bf16"
     gemm_peak = PEAK_BF16_TFLOPS if bf16 else PEAK_FP32_VECTOR_TFLOPS
     attn_tflops = flops[attn].sum() / ktimes[attn].sum() / 1e3
@@ -368,16 +414,19 @@ def main():
                  "arena_bytes_needed": pe["arena_needed"], "planner_seconds": plan_s},
         "copy": {"d2h_GBps": d2h / args.steps / step_s / 1e9, "h2d_GBps": h2d / args.steps / step_s / 1e9,
                  "cap_GBps": bw / 1e9},
-        "kernel_ms_per_step": comp_s * 1e3, "overlap": 1.0 - max(0.0, step_s - comp_s) / step_s,
+        "kernel_ms_per_step": comp_s * 1e3, "kernel_share_of_step": comp_s / step_s,
+        "overlap": overlap,
         "attention_tflops": attn_tflops, "loss": loss,
         "hbm_kernels": {"peak_GBps": 8000.0, "bytes": "operand tensor sizes, counted once per read and once per write",
                         "classes": hbm},
         # fp32 workloads (the tiny parity configurations) run the contractions on the fp32 vector ALU
         "roofline": {"bound": "mfma" if bf16 else "alu",
-                     "kernel": ("gemm_bf16_pipe_k" if bf16 else "gemm_f32_k") + " (forward, dX and dW contractions)",
+                     "kernel": ("gemm_bf16_dl_k" if bf16 else "gemm_f32_k") + " (forward, dX and dW contractions)",
                      "achieved": gemm_tflops, "peak": gemm_peak, "unit": "TFLOP/s",
-                     "frac": gemm_tflops / gemm_peak, "traffic": GEMM_TRAFFIC_BYTES_PER_LAUNCH.get(args.workload),
-                     "traffic_unit": "bytes per launch missing the L2 (rocprofv3 FETCH_SIZE + WRITE_SIZE, calibrated)",
+                     "frac": gemm_tflops / gemm_peak, "traffic": (traffic or {}).get("bytes_per_launch"),
+                     "traffic_unit": "bytes per launch missing the L2 (rocprofv3 FETCH_SIZE + WRITE_SIZE, calibrated); "
+                                     "measured offline, not in this run",
+                     "traffic_provenance": ({k: traffic[k] for k in ("profile", "commit")} if traffic else None),
                      "algorithmic_bytes_per_launch": gemm_bytes / n_gemm,
                      "launches_per_step": n_gemm, "avg_launch_us": gemm_ns / n_gemm / 1e3,
                      "achieved_without_migration": gemm_flops / float(tau[gemm].sum()) / 1e3,
@@ -392,39 +441,40 @@ def main():
                             "staging_bytes": args.staging_mb << 20, "chunk_bytes": args.chunk_mb << 20}
     log('capped ms/step', step_s * 1e3, 'loss', loss)
     if not args.no_cpu_baseline:
+        # the oracle as it stands, fp32, on all host cores (numpy's BLAS threads), on the step's whole batch
         from oracle import model as om
         if small:
-            sample = dict(cfg, B=1)
-            stok, slab = tok[:1], lab[:1]
-            tr = om.Trainer(sample, params, dtype=np.float64)
+            cpu_tokens = S
+            tr = om.Trainer(cfg, params, dtype=np.float32)
             tc = time.perf_counter()
-            tr.step(stok, slab)
+            tr.step(tok, lab)
             cpu_s = time.perf_counter() - tc
-            what = (f"one full step (forward, backward, AdamW, fp64 numpy) of the same model on 1 of the "
-                    f"{cfg['B']} sequences ({cfg['T']} tokens), {cpu_s:.1f} s")
+            what = (f"one full step (forward, backward, AdamW; numpy fp32) of the same model on the same batch "
+                    f"({S} tokens), {cpu_s:.1f} s")
         else:
-            # one decoder layer at the workload's widths (small vocabulary, so that embedding and head are negligible),
-            # one sequence; the step of the whole model is taken as n_layers times that: an extrapolation
-            sample = dict(cfg, L=1, V=1024, B=1)
+            # one decoder layer at the workload's widths (small vocabulary, so that embedding and head are negligible) on
+            # the whole batch; the step of the whole model is taken as n_layers times that: an extrapolation
+            sample = dict(cfg, L=1, V=1024, B=CONFIGS[args.workload]["B"])
             sample.pop("micro_batches", None)
             sspecs = [(n, (r, c) if r > 1 else (c,), "normal" if (r > 1) else ("ones" if n.endswith("_g") else "zeros"))
                       for n, r, c in tio.tio_param_list(sample)]
             sparams = gen_params(sspecs, 0)
-            stok, slab = gen_tokens(1, cfg["T"], 1024, 0)
-            tr = om.Trainer(sample, sparams, dtype=np.float64)
+            stok, slab = gen_tokens(sample["B"], cfg["T"], 1024, 0)
+            cpu_tokens = sample["B"] * cfg["T"]
+            tr = om.Trainer(sample, sparams, dtype=np.float32)
             tc = time.perf_counter()
             tr.step(stok, slab)
             cpu_s = (time.perf_counter() - tc) * cfg["L"]
-            what = (f"EXTRAPOLATED: one decoder layer of the workload's widths (forward, backward, AdamW, fp64 numpy, "
-                    f"vocabulary 1024) on one sequence of {cfg['T']} tokens took {cpu_s / cfg['L']:.1f} s; times "
+            what = (f"EXTRAPOLATED: one decoder layer of the workload's widths (forward, backward, AdamW; numpy fp32, "
+                    f"vocabulary 1024) on the whole batch of {sample['B'] * cfg['T']} tokens took {cpu_s / cfg['L']:.1f} s; times "
                     f"{cfg['L']} layers, embedding and head left out")
         try:
             from threadpoolctl import threadpool_info
             cores = max([p.get("num_threads", 1) for p in threadpool_info() if p.get("user_api") == "blas"] or [1])
         except Exception:
             cores = len(os.sched_getaffinity(0))
-        out["cpu_baseline"] = {"value": cfg["T"] / cpu_s, "unit": "tokens/s", "cores": cores,
-                               "kind": "oracle",
+        out["cpu_baseline"] = {"value": cpu_tokens / cpu_s,
+                               "unit": "tokens/s", "cores": cores, "kind": "oracle", "dtype": "f32",
                                "sample": what}
     print(json.dumps(out))
 

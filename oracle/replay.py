@@ -135,6 +135,133 @@ def simulate(trace, plan, bw, duplex=True, iterations=3, host_bw=0):
     return dict(step_ns=t_iter[-1], compute_ns=sum(tau), per_iteration=t_iter)
 
 
+def simulate_engine(trace, plan, bw, duplex=True, iterations=3, host_bw=0, chunk_bytes=16 << 20, urgent_first=True):
+    """Performance model of the migration engine with a ready queue per channel (Section 3.2, "Minimize kernel
+    stalls": urgent migrations go ahead of the other pending ones; Section 3.3).  Reading:
+
+      * kernel times are fixed (Section 2.2); the entries triggered at kernel k are issued when kernel k-1 completes;
+      * a channel (one per direction and tier; one per tier when duplex is off) moves one chunk of at most chunk_bytes
+        at a time, ceil(bytes * 1e9 / bandwidth) ns per chunk;
+      * a request is ready once it has been issued and, for a prefetch, once its own offload and every offload whose
+        deadline had been reached when the prefetch was issued are complete (the memory it lands in is free);
+      * whenever a channel is free it takes the next chunk of the first ready urgent request in issue order, else of
+        the first ready request in issue order: an urgent request overtakes pending ones at a chunk boundary,
+        and a request that is not ready never holds up one that is (urgent_first=False: no priority, ready
+        requests in issue order);
+      * kernel k starts when kernel k-1, the prefetches due at k and every offload whose deadline is k or earlier
+        are complete.
+
+    Returns the duration of every simulated iteration and the compute-only time, like simulate."""
+    tau = trace["tau"]
+    N = len(tau)
+    entries = plan["entries"]
+    by_trigger = [[] for _ in range(N)]
+    for e in entries:
+        by_trigger[e[2] % N].append(e)
+    pre_deadline = [[] for _ in range(N)]
+    off_deadline = [[] for _ in range(N)]
+    for (t, kind, trig, dl, urgent, pair) in entries:
+        (off_deadline if kind == OFFLOAD else pre_deadline)[dl % N].append(pair)
+    tier = plan.get("tier") or [0] * (len(entries) // 2)
+    rate = (bw, host_bw)
+
+    class Req:
+        pass
+
+    n_chan = 4
+    chan_of = lambda kind, w: 2 * w + (kind if duplex else 0)
+    queue = [[] for _ in range(n_chan)]            # issued, unfinished requests in issue order
+    busy_until = [None] * n_chan                   # end of the chunk in flight
+    in_flight = [None] * n_chan
+    last_off, last_pre = {}, {}                    # pair -> latest request
+    due = []                                       # offload requests whose deadline has been reached, not yet known complete
+
+    def done(r, now):
+        return r.done_at is not None and r.done_at <= now
+
+    def issue(k, now):
+        for p in off_deadline[k]:
+            if p in last_off:
+                due.append(last_off[p])
+        for (t, kind, trig, dl, urgent, pair) in by_trigger[k]:
+            r = Req()
+            r.kind, r.pair, r.urgent, r.left, r.done_at = kind, pair, urgent, trace["tensors"][t][0], None
+            r.rate = rate[tier[pair]]
+            r.deps = []
+            if kind == PREFETCH:
+                if pair in last_off:
+                    r.deps.append(last_off[pair])
+                r.deps += [q for q in due if not done(q, now)]
+                last_pre[pair] = r
+            else:
+                last_off[pair] = r
+            queue[chan_of(kind, tier[pair])].append(r)
+        for p in off_deadline[k]:                  # offloads issued at this very trigger point
+            if p in last_off and last_off[p] not in due:
+                due.append(last_off[p])
+
+    def pick(c, now):
+        ready = [r for r in queue[c] if all(done(q, now) for q in r.deps)]
+        if urgent_first:
+            for r in ready:
+                if r.urgent:
+                    return r
+        return ready[0] if ready else None
+
+    def kernel_may_start(k, now):
+        due[:] = [q for q in due if not done(q, now)]
+        if due:
+            return False
+        return all(done(last_pre[p], now) for p in pre_deadline[k] if p in last_pre)
+
+    now, k_glob, running_until = 0, 0, None
+    total = iterations * N
+    t_iter, t_iter_start = [], 0
+    issue(0, 0)
+    while k_glob < total:
+        changed = True
+        while changed and k_glob < total:           # everything that happens at `now`
+            changed = False
+            for c in range(n_chan):                  # chunks that end now
+                if in_flight[c] is not None and busy_until[c] <= now:
+                    r = in_flight[c]
+                    if r.left == 0:
+                        r.done_at = busy_until[c]
+                        queue[c].remove(r)
+                    in_flight[c] = None
+                    changed = True
+            if running_until is not None and running_until <= now:      # the kernel that ends now
+                running_until = None
+                k_glob += 1
+                if k_glob % N == 0:
+                    t_iter.append(now - t_iter_start)
+                    t_iter_start = now
+                if k_glob < total:
+                    issue(k_glob % N, now)
+                changed = True
+                continue
+            for c in range(n_chan):                  # free channels take their next chunk
+                if in_flight[c] is None:
+                    r = pick(c, now)
+                    if r is not None:
+                        n = min(r.left, chunk_bytes) if chunk_bytes else r.left
+                        r.left -= n
+                        busy_until[c] = now + (-(-n * 10**9 // r.rate) if r.rate else 0)
+                        in_flight[c] = r
+                        changed = True
+            if running_until is None and kernel_may_start(k_glob % N, now):
+                running_until = now + tau[k_glob % N]
+                changed = True
+        if k_glob >= total:
+            break
+        pending = [busy_until[c] for c in range(n_chan) if in_flight[c] is not None]
+        if running_until is not None:
+            pending.append(running_until)
+        assert pending and min(pending) > now, "nothing in flight and nothing can start"
+        now = min(pending)
+    return dict(step_ns=t_iter[-1], compute_ns=sum(tau), per_iteration=t_iter)
+
+
 def check_layout(trace, life, plan, allocs, arena_bytes):
     """allocs: list of (tensor, first_kernel, last_kernel, address) with kernel indices unrolled
     (last may be >= N for a residency that crosses the iteration boundary)."""

@@ -39,3 +39,15 @@ def test_planner_times_compare_like_with_like(capsys):
     for r in out["planner_wall_time"]:
         assert r["same_plan"] and r["entries"] > 0 and r["planning_cap_bytes"] <= r["cap_bytes"]
         assert r["library_search_s"] > 0 and r["library_single_s"] > 0 and r["oracle_single_s"] > 0
+
+
+def test_compute_copy_overlap_of_a_small_timeline():
+    """Overlap = time a copy is in flight while a kernel runs, over the time a copy is in flight (unions on both sides)."""
+    b = _bench_module()
+    kernels = [(0, 100), (150, 250), (240, 300)]                 # union: [0,100) and [150,300)
+    copies = [(50, 200), (180, 220), (400, 500)]                  # union: [50,220) and [400,500): 270 busy
+    r = b.interval_overlap(kernels, copies)
+    assert abs(r["copy_busy_ms"] - 270e-6) < 1e-12 and abs(r["kernel_busy_ms"] - 250e-6) < 1e-12
+    assert abs(r["copy_busy_under_kernels_ms"] - (50 + 70) * 1e-6) < 1e-12
+    assert abs(r["frac_of_copy_time_with_a_kernel_running"] - 120 / 270) < 1e-12
+    assert b.interval_overlap(kernels, [])["frac_of_copy_time_with_a_kernel_running"] is None
