@@ -404,7 +404,11 @@ def main():
                                  "file": "file, direct I/O through a pinned staging ring"}[tier], "min_bytes": args.min_bytes,
                    "kernel_times": "modelled" if args.modelled_tau else "measured"},
         "ideal_tokens_per_s": S / ideal_s, "ideal_ms_per_step": ideal_s * 1e3,
-        "model_predicted_ms_per_step": tio.tio_plan_simulate(lt, plan, bw, duplex=not shared)[0] / 1e6,
+        # the engine of a paced tier serves a ready queue in 16 MiB chunks, urgent requests first; unthrottled tiers and the
+        # file tier serve in the order submitted
+        "model_predicted_ms_per_step": (tio.tio_plan_simulate_engine(lt, plan, bw, duplex=not shared)[0] if (bw and tier != "file")
+                                        else tio.tio_plan_simulate(lt, plan, bw, duplex=not shared)[0]) / 1e6,
+        "model_first_come_first_served_ms_per_step": tio.tio_plan_simulate(lt, plan, bw, duplex=not shared)[0] / 1e6,
         "frac_of_ideal": ideal_s / step_s,
         "migration_bound_ms": mig_bound_s * 1e3, "frac_of_min_ideal_migration_bound": bound_s / step_s,
         "plan": {"entries": len(pe["entries"]), "greedy_pairs": pe["n_greedy"], "urgent_pairs": pe["n_forced"],

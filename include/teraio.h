@@ -226,6 +226,16 @@ int tio_plan_validate(const tio_trace *trace, const tio_lifetimes *life, const t
  * last one (the steady state), out_compute_ns the sum of tau.  Pure CPU, integer arithmetic. */
 int tio_plan_simulate(const tio_trace *trace, const tio_plan *plan, uint64_t slow_tier_bw, int32_t duplex,
                       int32_t iterations, int64_t *out_step_ns, int64_t *out_compute_ns);
+/* The same model for the engine as the runtime runs it on tiers with an emulated bandwidth (Section 3.2, "Minimize
+ * kernel stalls": urgent migrations go ahead of the other pending ones; Section 3.3): each channel moves one chunk of at
+ * most chunk_bytes at a time (0: whole tensors), ceil(bytes * 1e9 / bandwidth) ns per chunk; a request is ready once it
+ * has been issued and, for a prefetch, once its own offload and every offload whose deadline had been reached at its
+ * issue are complete; a free channel takes the next chunk of the first ready urgent request in issue order, else of the
+ * first ready request (urgent_first = 0: ready requests in issue order, no priority); a kernel starts when its
+ * predecessor, the prefetches due at it and every offload whose deadline is that kernel or an earlier one are complete. */
+int tio_plan_simulate_engine(const tio_trace *trace, const tio_plan *plan, uint64_t slow_tier_bw, int32_t duplex,
+                             int32_t iterations, uint64_t chunk_bytes, int32_t urgent_first, int64_t *out_step_ns,
+                             int64_t *out_compute_ns);
 void tio_plan_free(tio_plan *plan);
 
 /* ---- Section 3.3: runtime ---------------------------------------------------------------------- */
@@ -249,6 +259,20 @@ typedef struct tio_file_tier_stats {
 int tio_file_tier_info(tio_ctx *ctx, tio_file_tier_stats *out);
 /* Bandwidth enforced on the copy streams from the next step on (0 = unthrottled). */
 int tio_set_slow_tier_bw(tio_ctx *ctx, uint64_t bytes_per_s);
+
+/* How the engine of a tier with an emulated bandwidth serves its requests (Section 3.2, "Minimize kernel stalls": urgent
+ * migrations go ahead of the other pending ones).  Default: chunks of 16 MiB, urgent_first = 1, ready_queue = 1: whenever a
+ * direction's channel is free it takes the next chunk of the first urgent request whose dependencies are met, else of the
+ * first request whose dependencies are met, in the order submitted.  chunk_bytes = 0 moves whole tensors (nothing can
+ * overtake a transfer in progress); urgent_first = 0 ignores the mark; ready_queue = 0 serves strictly in the order
+ * submitted, waiting for the dependencies of the oldest request.  Waits for the transfers in flight; applies from the
+ * next step on.  Tiers without an emulated bandwidth and the file tier serve in the order submitted and ignore this. */
+int tio_set_engine_policy(tio_ctx *ctx, uint64_t chunk_bytes, int32_t urgent_first, int32_t ready_queue);
+
+/* Testing aid (pure CPU): the choice a free channel of that engine makes.  ready[i] / urgent[i] (host, n bytes each)
+ * describe the queued requests in the order submitted; returns the index served next, -1 if none may go (no error code
+ * is negative one: a null array with n > 0 returns TIO_ERR_INVALID_ARG = -1 as well, so pass valid arrays). */
+int tio_engine_choose(const uint8_t *ready, const uint8_t *urgent, int32_t n, int32_t urgent_first, int32_t ready_queue);
 
 /* One training iteration: forward, backward, AdamW, with the plan's migrations on the copy
  * streams.  plan == NULL runs the uncapped layout with no migration.  tokens/labels: host int32.

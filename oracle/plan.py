@@ -158,7 +158,7 @@ class Channel:
 # ----------------------------------------------------------------------------
 # Section 3.2: Algorithm 1 and the forced (urgent) pass
 # ----------------------------------------------------------------------------
-def build_plan(trace, life, cap, bw, duplex=True, min_bytes=0, host_bw=0, host_budget=0):
+def build_plan(trace, life, cap, bw, duplex=True, min_bytes=0, host_bw=0, host_budget=0, clamp_benefit=False):
     """Returns dict(entries=[(tensor, kind, trigger, deadline, urgent, pair)], Mp=[...], n_greedy, n_forced,
     tier=[0 slow tier | 1 host tier, per pair], host_peak=bytes).
 
@@ -168,7 +168,12 @@ def build_plan(trace, life, cap, bw, duplex=True, min_bytes=0, host_bw=0, host_b
     memory, a prefetch before kernel deadline (its next use) runs.  `pair` numbers
     the selected periods in selection order; the tensor is counted out of GPU
     memory at kernels [offload deadline, prefetch trigger - 1].
+
+    clamp_benefit: the benefit of the prose ("Quantify the benefit and cost": the integral of the reduction in
+    critical memory pressure), B = sum over C of min(s, M'[k] - capacity) * tau[k], instead of the listing's
+    B = s * sum over C of tau[k]; candidates are compared by the exact fraction B / s.
     """
+    from fractions import Fraction
     tau = trace["tau"]
     N = len(tau)
     T = [0] * (2 * N + 1)                                  # T[k] = start of kernel k, unrolled
@@ -201,6 +206,8 @@ def build_plan(trace, life, cap, bw, duplex=True, min_bytes=0, host_bw=0, host_b
         for k in range(start + 1, end):
             Mh[k % N] += s
 
+    clamp_size = [0]                                       # size of the candidate being evaluated
+
     def evaluate(c_off, c_pre, lo, hi, d, over):
         """(score, g, t_offloaded, t_prefetch, k_off, k_pre) of a candidate on one tier's channels, or None"""
         g = c_off.earliest_gap(lo, hi, d)
@@ -220,6 +227,10 @@ def build_plan(trace, life, cap, bw, duplex=True, min_bytes=0, host_bw=0, host_b
         score = over[k_pre + 1] - over[k_off]                    # B / s = sum of tau over C
         if score <= 0:
             return None
+        if clamp_benefit:
+            s = clamp_size[0]
+            B = sum(min(s, Mp[k % N] - cap) * tau[k % N] for k in range(k_off, k_pre + 1) if Mp[k % N] > cap)
+            score = Fraction(B, s)
         return score, g, t_offloaded, t_prefetch, k_off, k_pre
 
     # ---- Algorithm 1
@@ -231,6 +242,7 @@ def build_plan(trace, life, cap, bw, duplex=True, min_bytes=0, host_bw=0, host_b
         for (t, s, start, end) in I:
             d = dur(s)
             lo, hi = T[start + 1], T[end]
+            clamp_size[0] = s
             ev, where = evaluate(ch_off, ch_pre, lo, hi, d, over), 0
             if two_tier:
                 # slow tier saturated for this candidate: planned transfers displace it (or leave it no room)

@@ -269,6 +269,22 @@ def tio_plan_simulate(trace: Trace, plan: Plan, slow_tier_bw: int, duplex=True, 
     return step.value, comp.value
 
 
+def tio_plan_simulate_engine(trace: Trace, plan: Plan, slow_tier_bw: int, duplex=True, iterations=3, chunk_bytes=16 << 20,
+                             urgent_first=True):
+    """Performance model of the engine with ready queues, chunked transfers and urgent-first service."""
+    step, comp = C.c_int64(), C.c_int64()
+    _check(lib().tio_plan_simulate_engine(trace.h, plan.h, C.c_uint64(int(slow_tier_bw)), 1 if duplex else 0, int(iterations),
+                                          C.c_uint64(int(chunk_bytes)), 1 if urgent_first else 0, C.byref(step), C.byref(comp)))
+    return step.value, comp.value
+
+
+def tio_engine_choose(ready, urgent, urgent_first=True, ready_queue=True):
+    """Index of the queued request a free channel of the paced engine serves next (-1: none)."""
+    r = (C.c_uint8 * max(1, len(ready)))(*[1 if x else 0 for x in ready])
+    u = (C.c_uint8 * max(1, len(urgent)))(*[1 if x else 0 for x in urgent])
+    return lib().tio_engine_choose(r, u, len(ready), 1 if urgent_first else 0, 1 if ready_queue else 0)
+
+
 # ------------------------------------------------------------------ runtime (needs a GPU)
 class Context:
     """Owns the arena (GPU), the slow-tier pool (pinned host) and three streams via torch,
@@ -384,6 +400,9 @@ class Context:
         _check(lib().tio_train_step(self.h, t.ctypes.data_as(C.POINTER(C.c_int32)), l.ctypes.data_as(C.POINTER(C.c_int32)),
                                     plan.h if plan is not None else None, flags, C.byref(st)))
         return {f: getattr(st, f) for f, _ in StepStats._fields_}
+
+    def tio_set_engine_policy(self, chunk_bytes=16 << 20, urgent_first=True, ready_queue=True):
+        _check(lib().tio_set_engine_policy(self.h, C.c_uint64(int(chunk_bytes)), 1 if urgent_first else 0, 1 if ready_queue else 0))
 
     def tio_step_timeline(self, n_kernels: int, n_entries: int):
         a = [np.empty(n_kernels, dtype=np.int64) for _ in range(2)] + [np.empty(max(n_entries, 1), dtype=np.int64) for _ in range(2)]

@@ -569,6 +569,121 @@ SimResult simulate_plan(const Trace &t, const Plan &plan, uint64_t bw, bool dupl
     return SimResult{last, compute};
 }
 
+// Discrete-event model of the engine with ready queues.  Events are the end of a chunk on one of the four channels
+// (direction x tier) and the end of the running kernel; at every event time the model first retires what ends,
+// issues the entries whose trigger point was reached, then lets every free channel take a chunk and the compute
+// stream start the next kernel if its migrations are complete.
+SimResult simulate_engine(const Trace &t, const Plan &plan, uint64_t bw, bool duplex, int iterations, uint64_t chunk_bytes,
+                          bool urgent_first) {
+    const int N = t.n_kernels;
+    const size_t np = plan.pairs.size();
+    struct Request {
+        int kind, pair, urgent;
+        uint64_t left, rate;
+        int64_t done_at;                       // -1 while unfinished
+        std::vector<int> deps;                 // requests that must be complete before the first chunk
+    };
+    std::vector<Request> req;
+    std::vector<std::vector<int32_t>> pre_deadline(N), off_deadline(N);
+    for (const tio_plan_entry &e : plan.entries)
+        (e.kind == TIO_OFFLOAD ? off_deadline : pre_deadline)[e.deadline % N].push_back(e.pair);
+    constexpr int NC = 4;
+    std::vector<int> queue[NC];                // issued and unfinished, in issue order
+    int in_flight[NC] = {-1, -1, -1, -1};
+    int64_t busy_until[NC] = {0, 0, 0, 0};
+    std::vector<int> last_off(np, -1), last_pre(np, -1), due;
+    auto done = [&](int r, int64_t now) { return req[r].done_at >= 0 && req[r].done_at <= now; };
+    auto issue = [&](int k, int64_t now) {
+        for (int32_t p : off_deadline[k]) if (last_off[p] >= 0) due.push_back(last_off[p]);
+        for (int32_t ei : plan.entries_at[k]) {
+            const tio_plan_entry &e = plan.entries[ei];
+            const Pair &pr = plan.pairs[e.pair];
+            Request r{e.kind, e.pair, e.urgent, pr.bytes, pr.tier ? plan.host_bw : bw, -1, {}};
+            const int id = (int)req.size();
+            if (e.kind == TIO_PREFETCH) {
+                if (last_off[e.pair] >= 0) r.deps.push_back(last_off[e.pair]);
+                for (int q : due) if (!done(q, now)) r.deps.push_back(q);
+                last_pre[e.pair] = id;
+            } else {
+                last_off[e.pair] = id;
+            }
+            req.push_back(std::move(r));
+            queue[2 * pr.tier + (duplex ? e.kind : 0)].push_back(id);
+        }
+        for (int32_t p : off_deadline[k])      // offloads issued at this very trigger point
+            if (last_off[p] >= 0 && std::find(due.begin(), due.end(), last_off[p]) == due.end()) due.push_back(last_off[p]);
+    };
+    auto ready = [&](int r, int64_t now) {
+        for (int q : req[r].deps) if (!done(q, now)) return false;
+        return true;
+    };
+    auto pick = [&](int c, int64_t now) {
+        int first = -1;
+        for (int r : queue[c]) {
+            if (!ready(r, now)) continue;
+            if (urgent_first && req[r].urgent) return r;
+            if (first < 0) first = r;
+            if (!urgent_first) break;
+        }
+        return first;
+    };
+    auto kernel_may_start = [&](int k, int64_t now) {
+        due.erase(std::remove_if(due.begin(), due.end(), [&](int q) { return done(q, now); }), due.end());
+        if (!due.empty()) return false;
+        for (int32_t p : pre_deadline[k]) if (last_pre[p] >= 0 && !done(last_pre[p], now)) return false;
+        return true;
+    };
+    int64_t compute = 0;
+    for (int k = 0; k < N; ++k) compute += t.tau[k];
+    const int64_t total = (int64_t)iterations * N;
+    int64_t now = 0, k_glob = 0, running_until = -1, iter_start = 0, last = 0;
+    issue(0, 0);
+    while (k_glob < total) {
+        bool changed = true;
+        while (changed && k_glob < total) {
+            changed = false;
+            for (int c = 0; c < NC; ++c)
+                if (in_flight[c] >= 0 && busy_until[c] <= now) {
+                    const int r = in_flight[c];
+                    if (req[r].left == 0) {
+                        req[r].done_at = busy_until[c];
+                        queue[c].erase(std::find(queue[c].begin(), queue[c].end(), r));
+                    }
+                    in_flight[c] = -1;
+                    changed = true;
+                }
+            if (running_until >= 0 && running_until <= now) {
+                running_until = -1;
+                ++k_glob;
+                if (k_glob % N == 0) { last = now - iter_start; iter_start = now; }
+                if (k_glob < total) issue((int)(k_glob % N), now);
+                changed = true;
+                continue;
+            }
+            for (int c = 0; c < NC; ++c)
+                if (in_flight[c] < 0) {
+                    const int r = pick(c, now);
+                    if (r < 0) continue;
+                    const uint64_t n = chunk_bytes ? std::min(req[r].left, chunk_bytes) : req[r].left;
+                    req[r].left -= n;
+                    busy_until[c] = now + (req[r].rate ? (int64_t)(((u128)n * 1000000000ull + req[r].rate - 1) / req[r].rate) : 0);
+                    in_flight[c] = r;
+                    changed = true;
+                }
+            if (running_until < 0 && kernel_may_start((int)(k_glob % N), now)) {
+                running_until = now + t.tau[k_glob % N];
+                changed = true;
+            }
+        }
+        if (k_glob >= total) break;
+        int64_t next = running_until >= 0 ? running_until : INT64_MAX;
+        for (int c = 0; c < NC; ++c) if (in_flight[c] >= 0) next = std::min(next, busy_until[c]);
+        if (next == INT64_MAX || next <= now) throw PlanError{TIO_ERR_PLAN_INVALID, "performance model: nothing in flight and nothing can start"};
+        now = next;
+    }
+    return SimResult{last, compute};
+}
+
 uint64_t address_at(const Plan &plan, int32_t tensor, int32_t k) {
     const int N = plan.n_kernels;
     for (int ai : plan.alloc_of[tensor]) {

@@ -98,6 +98,10 @@ void validate_plan(const Trace &t, const Lifetimes &life, const Plan &plan);   /
 // Returns the duration of the last of `iterations` consecutive iterations (steady state) in ns.
 struct SimResult { int64_t step_ns, compute_ns; };
 SimResult simulate_plan(const Trace &t, const Plan &plan, uint64_t bw, bool duplex, int iterations);
+// The same question for an engine that keeps a ready queue per channel, moves chunks of at most chunk_bytes and lets
+// urgent requests overtake at chunk boundaries (Section 3.2, "Minimize kernel stalls"; Section 3.3).
+SimResult simulate_engine(const Trace &t, const Plan &plan, uint64_t bw, bool duplex, int iterations, uint64_t chunk_bytes,
+                          bool urgent_first);
 
 // Address of tensor `id` while kernel k (0..N-1) runs, or UINT64_MAX when it is not resident.
 uint64_t address_at(const Plan &plan, int32_t tensor, int32_t k);

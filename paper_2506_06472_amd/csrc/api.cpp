@@ -192,6 +192,20 @@ int tio_plan_simulate(const tio_trace *trace, const tio_plan *plan, uint64_t slo
     TIO_GUARD_END
 }
 
+int tio_plan_simulate_engine(const tio_trace *trace, const tio_plan *plan, uint64_t slow_tier_bw, int32_t duplex,
+                             int32_t iterations, uint64_t chunk_bytes, int32_t urgent_first, int64_t *out_step_ns,
+                             int64_t *out_compute_ns) {
+    if (!trace || !plan || !out_step_ns || !out_compute_ns) return fail(TIO_ERR_INVALID_ARG, "null argument");
+    if (iterations < 1) return fail(TIO_ERR_INVALID_ARG, "iterations must be at least 1");
+    if (plan->p.n_kernels != trace->t.n_kernels) return fail(TIO_ERR_PLAN_STALE, "plan was built from a different trace");
+    TIO_GUARD_BEGIN
+    const SimResult r = simulate_engine(trace->t, plan->p, slow_tier_bw, duplex != 0, iterations, chunk_bytes, urgent_first != 0);
+    *out_step_ns = r.step_ns;
+    *out_compute_ns = r.compute_ns;
+    return TIO_OK;
+    TIO_GUARD_END
+}
+
 void tio_plan_free(tio_plan *plan) { delete plan; }
 
 }  // extern "C"

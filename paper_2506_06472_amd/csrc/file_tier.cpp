@@ -199,7 +199,7 @@ void FileTier::to_device(uint64_t off, void *dev, uint64_t bytes) {
 
 // ---------------------------------------------------------------- asynchronous path: caller side
 uint64_t FileTier::submit_offload(int pair, hipEvent_t after, const void *dev, uint64_t file_off, uint64_t bytes,
-                                  hipEvent_t done, hipEvent_t t0, hipEvent_t t1) {
+                                  hipEvent_t done, hipEvent_t t0, hipEvent_t t1, bool) {
     if (bytes == 0 || file_off % kAlign || file_off + align_up(bytes) > file_bytes_) throw FileTierError{"bad offload request"};
     auto r = std::make_shared<Request>();
     r->pair = pair; r->after = after; r->done = done; r->t0 = t0; r->t1 = t1;
@@ -216,7 +216,7 @@ uint64_t FileTier::submit_offload(int pair, hipEvent_t after, const void *dev, u
 
 uint64_t FileTier::submit_prefetch(int pair, hipEvent_t after, void *dev, uint64_t file_off, uint64_t bytes, Dep written,
                                    std::vector<Dep> landed, std::vector<hipEvent_t> after_more, hipEvent_t done,
-                                   hipEvent_t t0, hipEvent_t t1) {
+                                   hipEvent_t t0, hipEvent_t t1, bool) {
     if (bytes == 0 || file_off % kAlign || file_off + align_up(bytes) > file_bytes_) throw FileTierError{"bad prefetch request"};
     auto r = std::make_shared<Request>();
     r->pair = pair; r->after = after; r->done = done; r->t0 = t0; r->t1 = t1;
@@ -250,6 +250,16 @@ void FileTier::wait_offload_written(int pair, uint64_t seq) {
     std::unique_lock<std::mutex> lk(mu_);
     cv_.wait(lk, [&] { return !error_.empty() || off_written_[pair] >= seq; });
     if (!error_.empty()) throw FileTierError{error_};
+}
+bool FileTier::offload_landed_now(int pair, uint64_t seq) {
+    std::lock_guard<std::mutex> lk(mu_);
+    if (!error_.empty()) throw FileTierError{error_};
+    return off_landed_[pair] >= seq;
+}
+bool FileTier::offload_written_now(int pair, uint64_t seq) {
+    std::lock_guard<std::mutex> lk(mu_);
+    if (!error_.empty()) throw FileTierError{error_};
+    return off_written_[pair] >= seq;
 }
 // a dependency of a prefetch, on this engine (waited for under the lock) or on another one
 void FileTier::wait_dep(const Dep &d, bool written, std::unique_lock<std::mutex> &lk) {

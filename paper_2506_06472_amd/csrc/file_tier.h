@@ -52,11 +52,14 @@ class FileTier : public MigrationEngine {
     void to_device(uint64_t file_off, void *dev, uint64_t bytes);
 
     // ---- asynchronous migration path (MigrationEngine); `where` is a 4096-byte aligned file offset ----
+    // (requests are served in the order submitted: `urgent` is accepted and not used by this tier)
     uint64_t submit_offload(int pair, hipEvent_t after, const void *dev, uint64_t where, uint64_t bytes, hipEvent_t done,
-                            hipEvent_t t0, hipEvent_t t1) override;
+                            hipEvent_t t0, hipEvent_t t1, bool urgent) override;
     uint64_t submit_prefetch(int pair, hipEvent_t after, void *dev, uint64_t where, uint64_t bytes, Dep written,
                              std::vector<Dep> landed, std::vector<hipEvent_t> after_more, hipEvent_t done, hipEvent_t t0,
-                             hipEvent_t t1) override;
+                             hipEvent_t t1, bool urgent) override;
+    bool offload_landed_now(int pair, uint64_t seq) override;
+    bool offload_written_now(int pair, uint64_t seq) override;
     void wait_offload_recorded(int pair, uint64_t seq) override;
     void wait_prefetch_recorded(int pair, uint64_t seq) override;
     void wait_offload_landed(int pair, uint64_t seq) override;

@@ -4,12 +4,14 @@
 // device-to-host stream, prefetches on the host-to-device stream), then makes the compute stream
 // wait for exactly the events kernel k depends on (its prefetched operands, and the offloads that
 // empty address ranges its outputs reuse), then launches kernel k.  A late migration therefore
-// stalls the kernel that needs it and nothing else, which is the paper's "kernel stall".  Urgent
-// entries come first within each direction at every trigger point.  The slow tier is pinned host
-// memory (or a device buffer outside the arena, or a file).  Unthrottled memory tiers are plain hipMemcpyAsync
-// on the tier's two streams.  A tier with an emulated bandwidth (paced_pool.h) or in a file (file_tier.h) is
-// run by threads of its own: the host then blocks, before kernel k, until the completion events kernel k
-// depends on have been recorded by those threads.
+// stalls the kernel that needs it and nothing else, which is the paper's "kernel stall".  The slow tier is pinned host
+// memory (or a device buffer outside the arena, or a file).  A tier with an emulated bandwidth (paced_pool.h) is run by
+// threads of its own with a ready queue per direction: transfers move in chunks, an urgent request whose dependencies are
+// met overtakes the pending ones at a chunk boundary, and a blocked request never holds up a ready one (Section 3.2,
+// "Minimize kernel stalls").  A tier in a file (file_tier.h) has threads of its own too and serves each direction in the
+// order submitted; unthrottled memory tiers are plain hipMemcpyAsync on the tier's two streams, also in the order submitted
+// (there urgent entries only come first among the entries of one trigger point).  With engine threads the host blocks, before
+// kernel k, until the completion events kernel k depends on have been recorded by those threads.
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
@@ -393,7 +395,8 @@ void run_step_body(tio_ctx *c, const int32_t *tokens, const int32_t *labels, boo
                 const Alloc &al = p.allocs[pr.alloc_before];
                 if (eng) {
                     const uint64_t seq = eng->submit_offload(e.pair, progress_event(), c->arena + al.address, place(), pr.bytes,
-                                                             c->ev_off[e.pair], tl ? c->ev_c0[ei] : nullptr, tl ? c->ev_c1[ei] : nullptr);
+                                                             c->ev_off[e.pair], tl ? c->ev_c0[ei] : nullptr, tl ? c->ev_c1[ei] : nullptr,
+                                                             e.urgent != 0);
                     c->req_seq[ei] = c->off_seq[e.pair] = seq;
                     if (tl) issued[ei] = 1;
                 } else {
@@ -404,7 +407,7 @@ void run_step_body(tio_ctx *c, const int32_t *tokens, const int32_t *labels, boo
                     }
                     if (c->rec_kernel[prev]) HIPCHK(hipStreamWaitEvent(so, c->ev_kernel[prev], 0));
                     if (tl) { HIPCHK(hipEventRecord(c->ev_c0[ei], so)); issued[ei] = 1; }
-                    HIPCHK(hipMemcpyAsync(pool + pr.host_offset, c->arena + al.address, pr.bytes, hipMemcpyDefault, so));
+                    HIPCHK(hipMemcpyAsync(pool + pr.host_offset, c->arena + al.address, pr.bytes, (c->pool_dev && !t1) ? hipMemcpyDeviceToDeviceNoCU : hipMemcpyDefault, so));
                     if (c->rt.poison_freed) poison_range(so, c->arena + al.address, pr.bytes);
                     if (tl) HIPCHK(hipEventRecord(c->ev_c1[ei], so));
                     HIPCHK(hipEventRecord(c->ev_off[e.pair], so));
@@ -440,7 +443,7 @@ void run_step_body(tio_ctx *c, const int32_t *tokens, const int32_t *labels, boo
                     const uint64_t where = from_home ? (uint64_t)(uintptr_t)(c->host + c->home[e.tensor]) : place();
                     const uint64_t seq = eng->submit_prefetch(e.pair, progress_event(), c->arena + al.address, where, pr.bytes,
                                                               written, landed, more, c->ev_pre[e.pair],
-                                                              tl ? c->ev_c0[ei] : nullptr, tl ? c->ev_c1[ei] : nullptr);
+                                                              tl ? c->ev_c0[ei] : nullptr, tl ? c->ev_c1[ei] : nullptr, e.urgent != 0);
                     c->req_seq[ei] = c->pre_seq[e.pair] = seq;
                     for (int q : al.wait_pairs)
                         if (c->rec_off[q] && !engine_of(c, p.pairs[q].tier)) c->ev_off_user[q] = {eng, q, seq};
@@ -455,7 +458,7 @@ void run_step_body(tio_ctx *c, const int32_t *tokens, const int32_t *labels, boo
                         HIPCHK(hipStreamWaitEvent(sp, c->ev_off[q], 0));
                     }
                     if (tl) { HIPCHK(hipEventRecord(c->ev_c0[ei], sp)); issued[ei] = 1; }
-                    HIPCHK(hipMemcpyAsync(c->arena + al.address, src, pr.bytes, hipMemcpyDefault, sp));
+                    HIPCHK(hipMemcpyAsync(c->arena + al.address, src, pr.bytes, (c->pool_dev && !(t1 && !from_home)) ? hipMemcpyDeviceToDeviceNoCU : hipMemcpyDefault, sp));
                     if (tl) HIPCHK(hipEventRecord(c->ev_c1[ei], sp));
                     HIPCHK(hipEventRecord(c->ev_pre[e.pair], sp));
                     c->pre_seq[e.pair] = 0;
@@ -613,7 +616,7 @@ int tio_ctx_create(const tio_model_cfg *cfg, const tio_runtime_cfg *rt, tio_ctx 
             c->ft->resize(c->home_file_bytes);
         } catch (...) { tio_ctx_destroy(c); throw; }
     } else {
-        try { c->pp0.reset(new PacedPool(c->sd, c->sh, c->bw)); } catch (...) { tio_ctx_destroy(c); throw; }
+        try { c->pp0.reset(new PacedPool(c->sd, c->sh, c->bw, c->pool_dev)); } catch (...) { tio_ctx_destroy(c); throw; }
     }
     if (c->host1 && c->sd1 && c->sh1) {
         try { c->pp1.reset(new PacedPool(c->sd1, c->sh1, c->bw1)); } catch (...) { tio_ctx_destroy(c); throw; }
@@ -754,6 +757,22 @@ int tio_set_slow_tier_bw(tio_ctx *c, uint64_t bw) {
     sync_all(c);                                         // the change may move the tier between plain copies and its paced engine
     c->bw = bw;
     if (c->pp0) c->pp0->set_bandwidth(bw);
+    return TIO_OK;
+    TIO_RT_END
+}
+
+int tio_engine_choose(const uint8_t *ready, const uint8_t *urgent, int32_t n, int32_t urgent_first, int32_t ready_queue) {
+    if (n < 0 || (n > 0 && (!ready || !urgent))) return fail(TIO_ERR_INVALID_ARG, "null argument");
+    return PacedPool::choose(std::vector<uint8_t>(ready, ready + n), std::vector<uint8_t>(urgent, urgent + n), urgent_first != 0,
+                             ready_queue != 0);
+}
+
+int tio_set_engine_policy(tio_ctx *c, uint64_t chunk_bytes, int32_t urgent_first, int32_t ready_queue) {
+    if (!c) return fail(TIO_ERR_INVALID_ARG, "null argument");
+    TIO_RT_BEGIN
+    sync_all(c);
+    if (c->pp0) c->pp0->set_policy(chunk_bytes, urgent_first != 0, ready_queue != 0);
+    if (c->pp1) c->pp1->set_policy(chunk_bytes, urgent_first != 0, ready_queue != 0);
     return TIO_OK;
     TIO_RT_END
 }
