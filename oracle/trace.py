@@ -29,11 +29,16 @@ the persistent tensors); parameter gradients and the scalar loss are written by
 the first group and accumulated in place by the later ones; the AdamW launches
 follow the gradient-completing launches of the last group only.
 
-Pins (tests/test_oracle_plan.py): kernel and tensor counts in closed form,
-persistent bytes = 12 or 14 bytes per parameter, every transient written before
-read, peak memory at the loss kernel in closed form.  The exact schedule is a
-reading of this build (the paper names no kernels): parity unpinned beyond
-those invariants.
+Pins (tests/test_oracle_plan.py): the complete launch list of a one-layer GPT-shaped
+and a one-layer Llama-shaped model, with the names of the tensors every launch reads,
+writes and updates, against lists written by hand from the dataflow
+(tests/golden/trace_*_one_layer.txt), and the repetition of that pattern in a second
+layer; kernel and tensor counts in closed form, persistent bytes = 12 or 14 bytes per
+parameter, every transient written before read, peak memory at the loss kernel in
+closed form.  The schedule itself is a reading of this build (the paper names no
+kernels); the contraction-splitting rule of the weight-gradient products (dw_splits)
+and the norm-backward row count are launch parameters of the library restated here:
+their values are pinned only by the library's trace being equal to this one.
 """
 from __future__ import annotations
 
