@@ -135,9 +135,18 @@ def test_measured_profile_gives_the_same_structure_and_positive_times():
     ctx = _ctx(cfg, up.export())
     ctx.tio_params_load(params)
     tr = ctx.tio_profile_iteration(tok, lab, tio.PROFILE_MEASURED).export()
-    ref = lt.export()
-    for key in ("op", "operand_off", "operand_tensor", "operand_flags", "tensor_bytes", "tensor_kind"):
-        assert np.array_equal(tr[key], ref[key]), key
+    # the structure the launcher recorded while it ran the kernels, against the oracle's trace of the same model
+    from oracle import trace as ot
+    otr = ot.build_trace(cfg)
+    assert (tr["n_kernels"], tr["n_tensors"], tr["n_persistent"]) == (len(otr["kernels"]), len(otr["tensors"]), otr["n_persistent"])
+    assert tr["op"].tolist() == [k[0] for k in otr["kernels"]]
+    flat, off = [], [0]
+    for _, ops, _ in otr["kernels"]:
+        flat += ops
+        off.append(len(flat))
+    assert tr["operand_off"].tolist() == off
+    assert tr["operand_tensor"].tolist() == [t for t, _ in flat] and tr["operand_flags"].tolist() == [f for _, f in flat]
+    assert tr["tensor_bytes"].tolist() == [t[0] for t in otr["tensors"]] and tr["tensor_kind"].tolist() == [t[1] for t in otr["tensors"]]
     assert tr["tau"].min() > 0 and tr["tau"].sum() < 10**9
     # a plan built from measured times runs and still matches the uncapped numerics
     ctx.tio_params_load(params)
@@ -357,3 +366,52 @@ def test_kernel_times_of_the_full_model_from_one_measured_layer():
     assert len(tau) == lt.export()["n_kernels"] and (tau > 0).all()
     rows = sw.sweep(name, [10**9, 10**10], tau=tau, out=io.StringIO())
     assert rows[0][2] >= rows[1][2] >= int(tau.sum())
+
+
+@pytest.mark.parametrize("cfg", [SMALL_BF16, SMALL_LLAMA_BF16, CONFIGS["tiny_gpt_fp32"], CONFIGS["tiny_llama_fp32"]],
+                         ids=["gpt_bf16", "llama_bf16", "gpt_fp32", "llama_fp32"])
+def test_optimizer_state_follows_the_oracle_from_the_gpu_gradients(cfg):
+    """Three steps; after each one the oracle's AdamW (float64) is fed the gradients the GPU produced, so the two sides
+    differ only by the optimizer arithmetic: master copy (bf16 recipe) or weights (fp32), first and second moment agree
+    element by element to 1e-6 relative, and the bf16 weights are the master copy rounded to nearest even."""
+    from synth import to_bf16_round
+    params, tok, lab = make_inputs(cfg, seed=5)
+    lt, ll, up, _, peak = plans_for(cfg)
+    ctx = _ctx(cfg, up.export())
+    ctx.tio_params_load(params)
+    bf16 = cfg["precision"] == "bf16"
+    names = [n for n, _, _ in ctx.params]
+    th = {n: np.asarray(params[n], np.float64).reshape(-1) for n in names}
+    m = {n: np.zeros_like(th[n]) for n in names}
+    v = {n: np.zeros_like(th[n]) for n in names}
+    gmax = {n: np.zeros_like(th[n]) for n in names}
+    # the hyperparameters as the library receives them: single-precision fields of the model description
+    f32 = lambda x: float(np.float32(x))
+    hp = dict(lr=f32(cfg["lr"]), beta1=f32(0.9), beta2=f32(0.999), eps=f32(1e-8), wd=f32(0.01))
+    for step in range(3):
+        print(f"optimizer state {cfg['arch']} {cfg['precision']} step {step}", flush=True)
+        ctx.tio_train_step(tok, lab, None, capture_grads=True)
+        for n in names:
+            g = ctx.tio_grads_read(n).astype(np.float64).reshape(-1)
+            gmax[n] = np.maximum(gmax[n], np.abs(g))
+            th[n], m[n], v[n] = om.adamw_step(th[n], g, m[n], v[n], step + 1, **hp)
+    worst = 0.0
+    for n in names:
+        got_th = ctx.tio_params_read(n, 1 if bf16 else 0).astype(np.float64).reshape(-1)
+        got_m = ctx.tio_params_read(n, 2).astype(np.float64).reshape(-1)
+        got_v = ctx.tio_params_read(n, 3).astype(np.float64).reshape(-1)
+        # 1e-6 of what each element is made of: the parameter and its three updates of at most lr each; the moment and
+        # the largest gradient term that went into it (terms of either sign cancel); the second moment itself (all its
+        # terms are positive), with the smallest normal fp32 for squares that underflow
+        for what, got, ref, scale in (("theta", got_th, th[n], np.abs(th[n]) + 3 * hp["lr"]),
+                                      ("m", got_m, m[n], np.abs(m[n]) + 0.1 * gmax[n]),
+                                      ("v", got_v, v[n], np.abs(v[n]))):
+            err = np.abs(got - ref)
+            bound = 1e-6 * scale + 1.2e-38
+            assert np.all(err <= bound), (n, what, float((err / (scale + 1e-300)).max()))
+            worst = max(worst, float((err / (scale + 1e-30)).max()))
+        if bf16:
+            w = ctx.tio_params_read(n, 0).astype(np.float32).reshape(-1)
+            assert np.array_equal(w, to_bf16_round(ctx.tio_params_read(n, 1).astype(np.float32)).reshape(-1)), n
+    print("largest relative deviation of the optimizer state", worst, flush=True)
+    ctx.close()
