@@ -205,6 +205,10 @@ def main():
     ap.add_argument("--micro-batches", type=int, default=1,
                     help="n > 1: a step is n micro-batches of the workload's batch with gradient accumulation and one "
                          "AdamW update (n times the tokens per step, same memory cap); not the headline configuration")
+    ap.add_argument("--layers", type=int, default=0,
+                    help="run the workload at reduced depth: this many decoder layers at the workload's widths, sequence "
+                         "length and batch, with the memory cap scaled by (uncapped peak at this depth) / (uncapped peak at "
+                         "full depth); for workloads whose arena plus slow-tier pool exceed one GPU's memory")
     ap.add_argument("--planner-times", action="store_true",
                     help="no GPU: time the library's and the oracle's planner on the five workloads' traces and exit")
     args = ap.parse_args()
@@ -220,6 +224,12 @@ def main():
     from synth import CONFIGS, gen_params, gen_tokens, iter_params_pooled, to_bf16_round
 
     cfg = dict(CONFIGS[args.workload])
+    full_layers, cap_scale = cfg["L"], 1.0
+    if args.layers and args.layers != cfg["L"]:
+        peak_of = lambda c: int(tio.tio_analyze_lifetimes(tio.tio_trace_build(c)).export()["M"].max())
+        full_peak = peak_of(cfg)
+        cfg["L"] = args.layers
+        cap_scale = peak_of(cfg) / full_peak
     base_peak = None
     if args.micro_batches > 1:
         # the cap stays that of the workload itself (a fraction of the single-batch peak, or its byte figure)
@@ -270,7 +280,7 @@ def main():
     ll = tio.tio_analyze_lifetimes(lt)
     M = ll.export()["M"]
     peak = int(M.max())
-    cap = int(cfg["cap_bytes"]) if "cap_bytes" in cfg else int((base_peak or peak) * cfg["cap_frac"]) // 256 * 256
+    cap = (int(cfg["cap_bytes"] * cap_scale) if "cap_bytes" in cfg else int((base_peak or peak) * cfg["cap_frac"])) // 256 * 256
     up = tio.tio_build_plan(lt, ll, 2**62, 0)
     upe = up.export()
     prelim = tio.tio_build_plan(lt, ll, cap, bw, duplex=not shared, min_bytes=args.min_bytes).export()
@@ -398,7 +408,8 @@ def main():
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": step_s * 1e3,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": cfg["precision"],
         "data": "synthetic",
-        "config": {"workload": args.workload, "micro_batches": args.micro_batches, "batch_split": bool(args.split_batch), "tokens_per_step": S, "mem_cap_bytes": cap, "uncapped_peak_bytes": peak,
+        "config": {"workload": args.workload, "layers_run": cfg["L"], "layers_of_the_workload": full_layers,
+                   "cap_scaled_by": cap_scale, "micro_batches": args.micro_batches, "batch_split": bool(args.split_batch), "tokens_per_step": S, "mem_cap_bytes": cap, "uncapped_peak_bytes": peak,
                    "cap_frac_of_peak": cap / peak, "slow_tier_bw_bytes_per_s": bw, "channels": "one shared" if shared else "one per direction", 
                    "slow_tier": {"host": "pinned host memory", "device": "device memory outside the arena (stand-in)",
                                  "file": "file, direct I/O through a pinned staging ring"}[tier], "min_bytes": args.min_bytes,

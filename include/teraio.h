@@ -242,7 +242,9 @@ void tio_plan_free(tio_plan *plan);
 int tio_ctx_create(const tio_model_cfg *cfg, const tio_runtime_cfg *rt, tio_ctx **out);
 int tio_ctx_destroy(tio_ctx *ctx);
 /* Loads parameter `index` from host fp32 values (rounded to the compute precision; fp32 master
- * copy kept in bf16 mode); moments are zeroed and the step counter of the context is reset. */
+ * copy kept in bf16 mode); its moments are zeroed.  The step counter of the context (AdamW's bias correction) restarts
+ * at the call that completes a reload of every parameter; reloading only some of them leaves the counter and the other
+ * parameters' moments as they are. */
 int tio_params_load(tio_ctx *ctx, int32_t index, const float *host_values, int64_t numel);
 /* which: 0 compute weight, 1 master copy (bf16 mode only), 2 first moment, 3 second moment;
  * values are returned as fp32 wherever the tensor currently lives (GPU or slow tier). */
@@ -332,7 +334,9 @@ int tio_op_attention(void *stream, int32_t dtype, int64_t B, int64_t T, int64_t 
                      const void *qkv, void *o, float *lse, const void *dO, float *delta, void *dqkv);
 /* Measuring aid: launch number kernel_index of the schedule, repeated reps times on the compute stream with the
  * uncapped layout (the arena must hold it) and whatever the arena contains, HIP events around the repetitions;
- * returns average ns per launch.  It overwrites that launch's outputs: not for use between training steps. */
+ * returns average ns per launch.  It overwrites that launch's outputs, and a launch that updates its operands in place
+ * (AdamW, gradient accumulation of later micro-batches, RoPE, cross entropy) applies its update reps + 1 times: weights
+ * and optimizer state are not what training left.  Not for use between training steps; reload the parameters afterwards. */
 int tio_op_bench(tio_ctx *ctx, int32_t kernel_index, int32_t reps, double *out_avg_ns);
 
 #ifdef __cplusplus

@@ -198,6 +198,64 @@ __global__ void __launch_bounds__(TPB) norm_fwd_k(const T *__restrict__ x, const
     }
 }
 
+// Same contract as norm_fwd_k, for rows of at most 64*NCH 16-byte chunks: a wavefront owns a row and keeps it in
+// registers, so the row is read once and all of its loads are in flight together.
+template <typename T, bool RMS, int NCH>
+__global__ void __launch_bounds__(TPB) norm_fwd_wave_k(const T *__restrict__ x, const T *__restrict__ g,
+                                                       const T *__restrict__ b, T *__restrict__ y,
+                                                       float *__restrict__ stats, int64_t S, int64_t d, float eps) {
+    constexpr int V = Vec16<T>::N;
+    const int lane = threadIdx.x & 63;
+    const int64_t row = (int64_t)blockIdx.x * (TPB / 64) + (threadIdx.x >> 6);
+    if (row >= S) return;
+    const int cpr = (int)(d / V);
+    const T *xr = x + row * d;
+    Vec16<T> a[NCH];
+#pragma unroll
+    for (int i = 0; i < NCH; ++i)
+        if (lane + 64 * i < cpr) a[i].load(xr + (lane + 64 * i) * V);
+    const float inv_d = 1.0f / (float)d;
+    float mean = 0.f;
+    if (!RMS) {
+        float s = 0.f;
+#pragma unroll
+        for (int i = 0; i < NCH; ++i)
+            if (lane + 64 * i < cpr) {
+                float f[V]; a[i].get(f);
+#pragma unroll
+                for (int e = 0; e < V; ++e) s += f[e];
+            }
+        mean = wave_sum(s) * inv_d;
+    }
+    float q = 0.f;
+#pragma unroll
+    for (int i = 0; i < NCH; ++i)
+        if (lane + 64 * i < cpr) {
+            float f[V]; a[i].get(f);
+#pragma unroll
+            for (int e = 0; e < V; ++e) { const float t = f[e] - mean; q += t * t; }
+        }
+    const float rstd = 1.0f / sqrtf(wave_sum(q) * inv_d + eps);
+    if (lane == 0) {
+        if (RMS) stats[row] = rstd;
+        else { stats[2 * row] = mean; stats[2 * row + 1] = rstd; }
+    }
+#pragma unroll
+    for (int i = 0; i < NCH; ++i)
+        if (lane + 64 * i < cpr) {
+            Vec16<T> gv; gv.load(g + (lane + 64 * i) * V);
+            float f[V], gf[V], bf[V];
+            a[i].get(f); gv.get(gf);
+            if (!RMS) { Vec16<T> bv; bv.load(b + (lane + 64 * i) * V); bv.get(bf); }
+#pragma unroll
+            for (int e = 0; e < V; ++e) {
+                const float xh = (f[e] - mean) * rstd;
+                f[e] = RMS ? xh * gf[e] : xh * gf[e] + bf[e];
+            }
+            Vec16<T> o; o.set(f); o.store(y + row * d + (lane + 64 * i) * V);
+        }
+}
+
 // one workgroup per kNormBwdRows rows, rows in order; column sums for the gain / bias gradients are
 // kept in LDS, each column owned by one thread, and written out as one partial row per workgroup
 template <typename T, bool RMS>
@@ -284,13 +342,20 @@ __global__ void __launch_bounds__(TPB) norm_bwd_wave_k(const T *__restrict__ dy,
     for (int64_t row = r0 + w; row < r1; row += NW) {
         const float mean = RMS ? 0.f : stats[2 * row];
         const float rstd = RMS ? stats[row] : stats[2 * row + 1];
-        Vec16<T> a[NCH], b[NCH];
+        Vec16<T> a[NCH], b[NCH], rr[NCH];
         float s1 = 0.f, s2 = 0.f;
+        // every load of the row goes out before the first use: dy, x and the residual gradient
 #pragma unroll
         for (int i = 0; i < NCH; ++i) {
             if (l + 64 * i < cpr) {
                 a[i].load(dy + row * d + (l + 64 * i) * V);
                 b[i].load(x + row * d + (l + 64 * i) * V);
+                if (dres) rr[i].load(dres + row * d + (l + 64 * i) * V);
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < NCH; ++i) {
+            if (l + 64 * i < cpr) {
                 if (!KEEP_G) gv[0].load(g + (l + 64 * i) * V);
                 float fa[V], fb[V], fg[V]; a[i].get(fa); b[i].get(fb); gv[KEEP_G ? i : 0].get(fg);
 #pragma unroll
@@ -307,7 +372,7 @@ __global__ void __launch_bounds__(TPB) norm_bwd_wave_k(const T *__restrict__ dy,
             if (l + 64 * i < cpr) {
                 if (!KEEP_G) gv[0].load(g + (l + 64 * i) * V);
                 float fa[V], fb[V], fg[V], fr[V], out[V]; a[i].get(fa); b[i].get(fb); gv[KEEP_G ? i : 0].get(fg);
-                if (dres) { Vec16<T> r; r.load(dres + row * d + (l + 64 * i) * V); r.get(fr); }
+                if (dres) rr[i].get(fr);
 #pragma unroll
                 for (int e = 0; e < V; ++e) {
                     const float xh = (fb[e] - mean) * rstd, dxh = fa[e] * fg[e];
@@ -337,6 +402,107 @@ __global__ void __launch_bounds__(TPB) norm_bwd_wave_k(const T *__restrict__ dy,
     }
     float *p = part + (int64_t)blockIdx.x * NP * d;
     for (int64_t i = threadIdx.x; i < NP * d; i += TPB) p[i] = lds[i];
+}
+
+// Same contract as norm_bwd_k, for rows of at most TPB*NCH 16-byte chunks: the workgroup takes its rows one after the
+// other, a thread owns the same NCH chunks of every row, so a row is read once and the gain / bias gradient sums of
+// a thread's columns stay in its registers over all the rows and go straight to the partial row.  The loads of the
+// next row are issued before the current row is reduced (one barrier per row; the two row sums go through LDS in
+// wavefront order), which keeps two rows of dy, x and the residual gradient in flight per workgroup.
+template <typename T, bool RMS, int NCH>
+__global__ void __launch_bounds__(TPB) norm_bwd_block_k(const T *__restrict__ dy, const T *__restrict__ x,
+                                                        const float *__restrict__ stats, const T *__restrict__ g,
+                                                        const T *__restrict__ dres, T *__restrict__ dx,
+                                                        float *__restrict__ part, int64_t S, int64_t d, int rows_per_blk) {
+    constexpr int V = Vec16<T>::N;
+    constexpr int NP = RMS ? 1 : 2, NW = TPB / 64;
+    __shared__ float red[2][2][NW];
+    const int cpr = (int)(d / V);
+    const int64_t r0 = (int64_t)blockIdx.x * rows_per_blk;
+    const int64_t r1 = r0 + rows_per_blk < S ? r0 + rows_per_blk : S;
+    const int w = threadIdx.x >> 6, l = threadIdx.x & 63;
+    float cg[NCH][V], cb[RMS ? 1 : NCH][V];
+    Vec16<T> gv[NCH], a[NCH], b[NCH], rr[NCH], na[NCH], nb[NCH], nr[NCH];
+#pragma unroll
+    for (int i = 0; i < NCH; ++i) {
+        const int c = threadIdx.x + TPB * i;
+        if (c < cpr) {
+            gv[i].load(g + (int64_t)c * V);
+            if (r0 < r1) {
+                a[i].load(dy + r0 * d + (int64_t)c * V);
+                b[i].load(x + r0 * d + (int64_t)c * V);
+                if (dres) rr[i].load(dres + r0 * d + (int64_t)c * V);
+            }
+        }
+#pragma unroll
+        for (int e = 0; e < V; ++e) { cg[i][e] = 0.f; if (!RMS) cb[i][e] = 0.f; }
+    }
+    const float inv_d = 1.0f / (float)d;
+    int par = 0;
+    for (int64_t row = r0; row < r1; ++row, par ^= 1) {
+        if (row + 1 < r1) {
+#pragma unroll
+            for (int i = 0; i < NCH; ++i) {
+                const int c = threadIdx.x + TPB * i;
+                if (c < cpr) {
+                    na[i].load(dy + (row + 1) * d + (int64_t)c * V);
+                    nb[i].load(x + (row + 1) * d + (int64_t)c * V);
+                    if (dres) nr[i].load(dres + (row + 1) * d + (int64_t)c * V);
+                }
+            }
+        }
+        const float mean = RMS ? 0.f : stats[2 * row];
+        const float rstd = RMS ? stats[row] : stats[2 * row + 1];
+        float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+        for (int i = 0; i < NCH; ++i) {
+            if (threadIdx.x + TPB * i < cpr) {
+                float fa[V], fb[V], fg[V]; a[i].get(fa); b[i].get(fb); gv[i].get(fg);
+#pragma unroll
+                for (int e = 0; e < V; ++e) {
+                    const float xh = (fb[e] - mean) * rstd, dxh = fa[e] * fg[e];
+                    s1 += dxh; s2 += dxh * xh;
+                }
+            }
+        }
+        s1 = wave_sum(s1); s2 = wave_sum(s2);
+        if (l == 0) { red[par][0][w] = s1; red[par][1][w] = s2; }
+        __syncthreads();
+        s1 = 0.f; s2 = 0.f;
+#pragma unroll
+        for (int i = 0; i < NW; ++i) { s1 += red[par][0][i]; s2 += red[par][1][i]; }
+        s1 = RMS ? 0.f : s1 * inv_d;
+        s2 *= inv_d;
+#pragma unroll
+        for (int i = 0; i < NCH; ++i) {
+            const int c = threadIdx.x + TPB * i;
+            if (c < cpr) {
+                float fa[V], fb[V], fg[V], fr[V], out[V]; a[i].get(fa); b[i].get(fb); gv[i].get(fg);
+                if (dres) rr[i].get(fr);
+#pragma unroll
+                for (int e = 0; e < V; ++e) {
+                    const float xh = (fb[e] - mean) * rstd, dxh = fa[e] * fg[e];
+                    out[e] = rstd * (dxh - s1 - xh * s2) + (dres ? fr[e] : 0.f);
+                    cg[i][e] += fa[e] * xh;
+                    if (!RMS) cb[i][e] += fa[e];
+                }
+                Vec16<T> o; o.set(out); o.store(dx + row * d + (int64_t)c * V);
+            }
+            a[i] = na[i]; b[i] = nb[i]; rr[i] = nr[i];
+        }
+    }
+    float *p = part + (int64_t)blockIdx.x * NP * d;
+#pragma unroll
+    for (int i = 0; i < NCH; ++i) {
+        const int c = threadIdx.x + TPB * i;
+        if (c < cpr) {
+#pragma unroll
+            for (int e = 0; e < V; e += 4) {
+                *reinterpret_cast<float4 *>(p + (int64_t)c * V + e) = make_float4(cg[i][e], cg[i][e + 1], cg[i][e + 2], cg[i][e + 3]);
+                if (!RMS) *reinterpret_cast<float4 *>(p + d + (int64_t)c * V + e) = make_float4(cb[i][e], cb[i][e + 1], cb[i][e + 2], cb[i][e + 3]);
+            }
+        }
+    }
 }
 
 // column sums of the per-workgroup partial rows: 32 columns x 8 row groups per workgroup, each
@@ -391,63 +557,115 @@ __device__ __forceinline__ float gelu_grad_f(float x) {
     return 0.5f * (1.0f + t) + 0.5f * x * (1.0f - t * t) * 0.7978845608028654f * (1.0f + 3.0f * 0.044715f * x * x);
 }
 
+// The activation kernels give a thread ACT_UNROLL 16-byte chunks, a whole grid apart from one another, and issue all
+// of their loads before the first use: with one chunk per thread too few bytes are in flight to fill the memory system.
+constexpr int ACT_UNROLL = 4;
+
 template <typename T>
 __global__ void __launch_bounds__(TPB) gelu_fwd_k(const T *__restrict__ u, T *__restrict__ y, int64_t nvec) {
     constexpr int V = Vec16<T>::N;
-    const int64_t i = (int64_t)blockIdx.x * TPB + threadIdx.x;
-    if (i >= nvec) return;
-    Vec16<T> a; a.load(u + i * V);
-    float f[V]; a.get(f);
+    const int64_t i0 = (int64_t)blockIdx.x * TPB + threadIdx.x, stride = (int64_t)gridDim.x * TPB;
+    Vec16<T> a[ACT_UNROLL];
 #pragma unroll
-    for (int j = 0; j < V; ++j) f[j] = gelu_f(f[j]);
-    a.set(f); a.store(y + i * V);
+    for (int k = 0; k < ACT_UNROLL; ++k) if (i0 + k * stride < nvec) a[k].load(u + (i0 + k * stride) * V);
+#pragma unroll
+    for (int k = 0; k < ACT_UNROLL; ++k) {
+        if (i0 + k * stride >= nvec) continue;
+        float f[V]; a[k].get(f);
+#pragma unroll
+        for (int j = 0; j < V; ++j) f[j] = gelu_f(f[j]);
+        a[k].set(f); a[k].store(y + (i0 + k * stride) * V);
+    }
 }
 
 template <typename T>
 __global__ void __launch_bounds__(TPB) gelu_bwd_k(T *__restrict__ dact, const T *__restrict__ u, int64_t nvec) {
     constexpr int V = Vec16<T>::N;
-    const int64_t i = (int64_t)blockIdx.x * TPB + threadIdx.x;
-    if (i >= nvec) return;
-    Vec16<T> a, b; a.load(dact + i * V); b.load(u + i * V);
-    float fa[V], fb[V]; a.get(fa); b.get(fb);
+    const int64_t i0 = (int64_t)blockIdx.x * TPB + threadIdx.x, stride = (int64_t)gridDim.x * TPB;
+    Vec16<T> a[ACT_UNROLL], b[ACT_UNROLL];
 #pragma unroll
-    for (int j = 0; j < V; ++j) fa[j] *= gelu_grad_f(fb[j]);
-    a.set(fa); a.store(dact + i * V);
+    for (int k = 0; k < ACT_UNROLL; ++k)
+        if (i0 + k * stride < nvec) { a[k].load(dact + (i0 + k * stride) * V); b[k].load(u + (i0 + k * stride) * V); }
+#pragma unroll
+    for (int k = 0; k < ACT_UNROLL; ++k) {
+        if (i0 + k * stride >= nvec) continue;
+        float fa[V], fb[V]; a[k].get(fa); b[k].get(fb);
+#pragma unroll
+        for (int j = 0; j < V; ++j) fa[j] *= gelu_grad_f(fb[j]);
+        a[k].set(fa); a[k].store(dact + (i0 + k * stride) * V);
+    }
+}
+
+// element index -> (row, chunk in the row): one division per thread, 32-bit whenever the tensor allows it (a 64-bit
+// division by a run-time value is some hundred instructions and was a third of these kernels' work)
+__device__ __forceinline__ void split_row(int64_t idx, int64_t cpr, int64_t n, int64_t &row, int64_t &c) {
+    if (n <= 0x7fffffff) { const uint32_t r = (uint32_t)idx / (uint32_t)cpr; row = r; c = (uint32_t)idx - r * (uint32_t)cpr; }
+    else { row = idx / cpr; c = idx - row * cpr; }
+}
+// logistic function; in bf16 the hardware's exponential and reciprocal (relative error about 1e-6, against the 4e-3
+// of the output's rounding), in fp32 the library's
+template <typename T>
+__device__ __forceinline__ float sigmoid_f(float x) {
+    if (sizeof(T) == 2) return __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.4426950408889634f * x));
+    return 1.0f / (1.0f + expf(-x));
 }
 
 template <typename T>
 __global__ void __launch_bounds__(TPB) swiglu_fwd_k(const T *__restrict__ gu, T *__restrict__ y, int64_t S, int64_t f) {
     constexpr int V = Vec16<T>::N;
-    const int64_t cpr = f / V;
-    const int64_t idx = (int64_t)blockIdx.x * TPB + threadIdx.x;
-    if (idx >= S * cpr) return;
-    const int64_t row = idx / cpr, c = idx % cpr;
-    Vec16<T> a, b; a.load(gu + row * 2 * f + c * V); b.load(gu + row * 2 * f + f + c * V);
-    float fg[V], fu[V]; a.get(fg); b.get(fu);
+    const int64_t cpr = f / V, n = S * cpr;
+    const int64_t i0 = (int64_t)blockIdx.x * TPB + threadIdx.x, stride = (int64_t)gridDim.x * TPB;
+    Vec16<T> a[ACT_UNROLL], b[ACT_UNROLL];
+    int64_t row[ACT_UNROLL], c[ACT_UNROLL];
 #pragma unroll
-    for (int j = 0; j < V; ++j) fg[j] = fg[j] / (1.0f + expf(-fg[j])) * fu[j];
-    a.set(fg); a.store(y + row * f + c * V);
+    for (int k = 0; k < ACT_UNROLL; ++k) {
+        const int64_t idx = i0 + k * stride;
+        if (idx < n) {
+            split_row(idx, cpr, n, row[k], c[k]);
+            a[k].load(gu + row[k] * 2 * f + c[k] * V); b[k].load(gu + row[k] * 2 * f + f + c[k] * V);
+        }
+    }
+#pragma unroll
+    for (int k = 0; k < ACT_UNROLL; ++k) {
+        if (i0 + k * stride >= n) continue;
+        float fg[V], fu[V]; a[k].get(fg); b[k].get(fu);
+#pragma unroll
+        for (int j = 0; j < V; ++j) fg[j] = fg[j] * sigmoid_f<T>(fg[j]) * fu[j];
+        a[k].set(fg); a[k].store(y + row[k] * f + c[k] * V);
+    }
 }
 
 template <typename T>
 __global__ void __launch_bounds__(TPB) swiglu_bwd_k(const T *__restrict__ dy, const T *__restrict__ gu,
                                                     T *__restrict__ dgu, int64_t S, int64_t f) {
     constexpr int V = Vec16<T>::N;
-    const int64_t cpr = f / V;
-    const int64_t idx = (int64_t)blockIdx.x * TPB + threadIdx.x;
-    if (idx >= S * cpr) return;
-    const int64_t row = idx / cpr, c = idx % cpr;
-    Vec16<T> a, b, e; a.load(gu + row * 2 * f + c * V); b.load(gu + row * 2 * f + f + c * V); e.load(dy + row * f + c * V);
-    float fg[V], fu[V], fd[V]; a.get(fg); b.get(fu); e.get(fd);
+    const int64_t cpr = f / V, n = S * cpr;
+    const int64_t i0 = (int64_t)blockIdx.x * TPB + threadIdx.x, stride = (int64_t)gridDim.x * TPB;
+    Vec16<T> a[ACT_UNROLL], b[ACT_UNROLL], e[ACT_UNROLL];
+    int64_t row[ACT_UNROLL], c[ACT_UNROLL];
 #pragma unroll
-    for (int j = 0; j < V; ++j) {
-        const float s = 1.0f / (1.0f + expf(-fg[j]));
-        const float dg = fd[j] * fu[j] * (s + fg[j] * s * (1.0f - s));
-        fu[j] = fd[j] * fg[j] * s;
-        fg[j] = dg;
+    for (int k = 0; k < ACT_UNROLL; ++k) {
+        const int64_t idx = i0 + k * stride;
+        if (idx < n) {
+            split_row(idx, cpr, n, row[k], c[k]);
+            a[k].load(gu + row[k] * 2 * f + c[k] * V); b[k].load(gu + row[k] * 2 * f + f + c[k] * V);
+            e[k].load(dy + row[k] * f + c[k] * V);
+        }
     }
-    a.set(fg); a.store(dgu + row * 2 * f + c * V);
-    b.set(fu); b.store(dgu + row * 2 * f + f + c * V);
+#pragma unroll
+    for (int k = 0; k < ACT_UNROLL; ++k) {
+        if (i0 + k * stride >= n) continue;
+        float fg[V], fu[V], fd[V]; a[k].get(fg); b[k].get(fu); e[k].get(fd);
+#pragma unroll
+        for (int j = 0; j < V; ++j) {
+            const float sg = sigmoid_f<T>(fg[j]);
+            const float dg = fd[j] * fu[j] * (sg + fg[j] * sg * (1.0f - sg));
+            fu[j] = fd[j] * fg[j] * sg;
+            fg[j] = dg;
+        }
+        a[k].set(fg); a[k].store(dgu + row[k] * 2 * f + c[k] * V);
+        b[k].set(fu); b[k].store(dgu + row[k] * 2 * f + f + c[k] * V);
+    }
 }
 
 // rotation of adjacent pairs of q and k, in place; angle = pos * theta^(-2i/dh).  A thread owns one
@@ -535,6 +753,65 @@ __global__ void __launch_bounds__(TPB) ce_k(T *__restrict__ logits, const int32_
             f[j] = col < Vn ? (ce_exp(f[j] - lse) - (col == lab ? 1.0f : 0.0f)) * invS : 0.0f;
         }
         a.set(f); a.store(xr + c * V);
+    }
+}
+
+// Same contract as ce_k, for rows of at most TPB*NCH 16-byte chunks: the workgroup keeps its row in registers, so
+// the logits are read once with all of a thread's loads in flight together, and maximum, sum and gradient are three
+// passes over registers.
+template <typename T, int NCH>
+__global__ void __launch_bounds__(TPB) ce_reg_k(T *__restrict__ logits, const int32_t *__restrict__ labels,
+                                                float *__restrict__ losses, int64_t S, int64_t Vn, int64_t ld, int64_t S_total) {
+    constexpr int V = Vec16<T>::N;
+    __shared__ float red[8];
+    const int64_t row = blockIdx.x;
+    T *xr = logits + row * ld;
+    const int nchunk = (int)(ld / V), nv = (int)Vn;
+    Vec16<T> a[NCH];
+#pragma unroll
+    for (int i = 0; i < NCH; ++i) {
+        const int c = threadIdx.x + TPB * i;
+        if (c < nchunk) a[i].load(xr + (int64_t)c * V);
+    }
+    const int32_t lab = labels[row];
+    const float x_lab = threadIdx.x == 0 ? to_f32(xr[lab]) : 0.f;      // read long before the row is overwritten
+    float m = -INFINITY;
+#pragma unroll
+    for (int i = 0; i < NCH; ++i) {
+        const int c = threadIdx.x + TPB * i;
+        if (c < nchunk) {
+            float f[V]; a[i].get(f);
+#pragma unroll
+            for (int j = 0; j < V; ++j) if (c * V + j < nv) m = fmaxf(m, f[j]);
+        }
+    }
+    const float M = block_max<TPB / 64>(m, red);
+    float sum = 0.f;
+#pragma unroll
+    for (int i = 0; i < NCH; ++i) {
+        const int c = threadIdx.x + TPB * i;
+        if (c < nchunk) {
+            float f[V]; a[i].get(f);
+#pragma unroll
+            for (int j = 0; j < V; ++j) if (c * V + j < nv) sum += ce_exp(f[j] - M);
+        }
+    }
+    const float tot = block_sum<TPB / 64>(sum, red);
+    const float lse = M + logf(tot);
+    if (threadIdx.x == 0) losses[row] = lse - x_lab;
+    const float invS = 1.0f / (float)S_total;          // the loss is the mean over the whole batch
+#pragma unroll
+    for (int i = 0; i < NCH; ++i) {
+        const int c = threadIdx.x + TPB * i;
+        if (c < nchunk) {
+            float f[V]; a[i].get(f);
+#pragma unroll
+            for (int j = 0; j < V; ++j) {
+                const int col = c * V + j;
+                f[j] = col < nv ? (ce_exp(f[j] - lse) - (col == lab ? 1.0f : 0.0f)) * invS : 0.0f;
+            }
+            a[i].set(f); a[i].store(xr + (int64_t)c * V);
+        }
     }
 }
 
@@ -651,19 +928,29 @@ void posemb_bwd(hipStream_t s, int dtype, const void *dx, void *dwpe, int64_t B,
 
 void norm_fwd(hipStream_t s, int dtype, bool rms, const void *x, const void *g, const void *b, void *y, float *stats,
               int64_t S, int64_t d, float eps) {
+#define TIO_NORM_FWD_WAVE(NCH)                                                                                              \
+    do {                                                                                                                \
+        if (rms) norm_fwd_wave_k<T, true, NCH><<<nb, TPB, 0, s>>>((const T *)x, (const T *)g, nullptr, (T *)y, stats, S, d, eps); \
+        else norm_fwd_wave_k<T, false, NCH><<<nb, TPB, 0, s>>>((const T *)x, (const T *)g, (const T *)b, (T *)y, stats, S, d, eps); \
+    } while (0)
     TIO_DISPATCH(dtype, {
         const unsigned nb = blocks_for(S, TPB / 64);
-        if (rms) norm_fwd_k<T, true><<<nb, TPB, 0, s>>>((const T *)x, (const T *)g, nullptr, (T *)y, stats, S, d, eps);
+        const int64_t chunks = d / Vec16<T>::N;          // 16-byte chunks per row; 64 lanes take NCH each
+        if (chunks <= 64 * 2) TIO_NORM_FWD_WAVE(2);
+        else if (chunks <= 64 * 8) TIO_NORM_FWD_WAVE(8);
+        else if (chunks <= 64 * 16) TIO_NORM_FWD_WAVE(16);
+        else if (rms) norm_fwd_k<T, true><<<nb, TPB, 0, s>>>((const T *)x, (const T *)g, nullptr, (T *)y, stats, S, d, eps);
         else norm_fwd_k<T, false><<<nb, TPB, 0, s>>>((const T *)x, (const T *)g, (const T *)b, (T *)y, stats, S, d, eps);
     });
+#undef TIO_NORM_FWD_WAVE
 }
 
-#define TIO_NORM_BWD_WAVE(NCH)                                                                                          \
+#define TIO_NORM_BWD(KERNEL, NCH, LDS)                                                                                   \
     do {                                                                                                            \
-        if (rms) norm_bwd_wave_k<T, true, NCH><<<(unsigned)nb, TPB, lds, s>>>((const T *)dy, (const T *)x, stats, (const T *)g, \
-                                                                              (const T *)dres, (T *)dx, part, S, d, rows); \
-        else norm_bwd_wave_k<T, false, NCH><<<(unsigned)nb, TPB, lds, s>>>((const T *)dy, (const T *)x, stats, (const T *)g, \
-                                                                           (const T *)dres, (T *)dx, part, S, d, rows); \
+        if (rms) KERNEL<T, true, NCH><<<(unsigned)nb, TPB, LDS, s>>>((const T *)dy, (const T *)x, stats, (const T *)g,  \
+                                                                     (const T *)dres, (T *)dx, part, S, d, rows);   \
+        else KERNEL<T, false, NCH><<<(unsigned)nb, TPB, LDS, s>>>((const T *)dy, (const T *)x, stats, (const T *)g,     \
+                                                                  (const T *)dres, (T *)dx, part, S, d, rows);      \
     } while (0)
 
 void norm_bwd(hipStream_t s, int dtype, bool rms, const void *dy, const void *x, const float *stats, const void *g,
@@ -671,16 +958,19 @@ void norm_bwd(hipStream_t s, int dtype, bool rms, const void *dy, const void *x,
     const int rows = (int)((S + nb - 1) / nb);
     const size_t lds = ((rms ? 1 : 2) * d + 16) * sizeof(float);
     TIO_DISPATCH(dtype, {
-        const int64_t chunks = d / Vec16<T>::N;          // 16-byte chunks per row; 64 lanes take NCH each
-        if (chunks <= 64 * 2) TIO_NORM_BWD_WAVE(2);
-        else if (chunks <= 64 * 8) TIO_NORM_BWD_WAVE(8);
-        else if (chunks <= 64 * 13 && lds <= 48 * 1024) TIO_NORM_BWD_WAVE(13);   // up to d = 6656 in bf16
+        const int64_t chunks = d / Vec16<T>::N;          // 16-byte chunks per row
+        if (chunks <= 64 * 2) TIO_NORM_BWD(norm_bwd_wave_k, 2, lds);          // a wavefront per row
+        else if (chunks <= TPB) TIO_NORM_BWD(norm_bwd_block_k, 1, 0);         // a workgroup per row
+        else if (chunks <= TPB * 2) TIO_NORM_BWD(norm_bwd_block_k, 2, 0);
+        else if (chunks <= TPB * 4) TIO_NORM_BWD(norm_bwd_block_k, 4, 0);
+        else if (chunks <= TPB * 8) TIO_NORM_BWD(norm_bwd_block_k, 8, 0);
         else if (rms) norm_bwd_k<T, true><<<(unsigned)nb, TPB, lds, s>>>((const T *)dy, (const T *)x, stats, (const T *)g,
                                                                          (const T *)dres, (T *)dx, part, S, d, rows);
         else norm_bwd_k<T, false><<<(unsigned)nb, TPB, lds, s>>>((const T *)dy, (const T *)x, stats, (const T *)g,
                                                                  (const T *)dres, (T *)dx, part, S, d, rows);
     });
 }
+#undef TIO_NORM_BWD
 
 void norm_bwd_params(hipStream_t s, int dtype, bool rms, const float *part, void *dg, void *db, int64_t nb, int64_t d,
                      bool accumulate) {
@@ -693,28 +983,28 @@ void norm_bwd_params(hipStream_t s, int dtype, bool rms, const float *part, void
 void gelu_fwd(hipStream_t s, int dtype, const void *u, void *y, int64_t n) {
     TIO_DISPATCH(dtype, {
         const int64_t nv = n / Vec16<T>::N;
-        gelu_fwd_k<T><<<blocks_for(nv, TPB), TPB, 0, s>>>((const T *)u, (T *)y, nv);
+        gelu_fwd_k<T><<<blocks_for(nv, TPB * ACT_UNROLL), TPB, 0, s>>>((const T *)u, (T *)y, nv);
     });
 }
 
 void gelu_bwd(hipStream_t s, int dtype, void *dact, const void *u, int64_t n) {
     TIO_DISPATCH(dtype, {
         const int64_t nv = n / Vec16<T>::N;
-        gelu_bwd_k<T><<<blocks_for(nv, TPB), TPB, 0, s>>>((T *)dact, (const T *)u, nv);
+        gelu_bwd_k<T><<<blocks_for(nv, TPB * ACT_UNROLL), TPB, 0, s>>>((T *)dact, (const T *)u, nv);
     });
 }
 
 void swiglu_fwd(hipStream_t s, int dtype, const void *gu, void *y, int64_t S, int64_t f) {
     TIO_DISPATCH(dtype, {
         const int64_t n = S * (f / Vec16<T>::N);
-        swiglu_fwd_k<T><<<blocks_for(n, TPB), TPB, 0, s>>>((const T *)gu, (T *)y, S, f);
+        swiglu_fwd_k<T><<<blocks_for(n, TPB * ACT_UNROLL), TPB, 0, s>>>((const T *)gu, (T *)y, S, f);
     });
 }
 
 void swiglu_bwd(hipStream_t s, int dtype, const void *dact, const void *gu, void *dgu, int64_t S, int64_t f) {
     TIO_DISPATCH(dtype, {
         const int64_t n = S * (f / Vec16<T>::N);
-        swiglu_bwd_k<T><<<blocks_for(n, TPB), TPB, 0, s>>>((const T *)dact, (const T *)gu, (T *)dgu, S, f);
+        swiglu_bwd_k<T><<<blocks_for(n, TPB * ACT_UNROLL), TPB, 0, s>>>((const T *)dact, (const T *)gu, (T *)dgu, S, f);
     });
 }
 
@@ -728,7 +1018,16 @@ void rope(hipStream_t s, int dtype, void *qkv, int64_t B, int64_t Tn, int64_t H,
 
 void ce_fwd_bwd(hipStream_t s, int dtype, void *logits, const int32_t *labels, float *losses, int64_t S, int64_t V,
                 int64_t ld, int64_t S_total) {
-    TIO_DISPATCH(dtype, { ce_k<T><<<(unsigned)S, TPB, 0, s>>>((T *)logits, labels, losses, S, V, ld, S_total); });
+#define TIO_CE_REG(NCH) ce_reg_k<T, NCH><<<(unsigned)S, TPB, 0, s>>>((T *)logits, labels, losses, S, V, ld, S_total)
+    TIO_DISPATCH(dtype, {
+        const int64_t chunks = ld / Vec16<T>::N;         // 16-byte chunks per row; TPB threads take NCH each
+        if (chunks <= TPB * 4) TIO_CE_REG(4);
+        else if (chunks <= TPB * 8) TIO_CE_REG(8);
+        else if (chunks <= TPB * 16) TIO_CE_REG(16);
+        else if (chunks <= TPB * 32) TIO_CE_REG(32);
+        else ce_k<T><<<(unsigned)S, TPB, 0, s>>>((T *)logits, labels, losses, S, V, ld, S_total);
+    });
+#undef TIO_CE_REG
 }
 
 void loss_reduce(hipStream_t s, const float *losses, float *loss, int64_t S, int64_t S_total, bool accumulate) {

@@ -80,6 +80,8 @@ struct tio_ctx {
     bool installed = false, params_dirty = true;
     bool failed = false;                                 // a step stopped half-way (HIP or I/O error): tensor state unknown
     std::vector<uint8_t> loaded;                         // per parameter: tio_params_load has been called
+    std::vector<uint8_t> reloaded;                       // per parameter: loaded since the step counter was last reset
+    size_t n_reloaded = 0;
     std::vector<uint8_t> on_dev;                         // per persistent tensor: latest version is in the arena
     std::vector<uint64_t> dev_addr;
     std::vector<uint8_t> in_host1;                       // per persistent tensor: latest version is in a host-tier slot
@@ -609,6 +611,7 @@ int tio_ctx_create(const tio_model_cfg *cfg, const tio_runtime_cfg *rt, tio_ctx 
     }
     if (h > rt->host_bytes) { delete c; return fail(TIO_ERR_OOM_HOST, "slow-tier pool smaller than the persistent tensors"); }
     c->loaded.assign(c->prog.params.size(), 0);
+    c->reloaded.assign(c->prog.params.size(), 0);
     if (hipHostMalloc((void **)&c->loss_pinned, 4096, hipHostMallocDefault) != hipSuccess) { delete c; return fail(TIO_ERR_HIP, "hipHostMalloc failed"); }
     if (file_tier) {
         try {
@@ -704,7 +707,14 @@ int tio_params_load(tio_ctx *c, int32_t index, const float *v, int64_t numel) {
         HIPCHK(hipDeviceSynchronize());
     }
     c->loaded[index] = 1;
-    c->step = 0;
+    // the step counter (AdamW's bias correction) restarts once every parameter has been loaded anew; reloading some of
+    // them leaves it, and the moments of the others, as they are
+    if (!c->reloaded[index]) { c->reloaded[index] = 1; ++c->n_reloaded; }
+    if (c->n_reloaded == c->reloaded.size()) {
+        c->step = 0;
+        c->reloaded.assign(c->reloaded.size(), 0);
+        c->n_reloaded = 0;
+    }
     return TIO_OK;
     TIO_RT_END
 }

@@ -183,3 +183,39 @@ def test_gpt2_small_slow_tier_in_a_file(tmp_path):
             assert info["bytes_read"] == 3 * ce["bytes_per_direction"]
         else:
             assert 0 < info["bytes_read"] < 3 * ce["bytes_per_direction"]
+
+
+def test_two_layers_at_the_30b_widths_and_sequence_length_bitwise_under_cap():
+    """Llama-30B widths (d = 6656, 52 heads of 128, SwiGLU 17920) at the workload's own sequence length of 4096, two layers,
+    one sequence, a small vocabulary: the run under a 55 % cap with the slow tier paced to 25 GB/s gives the bits of the
+    uncapped run (losses and sampled optimizer state), and the kernels at this shape are the ones the full model launches
+    (256 x 256 GEMM tiles, attention with T = 4096)."""
+    import torch
+    import paper_2506_06472_amd as tio
+    from synth import iter_params_pooled
+    cfg = dict(arch="llama", L=2, d=6656, H=52, f=17920, V=4096, T=4096, B=1, precision="bf16", lr=3e-4)
+    bw = 25 * 10**9
+    specs = [(n, (r, c) if r > 1 else (c,), "normal" if (r > 1) else "ones") for n, r, c in tio.tio_param_list(cfg)]
+    from synth import gen_tokens
+    tok, lab = gen_tokens(cfg["B"], cfg["T"], cfg["V"], 3)
+    lt, ll, up, cp, peak = plans_for(cfg, 0.55, bw, 1 << 20)
+    ue, ce = up.export(), cp.export()
+    print(f"peak {peak / 1e9:.2f} GB cap {ce['cap'] / 1e9:.2f} GB entries {len(ce['entries'])} moved {ce['bytes_per_direction'] / 1e9:.2f} GB", flush=True)
+    assert ce["n_forced"] + ce["n_greedy"] > 0
+    hb = max(ue["host_needed"], ce["host_needed"]) + (1 << 20)
+    sample = ["l0.w_qkv", "l1.w_down", "rmsf_g", "w_head"]
+    runs = []
+    for label, plan, arena_bytes in (("uncapped", None, ue["arena_needed"]), ("capped", cp, ce["cap"])):
+        print(label, flush=True)
+        ctx = tio.tio_ctx_create(cfg, arena_bytes, hb, bw if plan is not None else 0)
+        for name, arr in iter_params_pooled(specs, 0):
+            ctx.tio_params_load({name: arr})
+        losses = [ctx.tio_train_step(tok, lab, plan)["loss"] for _ in range(2)]
+        runs.append((losses, read_state(ctx, sample, True)))
+        ctx.close()
+        torch.cuda.empty_cache()
+    (l0, s0), (l1, s1) = runs
+    assert np.array(l0, np.float32).tobytes() == np.array(l1, np.float32).tobytes(), (l0, l1)
+    assert np.isfinite(l0).all() and l0[1] < l0[0], l0
+    for key in s0:
+        assert s0[key].tobytes() == s1[key].tobytes(), key
