@@ -10,13 +10,16 @@ namespace tio {
 struct bf16_t { uint16_t v; };
 
 __device__ __forceinline__ float bf16_bits_to_f32(uint32_t b) { return __uint_as_float(b << 16); }
-// round to nearest even; NaN stays NaN
-__device__ __forceinline__ uint32_t f32_to_bf16_bits(float f) {
-    uint32_t u = __float_as_uint(f);
-    if ((u & 0x7fffffffu) > 0x7f800000u) return 0x7fc0u;
-    u += 0x7fffu + ((u >> 16) & 1u);
-    return u >> 16;
+// two floats -> two bf16 in one word (lo in bits 15:0), round to nearest even, NaN stays NaN: gfx950 converts a pair
+// in one instruction (v_cvt_pk_bf16_f32); doing it by hand costs about a dozen integer operations per pair, which made
+// the bf16 elementwise kernels instruction-bound rather than memory-bound
+typedef __bf16 tio_bf16x2 __attribute__((ext_vector_type(2)));
+typedef float tio_f32x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+    const tio_f32x2 v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, tio_bf16x2));
 }
+__device__ __forceinline__ uint32_t f32_to_bf16_bits(float f) { return pack_bf16x2(f, 0.f) & 0xffffu; }
 
 __device__ __forceinline__ float to_f32(float x) { return x; }
 __device__ __forceinline__ float to_f32(bf16_t x) { return bf16_bits_to_f32(x.v); }
@@ -47,7 +50,7 @@ template <> struct Vec16<bf16_t> {
     __device__ __forceinline__ void set(const float *f) {
         uint32_t w[4];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) w[i] = f32_to_bf16_bits(f[2 * i]) | (f32_to_bf16_bits(f[2 * i + 1]) << 16);
+        for (int i = 0; i < 4; ++i) w[i] = pack_bf16x2(f[2 * i], f[2 * i + 1]);
         raw = make_uint4(w[0], w[1], w[2], w[3]);
     }
 };

@@ -775,40 +775,61 @@ __global__ void __launch_bounds__(TPB) ce_reg_k(T *__restrict__ logits, const in
     }
     const int32_t lab = labels[row];
     const float x_lab = threadIdx.x == 0 ? to_f32(xr[lab]) : 0.f;      // read long before the row is overwritten
+    // only the last chunk that holds logits can be partly padding: the others take the paths without column tests
+    constexpr float L2E = 1.4426950408889634f;
     float m = -INFINITY;
 #pragma unroll
     for (int i = 0; i < NCH; ++i) {
         const int c = threadIdx.x + TPB * i;
         if (c < nchunk) {
             float f[V]; a[i].get(f);
+            if ((c + 1) * V <= nv) {
 #pragma unroll
-            for (int j = 0; j < V; ++j) if (c * V + j < nv) m = fmaxf(m, f[j]);
+                for (int j = 0; j < V; ++j) m = fmaxf(m, f[j]);
+            } else {
+#pragma unroll
+                for (int j = 0; j < V; ++j) if (c * V + j < nv) m = fmaxf(m, f[j]);
+            }
         }
     }
     const float M = block_max<TPB / 64>(m, red);
+    const float kM = -M * L2E;
     float sum = 0.f;
 #pragma unroll
     for (int i = 0; i < NCH; ++i) {
         const int c = threadIdx.x + TPB * i;
         if (c < nchunk) {
             float f[V]; a[i].get(f);
+            if ((c + 1) * V <= nv) {
 #pragma unroll
-            for (int j = 0; j < V; ++j) if (c * V + j < nv) sum += ce_exp(f[j] - M);
+                for (int j = 0; j < V; ++j) sum += __builtin_amdgcn_exp2f(fmaf(f[j], L2E, kM));
+            } else {
+#pragma unroll
+                for (int j = 0; j < V; ++j) if (c * V + j < nv) sum += __builtin_amdgcn_exp2f(fmaf(f[j], L2E, kM));
+            }
         }
     }
     const float tot = block_sum<TPB / 64>(sum, red);
     const float lse = M + logf(tot);
     if (threadIdx.x == 0) losses[row] = lse - x_lab;
-    const float invS = 1.0f / (float)S_total;          // the loss is the mean over the whole batch
+    // gradient of the mean loss over the whole batch: exp(x - lse) / S_total as one exponential, the 1/S_total folded
+    // into the exponent; the label's column is corrected in the one chunk that holds it
+    const float invS = 1.0f / (float)S_total;
+    const float kL = -lse * L2E - log2f((float)S_total);
 #pragma unroll
     for (int i = 0; i < NCH; ++i) {
         const int c = threadIdx.x + TPB * i;
         if (c < nchunk) {
             float f[V]; a[i].get(f);
 #pragma unroll
-            for (int j = 0; j < V; ++j) {
-                const int col = c * V + j;
-                f[j] = col < nv ? (ce_exp(f[j] - lse) - (col == lab ? 1.0f : 0.0f)) * invS : 0.0f;
+            for (int j = 0; j < V; ++j) f[j] = __builtin_amdgcn_exp2f(fmaf(f[j], L2E, kL));
+            if (lab >= c * V && lab < (c + 1) * V) {
+#pragma unroll
+                for (int j = 0; j < V; ++j) if (c * V + j == lab) f[j] -= invS;
+            }
+            if ((c + 1) * V > nv) {
+#pragma unroll
+                for (int j = 0; j < V; ++j) if (c * V + j >= nv) f[j] = 0.f;
             }
             a[i].set(f); a[i].store(xr + (int64_t)c * V);
         }
@@ -857,8 +878,8 @@ __global__ void __launch_bounds__(TPB) adamw_k(const T *__restrict__ g, T *__res
         *reinterpret_cast<float4 *>(v + i0) = vv;
         if (master) {
             uint2 o;
-            o.x = f32_to_bf16_bits(pt[0]) | (f32_to_bf16_bits(pt[1]) << 16);
-            o.y = f32_to_bf16_bits(pt[2]) | (f32_to_bf16_bits(pt[3]) << 16);
+            o.x = pack_bf16x2(pt[0], pt[1]);
+            o.y = pack_bf16x2(pt[2], pt[3]);
             *reinterpret_cast<uint2 *>(w + i0) = o;
         }
     } else {

@@ -175,8 +175,8 @@ __global__ void __launch_bounds__(WGM *WGN * 64)
                         v[2] += __uint_as_float(t.y << 16); v[3] += __uint_as_float(t.y & 0xffff0000u);
                     }
                     uint2 o;
-                    o.x = f32_to_bf16_bits(v[0]) | (f32_to_bf16_bits(v[1]) << 16);
-                    o.y = f32_to_bf16_bits(v[2]) | (f32_to_bf16_bits(v[3]) << 16);
+                    o.x = pack_bf16x2(v[0], v[1]);
+                    o.y = pack_bf16x2(v[2], v[3]);
                     *reinterpret_cast<uint2 *>(C + m * ldc + n) = o;
                 } else {
                     for (int e = 0; e < 4 && n + e < N; ++e) {
@@ -210,8 +210,8 @@ __global__ void __launch_bounds__(256) splitk_reduce_k(const float *__restrict__
             a.z += __uint_as_float(t.y << 16); a.w += __uint_as_float(t.y & 0xffff0000u);
         }
         uint2 o;
-        o.x = f32_to_bf16_bits(a.x) | (f32_to_bf16_bits(a.y) << 16);
-        o.y = f32_to_bf16_bits(a.z) | (f32_to_bf16_bits(a.w) << 16);
+        o.x = pack_bf16x2(a.x, a.y);
+        o.y = pack_bf16x2(a.z, a.w);
         *reinterpret_cast<uint2 *>(C + m * ldc + n) = o;
     } else if (rowsum != nullptr && idx - total < M) {
         const int64_t m = idx - total;
