@@ -156,6 +156,12 @@ typedef struct tio_plan_opts {
      * host_bw = 0 or host_budget = 0: no host tier (default). */
     uint64_t host_bw;                /* bytes/s per direction of the host-memory tier */
     uint64_t host_budget;            /* most bytes host memory may hold for migrated tensors */
+    /* Benefit of a candidate (Section 3.2, "Quantify the benefit and cost").  0 (default): the formula of Algorithm 1,
+     * B = s * (sum of tau over the kernels of the absent region that are over capacity).  1: the prose form, in which a
+     * kernel counts only with the bytes it is over capacity, B = sum of min(s, M'[k] - capacity) * tau[k].  Candidates
+     * are ranked by B / s, compared exactly. */
+    int32_t clamp_benefit;
+    int32_t reserved;
 } tio_plan_opts;
 
 typedef struct tio_step_stats {

@@ -82,7 +82,8 @@ class PlanView(C.Structure):
 
 class PlanOpts(C.Structure):
     _fields_ = [("duplex", C.c_int32), ("layout_retries", C.c_int32), ("min_bytes", C.c_uint64),
-                ("arena_bytes", C.c_uint64), ("host_bw", C.c_uint64), ("host_budget", C.c_uint64)]
+                ("arena_bytes", C.c_uint64), ("host_bw", C.c_uint64), ("host_budget", C.c_uint64),
+                ("clamp_benefit", C.c_int32), ("reserved", C.c_int32)]
 
 
 class StepStats(C.Structure):
@@ -249,8 +250,9 @@ class Plan:
 
 
 def tio_build_plan(trace: Trace, life: Lifetimes, mem_cap_bytes: int, slow_tier_bw: int, duplex=True,
-                   min_bytes=0, arena_bytes=0, layout_retries=24, host_bw=0, host_budget=0) -> Plan:
-    o = PlanOpts(1 if duplex else 0, layout_retries, min_bytes, arena_bytes, int(host_bw), int(host_budget))
+                   min_bytes=0, arena_bytes=0, layout_retries=24, host_bw=0, host_budget=0, clamp_benefit=False) -> Plan:
+    o = PlanOpts(1 if duplex else 0, layout_retries, min_bytes, arena_bytes, int(host_bw), int(host_budget),
+                 1 if clamp_benefit else 0, 0)
     h = C.c_void_p()
     _check(lib().tio_build_plan(trace.h, life.h, C.c_uint64(mem_cap_bytes), C.c_uint64(slow_tier_bw), C.byref(o),
                                 C.byref(h)))

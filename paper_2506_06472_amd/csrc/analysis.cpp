@@ -168,7 +168,7 @@ struct ForcedKey {
 }  // namespace
 
 void select_periods(const Trace &t, const Lifetimes &life, uint64_t cap, uint64_t bw, bool duplex,
-                    uint64_t min_bytes, uint64_t host_bw, uint64_t host_budget, Plan &out) {
+                    uint64_t min_bytes, uint64_t host_bw, uint64_t host_budget, bool clamp_benefit, Plan &out) {
     const int N = t.n_kernels;
     const std::vector<int64_t> &tau = t.tau;
     std::vector<int64_t> T(2 * N + 1, 0);
@@ -199,7 +199,15 @@ void select_periods(const Trace &t, const Lifetimes &life, uint64_t cap, uint64_
     std::vector<Pair> sel;
     auto dur = [&](uint64_t s) -> int64_t { return bw ? (int64_t)(((u128)s * 1000000000ull + bw - 1) / bw) : 0; };
     auto hdur = [&](uint64_t s) -> int64_t { return (int64_t)(((u128)s * 1000000000ull + host_bw - 1) / host_bw); };
-    struct Eval { bool ok; int64_t score, g, t_offloaded, t_prefetch; int32_t k_off, k_pre; };
+    // score: sum of tau over the region C (= B / s of Algorithm 1).  With clamp_benefit the benefit is the prose form of
+    // "Quantify the benefit and cost", B = sum over C of min(s, M'[k] - capacity) * tau[k]: only the bytes a kernel is
+    // actually over capacity count.  Candidates are then ranked by the exact fraction B / s (cross-multiplied in 128 bits).
+    struct Eval { bool ok; int64_t score, g, t_offloaded, t_prefetch; int32_t k_off, k_pre; u128 B; };
+    auto compare_scores = [&](const Eval &a, uint64_t sa, const Eval &b, uint64_t sb) -> int {
+        if (!clamp_benefit) return a.score < b.score ? -1 : (a.score > b.score ? 1 : 0);
+        const u128 l = a.B * (u128)sb, r = b.B * (u128)sa;
+        return l < r ? -1 : (l > r ? 1 : 0);
+    };
 
     // ---- Algorithm 1
     std::vector<int64_t> over(2 * N + 1);
@@ -207,11 +215,11 @@ void select_periods(const Trace &t, const Lifetimes &life, uint64_t cap, uint64_
         over[0] = 0;
         for (int k = 0; k < 2 * N; ++k) over[k + 1] = over[k] + (Mp[k % N] > cap ? tau[k % N] : 0);
         int best = -1;
-        int64_t best_score = 0, bg = 0, bto = 0, btp = 0, bd = 0;
-        int32_t bko = 0, bkp = 0;
+        int64_t bd = 0;
+        Eval best_ev{false, 0, 0, 0, 0, 0, 0, 0};
         // benefit of a candidate on one tier's channels
-        auto evaluate = [&](Channel &c_off, Channel &c_pre, int64_t lo, int64_t hi, int64_t d) -> Eval {
-            Eval e{false, 0, 0, 0, 0, 0, 0};
+        auto evaluate = [&](Channel &c_off, Channel &c_pre, int64_t lo, int64_t hi, int64_t d, uint64_t bytes) -> Eval {
+            Eval e{false, 0, 0, 0, 0, 0, 0, 0};
             e.g = c_off.earliest(lo, hi, d);
             if (e.g < 0) return e;
             e.t_offloaded = e.g + d;
@@ -222,6 +230,11 @@ void select_periods(const Trace &t, const Lifetimes &life, uint64_t cap, uint64_
             if (e.k_off > e.k_pre) return e;
             e.score = over[e.k_pre + 1] - over[e.k_off];             // B / s = sum of tau over the region C
             e.ok = e.score > 0;
+            if (e.ok && clamp_benefit)
+                for (int k = e.k_off; k <= e.k_pre; ++k) {
+                    const uint64_t m = Mp[k % N];
+                    if (m > cap) e.B += (u128)std::min<uint64_t>(bytes, m - cap) * (u128)tau[k % N];
+                }
             return e;
         };
         int best_tier = 0;
@@ -230,28 +243,29 @@ void select_periods(const Trace &t, const Lifetimes &life, uint64_t cap, uint64_
             if (!c.alive) continue;
             int64_t d = dur(c.bytes);
             const int64_t lo = T[c.start + 1], hi = T[c.end];
-            Eval ev = evaluate(ch_off, ch_pre, lo, hi, d);
+            Eval ev = evaluate(ch_off, ch_pre, lo, hi, d, c.bytes);
             int where = 0;
             if (two_tier) {
                 const bool displaced = !ev.ok || ev.g > lo || ev.t_prefetch + d < hi;
                 if (displaced && host_fits(c.bytes, c.start, c.end)) {
-                    const Eval hev = evaluate(hch_off, hch_pre, lo, hi, hdur(c.bytes));
-                    if (hev.ok && (!ev.ok || hev.score > ev.score)) { ev = hev; where = 1; d = hdur(c.bytes); }
+                    const Eval hev = evaluate(hch_off, hch_pre, lo, hi, hdur(c.bytes), c.bytes);
+                    if (hev.ok && (!ev.ok || compare_scores(hev, c.bytes, ev, c.bytes) > 0)) { ev = hev; where = 1; d = hdur(c.bytes); }
                 }
             }
             if (!ev.ok) continue;
-            const int64_t score = ev.score, g = ev.g, t_offloaded = ev.t_offloaded, t_prefetch = ev.t_prefetch;
-            const int32_t k_off = ev.k_off, k_pre = ev.k_pre;
             bool take = best < 0;
             if (!take) {
                 const Cand &o = I[best];
-                take = std::make_tuple(score, c.bytes, -c.start, -c.tensor, -c.end) >
-                       std::make_tuple(best_score, o.bytes, -o.start, -o.tensor, -o.end);
+                const int by_score = compare_scores(ev, c.bytes, best_ev, o.bytes);
+                take = by_score > 0 || (by_score == 0 && std::make_tuple(c.bytes, -c.start, -c.tensor, -c.end) >
+                                                             std::make_tuple(o.bytes, -o.start, -o.tensor, -o.end));
             }
-            if (take) { best = i; best_score = score; bg = g; bto = t_offloaded; btp = t_prefetch; bd = d; bko = k_off; bkp = k_pre; best_tier = where; }
+            if (take) { best = i; best_ev = ev; bd = d; best_tier = where; }
         }
         if (best < 0) break;
         Cand &c = I[best];
+        const int64_t bg = best_ev.g, bto = best_ev.t_offloaded, btp = best_ev.t_prefetch;
+        const int32_t bko = best_ev.k_off, bkp = best_ev.k_pre;
         sel.push_back({c.tensor, c.bytes, c.start, c.end, bko, bkp, 0, 0});
         sel.back().tier = best_tier;
         for (int k = bko; k <= bkp; ++k) Mp[k % N] -= c.bytes;
@@ -706,7 +720,7 @@ Plan build_plan(const Trace &t, const Lifetimes &life, uint64_t cap, uint64_t bw
     auto attempt = [&](uint64_t planning_cap, Plan &p) {
         p = Plan();
         p.cap = cap; p.planning_cap = planning_cap; p.bw = bw; p.structure_hash = t.structure_hash;
-        select_periods(t, life, planning_cap, bw, o.duplex != 0, o.min_bytes, o.host_bw, o.host_budget, p);
+        select_periods(t, life, planning_cap, bw, o.duplex != 0, o.min_bytes, o.host_bw, o.host_budget, o.clamp_benefit != 0, p);
         return assign_addresses(t, life, arena, p);
     };
     for (int r = 0; r <= retries; ++r) {

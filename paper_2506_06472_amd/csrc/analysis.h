@@ -85,7 +85,7 @@ struct PlanError { int code; std::string msg; };
 Plan build_plan(const Trace &t, const Lifetimes &life, uint64_t cap, uint64_t bw, const tio_plan_opts &opts);
 // Algorithm 1 + urgent pass only (no layout); fills pairs, Mp, n_greedy, n_forced.
 void select_periods(const Trace &t, const Lifetimes &life, uint64_t cap, uint64_t bw, bool duplex,
-                    uint64_t min_bytes, uint64_t host_bw, uint64_t host_budget, Plan &out);
+                    uint64_t min_bytes, uint64_t host_bw, uint64_t host_budget, bool clamp_benefit, Plan &out);
 // Address assignment and executor tables; returns false when the arena is too small.
 bool assign_addresses(const Trace &t, const Lifetimes &life, uint64_t arena_bytes, Plan &plan);
 void validate_plan(const Trace &t, const Lifetimes &life, const Plan &plan);   // throws PlanError

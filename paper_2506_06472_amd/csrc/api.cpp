@@ -145,7 +145,7 @@ int tio_build_plan(const tio_trace *trace, const tio_lifetimes *life, uint64_t c
     if (!trace || !life || !out) return fail(TIO_ERR_INVALID_ARG, "null argument");
     if (cap == 0) return fail(TIO_ERR_INVALID_ARG, "capacity must be positive");
     TIO_GUARD_BEGIN
-    tio_plan_opts o{1, 24, 0, 0, 0, 0};
+    tio_plan_opts o{1, 24, 0, 0, 0, 0, 0, 0};
     if (opts) o = *opts;
     static std::atomic<uint64_t> serial{1};
     tio_plan *h = new tio_plan{build_plan(trace->t, life->l, cap, bw, o)};

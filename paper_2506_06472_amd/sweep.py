@@ -35,7 +35,9 @@ def _cfg(name, micro_batches):
 
 
 def sweep(name, bws, micro_batches=1, tau=None, min_bytes=1 << 20, out=sys.stdout, host_bw=0, host_budgets=(0,),
-          shared_channel=False):
+          shared_channel=False, benefits=(False,)):
+    """benefits: which benefit definitions to plan with, one row each: False = the formula of Algorithm 1, True = the
+    prose form in which a kernel counts only with the bytes it is over capacity (tio_plan_opts.clamp_benefit)."""
     cfg, base_peak = _cfg(name, micro_batches)
     lt = tio.tio_trace_build(cfg)
     if tau is not None:
@@ -49,18 +51,23 @@ def sweep(name, bws, micro_batches=1, tau=None, min_bytes=1 << 20, out=sys.stdou
           f"micro-batches {micro_batches}, kernel times {'measured' if tau is not None else 'modelled'}"
           f"{', one channel shared by both directions' if shared_channel else ''}"
           f"{f', host-memory tier at {host_bw / 1e9:.0f} GB/s' if host_bw else ''}", file=out)
-    print(f"{'GB/s':>7} {'host GB':>8} {'step ms':>10} {'tokens/s':>10} {'of ideal':>9} {'GB/direction':>13} {'pairs':>6} {'urgent':>7} {'to host':>8}", file=out)
+    print(f"{'GB/s':>7} {'host GB':>8} {'benefit':>8} {'step ms':>10} {'tokens/s':>10} {'of ideal':>9} {'GB/direction':>13} {'pairs':>6} {'urgent':>7} {'to host':>8}", file=out)
     rows = []
     for bw in bws:
         for hb in host_budgets:
-            plan = tio.tio_build_plan(lt, ll, cap, int(bw), duplex=not shared_channel, min_bytes=min_bytes,
-                                      host_bw=int(host_bw) if hb else 0, host_budget=int(hb))
-            pe = plan.export()
-            step, comp = tio.tio_plan_simulate(lt, plan, int(bw), duplex=not shared_channel)
-            gb = pe["bytes_per_direction"] / 1e9
-            rows.append((bw, hb, step, comp, pe))
-            print(f"{bw / 1e9:7.1f} {hb / 1e9:8.1f} {step / 1e6:10.1f} {tokens / (step / 1e9):10.0f} {comp / step:9.3f} {gb:13.2f} "
-                  f"{pe['n_greedy'] + pe['n_forced']:6d} {pe['n_forced']:7d} {sum(pe['tier']):8d}", file=out)
+            entries = []
+            for clamp in benefits:
+                plan = tio.tio_build_plan(lt, ll, cap, int(bw), duplex=not shared_channel, min_bytes=min_bytes,
+                                          host_bw=int(host_bw) if hb else 0, host_budget=int(hb), clamp_benefit=clamp)
+                pe = plan.export()
+                step, comp = tio.tio_plan_simulate(lt, plan, int(bw), duplex=not shared_channel)
+                gb = pe["bytes_per_direction"] / 1e9
+                rows.append((bw, hb, step, comp, pe))
+                entries.append(pe["entries"])
+                print(f"{bw / 1e9:7.1f} {hb / 1e9:8.1f} {'prose' if clamp else 'formula':>8} {step / 1e6:10.1f} {tokens / (step / 1e9):10.0f} {comp / step:9.3f} {gb:13.2f} "
+                      f"{pe['n_greedy'] + pe['n_forced']:6d} {pe['n_forced']:7d} {sum(pe['tier']):8d}", file=out)
+            if len(entries) == 2:
+                print(f"        the two benefit definitions give {'the same plan' if entries[0] == entries[1] else 'different plans'}", file=out)
     return rows
 
 
@@ -147,13 +154,16 @@ def main(argv=None):
     ap.add_argument("--host-bw", type=float, default=0, help="GB/s per direction of a host-memory tier beside the slow tier")
     ap.add_argument("--host-budget", nargs="+", type=float, default=[0], help="GB of host memory that tier may hold (one row each)")
     ap.add_argument("--shared-channel", action="store_true", help="offloads and prefetches share one channel (a single storage device)")
+    ap.add_argument("--benefit", choices=["formula", "prose", "both"], default="formula",
+                    help="benefit of a candidate: Algorithm 1's formula, the prose form (only the bytes over capacity count), or a row for each")
     a = ap.parse_args(argv)
     tau = np.loadtxt(a.tau, dtype=np.int64) if a.tau else None
     for name in a.workload:
         if a.measure_layer:
             tau = measure_layer_tau(name, a.micro_batches)
         sweep(name, [int(b * 1e9) for b in a.bw], a.micro_batches, tau, a.min_bytes, host_bw=a.host_bw * 1e9,
-              host_budgets=[h * 1e9 for h in a.host_budget], shared_channel=a.shared_channel)
+              host_budgets=[h * 1e9 for h in a.host_budget], shared_channel=a.shared_channel,
+              benefits={"formula": (False,), "prose": (True,), "both": (False, True)}[a.benefit])
         if a.characterize:
             characterize(name, a.micro_batches)
         print()

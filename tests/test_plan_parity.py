@@ -24,10 +24,11 @@ def assert_same_plan(tr, lt, ll, cap, bw, **kw):
         assert e.code == -3, e
         with pytest.raises(ValueError):
             op.build_plan(tr, op.analyze_lifetimes(tr), cap, bw, duplex=kw.get("duplex", True),
-                          min_bytes=kw.get("min_bytes", 0))
+                          min_bytes=kw.get("min_bytes", 0), clamp_benefit=kw.get("clamp_benefit", False))
         return None
     life = op.analyze_lifetimes(tr)
-    ref = op.build_plan(tr, life, pl["planning_cap"], bw, duplex=kw.get("duplex", True), min_bytes=kw.get("min_bytes", 0))
+    ref = op.build_plan(tr, life, pl["planning_cap"], bw, duplex=kw.get("duplex", True), min_bytes=kw.get("min_bytes", 0),
+                        clamp_benefit=kw.get("clamp_benefit", False))
     assert pl["entries"] == ref["entries"]
     assert pl["Mp"] == ref["Mp"]
     assert (pl["n_greedy"], pl["n_forced"]) == (ref["n_greedy"], ref["n_forced"])
@@ -118,6 +119,42 @@ def test_random_synthetic_traces_bit_exact():
         pl = assert_same_plan(tr, lt, ll, cap, bw, duplex=bool(trial % 2), arena_bytes=4 * max(life["M"]))
         n += pl is not None
     assert n > 30
+
+
+def test_prose_benefit_variant_bit_exact_and_different_from_the_formula():
+    """clamp_benefit (a kernel counts only with the bytes it is over capacity, the prose of "Quantify the benefit and
+    cost") through the C ABI against the oracle's exact-fraction ranking: random traces, where the two variants do pick
+    different periods, and the small model traces."""
+    rng = np.random.default_rng(21)
+    n = differ = 0
+    for trial in range(80):
+        tr = random_trace(rng, N=int(rng.integers(5, 40)), n_pers=int(rng.integers(1, 6)),
+                          n_trans=int(rng.integers(3, 30)))
+        tr["tensors"] = [(s * 32, k, nme) for s, k, nme in tr["tensors"]]
+        lt = lib_trace_from_oracle(tr)
+        ll = tio.tio_analyze_lifetimes(lt)
+        life = op.analyze_lifetimes(tr)
+        cap = int(max(life["M"]) * rng.uniform(0.5, 1.0)) // 256 * 256
+        bw = int(10 ** rng.uniform(9, 12.5))
+        kw = dict(duplex=bool(trial % 2), arena_bytes=4 * max(life["M"]))
+        pl = assert_same_plan(tr, lt, ll, cap, bw, clamp_benefit=True, **kw)
+        if pl is None:
+            continue
+        n += 1
+        try:
+            plain = tio.tio_build_plan(lt, ll, cap, bw, **kw).export()
+            differ += plain["entries"] != pl["entries"]
+        except tio.TioError:
+            pass
+    assert n > 30 and differ >= 5, (n, differ)
+    for name, frac, bw in (("tiny_gpt_fp32", 0.5, 25 * 10**9), ("tiny_llama_fp32", 0.4, 10**9), ("tiny_llama_fp32", 0.8, 10**10)):
+        cfg = CONFIGS[name]
+        tr = ot.build_trace(cfg)
+        lt = tio.tio_trace_build(cfg)
+        ll = tio.tio_analyze_lifetimes(lt)
+        cap = int(max(op.analyze_lifetimes(tr)["M"]) * frac)
+        for duplex in (True, False):
+            assert assert_same_plan(tr, lt, ll, cap, bw, duplex=duplex, clamp_benefit=True) is not None
 
 
 def test_uncapped_plan_is_empty_and_layout_valid():
