@@ -441,7 +441,7 @@ def main():
                      "frac": gemm_tflops / gemm_peak, "traffic": (traffic or {}).get("bytes_per_launch"),
                      "traffic_unit": "bytes per launch missing the L2 (rocprofv3 FETCH_SIZE + WRITE_SIZE, calibrated); "
                                      "measured offline, not in this run",
-                     "traffic_provenance": ({k: traffic[k] for k in ("profile", "commit")} if traffic else None),
+                     "traffic_provenance": ({k: traffic[k] for k in ("profile", "kernels_as_of_commit")} if traffic else None),
                      "algorithmic_bytes_per_launch": gemm_bytes / n_gemm,
                      "launches_per_step": n_gemm, "avg_launch_us": gemm_ns / n_gemm / 1e3,
                      "achieved_without_migration": gemm_flops / float(tau[gemm].sum()) / 1e3,

@@ -53,7 +53,7 @@ from .model import param_specs
 K_WEIGHT, K_MASTER, K_M, K_V, K_INPUT, K_ACT, K_GRAD, K_PGRAD = range(8)
 
 READ, WRITE = 1, 2
-NORM_BWD_ROWS = 16          # rows of the token dimension handled by one norm-backward workgroup
+NORM_BWD_ROWS = 8           # rows of the token dimension handled by one norm-backward workgroup
 
 # modelled kernel time constants
 MODEL_FLOPS_PER_S = 1_250_000_000_000_000     # half of the dense bf16 MFMA peak

@@ -55,6 +55,29 @@ template <> struct Vec16<bf16_t> {
     }
 };
 
+// 16-byte accesses through a buffer descriptor: an access whose offset lies at or beyond the descriptor's size reads
+// zeros / is dropped by the hardware, which lets a kernel guard ragged edges without branches around its memory operations
+typedef uint32_t tio_u32x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t buffer_over(const void *base, uint32_t bytes) {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, (int)bytes, 0x00020000);
+}
+__device__ __forceinline__ void buffer_load16(Vec16<float> &v, __amdgpu_buffer_rsrc_t r, uint32_t off) {
+    const tio_u32x4 t = __builtin_amdgcn_raw_buffer_load_b128(r, (int)off, 0, 0);
+    v.raw = make_float4(__uint_as_float(t.x), __uint_as_float(t.y), __uint_as_float(t.z), __uint_as_float(t.w));
+}
+__device__ __forceinline__ void buffer_load16(Vec16<bf16_t> &v, __amdgpu_buffer_rsrc_t r, uint32_t off) {
+    const tio_u32x4 t = __builtin_amdgcn_raw_buffer_load_b128(r, (int)off, 0, 0);
+    v.raw = make_uint4(t.x, t.y, t.z, t.w);
+}
+__device__ __forceinline__ void buffer_store16(const Vec16<float> &v, __amdgpu_buffer_rsrc_t r, uint32_t off) {
+    const tio_u32x4 t = {__float_as_uint(v.raw.x), __float_as_uint(v.raw.y), __float_as_uint(v.raw.z), __float_as_uint(v.raw.w)};
+    __builtin_amdgcn_raw_buffer_store_b128(t, r, (int)off, 0, 0);
+}
+__device__ __forceinline__ void buffer_store16(const Vec16<bf16_t> &v, __amdgpu_buffer_rsrc_t r, uint32_t off) {
+    const tio_u32x4 t = {v.raw.x, v.raw.y, v.raw.z, v.raw.w};
+    __builtin_amdgcn_raw_buffer_store_b128(t, r, (int)off, 0, 0);
+}
+
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);

@@ -256,7 +256,7 @@ __global__ void __launch_bounds__(TPB) norm_fwd_wave_k(const T *__restrict__ x, 
         }
 }
 
-// one workgroup per kNormBwdRows rows, rows in order; column sums for the gain / bias gradients are
+// one workgroup per rows_per_blk rows, rows in order; column sums for the gain / bias gradients are
 // kept in LDS, each column owned by one thread, and written out as one partial row per workgroup
 template <typename T, bool RMS>
 __global__ void __launch_bounds__(TPB) norm_bwd_k(const T *__restrict__ dy, const T *__restrict__ x,
@@ -404,65 +404,79 @@ __global__ void __launch_bounds__(TPB) norm_bwd_wave_k(const T *__restrict__ dy,
     for (int64_t i = threadIdx.x; i < NP * d; i += TPB) p[i] = lds[i];
 }
 
-// Same contract as norm_bwd_k, for rows of at most TPB*NCH 16-byte chunks: the workgroup takes its rows one after the
-// other, a thread owns the same NCH chunks of every row, so a row is read once and the gain / bias gradient sums of
-// a thread's columns stay in its registers over all the rows and go straight to the partial row.  The loads of the
-// next row are issued before the current row is reduced (one barrier per row; the two row sums go through LDS in
-// wavefront order), which keeps two rows of dy, x and the residual gradient in flight per workgroup.
-template <typename T, bool RMS, int NCH>
-__global__ void __launch_bounds__(TPB) norm_bwd_block_k(const T *__restrict__ dy, const T *__restrict__ x,
+// Same contract as norm_bwd_k (one partial row of gain / bias gradient sums per workgroup, ROWS rows per workgroup),
+// for rows of at most NT*NCH 16-byte chunks; which rows a workgroup takes differs (workgroup w takes rows w, w + G,
+// w + 2G, ... of G workgroups, so the grid sweeps every tensor as one contiguous window), so the partial rows hold
+// different subsets than norm_bwd_k's and their total is the same sum in another order.  A thread owns the same NCH
+// chunks of every row, so a row is read once and the gradient sums of a thread's columns stay in its registers over
+// all the rows and go straight to the partial row.  PF rows of dy, x, the residual gradient and the row statistics
+// are in flight per workgroup: a row's registers are refilled with the row PF further on as soon as the row is done
+// (one barrier per row; the two row sums go through LDS in wavefront order).  All row accesses go through buffer
+// descriptors, so chunks past the row's end and rows past the last read zeros and write nothing: there is no branch
+// around a memory operation, and the ROWS rows are unrolled into straight-line code, which lets the compiler count
+// outstanding loads exactly (at a loop header it waits for all of them).
+// What decides this kernel's rate is the number of independent workgroups per compute unit, not the loads in flight
+// per workgroup: at d = 4096 in bf16, 8192 rows, on data that is not in any cache, 32 rows per workgroup (one
+// workgroup per CU) gives 2.2 TB/s, 16 rows 3.3, 8 rows 4.8, 4 rows 4.7, whatever PF is and however the rows are
+// assigned; eight rows per workgroup it is, at the price of a partial row per eight rows.
+template <typename T, bool RMS, bool RES, int NCH, int PF, int ROWS, bool CYCLIC = true, int NT = TPB>
+__global__ void __launch_bounds__(NT) norm_bwd_block_k(const T *__restrict__ dy, const T *__restrict__ x,
                                                         const float *__restrict__ stats, const T *__restrict__ g,
                                                         const T *__restrict__ dres, T *__restrict__ dx,
                                                         float *__restrict__ part, int64_t S, int64_t d, int rows_per_blk) {
     constexpr int V = Vec16<T>::N;
-    constexpr int NP = RMS ? 1 : 2, NW = TPB / 64;
+    constexpr int NP = RMS ? 1 : 2, NW = NT / 64;
+    constexpr uint32_t OUTSIDE = 0x40000000u;
     __shared__ float red[2][2][NW];
     const int cpr = (int)(d / V);
-    const int64_t r0 = (int64_t)blockIdx.x * rows_per_blk;
-    const int64_t r1 = r0 + rows_per_blk < S ? r0 + rows_per_blk : S;
+    const uint32_t row_bytes = (uint32_t)(d * sizeof(T));
+    // a descriptor per row and tensor: rows at or past S have size zero, so they read zeros and write nothing
+    const int64_t G = gridDim.x;
+    auto row_of = [&](int r) -> int64_t { return CYCLIC ? (int64_t)blockIdx.x + (int64_t)r * G : (int64_t)blockIdx.x * ROWS + r; };
+    auto over_row = [&](const T *base, int r) { const int64_t row = row_of(r); return buffer_over(base + (row < S ? row : 0) * d, row < S ? row_bytes : 0u); };
+    auto stats_row = [&](int r) { const int64_t row = row_of(r); return buffer_over(stats + (row < S ? row : 0) * NP, row < S ? (uint32_t)(NP * sizeof(float)) : 0u); };
     const int w = threadIdx.x >> 6, l = threadIdx.x & 63;
+    uint32_t off[NCH];
     float cg[NCH][V], cb[RMS ? 1 : NCH][V];
-    Vec16<T> gv[NCH], a[NCH], b[NCH], rr[NCH], na[NCH], nb[NCH], nr[NCH];
+    Vec16<T> gv[NCH], a[PF][NCH], b[PF][NCH], rr[RES ? PF : 1][NCH];
+    float st_mean[PF], st_rstd[PF];
+    auto fetch = [&](int j, int r) {
+        const __amdgpu_buffer_rsrc_t rs_st = stats_row(r), rs_dy = over_row(dy, r), rs_x = over_row(x, r);
+        if (RMS) { st_mean[j] = 0.f; st_rstd[j] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rs_st, 0, 0, 0)); }
+        else {
+            st_mean[j] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rs_st, 0, 0, 0));
+            st_rstd[j] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rs_st, 4, 0, 0));
+        }
+#pragma unroll
+        for (int i = 0; i < NCH; ++i) {
+            buffer_load16(a[j][i], rs_dy, off[i]);
+            buffer_load16(b[j][i], rs_x, off[i]);
+            if (RES) buffer_load16(rr[j][i], over_row(dres, r), off[i]);
+        }
+    };
 #pragma unroll
     for (int i = 0; i < NCH; ++i) {
-        const int c = threadIdx.x + TPB * i;
-        if (c < cpr) {
-            gv[i].load(g + (int64_t)c * V);
-            if (r0 < r1) {
-                a[i].load(dy + r0 * d + (int64_t)c * V);
-                b[i].load(x + r0 * d + (int64_t)c * V);
-                if (dres) rr[i].load(dres + r0 * d + (int64_t)c * V);
-            }
-        }
+        const int c = threadIdx.x + NT * i;
+        off[i] = c < cpr ? (uint32_t)c * 16u : OUTSIDE;
+        buffer_load16(gv[i], buffer_over(g, row_bytes), off[i]);
 #pragma unroll
         for (int e = 0; e < V; ++e) { cg[i][e] = 0.f; if (!RMS) cb[i][e] = 0.f; }
     }
-    const float inv_d = 1.0f / (float)d;
-    int par = 0;
-    for (int64_t row = r0; row < r1; ++row, par ^= 1) {
-        if (row + 1 < r1) {
 #pragma unroll
-            for (int i = 0; i < NCH; ++i) {
-                const int c = threadIdx.x + TPB * i;
-                if (c < cpr) {
-                    na[i].load(dy + (row + 1) * d + (int64_t)c * V);
-                    nb[i].load(x + (row + 1) * d + (int64_t)c * V);
-                    if (dres) nr[i].load(dres + (row + 1) * d + (int64_t)c * V);
-                }
-            }
-        }
-        const float mean = RMS ? 0.f : stats[2 * row];
-        const float rstd = RMS ? stats[row] : stats[2 * row + 1];
+    for (int j = 0; j < PF; ++j) fetch(j, j);
+    const float inv_d = 1.0f / (float)d;
+#pragma unroll
+    for (int r = 0; r < ROWS; ++r) {                  // rows at or past S (last rows of some workgroups): all zeros, nothing written
+        const int j = r % PF, par = r & 1;
+        const float mean = st_mean[j], rstd = st_rstd[j];
         float s1 = 0.f, s2 = 0.f;
 #pragma unroll
         for (int i = 0; i < NCH; ++i) {
-            if (threadIdx.x + TPB * i < cpr) {
-                float fa[V], fb[V], fg[V]; a[i].get(fa); b[i].get(fb); gv[i].get(fg);
+            float fa[V], fb[V], fg[V]; a[j][i].get(fa); b[j][i].get(fb); gv[i].get(fg);
 #pragma unroll
-                for (int e = 0; e < V; ++e) {
-                    const float xh = (fb[e] - mean) * rstd, dxh = fa[e] * fg[e];
-                    s1 += dxh; s2 += dxh * xh;
-                }
+            for (int e = 0; e < V; ++e) {
+                const float xh = (fb[e] - mean) * rstd, dxh = fa[e] * fg[e];
+                s1 += dxh; s2 += dxh * xh;
             }
         }
         s1 = wave_sum(s1); s2 = wave_sum(s2);
@@ -473,28 +487,27 @@ __global__ void __launch_bounds__(TPB) norm_bwd_block_k(const T *__restrict__ dy
         for (int i = 0; i < NW; ++i) { s1 += red[par][0][i]; s2 += red[par][1][i]; }
         s1 = RMS ? 0.f : s1 * inv_d;
         s2 *= inv_d;
+        const __amdgpu_buffer_rsrc_t rs_dx = over_row(dx, r);
 #pragma unroll
         for (int i = 0; i < NCH; ++i) {
-            const int c = threadIdx.x + TPB * i;
-            if (c < cpr) {
-                float fa[V], fb[V], fg[V], fr[V], out[V]; a[i].get(fa); b[i].get(fb); gv[i].get(fg);
-                if (dres) rr[i].get(fr);
+            float fa[V], fb[V], fg[V], fr[V], out[V]; a[j][i].get(fa); b[j][i].get(fb); gv[i].get(fg);
+            if (RES) rr[j][i].get(fr);
 #pragma unroll
-                for (int e = 0; e < V; ++e) {
-                    const float xh = (fb[e] - mean) * rstd, dxh = fa[e] * fg[e];
-                    out[e] = rstd * (dxh - s1 - xh * s2) + (dres ? fr[e] : 0.f);
-                    cg[i][e] += fa[e] * xh;
-                    if (!RMS) cb[i][e] += fa[e];
-                }
-                Vec16<T> o; o.set(out); o.store(dx + row * d + (int64_t)c * V);
+            for (int e = 0; e < V; ++e) {
+                const float xh = (fb[e] - mean) * rstd, dxh = fa[e] * fg[e];
+                out[e] = rstd * (dxh - s1 - xh * s2) + (RES ? fr[e] : 0.f);
+                cg[i][e] += fa[e] * xh;
+                if (!RMS) cb[i][e] += fa[e];
             }
-            a[i] = na[i]; b[i] = nb[i]; rr[i] = nr[i];
+            Vec16<T> o; o.set(out);
+            buffer_store16(o, rs_dx, off[i]);
         }
+        if (r + PF < ROWS) fetch(j, r + PF);
     }
     float *p = part + (int64_t)blockIdx.x * NP * d;
 #pragma unroll
     for (int i = 0; i < NCH; ++i) {
-        const int c = threadIdx.x + TPB * i;
+        const int c = threadIdx.x + NT * i;
         if (c < cpr) {
 #pragma unroll
             for (int e = 0; e < V; e += 4) {
@@ -966,12 +979,15 @@ void norm_fwd(hipStream_t s, int dtype, bool rms, const void *x, const void *g, 
 #undef TIO_NORM_FWD_WAVE
 }
 
-#define TIO_NORM_BWD(KERNEL, NCH, LDS)                                                                                   \
-    do {                                                                                                            \
-        if (rms) KERNEL<T, true, NCH><<<(unsigned)nb, TPB, LDS, s>>>((const T *)dy, (const T *)x, stats, (const T *)g,  \
-                                                                     (const T *)dres, (T *)dx, part, S, d, rows);   \
-        else KERNEL<T, false, NCH><<<(unsigned)nb, TPB, LDS, s>>>((const T *)dy, (const T *)x, stats, (const T *)g,     \
-                                                                  (const T *)dres, (T *)dx, part, S, d, rows);      \
+// rows per workgroup the unrolled kernel is built for (what the training program asks for); other counts take the loop kernel
+constexpr int NORM_BLOCK_ROWS = 8;
+#define TIO_NORM_BWD_ARGS (const T *)dy, (const T *)x, stats, (const T *)g, (const T *)dres, (T *)dx, part, S, d, rows
+#define TIO_NORM_BWD_BLOCK(NCH, PF)                                                                              \
+    do {                                                                                                         \
+        if (rms && dres) norm_bwd_block_k<T, true, true, NCH, PF, NORM_BLOCK_ROWS><<<(unsigned)nb, TPB, 0, s>>>(TIO_NORM_BWD_ARGS);  \
+        else if (rms) norm_bwd_block_k<T, true, false, NCH, PF, NORM_BLOCK_ROWS><<<(unsigned)nb, TPB, 0, s>>>(TIO_NORM_BWD_ARGS);    \
+        else if (dres) norm_bwd_block_k<T, false, true, NCH, PF, NORM_BLOCK_ROWS><<<(unsigned)nb, TPB, 0, s>>>(TIO_NORM_BWD_ARGS);   \
+        else norm_bwd_block_k<T, false, false, NCH, PF, NORM_BLOCK_ROWS><<<(unsigned)nb, TPB, 0, s>>>(TIO_NORM_BWD_ARGS);            \
     } while (0)
 
 void norm_bwd(hipStream_t s, int dtype, bool rms, const void *dy, const void *x, const float *stats, const void *g,
@@ -980,18 +996,21 @@ void norm_bwd(hipStream_t s, int dtype, bool rms, const void *dy, const void *x,
     const size_t lds = ((rms ? 1 : 2) * d + 16) * sizeof(float);
     TIO_DISPATCH(dtype, {
         const int64_t chunks = d / Vec16<T>::N;          // 16-byte chunks per row
-        if (chunks <= 64 * 2) TIO_NORM_BWD(norm_bwd_wave_k, 2, lds);          // a wavefront per row
-        else if (chunks <= TPB) TIO_NORM_BWD(norm_bwd_block_k, 1, 0);         // a workgroup per row
-        else if (chunks <= TPB * 2) TIO_NORM_BWD(norm_bwd_block_k, 2, 0);
-        else if (chunks <= TPB * 4) TIO_NORM_BWD(norm_bwd_block_k, 4, 0);
-        else if (chunks <= TPB * 8) TIO_NORM_BWD(norm_bwd_block_k, 8, 0);
-        else if (rms) norm_bwd_k<T, true><<<(unsigned)nb, TPB, lds, s>>>((const T *)dy, (const T *)x, stats, (const T *)g,
-                                                                         (const T *)dres, (T *)dx, part, S, d, rows);
-        else norm_bwd_k<T, false><<<(unsigned)nb, TPB, lds, s>>>((const T *)dy, (const T *)x, stats, (const T *)g,
-                                                                 (const T *)dres, (T *)dx, part, S, d, rows);
+        const bool block_ok = rows == NORM_BLOCK_ROWS;
+        if (chunks <= 64 * 2) {                          // a wavefront per row
+            if (rms) norm_bwd_wave_k<T, true, 2><<<(unsigned)nb, TPB, lds, s>>>(TIO_NORM_BWD_ARGS);
+            else norm_bwd_wave_k<T, false, 2><<<(unsigned)nb, TPB, lds, s>>>(TIO_NORM_BWD_ARGS);
+        }
+        else if (block_ok && chunks <= TPB) TIO_NORM_BWD_BLOCK(1, 4);         // a workgroup per row, rows in flight: 4
+        else if (block_ok && chunks <= TPB * 2) TIO_NORM_BWD_BLOCK(2, 4);
+        else if (block_ok && chunks <= TPB * 4) TIO_NORM_BWD_BLOCK(4, 2);
+        else if (block_ok && chunks <= TPB * 8) TIO_NORM_BWD_BLOCK(8, 1);
+        else if (rms) norm_bwd_k<T, true><<<(unsigned)nb, TPB, lds, s>>>(TIO_NORM_BWD_ARGS);
+        else norm_bwd_k<T, false><<<(unsigned)nb, TPB, lds, s>>>(TIO_NORM_BWD_ARGS);
     });
 }
-#undef TIO_NORM_BWD
+#undef TIO_NORM_BWD_BLOCK
+#undef TIO_NORM_BWD_ARGS
 
 void norm_bwd_params(hipStream_t s, int dtype, bool rms, const float *part, void *dg, void *db, int64_t nb, int64_t d,
                      bool accumulate) {

@@ -21,7 +21,7 @@ enum Op : int32_t {
 enum Kind : int32_t { KIND_WEIGHT = 0, KIND_MASTER, KIND_M, KIND_V, KIND_INPUT, KIND_ACT, KIND_GRAD, KIND_PGRAD };
 
 constexpr int kMaxRoles = 8;
-constexpr int kNormBwdRows = 16;   // token rows per norm-backward workgroup (fixes the partials size)
+constexpr int kNormBwdRows = 8;    // token rows per norm-backward workgroup (fixes the partials size)
 
 struct TensorInfo {
     uint64_t bytes;      // payload rounded up to 256
