@@ -181,6 +181,8 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--retime", type=int, default=8,
+                    help="re-timing passes of the planner (0: the paper's plan alone); with passes, the paper's plan is timed as well")
     ap.add_argument("--workload", default="llama_7b_bf16")
     ap.add_argument("--bw", type=float, default=-1, help="slow-tier bytes/s per direction; 0 = unthrottled; default: the workload's (25e9)")
     ap.add_argument("--min-bytes", type=int, default=1 << 20)
@@ -324,22 +326,27 @@ def main():
     if not args.modelled_tau:
         lt.set_tau(tau)
     tp0 = time.perf_counter()
-    plan = tio.tio_build_plan(lt, ll, cap, bw, duplex=not shared, min_bytes=args.min_bytes, host_bw=int(args.host_tier_bw),
-                              host_budget=int(args.host_budget))
+    plan_kw = dict(duplex=not shared, min_bytes=args.min_bytes, host_bw=int(args.host_tier_bw), host_budget=int(args.host_budget))
+    plan = tio.tio_build_plan(lt, ll, cap, bw, retime_passes=args.retime, **plan_kw)
     plan_s = time.perf_counter() - tp0
     pe = plan.export()
+    # the paper's plan (Algorithm 1 run once on the kernel times) beside the re-timed one, when they differ
+    paper_plan = tio.tio_build_plan(lt, ll, cap, bw, **plan_kw) if pe["retime_pass"] > 0 else None
+    ppe = paper_plan.export() if paper_plan is not None else None
     log('ideal ms', ideal_s * 1e3, 'plan: entries', len(pe['entries']), 'moved GB', pe['bytes_per_direction'] / 1e9, 'planner s', plan_s)
+    host_needed = max(pe["host_needed"], ppe["host_needed"] if ppe else 0)
     if tier == "file":
-        host_bytes = max(host_bytes, int(pe["host_needed"] * 1.05) + (64 << 20))
-    elif pe["host_needed"] + (1 << 20) > host_bytes:
+        host_bytes = max(host_bytes, int(host_needed * 1.05) + (64 << 20))
+    elif host_needed + (1 << 20) > host_bytes:
         host = None
-        host_bytes = pe["host_needed"] + (1 << 20)
+        host_bytes = host_needed + (1 << 20)
         host = torch.empty(host_bytes, dtype=torch.uint8, pin_memory=True) if tier == "host" else \
             torch.empty(host_bytes, dtype=torch.uint8, device="cuda:0")
 
     # ---- capped run: the context sees only `cap` bytes of the arena
     ctx = tio.tio_ctx_create(cfg, cap, host_bytes, bw, arena=arena, host=host,
-                             host_tier_bytes=pe["host_tier_needed"] + 4096 if pe["host_tier_needed"] else 0,
+                             host_tier_bytes=max(pe["host_tier_needed"], ppe["host_tier_needed"] if ppe else 0) + 4096
+                             if pe["host_tier_needed"] else 0,
                              host_tier_bw=int(args.host_tier_bw), **file_kw)
     load_params(ctx)
     first = ctx.tio_train_step(tok, lab, plan)
@@ -372,6 +379,22 @@ def main():
     k0, k1, c0, c1 = ctx.tio_step_timeline(N, len(pe["entries"]))
     overlap = interval_overlap(list(zip(k0.tolist(), k1.tolist())), [(a, b) for a, b in zip(c0.tolist(), c1.tolist()) if a >= 0])
     file_info = ctx.tio_file_tier_info() if tier == "file" else None
+    paper = None
+    if paper_plan is not None:
+        # the same context goes on training under the paper's plan: one untimed step to settle, then the timed ones
+        ctx.tio_train_step(tok, lab, paper_plan)
+        torch.cuda.synchronize()
+        tq = time.perf_counter()
+        for _ in range(args.steps):
+            ctx.tio_train_step(tok, lab, paper_plan, time_kernels=True)
+        torch.cuda.synchronize()
+        paper_s = (time.perf_counter() - tq) / args.steps
+        paper = {"what": "Algorithm 1 and the urgent pass run once, on the measured kernel times (Section 3.2 as printed)",
+                 "tokens_per_s": S / paper_s, "ms_per_step": paper_s * 1e3,
+                 "model_predicted_ms_per_step": tio.tio_plan_simulate_engine(lt, paper_plan, bw, duplex=not shared)[0] / 1e6
+                 if (bw and tier != "file") else tio.tio_plan_simulate(lt, paper_plan, bw, duplex=not shared)[0] / 1e6,
+                 "bytes_per_direction": ppe["bytes_per_direction"], "greedy_pairs": ppe["n_greedy"], "urgent_pairs": ppe["n_forced"],
+                 "planning_cap_bytes": ppe["planning_cap"]}
     ctx.close()
     if tier == "file" and os.path.exists(args.file):
         os.remove(args.file)
@@ -422,7 +445,9 @@ def main():
         "model_first_come_first_served_ms_per_step": tio.tio_plan_simulate(lt, plan, bw, duplex=not shared)[0] / 1e6,
         "frac_of_ideal": ideal_s / step_s,
         "migration_bound_ms": mig_bound_s * 1e3, "frac_of_min_ideal_migration_bound": bound_s / step_s,
-        "plan": {"entries": len(pe["entries"]), "greedy_pairs": pe["n_greedy"], "urgent_pairs": pe["n_forced"],
+        "plan": {"how": ("Algorithm 1 re-run on the stalled timeline: pass %d of %d kept" % (pe["retime_pass"], args.retime))
+                        if args.retime else "Algorithm 1 run once",
+                 "entries": len(pe["entries"]), "greedy_pairs": pe["n_greedy"], "urgent_pairs": pe["n_forced"],
                  "host_tier_pairs": sum(pe["tier"]), "host_tier_peak_bytes": pe["host_peak"],
                  "host_tier_bw_bytes_per_s": int(args.host_tier_bw), "host_tier_budget_bytes": int(args.host_budget),
                  "bytes_per_direction": pe["bytes_per_direction"], "planning_cap_bytes": pe["planning_cap"],
@@ -454,7 +479,9 @@ def main():
                             "probe_duplex_write_GBps": file_probe["duplex_write_Bps"] / 1e9,
                             "probe_duplex_read_GBps": file_probe["duplex_read_Bps"] / 1e9,
                             "staging_bytes": args.staging_mb << 20, "chunk_bytes": args.chunk_mb << 20}
-    log('capped ms/step', step_s * 1e3, 'loss', loss)
+    if paper is not None:
+        out["paper_plan"] = paper
+    log('capped ms/step', step_s * 1e3, 'loss', loss, 'paper plan ms/step', paper and paper["ms_per_step"])
     if not args.no_cpu_baseline:
         # the oracle as it stands, fp32, on all host cores (numpy's BLAS threads), on the step's whole batch
         from oracle import model as om

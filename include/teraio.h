@@ -141,6 +141,7 @@ typedef struct tio_plan_view {
     uint64_t host_tier_bytes_needed; /* pool size of the host-memory tier (slots are reused over time) */
     uint64_t host_tier_peak_bytes;   /* most bytes the planner counts in host memory at any kernel (<= the budget) */
     uint64_t host_tier_bw;
+    int32_t retime_pass, reserved3;  /* run of the re-timing loop whose plan this is (0: the first, on the kernel times) */
 } tio_plan_view;
 
 typedef struct tio_plan_opts {
@@ -161,7 +162,14 @@ typedef struct tio_plan_opts {
      * kernel counts only with the bytes it is over capacity, B = sum of min(s, M'[k] - capacity) * tau[k].  Candidates
      * are ranked by B / s, compared exactly. */
     int32_t clamp_benefit;
-    int32_t reserved;
+    /* Re-timing (an extension beyond the paper, default 0 = plan once as the paper does).  n > 0: Algorithm 1 and the
+     * urgent pass are run n more times, each time on the timeline of the iteration as the performance model
+     * (tio_plan_simulate) predicts it under the previous run's plan, i.e. every kernel takes its own time plus the stall
+     * in front of it; every run's plan is simulated on the true kernel times and the one with the shortest predicted
+     * iteration is kept (the first run counts, so the result is never predicted slower than the paper's plan).  Helps
+     * where migration takes longer than compute: the stalled iteration gives the channels several times the compute
+     * time, which the first run cannot see.  tio_plan_view.retime_pass says which run won. */
+    int32_t retime_passes;
 } tio_plan_opts;
 
 typedef struct tio_step_stats {

@@ -107,6 +107,7 @@ def simulate(trace, plan, bw, duplex=True, iterations=3, host_bw=0):
     done_prev = 0            # completion of the previous kernel
     mem_ready = 0            # completion of every offload whose deadline has been passed
     t_iter = []
+    stretched = [0] * N      # last iteration: a kernel's own time plus the stall in front of it
     for it in range(iterations):
         t0 = done_prev
         for k in range(N):
@@ -130,9 +131,10 @@ def simulate(trace, plan, bw, duplex=True, iterations=3, host_bw=0):
                 st = max(st, pre_done.get(p, 0))
             for p in off_deadline[k]:           # offloads issued at this very trigger point
                 st = max(st, off_done.get(p, 0))
+            stretched[k] = st + tau[k] - done_prev
             done_prev = st + tau[k]
         t_iter.append(done_prev - t0)
-    return dict(step_ns=t_iter[-1], compute_ns=sum(tau), per_iteration=t_iter)
+    return dict(step_ns=t_iter[-1], compute_ns=sum(tau), per_iteration=t_iter, stretched=stretched)
 
 
 def simulate_engine(trace, plan, bw, duplex=True, iterations=3, host_bw=0, chunk_bytes=16 << 20, urgent_first=True):

@@ -77,13 +77,14 @@ class PlanView(C.Structure):
                [(n, C.c_uint64) for n in ("cap_bytes", "planning_cap_bytes", "arena_bytes_needed",
                                           "host_bytes_needed", "bytes_per_direction")] + \
                [("n_pairs", C.c_int32), ("reserved2", C.c_int32), ("pair_tier", C.POINTER(C.c_int32))] + \
-               [(n, C.c_uint64) for n in ("host_tier_bytes_needed", "host_tier_peak_bytes", "host_tier_bw")]
+               [(n, C.c_uint64) for n in ("host_tier_bytes_needed", "host_tier_peak_bytes", "host_tier_bw")] + \
+               [("retime_pass", C.c_int32), ("reserved3", C.c_int32)]
 
 
 class PlanOpts(C.Structure):
     _fields_ = [("duplex", C.c_int32), ("layout_retries", C.c_int32), ("min_bytes", C.c_uint64),
                 ("arena_bytes", C.c_uint64), ("host_bw", C.c_uint64), ("host_budget", C.c_uint64),
-                ("clamp_benefit", C.c_int32), ("reserved", C.c_int32)]
+                ("clamp_benefit", C.c_int32), ("retime_passes", C.c_int32)]
 
 
 class StepStats(C.Structure):
@@ -246,13 +247,14 @@ class Plan:
                     arena_needed=v.arena_bytes_needed, host_needed=v.host_bytes_needed,
                     bytes_per_direction=v.bytes_per_direction,
                     tier=[int(x) for x in _arr(v.pair_tier, v.n_pairs, np.int32)],
-                    host_tier_needed=v.host_tier_bytes_needed, host_peak=v.host_tier_peak_bytes, host_bw=v.host_tier_bw)
+                    host_tier_needed=v.host_tier_bytes_needed, host_peak=v.host_tier_peak_bytes, host_bw=v.host_tier_bw, retime_pass=v.retime_pass)
 
 
 def tio_build_plan(trace: Trace, life: Lifetimes, mem_cap_bytes: int, slow_tier_bw: int, duplex=True,
-                   min_bytes=0, arena_bytes=0, layout_retries=24, host_bw=0, host_budget=0, clamp_benefit=False) -> Plan:
+                   min_bytes=0, arena_bytes=0, layout_retries=24, host_bw=0, host_budget=0, clamp_benefit=False,
+                   retime_passes=0) -> Plan:
     o = PlanOpts(1 if duplex else 0, layout_retries, min_bytes, arena_bytes, int(host_bw), int(host_budget),
-                 1 if clamp_benefit else 0, 0)
+                 1 if clamp_benefit else 0, int(retime_passes))
     h = C.c_void_p()
     _check(lib().tio_build_plan(trace.h, life.h, C.c_uint64(mem_cap_bytes), C.c_uint64(slow_tier_bw), C.byref(o),
                                 C.byref(h)))

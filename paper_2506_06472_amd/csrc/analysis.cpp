@@ -538,9 +538,14 @@ bool assign_addresses(const Trace &t, const Lifetimes &life, uint64_t arena_byte
     return top <= arena_bytes;
 }
 
-SimResult simulate_plan(const Trace &t, const Plan &plan, uint64_t bw, bool duplex, int iterations) {
+SimResult simulate_plan(const Trace &t, const Plan &plan, uint64_t bw, bool duplex, int iterations,
+                        std::vector<int64_t> *stretched) {
     const int N = t.n_kernels;
     const size_t np = plan.pairs.size();
+    if (stretched) stretched->assign(N, 0);
+    // entry indices by trigger point, in the plan's issue order (the executor tables may not have been built yet)
+    std::vector<std::vector<int32_t>> entries_at(N);
+    for (int i = 0; i < (int)plan.entries.size(); ++i) entries_at[plan.entries[i].trigger % N].push_back(i);
     std::vector<std::vector<int32_t>> pre_deadline(N), off_deadline(N);
     for (const tio_plan_entry &e : plan.entries)
         (e.kind == TIO_OFFLOAD ? off_deadline : pre_deadline)[e.deadline % N].push_back(e.pair);
@@ -559,7 +564,7 @@ SimResult simulate_plan(const Trace &t, const Plan &plan, uint64_t bw, bool dupl
         const int64_t t0 = done_prev;
         for (int k = 0; k < N; ++k) {
             for (int32_t p : off_deadline[k]) mem_ready = std::max(mem_ready, off_done[p]);
-            for (int32_t ei : plan.entries_at[k]) {
+            for (int32_t ei : entries_at[k]) {
                 const tio_plan_entry &e = plan.entries[ei];
                 const int64_t d = dur(plan.pairs[e.pair]);
                 const int w = plan.pairs[e.pair].tier;
@@ -576,6 +581,7 @@ SimResult simulate_plan(const Trace &t, const Plan &plan, uint64_t bw, bool dupl
             int64_t st = std::max(done_prev, mem_ready);
             for (int32_t p : pre_deadline[k]) st = std::max(st, pre_done[p]);
             for (int32_t p : off_deadline[k]) st = std::max(st, off_done[p]);     // offloads issued at this very trigger point
+            if (stretched) (*stretched)[k] = st + t.tau[k] - done_prev;           // the kernel and the stall in front of it
             done_prev = st + t.tau[k];
         }
         last = done_prev - t0;
@@ -708,6 +714,38 @@ uint64_t address_at(const Plan &plan, int32_t tensor, int32_t k) {
 }
 
 // ------------------------------------------------------------------------------------------------
+// Re-timing (an extension; the paper plans once, on the kernel times of an iteration that does not stall).  When the
+// bytes that must move take longer than the compute, the iteration stalls, and the timeline Algorithm 1 plans on (the
+// sum of the kernel times) is several times shorter than the iteration the engine will run: the channels look full
+// after a fraction of the bytes, the rest is evicted by the urgent pass at the kernels where memory overflows (all
+// offloads in the forward pass, all prefetches in the backward pass), and the two directions end up working one
+// after the other.  Re-timing runs Algorithm 1 again on the timeline of the iteration as the performance model says
+// it executes under the previous plan: kernel k takes its own time plus the stall in front of it.  On that timeline
+// the channels have the time they really have, and the greedy loop spreads both directions over the whole iteration.
+// Every pass is simulated on the true kernel times; the pass with the shortest predicted iteration wins (pass 0 is the
+// paper's plan, so the result is never predicted slower than it).  A plan's validity does not depend on kernel times
+// (residency is counted per kernel index), so every pass yields a valid plan for the same trace.
+// ------------------------------------------------------------------------------------------------
+void select_periods_retimed(const Trace &t, const Lifetimes &life, uint64_t cap, uint64_t bw, bool duplex,
+                            uint64_t min_bytes, uint64_t host_bw, uint64_t host_budget, bool clamp_benefit, int passes,
+                            Plan &out) {
+    select_periods(t, life, cap, bw, duplex, min_bytes, host_bw, host_budget, clamp_benefit, out);
+    out.retime_pass = 0;
+    if (passes <= 0 || bw == 0) return;
+    std::vector<int64_t> stretched;
+    int64_t best_step = simulate_plan(t, out, bw, duplex, 3, &stretched).step_ns;
+    Trace tt = t;
+    for (int pass = 1; pass <= passes; ++pass) {
+        tt.tau = stretched;
+        Plan p;
+        p.cap = out.cap; p.planning_cap = out.planning_cap; p.bw = out.bw; p.structure_hash = out.structure_hash;
+        select_periods(tt, life, cap, bw, duplex, min_bytes, host_bw, host_budget, clamp_benefit, p);
+        const int64_t step = simulate_plan(t, p, bw, duplex, 3, &stretched).step_ns;
+        if (step < best_step) { best_step = step; out = std::move(p); out.retime_pass = pass; }
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
 // plan = selection + layout, with the planning capacity lowered until the layout fits the arena
 // ------------------------------------------------------------------------------------------------
 Plan build_plan(const Trace &t, const Lifetimes &life, uint64_t cap, uint64_t bw, const tio_plan_opts &o) {
@@ -720,7 +758,8 @@ Plan build_plan(const Trace &t, const Lifetimes &life, uint64_t cap, uint64_t bw
     auto attempt = [&](uint64_t planning_cap, Plan &p) {
         p = Plan();
         p.cap = cap; p.planning_cap = planning_cap; p.bw = bw; p.structure_hash = t.structure_hash;
-        select_periods(t, life, planning_cap, bw, o.duplex != 0, o.min_bytes, o.host_bw, o.host_budget, o.clamp_benefit != 0, p);
+        select_periods_retimed(t, life, planning_cap, bw, o.duplex != 0, o.min_bytes, o.host_bw, o.host_budget,
+                               o.clamp_benefit != 0, o.retime_passes, p);
         return assign_addresses(t, life, arena, p);
     };
     for (int r = 0; r <= retries; ++r) {

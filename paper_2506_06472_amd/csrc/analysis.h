@@ -70,6 +70,7 @@ struct Plan {
     std::vector<uint64_t> persistent_home;       // host offset of each persistent tensor's home slot
     // executor tables, indexed by kernel
     std::vector<std::vector<int32_t>> entries_at;        // entry indices with trigger % N == k
+    int32_t retime_pass = 0;                             // which re-timing pass produced the selection (0: the first, on the kernel times)
     std::vector<std::vector<int32_t>> kernel_wait_pre;   // pair ids whose prefetch event kernel k waits for
     std::vector<std::vector<int32_t>> kernel_wait_off;   // pair ids whose offload event kernel k waits for
     std::vector<uint8_t> kernel_needs_event;             // record an event after kernel k
@@ -86,6 +87,11 @@ Plan build_plan(const Trace &t, const Lifetimes &life, uint64_t cap, uint64_t bw
 // Algorithm 1 + urgent pass only (no layout); fills pairs, Mp, n_greedy, n_forced.
 void select_periods(const Trace &t, const Lifetimes &life, uint64_t cap, uint64_t bw, bool duplex,
                     uint64_t min_bytes, uint64_t host_bw, uint64_t host_budget, bool clamp_benefit, Plan &out);
+// select_periods, then `passes` more runs of it on the timeline stretched by the stalls the performance model predicts
+// for the previous run's plan; keeps the run whose plan has the shortest predicted iteration on the true kernel times
+void select_periods_retimed(const Trace &t, const Lifetimes &life, uint64_t cap, uint64_t bw, bool duplex,
+                            uint64_t min_bytes, uint64_t host_bw, uint64_t host_budget, bool clamp_benefit, int passes,
+                            Plan &out);
 // Address assignment and executor tables; returns false when the arena is too small.
 bool assign_addresses(const Trace &t, const Lifetimes &life, uint64_t arena_bytes, Plan &plan);
 void validate_plan(const Trace &t, const Lifetimes &life, const Plan &plan);   // throws PlanError
@@ -97,7 +103,9 @@ void validate_plan(const Trace &t, const Lifetimes &life, const Plan &plan);   /
 // starts when its predecessor, the prefetches due at it and the offloads due at it have completed.
 // Returns the duration of the last of `iterations` consecutive iterations (steady state) in ns.
 struct SimResult { int64_t step_ns, compute_ns; };
-SimResult simulate_plan(const Trace &t, const Plan &plan, uint64_t bw, bool duplex, int iterations);
+// stretched (optional): per kernel of the last simulated iteration, its own time plus the stall in front of it
+SimResult simulate_plan(const Trace &t, const Plan &plan, uint64_t bw, bool duplex, int iterations,
+                        std::vector<int64_t> *stretched = nullptr);
 // The same question for an engine that keeps a ready queue per channel, moves chunks of at most chunk_bytes and lets
 // urgent requests overtake at chunk boundaries (Section 3.2, "Minimize kernel stalls"; Section 3.3).
 SimResult simulate_engine(const Trace &t, const Plan &plan, uint64_t bw, bool duplex, int iterations, uint64_t chunk_bytes,

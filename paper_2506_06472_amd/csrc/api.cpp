@@ -168,6 +168,7 @@ int tio_plan_export(const tio_plan *plan, tio_plan_view *out) {
     out->n_pairs = (int32_t)p.pair_tier.size(); out->reserved2 = 0;
     out->pair_tier = p.pair_tier.data();
     out->host_tier_bytes_needed = p.host_tier_needed; out->host_tier_peak_bytes = p.host_peak; out->host_tier_bw = p.host_bw;
+    out->retime_pass = p.retime_pass; out->reserved3 = 0;
     return TIO_OK;
 }
 

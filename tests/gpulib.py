@@ -14,7 +14,7 @@ def make_inputs(cfg, seed=0):
     return params, tok, lab
 
 
-def plans_for(cfg, cap_frac=None, bw=25 * 10**9, min_bytes=0, tau=None):
+def plans_for(cfg, cap_frac=None, bw=25 * 10**9, min_bytes=0, tau=None, retime_passes=0):
     """(trace, lifetimes, uncapped plan, capped plan or None)"""
     lt = tio.tio_trace_build(cfg)
     if tau is not None:
@@ -25,7 +25,7 @@ def plans_for(cfg, cap_frac=None, bw=25 * 10**9, min_bytes=0, tau=None):
     cp = None
     if cap_frac is not None:
         cap = int(peak * cap_frac) // 256 * 256
-        cp = tio.tio_build_plan(lt, ll, cap, bw, min_bytes=min_bytes)
+        cp = tio.tio_build_plan(lt, ll, cap, bw, min_bytes=min_bytes, retime_passes=retime_passes)
     return lt, ll, up, cp, peak
 
 

@@ -58,9 +58,21 @@ def test_fp32_steps_match_oracle(name):
     ("tiny_gpt_fp32", 0.5, 25 * 10**9, 0), ("tiny_gpt_fp32", 0.3, 10**9, 0), ("tiny_llama_fp32", 0.5, 25 * 10**9, 0),
     ("tiny_llama_fp32", 0.45, 0, 16384)])
 def test_offloading_leaves_numerics_bitwise_unchanged(name, cap_frac, bw, min_bytes):
+    _bitwise_under_cap(name, cap_frac, bw, min_bytes, 0)
+
+
+@pytest.mark.parametrize("name,cap_frac,bw,passes", [("tiny_gpt_fp32", 0.3, 10**8, 4), ("tiny_llama_fp32", 0.5, 10**9, 3)])
+def test_re_timed_plans_leave_numerics_bitwise_unchanged(name, cap_frac, bw, passes):
+    """Plans from the re-timing loop (Algorithm 1 run again on the stalled timeline) at bandwidths where a later pass
+    wins: the capped run still gives the bits of the uncapped one and moves exactly the planned bytes."""
+    ce = _bitwise_under_cap(name, cap_frac, bw, 0, passes)
+    assert ce["retime_pass"] > 0
+
+
+def _bitwise_under_cap(name, cap_frac, bw, min_bytes, passes):
     cfg = CONFIGS[name]
     params, tok, lab = make_inputs(cfg, seed=1)
-    lt, ll, up, cp, peak = plans_for(cfg, cap_frac, bw, min_bytes)
+    lt, ll, up, cp, peak = plans_for(cfg, cap_frac, bw, min_bytes, retime_passes=passes)
     ce = cp.export()
     print(f"{name}: peak {peak} cap {ce['cap']} planning cap {ce['planning_cap']} entries {len(ce['entries'])} "
           f"forced {ce['n_forced']} arena {ce['arena_needed']}", flush=True)
@@ -89,6 +101,7 @@ def test_offloading_leaves_numerics_bitwise_unchanged(name, cap_frac, bw, min_by
     for key in s0:
         assert s0[key].tobytes() == s1[key].tobytes(), key
     assert l0[-1] < l0[0]
+    return ce
 
 
 @pytest.mark.parametrize("cfg", [SMALL_BF16, SMALL_LLAMA_BF16], ids=["gpt", "llama"])

@@ -1,0 +1,140 @@
+"""Re-timed planning (an extension of this build): the oracle's definition against a hand-worked example and against
+what the definition implies, then the library (C ABI) against the oracle, bit for bit."""
+import os
+
+import numpy as np
+import pytest
+
+import paper_2506_06472_amd as tio
+from oracle import plan as op
+from oracle import plan_plain as opp
+from oracle import replay as orp
+from oracle import retime as ort
+from oracle import trace as ot
+from synth import CONFIGS
+from planlib import GOLDEN, load_golden, random_trace
+from test_plan_parity import lib_trace_from_oracle
+
+
+def golden_retime():
+    tr, cap, bw, entries, Mp, _ = load_golden("retime_example.txt")
+    extra = {}
+    for line in open(os.path.join(GOLDEN, "retime_example.txt")):
+        w = line.split("#")[0].split()
+        if w and w[0] in ("step", "stretched"):
+            extra[w[0]] = [int(x) for x in w[1:]]
+    assert len(entries) == 8
+    return tr, cap, bw, entries[:4], entries[4:], Mp, extra["step"], extra["stretched"]
+
+
+def test_hand_worked_example_both_passes():
+    tr, cap, bw, e0, e1, Mp, steps, stretched = golden_retime()
+    life = op.analyze_lifetimes(tr)
+    p0 = ort.build_plan_retimed(tr, life, cap, bw, 0)
+    assert p0["entries"] == e0 and p0["retime_pass"] == 0 and p0["Mp"] == Mp
+    s0 = orp.simulate(tr, p0, bw)
+    assert s0["step_ns"] == steps[0] and s0["stretched"] == stretched
+    p1 = ort.build_plan_retimed(tr, life, cap, bw, 1)
+    assert p1["entries"] == e1 and p1["retime_pass"] == 1 and p1["Mp"] == Mp
+    assert p1["predicted_step_ns"] == steps[1] == orp.simulate(tr, p1, bw)["step_ns"]
+    # the plain planner on the stretched timeline gives the second plan too
+    assert opp.build_plan(dict(tr, tau=stretched), cap, bw)["entries"] == e1
+    assert opp.build_plan(tr, cap, bw)["entries"] == e0
+    # through the C ABI
+    lt = lib_trace_from_oracle(tr)
+    ll = tio.tio_analyze_lifetimes(lt)
+    for passes, want, pas in ((0, e0, 0), (1, e1, 1), (5, e1, 1)):
+        pl = tio.tio_build_plan(lt, ll, cap, bw, arena_bytes=8 * cap, retime_passes=passes).export()
+        assert pl["entries"] == want and pl["retime_pass"] == pas, (passes, pl["entries"])
+    assert tio.tio_plan_simulate(lt, tio.tio_build_plan(lt, ll, cap, bw, arena_bytes=8 * cap, retime_passes=1), bw)[0] == steps[1]
+
+
+def test_what_the_definition_implies_on_random_traces():
+    """Pass 0 is the paper's plan; more passes never predict a slower iteration; every result is a valid plan for the
+    trace with its true kernel times; the stretched times add up to the predicted iteration."""
+    rng = np.random.default_rng(5)
+    improved = 0
+    for trial in range(60):
+        tr = random_trace(rng, N=int(rng.integers(6, 30)), n_pers=int(rng.integers(1, 5)), n_trans=int(rng.integers(3, 20)))
+        life = op.analyze_lifetimes(tr)
+        cap = int(max(life["M"]) * rng.uniform(0.4, 0.95))
+        bw = int(10 ** rng.uniform(8.0, 9.7))            # slower than the compute: iterations stall
+        duplex = bool(trial % 2)
+        try:
+            base = op.build_plan(tr, life, cap, bw, duplex=duplex)
+        except ValueError:
+            continue
+        prev = None
+        for passes in (0, 1, 3, 6):
+            p = ort.build_plan_retimed(tr, life, cap, bw, passes, duplex=duplex)
+            if passes == 0:
+                assert p["entries"] == base["entries"]
+            orp.check_plan(tr, life, p, cap)
+            sim = orp.simulate(tr, p, bw, duplex=duplex)
+            assert sum(sim["stretched"]) == sim["step_ns"]
+            assert prev is None or sim["step_ns"] <= prev
+            prev = sim["step_ns"]
+        improved += prev < orp.simulate(tr, base, bw, duplex=duplex)["step_ns"]
+    assert improved >= 5, improved
+
+
+def assert_same_retimed_plan(tr, lt, ll, cap, bw, passes, **kw):
+    try:
+        pl = tio.tio_build_plan(lt, ll, cap, bw, retime_passes=passes, **kw).export()
+    except tio.TioError as e:
+        assert e.code == -3, e
+        return None
+    life = op.analyze_lifetimes(tr)
+    ref = ort.build_plan_retimed(tr, life, pl["planning_cap"], bw, passes, duplex=kw.get("duplex", True),
+                                 min_bytes=kw.get("min_bytes", 0), clamp_benefit=kw.get("clamp_benefit", False))
+    assert pl["entries"] == ref["entries"]
+    assert pl["Mp"] == ref["Mp"]
+    assert pl["retime_pass"] == ref["retime_pass"]
+    return pl
+
+
+def test_library_bit_exact_on_random_traces():
+    rng = np.random.default_rng(17)
+    n = won_later = 0
+    for trial in range(80):
+        tr = random_trace(rng, N=int(rng.integers(5, 40)), n_pers=int(rng.integers(1, 6)), n_trans=int(rng.integers(3, 30)))
+        tr["tensors"] = [(s * 32, k, nme) for s, k, nme in tr["tensors"]]
+        lt = lib_trace_from_oracle(tr)
+        ll = tio.tio_analyze_lifetimes(lt)
+        life = op.analyze_lifetimes(tr)
+        cap = int(max(life["M"]) * rng.uniform(0.4, 1.0)) // 256 * 256
+        bw = int(10 ** rng.uniform(9, 11.5))
+        pl = assert_same_retimed_plan(tr, lt, ll, cap, bw, int(rng.integers(1, 6)), duplex=bool(trial % 2),
+                                      arena_bytes=4 * max(life["M"]), clamp_benefit=bool(trial % 3 == 0))
+        if pl is not None:
+            n += 1
+            won_later += pl["retime_pass"] > 0
+    assert n > 30 and won_later >= 10, (n, won_later)
+
+
+@pytest.mark.parametrize("name,frac,bw,passes", [("tiny_gpt_fp32", 0.5, 10**8, 4), ("tiny_llama_fp32", 0.4, 10**9, 3),
+                                                 ("tiny_llama_fp32", 0.6, 25 * 10**9, 2)])
+def test_library_bit_exact_on_model_traces(name, frac, bw, passes):
+    cfg = CONFIGS[name]
+    tr = ot.build_trace(cfg)
+    lt = tio.tio_trace_build(cfg)
+    ll = tio.tio_analyze_lifetimes(lt)
+    cap = int(max(op.analyze_lifetimes(tr)["M"]) * frac)
+    for duplex in (True, False):
+        pl = assert_same_retimed_plan(tr, lt, ll, cap, bw, passes, duplex=duplex)
+        assert pl is not None
+        tio.tio_plan_validate(lt, ll, tio.tio_build_plan(lt, ll, cap, bw, duplex=duplex, retime_passes=passes))
+
+
+def test_gpt2_small_at_full_size_bit_exact_and_faster():
+    cfg = CONFIGS["gpt2_small_bf16"]
+    tr = ot.build_trace(cfg)
+    lt = tio.tio_trace_build(cfg)
+    ll = tio.tio_analyze_lifetimes(lt)
+    cap = int(max(op.analyze_lifetimes(tr)["M"]) * cfg["cap_frac"]) // 256 * 256
+    bw = 25 * 10**9
+    pl = assert_same_retimed_plan(tr, lt, ll, cap, bw, 2, min_bytes=1 << 20)
+    assert pl is not None and pl["retime_pass"] > 0
+    once = tio.tio_plan_simulate(lt, tio.tio_build_plan(lt, ll, cap, bw, min_bytes=1 << 20), bw)[0]
+    again = tio.tio_plan_simulate(lt, tio.tio_build_plan(lt, ll, cap, bw, min_bytes=1 << 20, retime_passes=2), bw)[0]
+    assert again < once
