@@ -121,6 +121,23 @@ def test_random_synthetic_traces_bit_exact():
     assert n > 30
 
 
+def test_hand_worked_example_where_the_two_benefit_readings_differ():
+    """tests/golden/plan_example_g.txt: the formula of Algorithm 1 takes the larger of two tensors that tie, the prose
+    reading the one that is just large enough; both oracles and the library through the C ABI."""
+    from oracle import plan_plain as opp
+    tr, cap, bw, entries, _, _ = load_golden("plan_example_g.txt")
+    formula, prose = entries[:2], entries[2:]
+    life = op.analyze_lifetimes(tr)
+    lt = lib_trace_from_oracle(tr)
+    ll = tio.tio_analyze_lifetimes(lt)
+    for clamp, want, Mp in ((False, formula, [500, 300, 300, 500]), (True, prose, [500, 600, 600, 500])):
+        ref = op.build_plan(tr, life, cap, bw, clamp_benefit=clamp)
+        assert ref["entries"] == want and ref["Mp"] == Mp
+        assert opp.build_plan(tr, cap, bw, clamp_benefit=clamp)["entries"] == want
+        pl = tio.tio_build_plan(lt, ll, cap, bw, arena_bytes=4 * cap, clamp_benefit=clamp).export()
+        assert pl["entries"] == want and pl["Mp"] == Mp
+
+
 def test_prose_benefit_variant_bit_exact_and_different_from_the_formula():
     """clamp_benefit (a kernel counts only with the bytes it is over capacity, the prose of "Quantify the benefit and
     cost") through the C ABI against the oracle's exact-fraction ranking: random traces, where the two variants do pick
