@@ -35,7 +35,7 @@ def _cfg(name, micro_batches):
 
 
 def sweep(name, bws, micro_batches=1, tau=None, min_bytes=1 << 20, out=sys.stdout, host_bw=0, host_budgets=(0,),
-          shared_channel=False, benefits=(False,)):
+          shared_channel=False, benefits=(False,), retime_passes=0):
     """benefits: which benefit definitions to plan with, one row each: False = the formula of Algorithm 1, True = the
     prose form in which a kernel counts only with the bytes it is over capacity (tio_plan_opts.clamp_benefit)."""
     cfg, base_peak = _cfg(name, micro_batches)
@@ -50,7 +50,8 @@ def sweep(name, bws, micro_batches=1, tau=None, min_bytes=1 << 20, out=sys.stdou
     print(f"{name}: {len(M)} kernels, uncapped peak {peak / 1e9:.2f} GB, cap {cap / 1e9:.2f} GB, {tokens} tokens/step, "
           f"micro-batches {micro_batches}, kernel times {'measured' if tau is not None else 'modelled'}"
           f"{', one channel shared by both directions' if shared_channel else ''}"
-          f"{f', host-memory tier at {host_bw / 1e9:.0f} GB/s' if host_bw else ''}", file=out)
+          f"{f', host-memory tier at {host_bw / 1e9:.0f} GB/s' if host_bw else ''}"
+          f"{f', planner re-timed ({retime_passes} passes)' if retime_passes else ''}", file=out)
     print(f"{'GB/s':>7} {'host GB':>8} {'benefit':>8} {'step ms':>10} {'tokens/s':>10} {'of ideal':>9} {'GB/direction':>13} {'pairs':>6} {'urgent':>7} {'to host':>8}", file=out)
     rows = []
     for bw in bws:
@@ -58,7 +59,8 @@ def sweep(name, bws, micro_batches=1, tau=None, min_bytes=1 << 20, out=sys.stdou
             entries = []
             for clamp in benefits:
                 plan = tio.tio_build_plan(lt, ll, cap, int(bw), duplex=not shared_channel, min_bytes=min_bytes,
-                                          host_bw=int(host_bw) if hb else 0, host_budget=int(hb), clamp_benefit=clamp)
+                                          host_bw=int(host_bw) if hb else 0, host_budget=int(hb), clamp_benefit=clamp,
+                                          retime_passes=retime_passes)
                 pe = plan.export()
                 step, comp = tio.tio_plan_simulate(lt, plan, int(bw), duplex=not shared_channel)
                 gb = pe["bytes_per_direction"] / 1e9
@@ -156,6 +158,8 @@ def main(argv=None):
     ap.add_argument("--shared-channel", action="store_true", help="offloads and prefetches share one channel (a single storage device)")
     ap.add_argument("--benefit", choices=["formula", "prose", "both"], default="formula",
                     help="benefit of a candidate: Algorithm 1's formula, the prose form (only the bytes over capacity count), or a row for each")
+    ap.add_argument("--retime", type=int, default=0,
+                    help="re-timing passes of the planner (Algorithm 1 run again on the stalled timeline); 0 = the paper's plan")
     a = ap.parse_args(argv)
     tau = np.loadtxt(a.tau, dtype=np.int64) if a.tau else None
     for name in a.workload:
@@ -163,7 +167,7 @@ def main(argv=None):
             tau = measure_layer_tau(name, a.micro_batches)
         sweep(name, [int(b * 1e9) for b in a.bw], a.micro_batches, tau, a.min_bytes, host_bw=a.host_bw * 1e9,
               host_budgets=[h * 1e9 for h in a.host_budget], shared_channel=a.shared_channel,
-              benefits={"formula": (False,), "prose": (True,), "both": (False, True)}[a.benefit])
+              benefits={"formula": (False,), "prose": (True,), "both": (False, True)}[a.benefit], retime_passes=a.retime)
         if a.characterize:
             characterize(name, a.micro_batches)
         print()
