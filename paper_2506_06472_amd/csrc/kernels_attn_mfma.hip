@@ -127,12 +127,85 @@ __device__ __forceinline__ bool head_and_block(int64_t n_heads, int n_blocks, in
 }
 
 // ------------------------------------------------------------------------------------------ forward
+// LDS tiles of the forward kernel: [64 rows][DH] bf16 without padding, filled straight from global memory (no
+// staging registers, no LDS store instructions); the 16-byte chunk c of row r sits at chunk c ^ swz(r).  K is read
+// row-wise (16-byte fragments of 16 consecutive rows at one logical chunk) and V through transposing reads (32 lanes
+// take 64 bytes, an aligned quad of chunks, of each of four consecutive rows); the permutation keeps both free of bank
+// conflicts (the banks span 256 bytes): over the rows that share banks swz takes 16 (DH 128) or 8 (DH 64, two rows per
+// 256 bytes) different values, and the quads of four consecutive rows land on different quads (DH 128:
+// swz = (r%4)*4 + (r/4)%4) or on two quads in each half of the banks (DH 64: swz = ((r/2)%2)*4 + (r/4)%4).
+template <int DH> __device__ __forceinline__ int swz(int r) {
+    return DH == 128 ? (((r & 3) << 2) | ((r >> 2) & 3)) : ((((r >> 1) & 1) << 2) | ((r >> 2) & 3));
+}
+// per-lane parts of the fragment addresses (element offsets into a tile), computed once per kernel: the XOR makes
+// them non-additive in the contraction step, so each step has its own
+template <int DH> struct TileLanes {
+    static constexpr int CPR = DH / 8, KS = DH / 16, DT = DH / 32;
+    int roff[KS];          // row-wise fragment of contraction step ks: row lane%32, chunk 2 ks + lane/32
+    int troff[DT][2];      // transposing fragment of column block i: rows 4 (lane/32) + (lane%16)/4 (+ 8), columns by lane
+    __device__ __forceinline__ TileLanes(int lane) {
+        const int l32 = lane & 31, lhi = lane >> 5;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) roff[ks] = (l32 * CPR + ((ks * 2 + lhi) ^ swz<DH>(l32 & 15))) * 8;
+#pragma unroll
+        for (int i = 0; i < DT; ++i)
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const int rl = 4 * lhi + ((lane & 15) >> 2) + 8 * h;
+                const int chunk = 4 * i + 2 * ((lane >> 4) & 1) + ((lane & 3) >> 1);
+                troff[i][h] = (rl * CPR + (chunk ^ swz<DH>(rl))) * 8 + 4 * (lane & 1);
+            }
+    }
+    // A operand, rows row0 + lane%32 (row0 a multiple of 16), contraction step ks
+    __device__ __forceinline__ bf16x8 row(const uint16_t *lds, int row0, int ks) const {
+        Frag f;
+        f.u = *reinterpret_cast<const uint4 *>(lds + row0 * DH + roff[ks]);
+        return f.v;
+    }
+    // A operand "column 32 i + lane%32, contraction over rows r0 .. r0+15 in the slot order of pack8" (r0 a multiple of 16)
+    __device__ __forceinline__ bf16x8 tr(const uint16_t *lds, int r0, int i) const {
+        typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+        union { s16x4 h[2]; bf16x8 v; } f;
+        f.h[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(lds + r0 * DH + troff[i][0]));
+        f.h[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(lds + r0 * DH + troff[i][1]));
+        return f.v;
+    }
+};
+// A [64][DH] tile on its way from global memory into LDS: a wavefront-wide load fills 1 KiB of consecutive LDS bytes
+// (lane i writes bytes 16 i ..), so which chunk a lane fetches decides where it lands: lane i of block b fetches, for
+// row b*RPB + i/CPR, the logical chunk (i%CPR) ^ swz(row).  Rows past the sequence lie outside the descriptor and
+// arrive as zeros.
+template <int DH> struct DmaTile {
+    static constexpr int CPR = DH / 8, RPB = 64 / CPR, BLOCKS = 64 * DH * 2 / 1024, PER = BLOCKS / (NT / 64);
+    static_assert(BLOCKS % (NT / 64) == 0, "blocks divide over the wavefronts");
+    uint32_t voff[PER];
+    __device__ __forceinline__ DmaTile(uint32_t ld_bytes, int wave, int lane) {
+#pragma unroll
+        for (int i = 0; i < PER; ++i) {
+            const int row = (i * (NT / 64) + wave) * RPB + lane / CPR;
+            voff[i] = (uint32_t)row * ld_bytes + (uint32_t)(((lane % CPR) ^ swz<DH>(row & 15)) * 16);
+        }
+    }
+    // rows row0 .. row0+63 of the head behind rsrc to the tile at LDS address lds_addr
+    __device__ __forceinline__ void load(i32x4 rsrc, uint32_t row0, uint32_t ld_bytes, uint32_t lds_addr, int wave) const {
+        const uint32_t soff = __builtin_amdgcn_readfirstlane(row0 * ld_bytes);
+#pragma unroll
+        for (int i = 0; i < PER; ++i) load_to_lds_b128(rsrc, lds_addr + (uint32_t)(i * (NT / 64) + wave) * 1024u, voff[i], soff);
+    }
+};
+
+// Scores are produced transposed (keys x queries); a 64-key tile is handled as two groups of 32 keys.  The K
+// fragments run through a ring of registers RING fragments ahead of their products: left to itself the compiler reads
+// every fragment into the same registers right before its product and waits for it, sixteen exposed LDS latencies per
+// tile.  Both score products are issued first; the softmax arithmetic of the first group then runs on the vector ALU
+// while the matrix cores are still busy with the second group's scores, and that of the second group while they
+// accumulate the first group's P.V.
 template <int DH>
 __global__ void __launch_bounds__(NT, 2) attn_fwd_mfma_k(const uint16_t *__restrict__ qkv, uint16_t *__restrict__ o,
                                                       float *__restrict__ lse, int64_t Bn, int64_t Tn, int64_t H, float scale) {
-    constexpr int KS = DH / 16, DT = DH / 32, PK = tile_pitch<DH>(), TE = RowTile<DH>::ELEMS;
-    extern __shared__ __attribute__((aligned(16))) uint16_t smem[];      // [2 buffers][K tile | V tile]
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, l32 = lane & 31, lhi = lane >> 5;
+    constexpr int KS = DH / 16, DT = DH / 32, TE = 64 * DH, RING = 4;
+    extern __shared__ __attribute__((aligned(1024))) uint16_t smem[];    // [2 buffers][K tile | V tile]
+    const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63, l32 = lane & 31, lhi = lane >> 5;
     const int64_t d = H * DH, ld = 3 * d;
     const uint32_t ldb = (uint32_t)(ld * 2);
     const int nblk = (int)((Tn + 127) / 128);
@@ -143,9 +216,13 @@ __global__ void __launch_bounds__(NT, 2) attn_fwd_mfma_k(const uint16_t *__restr
     const int q0 = (nblk - 1 - blk) * 128;                               // longest rows first
     const int q0w = q0 + wave * 32, q = q0w + l32;
     const uint16_t *qb = qkv + b * Tn * ld + h * DH;
-    const __amdgpu_buffer_rsrc_t rsQ = head_rsrc(qb, Tn, ld, DH), rsK = head_rsrc(qb + d, Tn, ld, DH), rsV = head_rsrc(qb + 2 * d, Tn, ld, DH);
+    const __amdgpu_buffer_rsrc_t rsQ = head_rsrc(qb, Tn, ld, DH);
+    const uint32_t head_bytes = (uint32_t)(((Tn - 1) * ld + DH) * 2);
+    const i32x4 rsK = make_rsrc(qb + d, head_bytes), rsV = make_rsrc(qb + 2 * d, head_bytes);
     const float c = scale * LOG2E;
-    const int trb = tr_lane_base(PK, lane);
+    const TileLanes<DH> L(lane);
+    const DmaTile<DH> dma(ldb, wave, lane);
+    const uint32_t lds0 = __builtin_amdgcn_readfirstlane(lds_address(smem));
 
     bf16x8 qf[KS];
 #pragma unroll
@@ -157,40 +234,40 @@ __global__ void __launch_bounds__(NT, 2) attn_fwd_mfma_k(const uint16_t *__restr
     const int kv_end = q0 + 128 < (int)Tn ? q0 + 128 : (int)Tn;
     const int ntiles = (kv_end + 63) / 64;
 
-    RowTile<DH> tk, tv;
-    tk.load(rsK, 0, ldb, tid);
-    tv.load(rsV, 0, ldb, tid);
-    tk.store(smem, tid);
-    tv.store(smem + TE, tid);
-    if (ntiles > 1) {
-        tk.load(rsK, 64, ldb, tid);
-        tv.load(rsV, 64, ldb, tid);
-    }
+    dma.load(rsK, 0, ldb, lds0, wave);
+    dma.load(rsV, 0, ldb, lds0 + TE * 2, wave);
+    __builtin_amdgcn_s_waitcnt(0x0F70);                 // vmcnt(0): this wavefront's part of tile 0 has landed
     __syncthreads();
     for (int t = 0; t < ntiles; ++t) {
         const int j0 = t * 64;
         const uint16_t *Ks = smem + (t & 1) * 2 * TE, *Vs = Ks + TE;
-        if (t + 1 < ntiles) {
-            uint16_t *nx = smem + ((t + 1) & 1) * 2 * TE;
-            tk.store(nx, tid);
-            tv.store(nx + TE, tid);
-            if (t + 2 < ntiles) {
-                tk.load(rsK, j0 + 128, ldb, tid);
-                tv.load(rsV, j0 + 128, ldb, tid);
-            }
+        if (t + 1 < ntiles) {                           // the other buffer is free since the barrier that ended tile t-1
+            const uint32_t nx = lds0 + (uint32_t)((t + 1) & 1) * 2 * TE * 2;
+            dma.load(rsK, (uint32_t)j0 + 64, ldb, nx, wave);
+            dma.load(rsV, (uint32_t)j0 + 64, ldb, nx + TE * 2, wave);
         }
         if (j0 <= q0w + 31) {
-            // The tile is handled as two groups of 32 keys.  Both score products are issued first; the
-            // softmax arithmetic of the first group then runs on the vector ALU while the matrix cores
-            // are still busy with the second group's scores, and that of the second group while they
-            // accumulate the first group's P.V.
             floatx16 s[2];
+            {
+                constexpr int N = 2 * KS;
+                bf16x8 ring[RING];
 #pragma unroll
-            for (int kt = 0; kt < 2; ++kt) {
-                s[kt] = zero16();
+                for (int i = 0; i < RING; ++i) ring[i] = L.row(Ks, (i / KS) * 32, i % KS);
+                s[0] = zero16();
+                s[1] = zero16();
 #pragma unroll
-                for (int ks = 0; ks < KS; ++ks)
-                    s[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(row_frag(Ks, PK, kt * 32 + l32, ks * 16 + lhi * 8), qf[ks], s[kt], 0, 0, 0);
+                for (int idx = 0; idx < N; ++idx) {
+                    s[idx / KS] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ring[idx % RING], qf[idx % KS], s[idx / KS], 0, 0, 0);
+                    if (idx + RING < N) ring[idx % RING] = L.row(Ks, ((idx + RING) / KS) * 32, (idx + RING) % KS);
+                }
+                // pin the order: RING reads, then one product and one read in turn, then the last products
+                __builtin_amdgcn_sched_group_barrier(0x100, RING, 0);
+#pragma unroll
+                for (int idx = 0; idx < N - RING; ++idx) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                }
+                __builtin_amdgcn_sched_group_barrier(0x008, RING, 0);
             }
             const bool diag = j0 + 63 > q0w;           // the tile crosses the diagonal of some row of this wavefront
 #pragma unroll
@@ -229,11 +306,12 @@ __global__ void __launch_bounds__(NT, 2) attn_fwd_mfma_k(const uint16_t *__restr
                 const bf16x8 p0 = pack8<0>(s[kt]), p1 = pack8<8>(s[kt]);
 #pragma unroll
                 for (int i = 0; i < DT; ++i) {
-                    oacc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tr_frag(Vs, PK, trb, kt * 32, i * 32), p0, oacc[i], 0, 0, 0);
-                    oacc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tr_frag(Vs, PK, trb, kt * 32 + 16, i * 32), p1, oacc[i], 0, 0, 0);
+                    oacc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(L.tr(Vs, kt * 32, i), p0, oacc[i], 0, 0, 0);
+                    oacc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(L.tr(Vs, kt * 32 + 16, i), p1, oacc[i], 0, 0, 0);
                 }
             }
         }
+        __builtin_amdgcn_s_waitcnt(0x0F70);             // vmcnt(0): this wavefront's part of tile t+1 has landed
         __syncthreads();
     }
     l += __shfl_xor(l, 32, 64);
@@ -501,6 +579,7 @@ __global__ void __launch_bounds__(NT, 2) attn_bwd_dkv_mfma_k(const uint16_t *__r
     }
 }
 
+template <int DH> constexpr size_t fwd_smem() { return (size_t)2 * 2 * 64 * DH * 2; }      // unpadded tiles
 template <int DH> constexpr size_t kv_smem() { return (size_t)2 * 2 * RowTile<DH>::ELEMS * 2; }
 template <int DH> constexpr size_t dkv_smem() { return (size_t)2 * (2 * RowTile<DH>::ELEMS + 256) * 2; }
 
@@ -518,11 +597,11 @@ void attn_fwd_mfma(hipStream_t s, const void *qkv, void *o, float *lse, int64_t 
     const float scale = 1.0f / sqrtf((float)dh);
     static bool attr_set = false;
     if (!attr_set) {       // head dimension 128 needs more than the default 64 KiB of LDS
-        (void)hipFuncSetAttribute((const void *)attn_fwd_mfma_k<128>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kv_smem<128>());
+        (void)hipFuncSetAttribute((const void *)attn_fwd_mfma_k<128>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)fwd_smem<128>());
         attr_set = true;
     }
-    if (dh == 64) attn_fwd_mfma_k<64><<<grid, NT, kv_smem<64>(), s>>>((const uint16_t *)qkv, (uint16_t *)o, lse, B, Tn, H, scale);
-    else attn_fwd_mfma_k<128><<<grid, NT, kv_smem<128>(), s>>>((const uint16_t *)qkv, (uint16_t *)o, lse, B, Tn, H, scale);
+    if (dh == 64) attn_fwd_mfma_k<64><<<grid, NT, fwd_smem<64>(), s>>>((const uint16_t *)qkv, (uint16_t *)o, lse, B, Tn, H, scale);
+    else attn_fwd_mfma_k<128><<<grid, NT, fwd_smem<128>(), s>>>((const uint16_t *)qkv, (uint16_t *)o, lse, B, Tn, H, scale);
 }
 
 void attn_bwd_mfma(hipStream_t s, const void *dO, const void *qkv, const float *lse, const float *delta, void *dqkv,

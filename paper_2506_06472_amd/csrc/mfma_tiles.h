@@ -14,12 +14,45 @@ namespace k {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
+typedef int i32x4 __attribute__((ext_vector_type(4)));
+
 constexpr int LDS_PAD = 8;     // bf16 elements (16 bytes) appended to every LDS row
 
 union Frag {
     uint4 u;
     bf16x8 v;
 };
+
+// ---- tiles from global memory straight into LDS
+// One wavefront-wide 16-byte-per-lane load from a buffer straight into LDS: lane i's bytes land at
+// lds_addr + 16 i.  Written as inline assembly so that the compiler does not order the wavefront's later LDS reads
+// behind it (it would wait for every outstanding load before each read of LDS): the kernel waits for these loads
+// itself, with s_waitcnt vmcnt before the barrier that publishes a stage.  M0 holds the LDS address; one wait
+// state separates its write from the load.
+__device__ __forceinline__ void load_to_lds_b128(i32x4 rsrc, uint32_t lds_addr, uint32_t voff, uint32_t soff) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+                 :
+                 : "s"(lds_addr), "v"(voff), "s"(rsrc), "s"(soff)
+                 : "memory", "m0");
+}
+
+// buffer descriptor over [base, base + bytes): raw (stride 0) addressing, out-of-range lanes read zero
+__device__ __forceinline__ i32x4 make_rsrc(const void *base, uint32_t bytes) {
+    const uint64_t a = (uint64_t)(uintptr_t)base;
+    i32x4 r;
+    r[0] = __builtin_amdgcn_readfirstlane((int)(uint32_t)a);
+    r[1] = __builtin_amdgcn_readfirstlane((int)(uint32_t)(a >> 32) & 0xffff);
+    r[2] = __builtin_amdgcn_readfirstlane((int)bytes);
+    r[3] = 0x00020000;
+    return r;
+}
+
+__device__ __forceinline__ uint32_t lds_address(const void *p) {
+    return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const unsigned char *)p;
+}
+
+// byte offsets of valid lanes stay below 2^30; a lane that must read zeros adds this and leaves the descriptor's range
+constexpr uint32_t DL_OOB = 0x40000000u;
 
 // ---- staging of one operand tile: global -> registers -> LDS ([row][k], row stride BK+LDS_PAD)
 template <int ROWS, int BK, int NT, bool KM> struct Stage;
