@@ -10,8 +10,12 @@
 // operand.  The operand whose contraction index is the sequence position (V in P.V, K in dS.K, Q and dO
 // in the dK/dV products) is read from the same row-major tile with the transposing LDS read
 // (ds_read_b64_tr_b16), in the slot order the accumulator registers dictate: no transposed copies.
-// Tiles are fetched with raw buffer loads (rows past the end of the sequence read as zero) one tile
-// ahead into registers and written to the other half of a double LDS buffer, so a tile costs one barrier.
+// Tiles go from global memory straight into the other half of a double LDS buffer one tile ahead (buffer
+// loads with the LDS bit; rows past the end of the sequence arrive as zeros), so a tile costs one barrier and
+// neither staging registers nor LDS store instructions.  The tiles are unpadded; a permutation of the 16-byte
+// chunks of every row, applied through the choice of the chunk each lane fetches, keeps both kinds of
+// fragment reads free of bank conflicts.  The fragments of the first products of a tile run through a small
+// ring of registers a few fragments ahead of the products that use them.
 // Statistics are fp32, exp2 with the 1/sqrt(dh) scale folded into the exponent; the causal mask is
 // applied only on tiles that cross the diagonal; the backward pass recomputes P from the saved
 // log-sum-exp; dQ and dK/dV are separate launches, so every sum has a fixed order and no atomics.
@@ -48,25 +52,6 @@ template <int R0> __device__ __forceinline__ bf16x8 pack8(const floatx16 &v) {
     f.u = make_uint4(pack2(v[R0], v[R0 + 1]), pack2(v[R0 + 2], v[R0 + 3]), pack2(v[R0 + 4], v[R0 + 5]), pack2(v[R0 + 6], v[R0 + 7]));
     return f.v;
 }
-// A operand from a row-major LDS tile: row, 8 consecutive elements
-__device__ __forceinline__ bf16x8 row_frag(const uint16_t *lds, int pitch, int row, int col) {
-    Frag f;
-    f.u = *reinterpret_cast<const uint4 *>(lds + row * pitch + col);
-    return f.v;
-}
-// A operand "column c0 + lane%32, contraction over rows r0 .. r0+15 in the slot order of pack8" from a
-// row-major LDS tile.  `base` is the per-lane part of the address (see tr_lane_base).
-__device__ __forceinline__ int tr_lane_base(int pitch, int lane) {
-    return (4 * (lane >> 5) + ((lane & 15) >> 2)) * pitch + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
-}
-__device__ __forceinline__ bf16x8 tr_frag(const uint16_t *lds, int pitch, int base, int r0, int c0) {
-    typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
-    const uint16_t *p = lds + base + r0 * pitch + c0;
-    union { s16x4 h[2]; bf16x8 v; } f;
-    f.h[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(p));
-    f.h[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(p + 8 * pitch));
-    return f.v;
-}
 __device__ __forceinline__ floatx16 zero16() {
     floatx16 z;
 #pragma unroll
@@ -88,32 +73,6 @@ __device__ __forceinline__ bf16x8 buf_frag(__amdgpu_buffer_rsrc_t rsrc, uint32_t
     f.u = buf_load(rsrc, off);
     return f.v;
 }
-
-// Row pitch of the LDS tiles.  A tile is read both row-wise (16-byte fragments, 16 consecutive rows at a
-// time: the pitch must be an odd multiple of 16 bytes) and through transposing reads (four consecutive
-// rows, 32 bytes each: these must not overlap modulo the 256 bytes the banks span).  144 bytes does both
-// for 128-byte rows; for 256-byte rows 272 would make neighbouring rows overlap, 304 does not.
-template <int DH> constexpr int tile_pitch() { return DH == 128 ? DH + 24 : DH + LDS_PAD; }
-
-// a [64][DH] tile of rows row0.. of one head: registers on the way from memory to LDS ([row][pitch])
-template <int DH> struct RowTile {
-    static constexpr int PITCH = tile_pitch<DH>(), CPR = DH / 8, PER = 64 * CPR / NT, ELEMS = 64 * PITCH;
-    u32x4 r[PER];
-    __device__ __forceinline__ void load(__amdgpu_buffer_rsrc_t rsrc, int64_t row0, uint32_t ld_bytes, int tid) {
-#pragma unroll
-        for (int i = 0; i < PER; ++i) {
-            const int c = tid + i * NT, row = c / CPR, kc = c % CPR;
-            r[i] = buf_load(rsrc, (uint32_t)(row0 + row) * ld_bytes + kc * 16);
-        }
-    }
-    __device__ __forceinline__ void store(uint16_t *lds, int tid) const {
-#pragma unroll
-        for (int i = 0; i < PER; ++i) {
-            const int c = tid + i * NT, row = c / CPR, kc = c % CPR;
-            *reinterpret_cast<u32x4 *>(lds + row * PITCH + kc * 8) = r[i];
-        }
-    }
-};
 
 // Workgroup index -> (batch*head, block of 128 rows).  Workgroups are dealt to the 8 XCDs round-robin and
 // each XCD has its own L2, so all row blocks of one head are given to one XCD (head = 8*i + xcd): the K and
@@ -336,9 +295,9 @@ template <int DH>
 __global__ void __launch_bounds__(NT, 2) attn_bwd_dq_mfma_k(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ qkv,
                                                          const float *__restrict__ lse, const float *__restrict__ delta,
                                                          uint16_t *__restrict__ dqkv, int64_t Bn, int64_t Tn, int64_t H, float scale) {
-    constexpr int KS = DH / 16, DT = DH / 32, PK = tile_pitch<DH>(), TE = RowTile<DH>::ELEMS;
-    extern __shared__ __attribute__((aligned(16))) uint16_t smem[];      // [2 buffers][K tile | V tile]
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, l32 = lane & 31, lhi = lane >> 5;
+    constexpr int KS = DH / 16, DT = DH / 32, TE = 64 * DH, RING = 4;
+    extern __shared__ __attribute__((aligned(1024))) uint16_t smem[];    // [2 buffers][K tile | V tile], filled as in the forward kernel
+    const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63, l32 = lane & 31, lhi = lane >> 5;
     const int64_t d = H * DH, ld = 3 * d;
     const uint32_t ldb = (uint32_t)(ld * 2);
     const int nblk = (int)((Tn + 127) / 128);
@@ -349,11 +308,15 @@ __global__ void __launch_bounds__(NT, 2) attn_bwd_dq_mfma_k(const uint16_t *__re
     const int q0 = (nblk - 1 - blk) * 128;
     const int q0w = q0 + wave * 32, q = q0w + l32;
     const uint16_t *qb = qkv + b * Tn * ld + h * DH;
-    const __amdgpu_buffer_rsrc_t rsQ = head_rsrc(qb, Tn, ld, DH), rsK = head_rsrc(qb + d, Tn, ld, DH), rsV = head_rsrc(qb + 2 * d, Tn, ld, DH);
+    const __amdgpu_buffer_rsrc_t rsQ = head_rsrc(qb, Tn, ld, DH);
+    const uint32_t head_bytes = (uint32_t)(((Tn - 1) * ld + DH) * 2);
+    const i32x4 rsK = make_rsrc(qb + d, head_bytes), rsV = make_rsrc(qb + 2 * d, head_bytes);
     const __amdgpu_buffer_rsrc_t rsG = head_rsrc(dO + b * Tn * d + h * DH, Tn, d, DH);
     const float c = scale * LOG2E;
     const bool live = q < Tn;
-    const int trb = tr_lane_base(PK, lane);
+    const TileLanes<DH> L(lane);
+    const DmaTile<DH> dma(ldb, wave, lane);
+    const uint32_t lds0 = __builtin_amdgcn_readfirstlane(lds_address(smem));
 
     bf16x8 qf[KS], gf[KS];
 #pragma unroll
@@ -369,38 +332,42 @@ __global__ void __launch_bounds__(NT, 2) attn_bwd_dq_mfma_k(const uint16_t *__re
     const int kv_end = q0 + 128 < (int)Tn ? q0 + 128 : (int)Tn;
     const int ntiles = (kv_end + 63) / 64;
 
-    RowTile<DH> tk, tv;
-    tk.load(rsK, 0, ldb, tid);
-    tv.load(rsV, 0, ldb, tid);
-    tk.store(smem, tid);
-    tv.store(smem + TE, tid);
-    if (ntiles > 1) {
-        tk.load(rsK, 64, ldb, tid);
-        tv.load(rsV, 64, ldb, tid);
-    }
+    dma.load(rsK, 0, ldb, lds0, wave);
+    dma.load(rsV, 0, ldb, lds0 + TE * 2, wave);
+    __builtin_amdgcn_s_waitcnt(0x0F70);                 // vmcnt(0): this wavefront's part of tile 0 has landed
     __syncthreads();
     for (int t = 0; t < ntiles; ++t) {
         const int j0 = t * 64;
         const uint16_t *Ks = smem + (t & 1) * 2 * TE, *Vs = Ks + TE;
-        if (t + 1 < ntiles) {
-            uint16_t *nx = smem + ((t + 1) & 1) * 2 * TE;
-            tk.store(nx, tid);
-            tv.store(nx + TE, tid);
-            if (t + 2 < ntiles) {
-                tk.load(rsK, j0 + 128, ldb, tid);
-                tv.load(rsV, j0 + 128, ldb, tid);
-            }
+        if (t + 1 < ntiles) {                           // the other buffer is free since the barrier that ended tile t-1
+            const uint32_t nx = lds0 + (uint32_t)((t + 1) & 1) * 2 * TE * 2;
+            dma.load(rsK, (uint32_t)j0 + 64, ldb, nx, wave);
+            dma.load(rsV, (uint32_t)j0 + 64, ldb, nx + TE * 2, wave);
         }
         if (j0 <= q0w + 31) {
             floatx16 s[2], dp[2];
+            {
+                // S = K.Q^T and dP = V.dO^T for both key groups; the K and V fragments run RING ahead of their products
+                constexpr int N = 4 * KS;
+                bf16x8 ring[RING];
+                auto frag = [&](int idx) { return L.row((idx & 1) ? Vs : Ks, (idx / (2 * KS)) * 32, (idx / 2) % KS); };
 #pragma unroll
-            for (int kt = 0; kt < 2; ++kt) {
-                s[kt] = zero16(); dp[kt] = zero16();
+                for (int i = 0; i < RING; ++i) ring[i] = frag(i);
+                s[0] = zero16(); s[1] = zero16(); dp[0] = zero16(); dp[1] = zero16();
 #pragma unroll
-                for (int ks = 0; ks < KS; ++ks) {
-                    s[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(row_frag(Ks, PK, kt * 32 + l32, ks * 16 + lhi * 8), qf[ks], s[kt], 0, 0, 0);
-                    dp[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(row_frag(Vs, PK, kt * 32 + l32, ks * 16 + lhi * 8), gf[ks], dp[kt], 0, 0, 0);
+                for (int idx = 0; idx < N; ++idx) {
+                    const int kt = idx / (2 * KS), ks = (idx / 2) % KS;
+                    if (idx & 1) dp[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ring[idx % RING], gf[ks], dp[kt], 0, 0, 0);
+                    else s[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ring[idx % RING], qf[ks], s[kt], 0, 0, 0);
+                    if (idx + RING < N) ring[idx % RING] = frag(idx + RING);
                 }
+                __builtin_amdgcn_sched_group_barrier(0x100, RING, 0);
+#pragma unroll
+                for (int idx = 0; idx < N - RING; ++idx) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                }
+                __builtin_amdgcn_sched_group_barrier(0x008, RING, 0);
             }
             const bool diag = j0 + 63 > q0w;
             // per group of 32 keys: the element-wise part of one group overlaps the other group's products
@@ -415,11 +382,12 @@ __global__ void __launch_bounds__(NT, 2) attn_bwd_dq_mfma_k(const uint16_t *__re
                 const bf16x8 d0 = pack8<0>(s[kt]), d1 = pack8<8>(s[kt]);
 #pragma unroll
                 for (int i = 0; i < DT; ++i) {
-                    dq[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tr_frag(Ks, PK, trb, kt * 32, i * 32), d0, dq[i], 0, 0, 0);
-                    dq[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tr_frag(Ks, PK, trb, kt * 32 + 16, i * 32), d1, dq[i], 0, 0, 0);
+                    dq[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(L.tr(Ks, kt * 32, i), d0, dq[i], 0, 0, 0);
+                    dq[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(L.tr(Ks, kt * 32 + 16, i), d1, dq[i], 0, 0, 0);
                 }
             }
         }
+        __builtin_amdgcn_s_waitcnt(0x0F70);             // vmcnt(0): this wavefront's part of tile t+1 has landed
         __syncthreads();
     }
     if (live) {
@@ -444,10 +412,10 @@ template <int DH, int MODE>
 __global__ void __launch_bounds__(NT, 2) attn_bwd_dkv_mfma_k(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ qkv,
                                                           const float *__restrict__ lse, const float *__restrict__ delta,
                                                           uint16_t *__restrict__ dqkv, int64_t Bn, int64_t Tn, int64_t H, float scale) {
-    constexpr int KS = DH / 16, DT = DH / 32, PK = tile_pitch<DH>(), TE = RowTile<DH>::ELEMS;
-    constexpr int BUF = 2 * TE + 256;                                    // Q tile | dO tile | 64 lse | 64 delta (floats)
-    extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, l32 = lane & 31, lhi = lane >> 5;
+    constexpr int KS = DH / 16, DT = DH / 32, TE = 64 * DH, RING = 4;
+    constexpr int BUF = 2 * TE;                                          // Q tile | dO tile, filled as in the forward kernel
+    extern __shared__ __attribute__((aligned(1024))) uint16_t smem[];    // [2 buffers][Q | dO], then [2][64 lse | 64 delta] floats
+    const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63, l32 = lane & 31, lhi = lane >> 5;
     const int64_t d = H * DH, ld = 3 * d;
     const uint32_t ldb = (uint32_t)(ld * 2), ldg = (uint32_t)(d * 2);
     int64_t bh;
@@ -457,11 +425,14 @@ __global__ void __launch_bounds__(NT, 2) attn_bwd_dkv_mfma_k(const uint16_t *__r
     const int kv0 = blk * 128;                                            // earliest keys see the most queries: first
     const int kv0w = kv0 + wave * 32, kv = kv0w + l32;
     const uint16_t *qb = qkv + b * Tn * ld + h * DH;
-    const __amdgpu_buffer_rsrc_t rsQ = head_rsrc(qb, Tn, ld, DH), rsK = head_rsrc(qb + d, Tn, ld, DH), rsV = head_rsrc(qb + 2 * d, Tn, ld, DH);
-    const __amdgpu_buffer_rsrc_t rsG = head_rsrc(dO + b * Tn * d + h * DH, Tn, d, DH);
+    const __amdgpu_buffer_rsrc_t rsK = head_rsrc(qb + d, Tn, ld, DH), rsV = head_rsrc(qb + 2 * d, Tn, ld, DH);
+    const i32x4 rsQ = make_rsrc(qb, (uint32_t)(((Tn - 1) * ld + DH) * 2));
+    const i32x4 rsG = make_rsrc(dO + b * Tn * d + h * DH, (uint32_t)(((Tn - 1) * d + DH) * 2));
     const float c = scale * LOG2E;
     const bool live = kv < Tn;
-    const int trb = tr_lane_base(PK, lane);
+    const TileLanes<DH> L(lane);
+    const DmaTile<DH> dmaQ(ldb, wave, lane), dmaG(ldg, wave, lane);
+    const uint32_t lds0 = __builtin_amdgcn_readfirstlane(lds_address(smem));
     constexpr bool DO_DV = MODE != 2, DO_DK = MODE != 1;
     constexpr int NDK = DO_DK ? DT : 1, NDV = DO_DV ? DT : 1, NVF = DO_DK ? KS : 1;
 
@@ -478,37 +449,40 @@ __global__ void __launch_bounds__(NT, 2) attn_bwd_dkv_mfma_k(const uint16_t *__r
     for (int i = 0; i < NDV; ++i) dv[i] = zero16();
     const int ntiles = ((int)Tn - kv0 + 63) / 64;
 
-    RowTile<DH> tq, tg;
-    float st_l = 0.f, st_d = 0.f;                       // statistics of row i0 + tid (threads 0..63)
-    auto load_tile = [&](int i0) {
-        tq.load(rsQ, i0, ldb, tid);
-        tg.load(rsG, i0, ldg, tid);
+    float st_l = 0.f, st_d = 0.f;                       // statistics of row i0 + tid (threads 0..63), one tile ahead
+    float *stats = reinterpret_cast<float *>(smem + 2 * BUF);
+    auto load_stats = [&](int i0) {
         if (tid < 64) {
             const bool ok = i0 + tid < Tn;
             st_l = ok ? lse[bh * Tn + i0 + tid] * LOG2E : 0.f;
             st_d = ok ? delta[bh * Tn + i0 + tid] : 0.f;
         }
     };
-    auto store_tile = [&](uint16_t *buf) {
-        tq.store(buf, tid);
-        tg.store(buf + TE, tid);
+    auto store_stats = [&](int buf) {
         if (tid < 64) {
-            float *st = reinterpret_cast<float *>(buf + 2 * TE);
-            st[tid] = st_l;
-            st[64 + tid] = st_d;
+            stats[buf * 128 + tid] = st_l;
+            stats[buf * 128 + 64 + tid] = st_d;
         }
     };
-    load_tile(kv0);
-    store_tile(smem);
-    if (ntiles > 1) load_tile(kv0 + 64);
+    auto load_tile = [&](int i0, int buf) {
+        const uint32_t at = lds0 + (uint32_t)buf * BUF * 2;
+        dmaQ.load(rsQ, (uint32_t)i0, ldb, at, wave);
+        dmaG.load(rsG, (uint32_t)i0, ldg, at + TE * 2, wave);
+    };
+    load_tile(kv0, 0);
+    load_stats(kv0);
+    store_stats(0);
+    if (ntiles > 1) load_stats(kv0 + 64);
+    __builtin_amdgcn_s_waitcnt(0x0F70);                 // vmcnt(0): this wavefront's part of tile 0 has landed
     __syncthreads();
     for (int t = 0; t < ntiles; ++t) {
         const int i0 = kv0 + t * 64;
         const uint16_t *Qs = smem + (t & 1) * BUF, *Gs = Qs + TE;
-        const float *L2s = reinterpret_cast<const float *>(Qs + 2 * TE), *Ds = L2s + 64;
-        if (t + 1 < ntiles) {
-            store_tile(smem + ((t + 1) & 1) * BUF);
-            if (t + 2 < ntiles) load_tile(i0 + 128);
+        const float *L2s = stats + (t & 1) * 128, *Ds = L2s + 64;
+        if (t + 1 < ntiles) {                           // the other buffer is free since the barrier that ended tile t-1
+            load_tile(i0 + 64, (t + 1) & 1);
+            store_stats((t + 1) & 1);
+            if (t + 2 < ntiles) load_stats(i0 + 128);
         }
         if (i0 + 63 >= kv0w) {
             // masking is needed where some query of the tile precedes some key of this wavefront, and for
@@ -517,10 +491,27 @@ __global__ void __launch_bounds__(NT, 2) attn_bwd_dkv_mfma_k(const uint16_t *__r
 #pragma unroll
             for (int qt = 0; qt < 2; ++qt) {
                 floatx16 s = zero16(), dp = zero16();
+                {
+                    // S^T = Q.K^T (and dP^T = dO.V^T); the Q and dO fragments run RING ahead of their products
+                    constexpr int PERK = DO_DK ? 2 : 1, N = PERK * KS;
+                    bf16x8 ring[RING];
+                    auto frag = [&](int idx) { return L.row((PERK == 2 && (idx & 1)) ? Gs : Qs, qt * 32, idx / PERK); };
 #pragma unroll
-                for (int ks = 0; ks < KS; ++ks) {
-                    s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(row_frag(Qs, PK, qt * 32 + l32, ks * 16 + lhi * 8), kf[ks], s, 0, 0, 0);
-                    if (DO_DK) dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(row_frag(Gs, PK, qt * 32 + l32, ks * 16 + lhi * 8), vf[ks], dp, 0, 0, 0);
+                    for (int i = 0; i < RING; ++i) ring[i] = frag(i);
+#pragma unroll
+                    for (int idx = 0; idx < N; ++idx) {
+                        const int ks = idx / PERK;
+                        if (PERK == 2 && (idx & 1)) dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ring[idx % RING], vf[ks % NVF], dp, 0, 0, 0);
+                        else s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ring[idx % RING], kf[ks], s, 0, 0, 0);
+                        if (idx + RING < N) ring[idx % RING] = frag(idx + RING);
+                    }
+                    __builtin_amdgcn_sched_group_barrier(0x100, RING, 0);
+#pragma unroll
+                    for (int idx = 0; idx < N - RING; ++idx) {
+                        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                    }
+                    __builtin_amdgcn_sched_group_barrier(0x008, RING, 0);
                 }
 #pragma unroll
                 for (int r4 = 0; r4 < 4; ++r4) {
@@ -542,20 +533,21 @@ __global__ void __launch_bounds__(NT, 2) attn_bwd_dkv_mfma_k(const uint16_t *__r
                     const bf16x8 p0 = pack8<0>(s), p1 = pack8<8>(s);
 #pragma unroll
                     for (int i = 0; i < NDV; ++i) {
-                        dv[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tr_frag(Gs, PK, trb, qt * 32, i * 32), p0, dv[i], 0, 0, 0);
-                        dv[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tr_frag(Gs, PK, trb, qt * 32 + 16, i * 32), p1, dv[i], 0, 0, 0);
+                        dv[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(L.tr(Gs, qt * 32, i), p0, dv[i], 0, 0, 0);
+                        dv[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(L.tr(Gs, qt * 32 + 16, i), p1, dv[i], 0, 0, 0);
                     }
                 }
                 if (DO_DK) {
                     const bf16x8 d0 = pack8<0>(dp), d1 = pack8<8>(dp);
 #pragma unroll
                     for (int i = 0; i < NDK; ++i) {
-                        dk[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tr_frag(Qs, PK, trb, qt * 32, i * 32), d0, dk[i], 0, 0, 0);
-                        dk[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tr_frag(Qs, PK, trb, qt * 32 + 16, i * 32), d1, dk[i], 0, 0, 0);
+                        dk[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(L.tr(Qs, qt * 32, i), d0, dk[i], 0, 0, 0);
+                        dk[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(L.tr(Qs, qt * 32 + 16, i), d1, dk[i], 0, 0, 0);
                     }
                 }
             }
         }
+        __builtin_amdgcn_s_waitcnt(0x0F70);             // vmcnt(0): this wavefront's part of tile t+1 has landed
         __syncthreads();
     }
     if (live) {
@@ -579,9 +571,8 @@ __global__ void __launch_bounds__(NT, 2) attn_bwd_dkv_mfma_k(const uint16_t *__r
     }
 }
 
-template <int DH> constexpr size_t fwd_smem() { return (size_t)2 * 2 * 64 * DH * 2; }      // unpadded tiles
-template <int DH> constexpr size_t kv_smem() { return (size_t)2 * 2 * RowTile<DH>::ELEMS * 2; }
-template <int DH> constexpr size_t dkv_smem() { return (size_t)2 * (2 * RowTile<DH>::ELEMS + 256) * 2; }
+template <int DH> constexpr size_t kv_smem() { return (size_t)2 * 2 * 64 * DH * 2; }       // two buffers of two tiles
+template <int DH> constexpr size_t dkv_smem() { return (size_t)2 * 2 * 64 * DH * 2 + 2 * 128 * 4; }      // tiles, then statistics
 
 // 32-bit buffer offsets: one head's rows must span less than 2 GiB
 bool fits(int64_t Tn, int64_t H, int64_t dh) { return (Tn + 192) * 3 * H * dh * 2 < ((int64_t)1 << 31); }
@@ -597,11 +588,11 @@ void attn_fwd_mfma(hipStream_t s, const void *qkv, void *o, float *lse, int64_t 
     const float scale = 1.0f / sqrtf((float)dh);
     static bool attr_set = false;
     if (!attr_set) {       // head dimension 128 needs more than the default 64 KiB of LDS
-        (void)hipFuncSetAttribute((const void *)attn_fwd_mfma_k<128>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)fwd_smem<128>());
+        (void)hipFuncSetAttribute((const void *)attn_fwd_mfma_k<128>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kv_smem<128>());
         attr_set = true;
     }
-    if (dh == 64) attn_fwd_mfma_k<64><<<grid, NT, fwd_smem<64>(), s>>>((const uint16_t *)qkv, (uint16_t *)o, lse, B, Tn, H, scale);
-    else attn_fwd_mfma_k<128><<<grid, NT, fwd_smem<128>(), s>>>((const uint16_t *)qkv, (uint16_t *)o, lse, B, Tn, H, scale);
+    if (dh == 64) attn_fwd_mfma_k<64><<<grid, NT, kv_smem<64>(), s>>>((const uint16_t *)qkv, (uint16_t *)o, lse, B, Tn, H, scale);
+    else attn_fwd_mfma_k<128><<<grid, NT, kv_smem<128>(), s>>>((const uint16_t *)qkv, (uint16_t *)o, lse, B, Tn, H, scale);
 }
 
 void attn_bwd_mfma(hipStream_t s, const void *dO, const void *qkv, const float *lse, const float *delta, void *dqkv,
