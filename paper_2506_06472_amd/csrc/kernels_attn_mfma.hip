@@ -145,6 +145,10 @@ template <int DH> struct DmaTile {
             voff[i] = (uint32_t)row * ld_bytes + (uint32_t)(((lane % CPR) ^ swz<DH>(row & 15)) * 16);
         }
     }
+    // load i of the PER that make up this wavefront's share of a tile (soff = row0 * ld_bytes, uniform)
+    __device__ __forceinline__ void load_one(int i, i32x4 rsrc, uint32_t soff, uint32_t lds_addr, int wave) const {
+        load_to_lds_b128(rsrc, lds_addr + (uint32_t)(i * (NT / 64) + wave) * 1024u, voff[i], soff);
+    }
     // rows row0 .. row0+63 of the head behind rsrc to the tile at LDS address lds_addr
     __device__ __forceinline__ void load(i32x4 rsrc, uint32_t row0, uint32_t ld_bytes, uint32_t lds_addr, int wave) const {
         const uint32_t soff = __builtin_amdgcn_readfirstlane(row0 * ld_bytes);
@@ -200,10 +204,20 @@ __global__ void __launch_bounds__(NT, 2) attn_fwd_mfma_k(const uint16_t *__restr
     for (int t = 0; t < ntiles; ++t) {
         const int j0 = t * 64;
         const uint16_t *Ks = smem + (t & 1) * 2 * TE, *Vs = Ks + TE;
-        if (t + 1 < ntiles) {                           // the other buffer is free since the barrier that ended tile t-1
-            const uint32_t nx = lds0 + (uint32_t)((t + 1) & 1) * 2 * TE * 2;
-            dma.load(rsK, (uint32_t)j0 + 64, ldb, nx, wave);
-            dma.load(rsV, (uint32_t)j0 + 64, ldb, nx + TE * 2, wave);
+        // Tile t+1 goes to the other buffer, free since the barrier that ended tile t-1.  Its loads are issued one at a
+        // time between the score products: issued together right after the barrier, the loads of all eight wavefronts
+        // of a compute unit queue up behind one another and every wavefront stalls in the issue.
+        const bool more = t + 1 < ntiles;
+        const uint32_t nx = lds0 + (uint32_t)((t + 1) & 1) * 2 * TE * 2;
+        const uint32_t nsoff = __builtin_amdgcn_readfirstlane(((uint32_t)j0 + 64) * ldb);
+        constexpr int NL = 2 * DmaTile<DH>::PER;           // K loads, then V loads
+        auto next_load = [&](int i) {
+            if (i < DmaTile<DH>::PER) dma.load_one(i, rsK, nsoff, nx, wave);
+            else dma.load_one(i - DmaTile<DH>::PER, rsV, nsoff, nx + TE * 2, wave);
+        };
+        if (more && j0 > q0w + 31) {                    // this wavefront has no products here: it still loads its share
+#pragma unroll
+            for (int i = 0; i < NL; ++i) next_load(i);
         }
         if (j0 <= q0w + 31) {
             floatx16 s[2];
@@ -218,6 +232,10 @@ __global__ void __launch_bounds__(NT, 2) attn_fwd_mfma_k(const uint16_t *__restr
                 for (int idx = 0; idx < N; ++idx) {
                     s[idx / KS] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ring[idx % RING], qf[idx % KS], s[idx / KS], 0, 0, 0);
                     if (idx + RING < N) ring[idx % RING] = L.row(Ks, ((idx + RING) / KS) * 32, (idx + RING) % KS);
+                    if (more) {
+#pragma unroll
+                        for (int i = idx * NL / N; i < (idx + 1) * NL / N; ++i) next_load(i);
+                    }
                 }
                 // pin the order: RING reads, then one product and one read in turn, then the last products
                 __builtin_amdgcn_sched_group_barrier(0x100, RING, 0);
