@@ -163,12 +163,14 @@ typedef struct tio_plan_opts {
      * are ranked by B / s, compared exactly. */
     int32_t clamp_benefit;
     /* Re-timing (an extension beyond the paper, default 0 = plan once as the paper does).  n > 0: Algorithm 1 and the
-     * urgent pass are run n more times, each time on the timeline of the iteration as the performance model
-     * (tio_plan_simulate) predicts it under the previous run's plan, i.e. every kernel takes its own time plus the stall
-     * in front of it; every run's plan is simulated on the true kernel times and the one with the shortest predicted
-     * iteration is kept (the first run counts, so the result is never predicted slower than the paper's plan).  Helps
-     * where migration takes longer than compute: the stalled iteration gives the channels several times the compute
-     * time, which the first run cannot see.  tio_plan_view.retime_pass says which run won. */
+     * urgent pass are run 2n more times, each time on a timeline of the iteration as the performance model
+     * (tio_plan_simulate) predicts it under the previous run's plan: a kernel takes its own time plus the stall in
+     * front of it.  Runs 1..n stretch every kernel that way; runs n+1..2n (a second chain from the same start) only the
+     * kernels from the first kernel of largest memory demand on.  Every run's plan is simulated on the true kernel
+     * times; the runs are ranked by predicted iteration (the earlier run first among equals, the paper's plan is run 0)
+     * and the best one whose address layout fits the arena is kept.  Helps where migration takes longer than compute:
+     * the stalled iteration gives the channels several times the compute time, which the first run cannot see.
+     * tio_plan_view.retime_pass says which run was kept. */
     int32_t retime_passes;
 } tio_plan_opts;
 

@@ -23,23 +23,40 @@ from . import plan as op
 from . import replay as orp
 
 
-def build_plan_retimed(trace, life, cap, bw, passes, duplex=True, min_bytes=0, host_bw=0, host_budget=0,
+def retimed_candidates(trace, life, cap, bw, passes, duplex=True, min_bytes=0, host_bw=0, host_budget=0,
                        clamp_benefit=False):
-    """Result of oracle/plan.py build_plan plus retime_pass (which pass won) and predicted_step_ns."""
+    """Every pass's plan, in pass order: results of oracle/plan.py build_plan plus retime_pass and predicted_step_ns
+    (the iteration the performance model predicts on the true kernel times).  Pass 0 is the paper's plan; passes
+    1..passes are chain A (planned on the fully stretched timeline of the pass before), passes+1..2*passes chain B
+    (only the kernels from the first kernel of largest memory demand M on are stretched: before it memory grows and
+    the stalls wait for offloads; stretching there invites the planner to offload there again)."""
     kw = dict(duplex=duplex, min_bytes=min_bytes, host_bw=host_bw, host_budget=host_budget, clamp_benefit=clamp_benefit)
-    best = op.build_plan(trace, life, cap, bw, **kw)
-    best["retime_pass"] = 0
+    first = op.build_plan(trace, life, cap, bw, **kw)
+    first["retime_pass"] = 0
+    out = [first]
     if passes <= 0 or bw == 0:
-        return best
-    sim = orp.simulate(trace, best, bw, duplex=duplex, host_bw=host_bw)
-    best["predicted_step_ns"] = sim["step_ns"]
-    stretched = sim["stretched"]
-    for p in range(1, passes + 1):
-        cand = op.build_plan(dict(trace, tau=list(stretched)), life, cap, bw, **kw)
-        sim = orp.simulate(trace, cand, bw, duplex=duplex, host_bw=host_bw)
+        return out
+    sim = orp.simulate(trace, first, bw, duplex=duplex, host_bw=host_bw)
+    first["predicted_step_ns"] = sim["step_ns"]
+    tau = trace["tau"]
+    kpeak = life["M"].index(max(life["M"]))
+    for chain in (0, 1):
         stretched = sim["stretched"]
-        if sim["step_ns"] < best["predicted_step_ns"]:
-            best = cand
-            best["retime_pass"] = p
-            best["predicted_step_ns"] = sim["step_ns"]
-    return best
+        for p in range(1, passes + 1):
+            planned_on = [tau[k] if (chain == 1 and k < kpeak) else stretched[k] for k in range(len(tau))]
+            cand = op.build_plan(dict(trace, tau=planned_on), life, cap, bw, **kw)
+            s2 = orp.simulate(trace, cand, bw, duplex=duplex, host_bw=host_bw)
+            stretched = s2["stretched"]
+            cand["retime_pass"] = chain * passes + p
+            cand["predicted_step_ns"] = s2["step_ns"]
+            out.append(cand)
+    return out
+
+
+def build_plan_retimed(trace, life, cap, bw, passes, **kw):
+    """The candidate with the shortest predicted iteration, the earliest pass among equals.  (The library keeps the
+    best candidate whose address layout fits its arena: with an ample arena that is this one.)"""
+    cands = retimed_candidates(trace, life, cap, bw, passes, **kw)
+    if len(cands) == 1:
+        return cands[0]
+    return min(cands, key=lambda c: (c["predicted_step_ns"], c["retime_pass"]))

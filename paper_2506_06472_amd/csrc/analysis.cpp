@@ -722,27 +722,53 @@ uint64_t address_at(const Plan &plan, int32_t tensor, int32_t k) {
 // after the other.  Re-timing runs Algorithm 1 again on the timeline of the iteration as the performance model says
 // it executes under the previous plan: kernel k takes its own time plus the stall in front of it.  On that timeline
 // the channels have the time they really have, and the greedy loop spreads both directions over the whole iteration.
-// Every pass is simulated on the true kernel times; the pass with the shortest predicted iteration wins (pass 0 is the
-// paper's plan, so the result is never predicted slower than it).  A plan's validity does not depend on kernel times
+// Every pass is simulated on the true kernel times and the passes are ranked by predicted iteration, the earlier pass
+// first among equals; the caller keeps the best one whose address layout fits the arena (pass 0 is the paper's plan,
+// so with room in the arena the result is never predicted slower than it).  A plan's validity does not depend on kernel times
 // (residency is counted per kernel index), so every pass yields a valid plan for the same trace.
 // ------------------------------------------------------------------------------------------------
 void select_periods_retimed(const Trace &t, const Lifetimes &life, uint64_t cap, uint64_t bw, bool duplex,
                             uint64_t min_bytes, uint64_t host_bw, uint64_t host_budget, bool clamp_benefit, int passes,
-                            Plan &out) {
-    select_periods(t, life, cap, bw, duplex, min_bytes, host_bw, host_budget, clamp_benefit, out);
-    out.retime_pass = 0;
-    if (passes <= 0 || bw == 0) return;
-    std::vector<int64_t> stretched;
-    int64_t best_step = simulate_plan(t, out, bw, duplex, 3, &stretched).step_ns;
-    Trace tt = t;
-    for (int pass = 1; pass <= passes; ++pass) {
-        tt.tau = stretched;
+                            const Plan &proto, std::vector<Plan> &out) {
+    out.clear();
+    std::vector<int64_t> steps;
+    auto fresh = [&]() {
         Plan p;
-        p.cap = out.cap; p.planning_cap = out.planning_cap; p.bw = out.bw; p.structure_hash = out.structure_hash;
-        select_periods(tt, life, cap, bw, duplex, min_bytes, host_bw, host_budget, clamp_benefit, p);
-        const int64_t step = simulate_plan(t, p, bw, duplex, 3, &stretched).step_ns;
-        if (step < best_step) { best_step = step; out = std::move(p); out.retime_pass = pass; }
+        p.cap = proto.cap; p.planning_cap = proto.planning_cap; p.bw = proto.bw; p.structure_hash = proto.structure_hash;
+        return p;
+    };
+    out.push_back(fresh());
+    select_periods(t, life, cap, bw, duplex, min_bytes, host_bw, host_budget, clamp_benefit, out.back());
+    out.back().retime_pass = 0;
+    if (passes <= 0 || bw == 0) return;
+    std::vector<int64_t> first;
+    steps.push_back(simulate_plan(t, out.back(), bw, duplex, 3, &first).step_ns);
+    // Two chains of passes from the same start.  Chain A plans on the fully stretched timeline.  Chain B stretches
+    // only the kernels from the first kernel of largest memory demand on: before that point memory grows and the
+    // stalls wait for offloads, and a timeline stretched there invites the planner to offload exactly there again
+    // (at the Llama-7B shape: the forward pass keeps stalling on activation offloads while the offload channel has
+    // spare time in the backward pass); with the kernels before the peak at their own times, those offloads do not
+    // fit, and the planner keeps more optimizer state out across the forward pass instead.
+    const int N = t.n_kernels;
+    const int kpeak = (int)(std::max_element(life.M.begin(), life.M.end()) - life.M.begin());
+    Trace tt = t;
+    for (int chain = 0; chain < 2; ++chain) {
+        std::vector<int64_t> stretched = first;
+        for (int pass = 1; pass <= passes; ++pass) {
+            for (int k = 0; k < N; ++k) tt.tau[k] = (chain == 1 && k < kpeak) ? t.tau[k] : stretched[k];
+            out.push_back(fresh());
+            select_periods(tt, life, cap, bw, duplex, min_bytes, host_bw, host_budget, clamp_benefit, out.back());
+            out.back().retime_pass = chain * passes + pass;
+            steps.push_back(simulate_plan(t, out.back(), bw, duplex, 3, &stretched).step_ns);
+        }
     }
+    // shortest predicted iteration first, the earlier pass among equals
+    std::vector<int> order(out.size());
+    for (int i = 0; i < (int)order.size(); ++i) order[i] = i;
+    std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return steps[a] < steps[b]; });
+    std::vector<Plan> sorted;
+    for (int i : order) sorted.push_back(std::move(out[i]));
+    out = std::move(sorted);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -756,11 +782,16 @@ Plan build_plan(const Trace &t, const Lifetimes &life, uint64_t cap, uint64_t bw
     uint64_t pc = std::min(cap, peak);
     const uint64_t step = std::max<uint64_t>(256, std::min(cap, peak) / 50);
     auto attempt = [&](uint64_t planning_cap, Plan &p) {
-        p = Plan();
-        p.cap = cap; p.planning_cap = planning_cap; p.bw = bw; p.structure_hash = t.structure_hash;
+        Plan proto;
+        proto.cap = cap; proto.planning_cap = planning_cap; proto.bw = bw; proto.structure_hash = t.structure_hash;
+        std::vector<Plan> cands;
         select_periods_retimed(t, life, planning_cap, bw, o.duplex != 0, o.min_bytes, o.host_bw, o.host_budget,
-                               o.clamp_benefit != 0, o.retime_passes, p);
-        return assign_addresses(t, life, arena, p);
+                               o.clamp_benefit != 0, o.retime_passes, proto, cands);
+        // the best predicted plan whose layout fits the arena
+        for (Plan &c : cands)
+            if (assign_addresses(t, life, arena, c)) { p = std::move(c); return true; }
+        p = std::move(cands.front());
+        return false;
     };
     for (int r = 0; r <= retries; ++r) {
         Plan p;

@@ -87,11 +87,12 @@ Plan build_plan(const Trace &t, const Lifetimes &life, uint64_t cap, uint64_t bw
 // Algorithm 1 + urgent pass only (no layout); fills pairs, Mp, n_greedy, n_forced.
 void select_periods(const Trace &t, const Lifetimes &life, uint64_t cap, uint64_t bw, bool duplex,
                     uint64_t min_bytes, uint64_t host_bw, uint64_t host_budget, bool clamp_benefit, Plan &out);
-// select_periods, then `passes` more runs of it on the timeline stretched by the stalls the performance model predicts
-// for the previous run's plan; keeps the run whose plan has the shortest predicted iteration on the true kernel times
+// select_periods, then two chains of `passes` more runs of it on the timeline stretched by the stalls the performance
+// model predicts for the previous run's plan; returns every run's plan (fields of `proto` copied in), ranked by the
+// iteration predicted on the true kernel times, the earlier run first among equals
 void select_periods_retimed(const Trace &t, const Lifetimes &life, uint64_t cap, uint64_t bw, bool duplex,
                             uint64_t min_bytes, uint64_t host_bw, uint64_t host_budget, bool clamp_benefit, int passes,
-                            Plan &out);
+                            const Plan &proto, std::vector<Plan> &out);
 // Address assignment and executor tables; returns false when the arena is too small.
 bool assign_addresses(const Trace &t, const Lifetimes &life, uint64_t arena_bytes, Plan &plan);
 void validate_plan(const Trace &t, const Lifetimes &life, const Plan &plan);   // throws PlanError
