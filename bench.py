@@ -445,7 +445,8 @@ def main():
         "model_first_come_first_served_ms_per_step": tio.tio_plan_simulate(lt, plan, bw, duplex=not shared)[0] / 1e6,
         "frac_of_ideal": ideal_s / step_s,
         "migration_bound_ms": mig_bound_s * 1e3, "frac_of_min_ideal_migration_bound": bound_s / step_s,
-        "plan": {"how": ("Algorithm 1 re-run on the stalled timeline: pass %d of %d kept" % (pe["retime_pass"], args.retime))
+        "plan": {"how": ("Algorithm 1 re-run on the stalled timeline: pass %d kept (0 = the paper's plan, 1-%d fully stretched, %d-%d stretched from the memory peak on)"
+                         % (pe["retime_pass"], args.retime, args.retime + 1, 2 * args.retime))
                         if args.retime else "Algorithm 1 run once",
                  "entries": len(pe["entries"]), "greedy_pairs": pe["n_greedy"], "urgent_pairs": pe["n_forced"],
                  "host_tier_pairs": sum(pe["tier"]), "host_tier_peak_bytes": pe["host_peak"],
