@@ -58,6 +58,16 @@ __device__ __forceinline__ floatx16 zero16() {
     for (int i = 0; i < 16; ++i) z[i] = 0.f;
     return z;
 }
+// a value combined over the two halves of the wavefront (lanes i and i + 32), the same in both: v_permlane32_swap hands
+// every lane the value of both halves without a trip through the LDS queue, behind which a cross-lane read would wait
+__device__ __forceinline__ float max_halves(float x) {
+    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ float sum_halves(float x) {
+    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
 // row index inside a 32x32 accumulator tile of register r for lane half lhi
 __device__ __forceinline__ int acc_row(int r, int lhi) { return 8 * (r >> 2) + 4 * lhi + (r & 3); }
 
@@ -257,7 +267,7 @@ __global__ void __launch_bounds__(NT, 2) attn_fwd_mfma_k(const uint16_t *__restr
                 float tmax = -INFINITY;
 #pragma unroll
                 for (int r = 0; r < 16; ++r) tmax = fmaxf(tmax, s[kt][r]);
-                tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64)) * c;
+                tmax = max_halves(tmax) * c;
                 // The reference exponent m only has to keep exp2(x - m) in range, it need not be the exact
                 // running maximum: it is raised (and the accumulators rescaled) only when some row of the
                 // wavefront exceeds it by more than 2^8, which after the first keys is rare.  Key 0 is
@@ -280,18 +290,31 @@ __global__ void __launch_bounds__(NT, 2) attn_fwd_mfma_k(const uint16_t *__restr
                     s[kt][r] = p;
                 }
                 l += psum;
-                const bf16x8 p0 = pack8<0>(s[kt]), p1 = pack8<8>(s[kt]);
+                const bf16x8 pk[2] = {pack8<0>(s[kt]), pack8<8>(s[kt])};
+                // V fragment f of the group: keys 16 (f / DT) .. + 15, columns 32 (f % DT) .. + 31; like the K fragments
+                // they run through a ring of register sets, VR products ahead
+                constexpr int NPV = 2 * DT, VR = 4;
+                bf16x8 vf[VR];
 #pragma unroll
-                for (int i = 0; i < DT; ++i) {
-                    oacc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(L.tr(Vs, kt * 32, i), p0, oacc[i], 0, 0, 0);
-                    oacc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(L.tr(Vs, kt * 32 + 16, i), p1, oacc[i], 0, 0, 0);
+                for (int f = 0; f < VR; ++f) vf[f] = L.tr(Vs, kt * 32 + 16 * (f / DT), f % DT);
+#pragma unroll
+                for (int f = 0; f < NPV; ++f) {
+                    oacc[f % DT] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[f % VR], pk[f / DT], oacc[f % DT], 0, 0, 0);
+                    if (f + VR < NPV) vf[f % VR] = L.tr(Vs, kt * 32 + 16 * ((f + VR) / DT), (f + VR) % DT);
                 }
+                __builtin_amdgcn_sched_group_barrier(0x100, 2 * VR, 0);
+#pragma unroll
+                for (int f = 0; f < NPV - VR; ++f) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+                }
+                __builtin_amdgcn_sched_group_barrier(0x008, VR, 0);
             }
         }
         __builtin_amdgcn_s_waitcnt(0x0F70);             // vmcnt(0): this wavefront's part of tile t+1 has landed
         __syncthreads();
     }
-    l += __shfl_xor(l, 32, 64);
+    l = sum_halves(l);
     if (q < Tn) {
         const float inv = 1.0f / l;
         uint16_t *orow = o + (b * Tn + q) * d + h * DH;
