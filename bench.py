@@ -181,7 +181,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--retime", type=int, default=8,
+    ap.add_argument("--retime", type=int, default=16,
                     help="re-timing passes of the planner (0: the paper's plan alone); with passes, the paper's plan is timed as well")
     ap.add_argument("--workload", default="llama_7b_bf16")
     ap.add_argument("--bw", type=float, default=-1, help="slow-tier bytes/s per direction; 0 = unthrottled; default: the workload's (25e9)")
