@@ -1,6 +1,7 @@
-"""GPU parity at the benchmark's full size and launch configuration (GPT-2-small shape, bf16, 8192 tokens,
-cap = 40 % of the uncapped peak, paced slow tier): loss and sampled gradients against the CPU oracle, bitwise
-equality with and without offloading, and plan switching in the middle of training."""
+"""GPU parity at the benchmark's full sizes and launch configurations.  GPT-2-small shape (bf16, 8192 tokens, cap = 40 %
+of the uncapped peak, paced slow tier): loss and sampled gradients against the CPU oracle, bitwise equality with and
+without offloading, plan switching in the middle of training.  Llama widths: one decoder layer against the oracle, two
+layers at the 30B widths and sequence length, and the whole Llama-7B workload under its 96 GB cap, bitwise."""
 import numpy as np
 import pytest
 
@@ -217,5 +218,56 @@ def test_two_layers_at_the_30b_widths_and_sequence_length_bitwise_under_cap():
     (l0, s0), (l1, s1) = runs
     assert np.array(l0, np.float32).tobytes() == np.array(l1, np.float32).tobytes(), (l0, l1)
     assert np.isfinite(l0).all() and l0[1] < l0[0], l0
+    for key in s0:
+        assert s0[key].tobytes() == s1[key].tobytes(), key
+
+
+def test_llama_7b_full_size_bitwise_under_the_96_gb_cap():
+    """The default workload of bench.py at full size and in its launch configuration: Llama-7B shape (32 layers, d = 4096,
+    8192 tokens per step, bf16 with fp32 optimizer state), 96 GB cap, slow tier in device memory outside the arena paced
+    to 25 GB/s per direction, a re-timed plan.  No CPU oracle reaches this size in a test, so what is checked holds at
+    any size: the loss at initialisation is ln V + 0.0002 d (logits N(0, 0.0004 d): unit-variance normalised hidden
+    state times N(0, 0.02^2) head weights), the second loss is lower, the run under the cap gives the bits of the
+    uncapped run (both losses and sampled weights, masters and moments after two steps), and every steady-state step
+    moves exactly the plan's bytes in each direction."""
+    import torch
+    import paper_2506_06472_amd as tio
+    from synth import gen_tokens, iter_params_pooled
+    cfg = CONFIGS["llama_7b_bf16"]
+    bw = 25 * 10**9
+    specs = [(n, (r, c) if r > 1 else (c,), "normal" if (r > 1) else "ones") for n, r, c in tio.tio_param_list(cfg)]
+    tok, lab = gen_tokens(cfg["B"], cfg["T"], cfg["V"], 0)
+    lt = tio.tio_trace_build(cfg)
+    ll = tio.tio_analyze_lifetimes(lt)
+    peak = int(ll.export()["M"].max())
+    cap = cfg["cap_bytes"] // 256 * 256
+    up = tio.tio_build_plan(lt, ll, 2**62, 0)
+    cp = tio.tio_build_plan(lt, ll, cap, bw, min_bytes=1 << 20, retime_passes=2)        # modelled kernel times
+    ue, ce = up.export(), cp.export()
+    print(f"peak {peak / 1e9:.1f} GB cap {cap / 1e9:.1f} GB entries {len(ce['entries'])} moved {ce['bytes_per_direction'] / 1e9:.1f} GB "
+          f"pass {ce['retime_pass']}", flush=True)
+    assert peak > cap and ce["bytes_per_direction"] >= peak - cap
+    torch.cuda.empty_cache()                           # the two buffers below take 250 of the 288 GB
+    arena = torch.empty(max(ue["arena_needed"], cap) + 8192, dtype=torch.uint8, device="cuda:0")
+    pool = torch.empty(max(ue["host_needed"], ce["host_needed"]) + (1 << 20), dtype=torch.uint8, device="cuda:0")
+    sample = ["rmsf_g", "l0.rms1_g", "l31.rms2_g", "l17.w_o"]
+    runs = []
+    for label, plan, arena_bytes in (("uncapped", None, ue["arena_needed"]), ("capped", cp, cap)):
+        print(label, flush=True)
+        ctx = tio.tio_ctx_create(cfg, arena_bytes, pool.numel(), bw if plan is not None else 0, arena=arena, host=pool)
+        for name, arr in iter_params_pooled(specs, 0):
+            ctx.tio_params_load({name: arr})
+        stats = [ctx.tio_train_step(tok, lab, plan) for _ in range(2)]
+        print([s["loss"] for s in stats], flush=True)
+        runs.append((stats, read_state(ctx, sample, True)))
+        ctx.close()
+    del arena, pool
+    torch.cuda.empty_cache()
+    (st0, s0), (st1, s1) = runs
+    l0, l1 = [s["loss"] for s in st0], [s["loss"] for s in st1]
+    assert abs(l0[0] - (np.log(cfg["V"]) + 0.0002 * cfg["d"])) < 0.05, l0
+    assert np.isfinite(l0).all() and l0[1] < l0[0], l0
+    assert np.array(l0, np.float32).tobytes() == np.array(l1, np.float32).tobytes(), (l0, l1)
+    assert st1[1]["h2d_bytes"] == st1[1]["d2h_bytes"] == ce["bytes_per_direction"], (st1[1], ce["bytes_per_direction"])
     for key in s0:
         assert s0[key].tobytes() == s1[key].tobytes(), key
