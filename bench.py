@@ -197,6 +197,7 @@ def main():
                          "(auto: yes for the file tier, whose two directions share the device's bandwidth)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--modelled-tau", action="store_true", help="plan from modelled instead of measured kernel times")
+    ap.add_argument("--dump-tau", default="", help="write the measured kernel times (ns, one per line: the format sweep --tau reads) to this file")
     ap.add_argument("--host-tier-bw", type=float, default=0,
                     help="bytes/s per direction of a second, host-memory destination beside the slow tier (the paper's "
                          "mixed mode); 0 = none; not the headline configuration")
@@ -311,6 +312,8 @@ def main():
     measured = ctx.tio_profile_iteration(tok, lab, tio.PROFILE_MEASURED)
     tau = measured.export()["tau"]
     log("sum of kernel times ms", tau.sum() / 1e6)
+    if args.dump_tau:
+        np.savetxt(args.dump_tau, tau, fmt="%d")
     for _ in range(args.warmup):
         ctx.tio_train_step(tok, lab, None)
     torch.cuda.synchronize()

@@ -168,9 +168,12 @@ typedef struct tio_plan_opts {
      * front of it.  Runs 1..n stretch every kernel that way; runs n+1..2n (a second chain from the same start) only the
      * kernels from the first kernel of largest memory demand on.  Every run's plan is simulated on the true kernel
      * times; the runs are ranked by predicted iteration (the earlier run first among equals, the paper's plan is run 0)
-     * and the best one whose address layout fits the arena is kept.  Helps where migration takes longer than compute:
-     * the stalled iteration gives the channels several times the compute time, which the first run cannot see.
-     * tio_plan_view.retime_pass says which run was kept. */
+     * and the best one whose address layout fits the arena is kept.  Where the best run's layout does not fit, the
+     * search over planning capacities (2 % steps down from the cap) goes on for up to two more steps and keeps the
+     * plan predicted fastest among those that fit: a plan whose layout fits at a slightly lower planning capacity
+     * can beat, by more than its extra bytes cost, the first one that fits at the full capacity.  Helps where
+     * migration takes longer than compute: the stalled iteration gives the channels several times the compute time,
+     * which the first run cannot see.  tio_plan_view.retime_pass and planning_cap say what was kept. */
     int32_t retime_passes;
 } tio_plan_opts;
 

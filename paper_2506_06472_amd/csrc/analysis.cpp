@@ -767,7 +767,7 @@ void select_periods_retimed(const Trace &t, const Lifetimes &life, uint64_t cap,
     for (int i = 0; i < (int)order.size(); ++i) order[i] = i;
     std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return steps[a] < steps[b]; });
     std::vector<Plan> sorted;
-    for (int i : order) sorted.push_back(std::move(out[i]));
+    for (int i : order) { out[i].predicted_step_ns = steps[i]; sorted.push_back(std::move(out[i])); }
     out = std::move(sorted);
 }
 
@@ -781,37 +781,55 @@ Plan build_plan(const Trace &t, const Lifetimes &life, uint64_t cap, uint64_t bw
     const int retries = o.layout_retries > 0 ? o.layout_retries : 24;
     uint64_t pc = std::min(cap, peak);
     const uint64_t step = std::max<uint64_t>(256, std::min(cap, peak) / 50);
-    auto attempt = [&](uint64_t planning_cap, Plan &p) {
+    // Selections at one planning capacity, best predicted first (one selection without re-timing); p = the first whose
+    // layout fits the arena, top = the prediction of the best one whether it fits or not
+    auto attempt = [&](uint64_t planning_cap, Plan &p, int64_t &top) {
         Plan proto;
         proto.cap = cap; proto.planning_cap = planning_cap; proto.bw = bw; proto.structure_hash = t.structure_hash;
         std::vector<Plan> cands;
         select_periods_retimed(t, life, planning_cap, bw, o.duplex != 0, o.min_bytes, o.host_bw, o.host_budget,
                                o.clamp_benefit != 0, o.retime_passes, proto, cands);
-        // the best predicted plan whose layout fits the arena
+        top = cands.front().predicted_step_ns;
         for (Plan &c : cands)
             if (assign_addresses(t, life, arena, c)) { p = std::move(c); return true; }
-        p = std::move(cands.front());
         return false;
     };
+    // The planning capacity goes down in steps of 2 % until a layout fits.  With re-timing, several selections compete at
+    // every capacity and the first that fits may be predicted far slower than the best one, which may fit a step
+    // further down at the price of 2 % more bytes: the search goes on while a lower capacity can still win (the best
+    // found so far is predicted slower than the best selection of the current capacity, fitting or not), at most two
+    // steps (one on long traces, where a step takes seconds) beyond the last improvement.
+    Plan best;
+    bool have = false;
+    uint64_t best_pc = 0;
+    int best_r = 0, since = 0;
+    const int patience = t.n_kernels <= 4096 ? 2 : 1;
     for (int r = 0; r <= retries; ++r) {
         Plan p;
-        if (attempt(pc, p)) {
-            // the step before did not fit: look between the two for a larger planning capacity that does
-            // (every byte of it is a byte that need not move), halving the interval a few times; fewer times
-            // for long traces, where one attempt takes seconds
-            uint64_t lo = pc, hi = r > 0 ? pc + step : pc;
-            const int halvings = t.n_kernels <= 4096 ? 4 : t.n_kernels <= 16384 ? 2 : 0;
-            for (int i = 0; i < halvings && hi - lo >= 512; ++i) {
-                const uint64_t mid = (lo + (hi - lo) / 2) / 256 * 256;
-                Plan q;
-                if (attempt(mid, q)) { lo = mid; p = std::move(q); } else hi = mid;
-            }
-            return p;
+        int64_t top = 0;
+        const bool ok = attempt(pc, p, top);
+        if (ok && (!have || p.predicted_step_ns < best.predicted_step_ns)) {
+            best = std::move(p); have = true; best_pc = pc; best_r = r; since = 0;
+        } else if (have) {
+            ++since;
         }
+        if (have && (best.predicted_step_ns <= top || since >= patience)) break;
         if (pc <= step) break;
         pc -= step;
     }
-    throw PlanError{TIO_ERR_ARENA_TOO_SMALL, "no address assignment fits the arena"};
+    if (!have) throw PlanError{TIO_ERR_ARENA_TOO_SMALL, "no address assignment fits the arena"};
+    // the step above the chosen capacity did not do as well: look between the two for a larger planning capacity that
+    // does (every byte of it is a byte that need not move), halving the interval a few times; fewer times for long
+    // traces, where one attempt takes seconds
+    uint64_t lo = best_pc, hi = best_r > 0 ? best_pc + step : best_pc;
+    const int halvings = t.n_kernels <= 4096 ? 4 : t.n_kernels <= 16384 ? 2 : 0;
+    for (int i = 0; i < halvings && hi - lo >= 512; ++i) {
+        const uint64_t mid = (lo + (hi - lo) / 2) / 256 * 256;
+        Plan q;
+        int64_t top = 0;
+        if (attempt(mid, q, top) && q.predicted_step_ns <= best.predicted_step_ns) { lo = mid; best = std::move(q); } else hi = mid;
+    }
+    return best;
 }
 
 void validate_plan(const Trace &t, const Lifetimes &life, const Plan &plan) {

@@ -71,6 +71,7 @@ struct Plan {
     // executor tables, indexed by kernel
     std::vector<std::vector<int32_t>> entries_at;        // entry indices with trigger % N == k
     int32_t retime_pass = 0;                             // which re-timing pass produced the selection (0: the first, on the kernel times)
+    int64_t predicted_step_ns = 0;                       // with re-timing: the iteration the performance model predicts for this selection
     std::vector<std::vector<int32_t>> kernel_wait_pre;   // pair ids whose prefetch event kernel k waits for
     std::vector<std::vector<int32_t>> kernel_wait_off;   // pair ids whose offload event kernel k waits for
     std::vector<uint8_t> kernel_needs_event;             // record an event after kernel k
