@@ -147,23 +147,24 @@ template <int DH> struct TileLanes {
 template <int DH> struct DmaTile {
     static constexpr int CPR = DH / 8, RPB = 64 / CPR, BLOCKS = 64 * DH * 2 / 1024, PER = BLOCKS / (NT / 64);
     static_assert(BLOCKS % (NT / 64) == 0, "blocks divide over the wavefronts");
-    uint32_t voff[PER];
+    static_assert(((NT / 64) * RPB) % 16 == 0, "the permutation repeats from one load of a wavefront to its next");
+    uint32_t voff, step;           // byte offset of this lane's chunk in the wavefront's first block; bytes between its blocks (uniform)
     __device__ __forceinline__ DmaTile(uint32_t ld_bytes, int wave, int lane) {
-#pragma unroll
-        for (int i = 0; i < PER; ++i) {
-            const int row = (i * (NT / 64) + wave) * RPB + lane / CPR;
-            voff[i] = (uint32_t)row * ld_bytes + (uint32_t)(((lane % CPR) ^ swz<DH>(row & 15)) * 16);
-        }
+        const int row = wave * RPB + lane / CPR;
+        voff = (uint32_t)row * ld_bytes + (uint32_t)(((lane % CPR) ^ swz<DH>(row & 15)) * 16);
+        step = __builtin_amdgcn_readfirstlane((uint32_t)((NT / 64) * RPB) * ld_bytes);
     }
-    // load i of the PER that make up this wavefront's share of a tile (soff = row0 * ld_bytes, uniform)
+    // load i of the PER that make up this wavefront's share of a tile (soff = row0 * ld_bytes, uniform): rows
+    // i * (NT / 64) * RPB further down, which only moves the uniform part of the address (the scalar offset takes part
+    // in the descriptor's range check like the per-lane one: checked on the hardware)
     __device__ __forceinline__ void load_one(int i, i32x4 rsrc, uint32_t soff, uint32_t lds_addr, int wave) const {
-        load_to_lds_b128(rsrc, lds_addr + (uint32_t)(i * (NT / 64) + wave) * 1024u, voff[i], soff);
+        load_to_lds_b128(rsrc, lds_addr + (uint32_t)(i * (NT / 64) + wave) * 1024u, voff, soff + (uint32_t)i * step);
     }
     // rows row0 .. row0+63 of the head behind rsrc to the tile at LDS address lds_addr
     __device__ __forceinline__ void load(i32x4 rsrc, uint32_t row0, uint32_t ld_bytes, uint32_t lds_addr, int wave) const {
         const uint32_t soff = __builtin_amdgcn_readfirstlane(row0 * ld_bytes);
 #pragma unroll
-        for (int i = 0; i < PER; ++i) load_to_lds_b128(rsrc, lds_addr + (uint32_t)(i * (NT / 64) + wave) * 1024u, voff[i], soff);
+        for (int i = 0; i < PER; ++i) load_one(i, rsrc, soff, lds_addr, wave);
     }
 };
 
