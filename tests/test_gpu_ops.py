@@ -236,3 +236,67 @@ def test_attention_forward_backward(dtype, B, T, H, dh):
         err = np.abs(got[:, i * d:(i + 1) * d] - unheads(ref))
         assert np.all(err <= unheads(bnd)), ("dq dk dv".split()[i], float((err / unheads(bnd)).max()))
         print("  worst error / bound", "dq dk dv".split()[i], float((err / unheads(bnd)).max()), flush=True)
+
+
+@pytest.mark.parametrize("T,H,dh", [(200, 2, 64), (330, 1, 128), (70, 1, 128)])
+def test_attention_ignores_what_lies_behind_its_buffers(T, H, dh):
+    """Tiles of 64 rows reach past the last row of a sequence whose length is not a multiple of 64; the kernels' buffer
+    descriptors end with the sequence, so what lies behind qkv and dO in memory must not matter.  Both buffers are views at
+    the start of larger allocations: once followed by zeros, once by NaN.  Every output has to be finite and bitwise the
+    same in both runs (0 x NaN in a product of a masked probability with a row past the end would show at once)."""
+    import torch
+    import paper_2506_06472_amd as tio
+    print(f"attention behind the buffer T={T} H={H} dh={dh}", flush=True)
+    B, d = 1, H * dh
+    rng = np.random.default_rng(T + dh)
+    qkv = rng.standard_normal((B * T, 3 * d)).astype(np.float32)
+    dO = rng.standard_normal((B * T, d)).astype(np.float32)
+    outs = []
+    for fill in (0.0, float("nan")):
+        big_q = torch.full(((B * T + 192) * 3 * d,), fill, device="cuda", dtype=torch.bfloat16)
+        big_g = torch.full(((B * T + 192) * d,), fill, device="cuda", dtype=torch.bfloat16)
+        big_q[:B * T * 3 * d] = _dev(qkv, "bf16").reshape(-1)
+        big_g[:B * T * d] = _dev(dO, "bf16").reshape(-1)
+        o = torch.full((B * T, d), 7.0, device="cuda", dtype=torch.bfloat16)
+        dq = torch.full((B * T, 3 * d), 7.0, device="cuda", dtype=torch.bfloat16)
+        lse = torch.zeros(B * H * T, device="cuda", dtype=torch.float32)
+        delta = torch.zeros(B * H * T, device="cuda", dtype=torch.float32)
+        torch.cuda.synchronize()
+        tio.tio_op_attention(0, "bf16", B, T, H, dh, big_q.data_ptr(), o.data_ptr(), lse.data_ptr(), big_g.data_ptr(),
+                             delta.data_ptr(), dq.data_ptr())
+        torch.cuda.synchronize()
+        outs.append([t.float().cpu().numpy() for t in (o, dq, lse, delta)])
+    for a, b in zip(*outs):
+        assert np.isfinite(b).all()
+        assert a.tobytes() == b.tobytes()
+
+
+@pytest.mark.parametrize("a_km,b_km", [(0, 0), (0, 1), (1, 1), (1, 0)])
+def test_gemm_ignores_what_lies_behind_its_operands(a_km, b_km):
+    """Ragged M, N and K: the last tiles of both operands reach past their last row and, in the contraction, past their
+    last column.  The operands are views at the start of larger allocations followed by NaN; the product has to equal
+    the one computed with zeros behind them, bit for bit, and be finite."""
+    import torch
+    import paper_2506_06472_amd as tio
+    M, N, K = 333, 200, 136
+    print(f"gemm behind the operands a_km={a_km} b_km={b_km}", flush=True)
+    rng = np.random.default_rng(5 + 2 * a_km + b_km)
+    r8 = lambda n: (n + 7) // 8 * 8
+    lda, ldb, ldc = (r8(M) if a_km else r8(K)), (r8(N) if b_km else r8(K)), r8(N)
+    A = rng.standard_normal((K if a_km else M, lda)).astype(np.float32)
+    Bm = rng.standard_normal((K if b_km else N, ldb)).astype(np.float32)
+    outs = []
+    for fill in (0.0, float("nan")):
+        bufs = []
+        for X in (A, Bm):
+            t = torch.full((X.size + 300 * X.shape[1],), fill, device="cuda", dtype=torch.bfloat16)
+            t[:X.size] = _dev(X, "bf16").reshape(-1)
+            bufs.append(t)
+        C = torch.full((M, ldc), 7.0, device="cuda", dtype=torch.bfloat16)
+        torch.cuda.synchronize()
+        tio.tio_op_gemm(0, "bf16", a_km, b_km, M, N, K, bufs[0].data_ptr(), lda, bufs[1].data_ptr(), ldb, 0, 0, 0,
+                        C.data_ptr(), ldc, 0, 0, 1)
+        torch.cuda.synchronize()
+        outs.append(C.float().cpu().numpy())
+    assert np.isfinite(outs[1][:, :N]).all()
+    assert outs[0].tobytes() == outs[1].tobytes()
