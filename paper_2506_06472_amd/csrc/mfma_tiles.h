@@ -29,12 +29,17 @@ union Frag {
 // behind it (it would wait for every outstanding load before each read of LDS): the kernel waits for these loads
 // itself, with s_waitcnt vmcnt before the barrier that publishes a stage.  M0 holds the LDS address; one wait
 // state separates its write from the load.
+// (The compiler notes that M0 is a reserved register and that it does not track the clobber; it has no use of M0 of its
+// own in these kernels: no indirect register indexing, no message or GDS instructions.)
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"
 __device__ __forceinline__ void load_to_lds_b128(i32x4 rsrc, uint32_t lds_addr, uint32_t voff, uint32_t soff) {
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
                  :
                  : "s"(lds_addr), "v"(voff), "s"(rsrc), "s"(soff)
                  : "memory", "m0");
 }
+#pragma clang diagnostic pop
 
 // buffer descriptor over [base, base + bytes): raw (stride 0) addressing, out-of-range lanes read zero
 __device__ __forceinline__ i32x4 make_rsrc(const void *base, uint32_t bytes) {
