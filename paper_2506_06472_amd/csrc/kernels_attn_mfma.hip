@@ -265,15 +265,23 @@ __global__ void __launch_bounds__(NT, 2) attn_fwd_mfma_k(const uint16_t *__restr
                     for (int r = 0; r < 16; ++r)
                         if (j0 + kt * 32 + acc_row(r, lhi) > q) s[kt][r] = -INFINITY;
                 }
-                float tmax = -INFINITY;
+                // The reference exponent m only has to keep exp2(x - m) in range, it need not be the running maximum.  The
+                // probabilities are first taken with the m at hand, and their sum tells whether that was good enough: only
+                // when some lane's sum reaches 2^16 (or is not a number: m is still -inf in the first group of a row,
+                // where key 0 is visible to every row) is the row maximum of the group computed, m raised to it, everything
+                // accumulated so far rescaled and the group redone.  After the first keys that is rare, and the common
+                // path has no maximum, no exchange between the lane halves and no rescale in it.
+                float pr[16], psum = 0.f;
 #pragma unroll
-                for (int r = 0; r < 16; ++r) tmax = fmaxf(tmax, s[kt][r]);
-                tmax = max_halves(tmax) * c;
-                // The reference exponent m only has to keep exp2(x - m) in range, it need not be the exact
-                // running maximum: it is raised (and the accumulators rescaled) only when some row of the
-                // wavefront exceeds it by more than 2^8, which after the first keys is rare.  Key 0 is
-                // visible to every row, so from the first group on m is finite.
-                if (__any(tmax > m + 8.0f)) {
+                for (int r = 0; r < 16; ++r) {
+                    pr[r] = __builtin_amdgcn_exp2f(fmaf(s[kt][r], c, -m));
+                    psum += pr[r];
+                }
+                if (__any(!(psum < 65536.0f))) {
+                    float tmax = -INFINITY;
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) tmax = fmaxf(tmax, s[kt][r]);
+                    tmax = max_halves(tmax) * c;
                     const float mn = fmaxf(m, tmax);
                     const float corr = __builtin_amdgcn_exp2f(m - mn);
                     l *= corr;
@@ -282,15 +290,16 @@ __global__ void __launch_bounds__(NT, 2) attn_fwd_mfma_k(const uint16_t *__restr
                     for (int i = 0; i < DT; ++i)
 #pragma unroll
                         for (int r = 0; r < 16; ++r) oacc[i][r] *= corr;
-                }
-                float psum = 0.f;
+                    psum = 0.f;
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const float p = __builtin_amdgcn_exp2f(fmaf(s[kt][r], c, -m));
-                    psum += p;
-                    s[kt][r] = p;
+                    for (int r = 0; r < 16; ++r) {
+                        pr[r] = __builtin_amdgcn_exp2f(fmaf(s[kt][r], c, -m));
+                        psum += pr[r];
+                    }
                 }
                 l += psum;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) s[kt][r] = pr[r];
                 const bf16x8 pk[2] = {pack8<0>(s[kt]), pack8<8>(s[kt])};
                 // V fragment f of the group: keys 16 (f / DT) .. + 15, columns 32 (f % DT) .. + 31; like the K fragments
                 // they run through a ring of register sets, VR products ahead
