@@ -531,8 +531,11 @@ __global__ void __launch_bounds__(NT, 2) attn_bwd_dkv_mfma_k(const uint16_t *__r
         const uint16_t *Qs = smem + (t & 1) * BUF, *Gs = Qs + TE;
         const float *L2s = stats + (t & 1) * 128, *Ds = L2s + 64;
         if (t + 1 < ntiles) {                           // the other buffer is free since the barrier that ended tile t-1
-            load_tile(i0 + 64, (t + 1) & 1);
+            // The statistics fetched a tile ago go to LDS before the tile loads are issued: the write waits for every
+            // outstanding vector memory operation of the wavefront, and behind the tile loads that would be their
+            // whole latency, at the start of every tile.
             store_stats((t + 1) & 1);
+            load_tile(i0 + 64, (t + 1) & 1);
             if (t + 2 < ntiles) load_stats(i0 + 128);
         }
         if (i0 + 63 >= kv0w) {
