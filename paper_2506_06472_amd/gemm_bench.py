@@ -8,6 +8,8 @@ S = 8192 tokens.  Operands are resident in device memory; the time is the averag
 between two HIP events on the launch stream.  --data chooses the operand values: standard normal (what random-init
 training sees), multiples of 1/4 in [-1, 1) (few mantissa bits set), or zeros.  The rate depends on it because the
 chip's clock under matrix-core load depends on how many bits toggle: the same launches run faster on zeros.
+--vendor times the same products through torch.matmul (the vendor's GEMM library) instead: a yardstick measured on the
+same box with the same operands, nothing the library or its tests use.
 """
 import argparse
 
@@ -43,13 +45,14 @@ def main():
     ap.add_argument("--data", nargs="+", default=["normal"], choices=["normal", "small_int", "zero"])
     ap.add_argument("--tokens", type=int, default=8192)
     ap.add_argument("--reps", type=int, default=20)
+    ap.add_argument("--vendor", action="store_true", help="time torch.matmul on the same products instead of tio_op_gemm")
     args = ap.parse_args()
     import torch
     import paper_2506_06472_amd as tio
     st = torch.cuda.current_stream().cuda_stream
     for data in args.data:
         tot_f = tot_t = 0.0
-        print(f"shapes {args.shapes}, {args.tokens} tokens, operands: {data}", flush=True)
+        print(f"shapes {args.shapes}, {args.tokens} tokens, operands: {data}" + (", torch.matmul" if args.vendor else ""), flush=True)
         for name, akm, bkm, M, N, K, lda, ldb, ldc, weight in products(SHAPES[args.shapes], args.tokens):
             A = operand(torch, K if akm else M, lda, data)
             B = operand(torch, K if bkm else N, ldb, data)
@@ -62,6 +65,11 @@ def main():
             ws = torch.empty((splits * (M * N + M),), device="cuda", dtype=torch.float32) if splits > 1 else None
 
             def launch():
+                if args.vendor:       # C[M, N] = op(A) op(B)^T on the same buffers: a k-major operand is stored [K, rows]
+                    a = A[:, :M].t() if akm else A[:, :K]
+                    b = B[:, :N] if bkm else B[:, :K].t()
+                    torch.matmul(a, b, out=C[:, :N]) if ldc == N else C[:, :N].copy_(torch.matmul(a, b))
+                    return
                 tio.tio_op_gemm(st, "bf16", akm, bkm, M, N, K, A.data_ptr(), lda, B.data_ptr(), ldb, 0, 0, 0,
                                 C.data_ptr(), ldc, 0, ws.data_ptr() if ws is not None else 0, splits)
             launch()
@@ -77,7 +85,7 @@ def main():
             tot_f += fl * weight
             tot_t += us * weight
             print(f"  {name:12s} M={M:6d} N={N:6d} K={K:6d} {us:9.1f} us {fl / us / 1e6:8.1f} TFLOP/s"
-                  + (f"  split-K {splits}" if splits > 1 else ""), flush=True)
+                  + (f"  split-K {splits}" if splits > 1 and not args.vendor else ""), flush=True)
         print(f"  all GEMM launches of a step: {tot_t / 1e3:.2f} ms, {tot_f / tot_t / 1e6:.1f} TFLOP/s "
               f"({tot_f / tot_t / 1e6 / 2500:.3f} of 2.5 PFLOP/s)", flush=True)
 
