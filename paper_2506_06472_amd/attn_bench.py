@@ -6,7 +6,8 @@ Forward alone, and forward plus backward (row-sum pre-pass, dQ launch, dK/dV lau
 memory, standard normal values, the average over --reps back-to-back calls between two HIP events on the launch
 stream.  The rates count the algorithmic flops of causal attention: 4 B H T^2 dh / 2 forward, 2.5 times that backward
 (what the kernels execute is more: the backward launches recompute the scores, and tiles on the diagonal are computed
-whole).
+whole).  --vendor times torch's scaled_dot_product_attention (the vendor's fused attention) on the same shapes instead,
+on contiguous [B, H, T, dh] operands made outside the timed region: a yardstick, nothing the library or its tests use.
 """
 import argparse
 
@@ -26,6 +27,7 @@ def main():
     ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
     ap.add_argument("--shapes", nargs="+", default=list(SHAPES), choices=sorted(SHAPES))
     ap.add_argument("--reps", type=int, default=10)
+    ap.add_argument("--vendor", action="store_true", help="time torch's scaled_dot_product_attention instead of tio_op_attention")
     args = ap.parse_args()
     import torch
     import paper_2506_06472_amd as tio
@@ -46,6 +48,20 @@ def main():
         def both():
             tio.tio_op_attention(st, "bf16", B, T, H, dh, qkv.data_ptr(), o.data_ptr(), lse.data_ptr(), dO.data_ptr(),
                                  delta.data_ptr(), dqkv.data_ptr())
+        if args.vendor:
+            import torch.nn.functional as F
+            q, k, v = (qkv[:, i * d:(i + 1) * d].reshape(B, T, H, dh).permute(0, 2, 1, 3).contiguous().requires_grad_(True)
+                       for i in range(3))
+            g = dO.reshape(B, T, H, dh).permute(0, 2, 1, 3).contiguous()
+
+            def forward():
+                with torch.no_grad():
+                    F.scaled_dot_product_attention(q, k, v, is_causal=True)
+
+            def both():
+                out = F.scaled_dot_product_attention(q, k, v, is_causal=True)
+                out.backward(g)
+                q.grad = k.grad = v.grad = None
         us = []
         for call in (forward, both):
             call()
@@ -59,7 +75,7 @@ def main():
             us.append(e0.elapsed_time(e1) * 1e3 / args.reps)
         fwd, bwd = us[0], us[1] - us[0]
         fl = flops_forward(B, T, H, dh)
-        print(f"{name:11s} B={B} T={T} H={H} dh={dh}: forward {fwd:8.1f} us {fl / fwd / 1e6:7.1f} TFLOP/s | "
+        print(("torch sdpa " if args.vendor else "") + f"{name:11s} B={B} T={T} H={H} dh={dh}: forward {fwd:8.1f} us {fl / fwd / 1e6:7.1f} TFLOP/s | "
               f"backward {bwd:8.1f} us {2.5 * fl / bwd / 1e6:7.1f} TFLOP/s", flush=True)
 
 
