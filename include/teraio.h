@@ -171,7 +171,9 @@ typedef struct tio_plan_opts {
      * and the best one whose address layout fits the arena is kept.  Where the best run's layout does not fit, the
      * search over planning capacities (2 % steps down from the cap) goes on for up to two more steps and keeps the
      * plan predicted fastest among those that fit: a plan whose layout fits at a slightly lower planning capacity
-     * can beat, by more than its extra bytes cost, the first one that fits at the full capacity.  Helps where
+     * can beat, by more than its extra bytes cost, the first one that fits at the full capacity; and the plan built
+     * without re-timing for the same arena replaces the result when it is predicted faster, so the result is never
+     * predicted slower than that plan.  Helps where
      * migration takes longer than compute: the stalled iteration gives the channels several times the compute time,
      * which the first run cannot see.  tio_plan_view.retime_pass and planning_cap say what was kept. */
     int32_t retime_passes;

@@ -829,6 +829,18 @@ Plan build_plan(const Trace &t, const Lifetimes &life, uint64_t cap, uint64_t bw
         int64_t top = 0;
         if (attempt(mid, q, top) && q.predicted_step_ns <= best.predicted_step_ns) { lo = mid; best = std::move(q); } else hi = mid;
     }
+    // With re-timing the result is never predicted slower than the plan built without it for the same arena: that plan
+    // may sit at a planning capacity the search above did not reach.
+    if (o.retime_passes > 0 && bw != 0 && best.retime_pass != 0) {
+        tio_plan_opts once = o;
+        once.retime_passes = 0;
+        try {
+            Plan paper = build_plan(t, life, cap, bw, once);
+            paper.predicted_step_ns = simulate_plan(t, paper, bw, o.duplex != 0, 3, nullptr).step_ns;
+            if (paper.predicted_step_ns < best.predicted_step_ns) return paper;
+        } catch (const PlanError &) {
+        }
+    }
     return best;
 }
 

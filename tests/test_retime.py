@@ -148,3 +148,34 @@ def test_gpt2_small_at_full_size_bit_exact_and_faster():
     once = tio.tio_plan_simulate(lt, tio.tio_build_plan(lt, ll, cap, bw, min_bytes=1 << 20), bw)[0]
     again = tio.tio_plan_simulate(lt, tio.tio_build_plan(lt, ll, cap, bw, min_bytes=1 << 20, retime_passes=2), bw)[0]
     assert again < once
+
+
+def test_tight_arena_bit_exact_and_never_predicted_slower_than_the_papers_plan():
+    """Arena = cap: layouts fail, the planning capacity goes down, and the selections of several passes compete at every
+    capacity.  Whatever the search keeps is the oracle's plan of the reported pass at the reported planning capacity, is a
+    valid plan, and is never predicted slower than the plan the library builds without re-timing for the same arena."""
+    rng = np.random.default_rng(23)
+    n = better = lowered = 0
+    for trial in range(120):
+        tr = random_trace(rng, N=int(rng.integers(8, 40)), n_pers=int(rng.integers(1, 6)), n_trans=int(rng.integers(5, 30)))
+        tr["tensors"] = [(s * 32, k, nme) for s, k, nme in tr["tensors"]]
+        lt = lib_trace_from_oracle(tr)
+        ll = tio.tio_analyze_lifetimes(lt)
+        life = op.analyze_lifetimes(tr)
+        cap = int(max(life["M"]) * rng.uniform(0.4, 0.9)) // 256 * 256
+        bw = int(10 ** rng.uniform(9, 10.5))
+        passes = int(rng.integers(1, 6))
+        try:
+            paper = tio.tio_build_plan(lt, ll, cap, bw)
+        except tio.TioError:
+            continue
+        pl = assert_same_retimed_plan(tr, lt, ll, cap, bw, passes, ample_arena=False)
+        assert pl is not None
+        plan = tio.tio_build_plan(lt, ll, cap, bw, retime_passes=passes)
+        tio.tio_plan_validate(lt, ll, plan)
+        s0, s1 = tio.tio_plan_simulate(lt, paper, bw)[0], tio.tio_plan_simulate(lt, plan, bw)[0]
+        assert s1 <= s0, (trial, s1, s0)
+        n += 1
+        better += s1 < s0
+        lowered += pl["planning_cap"] < cap
+    assert n >= 40 and better >= n // 2 and lowered >= 3, (n, better, lowered)
