@@ -167,7 +167,9 @@ __global__ void __launch_bounds__(WGM *WGN * 64)
         bid = (int)(blockIdx.x % 8) * ((total_tiles + 7) / 8) + (int)(blockIdx.x / 8);
     }
     if (bid >= total_tiles) return;
-    constexpr int GROUP = 8;
+    // consecutive workgroups walk down GROUP tile rows before moving to the next tile column; products with very many tile
+    // rows (weight gradients of the wide layers) do better with the narrower band (measured: +3..5 % there, -2 % elsewhere)
+    const int GROUP = tiles_m > 64 ? 4 : 8;
     const int per_group = GROUP * tiles_n;
     const int g = bid / per_group;
     const int gm0 = g * GROUP;
