@@ -72,7 +72,9 @@ def main():
                     return
                 tio.tio_op_gemm(st, "bf16", akm, bkm, M, N, K, A.data_ptr(), lda, B.data_ptr(), ldb, 0, 0, 0,
                                 C.data_ptr(), ldc, 0, ws.data_ptr() if ws is not None else 0, splits)
-            for _ in range(max(3, args.reps // 2)):      # untimed: the clock has ramped up when the timed launches start
+            # untimed launches first: the clock takes some tenths of a second of load to ramp up after idling, so the
+            # first product of a run gets more of them
+            for _ in range(max(3, args.reps // 2) if tot_t else 300):
                 launch()
             torch.cuda.synchronize()
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
